@@ -1,0 +1,364 @@
+"""CPU fp64 oracle for the grid-code protected matrix product.  TEST INFRASTRUCTURE ONLY.
+
+This module is the slow, plain reference the GPU path is checked against.  It
+is imported only by tests, by the smoke check and by the benchmark's CPU
+baseline leg; nothing on the product path may call it, and it shares no code
+with the HIP library.
+
+Everything is numpy float64.  Indices in this API are 0-based; the paper's
+weight for 0-based index i is i+1 (its index sets start at 1, Section II-A).
+
+What follows the paper directly
+  * encode_a / encode_b      -- Section III, definitions of A_P, B_P with
+                                P_n1 = (1..1), P_n2 = (1..n) (same for m).
+  * encoded_product          -- Section III, C-bar = A-bar B-bar and its four
+                                blocks C, P_r, P_c, P_g.
+  * syndromes / detect       -- Section V step 1, the four threshold tests.
+  * d0_correct               -- Section V step 2 (s = 1 rule, 2x2 system for
+                                s = 2, "without loss of generality s <= t").
+  * global_syndromes         -- Definition 1, constraint (3) (used by the
+                                Lemma 3 rank pin only; the decoder of
+                                Section V never reads P_g).
+
+Readings taken where the paper is silent or garbled (each is listed again in
+the design notes of the repository):
+  * the 2x2 right-hand side is "sum minus parity" (Section V prints the
+    opposite sign there but subtracts the solution afterwards and Eq. (5)
+    uses sum minus parity);
+  * the weighted tests compare against the *second* parity symbol
+    (the "otherwise" branch of Section V step 1 prints m+1 / n+1 twice);
+  * one threshold per syndrome family (tau_r1, tau_r2, tau_q1, tau_q2)
+    instead of a single delta, because the weighted sums carry weights up
+    to n (or m) and therefore n-times larger rounding noise;
+  * operand errors (E1/E2 of Section II-A) hit the data part of A or B
+    after the parity rows/columns were formed and before the product reads
+    them, so every product term sees the same corrupted symbol;
+  * completion D1 (operand audit) -- the paper asserts that operand errors
+    "can be traced back to errors in C" and reports 100 % for its scenarios
+    a, b, d, e without printing a locating rule.  Because a corrupted a_il
+    also enters row i's own two parity symbols, the row syndromes are blind
+    to it; D1 re-forms the operand parities, diffs them with the stored
+    ones (each column of A-bar is a two-parity codeword, Section III),
+    locates row = weighted/plain ratio, patches the operand and removes the
+    rank-one footprint e * b-bar_l from C-bar, then re-runs Section V.
+  * every estimate is verified: after the tentative correction all
+    syndromes of the flagged rows/columns must fall inside the thresholds
+    (propagated through the estimate), otherwise the pattern is handed on.
+  * for s = t = 2 the 2x2 systems are first evaluated under the two sparse
+    hypotheses "one error per flagged column" (a column with a single error
+    is the s = 1 rule applied to that column); in exact arithmetic this
+    equals the 2x2 solution, numerically it avoids dividing a weighted
+    syndrome (noise ~ n^1.5) by s2 - s1.
+
+parity pins: see tests/test_oracle_pins.py (exact integer brute force of the
+product, block closed forms, zero syndromes, Theorem 1 enumeration, every
+single and pair placement over A, B, C on tiny sizes, the counter-example of
+Section IV, the rank statement of Lemma 3 built from Eq. (5), reductions to
+the single-checksum and weighted-checksum schemes).
+"""
+from dataclasses import dataclass, field
+from typing import List, Optional, Tuple
+
+import numpy as np
+
+CLEAN, CORRECTED, UNCORRECTABLE = 0, 1, 2
+MAT_A, MAT_B, MAT_C = 0, 1, 2
+MAX_REPORTED = 8          # capacity of the located-error list
+
+
+@dataclass
+class Thresholds:
+    """Detection thresholds, one per syndrome family (Section V, delta)."""
+    r1: float
+    r2: float
+    q1: float
+    q2: float
+    op: float = 0.0       # operand audit: |parity difference| > op flags a line
+
+
+@dataclass
+class Result:
+    status: int
+    s: int                               # flagged rows at first detection
+    t: int                               # flagged columns at first detection
+    errors: List[Tuple[int, int, int, float]]   # (matrix,row,col,magnitude) sorted
+    Cbar: np.ndarray                     # corrected encoded product
+    A: np.ndarray                        # (possibly patched) left operand
+    B: np.ndarray                        # (possibly patched) right operand
+    max_abs_synd: Tuple[float, float, float, float] = (0.0, 0.0, 0.0, 0.0)
+
+    @property
+    def C(self):
+        n, m = self.Cbar.shape[0] - 2, self.Cbar.shape[1] - 2
+        return self.Cbar[:n, :m]
+
+
+def _w(n):
+    """P_n2 of Section III: (1, 2, ..., n)."""
+    return np.arange(1, n + 1, dtype=np.float64)
+
+
+# ---------------------------------------------------------------- Section III
+def encode_a(A):
+    """A_P (2 x k): row 0 = P_n1 A (column sums), row 1 = P_n2 A (Section III)."""
+    A = np.asarray(A, dtype=np.float64)
+    n, k = A.shape
+    AP = np.empty((2, k), dtype=np.float64)
+    AP[0, :] = A.sum(axis=0)
+    AP[1, :] = (_w(n)[:, None] * A).sum(axis=0)
+    return AP
+
+
+def encode_b(B):
+    """B_P (k x 2): col 0 = B P_m1^T (row sums), col 1 = B P_m2^T (Section III)."""
+    B = np.asarray(B, dtype=np.float64)
+    k, m = B.shape
+    BP = np.empty((k, 2), dtype=np.float64)
+    BP[:, 0] = B.sum(axis=1)
+    BP[:, 1] = (B * _w(m)[None, :]).sum(axis=1)
+    return BP
+
+
+def encoded_product(A, AP, B, BP):
+    """C-bar = [A; A_P] [B  B_P]  ((n+2) x (m+2)), Section III."""
+    Abar = np.vstack([np.asarray(A, dtype=np.float64), AP])
+    Bbar = np.hstack([np.asarray(B, dtype=np.float64), BP])
+    return Abar @ Bbar
+
+
+def inject_c(Cbar, faults):
+    """E3 of Section II-A: add e to data symbol (i, j) of the product."""
+    n, m = Cbar.shape[0] - 2, Cbar.shape[1] - 2
+    for (i, j, e) in faults:
+        assert 0 <= i < n and 0 <= j < m
+        Cbar[i, j] += e
+
+
+# ------------------------------------------------------------------ Section V
+def syndromes(Cbar):
+    """The four families of Section V step 1, as (sum) - (parity symbol).
+
+    r1_i = sum_j c_ij       - cbar_{i,m+1}      r2_i = sum_j j c_ij - cbar_{i,m+2}
+    q1_j = sum_i c_ij       - cbar_{n+1,j}      q2_j = sum_i i c_ij - cbar_{n+2,j}
+    (paper's 1-based i, j inside the weights).
+    """
+    n, m = Cbar.shape[0] - 2, Cbar.shape[1] - 2
+    C = Cbar[:n, :m]
+    r1 = C.sum(axis=1) - Cbar[:n, m]
+    r2 = (C * _w(m)[None, :]).sum(axis=1) - Cbar[:n, m + 1]
+    q1 = C.sum(axis=0) - Cbar[n, :m]
+    q2 = (_w(n)[:, None] * C).sum(axis=0) - Cbar[n + 1, :m]
+    return r1, r2, q1, q2
+
+
+def global_syndromes(Cbar):
+    """Constraint (3) of Definition 1: the four global parity checks."""
+    n, m = Cbar.shape[0] - 2, Cbar.shape[1] - 2
+    C = Cbar[:n, :m]
+    wn, wm = _w(n), _w(m)
+    g = np.empty(4)
+    g[0] = C.sum() - Cbar[n, m]
+    g[1] = (C * wm[None, :]).sum() - Cbar[n, m + 1]
+    g[2] = (wn[:, None] * C).sum() - Cbar[n + 1, m]
+    g[3] = (wn[:, None] * C * wm[None, :]).sum() - Cbar[n + 1, m + 1]
+    return g
+
+
+def detect(r1, r2, q1, q2, tau):
+    """E_r, E_t of Section V step 1 (a line is flagged if either test fails)."""
+    Er = np.nonzero((np.abs(r1) > tau.r1) | (np.abs(r2) > tau.r2))[0]
+    Et = np.nonzero((np.abs(q1) > tau.q1) | (np.abs(q2) > tau.q2))[0]
+    return [int(i) for i in Er], [int(j) for j in Et]
+
+
+def _residual_ok(est, r1, r2, q1, q2, Er, Et, tau):
+    """All syndromes of the flagged lines must be explained by the estimate.
+
+    est: list of (i, j, x, u): error x at (i, j) known to within +-u.
+    """
+    for i in Er:
+        sx = sum(x for (ii, j, x, u) in est if ii == i)
+        su = sum(u for (ii, j, x, u) in est if ii == i)
+        wx = sum((j + 1) * x for (ii, j, x, u) in est if ii == i)
+        wu = sum((j + 1) * u for (ii, j, x, u) in est if ii == i)
+        if abs(r1[i] - sx) > tau.r1 + su:
+            return False
+        if abs(r2[i] - wx) > tau.r2 + wu:
+            return False
+    for j in Et:
+        sx = sum(x for (i, jj, x, u) in est if jj == j)
+        su = sum(u for (i, jj, x, u) in est if jj == j)
+        wx = sum((i + 1) * x for (i, jj, x, u) in est if jj == j)
+        wu = sum((i + 1) * u for (i, jj, x, u) in est if jj == j)
+        if abs(q1[j] - sx) > tau.q1 + su:
+            return False
+        if abs(q2[j] - wx) > tau.q2 + wu:
+            return False
+    return True
+
+
+def solve_2x2(w1, w2, y1, y2):
+    """Solve [[1, 1], [w1, w2]] (e1, e2)^T = (y1, y2)^T (Section V, s = 2)."""
+    e2 = (y2 - w1 * y1) / (w2 - w1)
+    e1 = y1 - e2
+    return e1, e2
+
+
+def d0_correct(r1, r2, q1, q2, Er, Et, tau):
+    """Section V step 2 for 1 <= s, t <= 2.
+
+    Returns the verified list [(i, j, x)] of C errors, or None when no
+    estimate explains the syndromes (the caller then tries the operand audit).
+    """
+    s, t = len(Er), len(Et)
+    assert 1 <= s <= 2 and 1 <= t <= 2
+
+    def accept(est):
+        est = [e for e in est if abs(e[2]) > e[3]]       # drop insignificant parts
+        if _residual_ok(est, r1, r2, q1, q2, Er, Et, tau):
+            return sorted((i, j, x) for (i, j, x, u) in est)
+        return None
+
+    if s <= t:
+        if s == 1:
+            # one faulty row: every flagged column has its error in that row
+            return accept([(Er[0], j, q1[j], tau.q1) for j in Et])
+        s1, s2 = Er
+        t1, t2 = Et
+        diag = accept([(s1, t1, q1[t1], tau.q1), (s2, t2, q1[t2], tau.q1)])
+        anti = accept([(s1, t2, q1[t2], tau.q1), (s2, t1, q1[t1], tau.q1)])
+        if diag is not None and anti is not None:
+            return None                                  # cannot tell them apart
+        if diag is not None:
+            return diag
+        if anti is not None:
+            return anti
+        w1, w2 = s1 + 1.0, s2 + 1.0
+        est = []
+        for j in Et:
+            e1, e2 = solve_2x2(w1, w2, q1[j], q2[j])
+            u2 = (tau.q2 + w1 * tau.q1) / (w2 - w1)
+            u1 = tau.q1 + u2
+            est += [(s1, j, e1, u1), (s2, j, e2, u2)]
+        return accept(est)
+    # s = 2 > t = 1: mirror image, rows play the role of columns
+    return accept([(i, Et[0], r1[i], tau.r1) for i in Er])
+
+
+# ------------------------------------------------------- completion D1: audit
+def audit_a(A, AP, tau_op):
+    """Re-form the parity rows of A and compare with the stored ones.
+
+    Each column l of [A; A_P] is a codeword with two parities (Section III):
+    a single wrong symbol a_il shows as (u1, u2) = (e, (i+1) e).
+    Returns (ok, [(i, l, e)]); ok is False when some column cannot be
+    explained by one wrong symbol (two errors in one column exceed the code).
+    """
+    n, k = A.shape
+    cur = encode_a(A)
+    u1 = cur[0] - AP[0]
+    u2 = cur[1] - AP[1]
+    found = []
+    for l in np.nonzero((np.abs(u1) > tau_op) | (np.abs(u2) > tau_op))[0]:
+        if not abs(u1[l]) > tau_op:
+            return False, []
+        rho = u2[l] / u1[l]
+        w = np.rint(rho)
+        if not (abs(rho - w) < 0.25 and 1 <= w <= n):
+            return False, []
+        found.append((int(w) - 1, int(l), float(u1[l])))
+    return True, found
+
+
+def audit_b(B, BP, tau_op):
+    """Mirror of audit_a for the parity columns of B. Returns [(l, j, e)]."""
+    k, m = B.shape
+    cur = encode_b(B)
+    u1 = cur[:, 0] - BP[:, 0]
+    u2 = cur[:, 1] - BP[:, 1]
+    found = []
+    for l in np.nonzero((np.abs(u1) > tau_op) | (np.abs(u2) > tau_op))[0]:
+        if not abs(u1[l]) > tau_op:
+            return False, []
+        rho = u2[l] / u1[l]
+        w = np.rint(rho)
+        if not (abs(rho - w) < 0.25 and 1 <= w <= m):
+            return False, []
+        found.append((int(l), int(w) - 1, float(u1[l])))
+    return True, found
+
+
+def decode(Cbar, A, AP, B, BP, tau):
+    """Detection, correction and the operand completion, on copies.
+
+    Cbar : (n+2) x (m+2) encoded product as computed (possibly corrupted)
+    A, B : operands as the product read them (possibly corrupted)
+    AP,BP: parities formed before the corruption
+    On UNCORRECTABLE the returned buffers hold whatever the attempt left
+    behind; a caller has to recompute (Section V: "needs to be recalculated").
+    """
+    Cbar = np.array(Cbar, dtype=np.float64)
+    A = np.array(A, dtype=np.float64)
+    B = np.array(B, dtype=np.float64)
+    n, m = Cbar.shape[0] - 2, Cbar.shape[1] - 2
+
+    r1, r2, q1, q2 = syndromes(Cbar)
+    mx = tuple(float(np.max(np.abs(v))) if v.size else 0.0 for v in (r1, r2, q1, q2))
+    Er, Et = detect(r1, r2, q1, q2, tau)
+    s0, t0 = len(Er), len(Et)
+
+    def done(status, errs):
+        return Result(status, s0, t0, sorted(errs), Cbar, A, B, mx)
+
+    if s0 == 0 and t0 == 0:
+        return done(CLEAN, [])
+
+    if 1 <= s0 <= 2 and 1 <= t0 <= 2:
+        fix = d0_correct(r1, r2, q1, q2, Er, Et, tau)
+        if fix is not None:
+            for (i, j, x) in fix:
+                Cbar[i, j] -= x
+            return done(CORRECTED, [(MAT_C, i, j, x) for (i, j, x) in fix])
+
+    # D1: operand audit, patch, rank-one repair, then Section V on the rest
+    okA, LA = audit_a(A, AP, tau.op)
+    okB, LB = audit_b(B, BP, tau.op)
+    if not (okA and okB) or (len(LA) + len(LB) == 0) or (len(LA) + len(LB) > MAX_REPORTED):
+        return done(UNCORRECTABLE, [])
+    errs = []
+    for (i, l, e) in LA:
+        A[i, l] -= e
+        Cbar[i, :] -= e * np.concatenate([B[l, :], BP[l, :]])
+        errs.append((MAT_A, i, l, e))
+    for (l, j, e) in LB:
+        B[l, j] -= e
+        Cbar[:, j] -= np.concatenate([A[:, l], AP[:, l]]) * e
+        errs.append((MAT_B, l, j, e))
+
+    r1, r2, q1, q2 = syndromes(Cbar)
+    Er, Et = detect(r1, r2, q1, q2, tau)
+    s, t = len(Er), len(Et)
+    if s == 0 and t == 0:
+        return done(CORRECTED, errs)
+    if 1 <= s <= 2 and 1 <= t <= 2:
+        fix = d0_correct(r1, r2, q1, q2, Er, Et, tau)
+        if fix is not None and len(errs) + len(fix) <= MAX_REPORTED:
+            for (i, j, x) in fix:
+                Cbar[i, j] -= x
+            return done(CORRECTED, errs + [(MAT_C, i, j, x) for (i, j, x) in fix])
+    return done(UNCORRECTABLE, [])
+
+
+def protected_gemm(A_enc, B_enc, A_mul, B_mul, c_faults, tau):
+    """The whole path: encode -> (operand faults) -> product -> (C faults) -> decode.
+
+    A_enc, B_enc : operands at the time the parities are formed
+    A_mul, B_mul : operands as the product reads them (equal to *_enc when no
+                   E1/E2 fault is injected)
+    c_faults     : [(i, j, e)] added to data symbols of the product (E3)
+    """
+    AP = encode_a(A_enc)
+    BP = encode_b(B_enc)
+    Cbar = encoded_product(A_mul, AP, B_mul, BP)
+    inject_c(Cbar, c_faults)
+    return decode(Cbar, A_mul, AP, B_mul, BP, tau)

@@ -1,0 +1,358 @@
+"""Pins of the CPU oracle against what the paper and plain mathematics fix.
+
+None of these tests touches the GPU path.  Each pin is chosen so that a
+plausible slip in the oracle (dropped term, wrong sign or index, transposed
+operand, off-by-one weight) makes it fail.
+"""
+import itertools
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from oracle import grid_code as oc
+from oracle.grid_code import CLEAN, CORRECTED, UNCORRECTABLE, MAT_A, MAT_B, MAT_C, Thresholds
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+TAU0 = Thresholds(1e-9, 1e-9, 1e-9, 1e-9, 0.0)       # exact-integer experiments
+
+
+def int_mats(seed, n, k, m, lo=1, hi=5):
+    rng = np.random.default_rng(seed)
+    return (rng.integers(lo, hi + 1, (n, k)).astype(np.float64),
+            rng.integers(lo, hi + 1, (k, m)).astype(np.float64))
+
+
+# ---- pin 1: the data block is the plain definition c_ij = sum_l a_il b_lj (Section II-A),
+#      evaluated with Python integers (exact), and the parity blocks follow their
+#      closed forms (Section III) evaluated the same way.
+@pytest.mark.parametrize("n,k,m", [(3, 4, 5), (5, 2, 3), (1, 1, 1), (6, 7, 2)])
+def test_encoded_product_blocks_exact_integers(n, k, m):
+    A, B = int_mats(11 + n, n, k, m, -7, 7)
+    Cbar = oc.encoded_product(A, oc.encode_a(A), B, oc.encode_b(B))
+    Ai = [[int(v) for v in row] for row in A]
+    Bi = [[int(v) for v in row] for row in B]
+    C = [[sum(Ai[i][l] * Bi[l][j] for l in range(k)) for j in range(m)] for i in range(n)]
+    assert Cbar.shape == (n + 2, m + 2)
+    for i in range(n):
+        for j in range(m):
+            assert Cbar[i, j] == C[i][j]
+        assert Cbar[i, m] == sum(C[i][j] for j in range(m))                 # P_r col 1
+        assert Cbar[i, m + 1] == sum((j + 1) * C[i][j] for j in range(m))   # P_r col 2
+    for j in range(m):
+        assert Cbar[n, j] == sum(C[i][j] for i in range(n))                 # P_c row 1
+        assert Cbar[n + 1, j] == sum((i + 1) * C[i][j] for i in range(n))   # P_c row 2
+    assert Cbar[n, m] == sum(C[i][j] for i in range(n) for j in range(m))
+    assert Cbar[n, m + 1] == sum((j + 1) * C[i][j] for i in range(n) for j in range(m))
+    assert Cbar[n + 1, m] == sum((i + 1) * C[i][j] for i in range(n) for j in range(m))
+    assert Cbar[n + 1, m + 1] == sum((i + 1) * (j + 1) * C[i][j] for i in range(n) for j in range(m))
+
+
+def test_parities_are_not_transposed_or_swapped():
+    # asymmetric shapes and a single non-zero entry make any axis/weight slip visible
+    A = np.zeros((4, 3)); A[2, 1] = 5.0
+    AP = oc.encode_a(A)
+    assert AP.shape == (2, 3) and AP[0, 1] == 5.0 and AP[1, 1] == 15.0 and AP[:, [0, 2]].sum() == 0
+    B = np.zeros((3, 6)); B[0, 4] = 2.0
+    BP = oc.encode_b(B)
+    assert BP.shape == (3, 2) and BP[0, 0] == 2.0 and BP[0, 1] == 10.0 and BP[1:, :].sum() == 0
+
+
+# ---- pin 2: all syndromes (Section V) and all global checks (Definition 1) vanish exactly
+def test_zero_syndromes_on_clean_integer_product():
+    for seed, (n, k, m) in enumerate([(4, 5, 6), (7, 3, 2), (16, 16, 16)]):
+        A, B = int_mats(seed, n, k, m, -9, 9)
+        Cbar = oc.encoded_product(A, oc.encode_a(A), B, oc.encode_b(B))
+        for v in oc.syndromes(Cbar):
+            assert np.all(v == 0)
+        assert np.all(oc.global_syndromes(Cbar) == 0)
+        res = oc.protected_gemm(A, B, A, B, [], TAU0)
+        assert res.status == CLEAN and res.errors == [] and (res.s, res.t) == (0, 0)
+
+
+def test_syndrome_signs_and_weights():
+    # one wrong symbol e at (i, j): r1_i = q1_j = e, r2_i = (j+1) e, q2_j = (i+1) e  (sum - parity)
+    n, m = 5, 7
+    A, B = int_mats(3, n, 4, m)
+    Cbar = oc.encoded_product(A, oc.encode_a(A), B, oc.encode_b(B))
+    Cbar[3, 5] += 2.0
+    r1, r2, q1, q2 = oc.syndromes(Cbar)
+    exp = np.zeros(n); exp[3] = 2.0
+    assert np.array_equal(r1, exp) and np.array_equal(r2, exp * 6)
+    exp = np.zeros(m); exp[5] = 2.0
+    assert np.array_equal(q1, exp) and np.array_equal(q2, exp * 4)
+
+
+# ---- pin 3: 2x2 closed form of Section V against a generic solver
+def test_solve_2x2_matches_linear_solver():
+    rng = np.random.default_rng(5)
+    for _ in range(50):
+        w1, w2 = sorted(rng.choice(np.arange(1, 40), 2, replace=False).astype(float))
+        y = rng.standard_normal(2)
+        e = np.linalg.solve(np.array([[1.0, 1.0], [w1, w2]]), y)
+        assert np.allclose(oc.solve_2x2(w1, w2, y[0], y[1]), e, rtol=1e-10, atol=1e-12)
+
+
+# ---- pin 4: Theorem 1 -- every pattern inside <= 2 rows x <= 2 columns of C is corrected
+def test_theorem1_all_patterns_in_2x2_blocks():
+    n, k, m = 4, 3, 4
+    A, B = int_mats(21, n, k, m)
+    AP, BP = oc.encode_a(A), oc.encode_b(B)
+    clean = oc.encoded_product(A, AP, B, BP)
+    vals = (0, 1, -1, 3)
+    count = 0
+    for rows in itertools.combinations(range(n), 2):
+        for cols in itertools.combinations(range(m), 2):
+            cells = [(i, j) for i in rows for j in cols]
+            for mags in itertools.product(vals, repeat=4):
+                if not any(mags):
+                    continue
+                faults = [(i, j, float(e)) for (i, j), e in zip(cells, mags) if e]
+                Cbar = clean.copy()
+                oc.inject_c(Cbar, faults)
+                res = oc.decode(Cbar, A, AP, B, BP, TAU0)
+                assert res.status == CORRECTED, (faults,)
+                assert np.array_equal(res.Cbar, clean), (faults,)
+                assert [(mt, i, j) for (mt, i, j, _) in res.errors] == sorted((MAT_C, i, j) for (i, j, _) in faults)
+                assert np.allclose([x for (*_, x) in res.errors], [e for (_, _, e) in sorted(faults)])
+                count += 1
+    assert count == 36 * (4 ** 4 - 1)
+
+
+# ---- pin 5: every single placement and every pair over A u B u C (tiny sizes, integers)
+def _placements(n, k, m):
+    return ([(MAT_A, i, l) for i in range(n) for l in range(k)] +
+            [(MAT_B, l, j) for l in range(k) for j in range(m)] +
+            [(MAT_C, i, j) for i in range(n) for j in range(m)])
+
+
+def _run_faults(A, B, AP, BP, placed):
+    A2, B2, cf = A.copy(), B.copy(), []
+    for (mt, r, c, e) in placed:
+        if mt == MAT_A:
+            A2[r, c] += e
+        elif mt == MAT_B:
+            B2[r, c] += e
+        else:
+            cf.append((r, c, e))
+    Cbar = oc.encoded_product(A2, AP, B2, BP)
+    oc.inject_c(Cbar, cf)
+    return oc.decode(Cbar, A2, AP, B2, BP, TAU0)
+
+
+@pytest.mark.parametrize("n,k,m", [(3, 3, 3), (4, 2, 3), (3, 4, 5)])
+def test_every_single_error_is_located_and_corrected(n, k, m):
+    A, B = int_mats(31 + k, n, k, m)
+    AP, BP = oc.encode_a(A), oc.encode_b(B)
+    clean = oc.encoded_product(A, AP, B, BP)
+    for p in _placements(n, k, m):
+        for e in (2.0, -7.0):
+            res = _run_faults(A, B, AP, BP, [p + (e,)])
+            assert res.status == CORRECTED, p
+            assert res.errors == [p + (e,)]
+            assert np.array_equal(res.Cbar, clean) and np.array_equal(res.A, A) and np.array_equal(res.B, B)
+
+
+def _beyond_code(p1, p2):
+    """Two errors in one column of A, or in one row of B: a two-parity line code has
+    distance 3, so such pairs exceed the code (Section III: each column of A-bar and each
+    row of B-bar carries exactly two parity symbols)."""
+    if p1[0] == p2[0] == MAT_A:
+        return p1[2] == p2[2]
+    if p1[0] == p2[0] == MAT_B:
+        return p1[1] == p2[1]
+    return False
+
+
+@pytest.mark.parametrize("n,k,m,mags", [(3, 3, 3, (1.0, 1.0)), (3, 3, 3, (2.0, -2.0)), (4, 2, 3, (3.0, -5.0)),
+                                         (3, 3, 4, (-1.0, 4.0))])
+def test_every_pair_of_errors_follows_the_correctability_map(n, k, m, mags):
+    A, B = int_mats(41 + n + k + m, n, k, m)
+    AP, BP = oc.encode_a(A), oc.encode_b(B)
+    clean = oc.encoded_product(A, AP, B, BP)
+    n_ok = n_beyond = 0
+    for p1, p2 in itertools.combinations(_placements(n, k, m), 2):
+        placed = [p1 + (mags[0],), p2 + (mags[1],)]
+        res = _run_faults(A, B, AP, BP, placed)
+        if _beyond_code(p1, p2):
+            n_beyond += 1
+            if res.status == CORRECTED:
+                # indistinguishable from one error: the decoder "repairs" a codeword at
+                # distance 1 -- C-bar is then consistent but the operand is not restored
+                assert all(abs(v).max() < 1e-9 for v in oc.syndromes(res.Cbar))
+            else:
+                assert res.status == UNCORRECTABLE
+            continue
+        n_ok += 1
+        assert res.status == CORRECTED, (p1, p2)
+        assert res.errors == sorted(placed), (p1, p2)
+        assert np.array_equal(res.Cbar, clean) and np.array_equal(res.A, A) and np.array_equal(res.B, B)
+    assert n_ok > 0 and n_beyond > 0
+
+
+def test_two_errors_in_one_operand_column_hit_the_bound():
+    # A(0,l,e) + A(2,l,e) has the same column parities as A(1,l,2e): mis-located by construction;
+    # A(0,l,e) + A(1,l,2e) gives a non-integer ratio 5/3: declared uncorrectable.
+    n, k, m = 5, 3, 4
+    A, B = int_mats(77, n, k, m)
+    AP, BP = oc.encode_a(A), oc.encode_b(B)
+    res = _run_faults(A, B, AP, BP, [(MAT_A, 0, 1, 1.0), (MAT_A, 2, 1, 1.0)])
+    assert res.status == CORRECTED and res.errors == [(MAT_A, 1, 1, 2.0)]
+    res = _run_faults(A, B, AP, BP, [(MAT_A, 0, 1, 1.0), (MAT_A, 1, 1, 2.0)])
+    assert res.status == UNCORRECTABLE
+    res = _run_faults(A, B, AP, BP, [(MAT_B, 1, 0, 1.0), (MAT_B, 1, 1, 2.0)])
+    assert res.status == UNCORRECTABLE
+
+
+# ---- pin 6: operand-error signature (Section II-A: an error in a_il reaches the whole row i)
+def test_operand_error_footprint_and_blind_row_syndromes():
+    n, k, m = 6, 5, 7
+    A, B = int_mats(55, n, k, m)
+    AP, BP = oc.encode_a(A), oc.encode_b(B)
+    clean = oc.encoded_product(A, AP, B, BP)
+    A2 = A.copy(); A2[4, 2] += 3.0
+    d = oc.encoded_product(A2, AP, B, BP) - clean
+    exp = np.zeros_like(d); exp[4, :] = 3.0 * np.concatenate([B[2], BP[2]])
+    assert np.array_equal(d, exp)
+    r1, r2, q1, q2 = oc.syndromes(clean + d)
+    assert np.all(r1 == 0) and np.all(r2 == 0)
+    assert np.array_equal(q1, 3.0 * B[2]) and np.array_equal(q2, 5 * 3.0 * B[2])
+    B2 = B.copy(); B2[1, 3] -= 2.0
+    d = oc.encoded_product(A, AP, B2, BP) - clean
+    exp = np.zeros_like(d); exp[:, 3] = -2.0 * np.concatenate([A[:, 1], AP[:, 1]])
+    assert np.array_equal(d, exp)
+    r1, r2, q1, q2 = oc.syndromes(clean + d)
+    assert np.all(q1 == 0) and np.all(q2 == 0)
+    assert np.array_equal(r1, -2.0 * A[:, 1]) and np.array_equal(r2, 4 * -2.0 * A[:, 1])
+
+
+# ---- pin 7: the counter-example of Section IV (values from the paper, tests/golden)
+def _load_counterexample():
+    rows = {"e1": [], "e2": []}
+    where = {}
+    for line in open(os.path.join(GOLDEN, "section4_counterexample.txt")):
+        tok = line.split()
+        if not tok or tok[0].startswith("#"):
+            continue
+        if tok[0].endswith("_rows"):
+            where[tok[0][:2]] = [int(v) - 1 for v in tok[1:]]
+        else:
+            rows[tok[0]].append([float(v) for v in tok[1:]])
+    return rows, where
+
+
+def test_section4_counterexample_is_invisible_to_plain_sums_and_ambiguous():
+    rows, where = _load_counterexample()
+    n = m = 6
+    def pattern(name, scale=1.0, at=None):
+        E = np.zeros((n + 2, m + 2))
+        for r, vals in zip(at or where[name], rows[name]):
+            E[r, :len(vals)] = np.array(vals) * scale
+        return E
+    e1, e2 = pattern("e1"), pattern("e2")
+    s1, s2 = oc.syndromes(e1), oc.syndromes(e2)
+    # both patterns leave every row syndrome and every plain column sum at zero ...
+    for s in (s1, s2):
+        assert np.all(s[0] == 0) and np.all(s[1] == 0) and np.all(s[2] == 0)
+    # ... and their weighted column syndromes are proportional: the printed e2 is twice the
+    # pattern that collides with e1 (e1 moved to rows 3-4); the halved e2 collides exactly.
+    assert np.array_equal(s2[3], 2 * s1[3])
+    e1_shift = pattern("e1", at=where["e2"])
+    assert np.array_equal(e1_shift * 2, e2)
+    for a, b in zip(oc.syndromes(e1_shift), s1):
+        assert np.array_equal(a, b)
+    # the decoder must not "correct" such a pattern
+    A, B = int_mats(9, n, 4, m)
+    AP, BP = oc.encode_a(A), oc.encode_b(B)
+    clean = oc.encoded_product(A, AP, B, BP)
+    res = oc.decode(clean + e1, A, AP, B, BP, TAU0)
+    assert res.status == UNCORRECTABLE and res.s == 0 and res.t == 3
+
+
+# ---- pin 8: Lemma 3 / Eq. (5): the 16 constraints on a 3x3 error block have rank 8
+def _eval_tokens(expr, env):
+    return float(eval(expr, {"__builtins__": {}}, env))
+
+
+def _oracle_constraint_matrix(n, m, srows, tcols):
+    """Column p = response of (row, column, global) checks to a unit error at position p."""
+    cols = []
+    for i in srows:
+        for j in tcols:
+            E = np.zeros((n + 2, m + 2)); E[i, j] = 1.0
+            r1, r2, q1, q2 = oc.syndromes(E)
+            g = oc.global_syndromes(E)
+            col = []
+            for si in srows:
+                col += [r1[si], r2[si]]
+            col += [q2[tj] for tj in tcols] + [q1[tj] for tj in tcols]      # printed row order
+            col += list(g)
+            cols.append(col)
+    return np.array(cols).T
+
+
+@pytest.mark.parametrize("s,t", [((1, 2, 3), (1, 2, 3)), ((2, 5, 9), (1, 4, 6)), ((1, 3, 10), (7, 8, 12))])
+def test_lemma3_rank_and_printed_matrix(s, t):
+    env = dict(s1=s[0], s2=s[1], s3=s[2], t1=t[0], t2=t[1], t3=t[2])
+    printed = []
+    for line in open(os.path.join(GOLDEN, "eq5_system.txt")):
+        if line.strip() and not line.startswith("#"):
+            printed.append([_eval_tokens(tok, env) for tok in line.split()])
+    printed = np.array(printed)
+    assert printed.shape == (16, 9)
+    n, m = 12, 14
+    M = _oracle_constraint_matrix(n, m, [v - 1 for v in s], [v - 1 for v in t])
+    # Row 15 of the printed matrix (the s-weighted global check) lists s1 s2 s3 three times;
+    # with unknowns ordered row-major in (s, t) it has to read s1 s1 s1 s2 s2 s2 s3 s3 s3.
+    fixed = printed.copy()
+    fixed[14] = np.repeat([float(v) for v in s], 3)
+    assert np.array_equal(M, fixed)
+    assert np.linalg.matrix_rank(M) == 8
+    # null direction = last column of the printed row-reduced matrix (e_p = -c_p e_9)
+    last = [_eval_tokens(line, env) for line in open(os.path.join(GOLDEN, "lemma3_reduced_last_column.txt"))
+            if line.strip() and not line.startswith("#")]
+    null = np.array([-c for c in last] + [1.0])
+    assert np.allclose(M @ null, 0, atol=1e-9)
+    # consequence (Corollary 4): a 3x3 pattern along the null direction satisfies every
+    # check of Definition 1, so it is invisible -- the decoder has to report "clean"
+    A, B = int_mats(13, n, 3, m)
+    AP, BP = oc.encode_a(A), oc.encode_b(B)
+    Cbar = oc.encoded_product(A, AP, B, BP)
+    scale = (s[0] - s[1]) * (t[0] - t[1])
+    for p, (i, j) in enumerate((i, j) for i in s for j in t):
+        Cbar[i - 1, j - 1] += null[p] * scale
+    assert np.all(oc.global_syndromes(Cbar) == 0)
+    res = oc.decode(Cbar, A, AP, B, BP, TAU0)
+    assert res.status == CLEAN and (res.s, res.t) == (0, 0)
+
+
+# ---- pin 9: reductions to the textbook schemes the paper builds on (Section I)
+def test_reduces_to_single_checksum_abft_and_weighted_checksum():
+    n, k, m = 8, 5, 9
+    A, B = int_mats(99, n, k, m)
+    AP, BP = oc.encode_a(A), oc.encode_b(B)
+    Cbar = oc.encoded_product(A, AP, B, BP)
+    Cbar[6, 2] += 4.0
+    r1, r2, q1, q2 = oc.syndromes(Cbar)
+    # checksum ABFT: the intersection of the flagged row and column locates the symbol, the
+    # plain checksum difference is its error
+    assert np.nonzero(r1)[0].tolist() == [6] and np.nonzero(q1)[0].tolist() == [2] and r1[6] == q1[2] == 4.0
+    # weighted checksum: ratio of weighted to plain syndrome is the (1-based) position
+    assert q2[2] / q1[2] == 7 and r2[6] / r1[6] == 3
+
+
+# ---- pin 10: rounding remark of Section V -- with real data the corrected symbols agree
+#      with an independently computed product up to rounding
+def test_real_valued_correction_matches_independent_product():
+    rng = np.random.default_rng(2)
+    n, k, m = 40, 30, 50
+    A, B = rng.standard_normal((n, k)), rng.standard_normal((k, m))
+    tau = Thresholds(1e-8, 1e-6, 1e-8, 1e-6)
+    ref = np.einsum("il,lj->ij", A, B)
+    A2 = A.copy(); A2[7, 3] += 11.5
+    res = oc.protected_gemm(A, B, A2, B, [(20, 41, -3.25)], tau)
+    assert res.status == CORRECTED
+    assert [(e[0], e[1], e[2]) for e in res.errors] == [(MAT_A, 7, 3), (MAT_C, 20, 41)]
+    assert np.allclose([e[3] for e in res.errors], [11.5, -3.25], rtol=0, atol=1e-9)
+    assert np.max(np.abs(res.C - ref)) < 1e-9 and np.max(np.abs(res.A - A)) < 1e-12
