@@ -1,0 +1,186 @@
+/*
+ * gecc -- grid-code protected matrix product for AMD MI355X (gfx950).
+ *
+ * C ABI of the library.  The calls follow the paper's statement of the
+ * problem: encode A and B (Section III), multiply the encoded operands
+ * (Section III, C-bar = A-bar B-bar), verify (Section V step 1), correct
+ * (Section V step 2), and return the corrected C plus the located errors.
+ *
+ * Conventions
+ *   - All indices in this ABI are 0-based; the weight of 0-based index i in a
+ *     weighted parity is i+1 (the paper's index sets start at 1, Section II-A).
+ *   - Logical shapes: A is n x k, B is k x m, C is n x m (Section II-A).
+ *   - "dev" pointers are device (HBM) addresses, "host" pointers host
+ *     addresses.  Every device buffer is allocated and owned by the caller;
+ *     the library allocates no device memory and frees none.
+ *   - All work is enqueued on the HIP stream handed in (a hipStream_t passed
+ *     as void*; NULL = the default stream).  No call synchronises except
+ *     gecc_report_to_host.
+ *   - Return value: 0 = ok, negative = usage or HIP error (see
+ *     gecc_strerror); nothing throws or aborts.  The outcome of decoding
+ *     travels in gecc_report.status, not in the return value.
+ *   - Calls on one context must not overlap in time (they share the context's
+ *     workspace); use one context per concurrent stream.
+ */
+#ifndef GECC_H
+#define GECC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct gecc_ctx gecc_ctx; /* opaque */
+
+/* element type of A and B; products accumulate in fp32 and C is fp32 */
+enum { GECC_F32 = 0, GECC_BF16 = 1 };
+
+/* decode outcome */
+enum {
+  GECC_CLEAN = 0,         /* every syndrome inside its threshold                    */
+  GECC_CORRECTED = 1,     /* errors located and removed                             */
+  GECC_UNCORRECTABLE = 2, /* pattern beyond the code: recompute (Section V, step 1) */
+  GECC_DETECTED = 3       /* gecc_verify found flagged lines; gecc_correct not run  */
+};
+
+/* which matrix a located error sits in */
+enum { GECC_MAT_A = 0, GECC_MAT_B = 1, GECC_MAT_C = 2 };
+
+/* error codes */
+enum {
+  GECC_OK = 0,
+  GECC_ERR_ARG = -1,       /* null pointer, non-positive size, bad enum, bad leading dim */
+  GECC_ERR_WORKSPACE = -2, /* workspace missing or too small                             */
+  GECC_ERR_HIP = -3,       /* a HIP runtime call failed (launch, copy)                   */
+  GECC_ERR_ALIGN = -4      /* a device pointer is not aligned to its element type (A, B: 2 or
+                              4 bytes; C: 4; parity buffers: 8; workspace: 256).  Operands
+                              whose base and rows are 16-byte aligned (lda/ldb multiples of 8
+                              bf16 or 4 fp32 elements, ldc a multiple of 4) take the vector
+                              paths; others are correct but slower                        */
+};
+
+typedef struct {
+  int32_t n, k, m;          /* logical sizes, each >= 1                                   */
+  int32_t batch;            /* number of independent products, >= 1                       */
+  int32_t dtype;            /* GECC_F32 or GECC_BF16                                      */
+  int32_t trans_a;          /* 0: A stored n x k row-major (k contiguous), lda >= k
+                               1: A stored k x n row-major (n contiguous), lda >= n       */
+  int32_t trans_b;          /* 0: B stored k x m row-major (m contiguous), ldb >= m
+                               1: B stored m x k row-major (k contiguous), ldb >= k       */
+  int32_t refine;           /* 1: after Section V's subtraction, every patched symbol of C
+                               is re-evaluated as its k-term dot product in fp64 (removes
+                               the sqrt(n)-fold rounding noise the subtraction inherits)  */
+  int64_t lda, ldb, ldc;    /* leading dimensions in elements; C is n x m row-major       */
+  int64_t stride_a, stride_b, stride_c; /* element distance between batch items           */
+  /* detection thresholds, one per syndrome family (the delta of Section V):
+     row plain, row weighted, column plain, column weighted; operand audit */
+  double tau_r1, tau_r2, tau_q1, tau_q2, tau_op;
+} gecc_params;
+
+/* one located error: `magnitude` is the additive offset that was removed */
+typedef struct {
+  int32_t matrix, row, col, reserved;
+  double magnitude;
+} gecc_err;
+
+#define GECC_MAX_ERR 8
+
+/* per batch item, written to device memory by verify / correct */
+typedef struct {
+  int32_t status;            /* GECC_CLEAN / CORRECTED / UNCORRECTABLE / DETECTED         */
+  int32_t s, t;              /* flagged rows / columns at first detection (Section V)     */
+  int32_t n_err;             /* entries used in err[], sorted by (matrix, row, col)       */
+  gecc_err err[GECC_MAX_ERR];
+  double max_abs_synd[4];    /* max |r1|, |r2|, |q1|, |q2| at first detection             */
+} gecc_report;
+
+/* a fault to be planted into the product while it is computed (E3 of Section II-A):
+   offset is added to data symbol (row, col) of batch item `batch` before the
+   syndromes are formed and before C is stored */
+typedef struct {
+  int32_t batch, row, col;
+  float offset;
+} gecc_fault;
+
+#define GECC_MAX_FAULTS 16
+
+/* ---- context ------------------------------------------------------------------------ */
+
+/* Validates *p and builds a context (host memory only). *out receives it. */
+int gecc_create(gecc_ctx** out, const gecc_params* p);
+void gecc_destroy(gecc_ctx* ctx);
+
+/* Bytes of device workspace the context needs (partial syndromes, syndromes, decoder
+   state, audit parities).  The caller allocates it (256-byte aligned) and hands it over;
+   it stays the caller's.  Its contents need not be initialised. */
+size_t gecc_workspace_bytes(const gecc_ctx* ctx);
+int gecc_set_workspace(gecc_ctx* ctx, void* dev_workspace, size_t bytes);
+
+/* Sizes (in doubles, per batch item) of the parity buffers below. */
+size_t gecc_a_par_len(const gecc_ctx* ctx); /* 2*k           */
+size_t gecc_b_par_len(const gecc_ctx* ctx); /* 2*k           */
+size_t gecc_c_par_len(const gecc_ctx* ctx); /* 2*n + 2*m + 4 */
+
+/* ---- the path ----------------------------------------------------------------------- */
+
+/* S1, Section III (A_P = [P_n1; P_n2] A).  dev_A: the operand, read only.
+   dev_A_par (out): batch x [2][k] doubles; [0][l] = sum_i a_il, [1][l] = sum_i (i+1) a_il. */
+int gecc_encode_a(gecc_ctx* ctx, const void* dev_A, double* dev_A_par, void* stream);
+
+/* S2, Section III (B_P = B [P_m1^T P_m2^T]).
+   dev_B_par (out): batch x [2][k] doubles; [0][l] = sum_j b_lj, [1][l] = sum_j (j+1) b_lj. */
+int gecc_encode_b(gecc_ctx* ctx, const void* dev_B, double* dev_B_par, void* stream);
+
+/* S3, Section III (C-bar = A-bar B-bar).  Writes the data block C (fp32, n x m, ldc) and
+   the parity blocks into dev_C_par: batch x { P_r [2][n], P_c [2][m], P_g [4] } doubles with
+   P_r[0][i] = cbar_{i,m+1}, P_r[1][i] = cbar_{i,m+2}, P_c[0][j] = cbar_{n+1,j},
+   P_c[1][j] = cbar_{n+2,j}, P_g = {cbar_{n+1,m+1}, cbar_{n+1,m+2}, cbar_{n+2,m+1},
+   cbar_{n+2,m+2}}.  The product kernel also leaves per-tile partial row/column sums of the
+   C it computed in the workspace, for gecc_verify(fused=1).
+   dev_faults: NULL or n_faults (<= GECC_MAX_FAULTS) entries in device memory. */
+int gecc_multiply(gecc_ctx* ctx, const void* dev_A, const double* dev_A_par, const void* dev_B,
+                  const double* dev_B_par, float* dev_C, double* dev_C_par,
+                  const gecc_fault* dev_faults, int32_t n_faults, void* stream);
+
+/* S4 + S5, Section V step 1: the four syndrome families and the threshold tests.
+   fused = 1: use the partial sums gecc_multiply left in the workspace (C is not read);
+   fused = 0: scan dev_C (for a C modified after the product, or produced elsewhere).
+   dev_report (out): batch entries; status = GECC_CLEAN or GECC_DETECTED, s, t,
+   max_abs_synd filled. */
+int gecc_verify(gecc_ctx* ctx, const float* dev_C, const double* dev_C_par,
+                gecc_report* dev_report, int32_t fused, void* stream);
+
+/* S6 + S7, Section V step 2 and the operand audit: locates and removes the errors.
+   Patches dev_A / dev_B / dev_C / dev_C_par in place; dev_report must be the one
+   gecc_verify just filled.  All work is gated on device-side state, so the call is cheap
+   when the report says CLEAN.  On GECC_UNCORRECTABLE the buffers hold whatever the attempt
+   left behind and the product has to be recomputed. */
+int gecc_correct(gecc_ctx* ctx, void* dev_A, const double* dev_A_par, void* dev_B,
+                 const double* dev_B_par, float* dev_C, double* dev_C_par,
+                 gecc_report* dev_report, void* stream);
+
+/* encode_a, encode_b, multiply, verify(fused), correct in stream order. */
+int gecc_protected_gemm(gecc_ctx* ctx, void* dev_A, void* dev_B, float* dev_C, double* dev_A_par,
+                        double* dev_B_par, double* dev_C_par, gecc_report* dev_report,
+                        void* stream);
+
+/* The same product kernel without parity work and without the syndrome epilogue:
+   the denominator of the overhead figure. */
+int gecc_plain_gemm(gecc_ctx* ctx, const void* dev_A, const void* dev_B, float* dev_C, void* stream);
+
+/* Copies `count` reports device -> host on `stream` and waits for it. */
+int gecc_report_to_host(gecc_ctx* ctx, const gecc_report* dev_report, gecc_report* host_report,
+                        int32_t count, void* stream);
+
+/* Copies the syndromes of the last gecc_verify (r1[n], r2[n], q1[m], q2[m] per batch item,
+   doubles) device -> host and waits; for threshold calibration. */
+int gecc_syndromes_to_host(gecc_ctx* ctx, double* host_syndromes, void* stream);
+
+const char* gecc_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GECC_H */

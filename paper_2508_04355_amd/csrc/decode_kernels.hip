@@ -1,0 +1,519 @@
+// Section V on the device: syndromes from the per-tile partial sums, threshold tests, the
+// correction rule for flagged rows/columns, and the operand audit that completes it for
+// errors in A and B (each column of [A; A_P] and each row of [B B_P] is a codeword with two
+// parity symbols, Section III).  All scalar decoding arithmetic is fp64; everything is
+// stream-ordered and gated on state kept in device memory, so no host round trip is needed.
+#include "gecc_internal.h"
+
+namespace gecc {
+namespace {
+
+struct Est { int i, j; double x, u; };
+
+__device__ __forceinline__ DecodeState* state_of(const DecodeArgs& a, int b) { return a.state + b; }
+__device__ __forceinline__ double* synd_of(const DecodeArgs& a, int b) {
+  return a.synd + (int64_t)b * (2 * a.p.n + 2 * a.p.m);
+}
+__device__ __forceinline__ double* cpar_of(const DecodeArgs& a, int b) {
+  return a.C_par + (int64_t)b * (2 * a.p.n + 2 * a.p.m + 4);
+}
+
+__device__ __forceinline__ double load_elem(const void* P, int dtype, int64_t idx) {
+  if (dtype == GECC_BF16)
+    return (double)__uint_as_float(((uint32_t) reinterpret_cast<const uint16_t*>(P)[idx]) << 16);
+  return (double)reinterpret_cast<const float*>(P)[idx];
+}
+// round-to-nearest-even store into the operand's storage type
+__device__ __forceinline__ void store_elem(void* P, int dtype, int64_t idx, double v) {
+  const float f = (float)v;
+  if (dtype == GECC_BF16) {
+    uint32_t u = __float_as_uint(f);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    reinterpret_cast<uint16_t*>(P)[idx] = (uint16_t)(u >> 16);
+  } else {
+    reinterpret_cast<float*>(P)[idx] = f;
+  }
+}
+__device__ __forceinline__ int64_t a_index(const gecc_params& p, int b, int i, int l) {
+  return (int64_t)b * p.stride_a + (p.trans_a ? (int64_t)l * p.lda + i : (int64_t)i * p.lda + l);
+}
+__device__ __forceinline__ int64_t b_index(const gecc_params& p, int b, int l, int j) {
+  return (int64_t)b * p.stride_b + (p.trans_b ? (int64_t)j * p.ldb + l : (int64_t)l * p.ldb + j);
+}
+
+// -------------------------------------------------------------------------------------------
+__global__ void reset_state_kernel(DecodeArgs a) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= a.p.batch) return;
+  DecodeState* s = state_of(a, b);
+  s->s_cnt = 0; s->t_cnt = 0;
+  for (int f = 0; f < 4; ++f) s->maxbits[f] = 0ull;
+  s->phase = PH_DONE;
+  s->a_cnt = 0; s->b_cnt = 0; s->n_err = 0;
+}
+
+// partial sums -> syndromes (sum - parity, Section V step 1) -> flags
+__global__ __launch_bounds__(256) void threshold_kernel(DecodeArgs a, int first) {
+  const int b = blockIdx.y;
+  DecodeState* st = state_of(a, b);
+  if (!first && st->phase != PH_REVERIFY) return;
+  const int n = a.p.n, m = a.p.m;
+  const int o = blockIdx.x * 256 + threadIdx.x;
+  const double* cpar = cpar_of(a, b);
+  double* synd = synd_of(a, b);
+  double v1 = 0.0, v2 = 0.0;
+  bool is_row = o < n, valid = o < n + m;
+  if (valid) {
+    if (is_row) {
+      const int i = o;
+      double S = 0.0, W = 0.0;
+      for (int tn = 0; tn < a.ntn; ++tn) {
+        const float* rp = a.rowpart + (((int64_t)b * a.ntn + tn) * n + i) * 2;
+        const double s = rp[0];
+        S += s;
+        W += (double)rp[1] + (double)(tn * a.tile_n) * s;
+      }
+      v1 = S - cpar[i];
+      v2 = W - cpar[n + i];
+      synd[i] = v1;
+      synd[n + i] = v2;
+      if (fabs(v1) > a.p.tau_r1 || fabs(v2) > a.p.tau_r2) {
+        const int idx = atomicAdd(&st->s_cnt, 1);
+        if (idx < GECC_MAX_ERR) st->rows[idx] = i;
+      }
+    } else {
+      const int j = o - n;
+      double S = 0.0, W = 0.0;
+      for (int tm = 0; tm < a.ntm; ++tm) {
+        const float* cp = a.colpart + (((int64_t)b * a.ntm + tm) * m + j) * 2;
+        const double s = cp[0];
+        S += s;
+        W += (double)cp[1] + (double)(tm * a.tile_m) * s;
+      }
+      v1 = S - cpar[2 * n + j];
+      v2 = W - cpar[2 * n + m + j];
+      synd[2 * n + j] = v1;
+      synd[2 * n + m + j] = v2;
+      if (fabs(v1) > a.p.tau_q1 || fabs(v2) > a.p.tau_q2) {
+        const int idx = atomicAdd(&st->t_cnt, 1);
+        if (idx < GECC_MAX_ERR) st->cols[idx] = j;
+      }
+    }
+  }
+  if (first) {
+    // family maxima: rows go to [0], [1]; columns to [2], [3]; one atomic per wavefront & family
+    double mr1 = (valid && is_row) ? fabs(v1) : 0.0, mr2 = (valid && is_row) ? fabs(v2) : 0.0;
+    double mq1 = (valid && !is_row) ? fabs(v1) : 0.0, mq2 = (valid && !is_row) ? fabs(v2) : 0.0;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+      mr1 = fmax(mr1, __shfl_down(mr1, off, 64));
+      mr2 = fmax(mr2, __shfl_down(mr2, off, 64));
+      mq1 = fmax(mq1, __shfl_down(mq1, off, 64));
+      mq2 = fmax(mq2, __shfl_down(mq2, off, 64));
+    }
+    if ((threadIdx.x & 63) == 0) {
+      if (mr1 > 0.0) atomicMax(&st->maxbits[0], (unsigned long long)__double_as_longlong(mr1));
+      if (mr2 > 0.0) atomicMax(&st->maxbits[1], (unsigned long long)__double_as_longlong(mr2));
+      if (mq1 > 0.0) atomicMax(&st->maxbits[2], (unsigned long long)__double_as_longlong(mq1));
+      if (mq2 > 0.0) atomicMax(&st->maxbits[3], (unsigned long long)__double_as_longlong(mq2));
+    }
+  }
+}
+
+// first report after detection: CLEAN or DETECTED
+__global__ void summarize_kernel(DecodeArgs a) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= a.p.batch) return;
+  DecodeState* st = state_of(a, b);
+  gecc_report* rep = a.report + b;
+  rep->s = st->s_cnt;
+  rep->t = st->t_cnt;
+  rep->n_err = 0;
+  for (int f = 0; f < 4; ++f) rep->max_abs_synd[f] = __longlong_as_double((long long)st->maxbits[f]);
+  rep->status = (st->s_cnt == 0 && st->t_cnt == 0) ? GECC_CLEAN : GECC_DETECTED;
+}
+
+// ---- Section V step 2 ------------------------------------------------------------------------
+__device__ void sort_small(int* v, int cnt) {
+  for (int x = 1; x < cnt; ++x) {
+    const int key = v[x];
+    int y = x - 1;
+    while (y >= 0 && v[y] > key) { v[y + 1] = v[y]; --y; }
+    v[y + 1] = key;
+  }
+}
+
+struct Synd {
+  const double *r1, *r2, *q1, *q2;
+  double tr1, tr2, tq1, tq2;
+};
+
+// every syndrome of a flagged line has to be explained by the estimate, within the thresholds
+// widened by the uncertainty the estimate itself carries
+__device__ bool residual_ok(const Est* est, int ne, const int* Er, int s, const int* Et, int t,
+                            const Synd& y) {
+  for (int a = 0; a < s; ++a) {
+    const int i = Er[a];
+    double sx = 0, su = 0, wx = 0, wu = 0;
+    for (int e = 0; e < ne; ++e)
+      if (est[e].i == i) {
+        sx += est[e].x; su += est[e].u;
+        wx += (est[e].j + 1) * est[e].x; wu += (est[e].j + 1) * est[e].u;
+      }
+    if (fabs(y.r1[i] - sx) > y.tr1 + su) return false;
+    if (fabs(y.r2[i] - wx) > y.tr2 + wu) return false;
+  }
+  for (int c = 0; c < t; ++c) {
+    const int j = Et[c];
+    double sx = 0, su = 0, wx = 0, wu = 0;
+    for (int e = 0; e < ne; ++e)
+      if (est[e].j == j) {
+        sx += est[e].x; su += est[e].u;
+        wx += (est[e].i + 1) * est[e].x; wu += (est[e].i + 1) * est[e].u;
+      }
+    if (fabs(y.q1[j] - sx) > y.tq1 + su) return false;
+    if (fabs(y.q2[j] - wx) > y.tq2 + wu) return false;
+  }
+  return true;
+}
+
+// drops insignificant parts, verifies, sorts by (i, j).  Returns the count or -1.
+__device__ int accept(Est* est, int ne, const int* Er, int s, const int* Et, int t, const Synd& y) {
+  int k = 0;
+  for (int e = 0; e < ne; ++e)
+    if (fabs(est[e].x) > est[e].u) est[k++] = est[e];
+  if (!residual_ok(est, k, Er, s, Et, t, y)) return -1;
+  for (int x = 1; x < k; ++x) {
+    const Est key = est[x];
+    int z = x - 1;
+    while (z >= 0 && (est[z].i > key.i || (est[z].i == key.i && est[z].j > key.j))) {
+      est[z + 1] = est[z];
+      --z;
+    }
+    est[z + 1] = key;
+  }
+  return k;
+}
+
+// Correction rule for 1 <= s, t <= 2 (s <= t: columns carry the information; s > t mirrored).
+__device__ int d0_correct(Est* out, const int* Er, int s, const int* Et, int t, const Synd& y) {
+  Est est[4];
+  if (s <= t) {
+    if (s == 1) {
+      for (int c = 0; c < t; ++c) est[c] = Est{Er[0], Et[c], y.q1[Et[c]], y.tq1};
+      const int k = accept(est, t, Er, s, Et, t, y);
+      for (int e = 0; e < k; ++e) out[e] = est[e];
+      return k;
+    }
+    const int s1 = Er[0], s2 = Er[1], t1 = Et[0], t2 = Et[1];
+    Est dg[4] = {Est{s1, t1, y.q1[t1], y.tq1}, Est{s2, t2, y.q1[t2], y.tq1}};
+    Est an[4] = {Est{s1, t2, y.q1[t2], y.tq1}, Est{s2, t1, y.q1[t1], y.tq1}};
+    const int kd = accept(dg, 2, Er, s, Et, t, y);
+    const int ka = accept(an, 2, Er, s, Et, t, y);
+    if (kd >= 0 && ka >= 0) return -1;   // cannot tell the two apart
+    if (kd >= 0) { for (int e = 0; e < kd; ++e) out[e] = dg[e]; return kd; }
+    if (ka >= 0) { for (int e = 0; e < ka; ++e) out[e] = an[e]; return ka; }
+    const double w1 = s1 + 1.0, w2 = s2 + 1.0;
+    int ne = 0;
+    for (int c = 0; c < 2; ++c) {
+      const int j = Et[c];
+      const double e2 = (y.q2[j] - w1 * y.q1[j]) / (w2 - w1);
+      const double e1 = y.q1[j] - e2;
+      const double u2 = (y.tq2 + w1 * y.tq1) / (w2 - w1);
+      const double u1 = y.tq1 + u2;
+      est[ne++] = Est{s1, j, e1, u1};
+      est[ne++] = Est{s2, j, e2, u2};
+    }
+    const int k = accept(est, ne, Er, s, Et, t, y);
+    for (int e = 0; e < k; ++e) out[e] = est[e];
+    return k;
+  }
+  for (int r = 0; r < s; ++r) est[r] = Est{Er[r], Et[0], y.r1[Er[r]], y.tr1};
+  const int k = accept(est, s, Er, s, Et, t, y);
+  for (int e = 0; e < k; ++e) out[e] = est[e];
+  return k;
+}
+
+// fp64 dot product of row i of A with column j of B over k, by the whole workgroup
+__device__ double block_dot(const DecodeArgs& a, int b, int i, int j, double* red) {
+  double s = 0.0;
+  for (int l = threadIdx.x; l < a.p.k; l += blockDim.x)
+    s = fma(load_elem(a.A, a.p.dtype, a_index(a.p, b, i, l)),
+            load_elem(a.B, a.p.dtype, b_index(a.p, b, l, j)), s);
+  red[threadIdx.x] = s;
+  __syncthreads();
+  for (int w = blockDim.x / 2; w > 0; w >>= 1) {
+    if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
+    __syncthreads();
+  }
+  const double r = red[0];
+  __syncthreads();
+  return r;
+}
+
+// One workgroup per batch item.  final_pass = 0: right after detection; = 1: after the operand
+// audit and the residual syndrome pass.
+__global__ __launch_bounds__(256) void decode_c_kernel(DecodeArgs a, int final_pass) {
+  const int b = blockIdx.x;
+  DecodeState* st = state_of(a, b);
+  gecc_report* rep = a.report + b;
+  if (final_pass) { if (st->phase != PH_REVERIFY) return; }
+  else            { if (rep->status != GECC_DETECTED) return; }
+
+  __shared__ Est fix[4];
+  __shared__ int nfix;          // -1: the rule does not apply / failed
+  __shared__ double red[256];
+  const int n = a.p.n, m = a.p.m;
+  if (threadIdx.x == 0) {
+    const int s = st->s_cnt, t = st->t_cnt;
+    nfix = -1;
+    if (s == 0 && t == 0) {
+      nfix = 0;
+    } else if (s >= 1 && s <= 2 && t >= 1 && t <= 2) {
+      int Er[2], Et[2];
+      for (int x = 0; x < s; ++x) Er[x] = st->rows[x];
+      for (int x = 0; x < t; ++x) Et[x] = st->cols[x];
+      sort_small(Er, s);
+      sort_small(Et, t);
+      const double* sy = synd_of(a, b);
+      Synd y{sy, sy + n, sy + 2 * n, sy + 2 * n + m, a.p.tau_r1, a.p.tau_r2, a.p.tau_q1, a.p.tau_q2};
+      Est tmp[4];
+      const int k = d0_correct(tmp, Er, s, Et, t, y);
+      if (k >= 0 && st->n_err + k <= GECC_MAX_ERR) {
+        for (int e = 0; e < k; ++e) fix[e] = tmp[e];
+        nfix = k;
+      }
+    }
+  }
+  __syncthreads();
+  const int k = nfix;
+  if (k < 0) {
+    if (threadIdx.x == 0) {
+      if (final_pass) { rep->status = GECC_UNCORRECTABLE; rep->n_err = 0; st->phase = PH_DONE; }
+      else            { st->phase = PH_AUDIT; }
+    }
+    return;
+  }
+  // patch C: Section V's subtraction, optionally followed by re-evaluating the symbol
+  float* C = a.C + (int64_t)b * a.p.stride_c;
+  for (int e = 0; e < k; ++e) {
+    const int64_t idx = (int64_t)fix[e].i * a.p.ldc + fix[e].j;
+    if (a.p.refine) {
+      const double d = block_dot(a, b, fix[e].i, fix[e].j, red);
+      if (threadIdx.x == 0) C[idx] = (float)d;
+    } else if (threadIdx.x == 0) {
+      C[idx] = (float)((double)C[idx] - fix[e].x);
+    }
+  }
+  if (threadIdx.x == 0) {
+    int ne = 0;
+    for (int e = 0; e < st->n_err; ++e) rep->err[ne++] = st->errs[e];   // A then B, sorted
+    for (int e = 0; e < k; ++e) {
+      gecc_err g;
+      g.matrix = GECC_MAT_C; g.row = fix[e].i; g.col = fix[e].j; g.reserved = 0;
+      g.magnitude = fix[e].x;
+      rep->err[ne++] = g;
+    }
+    rep->n_err = ne;
+    rep->status = GECC_CORRECTED;
+    st->phase = PH_DONE;
+  }
+}
+
+// ---- operand audit -----------------------------------------------------------------------------
+// blockIdx.y: 0 = A (columns l of A), 1 = B (rows l of B).  A single wrong symbol of a line
+// shows as (u1, u2) = (e, (pos+1) e) in the difference of re-formed and stored parities.
+__global__ __launch_bounds__(256) void audit_diff_kernel(DecodeArgs a) {
+  const int b = blockIdx.z;
+  DecodeState* st = state_of(a, b);
+  if (st->phase != PH_AUDIT) return;
+  const int l = blockIdx.x * 256 + threadIdx.x;
+  if (l >= a.p.k) return;
+  const bool isA = blockIdx.y == 0;
+  const double* cur = (isA ? a.audit_a : a.audit_b) + (int64_t)b * 2 * a.p.k;
+  const double* ref = (isA ? a.A_par : a.B_par) + (int64_t)b * 2 * a.p.k;
+  const double u1 = cur[l] - ref[l], u2 = cur[a.p.k + l] - ref[a.p.k + l];
+  const double tau = a.p.tau_op;
+  if (!(fabs(u1) > tau || fabs(u2) > tau)) return;
+  AuditHit h;
+  h.line = l; h.pos = -1; h.e = u1;
+  if (fabs(u1) > tau) {
+    const double rho = u2 / u1, w = rint(rho);
+    const int len = isA ? a.p.n : a.p.m;
+    if (fabs(rho - w) < 0.25 && w >= 1.0 && w <= (double)len) h.pos = (int)w - 1;
+  }
+  const int idx = atomicAdd(isA ? &st->a_cnt : &st->b_cnt, 1);
+  if (idx < GECC_MAX_ERR) (isA ? st->a_hits : st->b_hits)[idx] = h;
+}
+
+__device__ void sort_hits(AuditHit* h, int cnt) {
+  for (int x = 1; x < cnt; ++x) {
+    const AuditHit key = h[x];
+    int y = x - 1;
+    while (y >= 0 && h[y].line > key.line) { h[y + 1] = h[y]; --y; }
+    h[y + 1] = key;
+  }
+}
+
+// Remove the rank-one footprint of every audit hit from C-bar, then patch the operands.
+// Order (it absorbs the cross term when an A hit and a B hit share the index l): rows of the
+// A hits first, using B as the product read it; then columns of the B hits, using the
+// corrected A.  The operands themselves are written last, so nothing here depends on a
+// store becoming visible to another wavefront.
+__global__ __launch_bounds__(256) void repair_kernel(DecodeArgs a) {
+  const int b = blockIdx.x;
+  DecodeState* st = state_of(a, b);
+  if (st->phase != PH_AUDIT) return;
+  gecc_report* rep = a.report + b;
+  __shared__ int ok;
+  __shared__ AuditHit ha[GECC_MAX_ERR], hb[GECC_MAX_ERR];
+  const int n = a.p.n, m = a.p.m, k = a.p.k;
+  const int na = st->a_cnt, nb = st->b_cnt;
+  if (threadIdx.x == 0) {
+    ok = (na + nb > 0) && (na + nb <= GECC_MAX_ERR);
+    if (ok) {
+      for (int x = 0; x < na; ++x) { ha[x] = st->a_hits[x]; if (ha[x].pos < 0) ok = 0; }
+      for (int x = 0; x < nb; ++x) { hb[x] = st->b_hits[x]; if (hb[x].pos < 0) ok = 0; }
+    }
+    if (ok) { sort_hits(ha, na); sort_hits(hb, nb); }
+  }
+  __syncthreads();
+  if (!ok) {
+    if (threadIdx.x == 0) { rep->status = GECC_UNCORRECTABLE; rep->n_err = 0; st->phase = PH_DONE; }
+    return;
+  }
+  float* C = a.C + (int64_t)b * a.p.stride_c;
+  double* cpar = cpar_of(a, b);
+  const double* apar = a.A_par + (int64_t)b * 2 * k;
+  const double* bpar = a.B_par + (int64_t)b * 2 * k;
+  for (int x = 0; x < na; ++x) {
+    const int i = ha[x].pos, l = ha[x].line;
+    const double e = ha[x].e;
+    if (threadIdx.x == 0) {
+      cpar[i] -= e * bpar[l];              // cbar_{i,m+1}
+      cpar[n + i] -= e * bpar[k + l];      // cbar_{i,m+2}
+    }
+    for (int j = threadIdx.x; j < m; j += blockDim.x) {
+      const int64_t ic = (int64_t)i * a.p.ldc + j;
+      C[ic] = (float)((double)C[ic] - e * load_elem(a.B, a.p.dtype, b_index(a.p, b, l, j)));
+    }
+    __syncthreads();
+  }
+  for (int x = 0; x < nb; ++x) {
+    const int l = hb[x].line, j = hb[x].pos;
+    const double e = hb[x].e;
+    if (threadIdx.x == 0) {
+      cpar[2 * n + j] -= apar[l] * e;          // cbar_{n+1,j}
+      cpar[2 * n + m + j] -= apar[k + l] * e;  // cbar_{n+2,j}
+    }
+    for (int i = threadIdx.x; i < n; i += blockDim.x) {
+      double av = load_elem(a.A, a.p.dtype, a_index(a.p, b, i, l));
+      for (int z = 0; z < na; ++z)
+        if (ha[z].pos == i && ha[z].line == l) av -= ha[z].e;   // corrected A
+      const int64_t ic = (int64_t)i * a.p.ldc + j;
+      C[ic] = (float)((double)C[ic] - av * e);
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    for (int x = 0; x < na; ++x) {
+      const int64_t ia = a_index(a.p, b, ha[x].pos, ha[x].line);
+      store_elem(a.A, a.p.dtype, ia, load_elem(a.A, a.p.dtype, ia) - ha[x].e);
+    }
+    for (int x = 0; x < nb; ++x) {
+      const int64_t ib = b_index(a.p, b, hb[x].line, hb[x].pos);
+      store_elem(a.B, a.p.dtype, ib, load_elem(a.B, a.p.dtype, ib) - hb[x].e);
+    }
+    // located operand errors, sorted by (matrix, row, col)
+    int ne = 0;
+    for (int x = 0; x < na; ++x) {
+      gecc_err g;
+      g.matrix = GECC_MAT_A; g.row = ha[x].pos; g.col = ha[x].line; g.reserved = 0;
+      g.magnitude = ha[x].e;
+      st->errs[ne++] = g;
+    }
+    for (int x = 1; x < ne; ++x) {           // A hits were ordered by column: reorder by (row, col)
+      const gecc_err key = st->errs[x];
+      int y = x - 1;
+      while (y >= 0 && (st->errs[y].row > key.row ||
+                        (st->errs[y].row == key.row && st->errs[y].col > key.col))) {
+        st->errs[y + 1] = st->errs[y];
+        --y;
+      }
+      st->errs[y + 1] = key;
+    }
+    for (int x = 0; x < nb; ++x) {           // B hits are ordered by row l; one hit per row
+      gecc_err g;
+      g.matrix = GECC_MAT_B; g.row = hb[x].line; g.col = hb[x].pos; g.reserved = 0;
+      g.magnitude = hb[x].e;
+      st->errs[ne++] = g;
+    }
+    st->n_err = ne;
+    st->s_cnt = 0;
+    st->t_cnt = 0;
+    st->phase = PH_REVERIFY;
+  }
+}
+
+// global parity block P_g = A_P B_P (Section III), 2 x 2 per batch item
+__global__ __launch_bounds__(256) void pg_kernel(const double* A_par, const double* B_par,
+                                                 double* C_par, int n, int k, int m) {
+  const int b = blockIdx.x;
+  const double* ap = A_par + (int64_t)b * 2 * k;
+  const double* bp = B_par + (int64_t)b * 2 * k;
+  double acc[4] = {0, 0, 0, 0};
+  for (int l = threadIdx.x; l < k; l += 256) {
+    const double a0 = ap[l], a1 = ap[k + l], b0 = bp[l], b1 = bp[k + l];
+    acc[0] = fma(a0, b0, acc[0]); acc[1] = fma(a0, b1, acc[1]);
+    acc[2] = fma(a1, b0, acc[2]); acc[3] = fma(a1, b1, acc[3]);
+  }
+  __shared__ double red[4][256];
+  for (int q = 0; q < 4; ++q) red[q][threadIdx.x] = acc[q];
+  __syncthreads();
+  for (int w = 128; w > 0; w >>= 1) {
+    if ((int)threadIdx.x < w)
+      for (int q = 0; q < 4; ++q) red[q][threadIdx.x] += red[q][threadIdx.x + w];
+    __syncthreads();
+  }
+  if (threadIdx.x < 4) C_par[(int64_t)b * (2 * n + 2 * m + 4) + 2 * n + 2 * m + threadIdx.x] = red[threadIdx.x][0];
+}
+
+}  // namespace
+
+hipError_t launch_reset_state(const DecodeArgs& a, hipStream_t st) {
+  hipLaunchKernelGGL(reset_state_kernel, dim3((a.p.batch + 63) / 64), dim3(64), 0, st, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_threshold(const DecodeArgs& a, int first, hipStream_t st) {
+  dim3 grid((a.p.n + a.p.m + 255) / 256, a.p.batch);
+  hipLaunchKernelGGL(threshold_kernel, grid, dim3(256), 0, st, a, first);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || !first) return e;
+  hipLaunchKernelGGL(summarize_kernel, dim3((a.p.batch + 63) / 64), dim3(64), 0, st, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_decode_c(const DecodeArgs& a, int final_pass, hipStream_t st) {
+  hipLaunchKernelGGL(decode_c_kernel, dim3(a.p.batch), dim3(256), 0, st, a, final_pass);
+  return hipGetLastError();
+}
+
+hipError_t launch_audit_diff(const DecodeArgs& a, hipStream_t st) {
+  dim3 grid((a.p.k + 255) / 256, 2, a.p.batch);
+  hipLaunchKernelGGL(audit_diff_kernel, grid, dim3(256), 0, st, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_repair(const DecodeArgs& a, hipStream_t st) {
+  hipLaunchKernelGGL(repair_kernel, dim3(a.p.batch), dim3(256), 0, st, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_pg(const double* A_par, const double* B_par, double* C_par, int n, int k, int m,
+                     int batch, hipStream_t st) {
+  hipLaunchKernelGGL(pg_kernel, dim3(batch), dim3(256), 0, st, A_par, B_par, C_par, n, k, m);
+  return hipGetLastError();
+}
+
+}  // namespace gecc

@@ -1,0 +1,346 @@
+// C ABI of libgecc: argument checking, workspace layout and the stream-ordered launch
+// sequences.  Host code only; all arithmetic of the path runs in the kernels.
+#include <new>
+#include "gecc_internal.h"
+
+using namespace gecc;
+
+namespace {
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+size_t elem_size(int dtype) { return dtype == GECC_BF16 ? 2 : 4; }
+
+void make_layout(gecc_ctx* c) {
+  const gecc_params& p = c->p;
+  const size_t b = p.batch, n = p.n, k = p.k, m = p.m;
+  Layout& L = c->lay;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+  L.rowpart = take(b * c->ntn * n * 2 * sizeof(float));
+  L.colpart = take(b * c->ntm * m * 2 * sizeof(float));
+  L.synd = take(b * (2 * n + 2 * m) * sizeof(double));
+  L.state = take(b * sizeof(DecodeState));
+  L.audit_a = take(b * 2 * k * sizeof(double));
+  L.audit_b = take(b * 2 * k * sizeof(double));
+  // column reductions: A side reduces over n (A stored n x k) or over k (P_r with A stored
+  // k x n); B side over k (P_c with B stored k x m) or over m (B stored m x k)
+  const size_t sa = p.trans_a ? coldot_scratch_doubles(p.k, p.n, p.batch)
+                              : coldot_scratch_doubles(p.n, p.k, p.batch);
+  const size_t sb = p.trans_b ? coldot_scratch_doubles(p.m, p.k, p.batch)
+                              : coldot_scratch_doubles(p.k, p.m, p.batch);
+  L.scan_a = take(sa * sizeof(double));
+  L.scan_b = take(sb * sizeof(double));
+  L.total = off;
+}
+
+int check_ws(const gecc_ctx* c) {
+  if (!c) return GECC_ERR_ARG;
+  if (!c->ws || c->ws_bytes < c->lay.total) return GECC_ERR_WORKSPACE;
+  return GECC_OK;
+}
+
+int hip_rc(hipError_t e) { return e == hipSuccess ? GECC_OK : GECC_ERR_HIP; }
+
+// operands need only their natural alignment; 16-byte aligned rows get the vector paths
+bool aligned_to(const void* p, size_t a) { return reinterpret_cast<uintptr_t>(p) % a == 0; }
+
+DecodeArgs decode_args(gecc_ctx* c, void* A, const double* A_par, void* B, const double* B_par,
+                       float* C, double* C_par, gecc_report* rep) {
+  DecodeArgs d;
+  d.p = c->p;
+  d.tile_m = c->tile_m; d.tile_n = c->tile_n; d.ntm = c->ntm; d.ntn = c->ntn;
+  d.A = A; d.B = B; d.C = C;
+  d.A_par = A_par; d.B_par = B_par; d.C_par = C_par;
+  d.rowpart = reinterpret_cast<float*>(c->ws + c->lay.rowpart);
+  d.colpart = reinterpret_cast<float*>(c->ws + c->lay.colpart);
+  d.synd = reinterpret_cast<double*>(c->ws + c->lay.synd);
+  d.state = reinterpret_cast<DecodeState*>(c->ws + c->lay.state);
+  d.audit_a = reinterpret_cast<double*>(c->ws + c->lay.audit_a);
+  d.audit_b = reinterpret_cast<double*>(c->ws + c->lay.audit_b);
+  d.report = rep;
+  return d;
+}
+
+// out[2][k] = parity of A over its n-index with weights w (null: Section III's index weights)
+ScanArgs scan_base(const gecc_ctx* c, const void* X, int64_t ld, int64_t xs) {
+  ScanArgs s{};
+  s.X = X; s.dtype = c->p.dtype; s.ld = ld; s.xs = xs; s.batch = c->p.batch;
+  s.gate = nullptr; s.gate_stride = 0; s.gate_value = 0;
+  return s;
+}
+
+// reduce A over its row index i (length n) -> [2][k]
+hipError_t reduce_a_over_n(gecc_ctx* c, const void* A, const double* w, double* out,
+                           const int32_t* gate, hipStream_t st) {
+  const gecc_params& p = c->p;
+  ScanArgs s = scan_base(c, A, p.lda, p.stride_a);
+  s.w = w; s.out = out; s.w_stride = 2 * (int64_t)p.n; s.out_stride = 2 * (int64_t)p.k;
+  s.gate = gate; s.gate_stride = sizeof(DecodeState); s.gate_value = PH_AUDIT;
+  if (p.trans_a) { s.R = p.k; s.Cc = p.n; return launch_rowdot(s, st); }   // stored k x n
+  s.R = p.n; s.Cc = p.k;
+  s.scratch = reinterpret_cast<double*>(c->ws + c->lay.scan_a);
+  return launch_coldot(s, st);
+}
+// reduce A over its column index l (length k) -> [2][n]
+hipError_t reduce_a_over_k(gecc_ctx* c, const void* A, const double* w, double* out,
+                           int64_t out_stride, hipStream_t st) {
+  const gecc_params& p = c->p;
+  ScanArgs s = scan_base(c, A, p.lda, p.stride_a);
+  s.w = w; s.out = out; s.w_stride = 2 * (int64_t)p.k; s.out_stride = out_stride;
+  if (p.trans_a) {
+    s.R = p.k; s.Cc = p.n;
+    s.scratch = reinterpret_cast<double*>(c->ws + c->lay.scan_a);
+    return launch_coldot(s, st);
+  }
+  s.R = p.n; s.Cc = p.k;
+  return launch_rowdot(s, st);
+}
+// reduce B over its column index j (length m) -> [2][k]
+hipError_t reduce_b_over_m(gecc_ctx* c, const void* B, const double* w, double* out,
+                           const int32_t* gate, hipStream_t st) {
+  const gecc_params& p = c->p;
+  ScanArgs s = scan_base(c, B, p.ldb, p.stride_b);
+  s.w = w; s.out = out; s.w_stride = 2 * (int64_t)p.m; s.out_stride = 2 * (int64_t)p.k;
+  s.gate = gate; s.gate_stride = sizeof(DecodeState); s.gate_value = PH_AUDIT;
+  if (p.trans_b) {                                                         // stored m x k
+    s.R = p.m; s.Cc = p.k;
+    s.scratch = reinterpret_cast<double*>(c->ws + c->lay.scan_b);
+    return launch_coldot(s, st);
+  }
+  s.R = p.k; s.Cc = p.m;
+  return launch_rowdot(s, st);
+}
+// reduce B over its row index l (length k) -> [2][m]
+hipError_t reduce_b_over_k(gecc_ctx* c, const void* B, const double* w, double* out,
+                           int64_t out_stride, hipStream_t st) {
+  const gecc_params& p = c->p;
+  ScanArgs s = scan_base(c, B, p.ldb, p.stride_b);
+  s.w = w; s.out = out; s.w_stride = 2 * (int64_t)p.k; s.out_stride = out_stride;
+  if (p.trans_b) { s.R = p.m; s.Cc = p.k; return launch_rowdot(s, st); }
+  s.R = p.k; s.Cc = p.m;
+  s.scratch = reinterpret_cast<double*>(c->ws + c->lay.scan_b);
+  return launch_coldot(s, st);
+}
+
+GemmArgs gemm_args(const gecc_ctx* c, const void* A, const void* B, float* C) {
+  const gecc_params& p = c->p;
+  GemmArgs g{};
+  g.A = A; g.B = B; g.C = C;
+  g.dtype = p.dtype; g.trans_a = p.trans_a; g.trans_b = p.trans_b;
+  g.n = p.n; g.k = p.k; g.m = p.m; g.batch = p.batch;
+  g.lda = p.lda; g.ldb = p.ldb; g.ldc = p.ldc;
+  g.sa = p.stride_a; g.sb = p.stride_b; g.sc = p.stride_c;
+  g.tile_m = c->tile_m; g.tile_n = c->tile_n; g.ntm = c->ntm; g.ntn = c->ntn;
+  return g;
+}
+
+}  // namespace
+
+extern "C" {
+
+int gecc_create(gecc_ctx** out, const gecc_params* p) {
+  if (!out || !p) return GECC_ERR_ARG;
+  *out = nullptr;
+  if (p->n < 1 || p->k < 1 || p->m < 1 || p->batch < 1) return GECC_ERR_ARG;
+  if (p->dtype != GECC_F32 && p->dtype != GECC_BF16) return GECC_ERR_ARG;
+  if ((p->trans_a != 0 && p->trans_a != 1) || (p->trans_b != 0 && p->trans_b != 1)) return GECC_ERR_ARG;
+  if (p->lda < (p->trans_a ? p->n : p->k)) return GECC_ERR_ARG;
+  if (p->ldb < (p->trans_b ? p->k : p->m)) return GECC_ERR_ARG;
+  if (p->ldc < p->m) return GECC_ERR_ARG;
+  if (p->batch > 1) {
+    const int64_t rows_a = p->trans_a ? p->k : p->n, rows_b = p->trans_b ? p->m : p->k;
+    if (p->stride_a < rows_a * p->lda || p->stride_b < rows_b * p->ldb ||
+        p->stride_c < (int64_t)p->n * p->ldc)
+      return GECC_ERR_ARG;
+  }
+  if (!(p->tau_r1 >= 0) || !(p->tau_r2 >= 0) || !(p->tau_q1 >= 0) || !(p->tau_q2 >= 0) ||
+      !(p->tau_op >= 0))
+    return GECC_ERR_ARG;
+  if ((int64_t)p->n + p->m > (int64_t)1 << 30) return GECC_ERR_ARG;
+  gecc_ctx* c = new (std::nothrow) gecc_ctx;
+  if (!c) return GECC_ERR_ARG;
+  c->p = *p;
+  c->tile_m = 128;
+  c->tile_n = 128;
+  c->ntm = (p->n + c->tile_m - 1) / c->tile_m;
+  c->ntn = (p->m + c->tile_n - 1) / c->tile_n;
+  c->ws = nullptr;
+  c->ws_bytes = 0;
+  make_layout(c);
+  *out = c;
+  return GECC_OK;
+}
+
+void gecc_destroy(gecc_ctx* ctx) { delete ctx; }
+
+size_t gecc_workspace_bytes(const gecc_ctx* ctx) { return ctx ? ctx->lay.total : 0; }
+
+int gecc_set_workspace(gecc_ctx* ctx, void* dev_workspace, size_t bytes) {
+  if (!ctx || !dev_workspace) return GECC_ERR_ARG;
+  if (reinterpret_cast<uintptr_t>(dev_workspace) % 256) return GECC_ERR_ALIGN;
+  if (bytes < ctx->lay.total) return GECC_ERR_WORKSPACE;
+  ctx->ws = static_cast<char*>(dev_workspace);
+  ctx->ws_bytes = bytes;
+  return GECC_OK;
+}
+
+size_t gecc_a_par_len(const gecc_ctx* ctx) { return ctx ? 2 * (size_t)ctx->p.k : 0; }
+size_t gecc_b_par_len(const gecc_ctx* ctx) { return ctx ? 2 * (size_t)ctx->p.k : 0; }
+size_t gecc_c_par_len(const gecc_ctx* ctx) {
+  return ctx ? 2 * (size_t)ctx->p.n + 2 * (size_t)ctx->p.m + 4 : 0;
+}
+
+int gecc_encode_a(gecc_ctx* ctx, const void* dev_A, double* dev_A_par, void* stream) {
+  int rc = check_ws(ctx);
+  if (rc) return rc;
+  if (!dev_A || !dev_A_par) return GECC_ERR_ARG;
+  if (!aligned_to(dev_A, elem_size(ctx->p.dtype)) || !aligned_to(dev_A_par, 8)) return GECC_ERR_ALIGN;
+  return hip_rc(reduce_a_over_n(ctx, dev_A, nullptr, dev_A_par, nullptr, (hipStream_t)stream));
+}
+
+int gecc_encode_b(gecc_ctx* ctx, const void* dev_B, double* dev_B_par, void* stream) {
+  int rc = check_ws(ctx);
+  if (rc) return rc;
+  if (!dev_B || !dev_B_par) return GECC_ERR_ARG;
+  if (!aligned_to(dev_B, elem_size(ctx->p.dtype)) || !aligned_to(dev_B_par, 8)) return GECC_ERR_ALIGN;
+  return hip_rc(reduce_b_over_m(ctx, dev_B, nullptr, dev_B_par, nullptr, (hipStream_t)stream));
+}
+
+int gecc_multiply(gecc_ctx* ctx, const void* dev_A, const double* dev_A_par, const void* dev_B,
+                  const double* dev_B_par, float* dev_C, double* dev_C_par,
+                  const gecc_fault* dev_faults, int32_t n_faults, void* stream) {
+  int rc = check_ws(ctx);
+  if (rc) return rc;
+  if (!dev_A || !dev_A_par || !dev_B || !dev_B_par || !dev_C || !dev_C_par) return GECC_ERR_ARG;
+  if (n_faults < 0 || n_faults > GECC_MAX_FAULTS || (n_faults > 0 && !dev_faults)) return GECC_ERR_ARG;
+  if (!aligned_to(dev_A, elem_size(ctx->p.dtype)) || !aligned_to(dev_B, elem_size(ctx->p.dtype)) ||
+      !aligned_to(dev_C, 4) || !aligned_to(dev_C_par, 8) || !aligned_to(dev_A_par, 8) ||
+      !aligned_to(dev_B_par, 8))
+    return GECC_ERR_ALIGN;
+  hipStream_t st = (hipStream_t)stream;
+  const gecc_params& p = ctx->p;
+  hipError_t e;
+  // parity blocks of C-bar: P_r = A B_P (n x 2), P_c = A_P B (2 x m), P_g = A_P B_P
+  const int64_t rec = 2 * (int64_t)p.n + 2 * (int64_t)p.m + 4;
+  if ((e = reduce_a_over_k(ctx, dev_A, dev_B_par, dev_C_par, rec, st)) != hipSuccess) return hip_rc(e);
+  if ((e = reduce_b_over_k(ctx, dev_B, dev_A_par, dev_C_par + 2 * (size_t)p.n, rec, st)) != hipSuccess)
+    return hip_rc(e);
+  if ((e = launch_pg(dev_A_par, dev_B_par, dev_C_par, p.n, p.k, p.m, p.batch, st)) != hipSuccess)
+    return hip_rc(e);
+  GemmArgs g = gemm_args(ctx, dev_A, dev_B, dev_C);
+  g.rowpart = reinterpret_cast<float*>(ctx->ws + ctx->lay.rowpart);
+  g.colpart = reinterpret_cast<float*>(ctx->ws + ctx->lay.colpart);
+  g.faults = dev_faults;
+  g.n_faults = n_faults;
+  return hip_rc(launch_gemm(g, st));
+}
+
+int gecc_verify(gecc_ctx* ctx, const float* dev_C, const double* dev_C_par, gecc_report* dev_report,
+                int32_t fused, void* stream) {
+  int rc = check_ws(ctx);
+  if (rc) return rc;
+  if (!dev_C_par || !dev_report || (!fused && !dev_C)) return GECC_ERR_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  DecodeArgs d = decode_args(ctx, nullptr, nullptr, nullptr, nullptr, const_cast<float*>(dev_C),
+                             const_cast<double*>(dev_C_par), dev_report);
+  hipError_t e;
+  if ((e = launch_reset_state(d, st)) != hipSuccess) return hip_rc(e);
+  if (!fused) {
+    const gecc_params& p = ctx->p;
+    PartialArgs pa{};
+    pa.C = dev_C; pa.n = p.n; pa.m = p.m; pa.batch = p.batch; pa.ldc = p.ldc; pa.sc = p.stride_c;
+    pa.rowpart = const_cast<float*>(d.rowpart); pa.colpart = const_cast<float*>(d.colpart);
+    pa.tile_m = ctx->tile_m; pa.tile_n = ctx->tile_n; pa.ntm = ctx->ntm; pa.ntn = ctx->ntn;
+    pa.gate = nullptr;
+    if ((e = launch_partials(pa, st)) != hipSuccess) return hip_rc(e);
+  }
+  return hip_rc(launch_threshold(d, 1, st));
+}
+
+int gecc_correct(gecc_ctx* ctx, void* dev_A, const double* dev_A_par, void* dev_B,
+                 const double* dev_B_par, float* dev_C, double* dev_C_par, gecc_report* dev_report,
+                 void* stream) {
+  int rc = check_ws(ctx);
+  if (rc) return rc;
+  if (!dev_A || !dev_A_par || !dev_B || !dev_B_par || !dev_C || !dev_C_par || !dev_report)
+    return GECC_ERR_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  const gecc_params& p = ctx->p;
+  DecodeArgs d = decode_args(ctx, dev_A, dev_A_par, dev_B, dev_B_par, dev_C, dev_C_par, dev_report);
+  const int32_t* gate = &d.state->phase;
+  hipError_t e;
+  // Section V step 2 on the flagged lines; on failure the phase becomes PH_AUDIT
+  if ((e = launch_decode_c(d, 0, st)) != hipSuccess) return hip_rc(e);
+  // operand audit: re-form the parities of A and B as the product read them
+  if ((e = reduce_a_over_n(ctx, dev_A, nullptr, const_cast<double*>(d.audit_a), gate, st)) != hipSuccess)
+    return hip_rc(e);
+  if ((e = reduce_b_over_m(ctx, dev_B, nullptr, const_cast<double*>(d.audit_b), gate, st)) != hipSuccess)
+    return hip_rc(e);
+  if ((e = launch_audit_diff(d, st)) != hipSuccess) return hip_rc(e);
+  if ((e = launch_repair(d, st)) != hipSuccess) return hip_rc(e);
+  // residual syndromes of the repaired C-bar, then Section V once more
+  PartialArgs pa{};
+  pa.C = dev_C; pa.n = p.n; pa.m = p.m; pa.batch = p.batch; pa.ldc = p.ldc; pa.sc = p.stride_c;
+  pa.rowpart = const_cast<float*>(d.rowpart); pa.colpart = const_cast<float*>(d.colpart);
+  pa.tile_m = ctx->tile_m; pa.tile_n = ctx->tile_n; pa.ntm = ctx->ntm; pa.ntn = ctx->ntn;
+  pa.gate = gate; pa.gate_stride = sizeof(DecodeState); pa.gate_value = PH_REVERIFY;
+  if ((e = launch_partials(pa, st)) != hipSuccess) return hip_rc(e);
+  if ((e = launch_threshold(d, 0, st)) != hipSuccess) return hip_rc(e);
+  return hip_rc(launch_decode_c(d, 1, st));
+}
+
+int gecc_protected_gemm(gecc_ctx* ctx, void* dev_A, void* dev_B, float* dev_C, double* dev_A_par,
+                        double* dev_B_par, double* dev_C_par, gecc_report* dev_report, void* stream) {
+  int rc;
+  if ((rc = gecc_encode_a(ctx, dev_A, dev_A_par, stream))) return rc;
+  if ((rc = gecc_encode_b(ctx, dev_B, dev_B_par, stream))) return rc;
+  if ((rc = gecc_multiply(ctx, dev_A, dev_A_par, dev_B, dev_B_par, dev_C, dev_C_par, nullptr, 0, stream)))
+    return rc;
+  if ((rc = gecc_verify(ctx, dev_C, dev_C_par, dev_report, 1, stream))) return rc;
+  return gecc_correct(ctx, dev_A, dev_A_par, dev_B, dev_B_par, dev_C, dev_C_par, dev_report, stream);
+}
+
+int gecc_plain_gemm(gecc_ctx* ctx, const void* dev_A, const void* dev_B, float* dev_C, void* stream) {
+  if (!ctx || !dev_A || !dev_B || !dev_C) return GECC_ERR_ARG;
+  if (!aligned_to(dev_A, elem_size(ctx->p.dtype)) || !aligned_to(dev_B, elem_size(ctx->p.dtype)) ||
+      !aligned_to(dev_C, 4))
+    return GECC_ERR_ALIGN;
+  GemmArgs g = gemm_args(ctx, dev_A, dev_B, dev_C);
+  g.rowpart = nullptr; g.colpart = nullptr; g.faults = nullptr; g.n_faults = 0;
+  return hip_rc(launch_gemm(g, (hipStream_t)stream));
+}
+
+int gecc_report_to_host(gecc_ctx* ctx, const gecc_report* dev_report, gecc_report* host_report,
+                        int32_t count, void* stream) {
+  if (!ctx || !dev_report || !host_report || count < 1) return GECC_ERR_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  hipError_t e = hipMemcpyAsync(host_report, dev_report, sizeof(gecc_report) * (size_t)count,
+                                hipMemcpyDeviceToHost, st);
+  if (e != hipSuccess) return GECC_ERR_HIP;
+  return hip_rc(hipStreamSynchronize(st));
+}
+
+int gecc_syndromes_to_host(gecc_ctx* ctx, double* host_syndromes, void* stream) {
+  int rc = check_ws(ctx);
+  if (rc) return rc;
+  if (!host_syndromes) return GECC_ERR_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  const size_t bytes = (size_t)ctx->p.batch * (2 * (size_t)ctx->p.n + 2 * (size_t)ctx->p.m) * sizeof(double);
+  hipError_t e = hipMemcpyAsync(host_syndromes, ctx->ws + ctx->lay.synd, bytes, hipMemcpyDeviceToHost, st);
+  if (e != hipSuccess) return GECC_ERR_HIP;
+  return hip_rc(hipStreamSynchronize(st));
+}
+
+const char* gecc_strerror(int code) {
+  switch (code) {
+    case GECC_OK: return "ok";
+    case GECC_ERR_ARG: return "invalid argument (null pointer, size, enum or leading dimension)";
+    case GECC_ERR_WORKSPACE: return "workspace missing or too small";
+    case GECC_ERR_HIP: return "HIP runtime error";
+    case GECC_ERR_ALIGN: return "pointer or leading dimension breaks the alignment rule";
+    default: return "unknown error code";
+  }
+}
+
+}  // extern "C"

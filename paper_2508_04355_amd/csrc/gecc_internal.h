@@ -1,0 +1,147 @@
+// Internal declarations shared by the translation units of libgecc (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "gecc.h"
+
+namespace gecc {
+
+// ----------------------------------------------------------------------------------------
+// The product kernel and the stand-alone syndrome kernel both reduce C in tile_m x tile_n
+// tiles (the product kernel's own blocking, fixed when the context is created).
+
+// rows per chunk of the two-stage column reduction (scan kernels)
+constexpr int SCAN_CHUNK_ROWS = 256;
+
+// decoder phases kept in device memory (per batch item)
+enum : int { PH_DONE = 0, PH_AUDIT = 1, PH_REVERIFY = 2 };
+
+struct AuditHit {
+  int32_t line;   // l: column of A / row of B the hit is in
+  int32_t pos;    // located row of A / column of B (0-based); -1 = not explainable
+  double e;       // magnitude (plain parity difference)
+};
+
+struct DecodeState {
+  // filled by the threshold kernel (atomics; cleared by reset_state before each verify)
+  int32_t s_cnt, t_cnt;
+  int32_t rows[GECC_MAX_ERR], cols[GECC_MAX_ERR];
+  unsigned long long maxbits[4];
+  // decoder
+  int32_t phase;
+  int32_t a_cnt, b_cnt;       // audit hits (atomics)
+  int32_t n_err;              // operand errors already accepted by the audit
+  AuditHit a_hits[GECC_MAX_ERR], b_hits[GECC_MAX_ERR];
+  gecc_err errs[GECC_MAX_ERR];
+};
+
+struct Layout {            // byte offsets into the caller's workspace
+  size_t rowpart;          // float  [batch][ntn][n][2]   per-tile row sums (plain, local-weighted)
+  size_t colpart;          // float  [batch][ntm][m][2]   per-tile column sums
+  size_t synd;             // double [batch][2n + 2m]     r1, r2, q1, q2
+  size_t state;            // DecodeState [batch]
+  size_t audit_a;          // double [batch][2][k]        re-formed parity of A
+  size_t audit_b;          // double [batch][2][k]        re-formed parity of B
+  size_t scan_a;           // double scratch of the two-stage column reduction (A side)
+  size_t scan_b;           // same, B side
+  size_t total;
+};
+
+}  // namespace gecc
+
+struct gecc_ctx {
+  gecc_params p;
+  gecc::Layout lay;
+  int tile_m, tile_n;      // blocking of the product kernel = granularity of the partials
+  int ntm, ntn;            // partial tiles along n and m
+  char* ws;                // device workspace (caller's)
+  size_t ws_bytes;
+};
+
+namespace gecc {
+
+// ---- scan kernels (scan_kernels.hip) -----------------------------------------------------
+// X is a row-major R x Cc matrix (leading dimension ld, batch stride xs) of dtype.
+// rowdot: out[b][t][r] = sum_c w_t[c] X[r,c];  coldot: out[b][t][c] = sum_r w_t[r] X[r,c].
+// w == nullptr selects the index weights of Section III: w_0 = 1, w_1 = index + 1.
+// Otherwise w points at batch x [2][len] doubles.  gate (may be null): int per batch item at
+// byte stride gate_stride; the kernels return at once for items whose gate != gate_value.
+struct ScanArgs {
+  const void* X;
+  int dtype;
+  int R, Cc;
+  int64_t ld, xs;
+  int batch;
+  const double* w;      // [2][len] per batch item (batch stride w_stride doubles), or null
+  double* out;          // [2][len_out] per batch item (batch stride out_stride doubles)
+  int64_t w_stride, out_stride;
+  int vec_ok;           // set by the launcher: rows are 16-byte aligned, vector loads allowed
+  double* scratch;      // coldot only: [batch][nchunk][2][Cc]
+  const int32_t* gate;
+  int64_t gate_stride;  // in bytes
+  int gate_value;
+};
+hipError_t launch_rowdot(const ScanArgs& a, hipStream_t st);
+hipError_t launch_coldot(const ScanArgs& a, hipStream_t st);
+size_t coldot_scratch_doubles(int R, int Cc, int batch);
+
+// ---- product (gemm_kernels.hip) ------------------------------------------------------------
+struct GemmArgs {
+  const void* A;
+  const void* B;
+  float* C;
+  int dtype, trans_a, trans_b;
+  int n, k, m, batch;
+  int64_t lda, ldb, ldc, sa, sb, sc;
+  float* rowpart;       // null = no syndrome epilogue (plain product)
+  float* colpart;
+  int tile_m, tile_n, ntm, ntn;
+  const gecc_fault* faults;
+  int n_faults;
+};
+hipError_t launch_gemm(const GemmArgs& a, hipStream_t st);
+
+// stand-alone syndrome partials from a C in HBM (same workspace layout as the fused epilogue)
+struct PartialArgs {
+  const float* C;
+  int n, m, batch;
+  int64_t ldc, sc;
+  float* rowpart;
+  float* colpart;
+  int tile_m, tile_n, ntm, ntn;
+  const int32_t* gate;
+  int64_t gate_stride;
+  int gate_value;
+};
+hipError_t launch_partials(const PartialArgs& a, hipStream_t st);
+
+// ---- decoder (decode_kernels.hip) ----------------------------------------------------------
+struct DecodeArgs {
+  gecc_params p;
+  int tile_m, tile_n, ntm, ntn;
+  void* A;
+  void* B;
+  float* C;
+  const double* A_par;
+  const double* B_par;
+  double* C_par;
+  const float* rowpart;
+  const float* colpart;
+  double* synd;
+  DecodeState* state;
+  const double* audit_a;
+  const double* audit_b;
+  gecc_report* report;
+};
+hipError_t launch_reset_state(const DecodeArgs& a, hipStream_t st);
+// partial sums -> syndromes -> threshold flags.  first = 1: also fills max_abs_synd and the
+// report's s, t, status (CLEAN / DETECTED); first = 0: residual pass of the decoder, gated
+// on phase == PH_REVERIFY.
+hipError_t launch_threshold(const DecodeArgs& a, int first, hipStream_t st);
+hipError_t launch_decode_c(const DecodeArgs& a, int final_pass, hipStream_t st);
+hipError_t launch_audit_diff(const DecodeArgs& a, hipStream_t st);
+hipError_t launch_repair(const DecodeArgs& a, hipStream_t st);
+hipError_t launch_pg(const double* A_par, const double* B_par, double* C_par, int n, int k, int m,
+                     int batch, hipStream_t st);
+
+}  // namespace gecc

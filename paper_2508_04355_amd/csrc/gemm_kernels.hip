@@ -1,0 +1,343 @@
+// The data block of the encoded product (Section III, C = A B) on the MFMA units, with the
+// row/column sums that Section V's syndromes need taken from the accumulators before C
+// leaves the compute unit, so that verification never re-reads C from HBM.
+//
+// Per workgroup: a BM x BN tile of C.  Operand tiles are staged through LDS in a
+// k-contiguous layout (whatever the storage order of the operand is), MFMA fragments are read
+// from there.  After the k loop the tile passes through LDS once more in slabs of rows:
+// planted faults are applied, per-tile row sums (plain and weighted by the local column
+// index + 1) and column sums (plain and weighted by the local row index + 1) are formed, and
+// C is written with full-width stores.
+#include "gecc_internal.h"
+
+namespace gecc {
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+
+constexpr int THREADS = 256;
+constexpr int CPAD = 4;   // padding of the C slab rows (floats)
+
+template <int DT> struct GT;
+template <> struct GT<GECC_BF16> {
+  using T = uint16_t;
+  static constexpr int VEC = 8;    // elements per 16-byte load
+  static constexpr int BK = 32;
+  static constexpr int KPAD = 8;   // LDS row padding (elements)
+};
+template <> struct GT<GECC_F32> {
+  using T = float;
+  static constexpr int VEC = 4;
+  static constexpr int BK = 16;
+  static constexpr int KPAD = 1;
+};
+
+// ---- staging of one operand tile: ROWS (m- or n-index) x BK, into registers then LDS -------
+// KCONTIG: element (r, kk) lives at P[r * ld + kk]; otherwise at P[kk * ld + r].
+template <int DT, int ROWS, bool KCONTIG>
+struct Stager {
+  using G = GT<DT>;
+  using T = typename G::T;
+  static constexpr int VEC = G::VEC;
+  static constexpr int BK = G::BK;
+  static constexpr int LDK = BK + G::KPAD;
+  static constexpr int CHUNKS = ROWS * BK / VEC;
+  static constexpr int PER_THREAD = CHUNKS / THREADS;
+  static_assert(CHUNKS % THREADS == 0, "tile must split evenly over the workgroup");
+  T reg[PER_THREAD][VEC];
+
+  __device__ __forceinline__ void load(const T* P, int64_t ld, int r0, int k0, int rlim, int klim,
+                                       bool vec_ok) {
+#pragma unroll
+    for (int i = 0; i < PER_THREAD; ++i) {
+      const int c = threadIdx.x + THREADS * i;
+      int r, kk;
+      if (KCONTIG) { r = c / (BK / VEC); kk = (c % (BK / VEC)) * VEC; }
+      else         { kk = c / (ROWS / VEC); r = (c % (ROWS / VEC)) * VEC; }
+      const int gr = r0 + r, gk = k0 + kk;
+      const T* src = KCONTIG ? P + (int64_t)gr * ld + gk : P + (int64_t)gk * ld + gr;
+      const bool full = KCONTIG ? (gr < rlim && gk + VEC <= klim) : (gk < klim && gr + VEC <= rlim);
+      if (full && vec_ok) {
+        *reinterpret_cast<uint4*>(reg[i]) = *reinterpret_cast<const uint4*>(src);
+      } else {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+          const bool in = KCONTIG ? (gr < rlim && gk + e < klim) : (gk < klim && gr + e < rlim);
+          reg[i][e] = in ? src[e] : (T)0;
+        }
+      }
+    }
+  }
+
+  __device__ __forceinline__ void store(T (*S)[LDK]) const {
+#pragma unroll
+    for (int i = 0; i < PER_THREAD; ++i) {
+      const int c = threadIdx.x + THREADS * i;
+      if (KCONTIG) {
+        const int r = c / (BK / VEC), kk = (c % (BK / VEC)) * VEC;
+        if (DT == GECC_BF16) {
+          *reinterpret_cast<uint4*>(&S[r][kk]) = *reinterpret_cast<const uint4*>(reg[i]);
+        } else {
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) S[r][kk + e] = reg[i][e];
+        }
+      } else {
+        const int kk = c / (ROWS / VEC), r = (c % (ROWS / VEC)) * VEC;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) S[r + e][kk] = reg[i][e];
+      }
+    }
+  }
+};
+
+// ---- one row slab of the C tile, resident in LDS: faults, partial sums, store ---------------
+// Cs holds SLAB rows x BN columns; rows slab_r0.. of the tile.  cs/cw accumulate the column
+// sums of the thread's column (threads < BN) over the slabs.
+template <int BN, int SLAB>
+__device__ __forceinline__ void slab_reduce(float (*Cs)[BN + CPAD], int slab_r0, int tile_r0,
+                                            int tile_c0, int n, int m, float* rowpart_tile,
+                                            float& cs, float& cw) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // row sums: one wavefront per row, lanes stride the columns
+  if (rowpart_tile) {
+    for (int r = wave; r < SLAB; r += THREADS / 64) {
+      float s = 0.f, w = 0.f;
+#pragma unroll
+      for (int c = lane; c < BN; c += 64) {
+        const float v = Cs[r][c];
+        s += v;
+        w = fmaf((float)(c + 1), v, w);
+      }
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) {
+        s += __shfl_down(s, off, 64);
+        w += __shfl_down(w, off, 64);
+      }
+      const int gi = tile_r0 + slab_r0 + r;
+      if (lane == 0 && gi < n) {
+        rowpart_tile[(int64_t)gi * 2] = s;
+        rowpart_tile[(int64_t)gi * 2 + 1] = w;
+      }
+    }
+    if (tid < BN) {
+#pragma unroll 8
+      for (int r = 0; r < SLAB; ++r) {
+        const float v = Cs[r][tid];
+        cs += v;
+        cw = fmaf((float)(slab_r0 + r + 1), v, cw);
+      }
+    }
+  }
+}
+
+template <int BN, int SLAB>
+__device__ __forceinline__ void slab_store(float (*Cs)[BN + CPAD], int slab_r0, int tile_r0,
+                                           int tile_c0, int n, int m, float* C, int64_t ldc,
+                                           bool vec_ok) {
+  constexpr int V4 = BN / 4;
+  for (int o = threadIdx.x; o < SLAB * V4; o += THREADS) {
+    const int r = o / V4, c = (o % V4) * 4;
+    const int gi = tile_r0 + slab_r0 + r, gj = tile_c0 + c;
+    if (gi >= n || gj >= m) continue;
+    float* dst = C + (int64_t)gi * ldc + gj;
+    if (vec_ok && gj + 4 <= m) {
+      *reinterpret_cast<float4*>(dst) = *reinterpret_cast<const float4*>(&Cs[r][c]);
+    } else {
+      for (int e = 0; e < 4 && gj + e < m; ++e) dst[e] = Cs[r][c + e];
+    }
+  }
+}
+
+__device__ __forceinline__ void apply_faults(const gecc_fault* faults, int n_faults, int b,
+                                             int r_lo, int r_hi, int c_lo, int c_hi, float* Cs,
+                                             int ldcs) {
+  if (n_faults > 0 && threadIdx.x == 0) {
+    for (int f = 0; f < n_faults; ++f) {
+      const gecc_fault ft = faults[f];
+      if (ft.batch == b && ft.row >= r_lo && ft.row < r_hi && ft.col >= c_lo && ft.col < c_hi)
+        Cs[(ft.row - r_lo) * ldcs + (ft.col - c_lo)] += ft.offset;
+    }
+  }
+}
+
+// -------------------------------------------------------------------------------------------
+template <int DT, bool KCA, bool KCB>
+__global__ __launch_bounds__(THREADS) void gemm_kernel(GemmArgs a) {
+  using G = GT<DT>;
+  using T = typename G::T;
+  constexpr int BM = 128, BN = 128, BK = G::BK, LDK = BK + G::KPAD, SLAB = 64;
+  const int b = blockIdx.z;
+  const int tm = blockIdx.y, tn = blockIdx.x;
+  const int tile_r0 = tm * BM, tile_c0 = tn * BN;
+  const T* A = reinterpret_cast<const T*>(a.A) + (int64_t)b * a.sa;
+  const T* B = reinterpret_cast<const T*>(a.B) + (int64_t)b * a.sb;
+  float* C = a.C + (int64_t)b * a.sc;
+
+  constexpr int AB_BYTES = (BM + BN) * LDK * (int)sizeof(T);
+  constexpr int CS_BYTES = SLAB * (BN + CPAD) * (int)sizeof(float);
+  __shared__ __attribute__((aligned(16))) char smem[AB_BYTES > CS_BYTES ? AB_BYTES : CS_BYTES];
+  T (*As)[LDK] = reinterpret_cast<T (*)[LDK]>(smem);
+  T (*Bs)[LDK] = reinterpret_cast<T (*)[LDK]>(smem + BM * LDK * sizeof(T));
+  float (*Cs)[BN + CPAD] = reinterpret_cast<float (*)[BN + CPAD]>(smem);
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wr = wave >> 1, wc = wave & 1;          // 2 x 2 wavefronts, 64 x 64 each
+  const int l32 = lane & 31, lhi = lane >> 5;
+
+  const bool vecA = (reinterpret_cast<uintptr_t>(A) % 16 == 0) && (a.lda % G::VEC == 0);
+  const bool vecB = (reinterpret_cast<uintptr_t>(B) % 16 == 0) && (a.ldb % G::VEC == 0);
+
+  f32x16_t acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  Stager<DT, BM, KCA> sa;
+  Stager<DT, BN, KCB> sb;
+  sa.load(A, a.lda, tile_r0, 0, a.n, a.k, vecA);
+  sb.load(B, a.ldb, tile_c0, 0, a.m, a.k, vecB);
+
+  for (int k0 = 0; k0 < a.k; k0 += BK) {
+    __syncthreads();               // previous tile fully consumed
+    sa.store(As);
+    sb.store(Bs);
+    __syncthreads();
+    if (k0 + BK < a.k) {           // prefetch the next tile into registers
+      sa.load(A, a.lda, tile_r0, k0 + BK, a.n, a.k, vecA);
+      sb.load(B, a.ldb, tile_c0, k0 + BK, a.m, a.k, vecB);
+    }
+    if (DT == GECC_BF16) {
+#pragma unroll
+      for (int ks = 0; ks < BK; ks += 16) {
+        bf16x8_t fa[2], fb[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+          fa[i] = *reinterpret_cast<const bf16x8_t*>(&As[wr * 64 + i * 32 + l32][ks + lhi * 8]);
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          fb[j] = *reinterpret_cast<const bf16x8_t*>(&Bs[wc * 64 + j * 32 + l32][ks + lhi * 8]);
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+      }
+    } else {
+#pragma unroll
+      for (int ks = 0; ks < BK; ks += 2) {
+        float fa[2], fb[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+          fa[i] = *reinterpret_cast<const float*>(&As[wr * 64 + i * 32 + l32][ks + lhi]);
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          fb[j] = *reinterpret_cast<const float*>(&Bs[wc * 64 + j * 32 + l32][ks + lhi]);
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i], fb[j], acc[i][j], 0, 0, 0);
+      }
+    }
+  }
+
+  // ---- epilogue: the tile goes through LDS in two slabs of 64 rows -------------------------
+  const bool epi = a.rowpart != nullptr;
+  float* rowpart_tile = epi ? a.rowpart + ((int64_t)b * a.ntn + tn) * a.n * 2 : nullptr;
+  const bool vecC = (reinterpret_cast<uintptr_t>(C) % 16 == 0) && (a.ldc % 4 == 0);
+  float cs = 0.f, cw = 0.f;
+#pragma unroll
+  for (int slab = 0; slab < BM / SLAB; ++slab) {
+    __syncthreads();
+    if (wr == slab) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int r = i * 32 + (v >> 2) * 8 + lhi * 4 + (v & 3);
+            Cs[r][wc * 64 + j * 32 + l32] = acc[i][j][v];
+          }
+    }
+    __syncthreads();
+    const int r_lo = tile_r0 + slab * SLAB;
+    apply_faults(a.faults, a.n_faults, b, r_lo, min(r_lo + SLAB, a.n), tile_c0,
+                 min(tile_c0 + BN, a.m), &Cs[0][0], BN + CPAD);
+    if (a.n_faults > 0) __syncthreads();
+    slab_reduce<BN, SLAB>(Cs, slab * SLAB, tile_r0, tile_c0, a.n, a.m, rowpart_tile, cs, cw);
+    slab_store<BN, SLAB>(Cs, slab * SLAB, tile_r0, tile_c0, a.n, a.m, C, a.ldc, vecC);
+  }
+  if (epi && tid < BN && tile_c0 + tid < a.m) {
+    float* cp = a.colpart + (((int64_t)b * a.ntm + tm) * a.m + tile_c0 + tid) * 2;
+    cp[0] = cs;
+    cp[1] = cw;
+  }
+}
+
+// -------------------------------------------------------------------------------------------
+// Stand-alone partial sums of a C that sits in HBM (same tiling and workspace layout).
+template <int BM, int BN>
+__global__ __launch_bounds__(THREADS) void partials_kernel(PartialArgs a) {
+  constexpr int SLAB = 64;
+  const int b = blockIdx.z;
+  if (a.gate) {
+    const int32_t g = *reinterpret_cast<const int32_t*>(reinterpret_cast<const char*>(a.gate) +
+                                                        a.gate_stride * b);
+    if (g != a.gate_value) return;
+  }
+  const int tm = blockIdx.y, tn = blockIdx.x;
+  const int tile_r0 = tm * BM, tile_c0 = tn * BN;
+  const float* C = a.C + (int64_t)b * a.sc;
+  __shared__ __attribute__((aligned(16))) float Cs[SLAB][BN + CPAD];
+  float* rowpart_tile = a.rowpart + ((int64_t)b * a.ntn + tn) * a.n * 2;
+  const int tid = threadIdx.x;
+  float cs = 0.f, cw = 0.f;
+  for (int slab = 0; slab < BM / SLAB; ++slab) {
+    __syncthreads();
+    for (int o = tid; o < SLAB * BN; o += THREADS) {
+      const int r = o / BN, c = o % BN;
+      const int gi = tile_r0 + slab * SLAB + r, gj = tile_c0 + c;
+      Cs[r][c] = (gi < a.n && gj < a.m) ? C[(int64_t)gi * a.ldc + gj] : 0.f;
+    }
+    __syncthreads();
+    slab_reduce<BN, SLAB>(Cs, slab * SLAB, tile_r0, tile_c0, a.n, a.m, rowpart_tile, cs, cw);
+  }
+  if (tid < BN && tile_c0 + tid < a.m) {
+    float* cp = a.colpart + (((int64_t)b * a.ntm + tm) * a.m + tile_c0 + tid) * 2;
+    cp[0] = cs;
+    cp[1] = cw;
+  }
+}
+
+template <int DT>
+hipError_t launch_dt(const GemmArgs& a, hipStream_t st) {
+  dim3 grid((a.m + 127) / 128, (a.n + 127) / 128, a.batch);
+  // k-contiguous storage: A when not transposed, B when transposed
+  const bool kca = a.trans_a == 0, kcb = a.trans_b != 0;
+  if (kca && kcb)        hipLaunchKernelGGL((gemm_kernel<DT, true, true>), grid, dim3(THREADS), 0, st, a);
+  else if (kca && !kcb)  hipLaunchKernelGGL((gemm_kernel<DT, true, false>), grid, dim3(THREADS), 0, st, a);
+  else if (!kca && kcb)  hipLaunchKernelGGL((gemm_kernel<DT, false, true>), grid, dim3(THREADS), 0, st, a);
+  else                   hipLaunchKernelGGL((gemm_kernel<DT, false, false>), grid, dim3(THREADS), 0, st, a);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_gemm(const GemmArgs& a, hipStream_t st) {
+  if (a.tile_m != 128 || a.tile_n != 128) return hipErrorInvalidValue;
+  return a.dtype == GECC_BF16 ? launch_dt<GECC_BF16>(a, st) : launch_dt<GECC_F32>(a, st);
+}
+
+hipError_t launch_partials(const PartialArgs& a, hipStream_t st) {
+  if (a.tile_m != 128 || a.tile_n != 128) return hipErrorInvalidValue;
+  dim3 grid(a.ntn, a.ntm, a.batch);
+  hipLaunchKernelGGL((partials_kernel<128, 128>), grid, dim3(THREADS), 0, st, a);
+  return hipGetLastError();
+}
+
+}  // namespace gecc

@@ -1,0 +1,271 @@
+// HBM-bound weighted reductions over an operand: parity encoding (Section III, A_P and B_P),
+// the parity blocks of the encoded product (P_r = A B_P, P_c = A_P B) and the operand audit.
+//
+// Both kernels read the operand once with 16-byte loads that are contiguous across a
+// wavefront, accumulate in fp64 and reduce in a fixed order (no floating-point atomics), so
+// that re-forming a parity from an unchanged operand reproduces it bit for bit.
+#include "gecc_internal.h"
+
+namespace gecc {
+namespace {
+
+template <int DT> struct Elem;
+template <> struct Elem<GECC_F32> {
+  using type = float;
+  static constexpr int VEC = 4;
+  static __device__ __forceinline__ void load_vec(const float* p, double* v) {
+    float4 x = *reinterpret_cast<const float4*>(p);
+    v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
+  }
+  static __device__ __forceinline__ double load_one(const float* p) { return (double)*p; }
+};
+template <> struct Elem<GECC_BF16> {
+  using type = uint16_t;
+  static constexpr int VEC = 8;
+  static __device__ __forceinline__ void load_vec(const uint16_t* p, double* v) {
+    uint4 x = *reinterpret_cast<const uint4*>(p);
+    uint32_t w[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      v[2 * i] = (double)__uint_as_float(w[i] << 16);
+      v[2 * i + 1] = (double)__uint_as_float(w[i] & 0xffff0000u);
+    }
+  }
+  static __device__ __forceinline__ double load_one(const uint16_t* p) {
+    return (double)__uint_as_float(((uint32_t)*p) << 16);
+  }
+};
+
+__device__ __forceinline__ bool gated_off(const int32_t* gate, int64_t stride, int b, int value) {
+  if (!gate) return false;
+  const int32_t g = *reinterpret_cast<const int32_t*>(reinterpret_cast<const char*>(gate) + stride * b);
+  return g != value;
+}
+
+// -------------------------------------------------------------------------------------------
+// rowdot: out[t][r] = sum_c w_t[c] X[r,c].   One workgroup owns RB rows and walks all columns;
+// a thread keeps the weights of its VEC columns in registers and reuses them for the RB rows.
+constexpr int RD_THREADS = 256;
+constexpr int RD_RB = 16;
+
+template <int DT, bool IDXW>
+__global__ __launch_bounds__(RD_THREADS) void rowdot_kernel(ScanArgs a) {
+  using E = Elem<DT>;
+  using T = typename E::type;
+  constexpr int VEC = E::VEC;
+  const int b = blockIdx.y;
+  if (gated_off(a.gate, a.gate_stride, b, a.gate_value)) return;
+  const T* X = reinterpret_cast<const T*>(a.X) + (int64_t)b * a.xs;
+  const double* w0 = IDXW ? nullptr : a.w + (int64_t)b * a.w_stride;
+  const double* w1 = IDXW ? nullptr : w0 + a.Cc;
+  double* out = a.out + (int64_t)b * a.out_stride;
+  const int r0 = blockIdx.x * RD_RB;
+  const int tid = threadIdx.x;
+
+  double acc0[RD_RB], acc1[RD_RB];
+#pragma unroll
+  for (int r = 0; r < RD_RB; ++r) { acc0[r] = 0.0; acc1[r] = 0.0; }
+
+  for (int c0 = 0; c0 < a.Cc; c0 += RD_THREADS * VEC) {
+    const int c = c0 + tid * VEC;
+    if (c >= a.Cc) continue;
+    const int nv = min(VEC, a.Cc - c);
+    double wa[VEC], wb[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+      if (IDXW) { wa[e] = 1.0; wb[e] = (double)(c + e + 1); }
+      else      { wa[e] = e < nv ? w0[c + e] : 0.0; wb[e] = e < nv ? w1[c + e] : 0.0; }
+    }
+    if (nv == VEC && a.vec_ok) {
+#pragma unroll
+      for (int r = 0; r < RD_RB; ++r) {
+        const int row = r0 + r;
+        if (row < a.R) {
+          double v[VEC];
+          E::load_vec(X + (int64_t)row * a.ld + c, v);
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) {
+            acc0[r] = IDXW ? acc0[r] + v[e] : fma(wa[e], v[e], acc0[r]);
+            acc1[r] = fma(wb[e], v[e], acc1[r]);
+          }
+        }
+      }
+    } else {
+      for (int r = 0; r < RD_RB; ++r) {
+        const int row = r0 + r;
+        if (row < a.R)
+          for (int e = 0; e < nv; ++e) {
+            const double v = E::load_one(X + (int64_t)row * a.ld + c + e);
+            acc0[r] = fma(wa[e], v, acc0[r]);
+            acc1[r] = fma(wb[e], v, acc1[r]);
+          }
+      }
+    }
+  }
+
+  // fixed-order reduction over the 256 threads, one parity kind (t) at a time
+  __shared__ double red[RD_RB][RD_THREADS];
+  const int wave = tid >> 6, lane = tid & 63;
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+    if (t) __syncthreads();
+#pragma unroll
+    for (int r = 0; r < RD_RB; ++r) red[r][tid] = t ? acc1[r] : acc0[r];
+    __syncthreads();
+    for (int q = wave; q < RD_RB; q += RD_THREADS / 64) {
+      double s = (red[q][lane] + red[q][lane + 64]) + (red[q][lane + 128] + red[q][lane + 192]);
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) s += __shfl_down(s, off, 64);
+      const int row = r0 + q;
+      if (lane == 0 && row < a.R) out[(int64_t)t * a.R + row] = s;
+    }
+  }
+}
+
+// -------------------------------------------------------------------------------------------
+// coldot: out[t][c] = sum_r w_t[r] X[r,c].   Stage 1: a workgroup owns 64*VEC columns and one
+// chunk of SCAN_CHUNK_ROWS rows; its 4 wavefronts interleave the rows and are combined through
+// LDS.  Stage 2 adds the chunks in order.
+constexpr int CD_THREADS = 256;
+
+template <int DT, bool IDXW>
+__global__ __launch_bounds__(CD_THREADS) void coldot_stage1(ScanArgs a, int nchunk) {
+  using E = Elem<DT>;
+  using T = typename E::type;
+  constexpr int VEC = E::VEC;
+  const int b = blockIdx.z;
+  if (gated_off(a.gate, a.gate_stride, b, a.gate_value)) return;
+  const T* X = reinterpret_cast<const T*>(a.X) + (int64_t)b * a.xs;
+  const double* w0 = IDXW ? nullptr : a.w + (int64_t)b * a.w_stride;
+  const double* w1 = IDXW ? nullptr : w0 + a.R;
+  const int chunk = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int c = (blockIdx.x * 64 + lane) * VEC;
+  const int rbeg = chunk * SCAN_CHUNK_ROWS;
+  const int rend = min(a.R, rbeg + SCAN_CHUNK_ROWS);
+  const int nv = min(VEC, a.Cc - c);   // <= 0: this lane owns no column
+
+  double acc0[VEC], acc1[VEC];
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) { acc0[e] = 0.0; acc1[e] = 0.0; }
+
+  if (nv == VEC && a.vec_ok) {
+    int r = rbeg + wave;
+    for (; r + 12 < rend; r += 16) {   // 4 rows in flight per wavefront
+      double v[4][VEC];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) E::load_vec(X + (int64_t)(r + 4 * u) * a.ld + c, v[u]);
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int rr = r + 4 * u;
+        const double wa = IDXW ? 1.0 : w0[rr];
+        const double wb = IDXW ? (double)(rr + 1) : w1[rr];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+          acc0[e] = IDXW ? acc0[e] + v[u][e] : fma(wa, v[u][e], acc0[e]);
+          acc1[e] = fma(wb, v[u][e], acc1[e]);
+        }
+      }
+    }
+    for (; r < rend; r += 4) {
+      double v[VEC];
+      E::load_vec(X + (int64_t)r * a.ld + c, v);
+      const double wa = IDXW ? 1.0 : w0[r];
+      const double wb = IDXW ? (double)(r + 1) : w1[r];
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) {
+        acc0[e] = IDXW ? acc0[e] + v[e] : fma(wa, v[e], acc0[e]);
+        acc1[e] = fma(wb, v[e], acc1[e]);
+      }
+    }
+  } else if (nv > 0) {
+    for (int r = rbeg + wave; r < rend; r += 4) {
+      const double wa = IDXW ? 1.0 : w0[r];
+      const double wb = IDXW ? (double)(r + 1) : w1[r];
+      for (int e = 0; e < nv; ++e) {
+        const double v = E::load_one(X + (int64_t)r * a.ld + c + e);
+        acc0[e] = fma(wa, v, acc0[e]);
+        acc1[e] = fma(wb, v, acc1[e]);
+      }
+    }
+  }
+
+  __shared__ double red[4][2][VEC][64];
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) { red[wave][0][e][lane] = acc0[e]; red[wave][1][e][lane] = acc1[e]; }
+  __syncthreads();
+  // thread -> (t, e, lane'): 2*VEC*64 outputs, 256 threads
+  double* part = a.scratch + ((int64_t)b * nchunk + chunk) * 2 * a.Cc;
+  for (int o = tid; o < 2 * VEC * 64; o += CD_THREADS) {
+    const int l = o & 63, e = (o >> 6) % VEC, t = o / (64 * VEC);
+    const int col = (blockIdx.x * 64 + l) * VEC + e;
+    if (col < a.Cc) {
+      const double s = (red[0][t][e][l] + red[1][t][e][l]) + (red[2][t][e][l] + red[3][t][e][l]);
+      part[(int64_t)t * a.Cc + col] = s;
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void coldot_stage2(ScanArgs a, int nchunk) {
+  const int b = blockIdx.y;
+  if (gated_off(a.gate, a.gate_stride, b, a.gate_value)) return;
+  const int o = blockIdx.x * 256 + threadIdx.x;   // index into [2][Cc]
+  if (o >= 2 * a.Cc) return;
+  const double* part = a.scratch + (int64_t)b * nchunk * 2 * a.Cc + o;
+  double s = 0.0;
+  for (int ch = 0; ch < nchunk; ++ch) s += part[(int64_t)ch * 2 * a.Cc];
+  a.out[(int64_t)b * a.out_stride + o] = s;
+}
+
+// vector loads need 16-byte aligned rows
+bool vec_ok(const ScanArgs& a) {
+  const int vec = a.dtype == GECC_BF16 ? 8 : 4;
+  const size_t esz = a.dtype == GECC_BF16 ? 2 : 4;
+  return (reinterpret_cast<uintptr_t>(a.X) % 16 == 0) && (a.ld % vec == 0) && ((a.xs * esz) % 16 == 0);
+}
+
+}  // namespace
+
+size_t coldot_scratch_doubles(int R, int Cc, int batch) {
+  const size_t nchunk = (R + SCAN_CHUNK_ROWS - 1) / SCAN_CHUNK_ROWS;
+  return (size_t)batch * nchunk * 2 * (size_t)Cc;
+}
+
+hipError_t launch_rowdot(const ScanArgs& a0, hipStream_t st) {
+  ScanArgs a = a0;
+  a.vec_ok = vec_ok(a0) ? 1 : 0;
+  dim3 grid((a.R + RD_RB - 1) / RD_RB, a.batch);
+  const bool idx = a.w == nullptr;
+  if (a.dtype == GECC_BF16) {
+    if (idx) hipLaunchKernelGGL((rowdot_kernel<GECC_BF16, true>), grid, dim3(RD_THREADS), 0, st, a);
+    else     hipLaunchKernelGGL((rowdot_kernel<GECC_BF16, false>), grid, dim3(RD_THREADS), 0, st, a);
+  } else {
+    if (idx) hipLaunchKernelGGL((rowdot_kernel<GECC_F32, true>), grid, dim3(RD_THREADS), 0, st, a);
+    else     hipLaunchKernelGGL((rowdot_kernel<GECC_F32, false>), grid, dim3(RD_THREADS), 0, st, a);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_coldot(const ScanArgs& a0, hipStream_t st) {
+  ScanArgs a = a0;
+  a.vec_ok = vec_ok(a0) ? 1 : 0;
+  const int vec = a.dtype == GECC_BF16 ? 8 : 4;
+  const int nchunk = (a.R + SCAN_CHUNK_ROWS - 1) / SCAN_CHUNK_ROWS;
+  dim3 grid((a.Cc + 64 * vec - 1) / (64 * vec), nchunk, a.batch);
+  const bool idx = a.w == nullptr;
+  if (a.dtype == GECC_BF16) {
+    if (idx) hipLaunchKernelGGL((coldot_stage1<GECC_BF16, true>), grid, dim3(CD_THREADS), 0, st, a, nchunk);
+    else     hipLaunchKernelGGL((coldot_stage1<GECC_BF16, false>), grid, dim3(CD_THREADS), 0, st, a, nchunk);
+  } else {
+    if (idx) hipLaunchKernelGGL((coldot_stage1<GECC_F32, true>), grid, dim3(CD_THREADS), 0, st, a, nchunk);
+    else     hipLaunchKernelGGL((coldot_stage1<GECC_F32, false>), grid, dim3(CD_THREADS), 0, st, a, nchunk);
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  dim3 g2((2 * a.Cc + 255) / 256, a.batch);
+  hipLaunchKernelGGL(coldot_stage2, g2, dim3(256), 0, st, a, nchunk);
+  return hipGetLastError();
+}
+
+}  // namespace gecc
