@@ -77,6 +77,11 @@ typedef struct {
   /* detection thresholds, one per syndrome family (the delta of Section V):
      row plain, row weighted, column plain, column weighted; operand audit */
   double tau_r1, tau_r2, tau_q1, tau_q2, tau_op;
+  /* relative rounding allowance after an operand repair: a symbol of C whose running sum held
+     the corrupted term f = e * b_lj may be off by tau_rep * sqrt(k) * |f|; the thresholds of the
+     lines such a repair touched are widened accordingly in the second pass of Section V
+     (root-sum-square over a whole repaired line).  16 * 2^-24 suits fp32 accumulation. */
+  double tau_rep;
 } gecc_params;
 
 /* one located error: `magnitude` is the additive offset that was removed */
@@ -98,13 +103,13 @@ typedef struct {
 
 /* a fault to be planted into the product while it is computed (E3 of Section II-A):
    offset is added to data symbol (row, col) of batch item `batch` before the
-   syndromes are formed and before C is stored */
+   syndromes are formed and before C is stored.  Positions in one list must be distinct. */
 typedef struct {
   int32_t batch, row, col;
   float offset;
 } gecc_fault;
 
-#define GECC_MAX_FAULTS 16
+#define GECC_MAX_FAULTS 1024
 
 /* ---- context ------------------------------------------------------------------------ */
 
@@ -177,6 +182,14 @@ int gecc_report_to_host(gecc_ctx* ctx, const gecc_report* dev_report, gecc_repor
 /* Copies the syndromes of the last gecc_verify (r1[n], r2[n], q1[m], q2[m] per batch item,
    doubles) device -> host and waits; for threshold calibration. */
 int gecc_syndromes_to_host(gecc_ctx* ctx, double* host_syndromes, void* stream);
+
+/* Timing of the product kernel (the kernel of gecc_multiply / gecc_plain_gemm that holds all
+   the flops), for roofline reports.  gecc_timing_enable(ctx, r) with r > 0 makes the next r
+   product launches record a HIP event pair on their stream (host objects only, no device
+   memory); r = 0 disables and frees them.  gecc_timing_read waits for the recorded pairs,
+   writes their durations in milliseconds to host_ms[0..*count) (at most cap) and rearms. */
+int gecc_timing_enable(gecc_ctx* ctx, int32_t max_records);
+int gecc_timing_read(gecc_ctx* ctx, float* host_ms, int32_t cap, int32_t* count);
 
 const char* gecc_strerror(int code);
 

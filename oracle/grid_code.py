@@ -44,6 +44,12 @@ the design notes of the repository):
   * every estimate is verified: after the tentative correction all
     syndromes of the flagged rows/columns must fall inside the thresholds
     (propagated through the estimate), otherwise the pattern is handed on.
+  * after an operand repair the lines it touched carry extra rounding noise
+    in any finite-precision product (the corrupted term e * b_lj sat in the
+    running sum of every symbol of that row), so the second pass of Section V
+    widens the thresholds of those lines by rep * sqrt(k) * |footprint|
+    (root-sum-square over a whole repaired line).  With rep = 0 this is the
+    plain second pass.
   * for s = t = 2 the 2x2 systems are first evaluated under the two sparse
     hypotheses "one error per flagged column" (a column with a single error
     is the s = 1 rule applied to that column); in exact arithmetic this
@@ -74,6 +80,19 @@ class Thresholds:
     q1: float
     q2: float
     op: float = 0.0       # operand audit: |parity difference| > op flags a line
+    rep: float = 0.0      # relative rounding allowance for lines touched by an operand repair
+
+
+class LineThresholds:
+    """Per-line thresholds: the four numbers of `Thresholds` plus per-line allowances."""
+
+    def __init__(self, tau, n, m, allow=None):
+        z = np.zeros
+        a = allow if allow is not None else (z(n), z(n), z(m), z(m))
+        self.r1 = tau.r1 + a[0]
+        self.r2 = tau.r2 + a[1]
+        self.q1 = tau.q1 + a[2]
+        self.q2 = tau.q2 + a[3]
 
 
 @dataclass
@@ -165,7 +184,8 @@ def global_syndromes(Cbar):
 
 
 def detect(r1, r2, q1, q2, tau):
-    """E_r, E_t of Section V step 1 (a line is flagged if either test fails)."""
+    """E_r, E_t of Section V step 1 (a line is flagged if either test fails).
+    tau: Thresholds (one number per family) or LineThresholds (per-line arrays)."""
     Er = np.nonzero((np.abs(r1) > tau.r1) | (np.abs(r2) > tau.r2))[0]
     Et = np.nonzero((np.abs(q1) > tau.q1) | (np.abs(q2) > tau.q2))[0]
     return [int(i) for i in Er], [int(j) for j in Et]
@@ -181,18 +201,18 @@ def _residual_ok(est, r1, r2, q1, q2, Er, Et, tau):
         su = sum(u for (ii, j, x, u) in est if ii == i)
         wx = sum((j + 1) * x for (ii, j, x, u) in est if ii == i)
         wu = sum((j + 1) * u for (ii, j, x, u) in est if ii == i)
-        if abs(r1[i] - sx) > tau.r1 + su:
+        if abs(r1[i] - sx) > tau.r1[i] + su:
             return False
-        if abs(r2[i] - wx) > tau.r2 + wu:
+        if abs(r2[i] - wx) > tau.r2[i] + wu:
             return False
     for j in Et:
         sx = sum(x for (i, jj, x, u) in est if jj == j)
         su = sum(u for (i, jj, x, u) in est if jj == j)
         wx = sum((i + 1) * x for (i, jj, x, u) in est if jj == j)
         wu = sum((i + 1) * u for (i, jj, x, u) in est if jj == j)
-        if abs(q1[j] - sx) > tau.q1 + su:
+        if abs(q1[j] - sx) > tau.q1[j] + su:
             return False
-        if abs(q2[j] - wx) > tau.q2 + wu:
+        if abs(q2[j] - wx) > tau.q2[j] + wu:
             return False
     return True
 
@@ -207,8 +227,9 @@ def solve_2x2(w1, w2, y1, y2):
 def d0_correct(r1, r2, q1, q2, Er, Et, tau):
     """Section V step 2 for 1 <= s, t <= 2.
 
-    Returns the verified list [(i, j, x)] of C errors, or None when no
-    estimate explains the syndromes (the caller then tries the operand audit).
+    tau: LineThresholds.  Returns the verified list [(i, j, x)] of C errors,
+    or None when no estimate explains the syndromes (the caller then tries the
+    operand audit).
     """
     s, t = len(Er), len(Et)
     assert 1 <= s <= 2 and 1 <= t <= 2
@@ -222,11 +243,11 @@ def d0_correct(r1, r2, q1, q2, Er, Et, tau):
     if s <= t:
         if s == 1:
             # one faulty row: every flagged column has its error in that row
-            return accept([(Er[0], j, q1[j], tau.q1) for j in Et])
+            return accept([(Er[0], j, q1[j], tau.q1[j]) for j in Et])
         s1, s2 = Er
         t1, t2 = Et
-        diag = accept([(s1, t1, q1[t1], tau.q1), (s2, t2, q1[t2], tau.q1)])
-        anti = accept([(s1, t2, q1[t2], tau.q1), (s2, t1, q1[t1], tau.q1)])
+        diag = accept([(s1, t1, q1[t1], tau.q1[t1]), (s2, t2, q1[t2], tau.q1[t2])])
+        anti = accept([(s1, t2, q1[t2], tau.q1[t2]), (s2, t1, q1[t1], tau.q1[t1])])
         if diag is not None and anti is not None:
             return None                                  # cannot tell them apart
         if diag is not None:
@@ -237,12 +258,12 @@ def d0_correct(r1, r2, q1, q2, Er, Et, tau):
         est = []
         for j in Et:
             e1, e2 = solve_2x2(w1, w2, q1[j], q2[j])
-            u2 = (tau.q2 + w1 * tau.q1) / (w2 - w1)
-            u1 = tau.q1 + u2
+            u2 = (tau.q2[j] + w1 * tau.q1[j]) / (w2 - w1)
+            u1 = tau.q1[j] + u2
             est += [(s1, j, e1, u1), (s2, j, e2, u2)]
         return accept(est)
     # s = 2 > t = 1: mirror image, rows play the role of columns
-    return accept([(i, Et[0], r1[i], tau.r1) for i in Er])
+    return accept([(i, Et[0], r1[i], tau.r1[i]) for i in Er])
 
 
 # ------------------------------------------------------- completion D1: audit
@@ -314,7 +335,7 @@ def decode(Cbar, A, AP, B, BP, tau):
         return done(CLEAN, [])
 
     if 1 <= s0 <= 2 and 1 <= t0 <= 2:
-        fix = d0_correct(r1, r2, q1, q2, Er, Et, tau)
+        fix = d0_correct(r1, r2, q1, q2, Er, Et, LineThresholds(tau, n, m))
         if fix is not None:
             for (i, j, x) in fix:
                 Cbar[i, j] -= x
@@ -326,22 +347,37 @@ def decode(Cbar, A, AP, B, BP, tau):
     if not (okA and okB) or (len(LA) + len(LB) == 0) or (len(LA) + len(LB) > MAX_REPORTED):
         return done(UNCORRECTABLE, [])
     errs = []
+    k = A.shape[1]
+    c = tau.rep * np.sqrt(k)
+    allow = (np.zeros(n), np.zeros(n), np.zeros(m), np.zeros(m))
+    wn, wm = _w(n), _w(m)
     for (i, l, e) in LA:
         A[i, l] -= e
+        foot = e * B[l, :]                       # B as the product read it
         Cbar[i, :] -= e * np.concatenate([B[l, :], BP[l, :]])
         errs.append((MAT_A, i, l, e))
+        allow[0][i] += c * np.sqrt(np.sum(foot ** 2))
+        allow[1][i] += c * np.sqrt(np.sum((wm * foot) ** 2))
+        allow[2][:] += c * np.abs(foot)
+        allow[3][:] += c * (i + 1) * np.abs(foot)
     for (l, j, e) in LB:
         B[l, j] -= e
+        foot = A[:, l] * e                       # A already corrected
         Cbar[:, j] -= np.concatenate([A[:, l], AP[:, l]]) * e
         errs.append((MAT_B, l, j, e))
+        allow[2][j] += c * np.sqrt(np.sum(foot ** 2))
+        allow[3][j] += c * np.sqrt(np.sum((wn * foot) ** 2))
+        allow[0][:] += c * np.abs(foot)
+        allow[1][:] += c * (j + 1) * np.abs(foot)
+    tau2 = LineThresholds(tau, n, m, allow)
 
     r1, r2, q1, q2 = syndromes(Cbar)
-    Er, Et = detect(r1, r2, q1, q2, tau)
+    Er, Et = detect(r1, r2, q1, q2, tau2)
     s, t = len(Er), len(Et)
     if s == 0 and t == 0:
         return done(CORRECTED, errs)
     if 1 <= s <= 2 and 1 <= t <= 2:
-        fix = d0_correct(r1, r2, q1, q2, Er, Et, tau)
+        fix = d0_correct(r1, r2, q1, q2, Er, Et, tau2)
         if fix is not None and len(errs) + len(fix) <= MAX_REPORTED:
             for (i, j, x) in fix:
                 Cbar[i, j] -= x

@@ -14,6 +14,9 @@ __device__ __forceinline__ DecodeState* state_of(const DecodeArgs& a, int b) { r
 __device__ __forceinline__ double* synd_of(const DecodeArgs& a, int b) {
   return a.synd + (int64_t)b * (2 * a.p.n + 2 * a.p.m);
 }
+__device__ __forceinline__ double* allow_of(const DecodeArgs& a, int b) {
+  return a.allow + (int64_t)b * (2 * a.p.n + 2 * a.p.m);
+}
 __device__ __forceinline__ double* cpar_of(const DecodeArgs& a, int b) {
   return a.C_par + (int64_t)b * (2 * a.p.n + 2 * a.p.m + 4);
 }
@@ -61,6 +64,7 @@ __global__ __launch_bounds__(256) void threshold_kernel(DecodeArgs a, int first)
   const int o = blockIdx.x * 256 + threadIdx.x;
   const double* cpar = cpar_of(a, b);
   double* synd = synd_of(a, b);
+  const double* allow = allow_of(a, b);   // valid in the residual pass only
   double v1 = 0.0, v2 = 0.0;
   bool is_row = o < n, valid = o < n + m;
   if (valid) {
@@ -77,7 +81,8 @@ __global__ __launch_bounds__(256) void threshold_kernel(DecodeArgs a, int first)
       v2 = W - cpar[n + i];
       synd[i] = v1;
       synd[n + i] = v2;
-      if (fabs(v1) > a.p.tau_r1 || fabs(v2) > a.p.tau_r2) {
+      const double x1 = first ? 0.0 : allow[i], x2 = first ? 0.0 : allow[n + i];
+      if (fabs(v1) > a.p.tau_r1 + x1 || fabs(v2) > a.p.tau_r2 + x2) {
         const int idx = atomicAdd(&st->s_cnt, 1);
         if (idx < GECC_MAX_ERR) st->rows[idx] = i;
       }
@@ -94,7 +99,8 @@ __global__ __launch_bounds__(256) void threshold_kernel(DecodeArgs a, int first)
       v2 = W - cpar[2 * n + m + j];
       synd[2 * n + j] = v1;
       synd[2 * n + m + j] = v2;
-      if (fabs(v1) > a.p.tau_q1 || fabs(v2) > a.p.tau_q2) {
+      const double x1 = first ? 0.0 : allow[2 * n + j], x2 = first ? 0.0 : allow[2 * n + m + j];
+      if (fabs(v1) > a.p.tau_q1 + x1 || fabs(v2) > a.p.tau_q2 + x2) {
         const int idx = atomicAdd(&st->t_cnt, 1);
         if (idx < GECC_MAX_ERR) st->cols[idx] = j;
       }
@@ -145,7 +151,12 @@ __device__ void sort_small(int* v, int cnt) {
 
 struct Synd {
   const double *r1, *r2, *q1, *q2;
-  double tr1, tr2, tq1, tq2;
+  double b_r1, b_r2, b_q1, b_q2;            // thresholds of the four families
+  const double *a_r1, *a_r2, *a_q1, *a_q2;  // per-line allowances (null: none)
+  __device__ double tr1(int i) const { return b_r1 + (a_r1 ? a_r1[i] : 0.0); }
+  __device__ double tr2(int i) const { return b_r2 + (a_r2 ? a_r2[i] : 0.0); }
+  __device__ double tq1(int j) const { return b_q1 + (a_q1 ? a_q1[j] : 0.0); }
+  __device__ double tq2(int j) const { return b_q2 + (a_q2 ? a_q2[j] : 0.0); }
 };
 
 // every syndrome of a flagged line has to be explained by the estimate, within the thresholds
@@ -160,8 +171,8 @@ __device__ bool residual_ok(const Est* est, int ne, const int* Er, int s, const 
         sx += est[e].x; su += est[e].u;
         wx += (est[e].j + 1) * est[e].x; wu += (est[e].j + 1) * est[e].u;
       }
-    if (fabs(y.r1[i] - sx) > y.tr1 + su) return false;
-    if (fabs(y.r2[i] - wx) > y.tr2 + wu) return false;
+    if (fabs(y.r1[i] - sx) > y.tr1(i) + su) return false;
+    if (fabs(y.r2[i] - wx) > y.tr2(i) + wu) return false;
   }
   for (int c = 0; c < t; ++c) {
     const int j = Et[c];
@@ -171,8 +182,8 @@ __device__ bool residual_ok(const Est* est, int ne, const int* Er, int s, const 
         sx += est[e].x; su += est[e].u;
         wx += (est[e].i + 1) * est[e].x; wu += (est[e].i + 1) * est[e].u;
       }
-    if (fabs(y.q1[j] - sx) > y.tq1 + su) return false;
-    if (fabs(y.q2[j] - wx) > y.tq2 + wu) return false;
+    if (fabs(y.q1[j] - sx) > y.tq1(j) + su) return false;
+    if (fabs(y.q2[j] - wx) > y.tq2(j) + wu) return false;
   }
   return true;
 }
@@ -200,14 +211,14 @@ __device__ int d0_correct(Est* out, const int* Er, int s, const int* Et, int t, 
   Est est[4];
   if (s <= t) {
     if (s == 1) {
-      for (int c = 0; c < t; ++c) est[c] = Est{Er[0], Et[c], y.q1[Et[c]], y.tq1};
+      for (int c = 0; c < t; ++c) est[c] = Est{Er[0], Et[c], y.q1[Et[c]], y.tq1(Et[c])};
       const int k = accept(est, t, Er, s, Et, t, y);
       for (int e = 0; e < k; ++e) out[e] = est[e];
       return k;
     }
     const int s1 = Er[0], s2 = Er[1], t1 = Et[0], t2 = Et[1];
-    Est dg[4] = {Est{s1, t1, y.q1[t1], y.tq1}, Est{s2, t2, y.q1[t2], y.tq1}};
-    Est an[4] = {Est{s1, t2, y.q1[t2], y.tq1}, Est{s2, t1, y.q1[t1], y.tq1}};
+    Est dg[4] = {Est{s1, t1, y.q1[t1], y.tq1(t1)}, Est{s2, t2, y.q1[t2], y.tq1(t2)}};
+    Est an[4] = {Est{s1, t2, y.q1[t2], y.tq1(t2)}, Est{s2, t1, y.q1[t1], y.tq1(t1)}};
     const int kd = accept(dg, 2, Er, s, Et, t, y);
     const int ka = accept(an, 2, Er, s, Et, t, y);
     if (kd >= 0 && ka >= 0) return -1;   // cannot tell the two apart
@@ -219,8 +230,8 @@ __device__ int d0_correct(Est* out, const int* Er, int s, const int* Et, int t, 
       const int j = Et[c];
       const double e2 = (y.q2[j] - w1 * y.q1[j]) / (w2 - w1);
       const double e1 = y.q1[j] - e2;
-      const double u2 = (y.tq2 + w1 * y.tq1) / (w2 - w1);
-      const double u1 = y.tq1 + u2;
+      const double u2 = (y.tq2(j) + w1 * y.tq1(j)) / (w2 - w1);
+      const double u1 = y.tq1(j) + u2;
       est[ne++] = Est{s1, j, e1, u1};
       est[ne++] = Est{s2, j, e2, u2};
     }
@@ -228,7 +239,7 @@ __device__ int d0_correct(Est* out, const int* Er, int s, const int* Et, int t, 
     for (int e = 0; e < k; ++e) out[e] = est[e];
     return k;
   }
-  for (int r = 0; r < s; ++r) est[r] = Est{Er[r], Et[0], y.r1[Er[r]], y.tr1};
+  for (int r = 0; r < s; ++r) est[r] = Est{Er[r], Et[0], y.r1[Er[r]], y.tr1(Er[r])};
   const int k = accept(est, s, Er, s, Et, t, y);
   for (int e = 0; e < k; ++e) out[e] = est[e];
   return k;
@@ -276,7 +287,9 @@ __global__ __launch_bounds__(256) void decode_c_kernel(DecodeArgs a, int final_p
       sort_small(Er, s);
       sort_small(Et, t);
       const double* sy = synd_of(a, b);
-      Synd y{sy, sy + n, sy + 2 * n, sy + 2 * n + m, a.p.tau_r1, a.p.tau_r2, a.p.tau_q1, a.p.tau_q2};
+      const double* al = final_pass ? allow_of(a, b) : nullptr;
+      Synd y{sy, sy + n, sy + 2 * n, sy + 2 * n + m, a.p.tau_r1, a.p.tau_r2, a.p.tau_q1, a.p.tau_q2,
+             al, al ? al + n : nullptr, al ? al + 2 * n : nullptr, al ? al + 2 * n + m : nullptr};
       Est tmp[4];
       const int k = d0_correct(tmp, Er, s, Et, t, y);
       if (k >= 0 && st->n_err + k <= GECC_MAX_ERR) {
@@ -386,6 +399,15 @@ __global__ __launch_bounds__(256) void repair_kernel(DecodeArgs a) {
   double* cpar = cpar_of(a, b);
   const double* apar = a.A_par + (int64_t)b * 2 * k;
   const double* bpar = a.B_par + (int64_t)b * 2 * k;
+  // threshold allowances of the lines a repair touches (rounding noise of the corrupted terms)
+  double* al_r1 = allow_of(a, b);
+  double* al_r2 = al_r1 + n;
+  double* al_q1 = al_r1 + 2 * n;
+  double* al_q2 = al_r1 + 2 * n + m;
+  const double cc = a.p.tau_rep * sqrt((double)k);
+  __shared__ double red[2][256];
+  for (int o = threadIdx.x; o < 2 * n + 2 * m; o += blockDim.x) al_r1[o] = 0.0;
+  __syncthreads();
   for (int x = 0; x < na; ++x) {
     const int i = ha[x].pos, l = ha[x].line;
     const double e = ha[x].e;
@@ -393,10 +415,23 @@ __global__ __launch_bounds__(256) void repair_kernel(DecodeArgs a) {
       cpar[i] -= e * bpar[l];              // cbar_{i,m+1}
       cpar[n + i] -= e * bpar[k + l];      // cbar_{i,m+2}
     }
+    double s2 = 0.0, w2 = 0.0;
     for (int j = threadIdx.x; j < m; j += blockDim.x) {
       const int64_t ic = (int64_t)i * a.p.ldc + j;
-      C[ic] = (float)((double)C[ic] - e * load_elem(a.B, a.p.dtype, b_index(a.p, b, l, j)));
+      const double f = e * load_elem(a.B, a.p.dtype, b_index(a.p, b, l, j));
+      C[ic] = (float)((double)C[ic] - f);
+      s2 += f * f;
+      w2 += (double)(j + 1) * (j + 1) * f * f;
+      al_q1[j] += cc * fabs(f);
+      al_q2[j] += cc * (double)(i + 1) * fabs(f);
     }
+    red[0][threadIdx.x] = s2; red[1][threadIdx.x] = w2;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+      if ((int)threadIdx.x < w) { red[0][threadIdx.x] += red[0][threadIdx.x + w]; red[1][threadIdx.x] += red[1][threadIdx.x + w]; }
+      __syncthreads();
+    }
+    if (threadIdx.x == 0) { al_r1[i] += cc * sqrt(red[0][0]); al_r2[i] += cc * sqrt(red[1][0]); }
     __syncthreads();
   }
   for (int x = 0; x < nb; ++x) {
@@ -406,13 +441,26 @@ __global__ __launch_bounds__(256) void repair_kernel(DecodeArgs a) {
       cpar[2 * n + j] -= apar[l] * e;          // cbar_{n+1,j}
       cpar[2 * n + m + j] -= apar[k + l] * e;  // cbar_{n+2,j}
     }
+    double s2 = 0.0, w2 = 0.0;
     for (int i = threadIdx.x; i < n; i += blockDim.x) {
       double av = load_elem(a.A, a.p.dtype, a_index(a.p, b, i, l));
       for (int z = 0; z < na; ++z)
         if (ha[z].pos == i && ha[z].line == l) av -= ha[z].e;   // corrected A
       const int64_t ic = (int64_t)i * a.p.ldc + j;
-      C[ic] = (float)((double)C[ic] - av * e);
+      const double f = av * e;
+      C[ic] = (float)((double)C[ic] - f);
+      s2 += f * f;
+      w2 += (double)(i + 1) * (i + 1) * f * f;
+      al_r1[i] += cc * fabs(f);
+      al_r2[i] += cc * (double)(j + 1) * fabs(f);
     }
+    red[0][threadIdx.x] = s2; red[1][threadIdx.x] = w2;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+      if ((int)threadIdx.x < w) { red[0][threadIdx.x] += red[0][threadIdx.x + w]; red[1][threadIdx.x] += red[1][threadIdx.x + w]; }
+      __syncthreads();
+    }
+    if (threadIdx.x == 0) { al_q1[j] += cc * sqrt(red[0][0]); al_q2[j] += cc * sqrt(red[1][0]); }
     __syncthreads();
   }
   if (threadIdx.x == 0) {

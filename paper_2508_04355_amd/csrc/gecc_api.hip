@@ -20,6 +20,7 @@ void make_layout(gecc_ctx* c) {
   L.rowpart = take(b * c->ntn * n * 2 * sizeof(float));
   L.colpart = take(b * c->ntm * m * 2 * sizeof(float));
   L.synd = take(b * (2 * n + 2 * m) * sizeof(double));
+  L.allow = take(b * (2 * n + 2 * m) * sizeof(double));
   L.state = take(b * sizeof(DecodeState));
   L.audit_a = take(b * 2 * k * sizeof(double));
   L.audit_b = take(b * 2 * k * sizeof(double));
@@ -55,6 +56,7 @@ DecodeArgs decode_args(gecc_ctx* c, void* A, const double* A_par, void* B, const
   d.rowpart = reinterpret_cast<float*>(c->ws + c->lay.rowpart);
   d.colpart = reinterpret_cast<float*>(c->ws + c->lay.colpart);
   d.synd = reinterpret_cast<double*>(c->ws + c->lay.synd);
+  d.allow = reinterpret_cast<double*>(c->ws + c->lay.allow);
   d.state = reinterpret_cast<DecodeState*>(c->ws + c->lay.state);
   d.audit_a = reinterpret_cast<double*>(c->ws + c->lay.audit_a);
   d.audit_b = reinterpret_cast<double*>(c->ws + c->lay.audit_b);
@@ -135,6 +137,19 @@ GemmArgs gemm_args(const gecc_ctx* c, const void* A, const void* B, float* C) {
   return g;
 }
 
+// the product kernel, bracketed by a timing record when timing is enabled
+hipError_t timed_gemm(gecc_ctx* c, const GemmArgs& g, hipStream_t st) {
+  const bool rec = c->ev && c->ev_n < c->ev_cap;
+  hipError_t e;
+  if (rec && (e = hipEventRecord(c->ev[2 * c->ev_n], st)) != hipSuccess) return e;
+  if ((e = launch_gemm(g, st)) != hipSuccess) return e;
+  if (rec) {
+    if ((e = hipEventRecord(c->ev[2 * c->ev_n + 1], st)) != hipSuccess) return e;
+    ++c->ev_n;
+  }
+  return hipSuccess;
+}
+
 }  // namespace
 
 extern "C" {
@@ -155,7 +170,7 @@ int gecc_create(gecc_ctx** out, const gecc_params* p) {
       return GECC_ERR_ARG;
   }
   if (!(p->tau_r1 >= 0) || !(p->tau_r2 >= 0) || !(p->tau_q1 >= 0) || !(p->tau_q2 >= 0) ||
-      !(p->tau_op >= 0))
+      !(p->tau_op >= 0) || !(p->tau_rep >= 0))
     return GECC_ERR_ARG;
   if ((int64_t)p->n + p->m > (int64_t)1 << 30) return GECC_ERR_ARG;
   gecc_ctx* c = new (std::nothrow) gecc_ctx;
@@ -167,12 +182,52 @@ int gecc_create(gecc_ctx** out, const gecc_params* p) {
   c->ntn = (p->m + c->tile_n - 1) / c->tile_n;
   c->ws = nullptr;
   c->ws_bytes = 0;
+  c->ev = nullptr;
+  c->ev_cap = 0;
+  c->ev_n = 0;
   make_layout(c);
   *out = c;
   return GECC_OK;
 }
 
-void gecc_destroy(gecc_ctx* ctx) { delete ctx; }
+void gecc_destroy(gecc_ctx* ctx) {
+  if (!ctx) return;
+  gecc_timing_enable(ctx, 0);
+  delete ctx;
+}
+
+int gecc_timing_enable(gecc_ctx* ctx, int32_t max_records) {
+  if (!ctx || max_records < 0) return GECC_ERR_ARG;
+  for (int i = 0; i < 2 * ctx->ev_cap; ++i) (void)hipEventDestroy(ctx->ev[i]);
+  delete[] ctx->ev;
+  ctx->ev = nullptr;
+  ctx->ev_cap = 0;
+  ctx->ev_n = 0;
+  if (max_records == 0) return GECC_OK;
+  ctx->ev = new (std::nothrow) hipEvent_t[2 * (size_t)max_records];
+  if (!ctx->ev) return GECC_ERR_ARG;
+  for (int i = 0; i < 2 * max_records; ++i)
+    if (hipEventCreate(&ctx->ev[i]) != hipSuccess) {
+      for (int j = 0; j < i; ++j) (void)hipEventDestroy(ctx->ev[j]);
+      delete[] ctx->ev;
+      ctx->ev = nullptr;
+      return GECC_ERR_HIP;
+    }
+  ctx->ev_cap = max_records;
+  return GECC_OK;
+}
+
+int gecc_timing_read(gecc_ctx* ctx, float* host_ms, int32_t cap, int32_t* count) {
+  if (!ctx || !host_ms || !count || cap < 0) return GECC_ERR_ARG;
+  const int n = ctx->ev_n < cap ? ctx->ev_n : cap;
+  for (int i = 0; i < n; ++i) {
+    if (hipEventSynchronize(ctx->ev[2 * i + 1]) != hipSuccess) return GECC_ERR_HIP;
+    if (hipEventElapsedTime(&host_ms[i], ctx->ev[2 * i], ctx->ev[2 * i + 1]) != hipSuccess) return GECC_ERR_HIP;
+  }
+  *count = n;
+  ctx->ev_n = 0;
+  return GECC_OK;
+}
 
 size_t gecc_workspace_bytes(const gecc_ctx* ctx) { return ctx ? ctx->lay.total : 0; }
 
@@ -233,7 +288,7 @@ int gecc_multiply(gecc_ctx* ctx, const void* dev_A, const double* dev_A_par, con
   g.colpart = reinterpret_cast<float*>(ctx->ws + ctx->lay.colpart);
   g.faults = dev_faults;
   g.n_faults = n_faults;
-  return hip_rc(launch_gemm(g, st));
+  return hip_rc(timed_gemm(ctx, g, st));
 }
 
 int gecc_verify(gecc_ctx* ctx, const float* dev_C, const double* dev_C_par, gecc_report* dev_report,
@@ -308,7 +363,7 @@ int gecc_plain_gemm(gecc_ctx* ctx, const void* dev_A, const void* dev_B, float* 
     return GECC_ERR_ALIGN;
   GemmArgs g = gemm_args(ctx, dev_A, dev_B, dev_C);
   g.rowpart = nullptr; g.colpart = nullptr; g.faults = nullptr; g.n_faults = 0;
-  return hip_rc(launch_gemm(g, (hipStream_t)stream));
+  return hip_rc(timed_gemm(ctx, g, (hipStream_t)stream));
 }
 
 int gecc_report_to_host(gecc_ctx* ctx, const gecc_report* dev_report, gecc_report* host_report,

@@ -39,6 +39,7 @@ struct Layout {            // byte offsets into the caller's workspace
   size_t rowpart;          // float  [batch][ntn][n][2]   per-tile row sums (plain, local-weighted)
   size_t colpart;          // float  [batch][ntm][m][2]   per-tile column sums
   size_t synd;             // double [batch][2n + 2m]     r1, r2, q1, q2
+  size_t allow;            // double [batch][2n + 2m]     threshold allowances of repaired lines
   size_t state;            // DecodeState [batch]
   size_t audit_a;          // double [batch][2][k]        re-formed parity of A
   size_t audit_b;          // double [batch][2][k]        re-formed parity of B
@@ -56,6 +57,8 @@ struct gecc_ctx {
   int ntm, ntn;            // partial tiles along n and m
   char* ws;                // device workspace (caller's)
   size_t ws_bytes;
+  hipEvent_t* ev;          // optional timing records around the product kernel (start, stop pairs)
+  int ev_cap, ev_n;
 };
 
 namespace gecc {
@@ -128,6 +131,7 @@ struct DecodeArgs {
   const float* rowpart;
   const float* colpart;
   double* synd;
+  double* allow;
   DecodeState* state;
   const double* audit_a;
   const double* audit_b;

@@ -45,7 +45,7 @@ struct Stager {
   static constexpr int CHUNKS = ROWS * BK / VEC;
   static constexpr int PER_THREAD = CHUNKS / THREADS;
   static_assert(CHUNKS % THREADS == 0, "tile must split evenly over the workgroup");
-  T reg[PER_THREAD][VEC];
+  __attribute__((aligned(16))) T reg[PER_THREAD][VEC];
 
   __device__ __forceinline__ void load(const T* P, int64_t ld, int r0, int k0, int rlim, int klim,
                                        bool vec_ok) {
@@ -149,15 +149,14 @@ __device__ __forceinline__ void slab_store(float (*Cs)[BN + CPAD], int slab_r0, 
   }
 }
 
+// planted faults (distinct positions): each thread takes a strided share of the list
 __device__ __forceinline__ void apply_faults(const gecc_fault* faults, int n_faults, int b,
                                              int r_lo, int r_hi, int c_lo, int c_hi, float* Cs,
                                              int ldcs) {
-  if (n_faults > 0 && threadIdx.x == 0) {
-    for (int f = 0; f < n_faults; ++f) {
-      const gecc_fault ft = faults[f];
-      if (ft.batch == b && ft.row >= r_lo && ft.row < r_hi && ft.col >= c_lo && ft.col < c_hi)
-        Cs[(ft.row - r_lo) * ldcs + (ft.col - c_lo)] += ft.offset;
-    }
+  for (int f = threadIdx.x; f < n_faults; f += THREADS) {
+    const gecc_fault ft = faults[f];
+    if (ft.batch == b && ft.row >= r_lo && ft.row < r_hi && ft.col >= c_lo && ft.col < c_hi)
+      Cs[(ft.row - r_lo) * ldcs + (ft.col - c_lo)] += ft.offset;
   }
 }
 

@@ -15,7 +15,7 @@ import torch
 F32, BF16 = 0, 1
 CLEAN, CORRECTED, UNCORRECTABLE, DETECTED = 0, 1, 2, 3
 MAT_A, MAT_B, MAT_C = 0, 1, 2
-MAX_ERR, MAX_FAULTS = 8, 16
+MAX_ERR, MAX_FAULTS = 8, 1024
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libgecc.so")
 
@@ -27,7 +27,7 @@ class Params(C.Structure):
                 ("lda", C.c_int64), ("ldb", C.c_int64), ("ldc", C.c_int64),
                 ("stride_a", C.c_int64), ("stride_b", C.c_int64), ("stride_c", C.c_int64),
                 ("tau_r1", C.c_double), ("tau_r2", C.c_double), ("tau_q1", C.c_double),
-                ("tau_q2", C.c_double), ("tau_op", C.c_double)]
+                ("tau_q2", C.c_double), ("tau_op", C.c_double), ("tau_rep", C.c_double)]
 
 
 class Err(C.Structure):
@@ -51,7 +51,8 @@ _lib = None
 _SYMBOLS = ["gecc_create", "gecc_destroy", "gecc_workspace_bytes", "gecc_set_workspace",
             "gecc_a_par_len", "gecc_b_par_len", "gecc_c_par_len", "gecc_encode_a", "gecc_encode_b",
             "gecc_multiply", "gecc_verify", "gecc_correct", "gecc_protected_gemm", "gecc_plain_gemm",
-            "gecc_report_to_host", "gecc_syndromes_to_host", "gecc_strerror"]
+            "gecc_report_to_host", "gecc_syndromes_to_host", "gecc_timing_enable", "gecc_timing_read",
+            "gecc_strerror"]
 
 
 def lib():
@@ -82,6 +83,8 @@ def lib():
     L.gecc_plain_gemm.argtypes = [vp, vp, vp, vp, vp]
     L.gecc_report_to_host.argtypes = [vp, vp, C.POINTER(Report), i32, vp]
     L.gecc_syndromes_to_host.argtypes = [vp, vp, vp]
+    L.gecc_timing_enable.argtypes = [vp, i32]
+    L.gecc_timing_read.argtypes = [vp, C.POINTER(C.c_float), i32, C.POINTER(i32)]
     L.gecc_strerror.argtypes = [C.c_int]
     L.gecc_strerror.restype = C.c_char_p
     for f in _SYMBOLS:
@@ -116,6 +119,7 @@ class Thresholds:
     q1: float
     q2: float
     op: float = 0.0
+    rep: float = 16.0 * 2.0 ** -24     # rounding allowance for repaired lines (fp32 accumulation)
 
 
 def noise_thresholds(n, k, m, sigma_a, sigma_b, safety=16.0) -> Thresholds:
@@ -148,7 +152,8 @@ class Context:
                              stride_a=stride_a if stride_a is not None else rows_a * lda,
                              stride_b=stride_b if stride_b is not None else rows_b * ldb,
                              stride_c=stride_c if stride_c is not None else n * ldc,
-                             tau_r1=tau.r1, tau_r2=tau.r2, tau_q1=tau.q1, tau_q2=tau.q2, tau_op=tau.op)
+                             tau_r1=tau.r1, tau_r2=tau.r2, tau_q1=tau.q1, tau_q2=tau.q2, tau_op=tau.op,
+                             tau_rep=tau.rep)
         self._h = C.c_void_p()
         _check(lib().gecc_create(C.byref(self._h), C.byref(self.params)))
         self.device = torch.device(device)
@@ -206,6 +211,15 @@ class Context:
         host = (Report * self.batch)()
         _check(lib().gecc_report_to_host(self._h, _ptr(report), host, self.batch, _stream()))
         return list(host)
+
+    def timing_enable(self, max_records: int):
+        _check(lib().gecc_timing_enable(self._h, max_records))
+
+    def timing_read(self, cap: int) -> List[float]:
+        buf = (C.c_float * max(cap, 1))()
+        cnt = C.c_int32(0)
+        _check(lib().gecc_timing_read(self._h, buf, cap, C.byref(cnt)))
+        return [float(buf[i]) for i in range(cnt.value)]
 
     def syndromes_to_host(self):
         """(batch, 2n+2m) float64 numpy array: r1, r2, q1, q2 of the last verify."""

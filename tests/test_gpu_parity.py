@@ -1,0 +1,265 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on identical seeded inputs.
+
+Bar: status, located positions: bit-exact.  Corrected C: max |C - C_oracle| / max |C_oracle|
+<= 1e-5 (fp32 inputs) / 2e-2 (bf16 inputs, fp32 accumulation), checked at 1e-5 for both since
+the oracle consumes the same bf16-rounded inputs.  Parity buffers (fp64): relative 1e-12.
+"""
+import numpy as np
+import pytest
+
+import gpu_harness as H
+from oracle import grid_code as oc
+from paper_2508_04355_amd import configs, gecc, inputs
+
+pytestmark = pytest.mark.gpu
+
+MAT_A, MAT_B, MAT_C = inputs.MAT_A, inputs.MAT_B, inputs.MAT_C
+
+
+def _sigma(law):
+    return law[1] if law[0] == "normal" else (law[2] - law[1]) / 12 ** 0.5
+
+
+def _trial(rng, n, k, m, dtype, law_a, law_b, faults):
+    A, B = inputs.operands(rng, n, k, m, law_a, law_b, dtype)
+    A2, B2, cf, eff = inputs.apply_operand_faults(A, B, faults, dtype)
+    return A, B, A2, B2, cf, eff
+
+
+# ---------------------------------------------------------------------------------------------
+SHAPES = [(128, 128, 128), (1, 1, 1), (3, 5, 2), (130, 70, 257), (300, 200, 260), (257, 1031, 129)]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("trans", [(0, 0), (0, 1), (1, 0), (1, 1)])
+@pytest.mark.parametrize("shape", SHAPES)
+def test_clean_product_blocks_match_the_oracle(shape, trans, dtype):
+    n, k, m = shape
+    rng = inputs.rng_for(90, n + 7 * k + 13 * m)
+    law = ("normal", 1.0)
+    A, B = inputs.operands(rng, n, k, m, law, law, dtype)
+    tau = gecc.noise_thresholds(n, k, m, 1.0, 1.0)
+    g = H.run_gpu(A, B, A, B, [], tau, dtype, trans[0], trans[1])
+    AP, BP = oc.encode_a(A), oc.encode_b(B)
+    Cbar = oc.encoded_product(A, AP, B, BP)
+    assert g.reports[0].status == gecc.CLEAN and g.reports[0].n_err == 0
+    assert np.allclose(g.A_par[0], AP, rtol=1e-12, atol=1e-12 * np.abs(AP).max())
+    assert np.allclose(g.B_par[0], BP.T, rtol=1e-12, atol=1e-12 * np.abs(BP).max())
+    ref = np.concatenate([Cbar[:n, m], Cbar[:n, m + 1], Cbar[n, :m], Cbar[n + 1, :m], Cbar[n:, m:].ravel()])
+    assert np.allclose(g.C_par[0], ref, rtol=1e-11, atol=1e-12 * np.abs(ref).max())
+    scale = max(np.abs(Cbar[:n, :m]).max(), 1e-30)
+    assert np.abs(g.C[0] - Cbar[:n, :m]).max() / scale <= 1e-5
+    # syndromes (fp32 sums of an fp32 product) stay far inside the thresholds
+    mx = g.reports[0].max_abs_synd
+    assert mx[0] <= tau.r1 / 2 and mx[1] <= tau.r2 / 2 and mx[2] <= tau.q1 / 2 and mx[3] <= tau.q2 / 2
+
+
+def test_unaligned_leading_dimensions_take_the_scalar_paths():
+    n, k, m = 67, 45, 83
+    rng = inputs.rng_for(91)
+    for dtype in ("f32", "bf16"):
+        faults = [inputs.Fault(MAT_B, 44, 82, 9.0), inputs.Fault(MAT_C, 66, 0, -4.0)]
+        A, B, A2, B2, cf, eff = _trial(rng, n, k, m, dtype, ("normal", 1.0), ("normal", 1.0), faults)
+        tau = gecc.noise_thresholds(n, k, m, 1.0, 1.0)
+        cfb = [(0,) + c for c in cf]
+        g = H.run_gpu(A, B, A2, B2, cfb, tau, dtype, ld_pad=3)
+        H.compare(g, H.run_oracle(A, B, A2, B2, cfb, tau), 1e-5, what=dtype)
+        assert g.reports[0].status == gecc.CORRECTED
+
+
+def test_all_zero_operands_are_clean():
+    n, k, m = 200, 64, 136
+    Z = np.zeros((n, k), np.float32), np.zeros((k, m), np.float32)
+    tau = gecc.Thresholds(1e-6, 1e-6, 1e-6, 1e-6)
+    g = H.run_gpu(Z[0], Z[1], Z[0], Z[1], [], tau, "f32")
+    assert g.reports[0].status == gecc.CLEAN and np.all(g.C == 0) and np.all(g.C_par == 0)
+
+
+def test_results_are_reproducible_bit_for_bit():
+    w = configs.CFG1
+    rng = inputs.rng_for(1, 5)
+    faults = inputs.draw_faults(rng, w.n, w.k, w.m, 2, w.offset_law, [MAT_A, MAT_C])
+    A, B, A2, B2, cf, eff = _trial(rng, w.n, w.k, w.m, w.dtype, w.law_a, w.law_b, faults)
+    cfb = [(0,) + c for c in cf]
+    g1 = H.run_gpu(A, B, A2, B2, cfb, w.tau, w.dtype)
+    g2 = H.run_gpu(A, B, A2, B2, cfb, w.tau, w.dtype)
+    assert np.array_equal(g1.A_par, g2.A_par) and np.array_equal(g1.C_par, g2.C_par)
+    assert np.array_equal(g1.C, g2.C) and np.array_equal(g1.synd, g2.synd)
+    assert g1.reports[0].errors() == g2.reports[0].errors()
+
+
+# ---- configuration 1: 128^3 fp32 N(0,1), 0 / 1 / 2 errors, 1000 trials each -------------------
+@pytest.mark.parametrize("n_err", [0, 1, 2])
+def test_cfg1_thousand_trials_per_error_count(n_err):
+    w = configs.CFG1
+    BATCH = 250
+    n_corrected = n_unc = 0
+    for chunk in range(1000 // BATCH):
+        As, Bs, A2s, B2s, cfb, effs = [], [], [], [], [], []
+        for b in range(BATCH):
+            rng = inputs.rng_for(1, 10000 * n_err + chunk * BATCH + b)
+            faults = inputs.draw_faults(rng, w.n, w.k, w.m, n_err, w.offset_law)
+            A, B, A2, B2, cf, eff = _trial(rng, w.n, w.k, w.m, w.dtype, w.law_a, w.law_b, faults)
+            As.append(A); Bs.append(B); A2s.append(A2); B2s.append(B2); effs.append(eff)
+            cfb += [(b,) + c for c in cf]
+        As, Bs, A2s, B2s = map(np.stack, (As, Bs, A2s, B2s))
+        g = H.run_gpu(As, Bs, A2s, B2s, cfb, w.tau, w.dtype)
+        o = H.run_oracle(As, Bs, A2s, B2s, cfb, w.tau)
+        H.compare(g, o, w.tol_c, what="cfg1 n_err=%d chunk=%d" % (n_err, chunk))
+        for b, (rep, res) in enumerate(zip(g.reports, o)):
+            if n_err == 0:
+                assert rep.status == gecc.CLEAN
+            elif rep.status == gecc.CORRECTED:
+                n_corrected += 1
+                got = [(e[0], e[1], e[2]) for e in rep.errors()]
+                assert got == [(e[0], e[1], e[2]) for e in effs[b]], (chunk, b)
+            else:
+                n_unc += 1
+    if n_err == 1:
+        assert n_corrected == 1000
+    if n_err == 2:
+        # only two errors in one column of A / one row of B exceed the code (about 2 / (9 k) of pairs)
+        assert n_corrected + n_unc == 1000 and n_unc <= 10
+
+
+# ---- configuration 2: 1024^3 fp32 U(-1,1); none, 1 in C, 2 anywhere, adversarial pairs -------
+def _cfg2_patterns():
+    w = configs.CFG2
+    n, k, m = w.n, w.k, w.m
+    F = inputs.Fault
+    pats = {
+        "none": [],
+        "C": [F(MAT_C, 700, 13, 42.5)],
+        "C+C same row": [F(MAT_C, 5, 100, 3.0), F(MAT_C, 5, 900, -77.0)],
+        "C+C same row cancelling": [F(MAT_C, 5, 100, 8.0), F(MAT_C, 5, 101, -8.0)],
+        "C+C same col": [F(MAT_C, 1023, 0, 1.5), F(MAT_C, 0, 0, 99.0)],
+        "C+C adjacent diag": [F(MAT_C, 10, 20, 1.0), F(MAT_C, 11, 21, 1.0)],
+        "C+C anti": [F(MAT_C, 800, 20, -6.0), F(MAT_C, 30, 999, 2.0)],
+        "A": [F(MAT_A, 17, 1000, -31.0)],
+        "B": [F(MAT_B, 1000, 17, 12.0)],
+        "A+C C in A's row": [F(MAT_A, 300, 4, 10.0), F(MAT_C, 300, 77, -20.0)],
+        "A+C elsewhere": [F(MAT_A, 300, 4, 10.0), F(MAT_C, 301, 77, -20.0)],
+        "B+C C in B's col": [F(MAT_B, 9, 512, 5.0), F(MAT_C, 1000, 512, 64.0)],
+        "A+B same l": [F(MAT_A, 1, 600, 2.0), F(MAT_B, 600, 1022, -3.0)],
+        "A+B different l": [F(MAT_A, 1, 600, 2.0), F(MAT_B, 601, 1022, -3.0)],
+        "A+A same row": [F(MAT_A, 50, 1, 7.0), F(MAT_A, 50, 1023, 7.0)],
+        "B+B same col": [F(MAT_B, 2, 77, 1.25), F(MAT_B, 1000, 77, -90.0)],
+        "A+A same col (beyond the code)": [F(MAT_A, 50, 9, 7.0), F(MAT_A, 51, 9, 3.0)],
+        "B+B same row (beyond the code)": [F(MAT_B, 3, 9, 7.0), F(MAT_B, 3, 10, 3.0)],
+    }
+    for t in range(6):
+        rng = inputs.rng_for(2, 100 + t)
+        pats["random pair %d" % t] = inputs.draw_faults(rng, n, k, m, 2, w.offset_law)
+    return pats
+
+
+@pytest.mark.parametrize("name", list(_cfg2_patterns().keys()))
+def test_cfg2_patterns(name):
+    w = configs.CFG2
+    faults = _cfg2_patterns()[name]
+    rng = inputs.rng_for(2, 0)
+    A, B, A2, B2, cf, eff = _trial(rng, w.n, w.k, w.m, w.dtype, w.law_a, w.law_b, faults)
+    cfb = [(0,) + c for c in cf]
+    g = H.run_gpu(A, B, A2, B2, cfb, w.tau, w.dtype)
+    o = H.run_oracle(A, B, A2, B2, cfb, w.tau)
+    H.compare(g, o, w.tol_c, what=name)
+    rep = g.reports[0]
+    if "beyond" in name:
+        assert rep.status == gecc.UNCORRECTABLE
+    elif name == "none":
+        assert rep.status == gecc.CLEAN
+        mx = rep.max_abs_synd
+        assert mx[0] <= w.tau.r1 / 4 and mx[1] <= w.tau.r2 / 4 and mx[2] <= w.tau.q1 / 4 and mx[3] <= w.tau.q2 / 4
+    else:
+        assert rep.status == gecc.CORRECTED
+        assert [(e[0], e[1], e[2]) for e in rep.errors()] == [(e[0], e[1], e[2]) for e in eff]
+
+
+def test_cfg2_standalone_verify_and_unrefined_correction():
+    """C corrupted after the product (plain device writes), verified by the syndrome scan of C;
+    with refine off the corrected symbols carry the sqrt(n)-fold rounding noise of Section V's
+    subtraction: tolerance 16 sqrt(n) eps / max|C| instead of 1e-5."""
+    w = configs.CFG2
+    rng = inputs.rng_for(2, 1)
+    faults = [inputs.Fault(MAT_C, 100, 200, 17.0), inputs.Fault(MAT_C, 900, 201, -3.0)]
+    A, B, A2, B2, cf, eff = _trial(rng, w.n, w.k, w.m, w.dtype, w.law_a, w.law_b, faults)
+    cfb = [(0,) + c for c in cf]
+    o = H.run_oracle(A, B, A2, B2, cfb, w.tau)
+    g = H.run_gpu(A, B, A2, B2, cfb, w.tau, w.dtype, fused=False)
+    H.compare(g, o, w.tol_c, what="standalone")
+    g = H.run_gpu(A, B, A2, B2, cfb, w.tau, w.dtype, refine=0)
+    H.compare(g, o, w.tau.q1 / np.abs(o[0].C).max(), what="unrefined")
+
+
+# ---- configuration 3: 4096^3 bf16 N(0, 0.02^2), log-uniform offsets ---------------------------
+@pytest.mark.parametrize("trial", [0, 1, 2])
+def test_cfg3_trials(trial):
+    w = configs.CFG3
+    rng = inputs.rng_for(3, trial)
+    faults = inputs.draw_faults(rng, w.n, w.k, w.m, trial, w.offset_law,
+                                matrices=[None, [MAT_C], [MAT_A, MAT_C]][trial])
+    A, B, A2, B2, cf, eff = _trial(rng, w.n, w.k, w.m, w.dtype, w.law_a, w.law_b, faults)
+    cfb = [(0,) + c for c in cf]
+    g = H.run_gpu(A, B, A2, B2, cfb, w.tau, w.dtype)
+    o = H.run_oracle(A, B, A2, B2, cfb, w.tau)
+    H.compare(g, o, 1e-5, what="cfg3 trial %d" % trial)
+    if trial == 0:
+        mx = g.reports[0].max_abs_synd
+        assert mx[0] <= w.tau.r1 / 4 and mx[1] <= w.tau.r2 / 4 and mx[2] <= w.tau.q1 / 4 and mx[3] <= w.tau.q2 / 4
+    else:
+        assert g.reports[0].status == gecc.CORRECTED
+
+
+# ---- configuration 5: 256 batched 512^3 fp32, exactly two errors each ------------------------
+def test_cfg5_batched_two_errors_each():
+    w = configs.CFG5
+    As, Bs, A2s, B2s, cfb, effs = [], [], [], [], [], []
+    for b in range(w.batch):
+        rng = inputs.rng_for(5, b)
+        faults = inputs.draw_faults(rng, w.n, w.k, w.m, 2, w.offset_law)
+        A, B, A2, B2, cf, eff = _trial(rng, w.n, w.k, w.m, w.dtype, w.law_a, w.law_b, faults)
+        As.append(A); Bs.append(B); A2s.append(A2); B2s.append(B2); effs.append(eff)
+        cfb += [(b,) + c for c in cf]
+    As, Bs, A2s, B2s = map(np.stack, (As, Bs, A2s, B2s))
+    g = H.run_gpu(As, Bs, A2s, B2s, cfb, w.tau, w.dtype)
+    o = H.run_oracle(As, Bs, A2s, B2s, cfb, w.tau)
+    H.compare(g, o, w.tol_c, what="cfg5")
+    ok = sum(r.status == gecc.CORRECTED for r in g.reports)
+    assert ok >= w.batch - 3      # the rest: two errors in one line of an operand
+    for rep, eff in zip(g.reports, effs):
+        if rep.status == gecc.CORRECTED:
+            assert [(e[0], e[1], e[2]) for e in rep.errors()] == [(e[0], e[1], e[2]) for e in eff]
+
+
+# ---- configuration 4 at full size: sampled outputs and invariants -----------------------------
+@pytest.mark.parametrize("wname", ["cfg4-fwd", "cfg4-dgrad", "cfg4-wgrad"])
+def test_cfg4_full_size_sampled(wname):
+    w = configs.ALL[wname]
+    n, k, m = w.n, w.k, w.m
+    rng = inputs.rng_for(4, {"cfg4-fwd": 0, "cfg4-dgrad": 1, "cfg4-wgrad": 2}[wname])
+    faults = [inputs.Fault(MAT_A, n - 5, k - 3, 12.0), inputs.Fault(MAT_C, 4321 % n, m - 1, -33.0)]
+    A, B, A2, B2, cf, eff = _trial(rng, n, k, m, w.dtype, w.law_a, w.law_b, faults)
+    cfb = [(0,) + c for c in cf]
+    g = H.run_gpu(A, B, A2, B2, cfb, w.tau, w.dtype, w.trans_a, w.trans_b)
+    rep = g.reports[0]
+    assert rep.status == gecc.CORRECTED
+    assert [(e[0], e[1], e[2]) for e in rep.errors()] == [(e[0], e[1], e[2]) for e in eff]
+    assert np.allclose([e[3] for e in rep.errors()], [e[3] for e in eff], rtol=1e-3)
+    # parities against the oracle's encoder (whole operands)
+    AP, BP = oc.encode_a(A), oc.encode_b(B)
+    assert np.allclose(g.A_par[0], AP, rtol=1e-12, atol=1e-12 * np.abs(AP).max())
+    assert np.allclose(g.B_par[0], BP.T, rtol=1e-12, atol=1e-12 * np.abs(BP).max())
+    assert np.array_equal(g.A[0], A.astype(np.float64)) and np.array_equal(g.B[0], B.astype(np.float64))
+    # sampled rows / columns of the encoded product, computed by the oracle one slab at a time
+    rows = sorted({0, 1, 127, 128, n - 5, 4321 % n, n // 2 + 3, n - 1})
+    cols = sorted({0, 255, 256, m // 3, m - 2, m - 1})
+    R = oc.encoded_product(A[rows], AP, B, BP)          # rows of C-bar (plus the parity rows)
+    scale = np.abs(R[:len(rows), :m]).max()
+    assert np.abs(g.C[0][rows] - R[:len(rows), :m]).max() / scale <= 1e-5
+    cp = g.C_par[0]
+    assert np.allclose(cp[rows], R[:len(rows), m], rtol=1e-10, atol=1e-12 * scale * m)
+    assert np.allclose(cp[[n + r for r in rows]], R[:len(rows), m + 1], rtol=1e-10, atol=1e-12 * scale * m * m)
+    assert np.allclose(cp[2 * n:2 * n + m], R[len(rows), :m], rtol=1e-10, atol=1e-12 * scale * n)
+    assert np.allclose(cp[2 * n + m:2 * n + 2 * m], R[len(rows) + 1, :m], rtol=1e-10, atol=1e-12 * scale * n * n)
+    Ccols = oc.encoded_product(A, AP, B[:, cols], BP)[:n, :len(cols)]
+    assert np.abs(g.C[0][:, cols] - Ccols).max() / scale <= 1e-5
