@@ -133,7 +133,11 @@ def _cfg2_patterns():
         "C+C same row": [F(MAT_C, 5, 100, 3.0), F(MAT_C, 5, 900, -77.0)],
         "C+C same row cancelling": [F(MAT_C, 5, 100, 8.0), F(MAT_C, 5, 101, -8.0)],
         "C+C same col": [F(MAT_C, 1023, 0, 1.5), F(MAT_C, 0, 0, 99.0)],
-        "C+C adjacent diag": [F(MAT_C, 10, 20, 1.0), F(MAT_C, 11, 21, 1.0)],
+        # equal offsets in adjacent cells: the plain sums cannot tell the diagonal from the
+        # anti-diagonal and the weighted sums differ by less than their threshold -> ambiguous
+        "C+C adjacent diag, equal offsets (ambiguous)": [F(MAT_C, 10, 20, 1.0), F(MAT_C, 11, 21, 1.0)],
+        "C+C adjacent diag": [F(MAT_C, 10, 20, 1.0), F(MAT_C, 11, 21, 5.0)],
+        "C+C far diag, equal offsets": [F(MAT_C, 10, 20, 40.0), F(MAT_C, 900, 21, 40.0)],
         "C+C anti": [F(MAT_C, 800, 20, -6.0), F(MAT_C, 30, 999, 2.0)],
         "A": [F(MAT_A, 17, 1000, -31.0)],
         "B": [F(MAT_B, 1000, 17, 12.0)],
@@ -164,7 +168,7 @@ def test_cfg2_patterns(name):
     o = H.run_oracle(A, B, A2, B2, cfb, w.tau)
     H.compare(g, o, w.tol_c, what=name)
     rep = g.reports[0]
-    if "beyond" in name:
+    if "beyond" in name or "ambiguous" in name:
         assert rep.status == gecc.UNCORRECTABLE
     elif name == "none":
         assert rep.status == gecc.CLEAN
