@@ -8,7 +8,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libgecc.so")
-SOURCES = ["scan_kernels.hip", "gemm_kernels.hip", "decode_kernels.hip", "gecc_api.hip"]
+SOURCES = ["scan_kernels.hip", "gemm_kernels.hip", "gemm_bf16_kernels.hip", "decode_kernels.hip",
+           "gecc_api.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I" + os.path.join(ROOT, "include"),
          "-I" + CSRC, "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall",
          "-Wno-unused-function"]

@@ -103,6 +103,9 @@ struct GemmArgs {
   int n_faults;
 };
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t st);
+// 256 x 256-tile bf16 kernel for aligned operands (gemm_bf16_kernels.hip)
+bool gemm_bf16_fast_ok(const GemmArgs& a);
+hipError_t launch_gemm_bf16_fast(const GemmArgs& a, hipStream_t st);
 
 // stand-alone syndrome partials from a C in HBM (same workspace layout as the fused epilogue)
 struct PartialArgs {

@@ -329,6 +329,7 @@ hipError_t launch_dt(const GemmArgs& a, hipStream_t st) {
 
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t st) {
   if (a.tile_m != 128 || a.tile_n != 128) return hipErrorInvalidValue;
+  if (gemm_bf16_fast_ok(a)) return launch_gemm_bf16_fast(a, st);
   return a.dtype == GECC_BF16 ? launch_dt<GECC_BF16>(a, st) : launch_dt<GECC_F32>(a, st);
 }
 
