@@ -2,96 +2,137 @@
 // that holds nearly all flops of the path.
 //
 // Workgroup: 256 x 256 tile of C, 4 wavefronts (2 x 2), each owning a 128 x 128 sub-tile as
-// 4 x 4 MFMA 32x32x16 accumulators (256 fp32 registers per lane).  k advances in steps of 64
-// through two LDS buffers (2 x 64 KiB); the next operand tiles travel global -> registers
-// while the current ones feed the MFMA units.
+// 4 x 4 MFMA 32x32x16 accumulators (256 fp32 registers per lane).  k advances in steps of 32
+// through a ring of four LDS stages (4 x 32 KiB).  Operand tiles travel HBM -> LDS directly
+// (buffer loads with the LDS bit set: no registers in between, out-of-range rows read as
+// zero), three stages ahead of the one the MFMA units are consuming, which is what hides the
+// memory latency with a single workgroup per compute unit.
 //
-// LDS format (both operands, whatever their storage order): row = m- or n-index, 128 bytes
-// = 64 k-values per row, stored as eight 16-byte chunks whose position is XOR-swizzled with
-// the row index so that fragment reads (32 consecutive rows, one chunk each) and tile writes
-// are free of bank conflicts without padding.  An operand that is contiguous along m or n in
-// memory is loaded as 8 x 8 element blocks and transposed in registers on the way.
+// LDS formats, chosen so that neither the DMA writes (64 consecutive 16-byte slots per
+// wavefront instruction) nor the fragment reads hit a bank twice:
+//   operand contiguous along k in memory:  tile[row][32 k], 64 bytes per row, the four 16-byte
+//     chunks of a row XOR-swizzled with (row >> 1) & 3; fragments by ds_read_b128.
+//   operand contiguous along m (or n):     tile[32 k][256 m], 512 bytes per k-row, the sixteen
+//     32-byte chunks of a row XOR-swizzled with k & 3; fragments by the transposing LDS read
+//     (two ds_read_b64_tr_b16 per fragment: 16 lanes fetch 4 k-rows x 16 columns and each
+//     lane receives the 4 k-values of its own column).
 //
-// Epilogue, from the accumulators (no pass through LDS for C itself): planted faults, per
-// sub-tile column sums (in-lane) and row sums (through a small LDS transpose), then C.
+// Epilogue, from the accumulators (C itself never passes through LDS): per sub-tile column
+// sums (in-lane) and row sums (through a small LDS transpose) for Section V's syndromes, then
+// C.  A second instantiation additionally plants test faults into the accumulators first.
 #include "gecc_internal.h"
 
 namespace gecc {
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(4))) short s16x4_t;
+typedef __attribute__((ext_vector_type(8))) short s16x8_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+typedef __attribute__((ext_vector_type(4))) int i32x4_t;
+typedef __attribute__((address_space(3))) s16x4_t lds_s16x4_t;
 
 constexpr int THREADS = 256;
-constexpr int BM = 256, BN = 256, BK = 64;
-constexpr int ROW_BYTES = BK * 2;                  // 128
-constexpr int TILE_BYTES = BM * ROW_BYTES;         // 32 KiB per operand tile
+constexpr int BM = 256, BN = 256, BK = 32;
+constexpr int TILE_BYTES = BM * BK * 2;            // 16 KiB per operand tile
 constexpr int STAGE_BYTES = 2 * TILE_BYTES;        // A + B
-constexpr int SMEM_BYTES = 2 * STAGE_BYTES;        // double buffered: 128 KiB
+constexpr int NSTAGE = 4;
+constexpr int SMEM_BYTES = NSTAGE * STAGE_BYTES;   // 128 KiB
 constexpr int GROUP_M = 8;                         // tile rows per L2-sharing group
+constexpr unsigned OOB = 0x80000000u;              // voffset beyond any num_records: reads zero
 
-__device__ __forceinline__ int swz(int row) { return (row ^ (row >> 3)) & 7; }
-__device__ __forceinline__ int lds_off(int row, int chunk) {
-  return row * ROW_BYTES + ((chunk ^ swz(row)) << 4);
+// one LDS-DMA instruction: 64 lanes x 16 bytes from buffer `rsrc` at (voff + soff) into the
+// 1 KiB of LDS starting at lds_addr (lane L lands at lds_addr + 16 L).  Invisible to the
+// compiler's memory-counter bookkeeping on purpose: the waits are placed by hand below.
+__device__ __forceinline__ void dma16(unsigned lds_addr, unsigned voff, i32x4_t rsrc, unsigned soff) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+               :: "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff) : "memory");
 }
 
-// ---- operand tile: global -> registers -> LDS ------------------------------------------------
-// KC = true : element (r, kk) at P[r * ld + kk]  (k contiguous)
-// KC = false: element (r, kk) at P[kk * ld + r]  (r contiguous); 8 x 8 blocks, transposed here
-template <bool KC>
-struct TileStager {
-  uint4 reg[8];
+__device__ __forceinline__ i32x4_t make_rsrc(const void* base, unsigned bytes) {
+  const uint64_t p = reinterpret_cast<uint64_t>(base);
+  i32x4_t r;
+  r[0] = (int)(p & 0xffffffffu);
+  r[1] = (int)((p >> 32) & 0xffffu);       // stride 0: raw buffer, offsets in bytes
+  r[2] = (int)bytes;
+  r[3] = 0x00020000;
+  return r;
+}
 
-  __device__ __forceinline__ void load(const uint16_t* P, int64_t ld, int r0, int k0, int rlim, int klim) {
-    const int tid = threadIdx.x;
+// ---- per-operand addressing ---------------------------------------------------------------
+// KC = true : element (r, kk) at P[r * ld + kk]  (k contiguous)
+// KC = false: element (r, kk) at P[kk * ld + r]  (r contiguous)
+template <bool KC>
+struct Operand {
+  i32x4_t rsrc;
+  unsigned voff[4];     // byte offsets of this lane's four 16-byte slots, loop invariant
+  unsigned sstep;       // soffset advance per k-tile
+  int frag[4];          // LDS byte offset of this lane's fragment address for i = 0..3 (ks = 0)
+
+  // P: operand base for this batch item; r0: first row (m- or n-index) of the tile;
+  // rlim: number of valid rows; sub: first row of this wavefront's sub-tile inside the tile
+  __device__ __forceinline__ void init(const uint16_t* P, int64_t ld, int r0, int rlim, int klim, int sub) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     if (KC) {
+      const int64_t rows_left = rlim - r0;
+      const int64_t bytes = rows_left > 0 ? rows_left * ld * 2 : 0;
+      rsrc = make_rsrc(P + (int64_t)r0 * ld, (unsigned)(bytes > 0x7fffffff ? 0x7fffffff : bytes));
+      sstep = BK * 2;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const int q = tid + THREADS * i;
-        const int gr = r0 + (q >> 3), gk = k0 + ((q & 7) << 3);
-        const bool ok = gr < rlim && gk < klim;
-        reg[i] = ok ? *reinterpret_cast<const uint4*>(P + (int64_t)gr * ld + gk) : make_uint4(0, 0, 0, 0);
+      for (int i = 0; i < 4; ++i) {
+        const int s = (wave * 4 + i) * 64 + lane;          // slot in the tile
+        const int row = s >> 2, c = (s & 3) ^ ((row >> 1) & 3);
+        voff[i] = (unsigned)(row * ld * 2 + c * 16);
+      }
+      const int l32 = lane & 31, lhi = lane >> 5;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int row = sub + i * 32 + l32;
+        frag[i] = row * 64 + ((lhi ^ ((row >> 1) & 3)) << 4);   // chunk = 2 ks + lhi; ks toggles bit 1
       }
     } else {
-      const int gr = r0 + ((tid & 31) << 3);
-      const int gkb = k0 + ((tid >> 5) << 3);
+      const int64_t bytes = ((int64_t)klim * ld - r0) * 2;
+      rsrc = make_rsrc(P + r0, (unsigned)(bytes > 0x7fffffff ? 0x7fffffff : (bytes > 0 ? bytes : 0)));
+      sstep = (unsigned)(BK * ld * 2);
 #pragma unroll
-      for (int kk = 0; kk < 8; ++kk) {
-        const bool ok = gr < rlim && gkb + kk < klim;
-        reg[kk] = ok ? *reinterpret_cast<const uint4*>(P + (int64_t)(gkb + kk) * ld + gr) : make_uint4(0, 0, 0, 0);
+      for (int i = 0; i < 4; ++i) {
+        const int s = (wave * 4 + i) * 64 + lane;
+        const int krow = s >> 5, p = s & 31;
+        const int u = ((((p >> 1) ^ (krow & 3)) << 1) | (p & 1));   // logical 16-byte unit along r
+        voff[i] = (r0 + u * 8 < rlim) ? (unsigned)(krow * ld * 2 + u * 16) : OOB;
+      }
+      // transposing read: in each group of 16 lanes, lane 4 j + q supplies k-row j, columns 4 q..4 q + 3
+      const int g = lane >> 4, j = (lane >> 2) & 3, q = lane & 3;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int col = sub + i * 32 + 16 * (g & 1) + 4 * q;        // first of the 4 columns
+        const int krow = 8 * (g >> 1) + j;                          // + 16 ks, + 4 for the second read
+        const int u = col >> 3;
+        frag[i] = krow * 512 + (((((u >> 1) ^ j) << 1) | (u & 1)) << 4) + (col & 7) * 2;
       }
     }
   }
 
-  __device__ __forceinline__ void store(char* tile) const {
-    const int tid = threadIdx.x;
+  __device__ __forceinline__ void issue(unsigned lds_tile, unsigned soff) const {
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) dma16(lds_tile + (wave * 4 + i) * 1024, voff[i], rsrc, soff);
+  }
+
+  __device__ __forceinline__ bf16x8_t fragment(const char* tile, int i, int ks) const {
     if (KC) {
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const int q = tid + THREADS * i;
-        *reinterpret_cast<uint4*>(tile + lds_off(q >> 3, q & 7)) = reg[i];
-      }
+      return *reinterpret_cast<const bf16x8_t*>(tile + (frag[i] ^ (ks << 5)));
     } else {
-      // reg[kk] holds r = rb .. rb+7 at k = kb + kk.  Row (rb + e) of the tile needs the eight
-      // k-values of column e: dword p of it = { reg[2p][e], reg[2p+1][e] }.
-      const int rb = (tid & 31) << 3, g = tid >> 5;
-      const uint32_t* w = reinterpret_cast<const uint32_t*>(reg);   // w[kk * 4 + d]
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        uint4 o;
-        uint32_t* od = reinterpret_cast<uint32_t*>(&o);
-#pragma unroll
-        for (int p = 0; p < 4; ++p) {
-          const uint32_t x = w[(2 * p) * 4 + (e >> 1)], y = w[(2 * p + 1) * 4 + (e >> 1)];
-          od[p] = (e & 1) ? ((x >> 16) | (y & 0xffff0000u)) : ((x & 0xffffu) | (y << 16));
-        }
-        *reinterpret_cast<uint4*>(tile + lds_off(rb + e, g)) = o;
-      }
+      const char* p = tile + frag[i] + ks * (16 * 512);
+      const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(p));
+      const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(p + 4 * 512));
+      const s16x8_t v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      return __builtin_bit_cast(bf16x8_t, v);
     }
   }
 };
 
-template <bool KCA, bool KCB, bool EPI>
+template <bool KCA, bool KCB, bool EPI, bool FAULTS>
 __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -122,6 +163,11 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
   const uint16_t* B = reinterpret_cast<const uint16_t*>(a.B) + (int64_t)b * a.sb;
   float* C = a.C + (int64_t)b * a.sc;
 
+  Operand<KCA> oa;
+  Operand<KCB> ob;
+  oa.init(A, a.lda, tile_r0, a.n, a.k, wr * 128);
+  ob.init(B, a.ldb, tile_c0, a.m, a.k, wc * 128);
+
   f32x16_t acc[4][4];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
@@ -130,41 +176,40 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  // fragment addresses inside a tile: row = sub-tile base + 32 * i + l32, chunk = 2 * ks + lhi
-  int a_row[4], b_row[4], a_sw[4], b_sw[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    a_row[i] = (wr * 128 + i * 32 + l32) * ROW_BYTES;
-    b_row[i] = (wc * 128 + i * 32 + l32) * ROW_BYTES;
-    a_sw[i] = swz(wr * 128 + i * 32 + l32);
-    b_sw[i] = swz(wc * 128 + i * 32 + l32);
-  }
+  // LDS byte address of the ring (the address-space-3 pointer value, not the flat address)
+  const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
+  const int KT = a.k / BK;                           // k % 32 == 0 (checked by the launcher)
 
-  TileStager<KCA> sa;
-  TileStager<KCB> sb;
-  const int KT = (a.k + BK - 1) / BK;
-  sa.load(A, a.lda, tile_r0, 0, a.n, a.k);
-  sb.load(B, a.ldb, tile_c0, 0, a.m, a.k);
-  sa.store(smem);
-  sb.store(smem + TILE_BYTES);
-  __syncthreads();
+  // prologue: stages 0 .. 2 in flight
+#pragma unroll
+  for (int s = 0; s < NSTAGE - 1; ++s)
+    if (s < KT) {
+      oa.issue(lds0 + s * STAGE_BYTES, s * oa.sstep);
+      ob.issue(lds0 + s * STAGE_BYTES + TILE_BYTES, s * ob.sstep);
+    }
 
   for (int kt = 0; kt < KT; ++kt) {
-    char* cur = smem + (kt & 1) * STAGE_BYTES;
-    char* nxt = smem + ((kt & 1) ^ 1) * STAGE_BYTES;
-    const bool more = kt + 1 < KT;
-    if (more) {
-      sa.load(A, a.lda, tile_r0, (kt + 1) * BK, a.n, a.k);
-      sb.load(B, a.ldb, tile_c0, (kt + 1) * BK, a.m, a.k);
+    // stage kt has landed once at most the loads of the (up to two) younger stages are pending
+    const int younger = min(NSTAGE - 2, KT - 1 - kt);
+    if (younger >= 2)      asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+    else if (younger == 1) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    else                   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // own fragment reads of stage kt - 1 are back
+    __builtin_amdgcn_s_barrier();        // everyone's share of stage kt is in LDS, and everyone is
+    asm volatile("" ::: "memory");       // done reading stage kt - 1, whose slot is refilled next
+    if (kt + NSTAGE - 1 < KT) {
+      const unsigned st = lds0 + ((kt + NSTAGE - 1) & (NSTAGE - 1)) * STAGE_BYTES;
+      oa.issue(st, (kt + NSTAGE - 1) * oa.sstep);
+      ob.issue(st + TILE_BYTES, (kt + NSTAGE - 1) * ob.sstep);
     }
+    const char* cur = smem + (kt & (NSTAGE - 1)) * STAGE_BYTES;
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
+    for (int ks = 0; ks < 2; ++ks) {
       bf16x8_t fa[4], fb[4];
-      const int ch = 2 * ks + lhi;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        fa[i] = *reinterpret_cast<const bf16x8_t*>(cur + a_row[i] + ((ch ^ a_sw[i]) << 4));
-        fb[i] = *reinterpret_cast<const bf16x8_t*>(cur + TILE_BYTES + b_row[i] + ((ch ^ b_sw[i]) << 4));
+        fa[i] = oa.fragment(cur, i, ks);
+        fb[i] = ob.fragment(cur + TILE_BYTES, i, ks);
       }
 #pragma unroll
       for (int i = 0; i < 4; ++i)
@@ -172,19 +217,11 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
         for (int j = 0; j < 4; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
     }
-    if (more) {
-      sa.store(nxt);
-      sb.store(nxt + TILE_BYTES);
-    }
-    __syncthreads();
   }
 
   // ---- epilogue -------------------------------------------------------------------------------
   const int R0 = tile_r0 + wr * 128, C0 = tile_c0 + wc * 128;   // origin of this wavefront's sub-tile
-  if (R0 >= a.n || C0 >= a.m) {
-    // nothing of this sub-tile is inside C; still take part in the barriers below
-  }
-  if (a.n_faults > 0) {
+  if (FAULTS) {
     for (int f = 0; f < a.n_faults; ++f) {
       const gecc_fault ft = a.faults[f];
       if (ft.batch != b || ft.row < R0 || ft.row >= R0 + 128 || ft.col < C0 || ft.col >= C0 + 128) continue;
@@ -269,10 +306,10 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
     }
 }
 
-template <bool KCA, bool KCB, bool EPI>
+template <bool KCA, bool KCB, bool EPI, bool FAULTS>
 hipError_t launch_one(const GemmArgs& a, hipStream_t st) {
   static bool configured = false;   // per instantiation
-  auto kern = gemm_bf16_256<KCA, KCB, EPI>;
+  auto kern = gemm_bf16_256<KCA, KCB, EPI, FAULTS>;
   if (!configured) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, SMEM_BYTES);
@@ -285,32 +322,38 @@ hipError_t launch_one(const GemmArgs& a, hipStream_t st) {
   return hipGetLastError();
 }
 
-template <bool EPI>
-hipError_t launch_epi(const GemmArgs& a, hipStream_t st) {
+template <bool EPI, bool FAULTS>
+hipError_t launch_layout(const GemmArgs& a, hipStream_t st) {
   const bool kca = a.trans_a == 0, kcb = a.trans_b != 0;
-  if (kca && kcb) return launch_one<true, true, EPI>(a, st);
-  if (kca && !kcb) return launch_one<true, false, EPI>(a, st);
-  if (!kca && kcb) return launch_one<false, true, EPI>(a, st);
-  return launch_one<false, false, EPI>(a, st);
+  if (kca && kcb) return launch_one<true, true, EPI, FAULTS>(a, st);
+  if (kca && !kcb) return launch_one<true, false, EPI, FAULTS>(a, st);
+  if (!kca && kcb) return launch_one<false, true, EPI, FAULTS>(a, st);
+  return launch_one<false, false, EPI, FAULTS>(a, st);
 }
 
 }  // namespace
 
-// The fast kernel needs 16-byte aligned operand rows and whole 8-element chunks:
-// k % 8 == 0, leading dimensions % 8 == 0, and n (m) % 8 == 0 for an operand stored with n (m)
-// contiguous.  Partial sums are produced per 128 x 128 sub-tile.
+// The fast kernel needs 16-byte aligned operand rows, whole 16-byte chunks and whole k-tiles:
+// k % 32 == 0, leading dimensions % 8 == 0, n (m) % 8 == 0 for an operand stored with n (m)
+// contiguous, and operand panels that 32-bit byte offsets can address.  Partial sums are
+// produced per 128 x 128 sub-tile.  Everything else goes to the generic 128 x 128 kernel.
 bool gemm_bf16_fast_ok(const GemmArgs& a) {
   if (a.dtype != GECC_BF16 || a.tile_m != 128 || a.tile_n != 128) return false;
-  if (a.k % 8 || a.lda % 8 || a.ldb % 8) return false;
+  if (a.k % BK || a.lda % 8 || a.ldb % 8) return false;
   if (reinterpret_cast<uintptr_t>(a.A) % 16 || reinterpret_cast<uintptr_t>(a.B) % 16) return false;
   if (a.batch > 1 && (a.sa % 8 || a.sb % 8)) return false;
   if (a.trans_a && a.n % 8) return false;
   if (!a.trans_b && a.m % 8) return false;
+  // byte offsets inside a tile panel (k-contiguous: 256 rows; otherwise the whole k extent)
+  const int64_t span_a = (a.trans_a ? (int64_t)a.k : (int64_t)BM) * a.lda * 2;
+  const int64_t span_b = (a.trans_b ? (int64_t)BN : (int64_t)a.k) * a.ldb * 2;
+  if (span_a >= 0x7fffffff || span_b >= 0x7fffffff) return false;
   return (int64_t)a.n * a.m >= (int64_t)BM * BN;   // smaller problems: the 128 x 128 kernel
 }
 
 hipError_t launch_gemm_bf16_fast(const GemmArgs& a, hipStream_t st) {
-  return a.rowpart ? launch_epi<true>(a, st) : launch_epi<false>(a, st);
+  if (!a.rowpart) return launch_layout<false, false>(a, st);
+  return a.n_faults > 0 ? launch_layout<true, true>(a, st) : launch_layout<true, false>(a, st);
 }
 
 }  // namespace gecc
