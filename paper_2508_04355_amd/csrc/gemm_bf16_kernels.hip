@@ -20,6 +20,7 @@
 // Epilogue, from the accumulators (C itself never passes through LDS): per sub-tile column
 // sums (in-lane) and row sums (through a small LDS transpose) for Section V's syndromes, then
 // C.  A second instantiation additionally plants test faults into the accumulators first.
+#include <type_traits>
 #include "gecc_internal.h"
 
 namespace gecc {
@@ -132,6 +133,29 @@ struct Operand {
   }
 };
 
+// Scheduling hint for one quarter (4 MFMAs) of a half k-tile: the NDS LDS reads issued in that
+// quarter are placed one or two at a time behind the MFMAs instead of in front of them.
+template <int NDS>
+__device__ __forceinline__ void hint_quarter() {
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                       // one MFMA
+    if (r == 0 && (NDS + 3) / 4 > 0) __builtin_amdgcn_sched_group_barrier(0x100, (NDS + 3) / 4, 0);
+    if (r == 1 && (NDS + 2) / 4 > 0) __builtin_amdgcn_sched_group_barrier(0x100, (NDS + 2) / 4, 0);
+    if (r == 2 && (NDS + 1) / 4 > 0) __builtin_amdgcn_sched_group_barrier(0x100, (NDS + 1) / 4, 0);
+    if (r == 3 && NDS / 4 > 0)       __builtin_amdgcn_sched_group_barrier(0x100, NDS / 4, 0);
+  }
+}
+// reads per quarter: B fragments 0-2 | B fragment 3 and A fragments 0-1 | A fragments 2-3 | none
+template <bool KCA, bool KCB>
+__device__ __forceinline__ void interleave(int quarter, bool reads) {
+  constexpr int NA = KCA ? 1 : 2, NB = KCB ? 1 : 2;   // LDS instructions per fragment
+  if (!reads || quarter == 3) hint_quarter<0>();
+  else if (quarter == 0)      hint_quarter<3 * NB>();
+  else if (quarter == 1)      hint_quarter<NB + 2 * NA>();
+  else                        hint_quarter<2 * NA>();
+}
+
 template <bool KCA, bool KCB, bool EPI, bool FAULTS>
 __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
@@ -179,45 +203,101 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
   // LDS byte address of the ring (the address-space-3 pointer value, not the flat address)
   const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
   const int KT = a.k / BK;                           // k % 32 == 0 (checked by the launcher)
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
 
-  // prologue: stages 0 .. 2 in flight
+  // Software pipeline.  Stage t = k-tile t in ring slot t & 3.  Two fragment sets: fr0 for the
+  // first 16 k of a stage, fr1 for the second.  Steady state of iteration kt:
+  //     read fr1 of stage kt | 16 MFMAs on fr0 | stage kt+1 landed? barrier | start the DMA of
+  //     stage kt+4 into the slot stage kt just left, read fr0 of stage kt+1 | 16 MFMAs on fr1
+  // so every LDS read and every DMA issue has 16 MFMAs (512 cycles) of cover.
 #pragma unroll
-  for (int s = 0; s < NSTAGE - 1; ++s)
+  for (int s = 0; s < NSTAGE; ++s)
     if (s < KT) {
       oa.issue(lds0 + s * STAGE_BYTES, s * oa.sstep);
       ob.issue(lds0 + s * STAGE_BYTES + TILE_BYTES, s * ob.sstep);
     }
-
-  for (int kt = 0; kt < KT; ++kt) {
-    // stage kt has landed once at most the loads of the (up to two) younger stages are pending
-    const int younger = min(NSTAGE - 2, KT - 1 - kt);
-    if (younger >= 2)      asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+  {
+    const int younger = min(NSTAGE - 1, KT - 1);
+    if (younger >= 3)      asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
+    else if (younger == 2) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
     else if (younger == 1) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
     else                   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // own fragment reads of stage kt - 1 are back
-    __builtin_amdgcn_s_barrier();        // everyone's share of stage kt is in LDS, and everyone is
-    asm volatile("" ::: "memory");       // done reading stage kt - 1, whose slot is refilled next
-    if (kt + NSTAGE - 1 < KT) {
-      const unsigned st = lds0 + ((kt + NSTAGE - 1) & (NSTAGE - 1)) * STAGE_BYTES;
-      oa.issue(st, (kt + NSTAGE - 1) * oa.sstep);
-      ob.issue(st + TILE_BYTES, (kt + NSTAGE - 1) * ob.sstep);
-    }
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+  }
+  bf16x8_t fa0[4], fb0[4], fa1[4], fb1[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    fa0[i] = oa.fragment(smem, i, 0);
+    fb0[i] = ob.fragment(smem + TILE_BYTES, i, 0);
+  }
+
+  // one k-tile; REFILL / NEXT are compile-time in the steady state so that the body is one
+  // basic block the scheduler can interleave freely
+  auto k_tile = [&](auto refill_c, auto next_c, const int kt) {
+    constexpr bool REFILL = decltype(refill_c)::value, NEXT = decltype(next_c)::value;
     const char* cur = smem + (kt & (NSTAGE - 1)) * STAGE_BYTES;
+    const char* nxt = smem + ((kt + 1) & (NSTAGE - 1)) * STAGE_BYTES;
+    // first half: 16 MFMAs on fr0; the reads of fr1 (second 16 k of stage kt) are spread over
+    // the first three quarters, B fragments first (every quarter of the next half needs all of
+    // them, but only one A fragment)
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-      bf16x8_t fa[4], fb[4];
+    for (int i = 0; i < 4; ++i) {
+      if (i == 0) { fb1[0] = ob.fragment(cur + TILE_BYTES, 0, 1); fb1[1] = ob.fragment(cur + TILE_BYTES, 1, 1);
+                    fb1[2] = ob.fragment(cur + TILE_BYTES, 2, 1); }
+      if (i == 1) { fb1[3] = ob.fragment(cur + TILE_BYTES, 3, 1); fa1[0] = oa.fragment(cur, 0, 1);
+                    fa1[1] = oa.fragment(cur, 1, 1); }
+      if (i == 2) { fa1[2] = oa.fragment(cur, 2, 1); fa1[3] = oa.fragment(cur, 3, 1); }
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        fa[i] = oa.fragment(cur, i, ks);
-        fb[i] = ob.fragment(cur + TILE_BYTES, i, ks);
+      for (int j = 0; j < 4; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0[i], fb0[j], acc[i][j], 0, 0, 0);
+      interleave<KCA, KCB>(i, true);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+
+    if (NEXT) {
+      // stage kt+1 has landed once only the (up to two) younger stages are still pending
+      const int younger = REFILL ? NSTAGE - 2 : min(NSTAGE - 2, KT - 2 - kt);
+      if (younger >= 2)      asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+      else if (younger == 1) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+      else                   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // own reads of stage kt are back
+    __builtin_amdgcn_s_barrier();        // stage kt+1 complete for everyone; stage kt released
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+
+    // second half: 16 MFMAs on fr1; between them the reads of fr0 of stage kt+1 and the DMA of
+    // stage kt+4 into the slot stage kt just left
+    const unsigned slot = lds0 + (kt & (NSTAGE - 1)) * STAGE_BYTES + (wave_u * 4) * 1024;
+    const unsigned sa_off = (kt + NSTAGE) * oa.sstep, sb_off = (kt + NSTAGE) * ob.sstep;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if (NEXT) {
+        if (i == 0) { fb0[0] = ob.fragment(nxt + TILE_BYTES, 0, 0); fb0[1] = ob.fragment(nxt + TILE_BYTES, 1, 0);
+                      fb0[2] = ob.fragment(nxt + TILE_BYTES, 2, 0); }
+        if (i == 1) { fb0[3] = ob.fragment(nxt + TILE_BYTES, 3, 0); fa0[0] = oa.fragment(nxt, 0, 0);
+                      fa0[1] = oa.fragment(nxt, 1, 0); }
+        if (i == 2) { fa0[2] = oa.fragment(nxt, 2, 0); fa0[3] = oa.fragment(nxt, 3, 0); }
       }
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+      for (int j = 0; j < 4; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa1[i], fb1[j], acc[i][j], 0, 0, 0);
+      interleave<KCA, KCB>(i, NEXT);
+      __builtin_amdgcn_sched_barrier(0);
+      if (REFILL) {
+        dma16(slot + i * 1024, oa.voff[i], oa.rsrc, sa_off);
+        dma16(slot + TILE_BYTES + i * 1024, ob.voff[i], ob.rsrc, sb_off);
+      }
     }
-  }
+  };
+  using T_ = std::true_type;
+  using F_ = std::false_type;
+  int kt = 0;
+  for (; kt + NSTAGE < KT; ++kt) k_tile(T_{}, T_{}, kt);   // steady state
+  for (; kt + 1 < KT; ++kt) k_tile(F_{}, T_{}, kt);        // drain: nothing left to fetch
+  k_tile(F_{}, F_{}, kt);                                  // last k-tile
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
   // ---- epilogue -------------------------------------------------------------------------------
   const int R0 = tile_r0 + wr * 128, C0 = tile_c0 + wc * 128;   // origin of this wavefront's sub-tile
