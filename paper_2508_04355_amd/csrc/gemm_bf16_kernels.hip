@@ -2,20 +2,24 @@
 // that holds nearly all flops of the path.
 //
 // Workgroup: 256 x 256 tile of C, 4 wavefronts (2 x 2), each owning a 128 x 128 sub-tile as
-// 4 x 4 MFMA 32x32x16 accumulators (256 fp32 registers per lane).  k advances in steps of 32
-// through a ring of four LDS stages (4 x 32 KiB).  Operand tiles travel HBM -> LDS directly
-// (buffer loads with the LDS bit set: no registers in between, out-of-range rows read as
-// zero), three stages ahead of the one the MFMA units are consuming, which is what hides the
-// memory latency with a single workgroup per compute unit.
+// 4 x 4 MFMA 32x32x16 accumulators (256 fp32 registers per lane).  k advances in tiles of 32.
+// Operand tiles travel HBM -> LDS directly (buffer loads with the LDS bit set: no registers in
+// between, out-of-range rows read as zero) and several k-tiles ahead of the one the MFMA units
+// are consuming, which is what hides the memory latency with one workgroup per compute unit.
+// Every request asks L2 for whole 128-byte lines: the L2 request rate, not its bandwidth, is
+// what 32 compute units per XCD saturate first.
 //
-// LDS formats, chosen so that neither the DMA writes (64 consecutive 16-byte slots per
-// wavefront instruction) nor the fragment reads hit a bank twice:
-//   operand contiguous along k in memory:  tile[row][32 k], 64 bytes per row, the four 16-byte
-//     chunks of a row XOR-swizzled with (row >> 1) & 3; fragments by ds_read_b128.
-//   operand contiguous along m (or n):     tile[32 k][256 m], 512 bytes per k-row, the sixteen
-//     32-byte chunks of a row XOR-swizzled with k & 3; fragments by the transposing LDS read
-//     (two ds_read_b64_tr_b16 per fragment: 16 lanes fetch 4 k-rows x 16 columns and each
-//     lane receives the 4 k-values of its own column).
+// LDS (64 KiB per operand), laid out so that neither the DMA writes (64 consecutive 16-byte
+// slots per wavefront instruction) nor the fragment reads hit a bank twice:
+// (the LDS serves 256 bytes per cycle from 64 banks: 16 lanes of a 16-byte read, 32 lanes of
+// an 8-byte read):
+//   operand contiguous along k in memory:  two slots, each a PAIR of k-tiles: tile[row][64 k],
+//     128 bytes per row (one full line per row and request), the eight 16-byte chunks of a row
+//     XOR-swizzled with (row >> 1) & 7; fragments by ds_read_b128.
+//   operand contiguous along m (or n):     four slots of one k-tile: tile[32 k][256 m], 512
+//     bytes per k-row, the eight 64-byte chunks of a row XOR-swizzled with k & 3; fragments
+//     by the transposing LDS read (two ds_read_b64_tr_b16 per fragment: 16 lanes fetch 4
+//     k-rows x 16 columns and each lane receives the 4 k-values of its own column).
 //
 // Epilogue, from the accumulators (C itself never passes through LDS): per sub-tile column
 // sums (in-lane) and row sums (through a small LDS transpose) for Section V's syndromes, then
@@ -35,10 +39,10 @@ typedef __attribute__((address_space(3))) s16x4_t lds_s16x4_t;
 
 constexpr int THREADS = 256;
 constexpr int BM = 256, BN = 256, BK = 32;
-constexpr int TILE_BYTES = BM * BK * 2;            // 16 KiB per operand tile
-constexpr int STAGE_BYTES = 2 * TILE_BYTES;        // A + B
-constexpr int NSTAGE = 4;
-constexpr int SMEM_BYTES = NSTAGE * STAGE_BYTES;   // 128 KiB
+constexpr int TILE_BYTES = BM * BK * 2;            // 16 KiB: one k-tile of one operand
+constexpr int NSTAGE = 4;                          // k-tiles of one operand resident in LDS
+constexpr int REGION_BYTES = NSTAGE * TILE_BYTES;  // 64 KiB per operand
+constexpr int SMEM_BYTES = 2 * REGION_BYTES;       // 128 KiB
 constexpr int GROUP_M = 8;                         // tile rows per L2-sharing group
 constexpr unsigned OOB = 0x80000000u;              // voffset beyond any num_records: reads zero
 
@@ -61,14 +65,15 @@ __device__ __forceinline__ i32x4_t make_rsrc(const void* base, unsigned bytes) {
 }
 
 // ---- per-operand addressing ---------------------------------------------------------------
-// KC = true : element (r, kk) at P[r * ld + kk]  (k contiguous)
-// KC = false: element (r, kk) at P[kk * ld + r]  (r contiguous)
+// KC = true : element (r, kk) at P[r * ld + kk]  (k contiguous);  LDS: 2 slots x pair of k-tiles
+// KC = false: element (r, kk) at P[kk * ld + r]  (r contiguous);  LDS: 4 slots x one k-tile
 template <bool KC>
 struct Operand {
+  static constexpr int NV = KC ? 8 : 4;   // DMA instructions of this wavefront per pair / per k-tile
   i32x4_t rsrc;
-  unsigned voff[4];     // byte offsets of this lane's four 16-byte slots, loop invariant
-  unsigned sstep;       // soffset advance per k-tile
-  int frag[4];          // LDS byte offset of this lane's fragment address for i = 0..3 (ks = 0)
+  unsigned voff[NV];    // byte offsets of this lane's 16-byte slots, loop invariant
+  unsigned sstep;       // soffset advance per pair (KC) / per k-tile
+  int frag[4];          // LDS byte offset of this lane's fragment address for i = 0..3
 
   // P: operand base for this batch item; r0: first row (m- or n-index) of the tile;
   // rlim: number of valid rows; sub: first row of this wavefront's sub-tile inside the tile
@@ -78,28 +83,29 @@ struct Operand {
       const int64_t rows_left = rlim - r0;
       const int64_t bytes = rows_left > 0 ? rows_left * ld * 2 : 0;
       rsrc = make_rsrc(P + (int64_t)r0 * ld, (unsigned)(bytes > 0x7fffffff ? 0x7fffffff : bytes));
-      sstep = BK * 2;
+      sstep = 2 * BK * 2;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int s = (wave * 4 + i) * 64 + lane;          // slot in the tile
-        const int row = s >> 2, c = (s & 3) ^ ((row >> 1) & 3);
+      for (int i = 0; i < NV; ++i) {
+        const int s = (wave * NV + i) * 64 + lane;          // slot in the pair tile
+        const int row = s >> 3, c = (s & 7) ^ ((row >> 1) & 7);   // 8 lanes = one 128-byte line
         voff[i] = (unsigned)(row * ld * 2 + c * 16);
       }
       const int l32 = lane & 31, lhi = lane >> 5;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int row = sub + i * 32 + l32;
-        frag[i] = row * 64 + ((lhi ^ ((row >> 1) & 3)) << 4);   // chunk = 2 ks + lhi; ks toggles bit 1
+        // chunk = 4 (k-tile parity) + 2 ks + lhi; parity and ks toggle bits 6 and 5 of the offset
+        frag[i] = row * 128 + ((lhi ^ ((row >> 1) & 7)) << 4);
       }
     } else {
       const int64_t bytes = ((int64_t)klim * ld - r0) * 2;
       rsrc = make_rsrc(P + r0, (unsigned)(bytes > 0x7fffffff ? 0x7fffffff : (bytes > 0 ? bytes : 0)));
       sstep = (unsigned)(BK * ld * 2);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int s = (wave * 4 + i) * 64 + lane;
+      for (int i = 0; i < NV; ++i) {
+        const int s = (wave * NV + i) * 64 + lane;
         const int krow = s >> 5, p = s & 31;
-        const int u = ((((p >> 1) ^ (krow & 3)) << 1) | (p & 1));   // logical 16-byte unit along r
+        const int u = ((((p >> 2) ^ (krow & 3)) << 2) | (p & 3));   // logical 16-byte unit along r
         voff[i] = (r0 + u * 8 < rlim) ? (unsigned)(krow * ld * 2 + u * 16) : OOB;
       }
       // transposing read: in each group of 16 lanes, lane 4 j + q supplies k-row j, columns 4 q..4 q + 3
@@ -109,20 +115,31 @@ struct Operand {
         const int col = sub + i * 32 + 16 * (g & 1) + 4 * q;        // first of the 4 columns
         const int krow = 8 * (g >> 1) + j;                          // + 16 ks, + 4 for the second read
         const int u = col >> 3;
-        frag[i] = krow * 512 + (((((u >> 1) ^ j) << 1) | (u & 1)) << 4) + (col & 7) * 2;
+        frag[i] = krow * 512 + (((((u >> 2) ^ j) << 2) | (u & 3)) << 4) + (col & 7) * 2;
       }
     }
   }
 
-  __device__ __forceinline__ void issue(unsigned lds_tile, unsigned soff) const {
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) dma16(lds_tile + (wave * 4 + i) * 1024, voff[i], rsrc, soff);
+  // LDS byte offset (inside this operand's region) of the slot that holds k-tile kt
+  static __device__ __forceinline__ int slot_of(int kt) {
+    return KC ? ((kt >> 1) & 1) * (2 * TILE_BYTES) : (kt & (NSTAGE - 1)) * TILE_BYTES;
   }
 
-  __device__ __forceinline__ bf16x8_t fragment(const char* tile, int i, int ks) const {
+  // DMA instruction i (0 .. NV-1) of this wavefront for the unit (pair or k-tile) number `unit`
+  __device__ __forceinline__ void issue_one(unsigned lds_region, int wave_u, int unit, int i) const {
+    const unsigned slot = KC ? (unit & 1) * (2 * TILE_BYTES) : (unit & (NSTAGE - 1)) * TILE_BYTES;
+    dma16(lds_region + slot + (wave_u * NV + i) * 1024, voff[i], rsrc, unit * sstep);
+  }
+  __device__ __forceinline__ void issue_unit(unsigned lds_region, int wave_u, int unit) const {
+#pragma unroll
+    for (int i = 0; i < NV; ++i) issue_one(lds_region, wave_u, unit, i);
+  }
+
+  // fragment i of the ks-th 16 k of k-tile kt; region = this operand's LDS region
+  __device__ __forceinline__ bf16x8_t fragment(const char* region, int kt, int i, int ks) const {
+    const char* tile = region + slot_of(kt);
     if (KC) {
-      return *reinterpret_cast<const bf16x8_t*>(tile + (frag[i] ^ (ks << 5)));
+      return *reinterpret_cast<const bf16x8_t*>(tile + (frag[i] ^ (((kt & 1) << 6) | (ks << 5))));
     } else {
       const char* p = tile + frag[i] + ks * (16 * 512);
       const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(p));
@@ -132,6 +149,21 @@ struct Operand {
     }
   }
 };
+
+// s_waitcnt vmcnt(n) for the multiples of 4 the DMA bookkeeping below can ask for
+__device__ __forceinline__ void wait_vm(int n) {
+  switch (n >> 2) {
+    case 0: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
+    case 1: asm volatile("s_waitcnt vmcnt(4)" ::: "memory"); break;
+    case 2: asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); break;
+    case 3: asm volatile("s_waitcnt vmcnt(12)" ::: "memory"); break;
+    case 4: asm volatile("s_waitcnt vmcnt(16)" ::: "memory"); break;
+    case 5: asm volatile("s_waitcnt vmcnt(20)" ::: "memory"); break;
+    case 6: asm volatile("s_waitcnt vmcnt(24)" ::: "memory"); break;
+    case 7: asm volatile("s_waitcnt vmcnt(28)" ::: "memory"); break;
+    default: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
+  }
+}
 
 // Scheduling hint for one quarter (4 MFMAs) of a half k-tile: the NDS LDS reads issued in that
 // quarter are placed one or two at a time behind the MFMAs instead of in front of them.
@@ -200,54 +232,69 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  // LDS byte address of the ring (the address-space-3 pointer value, not the flat address)
-  const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
-  const int KT = a.k / BK;                           // k % 32 == 0 (checked by the launcher)
+  // LDS byte addresses of the two operand regions (address-space-3 values, not flat addresses)
+  const unsigned ldsA = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
+  const unsigned ldsB = ldsA + REGION_BYTES;
+  const char* regA = smem;
+  const char* regB = smem + REGION_BYTES;
+  const int KT = a.k / BK;                           // even: k % 64 == 0 (checked by the launcher)
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);
 
-  // Software pipeline.  Stage t = k-tile t in ring slot t & 3.  Two fragment sets: fr0 for the
-  // first 16 k of a stage, fr1 for the second.  Steady state of iteration kt:
-  //     read fr1 of stage kt | 16 MFMAs on fr0 | stage kt+1 landed? barrier | start the DMA of
-  //     stage kt+4 into the slot stage kt just left, read fr0 of stage kt+1 | 16 MFMAs on fr1
-  // so every LDS read and every DMA issue has 16 MFMAs (512 cycles) of cover.
+  // DMA bookkeeping.  A "unit" is what one slot holds: a pair of k-tiles for a k-contiguous
+  // operand (nK of them), one k-tile otherwise (nM of them).  Issue order per wavefront:
+  //   prologue:      pair 0 | k-tiles 0 1 2 3 | pair 1
+  //   iteration kt:  after its barrier, k-tile kt+4 (4 nM instructions), then, if kt is odd,
+  //                  pair (kt+3)/2 (8 nK instructions) -- into the slots k-tile kt just left
+  // The memory counter retires in order, so "k-tile kt+1 has landed" (needed at the barrier of
+  // iteration kt) means: at most the instructions issued after its unit are still pending,
+  //   kt even: those of iterations kt-2 and kt-1;  kt odd: those of iteration kt-1
+  // (with no k-contiguous operand the first rule holds for every kt).
+  constexpr int nK = (KCA ? 1 : 0) + (KCB ? 1 : 0), nM = 2 - nK;
+  auto issued_in = [&](int j) {   // DMA instructions of this wavefront in iteration j
+    return (j >= 0 && j + NSTAGE < KT ? 4 * nM : 0) + (j >= 0 && (j & 1) && j + 3 < KT ? 8 * nK : 0);
+  };
+  if (KCA) oa.issue_unit(ldsA, wave_u, 0);
+  if (KCB) ob.issue_unit(ldsB, wave_u, 0);
 #pragma unroll
   for (int s = 0; s < NSTAGE; ++s)
     if (s < KT) {
-      oa.issue(lds0 + s * STAGE_BYTES, s * oa.sstep);
-      ob.issue(lds0 + s * STAGE_BYTES + TILE_BYTES, s * ob.sstep);
+      if (!KCA) oa.issue_unit(ldsA, wave_u, s);
+      if (!KCB) ob.issue_unit(ldsB, wave_u, s);
     }
-  {
-    const int younger = min(NSTAGE - 1, KT - 1);
-    if (younger >= 3)      asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
-    else if (younger == 2) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
-    else if (younger == 1) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-    else                   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
+  if (2 < KT) {
+    if (KCA) oa.issue_unit(ldsA, wave_u, 1);
+    if (KCB) ob.issue_unit(ldsB, wave_u, 1);
   }
+  // k-tile 0: everything after pair 0 and k-tile 0 may still be pending
+  wait_vm(4 * nM * (min(NSTAGE, KT) - 1) + (2 < KT ? 8 * nK : 0));
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+
+  // Software pipeline with two fragment sets: fr0 = first 16 k of a k-tile, fr1 = second.
+  // Iteration kt:  16 MFMAs on fr0 with the reads of fr1 between them | k-tile kt+1 landed?
+  // barrier | 16 MFMAs on fr1 with the reads of fr0 of k-tile kt+1 and the DMA issue between
+  // them -- every LDS read and every DMA instruction has MFMAs in flight as cover.
   bf16x8_t fa0[4], fb0[4], fa1[4], fb1[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    fa0[i] = oa.fragment(smem, i, 0);
-    fb0[i] = ob.fragment(smem + TILE_BYTES, i, 0);
+    fa0[i] = oa.fragment(regA, 0, i, 0);
+    fb0[i] = ob.fragment(regB, 0, i, 0);
   }
 
-  // one k-tile; REFILL / NEXT are compile-time in the steady state so that the body is one
+  // one k-tile; STEADY: parity, refill and successor are compile-time so that the body is one
   // basic block the scheduler can interleave freely
-  auto k_tile = [&](auto refill_c, auto next_c, const int kt) {
-    constexpr bool REFILL = decltype(refill_c)::value, NEXT = decltype(next_c)::value;
-    const char* cur = smem + (kt & (NSTAGE - 1)) * STAGE_BYTES;
-    const char* nxt = smem + ((kt + 1) & (NSTAGE - 1)) * STAGE_BYTES;
-    // first half: 16 MFMAs on fr0; the reads of fr1 (second 16 k of stage kt) are spread over
-    // the first three quarters, B fragments first (every quarter of the next half needs all of
-    // them, but only one A fragment)
+  auto k_tile = [&](auto steady_c, auto odd_c, const int kt) {
+    constexpr bool STEADY = decltype(steady_c)::value, ODD = decltype(odd_c)::value;
+    const bool next = STEADY || kt + 1 < KT;
+    // first half: 16 MFMAs on fr0; the reads of fr1 are spread over the first three quarters,
+    // B fragments first (every quarter of the next half needs all of them, but only one A)
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      if (i == 0) { fb1[0] = ob.fragment(cur + TILE_BYTES, 0, 1); fb1[1] = ob.fragment(cur + TILE_BYTES, 1, 1);
-                    fb1[2] = ob.fragment(cur + TILE_BYTES, 2, 1); }
-      if (i == 1) { fb1[3] = ob.fragment(cur + TILE_BYTES, 3, 1); fa1[0] = oa.fragment(cur, 0, 1);
-                    fa1[1] = oa.fragment(cur, 1, 1); }
-      if (i == 2) { fa1[2] = oa.fragment(cur, 2, 1); fa1[3] = oa.fragment(cur, 3, 1); }
+      if (i == 0) { fb1[0] = ob.fragment(regB, kt, 0, 1); fb1[1] = ob.fragment(regB, kt, 1, 1);
+                    fb1[2] = ob.fragment(regB, kt, 2, 1); }
+      if (i == 1) { fb1[3] = ob.fragment(regB, kt, 3, 1); fa1[0] = oa.fragment(regA, kt, 0, 1);
+                    fa1[1] = oa.fragment(regA, kt, 1, 1); }
+      if (i == 2) { fa1[2] = oa.fragment(regA, kt, 2, 1); fa1[3] = oa.fragment(regA, kt, 3, 1); }
 #pragma unroll
       for (int j = 0; j < 4; ++j)
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0[i], fb0[j], acc[i][j], 0, 0, 0);
@@ -255,48 +302,53 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
     }
     __builtin_amdgcn_sched_barrier(0);
 
-    if (NEXT) {
-      // stage kt+1 has landed once only the (up to two) younger stages are still pending
-      const int younger = REFILL ? NSTAGE - 2 : min(NSTAGE - 2, KT - 2 - kt);
-      if (younger >= 2)      asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
-      else if (younger == 1) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-      else                   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if (STEADY) {
+      if (nK == 0 || !ODD) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+      else                 wait_vm(4 * nM);
+    } else if (next) {
+      wait_vm((nK == 0 || !(kt & 1)) ? issued_in(kt - 2) + issued_in(kt - 1) : issued_in(kt - 1));
     }
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // own reads of stage kt are back
-    __builtin_amdgcn_s_barrier();        // stage kt+1 complete for everyone; stage kt released
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // own reads of k-tile kt are back
+    __builtin_amdgcn_s_barrier();        // k-tile kt+1 complete for everyone; k-tile kt released
     asm volatile("" ::: "memory");
     __builtin_amdgcn_sched_barrier(0);
 
-    // second half: 16 MFMAs on fr1; between them the reads of fr0 of stage kt+1 and the DMA of
-    // stage kt+4 into the slot stage kt just left
-    const unsigned slot = lds0 + (kt & (NSTAGE - 1)) * STAGE_BYTES + (wave_u * 4) * 1024;
-    const unsigned sa_off = (kt + NSTAGE) * oa.sstep, sb_off = (kt + NSTAGE) * ob.sstep;
+    // second half: 16 MFMAs on fr1; between them the reads of fr0 of k-tile kt+1 and the DMA
+    // into the slots k-tile kt just left
+    const bool refill_m = STEADY || kt + NSTAGE < KT;
+    const bool refill_k = STEADY ? ODD : ((kt & 1) && kt + 3 < KT);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      if (NEXT) {
-        if (i == 0) { fb0[0] = ob.fragment(nxt + TILE_BYTES, 0, 0); fb0[1] = ob.fragment(nxt + TILE_BYTES, 1, 0);
-                      fb0[2] = ob.fragment(nxt + TILE_BYTES, 2, 0); }
-        if (i == 1) { fb0[3] = ob.fragment(nxt + TILE_BYTES, 3, 0); fa0[0] = oa.fragment(nxt, 0, 0);
-                      fa0[1] = oa.fragment(nxt, 1, 0); }
-        if (i == 2) { fa0[2] = oa.fragment(nxt, 2, 0); fa0[3] = oa.fragment(nxt, 3, 0); }
+      if (next) {
+        if (i == 0) { fb0[0] = ob.fragment(regB, kt + 1, 0, 0); fb0[1] = ob.fragment(regB, kt + 1, 1, 0);
+                      fb0[2] = ob.fragment(regB, kt + 1, 2, 0); }
+        if (i == 1) { fb0[3] = ob.fragment(regB, kt + 1, 3, 0); fa0[0] = oa.fragment(regA, kt + 1, 0, 0);
+                      fa0[1] = oa.fragment(regA, kt + 1, 1, 0); }
+        if (i == 2) { fa0[2] = oa.fragment(regA, kt + 1, 2, 0); fa0[3] = oa.fragment(regA, kt + 1, 3, 0); }
       }
 #pragma unroll
       for (int j = 0; j < 4; ++j)
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa1[i], fb1[j], acc[i][j], 0, 0, 0);
-      interleave<KCA, KCB>(i, NEXT);
+      interleave<KCA, KCB>(i, next);
       __builtin_amdgcn_sched_barrier(0);
-      if (REFILL) {
-        dma16(slot + i * 1024, oa.voff[i], oa.rsrc, sa_off);
-        dma16(slot + TILE_BYTES + i * 1024, ob.voff[i], ob.rsrc, sb_off);
+      if (refill_m) {
+        if (!KCA) oa.issue_one(ldsA, wave_u, kt + NSTAGE, i);
+        if (!KCB) ob.issue_one(ldsB, wave_u, kt + NSTAGE, i);
+      }
+      if (refill_k) {
+        if (KCA) { oa.issue_one(ldsA, wave_u, (kt + 3) >> 1, 2 * i); oa.issue_one(ldsA, wave_u, (kt + 3) >> 1, 2 * i + 1); }
+        if (KCB) { ob.issue_one(ldsB, wave_u, (kt + 3) >> 1, 2 * i); ob.issue_one(ldsB, wave_u, (kt + 3) >> 1, 2 * i + 1); }
       }
     }
   };
   using T_ = std::true_type;
   using F_ = std::false_type;
   int kt = 0;
-  for (; kt + NSTAGE < KT; ++kt) k_tile(T_{}, T_{}, kt);   // steady state
-  for (; kt + 1 < KT; ++kt) k_tile(F_{}, T_{}, kt);        // drain: nothing left to fetch
-  k_tile(F_{}, F_{}, kt);                                  // last k-tile
+  for (; kt + NSTAGE + 1 < KT; kt += 2) {   // steady state, two k-tiles per trip (kt even)
+    k_tile(T_{}, F_{}, kt);
+    k_tile(T_{}, T_{}, kt + 1);
+  }
+  for (; kt < KT; ++kt) k_tile(F_{}, F_{}, kt);   // drain
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
   // ---- epilogue -------------------------------------------------------------------------------
@@ -413,13 +465,13 @@ hipError_t launch_layout(const GemmArgs& a, hipStream_t st) {
 
 }  // namespace
 
-// The fast kernel needs 16-byte aligned operand rows, whole 16-byte chunks and whole k-tiles:
-// k % 32 == 0, leading dimensions % 8 == 0, n (m) % 8 == 0 for an operand stored with n (m)
+// The fast kernel needs 16-byte aligned operand rows, whole 16-byte chunks and whole pairs of
+// k-tiles: k % 64 == 0, leading dimensions % 8 == 0, n (m) % 8 == 0 for an operand stored with n (m)
 // contiguous, and operand panels that 32-bit byte offsets can address.  Partial sums are
 // produced per 128 x 128 sub-tile.  Everything else goes to the generic 128 x 128 kernel.
 bool gemm_bf16_fast_ok(const GemmArgs& a) {
   if (a.dtype != GECC_BF16 || a.tile_m != 128 || a.tile_n != 128) return false;
-  if (a.k % BK || a.lda % 8 || a.ldb % 8) return false;
+  if (a.k % (2 * BK) || a.lda % 8 || a.ldb % 8) return false;
   if (reinterpret_cast<uintptr_t>(a.A) % 16 || reinterpret_cast<uintptr_t>(a.B) % 16) return false;
   if (a.batch > 1 && (a.sa % 8 || a.sb % 8)) return false;
   if (a.trans_a && a.n % 8) return false;
