@@ -56,12 +56,12 @@ __global__ void reset_state_kernel(DecodeArgs a) {
 }
 
 // partial sums -> syndromes (sum - parity, Section V step 1) -> flags
-__global__ __launch_bounds__(256) void threshold_kernel(DecodeArgs a, int first) {
+__global__ __launch_bounds__(64) void threshold_kernel(DecodeArgs a, int first) {
   const int b = blockIdx.y;
   DecodeState* st = state_of(a, b);
   if (!first && st->phase != PH_REVERIFY) return;
   const int n = a.p.n, m = a.p.m;
-  const int o = blockIdx.x * 256 + threadIdx.x;
+  const int o = blockIdx.x * 64 + threadIdx.x;
   const double* cpar = cpar_of(a, b);
   double* synd = synd_of(a, b);
   const double* allow = allow_of(a, b);   // valid in the residual pass only
@@ -71,11 +71,22 @@ __global__ __launch_bounds__(256) void threshold_kernel(DecodeArgs a, int first)
     if (is_row) {
       const int i = o;
       double S = 0.0, W = 0.0;
-      for (int tn = 0; tn < a.ntn; ++tn) {
-        const float* rp = a.rowpart + (((int64_t)b * a.ntn + tn) * n + i) * 2;
-        const double s = rp[0];
-        S += s;
-        W += (double)rp[1] + (double)(tn * a.tile_n) * s;
+      const float2* rp = reinterpret_cast<const float2*>(a.rowpart) + (int64_t)b * a.ntn * n + i;
+      int tn = 0;
+      for (; tn + 8 <= a.ntn; tn += 8) {            // 8 loads in flight
+        float2 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = rp[(int64_t)(tn + u) * n];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          S += (double)v[u].x;
+          W += (double)v[u].y + (double)((tn + u) * a.tile_n) * (double)v[u].x;
+        }
+      }
+      for (; tn < a.ntn; ++tn) {
+        const float2 v = rp[(int64_t)tn * n];
+        S += (double)v.x;
+        W += (double)v.y + (double)(tn * a.tile_n) * (double)v.x;
       }
       v1 = S - cpar[i];
       v2 = W - cpar[n + i];
@@ -89,11 +100,22 @@ __global__ __launch_bounds__(256) void threshold_kernel(DecodeArgs a, int first)
     } else {
       const int j = o - n;
       double S = 0.0, W = 0.0;
-      for (int tm = 0; tm < a.ntm; ++tm) {
-        const float* cp = a.colpart + (((int64_t)b * a.ntm + tm) * m + j) * 2;
-        const double s = cp[0];
-        S += s;
-        W += (double)cp[1] + (double)(tm * a.tile_m) * s;
+      const float2* cp = reinterpret_cast<const float2*>(a.colpart) + (int64_t)b * a.ntm * m + j;
+      int tm = 0;
+      for (; tm + 8 <= a.ntm; tm += 8) {
+        float2 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = cp[(int64_t)(tm + u) * m];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          S += (double)v[u].x;
+          W += (double)v[u].y + (double)((tm + u) * a.tile_m) * (double)v[u].x;
+        }
+      }
+      for (; tm < a.ntm; ++tm) {
+        const float2 v = cp[(int64_t)tm * m];
+        S += (double)v.x;
+        W += (double)v.y + (double)(tm * a.tile_m) * (double)v.x;
       }
       v1 = S - cpar[2 * n + j];
       v2 = W - cpar[2 * n + m + j];
@@ -534,8 +556,8 @@ hipError_t launch_reset_state(const DecodeArgs& a, hipStream_t st) {
 }
 
 hipError_t launch_threshold(const DecodeArgs& a, int first, hipStream_t st) {
-  dim3 grid((a.p.n + a.p.m + 255) / 256, a.p.batch);
-  hipLaunchKernelGGL(threshold_kernel, grid, dim3(256), 0, st, a, first);
+  dim3 grid((a.p.n + a.p.m + 63) / 64, a.p.batch);   // one wavefront per workgroup: spreads over all CUs
+  hipLaunchKernelGGL(threshold_kernel, grid, dim3(64), 0, st, a, first);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || !first) return e;
   hipLaunchKernelGGL(summarize_kernel, dim3((a.p.batch + 63) / 64), dim3(64), 0, st, a);

@@ -46,9 +46,9 @@ __device__ __forceinline__ bool gated_off(const int32_t* gate, int64_t stride, i
 // rowdot: out[t][r] = sum_c w_t[c] X[r,c].   One workgroup owns RB rows and walks all columns;
 // a thread keeps the weights of its VEC columns in registers and reuses them for the RB rows.
 constexpr int RD_THREADS = 256;
-constexpr int RD_RB = 16;
 
-template <int DT, bool IDXW>
+// RD_RB rows per workgroup: 16 when there are rows enough to fill the chip, else 4
+template <int DT, bool IDXW, int RD_RB>
 __global__ __launch_bounds__(RD_THREADS) void rowdot_kernel(ScanArgs a) {
   using E = Elem<DT>;
   using T = typename E::type;
@@ -207,15 +207,29 @@ __global__ __launch_bounds__(CD_THREADS) void coldot_stage1(ScanArgs a, int nchu
   }
 }
 
+// 64 outputs per workgroup; the 4 wavefronts take the chunks 4 apart and are combined in order
 __global__ __launch_bounds__(256) void coldot_stage2(ScanArgs a, int nchunk) {
   const int b = blockIdx.y;
   if (gated_off(a.gate, a.gate_stride, b, a.gate_value)) return;
-  const int o = blockIdx.x * 256 + threadIdx.x;   // index into [2][Cc]
-  if (o >= 2 * a.Cc) return;
-  const double* part = a.scratch + (int64_t)b * nchunk * 2 * a.Cc + o;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int o = blockIdx.x * 64 + lane;            // index into [2][Cc]
+  __shared__ double red[4][64];
   double s = 0.0;
-  for (int ch = 0; ch < nchunk; ++ch) s += part[(int64_t)ch * 2 * a.Cc];
-  a.out[(int64_t)b * a.out_stride + o] = s;
+  if (o < 2 * a.Cc) {
+    const double* part = a.scratch + (int64_t)b * nchunk * 2 * a.Cc + o;
+    double t[4] = {0.0, 0.0, 0.0, 0.0};
+    int ch = wave;
+    for (; ch + 12 < nchunk; ch += 16) {           // 4 loads in flight
+#pragma unroll
+      for (int u = 0; u < 4; ++u) t[u] += part[(int64_t)(ch + 4 * u) * 2 * a.Cc];
+    }
+    for (; ch < nchunk; ch += 4) t[0] += part[(int64_t)ch * 2 * a.Cc];
+    s = (t[0] + t[1]) + (t[2] + t[3]);
+  }
+  red[wave][lane] = s;
+  __syncthreads();
+  if (wave == 0 && o < 2 * a.Cc)
+    a.out[(int64_t)b * a.out_stride + o] = (red[0][lane] + red[1][lane]) + (red[2][lane] + red[3][lane]);
 }
 
 // vector loads need 16-byte aligned rows
@@ -235,15 +249,21 @@ size_t coldot_scratch_doubles(int R, int Cc, int batch) {
 hipError_t launch_rowdot(const ScanArgs& a0, hipStream_t st) {
   ScanArgs a = a0;
   a.vec_ok = vec_ok(a0) ? 1 : 0;
-  dim3 grid((a.R + RD_RB - 1) / RD_RB, a.batch);
   const bool idx = a.w == nullptr;
+  const bool small = (int64_t)((a.R + 15) / 16) * a.batch < 1024;   // fewer than 4 workgroups per CU
+#define GECC_LAUNCH_ROWDOT(DT, IDX)                                                                  \
+  do {                                                                                              \
+    if (small) hipLaunchKernelGGL((rowdot_kernel<DT, IDX, 4>), dim3((a.R + 3) / 4, a.batch),          \
+                                  dim3(RD_THREADS), 0, st, a);                                        \
+    else       hipLaunchKernelGGL((rowdot_kernel<DT, IDX, 16>), dim3((a.R + 15) / 16, a.batch),       \
+                                  dim3(RD_THREADS), 0, st, a);                                        \
+  } while (0)
   if (a.dtype == GECC_BF16) {
-    if (idx) hipLaunchKernelGGL((rowdot_kernel<GECC_BF16, true>), grid, dim3(RD_THREADS), 0, st, a);
-    else     hipLaunchKernelGGL((rowdot_kernel<GECC_BF16, false>), grid, dim3(RD_THREADS), 0, st, a);
+    if (idx) GECC_LAUNCH_ROWDOT(GECC_BF16, true); else GECC_LAUNCH_ROWDOT(GECC_BF16, false);
   } else {
-    if (idx) hipLaunchKernelGGL((rowdot_kernel<GECC_F32, true>), grid, dim3(RD_THREADS), 0, st, a);
-    else     hipLaunchKernelGGL((rowdot_kernel<GECC_F32, false>), grid, dim3(RD_THREADS), 0, st, a);
+    if (idx) GECC_LAUNCH_ROWDOT(GECC_F32, true); else GECC_LAUNCH_ROWDOT(GECC_F32, false);
   }
+#undef GECC_LAUNCH_ROWDOT
   return hipGetLastError();
 }
 
@@ -263,7 +283,7 @@ hipError_t launch_coldot(const ScanArgs& a0, hipStream_t st) {
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  dim3 g2((2 * a.Cc + 255) / 256, a.batch);
+  dim3 g2((2 * a.Cc + 63) / 64, a.batch);
   hipLaunchKernelGGL(coldot_stage2, g2, dim3(256), 0, st, a, nchunk);
   return hipGetLastError();
 }
