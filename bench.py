@@ -21,18 +21,22 @@ if ROOT not in sys.path:
 PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}     # MI355X dense MFMA peaks
 HBM_PEAK_GBS = 8000.0
 
-# HBM traffic of the product kernel per launch (bytes), from rocprofv3 --pmc FETCH_SIZE /
-# WRITE_SIZE runs scaled by a copy kernel of known size; see profiles/.  None = not measured.
-TRAFFIC_BYTES = {}
+# Memory traffic of the product kernel per launch (bytes), from rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE runs, each scaled by what the same counter reads for a 1 GiB copy (factors 2.000 and
+# 1.000); profiles/bench_cfg4-fwd_hbm_traffic.txt.  Workloads not listed: not measured.
+TRAFFIC_BYTES = {"cfg4-fwd": 2.826e9 + 9.713e8}
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="cfg4-fwd")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--traffic-ref", action="store_true",
+                    help="also run one 1 GiB device copy (untimed): the known-size kernel that "
+                         "FETCH_SIZE / WRITE_SIZE counter runs are scaled by")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (--gpus 1); the path shards without "
@@ -64,6 +68,13 @@ def main():
     A_par, B_par, C_par = ctx.alloc_parities()
     rep = ctx.alloc_report()
     Cd = ctx.alloc_c()
+
+    if args.traffic_ref:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     def step():
         ctx.protected_gemm(dA, dB, Cd, A_par, B_par, C_par, rep)
@@ -146,13 +157,14 @@ def main():
                      "achieved": round(achieved, 3) if achieved else None, "peak": peak, "unit": "TFLOP/s",
                      "frac": round(achieved / peak, 4) if achieved else None,
                      "kernel_ms": round(g_ms, 4) if g_ms else None,
+                     "algorithmic_flops_per_launch": flops,
                      "traffic": TRAFFIC_BYTES.get(w.name)},
     }
 
     # ---- CPU baseline: the oracle as it stands, on a bounded sample of the same workload -----
     if not args.no_cpu_baseline:
         from oracle import grid_code as oc
-        rows = max(1, min(n, int(2.5e11 / (2.0 * k * m))))     # about 0.25 TFLOP of fp64 work
+        rows = max(1, min(n, int(6e12 / (2.0 * k * m))))       # up to about 6 TFLOP of fp64 work (10-20 s)
         A0 = (hA[0].T if w.trans_a else hA[0])[:rows]
         B0 = hB[0].T if w.trans_b else hB[0]
         tau = oc.Thresholds(w.tau.r1, w.tau.r2, w.tau.q1, w.tau.q2, w.tau.op, w.tau.rep)
@@ -166,8 +178,9 @@ def main():
             cores = os.cpu_count()
         out["cpu_baseline"] = {"value": round(2.0 * rows * k * m / dt / 1e12, 4), "unit": "TFLOP/s",
                                "cores": cores, "kind": "oracle",
-                               "sample": "oracle.protected_gemm (fp64 numpy) on the first %d of %d rows of A "
-                                         "times the full B, no faults, %.1f s" % (rows, n, dt),
+                               "sample": "oracle.protected_gemm (fp64 numpy: encode, product, syndromes, "
+                                         "decode) on the first %d of %d rows of A times the full B, "
+                                         "batch item 0, no faults, %.1f s" % (rows, n, dt),
                                "status": int(res.status)}
     print(json.dumps(out))
 
