@@ -43,6 +43,7 @@ constexpr int TILE_BYTES = BM * BK * 2;            // 16 KiB: one k-tile of one 
 constexpr int NSTAGE = 4;                          // k-tiles of one operand resident in LDS
 constexpr int REGION_BYTES = NSTAGE * TILE_BYTES;  // 64 KiB per operand
 constexpr int SMEM_BYTES = 2 * REGION_BYTES;       // 128 KiB
+constexpr int EPI_SMEM_BYTES = 4 * 2 * 128 * 33 * 4;  // 132 KiB: row-sum transpose of the epilogue
 constexpr int GROUP_M = 8;                         // tile rows per L2-sharing group
 constexpr unsigned OOB = 0x80000000u;              // voffset beyond any num_records: reads zero
 
@@ -371,86 +372,82 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
     }
   }
 
+  // One pass over the accumulators, one 32-row block at a time (keeps the live values few):
+  // C goes straight to memory (one store = 2 rows x 32 consecutive columns = two full lines),
+  // column sums build up in 8 registers, row sums go through LDS (per lane: its 4 columns,
+  // one per 32-wide block; the 32 lanes of a half wavefront are added after the pass).
+  const int tm128 = R0 >> 7, tn128 = C0 >> 7;
+  float cs[4] = {0.f, 0.f, 0.f, 0.f}, cw[4] = {0.f, 0.f, 0.f, 0.f};
+  float* red = reinterpret_cast<float*>(smem) + wave * (2 * 128 * 33);   // [kind][row][lane]
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int rl = i * 32 + (v >> 2) * 8 + lhi * 4 + (v & 3);   // row inside the sub-tile
+      const int row = R0 + rl;
+      float* crow = C + (int64_t)row * a.ldc + C0 + l32;
+      float rs = 0.f, rw = 0.f;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float x = acc[i][j][v];
+        if (row < a.n && C0 + j * 32 + l32 < a.m) crow[j * 32] = x;
+        if (EPI) {
+          cs[j] += x;
+          cw[j] = fmaf((float)(rl + 1), x, cw[j]);
+          rs += x;
+          rw = fmaf((float)(j * 32 + l32 + 1), x, rw);
+        }
+      }
+      if (EPI) {
+        red[rl * 33 + l32] = rs;
+        red[128 * 33 + rl * 33 + l32] = rw;
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  }
   if (EPI) {
-    const int tm128 = R0 >> 7, tn128 = C0 >> 7;
-    // column sums of the 128 x 128 sub-tile: plain and weighted by (local row + 1)
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      float cs = 0.f, cw = 0.f;
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const float x = acc[i][j][v];
-          cs += x;
-          cw = fmaf((float)(i * 32 + (v >> 2) * 8 + lhi * 4 + (v & 3) + 1), x, cw);
-        }
-      cs += __shfl_xor(cs, 32, 64);
-      cw += __shfl_xor(cw, 32, 64);
+      const float s = cs[j] + __shfl_xor(cs[j], 32, 64), w = cw[j] + __shfl_xor(cw[j], 32, 64);
       const int col = C0 + j * 32 + l32;
       if (lhi == 0 && col < a.m && R0 < a.n) {
         float2* cp = reinterpret_cast<float2*>(a.colpart + (((int64_t)b * a.ntm + tm128) * a.m + col) * 2);
-        *cp = make_float2(cs, cw);
+        *cp = make_float2(s, w);
       }
     }
-    // row sums: per lane over its 4 columns (one per 32-wide block), then across the 32 lanes
-    // of a half wavefront through LDS; plain first, then weighted by (local column + 1)
-    float* red = reinterpret_cast<float*>(smem) + wave * (128 * 33);
+    __syncthreads();
 #pragma unroll
-    for (int kind = 0; kind < 2; ++kind) {
-      __syncthreads();
+    for (int h = 0; h < 2; ++h) {
+      const int r = lane + 64 * h;
+      float s = 0.f, w = 0.f;
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          float s = 0.f;
-#pragma unroll
-          for (int j = 0; j < 4; ++j)
-            s = kind ? fmaf((float)(j * 32 + l32 + 1), acc[i][j][v], s) : s + acc[i][j][v];
-          red[(i * 32 + (v >> 2) * 8 + lhi * 4 + (v & 3)) * 33 + l32] = s;
-        }
-      __syncthreads();
-#pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        const int r = lane + 64 * h;
-        float s = 0.f;
-#pragma unroll
-        for (int c = 0; c < 32; ++c) s += red[r * 33 + c];
-        const int row = R0 + r;
-        if (row < a.n && C0 < a.m)
-          a.rowpart[(((int64_t)b * a.ntn + tn128) * a.n + row) * 2 + kind] = s;
+      for (int c = 0; c < 32; ++c) {
+        s += red[r * 33 + c];
+        w += red[128 * 33 + r * 33 + c];
+      }
+      const int row = R0 + r;
+      if (row < a.n && C0 < a.m) {
+        float2* rp = reinterpret_cast<float2*>(a.rowpart + (((int64_t)b * a.ntn + tn128) * a.n + row) * 2);
+        *rp = make_float2(s, w);
       }
     }
   }
-
-  // C, straight from the accumulators: one store covers 2 rows x 32 consecutive columns
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int row = R0 + i * 32 + (v >> 2) * 8 + lhi * 4 + (v & 3);
-      if (row < a.n) {
-        float* crow = C + (int64_t)row * a.ldc + C0 + l32;
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-          if (C0 + j * 32 + l32 < a.m) crow[j * 32] = acc[i][j][v];
-      }
-    }
 }
 
 template <bool KCA, bool KCB, bool EPI, bool FAULTS>
 hipError_t launch_one(const GemmArgs& a, hipStream_t st) {
   static bool configured = false;   // per instantiation
+  constexpr int lds_bytes = EPI && EPI_SMEM_BYTES > SMEM_BYTES ? EPI_SMEM_BYTES : SMEM_BYTES;
   auto kern = gemm_bf16_256<KCA, KCB, EPI, FAULTS>;
   if (!configured) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, SMEM_BYTES);
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
     if (e != hipSuccess) return e;
     configured = true;
   }
   const int ntm = (a.n + BM - 1) / BM, ntn = (a.m + BN - 1) / BN;
   dim3 grid(ntm * ntn, a.batch);
-  hipLaunchKernelGGL(kern, grid, dim3(THREADS), SMEM_BYTES, st, a);
+  hipLaunchKernelGGL(kern, grid, dim3(THREADS), lds_bytes, st, a);
   return hipGetLastError();
 }
 

@@ -279,10 +279,11 @@ __global__ __launch_bounds__(THREADS) void gemm_kernel(GemmArgs a) {
 }
 
 // -------------------------------------------------------------------------------------------
-// Stand-alone partial sums of a C that sits in HBM (same tiling and workspace layout).
-template <int BM, int BN>
+// Stand-alone partial sums of a C that sits in HBM (same 128 x 128 tiling and workspace layout
+// as the fused epilogues).  HBM-bound: every thread streams 16 rows x 4 columns with 16-byte
+// loads (two full 512-byte tile rows per wavefront instruction), keeps its row and column
+// partial sums in registers, and the workgroup combines them through LDS in a fixed order.
 __global__ __launch_bounds__(THREADS) void partials_kernel(PartialArgs a) {
-  constexpr int SLAB = 64;
   const int b = blockIdx.z;
   if (a.gate) {
     const int32_t g = *reinterpret_cast<const int32_t*>(reinterpret_cast<const char*>(a.gate) +
@@ -290,26 +291,64 @@ __global__ __launch_bounds__(THREADS) void partials_kernel(PartialArgs a) {
     if (g != a.gate_value) return;
   }
   const int tm = blockIdx.y, tn = blockIdx.x;
-  const int tile_r0 = tm * BM, tile_c0 = tn * BN;
+  const int tile_r0 = tm * 128, tile_c0 = tn * 128;
   const float* C = a.C + (int64_t)b * a.sc;
-  __shared__ __attribute__((aligned(16))) float Cs[SLAB][BN + CPAD];
-  float* rowpart_tile = a.rowpart + ((int64_t)b * a.ntn + tn) * a.n * 2;
   const int tid = threadIdx.x;
-  float cs = 0.f, cw = 0.f;
-  for (int slab = 0; slab < BM / SLAB; ++slab) {
-    __syncthreads();
-    for (int o = tid; o < SLAB * BN; o += THREADS) {
-      const int r = o / BN, c = o % BN;
-      const int gi = tile_r0 + slab * SLAB + r, gj = tile_c0 + c;
-      Cs[r][c] = (gi < a.n && gj < a.m) ? C[(int64_t)gi * a.ldc + gj] : 0.f;
+  const int cg = tid & 31, rg = tid >> 5;          // 32 column groups of 4, 8 row groups of 16
+  const int gj = tile_c0 + cg * 4;
+  const bool vec = (reinterpret_cast<uintptr_t>(C) % 16 == 0) && (a.ldc % 4 == 0) && gj + 4 <= a.m;
+  __shared__ float red_row[2][128][33];
+  __shared__ float red_col[2][8][128];
+  float cs[4] = {0.f, 0.f, 0.f, 0.f}, cw[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+  for (int r = 0; r < 16; ++r) {
+    const int rl = rg * 16 + r, gi = tile_r0 + rl;
+    float x[4] = {0.f, 0.f, 0.f, 0.f};
+    if (gi < a.n) {
+      const float* src = C + (int64_t)gi * a.ldc + gj;
+      if (vec) {
+        const float4 v = *reinterpret_cast<const float4*>(src);
+        x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
+      } else {
+        for (int e = 0; e < 4; ++e) if (gj + e < a.m) x[e] = src[e];
+      }
     }
-    __syncthreads();
-    slab_reduce<BN, SLAB>(Cs, slab * SLAB, tile_r0, tile_c0, a.n, a.m, rowpart_tile, cs, cw);
+    float rs = 0.f, rw = 0.f;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      cs[e] += x[e];
+      cw[e] = fmaf((float)(rl + 1), x[e], cw[e]);
+      rs += x[e];
+      rw = fmaf((float)(cg * 4 + e + 1), x[e], rw);
+    }
+    red_row[0][rl][cg] = rs;
+    red_row[1][rl][cg] = rw;
   }
-  if (tid < BN && tile_c0 + tid < a.m) {
-    float* cp = a.colpart + (((int64_t)b * a.ntm + tm) * a.m + tile_c0 + tid) * 2;
-    cp[0] = cs;
-    cp[1] = cw;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    red_col[0][rg][cg * 4 + e] = cs[e];
+    red_col[1][rg][cg * 4 + e] = cw[e];
+  }
+  __syncthreads();
+  if (tid < 128) {
+    float s = 0.f, w = 0.f;
+#pragma unroll
+    for (int c = 0; c < 32; ++c) { s += red_row[0][tid][c]; w += red_row[1][tid][c]; }
+    const int gi = tile_r0 + tid;
+    if (gi < a.n) {
+      float2* rp = reinterpret_cast<float2*>(a.rowpart + (((int64_t)b * a.ntn + tn) * a.n + gi) * 2);
+      *rp = make_float2(s, w);
+    }
+  } else {
+    const int c = tid - 128;
+    float s = 0.f, w = 0.f;
+#pragma unroll
+    for (int g = 0; g < 8; ++g) { s += red_col[0][g][c]; w += red_col[1][g][c]; }
+    const int gc = tile_c0 + c;
+    if (gc < a.m) {
+      float2* cp = reinterpret_cast<float2*>(a.colpart + (((int64_t)b * a.ntm + tm) * a.m + gc) * 2);
+      *cp = make_float2(s, w);
+    }
   }
 }
 
@@ -336,7 +375,7 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t st) {
 hipError_t launch_partials(const PartialArgs& a, hipStream_t st) {
   if (a.tile_m != 128 || a.tile_n != 128) return hipErrorInvalidValue;
   dim3 grid(a.ntn, a.ntm, a.batch);
-  hipLaunchKernelGGL((partials_kernel<128, 128>), grid, dim3(THREADS), 0, st, a);
+  hipLaunchKernelGGL(partials_kernel, grid, dim3(THREADS), 0, st, a);
   return hipGetLastError();
 }
 
