@@ -167,7 +167,7 @@ def main():
         rows = max(1, min(n, int(6e12 / (2.0 * k * m))))       # up to about 6 TFLOP of fp64 work (10-20 s)
         A0 = (hA[0].T if w.trans_a else hA[0])[:rows]
         B0 = hB[0].T if w.trans_b else hB[0]
-        tau = oc.Thresholds(w.tau.r1, w.tau.r2, w.tau.q1, w.tau.q2, w.tau.op, w.tau.rep)
+        tau = oc.Thresholds(w.tau.r1, w.tau.r2, w.tau.q1, w.tau.q2, w.tau.op, w.tau.rep, w.tau.rel)
         t0 = time.perf_counter()
         res = oc.protected_gemm(A0, B0, A0, B0, [], tau)
         dt = time.perf_counter() - t0

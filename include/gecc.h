@@ -82,6 +82,10 @@ typedef struct {
      lines such a repair touched are widened accordingly in the second pass of Section V
      (root-sum-square over a whole repaired line).  16 * 2^-24 suits fp32 accumulation. */
   double tau_rep;
+  /* relative rounding allowance of a syndrome value: when an estimate is verified, a syndrome y
+     (a difference of fp32 sums) is trusted to tau + tau_rel * |y|.  Detection uses tau alone.
+     2^-20 suits fp32 partial sums. */
+  double tau_rel;
 } gecc_params;
 
 /* one located error: `magnitude` is the additive offset that was removed */

@@ -50,6 +50,12 @@ the design notes of the repository):
     widens the thresholds of those lines by rep * sqrt(k) * |footprint|
     (root-sum-square over a whole repaired line).  With rep = 0 this is the
     plain second pass.
+  * a syndrome is a difference of sums of computed symbols, so in any
+    finite-precision product its own rounding error grows with its magnitude
+    (Section V: corrected symbols deviate "solely" by rounding); when an
+    estimate is verified, every syndrome y is therefore trusted to
+    tau + rel * |y| instead of tau.  Detection itself uses tau alone, and
+    rel = 0 gives the plain rule.
   * for s = t = 2 the 2x2 systems are first evaluated under the two sparse
     hypotheses "one error per flagged column" (a column with a single error
     is the s = 1 rule applied to that column); in exact arithmetic this
@@ -81,6 +87,7 @@ class Thresholds:
     q2: float
     op: float = 0.0       # operand audit: |parity difference| > op flags a line
     rep: float = 0.0      # relative rounding allowance for lines touched by an operand repair
+    rel: float = 0.0      # relative rounding allowance of a syndrome value (verification only)
 
 
 class LineThresholds:
@@ -93,6 +100,17 @@ class LineThresholds:
         self.r2 = tau.r2 + a[1]
         self.q1 = tau.q1 + a[2]
         self.q2 = tau.q2 + a[3]
+        self.rel = tau.rel
+
+    def trusted_to(self, r1, r2, q1, q2):
+        """Uncertainty of each syndrome value: threshold plus rel * |value|."""
+        u = LineThresholds.__new__(LineThresholds)
+        u.r1 = self.r1 + self.rel * np.abs(r1)
+        u.r2 = self.r2 + self.rel * np.abs(r2)
+        u.q1 = self.q1 + self.rel * np.abs(q1)
+        u.q2 = self.q2 + self.rel * np.abs(q2)
+        u.rel = self.rel
+        return u
 
 
 @dataclass
@@ -233,6 +251,7 @@ def d0_correct(r1, r2, q1, q2, Er, Et, tau):
     """
     s, t = len(Er), len(Et)
     assert 1 <= s <= 2 and 1 <= t <= 2
+    tau = tau.trusted_to(r1, r2, q1, q2)      # from here on: how far each syndrome value is trusted
 
     def accept(est):
         est = [e for e in est if abs(e[2]) > e[3]]       # drop insignificant parts

@@ -175,10 +175,12 @@ struct Synd {
   const double *r1, *r2, *q1, *q2;
   double b_r1, b_r2, b_q1, b_q2;            // thresholds of the four families
   const double *a_r1, *a_r2, *a_q1, *a_q2;  // per-line allowances (null: none)
-  __device__ double tr1(int i) const { return b_r1 + (a_r1 ? a_r1[i] : 0.0); }
-  __device__ double tr2(int i) const { return b_r2 + (a_r2 ? a_r2[i] : 0.0); }
-  __device__ double tq1(int j) const { return b_q1 + (a_q1 ? a_q1[j] : 0.0); }
-  __device__ double tq2(int j) const { return b_q2 + (a_q2 ? a_q2[j] : 0.0); }
+  double rel;                               // relative rounding allowance of a syndrome value
+  // how far each syndrome value is trusted when an estimate is verified
+  __device__ double tr1(int i) const { return b_r1 + (a_r1 ? a_r1[i] : 0.0) + rel * fabs(r1[i]); }
+  __device__ double tr2(int i) const { return b_r2 + (a_r2 ? a_r2[i] : 0.0) + rel * fabs(r2[i]); }
+  __device__ double tq1(int j) const { return b_q1 + (a_q1 ? a_q1[j] : 0.0) + rel * fabs(q1[j]); }
+  __device__ double tq2(int j) const { return b_q2 + (a_q2 ? a_q2[j] : 0.0) + rel * fabs(q2[j]); }
 };
 
 // every syndrome of a flagged line has to be explained by the estimate, within the thresholds
@@ -311,7 +313,8 @@ __global__ __launch_bounds__(256) void decode_c_kernel(DecodeArgs a, int final_p
       const double* sy = synd_of(a, b);
       const double* al = final_pass ? allow_of(a, b) : nullptr;
       Synd y{sy, sy + n, sy + 2 * n, sy + 2 * n + m, a.p.tau_r1, a.p.tau_r2, a.p.tau_q1, a.p.tau_q2,
-             al, al ? al + n : nullptr, al ? al + 2 * n : nullptr, al ? al + 2 * n + m : nullptr};
+             al, al ? al + n : nullptr, al ? al + 2 * n : nullptr, al ? al + 2 * n + m : nullptr,
+             a.p.tau_rel};
       Est tmp[4];
       const int k = d0_correct(tmp, Er, s, Et, t, y);
       if (k >= 0 && st->n_err + k <= GECC_MAX_ERR) {

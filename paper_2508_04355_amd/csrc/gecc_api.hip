@@ -170,7 +170,7 @@ int gecc_create(gecc_ctx** out, const gecc_params* p) {
       return GECC_ERR_ARG;
   }
   if (!(p->tau_r1 >= 0) || !(p->tau_r2 >= 0) || !(p->tau_q1 >= 0) || !(p->tau_q2 >= 0) ||
-      !(p->tau_op >= 0) || !(p->tau_rep >= 0))
+      !(p->tau_op >= 0) || !(p->tau_rep >= 0) || !(p->tau_rel >= 0))
     return GECC_ERR_ARG;
   if ((int64_t)p->n + p->m > (int64_t)1 << 30) return GECC_ERR_ARG;
   gecc_ctx* c = new (std::nothrow) gecc_ctx;

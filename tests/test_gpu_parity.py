@@ -214,6 +214,30 @@ def test_cfg3_trials(trial):
         assert g.reports[0].status == gecc.CORRECTED
 
 
+def test_cfg3_large_offsets_do_not_break_the_verification():
+    """Offsets of several hundred on |C| ~ 0.03: the fp32 partial sums of the flagged lines lose
+    absolute precision in proportion to the offset; the relative allowance of the verification
+    step has to absorb that, on both sides alike."""
+    w = configs.CFG3
+    rng = inputs.rng_for(3, 50)
+    faults = [inputs.Fault(MAT_C, 4000, 4090, 731.0), inputs.Fault(MAT_C, 17, 3, -402.5)]
+    A, B, A2, B2, cf, eff = _trial(rng, w.n, w.k, w.m, w.dtype, w.law_a, w.law_b, faults)
+    cfb = [(0,) + c for c in cf]
+    g = H.run_gpu(A, B, A2, B2, cfb, w.tau, w.dtype)
+    o = H.run_oracle(A, B, A2, B2, cfb, w.tau)
+    H.compare(g, o, 1e-5, tol_mag=1e-3, what="cfg3 large offsets")
+    assert g.reports[0].status == gecc.CORRECTED
+
+
+def test_campaign_rates_on_a_bf16_product():
+    """Detection / false-alarm / correction rates against the planted faults (no oracle)."""
+    from paper_2508_04355_amd import campaign
+    out = campaign.run("cfg3", 400)
+    assert out["false_alarm_rate"] == 0.0 and out["detection_rate"] == 1.0
+    assert all(v.get("miscorrected", 0) == 0 for v in out["by_class"].values())
+    assert out["exact_correction_rate"] >= 0.99
+
+
 # ---- configuration 5: 256 batched 512^3 fp32, exactly two errors each ------------------------
 def test_cfg5_batched_two_errors_each():
     w = configs.CFG5
