@@ -154,7 +154,9 @@ int gecc_multiply(gecc_ctx* ctx, const void* dev_A, const double* dev_A_par, con
                   const gecc_fault* dev_faults, int32_t n_faults, void* stream);
 
 /* S4 + S5, Section V step 1: the four syndrome families and the threshold tests.
-   fused = 1: use the partial sums gecc_multiply left in the workspace (C is not read);
+   fused = 1: use the partial sums the immediately preceding gecc_multiply left in the workspace
+              (C is not read; that call also reset the detection counters, so verify once per
+              multiply);
    fused = 0: scan dev_C (for a C modified after the product, or produced elsewhere).
    dev_report (out): batch entries; status = GECC_CLEAN or GECC_DETECTED, s, t,
    max_abs_synd filled. */

@@ -45,14 +45,16 @@ __device__ __forceinline__ int64_t b_index(const gecc_params& p, int b, int l, i
 }
 
 // -------------------------------------------------------------------------------------------
-__global__ void reset_state_kernel(DecodeArgs a) {
-  const int b = blockIdx.x * blockDim.x + threadIdx.x;
-  if (b >= a.p.batch) return;
-  DecodeState* s = state_of(a, b);
+__device__ void reset_state(DecodeState* s) {
   s->s_cnt = 0; s->t_cnt = 0;
   for (int f = 0; f < 4; ++f) s->maxbits[f] = 0ull;
   s->phase = PH_DONE;
-  s->a_cnt = 0; s->b_cnt = 0; s->n_err = 0;
+  s->n_err = 0;
+}
+__global__ void reset_state_kernel(DecodeArgs a) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= a.p.batch) return;
+  reset_state(state_of(a, b));
 }
 
 // partial sums -> syndromes (sum - parity, Section V step 1) -> flags
@@ -149,16 +151,19 @@ __global__ __launch_bounds__(64) void threshold_kernel(DecodeArgs a, int first) 
 }
 
 // first report after detection: CLEAN or DETECTED
-__global__ void summarize_kernel(DecodeArgs a) {
-  const int b = blockIdx.x * blockDim.x + threadIdx.x;
-  if (b >= a.p.batch) return;
-  DecodeState* st = state_of(a, b);
-  gecc_report* rep = a.report + b;
+__device__ int summarize(const DecodeState* st, gecc_report* rep) {
   rep->s = st->s_cnt;
   rep->t = st->t_cnt;
   rep->n_err = 0;
   for (int f = 0; f < 4; ++f) rep->max_abs_synd[f] = __longlong_as_double((long long)st->maxbits[f]);
-  rep->status = (st->s_cnt == 0 && st->t_cnt == 0) ? GECC_CLEAN : GECC_DETECTED;
+  const int status = (st->s_cnt == 0 && st->t_cnt == 0) ? GECC_CLEAN : GECC_DETECTED;
+  rep->status = status;
+  return status;
+}
+__global__ void summarize_kernel(DecodeArgs a) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= a.p.batch) return;
+  summarize(state_of(a, b), a.report + b);
 }
 
 // ---- Section V step 2 ------------------------------------------------------------------------
@@ -286,14 +291,25 @@ __device__ double block_dot(const DecodeArgs& a, int b, int i, int j, double* re
   return r;
 }
 
-// One workgroup per batch item.  final_pass = 0: right after detection; = 1: after the operand
-// audit and the residual syndrome pass.
-__global__ __launch_bounds__(256) void decode_c_kernel(DecodeArgs a, int final_pass) {
+// One workgroup per batch item.  final_pass = 0: right after detection (with_summary: this
+// kernel also writes the first report, saving the summary launch); = 1: after the operand audit
+// and the residual syndrome pass.
+__global__ __launch_bounds__(256) void decode_c_kernel(DecodeArgs a, int final_pass, int with_summary) {
   const int b = blockIdx.x;
   DecodeState* st = state_of(a, b);
   gecc_report* rep = a.report + b;
-  if (final_pass) { if (st->phase != PH_REVERIFY) return; }
-  else            { if (rep->status != GECC_DETECTED) return; }
+  if (final_pass) {
+    if (st->phase != PH_REVERIFY) return;
+  } else if (with_summary) {
+    // every thread derives the status from the counters (the report is written by thread 0 only)
+    if (st->s_cnt == 0 && st->t_cnt == 0) {
+      if (threadIdx.x == 0) summarize(st, rep);
+      return;
+    }
+    if (threadIdx.x == 0) summarize(st, rep);
+  } else {
+    if (rep->status != GECC_DETECTED) return;
+  }
 
   __shared__ Est fix[4];
   __shared__ int nfix;          // -1: the rule does not apply / failed
@@ -359,29 +375,19 @@ __global__ __launch_bounds__(256) void decode_c_kernel(DecodeArgs a, int final_p
 }
 
 // ---- operand audit -----------------------------------------------------------------------------
-// blockIdx.y: 0 = A (columns l of A), 1 = B (rows l of B).  A single wrong symbol of a line
-// shows as (u1, u2) = (e, (pos+1) e) in the difference of re-formed and stored parities.
-__global__ __launch_bounds__(256) void audit_diff_kernel(DecodeArgs a) {
-  const int b = blockIdx.z;
-  DecodeState* st = state_of(a, b);
-  if (st->phase != PH_AUDIT) return;
-  const int l = blockIdx.x * 256 + threadIdx.x;
-  if (l >= a.p.k) return;
-  const bool isA = blockIdx.y == 0;
-  const double* cur = (isA ? a.audit_a : a.audit_b) + (int64_t)b * 2 * a.p.k;
-  const double* ref = (isA ? a.A_par : a.B_par) + (int64_t)b * 2 * a.p.k;
-  const double u1 = cur[l] - ref[l], u2 = cur[a.p.k + l] - ref[a.p.k + l];
-  const double tau = a.p.tau_op;
-  if (!(fabs(u1) > tau || fabs(u2) > tau)) return;
+// A single wrong symbol of a line (column l of A, row l of B) shows as (u1, u2) = (e, (pos+1) e)
+// in the difference of re-formed and stored parities.
+__device__ AuditHit audit_line(const double* cur, const double* ref, int k, int l, int len, double tau,
+                               bool* hit) {
+  const double u1 = cur[l] - ref[l], u2 = cur[k + l] - ref[k + l];
   AuditHit h;
   h.line = l; h.pos = -1; h.e = u1;
-  if (fabs(u1) > tau) {
+  *hit = fabs(u1) > tau || fabs(u2) > tau;
+  if (*hit && fabs(u1) > tau) {
     const double rho = u2 / u1, w = rint(rho);
-    const int len = isA ? a.p.n : a.p.m;
     if (fabs(rho - w) < 0.25 && w >= 1.0 && w <= (double)len) h.pos = (int)w - 1;
   }
-  const int idx = atomicAdd(isA ? &st->a_cnt : &st->b_cnt, 1);
-  if (idx < GECC_MAX_ERR) (isA ? st->a_hits : st->b_hits)[idx] = h;
+  return h;
 }
 
 __device__ void sort_hits(AuditHit* h, int cnt) {
@@ -403,15 +409,31 @@ __global__ __launch_bounds__(256) void repair_kernel(DecodeArgs a) {
   DecodeState* st = state_of(a, b);
   if (st->phase != PH_AUDIT) return;
   gecc_report* rep = a.report + b;
-  __shared__ int ok;
+  __shared__ int ok, cnt_a, cnt_b;
   __shared__ AuditHit ha[GECC_MAX_ERR], hb[GECC_MAX_ERR];
   const int n = a.p.n, m = a.p.m, k = a.p.k;
-  const int na = st->a_cnt, nb = st->b_cnt;
+  if (threadIdx.x == 0) { cnt_a = 0; cnt_b = 0; }
+  __syncthreads();
+  {   // difference of the re-formed and the stored operand parities, line by line
+    const double* cur_a = a.audit_a + (int64_t)b * 2 * k;
+    const double* cur_b = a.audit_b + (int64_t)b * 2 * k;
+    const double* ref_a = a.A_par + (int64_t)b * 2 * k;
+    const double* ref_b = a.B_par + (int64_t)b * 2 * k;
+    for (int l = threadIdx.x; l < k; l += blockDim.x) {
+      bool hit;
+      AuditHit h = audit_line(cur_a, ref_a, k, l, n, a.p.tau_op, &hit);
+      if (hit) { const int idx = atomicAdd(&cnt_a, 1); if (idx < GECC_MAX_ERR) ha[idx] = h; }
+      h = audit_line(cur_b, ref_b, k, l, m, a.p.tau_op, &hit);
+      if (hit) { const int idx = atomicAdd(&cnt_b, 1); if (idx < GECC_MAX_ERR) hb[idx] = h; }
+    }
+  }
+  __syncthreads();
+  const int na = cnt_a, nb = cnt_b;
   if (threadIdx.x == 0) {
     ok = (na + nb > 0) && (na + nb <= GECC_MAX_ERR);
     if (ok) {
-      for (int x = 0; x < na; ++x) { ha[x] = st->a_hits[x]; if (ha[x].pos < 0) ok = 0; }
-      for (int x = 0; x < nb; ++x) { hb[x] = st->b_hits[x]; if (hb[x].pos < 0) ok = 0; }
+      for (int x = 0; x < na; ++x) if (ha[x].pos < 0) ok = 0;
+      for (int x = 0; x < nb; ++x) if (hb[x].pos < 0) ok = 0;
     }
     if (ok) { sort_hits(ha, na); sort_hits(hb, nb); }
   }
@@ -529,9 +551,11 @@ __global__ __launch_bounds__(256) void repair_kernel(DecodeArgs a) {
 }
 
 // global parity block P_g = A_P B_P (Section III), 2 x 2 per batch item
+// (also resets the decoder state of its batch item for the verification that follows)
 __global__ __launch_bounds__(256) void pg_kernel(const double* A_par, const double* B_par,
-                                                 double* C_par, int n, int k, int m) {
+                                                 double* C_par, int n, int k, int m, DecodeState* state) {
   const int b = blockIdx.x;
+  if (threadIdx.x == 0 && state) reset_state(state + b);
   const double* ap = A_par + (int64_t)b * 2 * k;
   const double* bp = B_par + (int64_t)b * 2 * k;
   double acc[4] = {0, 0, 0, 0};
@@ -561,20 +585,16 @@ hipError_t launch_reset_state(const DecodeArgs& a, hipStream_t st) {
 hipError_t launch_threshold(const DecodeArgs& a, int first, hipStream_t st) {
   dim3 grid((a.p.n + a.p.m + 63) / 64, a.p.batch);   // one wavefront per workgroup: spreads over all CUs
   hipLaunchKernelGGL(threshold_kernel, grid, dim3(64), 0, st, a, first);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess || !first) return e;
+  return hipGetLastError();
+}
+
+hipError_t launch_summarize(const DecodeArgs& a, hipStream_t st) {
   hipLaunchKernelGGL(summarize_kernel, dim3((a.p.batch + 63) / 64), dim3(64), 0, st, a);
   return hipGetLastError();
 }
 
-hipError_t launch_decode_c(const DecodeArgs& a, int final_pass, hipStream_t st) {
-  hipLaunchKernelGGL(decode_c_kernel, dim3(a.p.batch), dim3(256), 0, st, a, final_pass);
-  return hipGetLastError();
-}
-
-hipError_t launch_audit_diff(const DecodeArgs& a, hipStream_t st) {
-  dim3 grid((a.p.k + 255) / 256, 2, a.p.batch);
-  hipLaunchKernelGGL(audit_diff_kernel, grid, dim3(256), 0, st, a);
+hipError_t launch_decode_c(const DecodeArgs& a, int final_pass, int with_summary, hipStream_t st) {
+  hipLaunchKernelGGL(decode_c_kernel, dim3(a.p.batch), dim3(256), 0, st, a, final_pass, with_summary);
   return hipGetLastError();
 }
 
@@ -584,8 +604,8 @@ hipError_t launch_repair(const DecodeArgs& a, hipStream_t st) {
 }
 
 hipError_t launch_pg(const double* A_par, const double* B_par, double* C_par, int n, int k, int m,
-                     int batch, hipStream_t st) {
-  hipLaunchKernelGGL(pg_kernel, dim3(batch), dim3(256), 0, st, A_par, B_par, C_par, n, k, m);
+                     int batch, DecodeState* state, hipStream_t st) {
+  hipLaunchKernelGGL(pg_kernel, dim3(batch), dim3(256), 0, st, A_par, B_par, C_par, n, k, m, state);
   return hipGetLastError();
 }
 

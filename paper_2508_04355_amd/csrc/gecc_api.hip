@@ -281,7 +281,9 @@ int gecc_multiply(gecc_ctx* ctx, const void* dev_A, const double* dev_A_par, con
   if ((e = reduce_a_over_k(ctx, dev_A, dev_B_par, dev_C_par, rec, st)) != hipSuccess) return hip_rc(e);
   if ((e = reduce_b_over_k(ctx, dev_B, dev_A_par, dev_C_par + 2 * (size_t)p.n, rec, st)) != hipSuccess)
     return hip_rc(e);
-  if ((e = launch_pg(dev_A_par, dev_B_par, dev_C_par, p.n, p.k, p.m, p.batch, st)) != hipSuccess)
+  // P_g, and the decoder state is reset here for the fused verification that follows
+  if ((e = launch_pg(dev_A_par, dev_B_par, dev_C_par, p.n, p.k, p.m, p.batch,
+                     reinterpret_cast<DecodeState*>(ctx->ws + ctx->lay.state), st)) != hipSuccess)
     return hip_rc(e);
   GemmArgs g = gemm_args(ctx, dev_A, dev_B, dev_C);
   g.rowpart = reinterpret_cast<float*>(ctx->ws + ctx->lay.rowpart);
@@ -291,17 +293,17 @@ int gecc_multiply(gecc_ctx* ctx, const void* dev_A, const double* dev_A_par, con
   return hip_rc(timed_gemm(ctx, g, st));
 }
 
-int gecc_verify(gecc_ctx* ctx, const float* dev_C, const double* dev_C_par, gecc_report* dev_report,
-                int32_t fused, void* stream) {
-  int rc = check_ws(ctx);
-  if (rc) return rc;
-  if (!dev_C_par || !dev_report || (!fused && !dev_C)) return GECC_ERR_ARG;
-  hipStream_t st = (hipStream_t)stream;
+namespace {
+
+// S4 + S5.  summary = 0 leaves the first report to the decoder's first pass (saves a launch).
+int verify_impl(gecc_ctx* ctx, const float* dev_C, const double* dev_C_par, gecc_report* dev_report,
+                int32_t fused, int summary, hipStream_t st) {
   DecodeArgs d = decode_args(ctx, nullptr, nullptr, nullptr, nullptr, const_cast<float*>(dev_C),
                              const_cast<double*>(dev_C_par), dev_report);
   hipError_t e;
-  if ((e = launch_reset_state(d, st)) != hipSuccess) return hip_rc(e);
   if (!fused) {
+    // (the fused path had its state reset by gecc_multiply)
+    if ((e = launch_reset_state(d, st)) != hipSuccess) return hip_rc(e);
     const gecc_params& p = ctx->p;
     PartialArgs pa{};
     pa.C = dev_C; pa.n = p.n; pa.m = p.m; pa.batch = p.batch; pa.ldc = p.ldc; pa.sc = p.stride_c;
@@ -310,29 +312,24 @@ int gecc_verify(gecc_ctx* ctx, const float* dev_C, const double* dev_C_par, gecc
     pa.gate = nullptr;
     if ((e = launch_partials(pa, st)) != hipSuccess) return hip_rc(e);
   }
-  return hip_rc(launch_threshold(d, 1, st));
+  if ((e = launch_threshold(d, 1, st)) != hipSuccess) return hip_rc(e);
+  return summary ? hip_rc(launch_summarize(d, st)) : GECC_OK;
 }
 
-int gecc_correct(gecc_ctx* ctx, void* dev_A, const double* dev_A_par, void* dev_B,
-                 const double* dev_B_par, float* dev_C, double* dev_C_par, gecc_report* dev_report,
-                 void* stream) {
-  int rc = check_ws(ctx);
-  if (rc) return rc;
-  if (!dev_A || !dev_A_par || !dev_B || !dev_B_par || !dev_C || !dev_C_par || !dev_report)
-    return GECC_ERR_ARG;
-  hipStream_t st = (hipStream_t)stream;
+// S6 + S7.  with_summary = 1: the first decoder pass also writes the first report.
+int correct_impl(gecc_ctx* ctx, void* dev_A, const double* dev_A_par, void* dev_B, const double* dev_B_par,
+                 float* dev_C, double* dev_C_par, gecc_report* dev_report, int with_summary, hipStream_t st) {
   const gecc_params& p = ctx->p;
   DecodeArgs d = decode_args(ctx, dev_A, dev_A_par, dev_B, dev_B_par, dev_C, dev_C_par, dev_report);
   const int32_t* gate = &d.state->phase;
   hipError_t e;
   // Section V step 2 on the flagged lines; on failure the phase becomes PH_AUDIT
-  if ((e = launch_decode_c(d, 0, st)) != hipSuccess) return hip_rc(e);
+  if ((e = launch_decode_c(d, 0, with_summary, st)) != hipSuccess) return hip_rc(e);
   // operand audit: re-form the parities of A and B as the product read them
   if ((e = reduce_a_over_n(ctx, dev_A, nullptr, const_cast<double*>(d.audit_a), gate, st)) != hipSuccess)
     return hip_rc(e);
   if ((e = reduce_b_over_m(ctx, dev_B, nullptr, const_cast<double*>(d.audit_b), gate, st)) != hipSuccess)
     return hip_rc(e);
-  if ((e = launch_audit_diff(d, st)) != hipSuccess) return hip_rc(e);
   if ((e = launch_repair(d, st)) != hipSuccess) return hip_rc(e);
   // residual syndromes of the repaired C-bar, then Section V once more
   PartialArgs pa{};
@@ -342,18 +339,41 @@ int gecc_correct(gecc_ctx* ctx, void* dev_A, const double* dev_A_par, void* dev_
   pa.gate = gate; pa.gate_stride = sizeof(DecodeState); pa.gate_value = PH_REVERIFY;
   if ((e = launch_partials(pa, st)) != hipSuccess) return hip_rc(e);
   if ((e = launch_threshold(d, 0, st)) != hipSuccess) return hip_rc(e);
-  return hip_rc(launch_decode_c(d, 1, st));
+  return hip_rc(launch_decode_c(d, 1, 0, st));
+}
+
+}  // namespace
+
+int gecc_verify(gecc_ctx* ctx, const float* dev_C, const double* dev_C_par, gecc_report* dev_report,
+                int32_t fused, void* stream) {
+  int rc = check_ws(ctx);
+  if (rc) return rc;
+  if (!dev_C_par || !dev_report || (!fused && !dev_C)) return GECC_ERR_ARG;
+  return verify_impl(ctx, dev_C, dev_C_par, dev_report, fused, 1, (hipStream_t)stream);
+}
+
+int gecc_correct(gecc_ctx* ctx, void* dev_A, const double* dev_A_par, void* dev_B,
+                 const double* dev_B_par, float* dev_C, double* dev_C_par, gecc_report* dev_report,
+                 void* stream) {
+  int rc = check_ws(ctx);
+  if (rc) return rc;
+  if (!dev_A || !dev_A_par || !dev_B || !dev_B_par || !dev_C || !dev_C_par || !dev_report)
+    return GECC_ERR_ARG;
+  return correct_impl(ctx, dev_A, dev_A_par, dev_B, dev_B_par, dev_C, dev_C_par, dev_report, 0,
+                      (hipStream_t)stream);
 }
 
 int gecc_protected_gemm(gecc_ctx* ctx, void* dev_A, void* dev_B, float* dev_C, double* dev_A_par,
                         double* dev_B_par, double* dev_C_par, gecc_report* dev_report, void* stream) {
   int rc;
+  if (!dev_report) return GECC_ERR_ARG;
   if ((rc = gecc_encode_a(ctx, dev_A, dev_A_par, stream))) return rc;
   if ((rc = gecc_encode_b(ctx, dev_B, dev_B_par, stream))) return rc;
   if ((rc = gecc_multiply(ctx, dev_A, dev_A_par, dev_B, dev_B_par, dev_C, dev_C_par, nullptr, 0, stream)))
     return rc;
-  if ((rc = gecc_verify(ctx, dev_C, dev_C_par, dev_report, 1, stream))) return rc;
-  return gecc_correct(ctx, dev_A, dev_A_par, dev_B, dev_B_par, dev_C, dev_C_par, dev_report, stream);
+  if ((rc = verify_impl(ctx, dev_C, dev_C_par, dev_report, 1, 0, (hipStream_t)stream))) return rc;
+  return correct_impl(ctx, dev_A, dev_A_par, dev_B, dev_B_par, dev_C, dev_C_par, dev_report, 1,
+                      (hipStream_t)stream);
 }
 
 int gecc_plain_gemm(gecc_ctx* ctx, const void* dev_A, const void* dev_B, float* dev_C, void* stream) {

@@ -29,9 +29,7 @@ struct DecodeState {
   unsigned long long maxbits[4];
   // decoder
   int32_t phase;
-  int32_t a_cnt, b_cnt;       // audit hits (atomics)
   int32_t n_err;              // operand errors already accepted by the audit
-  AuditHit a_hits[GECC_MAX_ERR], b_hits[GECC_MAX_ERR];
   gecc_err errs[GECC_MAX_ERR];
 };
 
@@ -141,14 +139,17 @@ struct DecodeArgs {
   gecc_report* report;
 };
 hipError_t launch_reset_state(const DecodeArgs& a, hipStream_t st);
-// partial sums -> syndromes -> threshold flags.  first = 1: also fills max_abs_synd and the
-// report's s, t, status (CLEAN / DETECTED); first = 0: residual pass of the decoder, gated
-// on phase == PH_REVERIFY.
+// partial sums -> syndromes -> threshold flags.  first = 1: also collects max |syndrome| per
+// family; first = 0: residual pass of the decoder, gated on phase == PH_REVERIFY.
 hipError_t launch_threshold(const DecodeArgs& a, int first, hipStream_t st);
-hipError_t launch_decode_c(const DecodeArgs& a, int final_pass, hipStream_t st);
-hipError_t launch_audit_diff(const DecodeArgs& a, hipStream_t st);
+// first report (s, t, maxima, CLEAN / DETECTED) from the counters of the first threshold pass
+hipError_t launch_summarize(const DecodeArgs& a, hipStream_t st);
+// Section V step 2.  with_summary = 1 (first pass only): also writes the first report
+hipError_t launch_decode_c(const DecodeArgs& a, int final_pass, int with_summary, hipStream_t st);
+// audit differences, operand patches, rank-one repair of C-bar
 hipError_t launch_repair(const DecodeArgs& a, hipStream_t st);
+// P_g = A_P B_P; state != null: also resets the decoder state (counters, phase) of every item
 hipError_t launch_pg(const double* A_par, const double* B_par, double* C_par, int n, int k, int m,
-                     int batch, hipStream_t st);
+                     int batch, DecodeState* state, hipStream_t st);
 
 }  // namespace gecc
