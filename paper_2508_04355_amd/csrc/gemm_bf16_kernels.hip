@@ -372,12 +372,77 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
     }
   }
 
-  // One pass over the accumulators, one 32-row block at a time (keeps the live values few):
-  // C goes straight to memory (one store = 2 rows x 32 consecutive columns = two full lines),
-  // column sums build up in 8 registers, row sums go through LDS (per lane: its 4 columns,
-  // one per 32-wide block; the 32 lanes of a half wavefront are added after the pass).
   const int tm128 = R0 >> 7, tn128 = C0 >> 7;
   float cs[4] = {0.f, 0.f, 0.f, 0.f}, cw[4] = {0.f, 0.f, 0.f, 0.f};
+  // wave-uniform copies of the sub-tile origin (scalar registers: row addresses stay scalar)
+  const int R0u = tile_r0 + (wave_u >> 1) * 128, C0u = tile_c0 + (wave_u & 1) * 128;
+  const bool interior = R0u + 128 <= a.n && C0u + 128 <= a.m;
+  if (interior) {
+    // Sub-tile fully inside C: no predicates.  One pass over the accumulators: C goes straight
+    // to memory (one store = 2 rows x 32 consecutive columns = two full lines; scalar row base,
+    // one lane offset for all stores); the column sums build up in 8 registers with the
+    // lane-independent part of the row weight (the lane part, 4 lhi, is added at the end); of
+    // every row the lane keeps the sum of its 4 columns (one per 32-wide block) and
+    // u = x1 + 2 x2 + 3 x3, the block part of the column weight -- both go through LDS, where
+    // the 32 lanes of a half wavefront are added and the lane part of the weight is applied.
+    const char* cbase = reinterpret_cast<const char*>(C + (int64_t)R0u * a.ldc + C0u);
+    // byte offset of the lane inside a row group; fits 32 bits (ldc < 2^27, checked by the launcher)
+    const unsigned lane_off = ((unsigned)(lhi * 4) * (unsigned)a.ldc + (unsigned)l32) * 4u;
+    float2* red2 = reinterpret_cast<float2*>(smem) + wave_u * (128 * 33) + (lhi * 4) * 33 + l32;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int ru = i * 32 + (v >> 2) * 8 + (v & 3);   // row inside the sub-tile, without 4 lhi
+        float* crow = reinterpret_cast<float*>(const_cast<char*>(cbase + (int64_t)ru * a.ldc * 4 + lane_off));
+        const float x0 = acc[i][0][v], x1 = acc[i][1][v], x2 = acc[i][2][v], x3 = acc[i][3][v];
+        crow[0] = x0;
+        crow[32] = x1;
+        crow[64] = x2;
+        crow[96] = x3;
+        if (EPI) {
+          const float t2 = x2 + x3, t1 = x1 + t2;
+          red2[ru * 33] = make_float2(x0 + t1, (t1 + t2) + x3);
+          const float wr_ = (float)(ru + 1);
+          cs[0] += x0; cw[0] = fmaf(x0, wr_, cw[0]);
+          cs[1] += x1; cw[1] = fmaf(x1, wr_, cw[1]);
+          cs[2] += x2; cw[2] = fmaf(x2, wr_, cw[2]);
+          cs[3] += x3; cw[3] = fmaf(x3, wr_, cw[3]);
+        }
+      }
+    }
+    if (EPI) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float w1 = fmaf((float)(lhi * 4), cs[j], cw[j]);
+        const float s = cs[j] + __shfl_xor(cs[j], 32, 64), w = w1 + __shfl_xor(w1, 32, 64);
+        if (lhi == 0) {
+          float2* cp = reinterpret_cast<float2*>(a.colpart + (((int64_t)b * a.ntm + tm128) * a.m + C0 + j * 32 + l32) * 2);
+          *cp = make_float2(s, w);
+        }
+      }
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the region is this wavefront's own
+      const float2* mine = reinterpret_cast<const float2*>(smem) + wave_u * (128 * 33);
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const int r = lane + 64 * h;
+        float s = 0.f, w = 0.f, u = 0.f;
+#pragma unroll
+        for (int c = 0; c < 32; ++c) {
+          const float2 t = mine[r * 33 + c];
+          s += t.x;
+          w = fmaf((float)(c + 1), t.x, w);
+          u += t.y;
+        }
+        float2* rp = reinterpret_cast<float2*>(a.rowpart + (((int64_t)b * a.ntn + tn128) * a.n + R0 + r) * 2);
+        *rp = make_float2(s, fmaf(32.f, u, w));
+      }
+    }
+    return;
+  }
+
+  // Sub-tile on the edge of C: the same pass with every store predicated, full weights per
+  // element and one LDS array per kind.
   float* red = reinterpret_cast<float*>(smem) + wave * (2 * 128 * 33);   // [kind][row][lane]
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
@@ -403,7 +468,6 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
         red[128 * 33 + rl * 33 + l32] = rw;
       }
     }
-    __builtin_amdgcn_sched_barrier(0);
   }
   if (EPI) {
 #pragma unroll
@@ -415,7 +479,7 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
         *cp = make_float2(s, w);
       }
     }
-    __syncthreads();
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the region is this wavefront's own
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       const int r = lane + 64 * h;
@@ -476,7 +540,7 @@ bool gemm_bf16_fast_ok(const GemmArgs& a) {
   // byte offsets inside a tile panel (k-contiguous: 256 rows; otherwise the whole k extent)
   const int64_t span_a = (a.trans_a ? (int64_t)a.k : (int64_t)BM) * a.lda * 2;
   const int64_t span_b = (a.trans_b ? (int64_t)BN : (int64_t)a.k) * a.ldb * 2;
-  if (span_a >= 0x7fffffff || span_b >= 0x7fffffff) return false;
+  if (span_a >= 0x7fffffff || span_b >= 0x7fffffff || a.ldc >= (1 << 27)) return false;
   return (int64_t)a.n * a.m >= (int64_t)BM * BN;   // smaller problems: the 128 x 128 kernel
 }
 
