@@ -21,9 +21,15 @@
 //     by the transposing LDS read (two ds_read_b64_tr_b16 per fragment: 16 lanes fetch 4
 //     k-rows x 16 columns and each lane receives the 4 k-values of its own column).
 //
-// Epilogue, from the accumulators (C itself never passes through LDS): per sub-tile column
-// sums (in-lane) and row sums (through a small LDS transpose) for Section V's syndromes, then
-// C.  A second instantiation additionally plants test faults into the accumulators first.
+// Epilogue, from the accumulators (C itself never passes through LDS): one branch-free pass that
+// stores C through a range-checked raw buffer (rows and columns outside C are dropped by the
+// hardware) and forms, per 128 x 128 sub-tile, the column sums (in-lane) and row sums (through
+// a small LDS transpose) for Section V's syndromes.  A second instantiation additionally plants
+// test faults into the accumulators first.
+//
+// Every tile walks k cyclically from its own start (a few k-tiles apart for neighbouring
+// tiles), so that the compute units sharing an operand panel do not ask L2 for the same line
+// in the same cycle: the first one misses, the others hit.
 #include <type_traits>
 #include "gecc_internal.h"
 
@@ -44,6 +50,10 @@ constexpr int NSTAGE = 4;                          // k-tiles of one operand res
 constexpr int REGION_BYTES = NSTAGE * TILE_BYTES;  // 64 KiB per operand
 constexpr int SMEM_BYTES = 2 * REGION_BYTES;       // 128 KiB
 constexpr int EPI_SMEM_BYTES = 4 * 2 * 128 * 33 * 4;  // 132 KiB: row-sum transpose of the epilogue
+// DMA spread (see the schedule in the kernel): instructions of a pair in its first two halves,
+// instructions of a single k-tile in its first half
+constexpr int PA = 3, PB = 3, MX = 0;
+constexpr int SKEW_M = 1, SKEW_N = 1;              // k start offset (pairs of k-tiles) per tile row / column
 constexpr int GROUP_M = 8;                         // tile rows per L2-sharing group
 constexpr unsigned OOB = 0x80000000u;              // voffset beyond any num_records: reads zero
 
@@ -126,14 +136,16 @@ struct Operand {
     return KC ? ((kt >> 1) & 1) * (2 * TILE_BYTES) : (kt & (NSTAGE - 1)) * TILE_BYTES;
   }
 
-  // DMA instruction i (0 .. NV-1) of this wavefront for the unit (pair or k-tile) number `unit`
-  __device__ __forceinline__ void issue_one(unsigned lds_region, int wave_u, int unit, int i) const {
+  // DMA instruction i (0 .. NV-1) of this wavefront: unit (pair or k-tile) number `src` into the
+  // slot that unit number `unit` owns
+  __device__ __forceinline__ void issue_one(unsigned lds_region, int wave_u, int unit, int src, int i) const {
     const unsigned slot = KC ? (unit & 1) * (2 * TILE_BYTES) : (unit & (NSTAGE - 1)) * TILE_BYTES;
-    dma16(lds_region + slot + (wave_u * NV + i) * 1024, voff[i], rsrc, unit * sstep);
+    dma16(lds_region + slot + (wave_u * NV + i) * 1024, voff[i], rsrc, src * sstep);
   }
-  __device__ __forceinline__ void issue_unit(unsigned lds_region, int wave_u, int unit) const {
+  __device__ __forceinline__ void issue_range(unsigned lds_region, int wave_u, int unit, int src, int first, int count) const {
 #pragma unroll
-    for (int i = 0; i < NV; ++i) issue_one(lds_region, wave_u, unit, i);
+    for (int i = 0; i < NV; ++i)
+      if (i >= first && i < first + count) issue_one(lds_region, wave_u, unit, src, i);
   }
 
   // fragment i of the ks-th 16 k of k-tile kt; region = this operand's LDS region
@@ -151,42 +163,11 @@ struct Operand {
   }
 };
 
-// s_waitcnt vmcnt(n) for the multiples of 4 the DMA bookkeeping below can ask for
-__device__ __forceinline__ void wait_vm(int n) {
-  switch (n >> 2) {
-    case 0: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
-    case 1: asm volatile("s_waitcnt vmcnt(4)" ::: "memory"); break;
-    case 2: asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); break;
-    case 3: asm volatile("s_waitcnt vmcnt(12)" ::: "memory"); break;
-    case 4: asm volatile("s_waitcnt vmcnt(16)" ::: "memory"); break;
-    case 5: asm volatile("s_waitcnt vmcnt(20)" ::: "memory"); break;
-    case 6: asm volatile("s_waitcnt vmcnt(24)" ::: "memory"); break;
-    case 7: asm volatile("s_waitcnt vmcnt(28)" ::: "memory"); break;
-    default: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
-  }
-}
-
-// Scheduling hint for one quarter (4 MFMAs) of a half k-tile: the NDS LDS reads issued in that
-// quarter are placed one or two at a time behind the MFMAs instead of in front of them.
-template <int NDS>
-__device__ __forceinline__ void hint_quarter() {
-#pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                       // one MFMA
-    if (r == 0 && (NDS + 3) / 4 > 0) __builtin_amdgcn_sched_group_barrier(0x100, (NDS + 3) / 4, 0);
-    if (r == 1 && (NDS + 2) / 4 > 0) __builtin_amdgcn_sched_group_barrier(0x100, (NDS + 2) / 4, 0);
-    if (r == 2 && (NDS + 1) / 4 > 0) __builtin_amdgcn_sched_group_barrier(0x100, (NDS + 1) / 4, 0);
-    if (r == 3 && NDS / 4 > 0)       __builtin_amdgcn_sched_group_barrier(0x100, NDS / 4, 0);
-  }
-}
-// reads per quarter: B fragments 0-2 | B fragment 3 and A fragments 0-1 | A fragments 2-3 | none
-template <bool KCA, bool KCB>
-__device__ __forceinline__ void interleave(int quarter, bool reads) {
-  constexpr int NA = KCA ? 1 : 2, NB = KCB ? 1 : 2;   // LDS instructions per fragment
-  if (!reads || quarter == 3) hint_quarter<0>();
-  else if (quarter == 0)      hint_quarter<3 * NB>();
-  else if (quarter == 1)      hint_quarter<NB + 2 * NA>();
-  else                        hint_quarter<2 * NA>();
+// s_waitcnt vmcnt(N), N a compile-time constant below 64
+template <int N>
+__device__ __forceinline__ void wait_vm() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+  asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
 }
 
 template <bool KCA, bool KCB, bool EPI, bool FAULTS>
@@ -241,40 +222,79 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
   const int KT = a.k / BK;                           // even: k % 64 == 0 (checked by the launcher)
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);
 
-  // DMA bookkeeping.  A "unit" is what one slot holds: a pair of k-tiles for a k-contiguous
-  // operand (nK of them), one k-tile otherwise (nM of them).  Issue order per wavefront:
-  //   prologue:      pair 0 | k-tiles 0 1 2 3 | pair 1
-  //   iteration kt:  after its barrier, k-tile kt+4 (4 nM instructions), then, if kt is odd,
-  //                  pair (kt+3)/2 (8 nK instructions) -- into the slots k-tile kt just left
-  // The memory counter retires in order, so "k-tile kt+1 has landed" (needed at the barrier of
-  // iteration kt) means: at most the instructions issued after its unit are still pending,
-  //   kt even: those of iterations kt-2 and kt-1;  kt odd: those of iteration kt-1
-  // (with no k-contiguous operand the first rule holds for every kt).
+  // ---- DMA schedule ---------------------------------------------------------------------------
+  // A "unit" is what one LDS slot holds: a pair of k-tiles for a k-contiguous operand (nK of
+  // them, 8 instructions per wavefront and unit), one k-tile otherwise (nM of them, 4
+  // instructions).  An iteration (one k-tile) has two halves of 16 MFMAs with the workgroup
+  // barrier between them; that barrier releases the slot of k-tile kt (and of its pair when kt
+  // is odd) and is where k-tile kt+1 must have landed.  The loads are spread over the halves so
+  // that L2 sees a steady stream instead of bursts (the achieved L2 latency, which bounds the
+  // per-CU bandwidth through the L1 miss capacity, depends on it):
+  //   pair q+2:      PA instructions in the 2nd half of k-tile 2q+1, PB in the 1st half of
+  //                  2q+2, the rest in the 2nd half of 2q+2         (needed at barrier 2q+3)
+  //   k-tile kt+4:   MX instructions in the 2nd half of kt, the rest in the 1st half of kt+1
+  // Inside a half the k-contiguous operands go first.  The memory counter retires in order, so
+  // "k-tile kt+1 has landed" becomes "at most W instructions are pending", W = what the
+  // schedule issues after the last instruction of that k-tile's units:
+  //   kt even: (PA + PB) nK + 8 nM        kt odd: 4 nM  (8 nM without a k-contiguous operand)
+  // Units past the end of k are clamped to the last one (a harmless reload into a free slot),
+  // which keeps every iteration identical.
   constexpr int nK = (KCA ? 1 : 0) + (KCB ? 1 : 0), nM = 2 - nK;
-  auto issued_in = [&](int j) {   // DMA instructions of this wavefront in iteration j
-    return (j >= 0 && j + NSTAGE < KT ? 4 * nM : 0) + (j >= 0 && (j & 1) && j + 3 < KT ? 8 * nK : 0);
-  };
-  if (KCA) oa.issue_unit(ldsA, wave_u, 0);
-  if (KCB) ob.issue_unit(ldsB, wave_u, 0);
+  constexpr int PC = 8 - PA - PB;
+  constexpr int W_EVEN = (PA + PB) * nK + 8 * nM, W_ODD = nK > 0 ? 4 * nM : 8 * nM;
+  const int NP = KT / 2;
+  // k order of this tile: cyclic, starting at pair p0 (see SKEW_M, SKEW_N)
+  const int p0 = __builtin_amdgcn_readfirstlane(((tm & 7) * SKEW_M + (tn & 3) * SKEW_N) % NP);
+  auto src_pair = [&](int pair) { int x = pair + p0; x -= x >= NP ? NP : 0; x -= x >= NP ? NP : 0; return x; };
+  auto src_kt = [&](int t) { int x = t + 2 * p0; x -= x >= KT ? KT : 0; x -= x >= KT ? KT : 0; return x; };
+
+  // DMA instructions of half PH (0: 1st of even kt, 1: 2nd of even, 2: 1st of odd, 3: 2nd of odd)
+  // that belong behind MFMA number `step` of the half
+  auto dma_ops = [&](auto ph_c, const int step, const int kt) {
+    constexpr int PH = decltype(ph_c)::value;
+    constexpr int k_cnt = PH == 3 ? PA : PH == 0 ? PB : PH == 1 ? PC : 0;       // per operand
+    constexpr int k_first = PH == 3 ? 0 : PH == 0 ? PA : PA + PB;
+    constexpr int m_cnt = (PH & 1) ? MX : 4 - MX;
+    constexpr int m_first = (PH & 1) ? 0 : MX;
+    constexpr int issued = k_cnt * nK + m_cnt * nM, total = issued > 0 ? issued : 1;
+    const int pair = PH == 3 ? (kt + 3) >> 1 : (kt + 2) >> 1;   // slot (and source, clamped)
+    const int mt = (PH & 1) ? kt + 4 : kt + 3;
+    int r = 0;
 #pragma unroll
-  for (int s = 0; s < NSTAGE; ++s)
-    if (s < KT) {
-      if (!KCA) oa.issue_unit(ldsA, wave_u, s);
-      if (!KCB) ob.issue_unit(ldsB, wave_u, s);
+    for (int x = 0; x < k_cnt; ++x) {
+      if (KCA) { if (step == (r * 16) / total) oa.issue_one(ldsA, wave_u, pair, src_pair(pair), k_first + x); ++r; }
+      if (KCB) { if (step == (r * 16) / total) ob.issue_one(ldsB, wave_u, pair, src_pair(pair), k_first + x); ++r; }
     }
-  if (2 < KT) {
-    if (KCA) oa.issue_unit(ldsA, wave_u, 1);
-    if (KCB) ob.issue_unit(ldsB, wave_u, 1);
-  }
-  // k-tile 0: everything after pair 0 and k-tile 0 may still be pending
-  wait_vm(4 * nM * (min(NSTAGE, KT) - 1) + (2 < KT ? 8 * nK : 0));
+#pragma unroll
+    for (int x = 0; x < m_cnt; ++x) {
+      if (!KCA) { if (step == (r * 16) / total) oa.issue_one(ldsA, wave_u, mt, src_kt(mt), m_first + x); ++r; }
+      if (!KCB) { if (step == (r * 16) / total) ob.issue_one(ldsB, wave_u, mt, src_kt(mt), m_first + x); ++r; }
+    }
+  };
+
+  // prologue, in the order the waits assume: pair 0, k-tile 0 | k-tile 1 | start of pair 1,
+  // k-tile 2, start of k-tile 3
+  if (KCA) oa.issue_range(ldsA, wave_u, 0, src_pair(0), 0, 8);
+  if (KCB) ob.issue_range(ldsB, wave_u, 0, src_pair(0), 0, 8);
+  if (!KCA) oa.issue_range(ldsA, wave_u, 0, src_kt(0), 0, 4);
+  if (!KCB) ob.issue_range(ldsB, wave_u, 0, src_kt(0), 0, 4);
+  if (!KCA) oa.issue_range(ldsA, wave_u, 1, src_kt(1), 0, 4);
+  if (!KCB) ob.issue_range(ldsB, wave_u, 1, src_kt(1), 0, 4);
+  if (KCA) oa.issue_range(ldsA, wave_u, 1, src_pair(1), 0, PA);
+  if (KCB) ob.issue_range(ldsB, wave_u, 1, src_pair(1), 0, PA);
+  if (!KCA) oa.issue_range(ldsA, wave_u, 2, src_kt(2), 0, 4);
+  if (!KCB) ob.issue_range(ldsB, wave_u, 2, src_kt(2), 0, 4);
+  if (!KCA) oa.issue_range(ldsA, wave_u, 3, src_kt(3), 0, MX);
+  if (!KCB) ob.issue_range(ldsB, wave_u, 3, src_kt(3), 0, MX);
+  wait_vm<PA * nK + (8 + MX) * nM>();
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
 
   // Software pipeline with two fragment sets: fr0 = first 16 k of a k-tile, fr1 = second.
-  // Iteration kt:  16 MFMAs on fr0 with the reads of fr1 between them | k-tile kt+1 landed?
-  // barrier | 16 MFMAs on fr1 with the reads of fr0 of k-tile kt+1 and the DMA issue between
-  // them -- every LDS read and every DMA instruction has MFMAs in flight as cover.
+  // 1st half of kt: 16 MFMAs on fr0, the reads of fr1 behind the first eight of them; barrier;
+  // 2nd half: 16 MFMAs on fr1, the reads of fr0 of k-tile kt+1 likewise.  Behind every MFMA at
+  // most one fragment read and the DMA instructions the schedule puts there, in exactly this
+  // order (every step is fenced), so each of them has MFMAs in flight as cover.
   bf16x8_t fa0[4], fb0[4], fa1[4], fb1[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
@@ -282,75 +302,46 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
     fb0[i] = ob.fragment(regB, 0, i, 0);
   }
 
-  // one k-tile; STEADY: parity, refill and successor are compile-time so that the body is one
-  // basic block the scheduler can interleave freely
-  auto k_tile = [&](auto steady_c, auto odd_c, const int kt) {
-    constexpr bool STEADY = decltype(steady_c)::value, ODD = decltype(odd_c)::value;
-    const bool next = STEADY || kt + 1 < KT;
-    // first half: 16 MFMAs on fr0; the reads of fr1 are spread over the first three quarters,
-    // B fragments first (every quarter of the next half needs all of them, but only one A)
+  auto half = [&](auto ph_c, const int kt) {
+    constexpr int PH = decltype(ph_c)::value;
+    constexpr bool SECOND = PH & 1;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      if (i == 0) { fb1[0] = ob.fragment(regB, kt, 0, 1); fb1[1] = ob.fragment(regB, kt, 1, 1);
-                    fb1[2] = ob.fragment(regB, kt, 2, 1); }
-      if (i == 1) { fb1[3] = ob.fragment(regB, kt, 3, 1); fa1[0] = oa.fragment(regA, kt, 0, 1);
-                    fa1[1] = oa.fragment(regA, kt, 1, 1); }
-      if (i == 2) { fa1[2] = oa.fragment(regA, kt, 2, 1); fa1[3] = oa.fragment(regA, kt, 3, 1); }
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0[i], fb0[j], acc[i][j], 0, 0, 0);
-      interleave<KCA, KCB>(i, true);
+      for (int j = 0; j < 4; ++j) {
+        const int step = i * 4 + j;
+        if (SECOND) {
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa1[i], fb1[j], acc[i][j], 0, 0, 0);
+          // (past the last k-tile this reads a slot nobody filled: in range, never used)
+          if (step < 4)      fb0[step] = ob.fragment(regB, kt + 1, step, 0);
+          else if (step < 8) fa0[step - 4] = oa.fragment(regA, kt + 1, step - 4, 0);
+        } else {
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0[i], fb0[j], acc[i][j], 0, 0, 0);
+          if (step < 4)      fb1[step] = ob.fragment(regB, kt, step, 1);
+          else if (step < 8) fa1[step - 4] = oa.fragment(regA, kt, step - 4, 1);
+        }
+        dma_ops(ph_c, step, kt);
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
-    __builtin_amdgcn_sched_barrier(0);
-
-    if (STEADY) {
-      if (nK == 0 || !ODD) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
-      else                 wait_vm(4 * nM);
-    } else if (next) {
-      wait_vm((nK == 0 || !(kt & 1)) ? issued_in(kt - 2) + issued_in(kt - 1) : issued_in(kt - 1));
-    }
+  };
+  auto barrier = [&](auto w_c) {
+    wait_vm<decltype(w_c)::value>();                     // k-tile kt+1 of this wavefront's loads
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // own reads of k-tile kt are back
     __builtin_amdgcn_s_barrier();        // k-tile kt+1 complete for everyone; k-tile kt released
     asm volatile("" ::: "memory");
     __builtin_amdgcn_sched_barrier(0);
-
-    // second half: 16 MFMAs on fr1; between them the reads of fr0 of k-tile kt+1 and the DMA
-    // into the slots k-tile kt just left
-    const bool refill_m = STEADY || kt + NSTAGE < KT;
-    const bool refill_k = STEADY ? ODD : ((kt & 1) && kt + 3 < KT);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      if (next) {
-        if (i == 0) { fb0[0] = ob.fragment(regB, kt + 1, 0, 0); fb0[1] = ob.fragment(regB, kt + 1, 1, 0);
-                      fb0[2] = ob.fragment(regB, kt + 1, 2, 0); }
-        if (i == 1) { fb0[3] = ob.fragment(regB, kt + 1, 3, 0); fa0[0] = oa.fragment(regA, kt + 1, 0, 0);
-                      fa0[1] = oa.fragment(regA, kt + 1, 1, 0); }
-        if (i == 2) { fa0[2] = oa.fragment(regA, kt + 1, 2, 0); fa0[3] = oa.fragment(regA, kt + 1, 3, 0); }
-      }
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa1[i], fb1[j], acc[i][j], 0, 0, 0);
-      interleave<KCA, KCB>(i, next);
-      __builtin_amdgcn_sched_barrier(0);
-      if (refill_m) {
-        if (!KCA) oa.issue_one(ldsA, wave_u, kt + NSTAGE, i);
-        if (!KCB) ob.issue_one(ldsB, wave_u, kt + NSTAGE, i);
-      }
-      if (refill_k) {
-        if (KCA) { oa.issue_one(ldsA, wave_u, (kt + 3) >> 1, 2 * i); oa.issue_one(ldsA, wave_u, (kt + 3) >> 1, 2 * i + 1); }
-        if (KCB) { ob.issue_one(ldsB, wave_u, (kt + 3) >> 1, 2 * i); ob.issue_one(ldsB, wave_u, (kt + 3) >> 1, 2 * i + 1); }
-      }
-    }
   };
-  using T_ = std::true_type;
-  using F_ = std::false_type;
-  int kt = 0;
-  for (; kt + NSTAGE + 1 < KT; kt += 2) {   // steady state, two k-tiles per trip (kt even)
-    k_tile(T_{}, F_{}, kt);
-    k_tile(T_{}, T_{}, kt + 1);
+  for (int kt = 0; kt < KT; kt += 2) {     // KT is even
+    half(std::integral_constant<int, 0>{}, kt);
+    barrier(std::integral_constant<int, W_EVEN>{});
+    half(std::integral_constant<int, 1>{}, kt);
+    half(std::integral_constant<int, 2>{}, kt + 1);
+    barrier(std::integral_constant<int, W_ODD>{});
+    half(std::integral_constant<int, 3>{}, kt + 1);
   }
-  for (; kt < KT; ++kt) k_tile(F_{}, F_{}, kt);   // drain
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __builtin_amdgcn_s_barrier();            // nobody's clamped reloads still land in LDS
 
   // ---- epilogue -------------------------------------------------------------------------------
   const int R0 = tile_r0 + wr * 128, C0 = tile_c0 + wc * 128;   // origin of this wavefront's sub-tile
@@ -372,107 +363,55 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
     }
   }
 
+  // One pass over the accumulators, no branches.  C goes straight to memory through a raw
+  // buffer whose base is the sub-tile origin and whose size ends with the last valid row: rows
+  // beyond n fail the hardware range check and are dropped, and a lane whose column is beyond m
+  // carries an offset that is out of range by itself.  (One store = 2 rows x 32 consecutive
+  // columns = two full lines.)  The accumulators of such rows and columns are exact zeros (their
+  // operand rows were read as zeros), so the sums below need no predicates.
+  // Column sums build up in 8 registers with the lane-independent part of the row weight (the
+  // lane part, 4 lhi, is added at the end); of every row the lane keeps the sum of its 4
+  // columns (one per 32-wide block) and u = x1 + 2 x2 + 3 x3, the block part of the column
+  // weight -- both go through LDS, where the 32 lanes of a half wavefront are added and the
+  // lane part of the weight is applied.
   const int tm128 = R0 >> 7, tn128 = C0 >> 7;
+  const int R0u = tile_r0 + (wave_u >> 1) * 128, C0u = tile_c0 + (wave_u & 1) * 128;   // scalar copies
+  const int rows_left = min(a.n - R0u, 128), cols_left = a.m - C0u;
+  const __amdgpu_buffer_rsrc_t crsrc = __builtin_amdgcn_make_buffer_rsrc(
+      C + (int64_t)R0u * a.ldc + C0u, 0, rows_left > 0 && cols_left > 0 ? rows_left * a.ldc * 4 : 0, 0x00020000);
+  int vo[4];   // byte offset of this lane in row 4 lhi of the sub-tile, per 32-wide block
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+    vo[j] = j * 32 + l32 < cols_left ? ((lhi * 4) * a.ldc + j * 32 + l32) * 4 : (int)OOB;
   float cs[4] = {0.f, 0.f, 0.f, 0.f}, cw[4] = {0.f, 0.f, 0.f, 0.f};
-  // wave-uniform copies of the sub-tile origin (scalar registers: row addresses stay scalar)
-  const int R0u = tile_r0 + (wave_u >> 1) * 128, C0u = tile_c0 + (wave_u & 1) * 128;
-  const bool interior = R0u + 128 <= a.n && C0u + 128 <= a.m;
-  if (interior) {
-    // Sub-tile fully inside C: no predicates.  One pass over the accumulators: C goes straight
-    // to memory (one store = 2 rows x 32 consecutive columns = two full lines; scalar row base,
-    // one lane offset for all stores); the column sums build up in 8 registers with the
-    // lane-independent part of the row weight (the lane part, 4 lhi, is added at the end); of
-    // every row the lane keeps the sum of its 4 columns (one per 32-wide block) and
-    // u = x1 + 2 x2 + 3 x3, the block part of the column weight -- both go through LDS, where
-    // the 32 lanes of a half wavefront are added and the lane part of the weight is applied.
-    const char* cbase = reinterpret_cast<const char*>(C + (int64_t)R0u * a.ldc + C0u);
-    // byte offset of the lane inside a row group; fits 32 bits (ldc < 2^27, checked by the launcher)
-    const unsigned lane_off = ((unsigned)(lhi * 4) * (unsigned)a.ldc + (unsigned)l32) * 4u;
-    float2* red2 = reinterpret_cast<float2*>(smem) + wave_u * (128 * 33) + (lhi * 4) * 33 + l32;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int ru = i * 32 + (v >> 2) * 8 + (v & 3);   // row inside the sub-tile, without 4 lhi
-        float* crow = reinterpret_cast<float*>(const_cast<char*>(cbase + (int64_t)ru * a.ldc * 4 + lane_off));
-        const float x0 = acc[i][0][v], x1 = acc[i][1][v], x2 = acc[i][2][v], x3 = acc[i][3][v];
-        crow[0] = x0;
-        crow[32] = x1;
-        crow[64] = x2;
-        crow[96] = x3;
-        if (EPI) {
-          const float t2 = x2 + x3, t1 = x1 + t2;
-          red2[ru * 33] = make_float2(x0 + t1, (t1 + t2) + x3);
-          const float wr_ = (float)(ru + 1);
-          cs[0] += x0; cw[0] = fmaf(x0, wr_, cw[0]);
-          cs[1] += x1; cw[1] = fmaf(x1, wr_, cw[1]);
-          cs[2] += x2; cw[2] = fmaf(x2, wr_, cw[2]);
-          cs[3] += x3; cw[3] = fmaf(x3, wr_, cw[3]);
-        }
-      }
-    }
-    if (EPI) {
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const float w1 = fmaf((float)(lhi * 4), cs[j], cw[j]);
-        const float s = cs[j] + __shfl_xor(cs[j], 32, 64), w = w1 + __shfl_xor(w1, 32, 64);
-        if (lhi == 0) {
-          float2* cp = reinterpret_cast<float2*>(a.colpart + (((int64_t)b * a.ntm + tm128) * a.m + C0 + j * 32 + l32) * 2);
-          *cp = make_float2(s, w);
-        }
-      }
-      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the region is this wavefront's own
-      const float2* mine = reinterpret_cast<const float2*>(smem) + wave_u * (128 * 33);
-#pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        const int r = lane + 64 * h;
-        float s = 0.f, w = 0.f, u = 0.f;
-#pragma unroll
-        for (int c = 0; c < 32; ++c) {
-          const float2 t = mine[r * 33 + c];
-          s += t.x;
-          w = fmaf((float)(c + 1), t.x, w);
-          u += t.y;
-        }
-        float2* rp = reinterpret_cast<float2*>(a.rowpart + (((int64_t)b * a.ntn + tn128) * a.n + R0 + r) * 2);
-        *rp = make_float2(s, fmaf(32.f, u, w));
-      }
-    }
-    return;
-  }
-
-  // Sub-tile on the edge of C: the same pass with every store predicated, full weights per
-  // element and one LDS array per kind.
-  float* red = reinterpret_cast<float*>(smem) + wave * (2 * 128 * 33);   // [kind][row][lane]
+  float2* red2 = reinterpret_cast<float2*>(smem) + wave_u * (128 * 33) + (lhi * 4) * 33 + l32;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
-      const int rl = i * 32 + (v >> 2) * 8 + lhi * 4 + (v & 3);   // row inside the sub-tile
-      const int row = R0 + rl;
-      float* crow = C + (int64_t)row * a.ldc + C0 + l32;
-      float rs = 0.f, rw = 0.f;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const float x = acc[i][j][v];
-        if (row < a.n && C0 + j * 32 + l32 < a.m) crow[j * 32] = x;
-        if (EPI) {
-          cs[j] += x;
-          cw[j] = fmaf((float)(rl + 1), x, cw[j]);
-          rs += x;
-          rw = fmaf((float)(j * 32 + l32 + 1), x, rw);
-        }
-      }
+      const int ru = i * 32 + (v >> 2) * 8 + (v & 3);   // row inside the sub-tile, without 4 lhi
+      const int rowoff = ru * a.ldc * 4;                // scalar; < 2^31 (ldc < 2^22, checked by the launcher)
+      const float x0 = acc[i][0][v], x1 = acc[i][1][v], x2 = acc[i][2][v], x3 = acc[i][3][v];
+      __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, x0), crsrc, vo[0] + rowoff, 0, 0);
+      __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, x1), crsrc, vo[1] + rowoff, 0, 0);
+      __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, x2), crsrc, vo[2] + rowoff, 0, 0);
+      __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, x3), crsrc, vo[3] + rowoff, 0, 0);
       if (EPI) {
-        red[rl * 33 + l32] = rs;
-        red[128 * 33 + rl * 33 + l32] = rw;
+        const float t2 = x2 + x3, t1 = x1 + t2;
+        red2[ru * 33] = make_float2(x0 + t1, (t1 + t2) + x3);
+        const float wr_ = (float)(ru + 1);
+        cs[0] += x0; cw[0] = fmaf(x0, wr_, cw[0]);
+        cs[1] += x1; cw[1] = fmaf(x1, wr_, cw[1]);
+        cs[2] += x2; cw[2] = fmaf(x2, wr_, cw[2]);
+        cs[3] += x3; cw[3] = fmaf(x3, wr_, cw[3]);
       }
     }
   }
   if (EPI) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      const float s = cs[j] + __shfl_xor(cs[j], 32, 64), w = cw[j] + __shfl_xor(cw[j], 32, 64);
+      const float w1 = fmaf((float)(lhi * 4), cs[j], cw[j]);
+      const float s = cs[j] + __shfl_xor(cs[j], 32, 64), w = w1 + __shfl_xor(w1, 32, 64);
       const int col = C0 + j * 32 + l32;
       if (lhi == 0 && col < a.m && R0 < a.n) {
         float2* cp = reinterpret_cast<float2*>(a.colpart + (((int64_t)b * a.ntm + tm128) * a.m + col) * 2);
@@ -480,19 +419,22 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
       }
     }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the region is this wavefront's own
+    const float2* mine = reinterpret_cast<const float2*>(smem) + wave_u * (128 * 33);
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       const int r = lane + 64 * h;
-      float s = 0.f, w = 0.f;
+      float s = 0.f, w = 0.f, u = 0.f;
 #pragma unroll
       for (int c = 0; c < 32; ++c) {
-        s += red[r * 33 + c];
-        w += red[128 * 33 + r * 33 + c];
+        const float2 t = mine[r * 33 + c];
+        s += t.x;
+        w = fmaf((float)(c + 1), t.x, w);
+        u += t.y;
       }
       const int row = R0 + r;
       if (row < a.n && C0 < a.m) {
         float2* rp = reinterpret_cast<float2*>(a.rowpart + (((int64_t)b * a.ntn + tn128) * a.n + row) * 2);
-        *rp = make_float2(s, w);
+        *rp = make_float2(s, fmaf(32.f, u, w));
       }
     }
   }
@@ -540,7 +482,7 @@ bool gemm_bf16_fast_ok(const GemmArgs& a) {
   // byte offsets inside a tile panel (k-contiguous: 256 rows; otherwise the whole k extent)
   const int64_t span_a = (a.trans_a ? (int64_t)a.k : (int64_t)BM) * a.lda * 2;
   const int64_t span_b = (a.trans_b ? (int64_t)BN : (int64_t)a.k) * a.ldb * 2;
-  if (span_a >= 0x7fffffff || span_b >= 0x7fffffff || a.ldc >= (1 << 27)) return false;
+  if (span_a >= 0x7fffffff || span_b >= 0x7fffffff || a.ldc >= (1 << 22)) return false;
   return (int64_t)a.n * a.m >= (int64_t)BM * BN;   // smaller problems: the 128 x 128 kernel
 }
 
