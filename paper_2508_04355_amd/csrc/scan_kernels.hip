@@ -13,17 +13,20 @@ template <int DT> struct Elem;
 template <> struct Elem<GECC_F32> {
   using type = float;
   static constexpr int VEC = 4;
-  static __device__ __forceinline__ void load_vec(const float* p, double* v) {
-    float4 x = *reinterpret_cast<const float4*>(p);
+  using raw = float4;
+  static __device__ __forceinline__ raw load_raw(const float* p) { return *reinterpret_cast<const float4*>(p); }
+  static __device__ __forceinline__ void widen(const raw& x, double* v) {
     v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
   }
+  static __device__ __forceinline__ void load_vec(const float* p, double* v) { widen(load_raw(p), v); }
   static __device__ __forceinline__ double load_one(const float* p) { return (double)*p; }
 };
 template <> struct Elem<GECC_BF16> {
   using type = uint16_t;
   static constexpr int VEC = 8;
-  static __device__ __forceinline__ void load_vec(const uint16_t* p, double* v) {
-    uint4 x = *reinterpret_cast<const uint4*>(p);
+  using raw = uint4;
+  static __device__ __forceinline__ raw load_raw(const uint16_t* p) { return *reinterpret_cast<const uint4*>(p); }
+  static __device__ __forceinline__ void widen(const raw& x, double* v) {
     uint32_t w[4] = {x.x, x.y, x.z, x.w};
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -31,6 +34,7 @@ template <> struct Elem<GECC_BF16> {
       v[2 * i + 1] = (double)__uint_as_float(w[i] & 0xffff0000u);
     }
   }
+  static __device__ __forceinline__ void load_vec(const uint16_t* p, double* v) { widen(load_raw(p), v); }
   static __device__ __forceinline__ double load_one(const uint16_t* p) {
     return (double)__uint_as_float(((uint32_t)*p) << 16);
   }
@@ -46,13 +50,18 @@ __device__ __forceinline__ bool gated_off(const int32_t* gate, int64_t stride, i
 // rowdot: out[t][r] = sum_c w_t[c] X[r,c].   One workgroup owns RB rows and walks all columns;
 // a thread keeps the weights of its VEC columns in registers and reuses them for the RB rows.
 constexpr int RD_THREADS = 256;
+constexpr int RD_BIG_RB = 16, RD_BIG_U = 1, RD_SMALL_RB = 4, RD_SMALL_U = 2;
 
-// RD_RB rows per workgroup: 16 when there are rows enough to fill the chip, else 4
-template <int DT, bool IDXW, int RD_RB>
+// RD_RB rows per workgroup: 16 when there are rows enough to fill the chip, else 4.  RD_U column
+// steps are taken together, so that a thread has RD_RB * RD_U independent 16-byte loads in
+// flight before the first of them is used (the kernel is a stream over the operand: what it
+// needs is memory-level parallelism, the arithmetic hides behind it).
+template <int DT, bool IDXW, int RD_RB, int RD_U>
 __global__ __launch_bounds__(RD_THREADS) void rowdot_kernel(ScanArgs a) {
   using E = Elem<DT>;
   using T = typename E::type;
   constexpr int VEC = E::VEC;
+  constexpr int STEP = RD_THREADS * VEC;   // columns one pass of the workgroup covers
   const int b = blockIdx.y;
   if (gated_off(a.gate, a.gate_stride, b, a.gate_value)) return;
   const T* X = reinterpret_cast<const T*>(a.X) + (int64_t)b * a.xs;
@@ -66,7 +75,42 @@ __global__ __launch_bounds__(RD_THREADS) void rowdot_kernel(ScanArgs a) {
 #pragma unroll
   for (int r = 0; r < RD_RB; ++r) { acc0[r] = 0.0; acc1[r] = 0.0; }
 
-  for (int c0 = 0; c0 < a.Cc; c0 += RD_THREADS * VEC) {
+  // whole vectors for every thread: rows past the end are clamped to the last one (their sums
+  // are computed and never stored), so the body has no branches
+  int c0 = 0;
+  if (a.vec_ok) {
+    for (; c0 + RD_U * STEP <= a.Cc; c0 += RD_U * STEP) {
+      typename E::raw x[RD_U][RD_RB];
+      double wa[RD_U][VEC], wb[RD_U][VEC];
+#pragma unroll
+      for (int u = 0; u < RD_U; ++u) {
+        const int c = c0 + u * STEP + tid * VEC;
+#pragma unroll
+        for (int r = 0; r < RD_RB; ++r)
+          x[u][r] = E::load_raw(X + (int64_t)min(r0 + r, a.R - 1) * a.ld + (unsigned)c);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+          if (IDXW) { wa[u][e] = 1.0; wb[u][e] = (double)(c + e + 1); }
+          else      { wa[u][e] = w0[c + e]; wb[u][e] = w1[c + e]; }
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < RD_U; ++u) {
+#pragma unroll
+        for (int r = 0; r < RD_RB; ++r) {
+          double v[VEC];
+          E::widen(x[u][r], v);
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) {
+            acc0[r] = IDXW ? acc0[r] + v[e] : fma(wa[u][e], v[e], acc0[r]);
+            acc1[r] = fma(wb[u][e], v[e], acc1[r]);
+          }
+        }
+      }
+    }
+  }
+  // the remaining columns (and everything, if the rows are not 16-byte aligned)
+  for (; c0 < a.Cc; c0 += STEP) {
     const int c = c0 + tid * VEC;
     if (c >= a.Cc) continue;
     const int nv = min(VEC, a.Cc - c);
@@ -77,17 +121,17 @@ __global__ __launch_bounds__(RD_THREADS) void rowdot_kernel(ScanArgs a) {
       else      { wa[e] = e < nv ? w0[c + e] : 0.0; wb[e] = e < nv ? w1[c + e] : 0.0; }
     }
     if (nv == VEC && a.vec_ok) {
+      typename E::raw x[RD_RB];
+#pragma unroll
+      for (int r = 0; r < RD_RB; ++r) x[r] = E::load_raw(X + (int64_t)min(r0 + r, a.R - 1) * a.ld + c);
 #pragma unroll
       for (int r = 0; r < RD_RB; ++r) {
-        const int row = r0 + r;
-        if (row < a.R) {
-          double v[VEC];
-          E::load_vec(X + (int64_t)row * a.ld + c, v);
+        double v[VEC];
+        E::widen(x[r], v);
 #pragma unroll
-          for (int e = 0; e < VEC; ++e) {
-            acc0[r] = IDXW ? acc0[r] + v[e] : fma(wa[e], v[e], acc0[r]);
-            acc1[r] = fma(wb[e], v[e], acc1[r]);
-          }
+        for (int e = 0; e < VEC; ++e) {
+          acc0[r] = IDXW ? acc0[r] + v[e] : fma(wa[e], v[e], acc0[r]);
+          acc1[r] = fma(wb[e], v[e], acc1[r]);
         }
       }
     } else {
@@ -250,12 +294,14 @@ hipError_t launch_rowdot(const ScanArgs& a0, hipStream_t st) {
   ScanArgs a = a0;
   a.vec_ok = vec_ok(a0) ? 1 : 0;
   const bool idx = a.w == nullptr;
-  const bool small = (int64_t)((a.R + 15) / 16) * a.batch < 1024;   // fewer than 4 workgroups per CU
+  const bool small = (int64_t)((a.R + RD_BIG_RB - 1) / RD_BIG_RB) * a.batch < 1024;   // fewer than 4 workgroups per CU
 #define GECC_LAUNCH_ROWDOT(DT, IDX)                                                                  \
   do {                                                                                              \
-    if (small) hipLaunchKernelGGL((rowdot_kernel<DT, IDX, 4>), dim3((a.R + 3) / 4, a.batch),          \
+    if (small) hipLaunchKernelGGL((rowdot_kernel<DT, IDX, RD_SMALL_RB, RD_SMALL_U>),                  \
+                                  dim3((a.R + RD_SMALL_RB - 1) / RD_SMALL_RB, a.batch),               \
                                   dim3(RD_THREADS), 0, st, a);                                        \
-    else       hipLaunchKernelGGL((rowdot_kernel<DT, IDX, 16>), dim3((a.R + 15) / 16, a.batch),       \
+    else       hipLaunchKernelGGL((rowdot_kernel<DT, IDX, RD_BIG_RB, RD_BIG_U>),                      \
+                                  dim3((a.R + RD_BIG_RB - 1) / RD_BIG_RB, a.batch),                   \
                                   dim3(RD_THREADS), 0, st, a);                                        \
   } while (0)
   if (a.dtype == GECC_BF16) {
