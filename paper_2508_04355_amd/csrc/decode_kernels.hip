@@ -47,7 +47,6 @@ __device__ __forceinline__ int64_t b_index(const gecc_params& p, int b, int l, i
 // -------------------------------------------------------------------------------------------
 __device__ void reset_state(DecodeState* s) {
   s->s_cnt = 0; s->t_cnt = 0;
-  for (int f = 0; f < 4; ++f) s->maxbits[f] = 0ull;
   s->phase = PH_DONE;
   s->n_err = 0;
 }
@@ -58,38 +57,56 @@ __global__ void reset_state_kernel(DecodeArgs a) {
 }
 
 // partial sums -> syndromes (sum - parity, Section V step 1) -> flags
-__global__ __launch_bounds__(64) void threshold_kernel(DecodeArgs a, int first) {
+constexpr int TH_SLICES = 4;    // wavefronts of a workgroup; each adds every 4th sub-tile of a line
+constexpr int TH_MAXLOADS = 32; // loads a thread keeps in flight
+
+__global__ __launch_bounds__(64 * TH_SLICES) void threshold_kernel(DecodeArgs a, int first) {
   const int b = blockIdx.y;
   DecodeState* st = state_of(a, b);
   if (!first && st->phase != PH_REVERIFY) return;
   const int n = a.p.n, m = a.p.m;
-  const int o = blockIdx.x * 64 + threadIdx.x;
+  const int lane = threadIdx.x & 63, slice = threadIdx.x >> 6;
+  const int o = blockIdx.x * 64 + lane;          // line: rows first, then columns
   const double* cpar = cpar_of(a, b);
   double* synd = synd_of(a, b);
   const double* allow = allow_of(a, b);   // valid in the residual pass only
+  const bool is_row = o < n, valid = o < n + m;
+
+  // partial sums of this line over the sub-tiles slice, slice + 4, ... (fixed order); all loads
+  // of a thread are issued before the first is used
+  double S = 0.0, W = 0.0;
+  {
+    // (lanes past the last line read the last line's data and drop the result; sub-tiles past
+    // the last one are clamped and count as zero: no load depends on a branch)
+    const int oo = min(o, n + m - 1);
+    const bool rowline = oo < n;
+    const int nt = rowline ? a.ntn : a.ntm, len = rowline ? a.rp_ld : a.cp_ld, tile = rowline ? a.tile_n : a.tile_m;
+    const float2* pp = rowline ? reinterpret_cast<const float2*>(a.rowpart) + (int64_t)b * a.ntn * a.rp_ld + oo
+                               : reinterpret_cast<const float2*>(a.colpart) + (int64_t)b * a.ntm * a.cp_ld + (oo - n);
+    for (int t0 = slice; t0 < nt; t0 += TH_SLICES * TH_MAXLOADS) {
+      float2 v[TH_MAXLOADS];
+#pragma unroll
+      for (int u = 0; u < TH_MAXLOADS; ++u) v[u] = pp[(int64_t)min(t0 + u * TH_SLICES, nt - 1) * len];
+#pragma unroll
+      for (int u = 0; u < TH_MAXLOADS; ++u) {
+        const int t = t0 + u * TH_SLICES;
+        const double x = t < nt ? (double)v[u].x : 0.0, y = t < nt ? (double)v[u].y : 0.0;
+        S += x;
+        W += y + (double)(t * tile) * x;
+      }
+    }
+  }
+  __shared__ double red[2][TH_SLICES][64];
+  red[0][slice][lane] = S;
+  red[1][slice][lane] = W;
+  __syncthreads();
+  if (slice != 0) return;
   double v1 = 0.0, v2 = 0.0;
-  bool is_row = o < n, valid = o < n + m;
   if (valid) {
+    S = (red[0][0][lane] + red[0][1][lane]) + (red[0][2][lane] + red[0][3][lane]);
+    W = (red[1][0][lane] + red[1][1][lane]) + (red[1][2][lane] + red[1][3][lane]);
     if (is_row) {
       const int i = o;
-      double S = 0.0, W = 0.0;
-      const float2* rp = reinterpret_cast<const float2*>(a.rowpart) + (int64_t)b * a.ntn * n + i;
-      int tn = 0;
-      for (; tn + 8 <= a.ntn; tn += 8) {            // 8 loads in flight
-        float2 v[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) v[u] = rp[(int64_t)(tn + u) * n];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          S += (double)v[u].x;
-          W += (double)v[u].y + (double)((tn + u) * a.tile_n) * (double)v[u].x;
-        }
-      }
-      for (; tn < a.ntn; ++tn) {
-        const float2 v = rp[(int64_t)tn * n];
-        S += (double)v.x;
-        W += (double)v.y + (double)(tn * a.tile_n) * (double)v.x;
-      }
       v1 = S - cpar[i];
       v2 = W - cpar[n + i];
       synd[i] = v1;
@@ -101,24 +118,6 @@ __global__ __launch_bounds__(64) void threshold_kernel(DecodeArgs a, int first) 
       }
     } else {
       const int j = o - n;
-      double S = 0.0, W = 0.0;
-      const float2* cp = reinterpret_cast<const float2*>(a.colpart) + (int64_t)b * a.ntm * m + j;
-      int tm = 0;
-      for (; tm + 8 <= a.ntm; tm += 8) {
-        float2 v[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) v[u] = cp[(int64_t)(tm + u) * m];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          S += (double)v[u].x;
-          W += (double)v[u].y + (double)((tm + u) * a.tile_m) * (double)v[u].x;
-        }
-      }
-      for (; tm < a.ntm; ++tm) {
-        const float2 v = cp[(int64_t)tm * m];
-        S += (double)v.x;
-        W += (double)v.y + (double)(tm * a.tile_m) * (double)v.x;
-      }
       v1 = S - cpar[2 * n + j];
       v2 = W - cpar[2 * n + m + j];
       synd[2 * n + j] = v1;
@@ -131,7 +130,8 @@ __global__ __launch_bounds__(64) void threshold_kernel(DecodeArgs a, int first) 
     }
   }
   if (first) {
-    // family maxima: rows go to [0], [1]; columns to [2], [3]; one atomic per wavefront & family
+    // family maxima of this workgroup (rows: [0], [1]; columns: [2], [3]); the summary reduces
+    // them (atomics on one line from every workgroup would serialise in L2)
     double mr1 = (valid && is_row) ? fabs(v1) : 0.0, mr2 = (valid && is_row) ? fabs(v2) : 0.0;
     double mq1 = (valid && !is_row) ? fabs(v1) : 0.0, mq2 = (valid && !is_row) ? fabs(v2) : 0.0;
 #pragma unroll
@@ -141,29 +141,49 @@ __global__ __launch_bounds__(64) void threshold_kernel(DecodeArgs a, int first) 
       mq1 = fmax(mq1, __shfl_down(mq1, off, 64));
       mq2 = fmax(mq2, __shfl_down(mq2, off, 64));
     }
-    if ((threadIdx.x & 63) == 0) {
-      if (mr1 > 0.0) atomicMax(&st->maxbits[0], (unsigned long long)__double_as_longlong(mr1));
-      if (mr2 > 0.0) atomicMax(&st->maxbits[1], (unsigned long long)__double_as_longlong(mr2));
-      if (mq1 > 0.0) atomicMax(&st->maxbits[2], (unsigned long long)__double_as_longlong(mq1));
-      if (mq2 > 0.0) atomicMax(&st->maxbits[3], (unsigned long long)__double_as_longlong(mq2));
+    if (lane == 0) {
+      double* bm = a.blockmax + ((int64_t)b * gridDim.x + blockIdx.x) * 4;
+      bm[0] = mr1; bm[1] = mr2; bm[2] = mq1; bm[3] = mq2;
     }
   }
 }
 
-// first report after detection: CLEAN or DETECTED
-__device__ int summarize(const DecodeState* st, gecc_report* rep) {
-  rep->s = st->s_cnt;
-  rep->t = st->t_cnt;
-  rep->n_err = 0;
-  for (int f = 0; f < 4; ++f) rep->max_abs_synd[f] = __longlong_as_double((long long)st->maxbits[f]);
+// first report after detection: CLEAN or DETECTED.  Called by every thread of a workgroup of 1
+// to 4 wavefronts (the family maxima are reduced over the threshold kernel's workgroups);
+// returns the status to all of them.
+__device__ int summarize(const DecodeArgs& a, int b, const DecodeState* st, gecc_report* rep) {
+  __shared__ double smx[4][4];
+  double mx[4] = {0.0, 0.0, 0.0, 0.0};
+  const double* bm = a.blockmax + (int64_t)b * a.nblk * 4;
+  for (int i = threadIdx.x; i < a.nblk; i += blockDim.x)
+#pragma unroll
+    for (int f = 0; f < 4; ++f) mx[f] = fmax(mx[f], bm[(int64_t)i * 4 + f]);
+#pragma unroll
+  for (int f = 0; f < 4; ++f)
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) mx[f] = fmax(mx[f], __shfl_down(mx[f], off, 64));
+  const int wave = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+  if ((threadIdx.x & 63) == 0)
+#pragma unroll
+    for (int f = 0; f < 4; ++f) smx[wave][f] = mx[f];
+  __syncthreads();
   const int status = (st->s_cnt == 0 && st->t_cnt == 0) ? GECC_CLEAN : GECC_DETECTED;
-  rep->status = status;
+  if (threadIdx.x == 0) {
+    rep->s = st->s_cnt;
+    rep->t = st->t_cnt;
+    rep->n_err = 0;
+    for (int f = 0; f < 4; ++f) {
+      double v = smx[0][f];
+      for (int w = 1; w < nw; ++w) v = fmax(v, smx[w][f]);
+      rep->max_abs_synd[f] = v;
+    }
+    rep->status = status;
+  }
   return status;
 }
-__global__ void summarize_kernel(DecodeArgs a) {
-  const int b = blockIdx.x * blockDim.x + threadIdx.x;
-  if (b >= a.p.batch) return;
-  summarize(state_of(a, b), a.report + b);
+__global__ __launch_bounds__(64) void summarize_kernel(DecodeArgs a) {   // one wavefront per item
+  const int b = blockIdx.x;
+  summarize(a, b, state_of(a, b), a.report + b);
 }
 
 // ---- Section V step 2 ------------------------------------------------------------------------
@@ -301,12 +321,7 @@ __global__ __launch_bounds__(256) void decode_c_kernel(DecodeArgs a, int final_p
   if (final_pass) {
     if (st->phase != PH_REVERIFY) return;
   } else if (with_summary) {
-    // every thread derives the status from the counters (the report is written by thread 0 only)
-    if (st->s_cnt == 0 && st->t_cnt == 0) {
-      if (threadIdx.x == 0) summarize(st, rep);
-      return;
-    }
-    if (threadIdx.x == 0) summarize(st, rep);
+    if (summarize(a, b, st, rep) == GECC_CLEAN) return;
   } else {
     if (rep->status != GECC_DETECTED) return;
   }
@@ -583,13 +598,13 @@ hipError_t launch_reset_state(const DecodeArgs& a, hipStream_t st) {
 }
 
 hipError_t launch_threshold(const DecodeArgs& a, int first, hipStream_t st) {
-  dim3 grid((a.p.n + a.p.m + 63) / 64, a.p.batch);   // one wavefront per workgroup: spreads over all CUs
-  hipLaunchKernelGGL(threshold_kernel, grid, dim3(64), 0, st, a, first);
+  dim3 grid((a.p.n + a.p.m + 63) / 64, a.p.batch);   // 64 lines per workgroup: spreads over all CUs
+  hipLaunchKernelGGL(threshold_kernel, grid, dim3(64 * TH_SLICES), 0, st, a, first);
   return hipGetLastError();
 }
 
 hipError_t launch_summarize(const DecodeArgs& a, hipStream_t st) {
-  hipLaunchKernelGGL(summarize_kernel, dim3((a.p.batch + 63) / 64), dim3(64), 0, st, a);
+  hipLaunchKernelGGL(summarize_kernel, dim3(a.p.batch), dim3(64), 0, st, a);
   return hipGetLastError();
 }
 

@@ -17,13 +17,14 @@ void make_layout(gecc_ctx* c) {
   Layout& L = c->lay;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
-  L.rowpart = take(b * c->ntn * n * 2 * sizeof(float));
-  L.colpart = take(b * c->ntm * m * 2 * sizeof(float));
+  L.rowpart = take(b * c->ntn * (size_t)c->rp_ld * 2 * sizeof(float));
+  L.colpart = take(b * c->ntm * (size_t)c->cp_ld * 2 * sizeof(float));
   L.synd = take(b * (2 * n + 2 * m) * sizeof(double));
   L.allow = take(b * (2 * n + 2 * m) * sizeof(double));
   L.state = take(b * sizeof(DecodeState));
   L.audit_a = take(b * 2 * k * sizeof(double));
   L.audit_b = take(b * 2 * k * sizeof(double));
+  L.blockmax = take(b * ((n + m + 63) / 64) * 4 * sizeof(double));
   // column reductions: A side reduces over n (A stored n x k) or over k (P_r with A stored
   // k x n); B side over k (P_c with B stored k x m) or over m (B stored m x k)
   const size_t sa = p.trans_a ? coldot_scratch_doubles(p.k, p.n, p.batch)
@@ -51,6 +52,7 @@ DecodeArgs decode_args(gecc_ctx* c, void* A, const double* A_par, void* B, const
   DecodeArgs d;
   d.p = c->p;
   d.tile_m = c->tile_m; d.tile_n = c->tile_n; d.ntm = c->ntm; d.ntn = c->ntn;
+  d.rp_ld = c->rp_ld; d.cp_ld = c->cp_ld;
   d.A = A; d.B = B; d.C = C;
   d.A_par = A_par; d.B_par = B_par; d.C_par = C_par;
   d.rowpart = reinterpret_cast<float*>(c->ws + c->lay.rowpart);
@@ -58,6 +60,8 @@ DecodeArgs decode_args(gecc_ctx* c, void* A, const double* A_par, void* B, const
   d.synd = reinterpret_cast<double*>(c->ws + c->lay.synd);
   d.allow = reinterpret_cast<double*>(c->ws + c->lay.allow);
   d.state = reinterpret_cast<DecodeState*>(c->ws + c->lay.state);
+  d.blockmax = reinterpret_cast<double*>(c->ws + c->lay.blockmax);
+  d.nblk = (c->p.n + c->p.m + 63) / 64;
   d.audit_a = reinterpret_cast<double*>(c->ws + c->lay.audit_a);
   d.audit_b = reinterpret_cast<double*>(c->ws + c->lay.audit_b);
   d.report = rep;
@@ -134,6 +138,7 @@ GemmArgs gemm_args(const gecc_ctx* c, const void* A, const void* B, float* C) {
   g.lda = p.lda; g.ldb = p.ldb; g.ldc = p.ldc;
   g.sa = p.stride_a; g.sb = p.stride_b; g.sc = p.stride_c;
   g.tile_m = c->tile_m; g.tile_n = c->tile_n; g.ntm = c->ntm; g.ntn = c->ntn;
+  g.rp_ld = c->rp_ld; g.cp_ld = c->cp_ld;
   return g;
 }
 
@@ -180,6 +185,10 @@ int gecc_create(gecc_ctx** out, const gecc_params* p) {
   c->tile_n = 128;
   c->ntm = (p->n + c->tile_m - 1) / c->tile_m;
   c->ntn = (p->m + c->tile_n - 1) / c->tile_n;
+  // slab strides of the partial sums: a multiple of 2 KiB would put the same line of every slab
+  // into the same memory channel
+  c->rp_ld = p->n % 256 == 0 ? p->n + 16 : p->n;
+  c->cp_ld = p->m % 256 == 0 ? p->m + 16 : p->m;
   c->ws = nullptr;
   c->ws_bytes = 0;
   c->ev = nullptr;
@@ -309,6 +318,7 @@ int verify_impl(gecc_ctx* ctx, const float* dev_C, const double* dev_C_par, gecc
     pa.C = dev_C; pa.n = p.n; pa.m = p.m; pa.batch = p.batch; pa.ldc = p.ldc; pa.sc = p.stride_c;
     pa.rowpart = const_cast<float*>(d.rowpart); pa.colpart = const_cast<float*>(d.colpart);
     pa.tile_m = ctx->tile_m; pa.tile_n = ctx->tile_n; pa.ntm = ctx->ntm; pa.ntn = ctx->ntn;
+    pa.rp_ld = ctx->rp_ld; pa.cp_ld = ctx->cp_ld;
     pa.gate = nullptr;
     if ((e = launch_partials(pa, st)) != hipSuccess) return hip_rc(e);
   }
@@ -336,6 +346,7 @@ int correct_impl(gecc_ctx* ctx, void* dev_A, const double* dev_A_par, void* dev_
   pa.C = dev_C; pa.n = p.n; pa.m = p.m; pa.batch = p.batch; pa.ldc = p.ldc; pa.sc = p.stride_c;
   pa.rowpart = const_cast<float*>(d.rowpart); pa.colpart = const_cast<float*>(d.colpart);
   pa.tile_m = ctx->tile_m; pa.tile_n = ctx->tile_n; pa.ntm = ctx->ntm; pa.ntn = ctx->ntn;
+  pa.rp_ld = ctx->rp_ld; pa.cp_ld = ctx->cp_ld;
   pa.gate = gate; pa.gate_stride = sizeof(DecodeState); pa.gate_value = PH_REVERIFY;
   if ((e = launch_partials(pa, st)) != hipSuccess) return hip_rc(e);
   if ((e = launch_threshold(d, 0, st)) != hipSuccess) return hip_rc(e);

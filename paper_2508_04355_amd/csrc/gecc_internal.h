@@ -26,7 +26,6 @@ struct DecodeState {
   // filled by the threshold kernel (atomics; cleared by reset_state before each verify)
   int32_t s_cnt, t_cnt;
   int32_t rows[GECC_MAX_ERR], cols[GECC_MAX_ERR];
-  unsigned long long maxbits[4];
   // decoder
   int32_t phase;
   int32_t n_err;              // operand errors already accepted by the audit
@@ -34,13 +33,15 @@ struct DecodeState {
 };
 
 struct Layout {            // byte offsets into the caller's workspace
-  size_t rowpart;          // float  [batch][ntn][n][2]   per-tile row sums (plain, local-weighted)
-  size_t colpart;          // float  [batch][ntm][m][2]   per-tile column sums
+  size_t rowpart;          // float  [batch][ntn][rp_ld][2]   per-tile row sums (plain, local-weighted)
+  size_t colpart;          // float  [batch][ntm][cp_ld][2]   per-tile column sums
+                           // (rp_ld, cp_ld: n, m padded so that the slab stride is no power of two)
   size_t synd;             // double [batch][2n + 2m]     r1, r2, q1, q2
   size_t allow;            // double [batch][2n + 2m]     threshold allowances of repaired lines
   size_t state;            // DecodeState [batch]
   size_t audit_a;          // double [batch][2][k]        re-formed parity of A
   size_t audit_b;          // double [batch][2][k]        re-formed parity of B
+  size_t blockmax;         // double [batch][nblk][4]     max |syndrome| per family and threshold workgroup
   size_t scan_a;           // double scratch of the two-stage column reduction (A side)
   size_t scan_b;           // same, B side
   size_t total;
@@ -53,6 +54,7 @@ struct gecc_ctx {
   gecc::Layout lay;
   int tile_m, tile_n;      // blocking of the product kernel = granularity of the partials
   int ntm, ntn;            // partial tiles along n and m
+  int rp_ld, cp_ld;        // lines per slab of the row / column partials (n, m plus padding)
   char* ws;                // device workspace (caller's)
   size_t ws_bytes;
   hipEvent_t* ev;          // optional timing records around the product kernel (start, stop pairs)
@@ -97,6 +99,7 @@ struct GemmArgs {
   float* rowpart;       // null = no syndrome epilogue (plain product)
   float* colpart;
   int tile_m, tile_n, ntm, ntn;
+  int rp_ld, cp_ld;     // lines per sub-tile slab of rowpart / colpart (n, m plus padding)
   const gecc_fault* faults;
   int n_faults;
 };
@@ -113,6 +116,7 @@ struct PartialArgs {
   float* rowpart;
   float* colpart;
   int tile_m, tile_n, ntm, ntn;
+  int rp_ld, cp_ld;
   const int32_t* gate;
   int64_t gate_stride;
   int gate_value;
@@ -123,6 +127,7 @@ hipError_t launch_partials(const PartialArgs& a, hipStream_t st);
 struct DecodeArgs {
   gecc_params p;
   int tile_m, tile_n, ntm, ntn;
+  int rp_ld, cp_ld;
   void* A;
   void* B;
   float* C;
@@ -136,6 +141,8 @@ struct DecodeArgs {
   DecodeState* state;
   const double* audit_a;
   const double* audit_b;
+  double* blockmax;     // [batch][nblk][4] family maxima per workgroup of the first threshold pass
+  int nblk;
   gecc_report* report;
 };
 hipError_t launch_reset_state(const DecodeArgs& a, hipStream_t st);

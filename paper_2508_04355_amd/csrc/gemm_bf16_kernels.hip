@@ -367,7 +367,9 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
   // buffer whose base is the sub-tile origin and whose size ends with the last valid row: rows
   // beyond n fail the hardware range check and are dropped, and a lane whose column is beyond m
   // carries an offset that is out of range by itself.  (One store = 2 rows x 32 consecutive
-  // columns = two full lines.)  The accumulators of such rows and columns are exact zeros (their
+  // columns = two full lines, marked non-temporal: C is written once and is larger than the
+  // memory-side cache, which is better spent on the operands the parity kernels read again.)
+  // The accumulators of such rows and columns are exact zeros (their
   // operand rows were read as zeros), so the sums below need no predicates.
   // Column sums build up in 8 registers with the lane-independent part of the row weight (the
   // lane part, 4 lhi, is added at the end); of every row the lane keeps the sum of its 4
@@ -392,10 +394,10 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
       const int ru = i * 32 + (v >> 2) * 8 + (v & 3);   // row inside the sub-tile, without 4 lhi
       const int rowoff = ru * a.ldc * 4;                // scalar; < 2^31 (ldc < 2^22, checked by the launcher)
       const float x0 = acc[i][0][v], x1 = acc[i][1][v], x2 = acc[i][2][v], x3 = acc[i][3][v];
-      __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, x0), crsrc, vo[0] + rowoff, 0, 0);
-      __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, x1), crsrc, vo[1] + rowoff, 0, 0);
-      __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, x2), crsrc, vo[2] + rowoff, 0, 0);
-      __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, x3), crsrc, vo[3] + rowoff, 0, 0);
+      __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, x0), crsrc, vo[0] + rowoff, 0, 2);
+      __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, x1), crsrc, vo[1] + rowoff, 0, 2);
+      __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, x2), crsrc, vo[2] + rowoff, 0, 2);
+      __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, x3), crsrc, vo[3] + rowoff, 0, 2);
       if (EPI) {
         const float t2 = x2 + x3, t1 = x1 + t2;
         red2[ru * 33] = make_float2(x0 + t1, (t1 + t2) + x3);
@@ -414,7 +416,7 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
       const float s = cs[j] + __shfl_xor(cs[j], 32, 64), w = w1 + __shfl_xor(w1, 32, 64);
       const int col = C0 + j * 32 + l32;
       if (lhi == 0 && col < a.m && R0 < a.n) {
-        float2* cp = reinterpret_cast<float2*>(a.colpart + (((int64_t)b * a.ntm + tm128) * a.m + col) * 2);
+        float2* cp = reinterpret_cast<float2*>(a.colpart + (((int64_t)b * a.ntm + tm128) * a.cp_ld + col) * 2);
         *cp = make_float2(s, w);
       }
     }
@@ -433,7 +435,7 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
       }
       const int row = R0 + r;
       if (row < a.n && C0 < a.m) {
-        float2* rp = reinterpret_cast<float2*>(a.rowpart + (((int64_t)b * a.ntn + tn128) * a.n + row) * 2);
+        float2* rp = reinterpret_cast<float2*>(a.rowpart + (((int64_t)b * a.ntn + tn128) * a.rp_ld + row) * 2);
         *rp = make_float2(s, fmaf(32.f, u, w));
       }
     }

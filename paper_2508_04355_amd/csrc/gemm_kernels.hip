@@ -246,7 +246,7 @@ __global__ __launch_bounds__(THREADS) void gemm_kernel(GemmArgs a) {
 
   // ---- epilogue: the tile goes through LDS in two slabs of 64 rows -------------------------
   const bool epi = a.rowpart != nullptr;
-  float* rowpart_tile = epi ? a.rowpart + ((int64_t)b * a.ntn + tn) * a.n * 2 : nullptr;
+  float* rowpart_tile = epi ? a.rowpart + ((int64_t)b * a.ntn + tn) * a.rp_ld * 2 : nullptr;
   const bool vecC = (reinterpret_cast<uintptr_t>(C) % 16 == 0) && (a.ldc % 4 == 0);
   float cs = 0.f, cw = 0.f;
 #pragma unroll
@@ -272,7 +272,7 @@ __global__ __launch_bounds__(THREADS) void gemm_kernel(GemmArgs a) {
     slab_store<BN, SLAB>(Cs, slab * SLAB, tile_r0, tile_c0, a.n, a.m, C, a.ldc, vecC);
   }
   if (epi && tid < BN && tile_c0 + tid < a.m) {
-    float* cp = a.colpart + (((int64_t)b * a.ntm + tm) * a.m + tile_c0 + tid) * 2;
+    float* cp = a.colpart + (((int64_t)b * a.ntm + tm) * a.cp_ld + tile_c0 + tid) * 2;
     cp[0] = cs;
     cp[1] = cw;
   }
@@ -336,7 +336,7 @@ __global__ __launch_bounds__(THREADS) void partials_kernel(PartialArgs a) {
     for (int c = 0; c < 32; ++c) { s += red_row[0][tid][c]; w += red_row[1][tid][c]; }
     const int gi = tile_r0 + tid;
     if (gi < a.n) {
-      float2* rp = reinterpret_cast<float2*>(a.rowpart + (((int64_t)b * a.ntn + tn) * a.n + gi) * 2);
+      float2* rp = reinterpret_cast<float2*>(a.rowpart + (((int64_t)b * a.ntn + tn) * a.rp_ld + gi) * 2);
       *rp = make_float2(s, w);
     }
   } else {
@@ -346,7 +346,7 @@ __global__ __launch_bounds__(THREADS) void partials_kernel(PartialArgs a) {
     for (int g = 0; g < 8; ++g) { s += red_col[0][g][c]; w += red_col[1][g][c]; }
     const int gc = tile_c0 + c;
     if (gc < a.m) {
-      float2* cp = reinterpret_cast<float2*>(a.colpart + (((int64_t)b * a.ntm + tm) * a.m + gc) * 2);
+      float2* cp = reinterpret_cast<float2*>(a.colpart + (((int64_t)b * a.ntm + tm) * a.cp_ld + gc) * 2);
       *cp = make_float2(s, w);
     }
   }

@@ -195,26 +195,50 @@ __global__ __launch_bounds__(CD_THREADS) void coldot_stage1(ScanArgs a, int nchu
   for (int e = 0; e < VEC; ++e) { acc0[e] = 0.0; acc1[e] = 0.0; }
 
   if (nv == VEC && a.vec_ok) {
-    int r = rbeg + wave;
-    for (; r + 12 < rend; r += 16) {   // 4 rows in flight per wavefront
-      double v[4][VEC];
+    // Batches of CD_NB rows per wavefront, double buffered: the loads of the next batch are in
+    // flight while this one is added up (a wavefront walks its rows one batch after the other,
+    // so without this every batch would pay the full memory latency).
+    constexpr int CD_NB = 8;
+    typename E::raw xa[CD_NB], xb[CD_NB];
+    const T* col = X + c;
+    auto load = [&](typename E::raw* x, int rr) {
 #pragma unroll
-      for (int u = 0; u < 4; ++u) E::load_vec(X + (int64_t)(r + 4 * u) * a.ld + c, v[u]);
+      for (int u = 0; u < CD_NB; ++u) x[u] = E::load_raw(col + (int64_t)(rr + 4 * u) * a.ld);
+    };
+    auto add = [&](const typename E::raw* x, int rr) {
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int rr = r + 4 * u;
-        const double wa = IDXW ? 1.0 : w0[rr];
-        const double wb = IDXW ? (double)(rr + 1) : w1[rr];
+      for (int u = 0; u < CD_NB; ++u) {
+        double v[VEC];
+        E::widen(x[u], v);
+        const int row = rr + 4 * u;
+        const double wa = IDXW ? 1.0 : w0[row];
+        const double wb = IDXW ? (double)(row + 1) : w1[row];
 #pragma unroll
         for (int e = 0; e < VEC; ++e) {
-          acc0[e] = IDXW ? acc0[e] + v[u][e] : fma(wa, v[u][e], acc0[e]);
-          acc1[e] = fma(wb, v[u][e], acc1[e]);
+          acc0[e] = IDXW ? acc0[e] + v[e] : fma(wa, v[e], acc0[e]);
+          acc1[e] = fma(wb, v[e], acc1[e]);
         }
       }
+    };
+    int r = rbeg + wave;
+    const int cnt = r < rend ? (rend - r + 3) / 4 : 0;   // rows of this wavefront
+    const int nb = cnt / CD_NB;
+    constexpr int STEP = 4 * CD_NB;
+    if (nb > 0) {
+      load(xa, r);
+      int bi = 0;
+      for (; bi + 1 < nb; bi += 2) {
+        load(xb, r + STEP);
+        add(xa, r);
+        if (bi + 2 < nb) load(xa, r + 2 * STEP);
+        add(xb, r + STEP);
+        r += 2 * STEP;
+      }
+      if (bi < nb) { add(xa, r); r += STEP; }
     }
     for (; r < rend; r += 4) {
       double v[VEC];
-      E::load_vec(X + (int64_t)r * a.ld + c, v);
+      E::load_vec(col + (int64_t)r * a.ld, v);
       const double wa = IDXW ? 1.0 : w0[r];
       const double wb = IDXW ? (double)(r + 1) : w1[r];
 #pragma unroll
