@@ -11,7 +11,7 @@ namespace gecc {
 // tiles (the product kernel's own blocking, fixed when the context is created).
 
 // rows per chunk of the two-stage column reduction (scan kernels)
-constexpr int SCAN_CHUNK_ROWS = 256;
+constexpr int SCAN_CHUNK_ROWS = 128;
 
 // decoder phases kept in device memory (per batch item)
 enum : int { PH_DONE = 0, PH_AUDIT = 1, PH_REVERIFY = 2 };

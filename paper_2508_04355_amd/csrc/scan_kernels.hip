@@ -51,6 +51,7 @@ __device__ __forceinline__ bool gated_off(const int32_t* gate, int64_t stride, i
 // a thread keeps the weights of its VEC columns in registers and reuses them for the RB rows.
 constexpr int RD_THREADS = 256;
 constexpr int RD_BIG_RB = 16, RD_BIG_U = 1, RD_SMALL_RB = 4, RD_SMALL_U = 2;
+constexpr int RD_BIG_RB_W = 8;   // with explicit weights (they take registers too)
 
 // RD_RB rows per workgroup: 16 when there are rows enough to fill the chip, else 4.  RD_U column
 // steps are taken together, so that a thread has RD_RB * RD_U independent 16-byte loads in
@@ -105,6 +106,7 @@ __global__ __launch_bounds__(RD_THREADS) void rowdot_kernel(ScanArgs a) {
             acc0[r] = IDXW ? acc0[r] + v[e] : fma(wa[u][e], v[e], acc0[r]);
             acc1[r] = fma(wb[u][e], v[e], acc1[r]);
           }
+          __builtin_amdgcn_sched_barrier(0);   // widen one vector at a time (registers)
         }
       }
     }
@@ -321,11 +323,12 @@ hipError_t launch_rowdot(const ScanArgs& a0, hipStream_t st) {
   const bool small = (int64_t)((a.R + RD_BIG_RB - 1) / RD_BIG_RB) * a.batch < 1024;   // fewer than 4 workgroups per CU
 #define GECC_LAUNCH_ROWDOT(DT, IDX)                                                                  \
   do {                                                                                              \
+    constexpr int BIG = IDX ? RD_BIG_RB : RD_BIG_RB_W;                                                \
     if (small) hipLaunchKernelGGL((rowdot_kernel<DT, IDX, RD_SMALL_RB, RD_SMALL_U>),                  \
                                   dim3((a.R + RD_SMALL_RB - 1) / RD_SMALL_RB, a.batch),               \
                                   dim3(RD_THREADS), 0, st, a);                                        \
-    else       hipLaunchKernelGGL((rowdot_kernel<DT, IDX, RD_BIG_RB, RD_BIG_U>),                      \
-                                  dim3((a.R + RD_BIG_RB - 1) / RD_BIG_RB, a.batch),                   \
+    else       hipLaunchKernelGGL((rowdot_kernel<DT, IDX, BIG, RD_BIG_U>),                            \
+                                  dim3((a.R + BIG - 1) / BIG, a.batch),                               \
                                   dim3(RD_THREADS), 0, st, a);                                        \
   } while (0)
   if (a.dtype == GECC_BF16) {
