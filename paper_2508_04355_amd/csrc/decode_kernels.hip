@@ -45,11 +45,6 @@ __device__ __forceinline__ int64_t b_index(const gecc_params& p, int b, int l, i
 }
 
 // -------------------------------------------------------------------------------------------
-__device__ void reset_state(DecodeState* s) {
-  s->s_cnt = 0; s->t_cnt = 0;
-  s->phase = PH_DONE;
-  s->n_err = 0;
-}
 __global__ void reset_state_kernel(DecodeArgs a) {
   const int b = blockIdx.x * blockDim.x + threadIdx.x;
   if (b >= a.p.batch) return;
@@ -565,31 +560,6 @@ __global__ __launch_bounds__(256) void repair_kernel(DecodeArgs a) {
   }
 }
 
-// global parity block P_g = A_P B_P (Section III), 2 x 2 per batch item
-// (also resets the decoder state of its batch item for the verification that follows)
-__global__ __launch_bounds__(256) void pg_kernel(const double* A_par, const double* B_par,
-                                                 double* C_par, int n, int k, int m, DecodeState* state) {
-  const int b = blockIdx.x;
-  if (threadIdx.x == 0 && state) reset_state(state + b);
-  const double* ap = A_par + (int64_t)b * 2 * k;
-  const double* bp = B_par + (int64_t)b * 2 * k;
-  double acc[4] = {0, 0, 0, 0};
-  for (int l = threadIdx.x; l < k; l += 256) {
-    const double a0 = ap[l], a1 = ap[k + l], b0 = bp[l], b1 = bp[k + l];
-    acc[0] = fma(a0, b0, acc[0]); acc[1] = fma(a0, b1, acc[1]);
-    acc[2] = fma(a1, b0, acc[2]); acc[3] = fma(a1, b1, acc[3]);
-  }
-  __shared__ double red[4][256];
-  for (int q = 0; q < 4; ++q) red[q][threadIdx.x] = acc[q];
-  __syncthreads();
-  for (int w = 128; w > 0; w >>= 1) {
-    if ((int)threadIdx.x < w)
-      for (int q = 0; q < 4; ++q) red[q][threadIdx.x] += red[q][threadIdx.x + w];
-    __syncthreads();
-  }
-  if (threadIdx.x < 4) C_par[(int64_t)b * (2 * n + 2 * m + 4) + 2 * n + 2 * m + threadIdx.x] = red[threadIdx.x][0];
-}
-
 }  // namespace
 
 hipError_t launch_reset_state(const DecodeArgs& a, hipStream_t st) {
@@ -618,10 +588,5 @@ hipError_t launch_repair(const DecodeArgs& a, hipStream_t st) {
   return hipGetLastError();
 }
 
-hipError_t launch_pg(const double* A_par, const double* B_par, double* C_par, int n, int k, int m,
-                     int batch, DecodeState* state, hipStream_t st) {
-  hipLaunchKernelGGL(pg_kernel, dim3(batch), dim3(256), 0, st, A_par, B_par, C_par, n, k, m, state);
-  return hipGetLastError();
-}
 
 }  // namespace gecc

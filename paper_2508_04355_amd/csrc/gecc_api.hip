@@ -290,15 +290,17 @@ int gecc_multiply(gecc_ctx* ctx, const void* dev_A, const double* dev_A_par, con
   if ((e = reduce_a_over_k(ctx, dev_A, dev_B_par, dev_C_par, rec, st)) != hipSuccess) return hip_rc(e);
   if ((e = reduce_b_over_k(ctx, dev_B, dev_A_par, dev_C_par + 2 * (size_t)p.n, rec, st)) != hipSuccess)
     return hip_rc(e);
-  // P_g, and the decoder state is reset here for the fused verification that follows
-  if ((e = launch_pg(dev_A_par, dev_B_par, dev_C_par, p.n, p.k, p.m, p.batch,
-                     reinterpret_cast<DecodeState*>(ctx->ws + ctx->lay.state), st)) != hipSuccess)
-    return hip_rc(e);
   GemmArgs g = gemm_args(ctx, dev_A, dev_B, dev_C);
   g.rowpart = reinterpret_cast<float*>(ctx->ws + ctx->lay.rowpart);
   g.colpart = reinterpret_cast<float*>(ctx->ws + ctx->lay.colpart);
   g.faults = dev_faults;
   g.n_faults = n_faults;
+  // P_g is formed inside the product kernel, which also resets the decoder state for the
+  // fused verification that follows
+  g.A_par = dev_A_par; g.B_par = dev_B_par;
+  g.pg_out = dev_C_par + 2 * (size_t)p.n + 2 * (size_t)p.m;
+  g.pg_stride = rec;
+  g.state = reinterpret_cast<DecodeState*>(ctx->ws + ctx->lay.state);
   return hip_rc(timed_gemm(ctx, g, st));
 }
 

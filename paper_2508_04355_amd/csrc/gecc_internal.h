@@ -102,8 +102,54 @@ struct GemmArgs {
   int rp_ld, cp_ld;     // lines per sub-tile slab of rowpart / colpart (n, m plus padding)
   const gecc_fault* faults;
   int n_faults;
+  // protected product only: P_g = A_P B_P goes to pg_out[b * pg_stride + 0..3], formed by the
+  // workgroup of the first tile, which also resets the decoder state of its batch item
+  const double* A_par;
+  const double* B_par;
+  double* pg_out;
+  int64_t pg_stride;
+  DecodeState* state;
 };
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t st);
+
+#if defined(__HIPCC__)
+// counters, phase and error list of one batch item, as before any verification
+static __device__ __forceinline__ void reset_state(DecodeState* s) {
+  s->s_cnt = 0; s->t_cnt = 0;
+  s->phase = PH_DONE;
+  s->n_err = 0;
+}
+
+// Global parity block P_g = A_P B_P (Section III, 2 x 2) of batch item b, in fp64 and in a fixed
+// order; thread 0 also resets the item's decoder state.  Called by every thread of one
+// workgroup of at most 256 threads, after its last use of the 16 doubles at `lds`.
+static __device__ __forceinline__ void form_pg(const GemmArgs& a, int b, double* lds) {
+  const double* ap = a.A_par + (int64_t)b * 2 * a.k;
+  const double* bp = a.B_par + (int64_t)b * 2 * a.k;
+  double acc[4] = {0.0, 0.0, 0.0, 0.0};
+  for (int l = threadIdx.x; l < a.k; l += blockDim.x) {
+    const double a0 = ap[l], a1 = ap[a.k + l], b0 = bp[l], b1 = bp[a.k + l];
+    acc[0] = fma(a0, b0, acc[0]); acc[1] = fma(a0, b1, acc[1]);
+    acc[2] = fma(a1, b0, acc[2]); acc[3] = fma(a1, b1, acc[3]);
+  }
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) acc[q] += __shfl_down(acc[q], off, 64);
+  const int wave = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) lds[wave * 4 + q] = acc[q];
+  __syncthreads();
+  if (threadIdx.x < 4) {
+    double v = lds[threadIdx.x];
+    for (int w = 1; w < nw; ++w) v += lds[w * 4 + threadIdx.x];
+    a.pg_out[(int64_t)b * a.pg_stride + threadIdx.x] = v;
+  }
+  if (threadIdx.x == 0 && a.state) reset_state(a.state + b);
+}
+#endif
 // 256 x 256-tile bf16 kernel for aligned operands (gemm_bf16_kernels.hip)
 bool gemm_bf16_fast_ok(const GemmArgs& a);
 hipError_t launch_gemm_bf16_fast(const GemmArgs& a, hipStream_t st);
@@ -155,8 +201,5 @@ hipError_t launch_summarize(const DecodeArgs& a, hipStream_t st);
 hipError_t launch_decode_c(const DecodeArgs& a, int final_pass, int with_summary, hipStream_t st);
 // audit differences, operand patches, rank-one repair of C-bar
 hipError_t launch_repair(const DecodeArgs& a, hipStream_t st);
-// P_g = A_P B_P; state != null: also resets the decoder state (counters, phase) of every item
-hipError_t launch_pg(const double* A_par, const double* B_par, double* C_par, int n, int k, int m,
-                     int batch, DecodeState* state, hipStream_t st);
 
 }  // namespace gecc

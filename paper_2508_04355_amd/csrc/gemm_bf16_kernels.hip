@@ -439,6 +439,7 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
         *rp = make_float2(s, fmaf(32.f, u, w));
       }
     }
+    if (blockIdx.x == 0) form_pg(a, b, reinterpret_cast<double*>(smem));   // P_g, once per batch item
   }
 }
 
