@@ -556,6 +556,21 @@ __global__ __launch_bounds__(256) void repair_kernel(DecodeArgs a) {
     st->n_err = ne;
     st->s_cnt = 0;
     st->t_cnt = 0;
+    // strips of C whose partial sums the residual pass has to form again
+    int ntm = 0, ntn = 0;
+    for (int x = 0; x < na; ++x) {
+      const int t = ha[x].pos / a.tile_m;
+      bool seen = false;
+      for (int y = 0; y < ntm; ++y) seen = seen || st->tm_list[y] == t;
+      if (!seen) st->tm_list[ntm++] = t;
+    }
+    for (int x = 0; x < nb; ++x) {
+      const int t = hb[x].pos / a.tile_n;
+      bool seen = false;
+      for (int y = 0; y < ntn; ++y) seen = seen || st->tn_list[y] == t;
+      if (!seen) st->tn_list[ntn++] = t;
+    }
+    st->n_tm = ntm; st->n_tn = ntn;
     st->phase = PH_REVERIFY;
   }
 }

@@ -350,6 +350,7 @@ int correct_impl(gecc_ctx* ctx, void* dev_A, const double* dev_A_par, void* dev_
   pa.tile_m = ctx->tile_m; pa.tile_n = ctx->tile_n; pa.ntm = ctx->ntm; pa.ntn = ctx->ntn;
   pa.rp_ld = ctx->rp_ld; pa.cp_ld = ctx->cp_ld;
   pa.gate = gate; pa.gate_stride = sizeof(DecodeState); pa.gate_value = PH_REVERIFY;
+  pa.strips = d.state;   // only the strips of C the repair wrote to
   if ((e = launch_partials(pa, st)) != hipSuccess) return hip_rc(e);
   if ((e = launch_threshold(d, 0, st)) != hipSuccess) return hip_rc(e);
   return hip_rc(launch_decode_c(d, 1, 0, st));

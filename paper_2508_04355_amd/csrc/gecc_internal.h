@@ -29,6 +29,9 @@ struct DecodeState {
   // decoder
   int32_t phase;
   int32_t n_err;              // operand errors already accepted by the audit
+  // 128-row / 128-column strips of C that the repair touched (the residual pass re-sums only these)
+  int32_t n_tm, n_tn;
+  int32_t tm_list[GECC_MAX_ERR], tn_list[GECC_MAX_ERR];
   gecc_err errs[GECC_MAX_ERR];
 };
 
@@ -118,6 +121,7 @@ static __device__ __forceinline__ void reset_state(DecodeState* s) {
   s->s_cnt = 0; s->t_cnt = 0;
   s->phase = PH_DONE;
   s->n_err = 0;
+  s->n_tm = 0; s->n_tn = 0;
 }
 
 // Global parity block P_g = A_P B_P (Section III, 2 x 2) of batch item b, in fp64 and in a fixed
@@ -166,6 +170,9 @@ struct PartialArgs {
   const int32_t* gate;
   int64_t gate_stride;
   int gate_value;
+  // null: every sub-tile.  Else the DecodeState of batch item 0 (stride gate_stride): only the
+  // sub-tiles in the strips its tm_list / tn_list name
+  const DecodeState* strips;
 };
 hipError_t launch_partials(const PartialArgs& a, hipStream_t st);
 
