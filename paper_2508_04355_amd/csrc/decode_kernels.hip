@@ -414,7 +414,9 @@ __device__ void sort_hits(AuditHit* h, int cnt) {
 // A hits first, using B as the product read it; then columns of the B hits, using the
 // corrected A.  The operands themselves are written last, so nothing here depends on a
 // store becoming visible to another wavefront.
-__global__ __launch_bounds__(256) void repair_kernel(DecodeArgs a) {
+constexpr int RP_THREADS = 1024;   // one workgroup per batch item: latency-bound loops, so a full one
+
+__global__ __launch_bounds__(RP_THREADS) void repair_kernel(DecodeArgs a) {
   const int b = blockIdx.x;
   DecodeState* st = state_of(a, b);
   if (st->phase != PH_AUDIT) return;
@@ -462,7 +464,7 @@ __global__ __launch_bounds__(256) void repair_kernel(DecodeArgs a) {
   double* al_q1 = al_r1 + 2 * n;
   double* al_q2 = al_r1 + 2 * n + m;
   const double cc = a.p.tau_rep * sqrt((double)k);
-  __shared__ double red[2][256];
+  __shared__ double red[2][RP_THREADS];
   for (int o = threadIdx.x; o < 2 * n + 2 * m; o += blockDim.x) al_r1[o] = 0.0;
   __syncthreads();
   for (int x = 0; x < na; ++x) {
@@ -484,7 +486,7 @@ __global__ __launch_bounds__(256) void repair_kernel(DecodeArgs a) {
     }
     red[0][threadIdx.x] = s2; red[1][threadIdx.x] = w2;
     __syncthreads();
-    for (int w = 128; w > 0; w >>= 1) {
+    for (int w = RP_THREADS / 2; w > 0; w >>= 1) {
       if ((int)threadIdx.x < w) { red[0][threadIdx.x] += red[0][threadIdx.x + w]; red[1][threadIdx.x] += red[1][threadIdx.x + w]; }
       __syncthreads();
     }
@@ -513,7 +515,7 @@ __global__ __launch_bounds__(256) void repair_kernel(DecodeArgs a) {
     }
     red[0][threadIdx.x] = s2; red[1][threadIdx.x] = w2;
     __syncthreads();
-    for (int w = 128; w > 0; w >>= 1) {
+    for (int w = RP_THREADS / 2; w > 0; w >>= 1) {
       if ((int)threadIdx.x < w) { red[0][threadIdx.x] += red[0][threadIdx.x + w]; red[1][threadIdx.x] += red[1][threadIdx.x + w]; }
       __syncthreads();
     }
@@ -599,7 +601,7 @@ hipError_t launch_decode_c(const DecodeArgs& a, int final_pass, int with_summary
 }
 
 hipError_t launch_repair(const DecodeArgs& a, hipStream_t st) {
-  hipLaunchKernelGGL(repair_kernel, dim3(a.p.batch), dim3(256), 0, st, a);
+  hipLaunchKernelGGL(repair_kernel, dim3(a.p.batch), dim3(RP_THREADS), 0, st, a);
   return hipGetLastError();
 }
 
