@@ -27,7 +27,10 @@ def _trial(rng, n, k, m, dtype, law_a, law_b, faults):
 
 
 # ---------------------------------------------------------------------------------------------
-SHAPES = [(128, 128, 128), (1, 1, 1), (3, 5, 2), (130, 70, 257), (300, 200, 260), (257, 1031, 129)]
+# the last two reach the 256 x 256-tile bf16 kernel (k % 64 == 0, rows of 8 elements) with ragged
+# tiles on both edges; everything else goes to the generic kernel
+SHAPES = [(128, 128, 128), (1, 1, 1), (3, 5, 2), (130, 70, 257), (300, 200, 260), (257, 1031, 129),
+          (520, 256, 264), (1000, 320, 776)]
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -52,6 +55,28 @@ def test_clean_product_blocks_match_the_oracle(shape, trans, dtype):
     # syndromes (fp32 sums of an fp32 product) stay far inside the thresholds
     mx = g.reports[0].max_abs_synd
     assert mx[0] <= tau.r1 / 2 and mx[1] <= tau.r2 / 2 and mx[2] <= tau.q1 / 2 and mx[3] <= tau.q2 / 2
+
+
+@pytest.mark.parametrize("trans", [(0, 0), (0, 1), (1, 0), (1, 1)])
+@pytest.mark.parametrize("pattern", ["C+C on the edges", "A+C", "B+C", "A+B"])
+def test_ragged_tiles_of_the_fast_bf16_kernel_with_errors(pattern, trans):
+    """Faults in the last row / column of C and of the operands, where the 256 x 256 tiles of the
+    bf16 kernel hang over the edge (range-checked stores, zero-filled operand rows)."""
+    n, k, m = 520, 256, 264
+    rng = inputs.rng_for(92, 0)
+    law = ("normal", 1.0)
+    faults = {"C+C on the edges": [inputs.Fault(MAT_C, n - 1, m - 1, 37.5), inputs.Fault(MAT_C, 256, 0, -12.25)],
+              "A+C": [inputs.Fault(MAT_A, n - 1, k - 1, 3.0), inputs.Fault(MAT_C, 0, m - 1, 55.0)],
+              "B+C": [inputs.Fault(MAT_B, k - 1, m - 1, -2.5), inputs.Fault(MAT_C, n - 1, 257, 9.0)],
+              "A+B": [inputs.Fault(MAT_A, 512, 0, 4.0), inputs.Fault(MAT_B, 0, 256, 6.0)]}[pattern]
+    A, B, A2, B2, cf, eff = _trial(rng, n, k, m, "bf16", law, law, faults)
+    tau = gecc.noise_thresholds(n, k, m, 1.0, 1.0)
+    cfb = [(0,) + c for c in cf]
+    g = H.run_gpu(A, B, A2, B2, cfb, tau, "bf16", trans[0], trans[1])
+    o = H.run_oracle(A, B, A2, B2, cfb, tau)
+    H.compare(g, o, 1e-5, what="ragged fast kernel, %s, trans %s" % (pattern, trans))
+    assert g.reports[0].status == gecc.CORRECTED
+    assert [(e[0], e[1], e[2]) for e in g.reports[0].errors()] == [(e[0], e[1], e[2]) for e in eff]
 
 
 def test_unaligned_leading_dimensions_take_the_scalar_paths():
