@@ -16,6 +16,10 @@ What follows the paper directly
   * syndromes / detect       -- Section V step 1, the four threshold tests.
   * d0_correct               -- Section V step 2 (s = 1 rule, 2x2 system for
                                 s = 2, "without loss of generality s <= t").
+  * known_lines_correct      -- Theorem 2 and its proof (Appendix B): errors in
+                                any number of columns are corrected from the
+                                column parities once they are confined to at
+                                most two known rows (and the mirror image).
   * global_syndromes         -- Definition 1, constraint (3) (used by the
                                 Lemma 3 rank pin only; the decoder of
                                 Section V never reads P_g).
@@ -56,6 +60,14 @@ the design notes of the repository):
     estimate is verified, every syndrome y is therefore trusted to
     tau + rel * |y| instead of tau.  Detection itself uses tau alone, and
     rel = 0 gives the plain rule.
+  * Theorem 2 asks for the rows (columns) of the errors to be "known"; the
+    only knowledge the decoder has is Section V step 1, so the at most two
+    flagged rows are taken as the known rows when three or more columns are
+    flagged (and the other way round).  A row whose own two syndromes vanish
+    although it holds errors (the construction of Section IV) is not known;
+    then the verification fails and nothing is corrected.
+  * the located-error list of a result is complete here; the library's
+    report carries the first MAX_REPORTED entries and the total.
   * for s = t = 2 the 2x2 systems are first evaluated under the two sparse
     hypotheses "one error per flagged column" (a column with a single error
     is the s = 1 rule applied to that column); in exact arithmetic this
@@ -75,7 +87,7 @@ import numpy as np
 
 CLEAN, CORRECTED, UNCORRECTABLE = 0, 1, 2
 MAT_A, MAT_B, MAT_C = 0, 1, 2
-MAX_REPORTED = 8          # capacity of the located-error list
+MAX_REPORTED = 8          # operand errors one audit accepts; entries the library's report lists
 
 
 @dataclass
@@ -285,6 +297,46 @@ def d0_correct(r1, r2, q1, q2, Er, Et, tau):
     return accept([(i, Et[0], r1[i], tau.r1[i]) for i in Er])
 
 
+def known_lines_correct(r1, r2, q1, q2, Er, Et, tau):
+    """Theorem 2 (proof in Appendix B): min(s, t) <= 2 < max(s, t).
+
+    The lines on the short side are the known ones.  With the rows known,
+    every flagged column j is decoded on its own from its two column
+    syndromes: one known row s1 gives e_{s1,j} = q1_j, two known rows give
+    the 2x2 system of Section V; columns known: the mirror image with the row
+    syndromes.  The estimates are verified like those of d0_correct.
+    Returns [(i, j, x)] or None.
+    """
+    s, t = len(Er), len(Et)
+    assert 1 <= min(s, t) <= 2 < max(s, t)
+    tau = tau.trusted_to(r1, r2, q1, q2)
+    if s <= 2:
+        known, lines, y1, y2, u1_, u2_ = Er, Et, q1, q2, tau.q1, tau.q2
+        at = lambda line, kn: (kn, line)
+    else:
+        known, lines, y1, y2, u1_, u2_ = Et, Er, r1, r2, tau.r1, tau.r2
+        at = lambda line, kn: (line, kn)
+    est = []
+    if len(known) == 1:
+        for c in lines:
+            i, j = at(c, known[0])
+            est.append((i, j, y1[c], u1_[c]))
+    else:
+        w1, w2 = known[0] + 1.0, known[1] + 1.0
+        for c in lines:
+            e1, e2 = solve_2x2(w1, w2, y1[c], y2[c])
+            ub = (u2_[c] + w1 * u1_[c]) / (w2 - w1)
+            ua = u1_[c] + ub
+            i, j = at(c, known[0])
+            est.append((i, j, e1, ua))
+            i, j = at(c, known[1])
+            est.append((i, j, e2, ub))
+    est = [e for e in est if abs(e[2]) > e[3]]           # drop insignificant parts
+    if _residual_ok(est, r1, r2, q1, q2, Er, Et, tau):
+        return sorted((i, j, x) for (i, j, x, u) in est)
+    return None
+
+
 # ------------------------------------------------------- completion D1: audit
 def audit_a(A, AP, tau_op):
     """Re-form the parity rows of A and compare with the stored ones.
@@ -353,12 +405,15 @@ def decode(Cbar, A, AP, B, BP, tau):
     if s0 == 0 and t0 == 0:
         return done(CLEAN, [])
 
+    fix = None
     if 1 <= s0 <= 2 and 1 <= t0 <= 2:
         fix = d0_correct(r1, r2, q1, q2, Er, Et, LineThresholds(tau, n, m))
-        if fix is not None:
-            for (i, j, x) in fix:
-                Cbar[i, j] -= x
-            return done(CORRECTED, [(MAT_C, i, j, x) for (i, j, x) in fix])
+    elif 1 <= min(s0, t0) <= 2:
+        fix = known_lines_correct(r1, r2, q1, q2, Er, Et, LineThresholds(tau, n, m))
+    if fix is not None:
+        for (i, j, x) in fix:
+            Cbar[i, j] -= x
+        return done(CORRECTED, [(MAT_C, i, j, x) for (i, j, x) in fix])
 
     # D1: operand audit, patch, rank-one repair, then Section V on the rest
     okA, LA = audit_a(A, AP, tau.op)
@@ -395,12 +450,15 @@ def decode(Cbar, A, AP, B, BP, tau):
     s, t = len(Er), len(Et)
     if s == 0 and t == 0:
         return done(CORRECTED, errs)
+    fix = None
     if 1 <= s <= 2 and 1 <= t <= 2:
         fix = d0_correct(r1, r2, q1, q2, Er, Et, tau2)
-        if fix is not None and len(errs) + len(fix) <= MAX_REPORTED:
-            for (i, j, x) in fix:
-                Cbar[i, j] -= x
-            return done(CORRECTED, errs + [(MAT_C, i, j, x) for (i, j, x) in fix])
+    elif 1 <= min(s, t) <= 2:
+        fix = known_lines_correct(r1, r2, q1, q2, Er, Et, tau2)
+    if fix is not None:
+        for (i, j, x) in fix:
+            Cbar[i, j] -= x
+        return done(CORRECTED, errs + [(MAT_C, i, j, x) for (i, j, x) in fix])
     return done(UNCORRECTABLE, [])
 
 

@@ -356,3 +356,96 @@ def test_real_valued_correction_matches_independent_product():
     assert [(e[0], e[1], e[2]) for e in res.errors] == [(MAT_A, 7, 3), (MAT_C, 20, 41)]
     assert np.allclose([e[3] for e in res.errors], [11.5, -3.25], rtol=0, atol=1e-9)
     assert np.max(np.abs(res.C - ref)) < 1e-9 and np.max(np.abs(res.A - A)) < 1e-12
+
+
+# ---- Theorem 2: any number of errors confined to at most two known rows (columns) ---------------
+def _row_known(pattern_row, cols):
+    """A row is known to Section V step 1 iff one of its two syndromes is nonzero."""
+    e = dict(zip(cols, pattern_row))
+    return sum(e.values()) != 0 or sum((j + 1) * x for j, x in e.items()) != 0
+
+
+@pytest.mark.parametrize("transpose", [False, True])
+def test_theorem2_errors_in_one_or_two_known_lines_and_three_or_more_of_the_other_kind(transpose):
+    """Every pattern with entries from {0, 1, -2, 3} on one row and 4 columns, from {0, 1, -2} on two rows
+    and 3 columns of a 4 x 5
+    product (and the mirror image): corrected exactly from the parities of the other direction
+    whenever each of the rows is flagged by its own syndromes; never corrected wrongly otherwise."""
+    n, k, m = (5, 3, 4) if transpose else (4, 3, 5)
+    A, B = int_mats(31, n, k, m)
+    AP, BP = oc.encode_a(A), oc.encode_b(B)
+    clean = oc.encoded_product(A, AP, B, BP)
+    vals = (0, 1, -2, 3)
+    nlines, nother = (m, n) if transpose else (n, m)       # known lines are rows unless transposed
+    corrected = rejected = 0
+    for nk in (1, 2):
+        for known in itertools.combinations(range(nlines), nk):
+            for others in itertools.combinations(range(nother), 3 if nk == 2 else 4):
+                for mags in itertools.product(vals if nk == 1 else vals[:3], repeat=nk * len(others)):
+                    M = np.array(mags).reshape(nk, len(others))
+                    if not all(M[:, c].any() for c in range(len(others))):
+                        continue                            # fewer than 3 lines of the other kind
+                    if not all(M[r].any() for r in range(nk)):
+                        continue
+                    faults = []
+                    for r, kn in enumerate(known):
+                        for c, ot in enumerate(others):
+                            if M[r, c]:
+                                faults.append((ot, kn, float(M[r, c])) if transpose else (kn, ot, float(M[r, c])))
+                    all_known = all(_row_known(M[r], others) for r in range(nk))
+                    Cbar = clean.copy()
+                    oc.inject_c(Cbar, faults)
+                    res = oc.decode(Cbar, A, AP, B, BP, TAU0)
+                    if all_known:
+                        assert res.status == CORRECTED, (faults,)
+                        assert np.array_equal(res.Cbar, clean), (faults,)
+                        assert [(i, j) for (_, i, j, _) in res.errors] == sorted((i, j) for (i, j, _) in faults)
+                        assert np.allclose([x for (*_, x) in res.errors], [e for (_, _, e) in sorted(faults)])
+                        corrected += 1
+                    else:
+                        # a row whose sums cancel is invisible to step 1: the rows are not "known"
+                        assert res.status != CORRECTED or np.array_equal(res.Cbar, clean), (faults,)
+                        rejected += 1
+    assert corrected > 5000 and rejected > 0
+
+
+def test_theorem2_one_known_row_is_the_column_parity_rule():
+    """Appendix B, case s = 1: the error in column j of the known row is that column's plain
+    syndrome; checked against the injected values on a real-valued product."""
+    rng = np.random.default_rng(5)
+    n, k, m = 9, 6, 40
+    A, B = rng.normal(size=(n, k)), rng.normal(size=(k, m))
+    AP, BP = oc.encode_a(A), oc.encode_b(B)
+    clean = oc.encoded_product(A, AP, B, BP)
+    cols = list(range(3, 33, 2))
+    e = rng.uniform(1.0, 5.0, size=len(cols)) * rng.choice([-1.0, 1.0], size=len(cols))
+    Cbar = clean.copy()
+    oc.inject_c(Cbar, [(4, j, x) for j, x in zip(cols, e)])
+    r1, r2, q1, q2 = oc.syndromes(Cbar)
+    assert np.allclose(q1[cols], e) and np.allclose(q2[cols], 5 * e)
+    res = oc.decode(Cbar, A, AP, B, BP, Thresholds(1e-9, 1e-9, 1e-9, 1e-9))
+    assert res.status == CORRECTED and res.s == 1 and res.t == len(cols)
+    assert [(i, j) for (_, i, j, _) in res.errors] == [(4, j) for j in cols]
+    assert np.allclose(res.Cbar, clean, atol=1e-12)
+
+
+def test_theorem2_does_not_reach_three_by_three():
+    """min(s, t) = 3: outside Theorem 2 (Lemma 3 shows that even known lines do not help)."""
+    n, k, m = 6, 3, 6
+    A, B = int_mats(33, n, k, m)
+    AP, BP = oc.encode_a(A), oc.encode_b(B)
+    Cbar = oc.encoded_product(A, AP, B, BP)
+    oc.inject_c(Cbar, [(0, 0, 1.0), (1, 1, 2.0), (2, 2, 3.0)])
+    assert oc.decode(Cbar, A, AP, B, BP, TAU0).status == UNCORRECTABLE
+
+
+def test_theorem2_operand_errors_still_go_through_the_audit():
+    """An error in A corrupts a whole row of C but leaves that row's own syndromes at zero
+    (s = 0): no known row, so the column flags alone must not be decoded by Theorem 2."""
+    n, k, m = 5, 4, 7
+    A, B = int_mats(34, n, k, m)
+    AP, BP = oc.encode_a(A), oc.encode_b(B)
+    res = _run_faults(A, B, AP, BP, [(MAT_A, 2, 1, 3.0), (MAT_C, 0, 4, 2.0)])
+    assert res.status == CORRECTED
+    assert [(mt, i, j) for (mt, i, j, _) in res.errors] == [(MAT_A, 2, 1), (MAT_C, 0, 4)]
+    assert res.t >= 3 and res.s == 1
