@@ -103,6 +103,10 @@ typedef struct {
   int32_t n_err;             /* entries used in err[], sorted by (matrix, row, col)       */
   gecc_err err[GECC_MAX_ERR];
   double max_abs_synd[4];    /* max |r1|, |r2|, |q1|, |q2| at first detection             */
+  int32_t n_total;           /* located errors in all; err[] lists the first n_err of them
+                                (more than GECC_MAX_ERR only for the patterns of Theorem 2:
+                                many errors in at most two rows or columns of C)           */
+  int32_t reserved;
 } gecc_report;
 
 /* a fault to be planted into the product while it is computed (E3 of Section II-A):

@@ -167,6 +167,8 @@ __device__ int summarize(const DecodeArgs& a, int b, const DecodeState* st, gecc
     rep->s = st->s_cnt;
     rep->t = st->t_cnt;
     rep->n_err = 0;
+    rep->n_total = 0;
+    rep->reserved = 0;
     for (int f = 0; f < 4; ++f) {
       double v = smx[0][f];
       for (int w = 1; w < nw; ++w) v = fmax(v, smx[w][f]);
@@ -306,6 +308,122 @@ __device__ double block_dot(const DecodeArgs& a, int b, int i, int j, double* re
   return r;
 }
 
+// Theorem 2 (Appendix B): min(s, t) <= 2 < max(s, t).  The at most two flagged lines of the
+// short side are the known lines; every flagged line c of the other kind is decoded on its own
+// from its two syndromes (one known line: e = y1_c; two: the 2x2 system of Section V), the
+// estimates are verified against every flagged line like those of d0_correct, and Section V's
+// subtraction is applied.  All threads of the workgroup take part: thread x owns a contiguous
+// chunk of the other-kind lines.  Returns the number of corrected symbols, or -1.
+struct LineEst { double x[2], u[2]; bool sig[2], flagged; };
+
+__device__ int known_lines_correct(const DecodeArgs& a, int b, DecodeState* st, gecc_report* rep,
+                                   const Synd& y, int final_pass) {
+  const int n = a.p.n, m = a.p.m;
+  const int s = st->s_cnt, t = st->t_cnt;
+  const bool rows_known = s <= 2;
+  const int nk = rows_known ? s : t;
+  const int L = rows_known ? m : n;
+  int K[2] = {0, 0};
+  for (int q = 0; q < nk; ++q) K[q] = rows_known ? st->rows[q] : st->cols[q];
+  if (nk == 2 && K[0] > K[1]) { const int z = K[0]; K[0] = K[1]; K[1] = z; }
+  const double w1 = K[0] + 1.0, w2 = K[1] + 1.0;
+  const double *y1 = rows_known ? y.q1 : y.r1, *y2 = rows_known ? y.q2 : y.r2;
+  const double b1 = rows_known ? y.b_q1 : y.b_r1, b2 = rows_known ? y.b_q2 : y.b_r2;
+  const double *a1 = rows_known ? y.a_q1 : y.a_r1, *a2 = rows_known ? y.a_q2 : y.a_r2;
+
+  auto estimate = [&](int c) {
+    LineEst e;
+    e.flagged = fabs(y1[c]) > b1 + (a1 ? a1[c] : 0.0) || fabs(y2[c]) > b2 + (a2 ? a2[c] : 0.0);
+    e.sig[0] = e.sig[1] = false; e.x[0] = e.x[1] = e.u[0] = e.u[1] = 0.0;
+    if (!e.flagged) return e;
+    const double u1 = rows_known ? y.tq1(c) : y.tr1(c), u2 = rows_known ? y.tq2(c) : y.tr2(c);
+    if (nk == 1) {
+      e.x[0] = y1[c]; e.u[0] = u1;
+    } else {
+      e.x[1] = (y2[c] - w1 * y1[c]) / (w2 - w1);
+      e.x[0] = y1[c] - e.x[1];
+      e.u[1] = (u2 + w1 * u1) / (w2 - w1);
+      e.u[0] = u1 + e.u[1];
+    }
+    for (int q = 0; q < nk; ++q) e.sig[q] = fabs(e.x[q]) > e.u[q];   // insignificant parts are dropped
+    return e;
+  };
+
+  __shared__ double t2_red[8][256];
+  __shared__ int t2_cnt[2][256];
+  __shared__ int t2_bad;
+  const int tid = threadIdx.x, ch = (L + (int)blockDim.x - 1) / (int)blockDim.x;
+  const int c0 = min(L, tid * ch), c1 = min(L, c0 + ch);
+  if (tid == 0) t2_bad = 0;
+  __syncthreads();
+  double acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};   // per known line: sum x, sum u, weighted sum x, weighted sum u
+  int cnt[2] = {0, 0};
+  bool bad = false;
+  for (int c = c0; c < c1; ++c) {
+    const LineEst e = estimate(c);
+    if (!e.flagged) continue;
+    // this line's own two syndromes
+    double sx = 0, su = 0, wx = 0, wu = 0;
+    for (int q = 0; q < nk; ++q)
+      if (e.sig[q]) {
+        const double w = K[q] + 1.0;
+        sx += e.x[q]; su += e.u[q]; wx += w * e.x[q]; wu += w * e.u[q];
+        acc[4 * q + 0] += e.x[q]; acc[4 * q + 1] += e.u[q];
+        acc[4 * q + 2] += (c + 1.0) * e.x[q]; acc[4 * q + 3] += (c + 1.0) * e.u[q];
+        ++cnt[q];
+      }
+    const double u1 = rows_known ? y.tq1(c) : y.tr1(c), u2 = rows_known ? y.tq2(c) : y.tr2(c);
+    bad = bad || fabs(y1[c] - sx) > u1 + su || fabs(y2[c] - wx) > u2 + wu;
+  }
+  for (int q = 0; q < 8; ++q) t2_red[q][tid] = acc[q];
+  t2_cnt[0][tid] = cnt[0]; t2_cnt[1][tid] = cnt[1];
+  if (bad) t2_bad = 1;
+  __syncthreads();
+  if (tid == 0) {
+    // the known lines' own syndromes against everything attributed to them
+    for (int q = 0; q < nk; ++q) {
+      double v[4] = {0, 0, 0, 0};
+      for (int x = 0; x < (int)blockDim.x; ++x)
+        for (int f = 0; f < 4; ++f) v[f] += t2_red[4 * q + f][x];
+      const int line = K[q];
+      const double z1 = rows_known ? y.r1[line] : y.q1[line], z2 = rows_known ? y.r2[line] : y.q2[line];
+      const double tz1 = rows_known ? y.tr1(line) : y.tq1(line), tz2 = rows_known ? y.tr2(line) : y.tq2(line);
+      if (fabs(z1 - v[0]) > tz1 + v[1] || fabs(z2 - v[2]) > tz2 + v[3]) t2_bad = 1;
+    }
+  }
+  __syncthreads();
+  if (t2_bad) return -1;
+  // position of this thread's entries in the list sorted by (row, column)
+  int before[2] = {0, 0}, total[2] = {0, 0};
+  for (int x = 0; x < (int)blockDim.x; ++x)
+    for (int q = 0; q < 2; ++q) {
+      if (x < tid) before[q] += t2_cnt[q][x];
+      total[q] += t2_cnt[q][x];
+    }
+  const int ne0 = st->n_err;                  // operand errors of the audit come first
+  int idx[2];
+  if (rows_known) { idx[0] = before[0]; idx[1] = total[0] + before[1]; }     // row K0 first, then row K1
+  else            { idx[0] = idx[1] = before[0] + before[1]; }               // row by row
+  float* C = a.C + (int64_t)b * a.p.stride_c;
+  for (int c = c0; c < c1; ++c) {
+    const LineEst e = estimate(c);
+    if (!e.flagged) continue;
+    for (int q = 0; q < nk; ++q)
+      if (e.sig[q]) {
+        const int i = rows_known ? K[q] : c, j = rows_known ? c : K[q];
+        const int64_t ic = (int64_t)i * a.p.ldc + j;
+        C[ic] = (float)((double)C[ic] - e.x[q]);
+        const int pos = ne0 + (rows_known ? idx[q]++ : idx[0]++);
+        if (pos < GECC_MAX_ERR) {
+          gecc_err g;
+          g.matrix = GECC_MAT_C; g.row = i; g.col = j; g.reserved = 0; g.magnitude = e.x[q];
+          rep->err[pos] = g;
+        }
+      }
+  }
+  return total[0] + total[1];
+}
+
 // One workgroup per batch item.  final_pass = 0: right after detection (with_summary: this
 // kernel also writes the first report, saving the summary launch); = 1: after the operand audit
 // and the residual syndrome pass.
@@ -325,6 +443,30 @@ __global__ __launch_bounds__(256) void decode_c_kernel(DecodeArgs a, int final_p
   __shared__ int nfix;          // -1: the rule does not apply / failed
   __shared__ double red[256];
   const int n = a.p.n, m = a.p.m;
+  {
+    const int s = st->s_cnt, t = st->t_cnt, lo = min(s, t), hi = max(s, t);
+    if (lo >= 1 && lo <= 2 && hi > 2) {       // Theorem 2: many lines of one kind, at most two of the other
+      const double* sy = synd_of(a, b);
+      const double* al = final_pass ? allow_of(a, b) : nullptr;
+      const Synd y{sy, sy + n, sy + 2 * n, sy + 2 * n + m, a.p.tau_r1, a.p.tau_r2, a.p.tau_q1, a.p.tau_q2,
+                   al, al ? al + n : nullptr, al ? al + 2 * n : nullptr, al ? al + 2 * n + m : nullptr,
+                   a.p.tau_rel};
+      const int k = known_lines_correct(a, b, st, rep, y, final_pass);
+      if (threadIdx.x == 0) {
+        if (k < 0) {
+          if (final_pass) { rep->status = GECC_UNCORRECTABLE; rep->n_err = 0; rep->n_total = 0; st->phase = PH_DONE; }
+          else            { st->phase = PH_AUDIT; }
+        } else {
+          for (int e = 0; e < st->n_err; ++e) rep->err[e] = st->errs[e];
+          rep->n_total = st->n_err + k;
+          rep->n_err = min(rep->n_total, GECC_MAX_ERR);
+          rep->status = GECC_CORRECTED;
+          st->phase = PH_DONE;
+        }
+      }
+      return;
+    }
+  }
   if (threadIdx.x == 0) {
     const int s = st->s_cnt, t = st->t_cnt;
     nfix = -1;
@@ -343,7 +485,7 @@ __global__ __launch_bounds__(256) void decode_c_kernel(DecodeArgs a, int final_p
              a.p.tau_rel};
       Est tmp[4];
       const int k = d0_correct(tmp, Er, s, Et, t, y);
-      if (k >= 0 && st->n_err + k <= GECC_MAX_ERR) {
+      if (k >= 0) {
         for (int e = 0; e < k; ++e) fix[e] = tmp[e];
         nfix = k;
       }
@@ -353,7 +495,7 @@ __global__ __launch_bounds__(256) void decode_c_kernel(DecodeArgs a, int final_p
   const int k = nfix;
   if (k < 0) {
     if (threadIdx.x == 0) {
-      if (final_pass) { rep->status = GECC_UNCORRECTABLE; rep->n_err = 0; st->phase = PH_DONE; }
+      if (final_pass) { rep->status = GECC_UNCORRECTABLE; rep->n_err = 0; rep->n_total = 0; st->phase = PH_DONE; }
       else            { st->phase = PH_AUDIT; }
     }
     return;
@@ -371,13 +513,15 @@ __global__ __launch_bounds__(256) void decode_c_kernel(DecodeArgs a, int final_p
   }
   if (threadIdx.x == 0) {
     int ne = 0;
-    for (int e = 0; e < st->n_err; ++e) rep->err[ne++] = st->errs[e];   // A then B, sorted
-    for (int e = 0; e < k; ++e) {
+    for (int e = 0; e < st->n_err; ++e) rep->err[ne++] = st->errs[e];   // A then B, sorted (at most 8)
+    const int total = ne + k;
+    for (int e = 0; e < k && ne < GECC_MAX_ERR; ++e) {
       gecc_err g;
       g.matrix = GECC_MAT_C; g.row = fix[e].i; g.col = fix[e].j; g.reserved = 0;
       g.magnitude = fix[e].x;
       rep->err[ne++] = g;
     }
+    rep->n_total = total;
     rep->n_err = ne;
     rep->status = GECC_CORRECTED;
     st->phase = PH_DONE;
@@ -451,7 +595,7 @@ __global__ __launch_bounds__(RP_THREADS) void repair_kernel(DecodeArgs a) {
   }
   __syncthreads();
   if (!ok) {
-    if (threadIdx.x == 0) { rep->status = GECC_UNCORRECTABLE; rep->n_err = 0; st->phase = PH_DONE; }
+    if (threadIdx.x == 0) { rep->status = GECC_UNCORRECTABLE; rep->n_err = 0; rep->n_total = 0; st->phase = PH_DONE; }
     return;
   }
   float* C = a.C + (int64_t)b * a.p.stride_c;

@@ -38,7 +38,8 @@ class Err(C.Structure):
 
 class Report(C.Structure):
     _fields_ = [("status", C.c_int32), ("s", C.c_int32), ("t", C.c_int32), ("n_err", C.c_int32),
-                ("err", Err * MAX_ERR), ("max_abs_synd", C.c_double * 4)]
+                ("err", Err * MAX_ERR), ("max_abs_synd", C.c_double * 4),
+                ("n_total", C.c_int32), ("reserved", C.c_int32)]
 
     def errors(self) -> List[Tuple[int, int, int, float]]:
         return [(e.matrix, e.row, e.col, e.magnitude) for e in list(self.err)[:self.n_err]]

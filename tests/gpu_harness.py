@@ -111,7 +111,9 @@ def compare(g: GpuResult, o: List[oc.Result], tol_c: float, tol_mag: float = Non
         assert rep.status == res.status, (tag, rep.status, res.status, rep.errors(), res.errors)
         if res.status == oc.UNCORRECTABLE:
             continue
-        ge, oe = rep.errors(), res.errors
+        # the report lists the first MAX_ERR located errors and counts all of them
+        assert rep.n_total == len(res.errors), (tag, rep.n_total, len(res.errors))
+        ge, oe = rep.errors(), res.errors[:gecc.MAX_ERR]
         assert [(x[0], x[1], x[2]) for x in ge] == [(x[0], x[1], x[2]) for x in oe], (tag, ge, oe)
         scale = float(np.max(np.abs(res.C)))
         mt = tol_mag if tol_mag is not None else 10 * tol_c * scale

@@ -79,6 +79,56 @@ def test_ragged_tiles_of_the_fast_bf16_kernel_with_errors(pattern, trans):
     assert [(e[0], e[1], e[2]) for e in g.reports[0].errors()] == [(e[0], e[1], e[2]) for e in eff]
 
 
+# ---- Theorem 2: many errors in at most two rows (or columns) of C ---------------------------------
+def _t2_faults(rng, lines, others, n_other, frac, rows_known):
+    faults = []
+    for ln in lines:
+        cols = rng.choice(n_other, size=max(3, int(frac * n_other)), replace=False) if others is None else others
+        for c in sorted(int(x) for x in cols):
+            e = float(rng.uniform(1.0, 100.0) * rng.choice([-1.0, 1.0]))
+            faults.append(inputs.Fault(MAT_C, ln, c, e) if rows_known else inputs.Fault(MAT_C, c, ln, e))
+    return faults
+
+
+@pytest.mark.parametrize("case", ["one row, 40 columns", "two rows, 25 columns each", "one column, 60 rows",
+                                  "two adjacent columns, 30 rows each", "a whole row"])
+@pytest.mark.parametrize("dtype,shape", [("f32", (257, 96, 300)), ("bf16", (520, 256, 264))])
+def test_theorem2_patterns(case, dtype, shape):
+    """Errors in any number of columns of at most two flagged rows (and the mirror image) are
+    removed by Section V's subtraction, line by line; the report lists the first eight and
+    counts all.  Corrected symbols carry the rounding noise of the syndromes they were
+    computed from (no re-evaluation for these patterns): tolerance tau_1 / max |C|."""
+    n, k, m = shape
+    rng = inputs.rng_for(93, len(case))
+    law = ("normal", 1.0)
+    if case == "one row, 40 columns":
+        faults = _t2_faults(rng, [n - 1], None, m, 40 / m, True)
+    elif case == "two rows, 25 columns each":
+        faults = _t2_faults(rng, [3, 200], None, m, 25 / m, True)
+    elif case == "one column, 60 rows":
+        faults = _t2_faults(rng, [m - 1], None, n, 60 / n, False)
+    elif case == "two adjacent columns, 30 rows each":
+        faults = _t2_faults(rng, [128, 129], None, n, 30 / n, False)
+    else:
+        faults = _t2_faults(rng, [129], list(range(m)), m, 1.0, True)
+    A, B, A2, B2, cf, eff = _trial(rng, n, k, m, dtype, law, law, faults)
+    tau = gecc.noise_thresholds(n, k, m, 1.0, 1.0)
+    cfb = [(0,) + c for c in cf]
+    g = H.run_gpu(A, B, A2, B2, cfb, tau, dtype)
+    o = H.run_oracle(A, B, A2, B2, cfb, tau)
+    scale = float(np.max(np.abs(o[0].C)))
+    # two known lines: the 2x2 system divides the weighted syndrome by the distance of the lines
+    tol = 4 * (max(tau.r1, tau.q1) + (max(tau.r2, tau.q2) if "two" in case else 0.0)) / scale
+    H.compare(g, o, tol, tol_mag=tol * scale, what="theorem 2, " + case)
+    assert g.reports[0].status == gecc.CORRECTED
+    assert g.reports[0].n_total == len(faults) and g.reports[0].n_err == 8
+    # every symbol outside the corrupted lines is the plain product to the usual tolerance
+    mask = np.ones((n, m), dtype=bool)
+    for f in faults:
+        mask[f.row, f.col] = False
+    assert np.max(np.abs(g.C[0] - o[0].C)[mask]) / scale <= 1e-5
+
+
 def test_unaligned_leading_dimensions_take_the_scalar_paths():
     n, k, m = 67, 45, 83
     rng = inputs.rng_for(91)
