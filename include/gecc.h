@@ -181,6 +181,19 @@ int gecc_protected_gemm(gecc_ctx* ctx, void* dev_A, void* dev_B, float* dev_C, d
                         double* dev_B_par, double* dev_C_par, gecc_report* dev_report,
                         void* stream);
 
+/* The recomputation Section V asks for when a pattern is beyond the code ("needs to be
+   recalculated"): encode_a, encode_b once, then multiply, verify(fused), correct and a read-back
+   of the reports -- this call waits for the stream after every attempt -- until no batch item
+   reports GECC_UNCORRECTABLE or max_retries (>= 0) recomputations were made.  The whole batch is
+   recomputed from the operands as the last attempt left them (an attempt patches located
+   operand errors).  dev_faults / n_faults (may be null / 0) are planted into the first product
+   only (transient faults, for tests).  host_report (out, host): batch entries of the last
+   attempt; *attempts (out, host, may be null): products computed. */
+int gecc_protected_gemm_retry(gecc_ctx* ctx, void* dev_A, void* dev_B, float* dev_C, double* dev_A_par,
+                              double* dev_B_par, double* dev_C_par, gecc_report* dev_report,
+                              gecc_report* host_report, int32_t max_retries, const gecc_fault* dev_faults,
+                              int32_t n_faults, int32_t* attempts, void* stream);
+
 /* The same product kernel without parity work and without the syndrome epilogue:
    the denominator of the overhead figure. */
 int gecc_plain_gemm(gecc_ctx* ctx, const void* dev_A, const void* dev_B, float* dev_C, void* stream);

@@ -390,6 +390,33 @@ int gecc_protected_gemm(gecc_ctx* ctx, void* dev_A, void* dev_B, float* dev_C, d
                       (hipStream_t)stream);
 }
 
+int gecc_protected_gemm_retry(gecc_ctx* ctx, void* dev_A, void* dev_B, float* dev_C, double* dev_A_par,
+                              double* dev_B_par, double* dev_C_par, gecc_report* dev_report,
+                              gecc_report* host_report, int32_t max_retries, const gecc_fault* dev_faults,
+                              int32_t n_faults, int32_t* attempts, void* stream) {
+  int rc;
+  if (!dev_report || !host_report || max_retries < 0) return GECC_ERR_ARG;
+  if (attempts) *attempts = 0;
+  if ((rc = gecc_encode_a(ctx, dev_A, dev_A_par, stream))) return rc;
+  if ((rc = gecc_encode_b(ctx, dev_B, dev_B_par, stream))) return rc;
+  for (int32_t a = 0; a <= max_retries; ++a) {
+    // the planted faults are transient: they strike the first product only
+    if ((rc = gecc_multiply(ctx, dev_A, dev_A_par, dev_B, dev_B_par, dev_C, dev_C_par,
+                            a == 0 ? dev_faults : nullptr, a == 0 ? n_faults : 0, stream)))
+      return rc;
+    if ((rc = verify_impl(ctx, dev_C, dev_C_par, dev_report, 1, 0, (hipStream_t)stream))) return rc;
+    if ((rc = correct_impl(ctx, dev_A, dev_A_par, dev_B, dev_B_par, dev_C, dev_C_par, dev_report, 1,
+                           (hipStream_t)stream)))
+      return rc;
+    if ((rc = gecc_report_to_host(ctx, dev_report, host_report, ctx->p.batch, stream))) return rc;
+    if (attempts) *attempts = a + 1;
+    bool again = false;
+    for (int32_t b = 0; b < ctx->p.batch; ++b) again = again || host_report[b].status == GECC_UNCORRECTABLE;
+    if (!again) break;
+  }
+  return GECC_OK;
+}
+
 int gecc_plain_gemm(gecc_ctx* ctx, const void* dev_A, const void* dev_B, float* dev_C, void* stream) {
   if (!ctx || !dev_A || !dev_B || !dev_C) return GECC_ERR_ARG;
   if (!aligned_to(dev_A, elem_size(ctx->p.dtype)) || !aligned_to(dev_B, elem_size(ctx->p.dtype)) ||

@@ -52,7 +52,8 @@ class Fault(C.Structure):
 _lib = None
 _SYMBOLS = ["gecc_create", "gecc_destroy", "gecc_workspace_bytes", "gecc_set_workspace",
             "gecc_a_par_len", "gecc_b_par_len", "gecc_c_par_len", "gecc_encode_a", "gecc_encode_b",
-            "gecc_multiply", "gecc_verify", "gecc_correct", "gecc_protected_gemm", "gecc_plain_gemm",
+            "gecc_multiply", "gecc_verify", "gecc_correct", "gecc_protected_gemm", "gecc_protected_gemm_retry",
+            "gecc_plain_gemm",
             "gecc_report_to_host", "gecc_syndromes_to_host", "gecc_timing_enable", "gecc_timing_read",
             "gecc_strerror"]
 
@@ -82,6 +83,8 @@ def lib():
     L.gecc_verify.argtypes = [vp, vp, vp, vp, i32, vp]
     L.gecc_correct.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp]
     L.gecc_protected_gemm.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    L.gecc_protected_gemm_retry.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, C.POINTER(Report), i32, vp, i32,
+                                            C.POINTER(i32), vp]
     L.gecc_plain_gemm.argtypes = [vp, vp, vp, vp, vp]
     L.gecc_report_to_host.argtypes = [vp, vp, C.POINTER(Report), i32, vp]
     L.gecc_syndromes_to_host.argtypes = [vp, vp, vp]
@@ -206,6 +209,17 @@ class Context:
     def protected_gemm(self, A, B, Cmat, A_par, B_par, C_par, report):
         _check(lib().gecc_protected_gemm(self._h, _ptr(A), _ptr(B), _ptr(Cmat), _ptr(A_par), _ptr(B_par),
                                          _ptr(C_par), _ptr(report), _stream()))
+
+    def protected_gemm_retry(self, A, B, Cmat, A_par, B_par, C_par, report, max_retries=1, faults=None, n_faults=0):
+        """protected_gemm with recomputation on UNCORRECTABLE (waits for the stream after every
+        attempt).  Returns (host reports of the last attempt, products computed)."""
+        host = (Report * self.batch)()
+        attempts = C.c_int32(0)
+        _check(lib().gecc_protected_gemm_retry(self._h, _ptr(A), _ptr(B), _ptr(Cmat), _ptr(A_par), _ptr(B_par),
+                                               _ptr(C_par), _ptr(report), host, max_retries,
+                                               _ptr(faults), n_faults,
+                                               C.byref(attempts), _stream()))
+        return list(host), attempts.value
 
     def plain_gemm(self, A, B, Cmat):
         _check(lib().gecc_plain_gemm(self._h, _ptr(A), _ptr(B), _ptr(Cmat), _stream()))

@@ -129,6 +129,26 @@ def test_theorem2_patterns(case, dtype, shape):
     assert np.max(np.abs(g.C[0] - o[0].C)[mask]) / scale <= 1e-5
 
 
+def test_recomputation_after_an_uncorrectable_pattern():
+    """Section V: a pattern beyond the code is recalculated.  Three transient C faults on a
+    diagonal (s = t = 3) make the first product UNCORRECTABLE; the second one is clean."""
+    n, k, m = 300, 128, 280
+    rng = inputs.rng_for(94)
+    A, B = inputs.operands(rng, n, k, m, ("normal", 1.0), ("normal", 1.0), "bf16")
+    tau = gecc.noise_thresholds(n, k, m, 1.0, 1.0)
+    ctx = gecc.Context(n, k, m, gecc.BF16, gecc.Thresholds(tau.r1, tau.r2, tau.q1, tau.q2))
+    dA, dB = H.to_dev(A[None], "bf16", False), H.to_dev(B[None], "bf16", False)
+    A_par, B_par, C_par = ctx.alloc_parities()
+    rep, Cd = ctx.alloc_report(), ctx.alloc_c()
+    fl, nf = gecc.make_faults([(0, 10, 20, 50.0), (0, 100, 120, -30.0), (0, 299, 279, 70.0)], H.DEV)
+    ref = A.astype(np.float64) @ B.astype(np.float64)
+    reports, attempts = ctx.protected_gemm_retry(dA, dB, Cd, A_par, B_par, C_par, rep, 0, fl, nf)
+    assert attempts == 1 and reports[0].status == gecc.UNCORRECTABLE and reports[0].s == 3 and reports[0].t == 3
+    reports, attempts = ctx.protected_gemm_retry(dA, dB, Cd, A_par, B_par, C_par, rep, 2, fl, nf)
+    assert attempts == 2 and reports[0].status == gecc.CLEAN
+    assert np.max(np.abs(Cd[0].cpu().numpy() - ref)) / np.max(np.abs(ref)) <= 1e-5
+
+
 def test_unaligned_leading_dimensions_take_the_scalar_paths():
     n, k, m = 67, 45, 83
     rng = inputs.rng_for(91)
