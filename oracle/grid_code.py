@@ -65,7 +65,11 @@ the design notes of the repository):
     flagged rows are taken as the known rows when three or more columns are
     flagged (and the other way round).  A row whose own two syndromes vanish
     although it holds errors (the construction of Section IV) is not known;
-    then the verification fails and nothing is corrected.
+    then the verification fails and nothing is corrected.  The theorem's
+    errors all lie in C-bar, so this decoder runs after the operand audit
+    (on what the repair leaves, or on the whole pattern when the operands
+    are intact): a wrong symbol of A a few rows from a known row would
+    otherwise be taken for a row full of small errors of C.
   * the located-error list of a result is complete here; the library's
     report carries the first MAX_REPORTED entries and the total.
   * for s = t = 2 the 2x2 systems are first evaluated under the two sparse
@@ -408,17 +412,18 @@ def decode(Cbar, A, AP, B, BP, tau):
     fix = None
     if 1 <= s0 <= 2 and 1 <= t0 <= 2:
         fix = d0_correct(r1, r2, q1, q2, Er, Et, LineThresholds(tau, n, m))
-    elif 1 <= min(s0, t0) <= 2:
-        fix = known_lines_correct(r1, r2, q1, q2, Er, Et, LineThresholds(tau, n, m))
     if fix is not None:
         for (i, j, x) in fix:
             Cbar[i, j] -= x
         return done(CORRECTED, [(MAT_C, i, j, x) for (i, j, x) in fix])
 
-    # D1: operand audit, patch, rank-one repair, then Section V on the rest
+    # D1: operand audit, patch, rank-one repair, then Section V on the rest.  Theorem 2's
+    # decoder runs only here, after the audit: it presumes that every error lies in C-bar
+    # (Appendix B), and a wrong operand symbol near a known line would otherwise pass for a
+    # line full of small errors of C.  With no operand hit the "rest" is the whole pattern.
     okA, LA = audit_a(A, AP, tau.op)
     okB, LB = audit_b(B, BP, tau.op)
-    if not (okA and okB) or (len(LA) + len(LB) == 0) or (len(LA) + len(LB) > MAX_REPORTED):
+    if not (okA and okB) or (len(LA) + len(LB) > MAX_REPORTED):
         return done(UNCORRECTABLE, [])
     errs = []
     k = A.shape[1]

@@ -51,6 +51,7 @@ def run(workload: str, trials: int, seed_cfg: int = 30, progress=None):
 
     stats = collections.defaultdict(lambda: collections.Counter())
     by_decade = collections.defaultdict(lambda: collections.Counter())
+    failures = []                                       # the first trials that were not corrected exactly
     for t in range(trials):
         frng = inputs.rng_for(seed_cfg, 1 + t)
         count = int(frng.integers(0, 3))
@@ -69,6 +70,11 @@ def run(workload: str, trials: int, seed_cfg: int = 30, progress=None):
                 want.append((f.matrix, f.row, f.col))
             touched.append((T, i, j, old))
         cls = CLASS_NAME[tuple(sorted(f.matrix for f in faults))]
+        if len(want) == 2 and want[0][0] == want[1][0] != MC and \
+                want[0][2 if want[0][0] == MA else 1] == want[1][2 if want[0][0] == MA else 1]:
+            # two wrong symbols in one column of A (one row of B): that line carries two parity
+            # symbols (Section III), so the pair is beyond the code and has to be recomputed
+            cls += " (one line)"
         fl, nf = gecc.make_faults(cf, dev)
         ctx.multiply(dA, A_par, dB, B_par, Cd, C_par, fl, nf)
         ctx.verify(Cd, C_par, rep, fused=True)
@@ -77,6 +83,8 @@ def run(workload: str, trials: int, seed_cfg: int = 30, progress=None):
         got = [(e[0], e[1], e[2]) for e in r.errors()]
         detected = r.status != gecc.CLEAN
         exact = r.status == gecc.CORRECTED and got == sorted(want)
+        if cls.endswith("(one line)"):
+            exact = r.status == gecc.UNCORRECTABLE
         st = stats[cls]
         st["trials"] += 1
         st["detected"] += int(detected)
@@ -89,6 +97,10 @@ def run(workload: str, trials: int, seed_cfg: int = 30, progress=None):
             bd["trials"] += 1
             bd["detected"] += int(detected)
             bd["corrected_exactly"] += int(exact)
+        if want and not exact and len(failures) < 32:
+            failures.append({"trial": t, "class": cls, "status": int(r.status), "n_total": int(r.n_total),
+                             "faults": [[int(f.matrix), int(f.row), int(f.col), float(f.offset)] for f in faults],
+                             "located": [[int(e[0]), int(e[1]), int(e[2]), float(e[3])] for e in r.errors()]})
         if touched and not exact:                       # the decoder may have patched elsewhere
             dA.copy_(Aclean)
             dB.copy_(Bclean)
@@ -100,7 +112,8 @@ def run(workload: str, trials: int, seed_cfg: int = 30, progress=None):
     out = {"workload": w.name, "trials": trials,
            "thresholds": [w.tau.r1, w.tau.r2, w.tau.q1, w.tau.q2],
            "by_class": {c: dict(v) for c, v in sorted(stats.items())},
-           "by_smallest_offset_decade": {d: dict(v) for d, v in sorted(by_decade.items())}}
+           "by_smallest_offset_decade": {d: dict(v) for d, v in sorted(by_decade.items())},
+           "failures": failures}
     none = stats.get("none")
     if none:
         out["false_alarm_rate"] = none["detected"] / max(1, none["trials"])

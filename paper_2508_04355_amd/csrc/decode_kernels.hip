@@ -184,6 +184,10 @@ __global__ __launch_bounds__(64) void summarize_kernel(DecodeArgs a) {   // one 
 }
 
 // ---- Section V step 2 ------------------------------------------------------------------------
+// The decoder's workgroup-wide routines below are written for exactly DC_THREADS threads
+// (threadIdx.x < DC_THREADS; a larger workgroup lets its other wavefronts end first).
+constexpr int DC_THREADS = 256;
+
 __device__ void sort_small(int* v, int cnt) {
   for (int x = 1; x < cnt; ++x) {
     const int key = v[x];
@@ -294,12 +298,12 @@ __device__ int d0_correct(Est* out, const int* Er, int s, const int* Et, int t, 
 // fp64 dot product of row i of A with column j of B over k, by the whole workgroup
 __device__ double block_dot(const DecodeArgs& a, int b, int i, int j, double* red) {
   double s = 0.0;
-  for (int l = threadIdx.x; l < a.p.k; l += blockDim.x)
+  for (int l = threadIdx.x; l < a.p.k; l += DC_THREADS)
     s = fma(load_elem(a.A, a.p.dtype, a_index(a.p, b, i, l)),
             load_elem(a.B, a.p.dtype, b_index(a.p, b, l, j)), s);
   red[threadIdx.x] = s;
   __syncthreads();
-  for (int w = blockDim.x / 2; w > 0; w >>= 1) {
+  for (int w = DC_THREADS / 2; w > 0; w >>= 1) {
     if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
     __syncthreads();
   }
@@ -352,7 +356,7 @@ __device__ int known_lines_correct(const DecodeArgs& a, int b, DecodeState* st, 
   __shared__ double t2_red[8][256];
   __shared__ int t2_cnt[2][256];
   __shared__ int t2_bad;
-  const int tid = threadIdx.x, ch = (L + (int)blockDim.x - 1) / (int)blockDim.x;
+  const int tid = threadIdx.x, ch = (L + DC_THREADS - 1) / DC_THREADS;
   const int c0 = min(L, tid * ch), c1 = min(L, c0 + ch);
   if (tid == 0) t2_bad = 0;
   __syncthreads();
@@ -383,7 +387,7 @@ __device__ int known_lines_correct(const DecodeArgs& a, int b, DecodeState* st, 
     // the known lines' own syndromes against everything attributed to them
     for (int q = 0; q < nk; ++q) {
       double v[4] = {0, 0, 0, 0};
-      for (int x = 0; x < (int)blockDim.x; ++x)
+      for (int x = 0; x < DC_THREADS; ++x)
         for (int f = 0; f < 4; ++f) v[f] += t2_red[4 * q + f][x];
       const int line = K[q];
       const double z1 = rows_known ? y.r1[line] : y.q1[line], z2 = rows_known ? y.r2[line] : y.q2[line];
@@ -395,7 +399,7 @@ __device__ int known_lines_correct(const DecodeArgs& a, int b, DecodeState* st, 
   if (t2_bad) return -1;
   // position of this thread's entries in the list sorted by (row, column)
   int before[2] = {0, 0}, total[2] = {0, 0};
-  for (int x = 0; x < (int)blockDim.x; ++x)
+  for (int x = 0; x < DC_THREADS; ++x)
     for (int q = 0; q < 2; ++q) {
       if (x < tid) before[q] += t2_cnt[q][x];
       total[q] += t2_cnt[q][x];
@@ -424,28 +428,21 @@ __device__ int known_lines_correct(const DecodeArgs& a, int b, DecodeState* st, 
   return total[0] + total[1];
 }
 
-// One workgroup per batch item.  final_pass = 0: right after detection (with_summary: this
-// kernel also writes the first report, saving the summary launch); = 1: after the operand audit
-// and the residual syndrome pass.
-__global__ __launch_bounds__(256) void decode_c_kernel(DecodeArgs a, int final_pass, int with_summary) {
-  const int b = blockIdx.x;
-  DecodeState* st = state_of(a, b);
-  gecc_report* rep = a.report + b;
-  if (final_pass) {
-    if (st->phase != PH_REVERIFY) return;
-  } else if (with_summary) {
-    if (summarize(a, b, st, rep) == GECC_CLEAN) return;
-  } else {
-    if (rep->status != GECC_DETECTED) return;
-  }
-
+// Section V step 2 for one batch item, by DC_THREADS threads.  final_pass = 0: right after
+// detection; = 1: on the residual syndromes after an operand repair (per-line allowances apply,
+// failure is final).
+__device__ void decode_c_body(const DecodeArgs& a, int b, DecodeState* st, gecc_report* rep, int final_pass) {
   __shared__ Est fix[4];
   __shared__ int nfix;          // -1: the rule does not apply / failed
   __shared__ double red[256];
   const int n = a.p.n, m = a.p.m;
   {
     const int s = st->s_cnt, t = st->t_cnt, lo = min(s, t), hi = max(s, t);
-    if (lo >= 1 && lo <= 2 && hi > 2) {       // Theorem 2: many lines of one kind, at most two of the other
+    // Theorem 2: many lines of one kind, at most two of the other.  Its errors all lie in C-bar,
+    // so it runs only after the operand audit (on what the repair leaves, or on the whole pattern
+    // when both operands are intact): a wrong symbol of A a few rows from a flagged row would
+    // otherwise pass for a row full of small errors of C.
+    if (final_pass && lo >= 1 && lo <= 2 && hi > 2) {
       const double* sy = synd_of(a, b);
       const double* al = final_pass ? allow_of(a, b) : nullptr;
       const Synd y{sy, sy + n, sy + 2 * n, sy + 2 * n + m, a.p.tau_r1, a.p.tau_r2, a.p.tau_q1, a.p.tau_q2,
@@ -454,8 +451,7 @@ __global__ __launch_bounds__(256) void decode_c_kernel(DecodeArgs a, int final_p
       const int k = known_lines_correct(a, b, st, rep, y, final_pass);
       if (threadIdx.x == 0) {
         if (k < 0) {
-          if (final_pass) { rep->status = GECC_UNCORRECTABLE; rep->n_err = 0; rep->n_total = 0; st->phase = PH_DONE; }
-          else            { st->phase = PH_AUDIT; }
+          rep->status = GECC_UNCORRECTABLE; rep->n_err = 0; rep->n_total = 0; st->phase = PH_DONE;
         } else {
           for (int e = 0; e < st->n_err; ++e) rep->err[e] = st->errs[e];
           rep->n_total = st->n_err + k;
@@ -528,6 +524,20 @@ __global__ __launch_bounds__(256) void decode_c_kernel(DecodeArgs a, int final_p
   }
 }
 
+// One workgroup per batch item, right after detection.  with_summary: this kernel also writes
+// the first report (saves the summary launch).
+__global__ __launch_bounds__(DC_THREADS) void decode_c_kernel(DecodeArgs a, int with_summary) {
+  const int b = blockIdx.x;
+  DecodeState* st = state_of(a, b);
+  gecc_report* rep = a.report + b;
+  if (with_summary) {
+    if (summarize(a, b, st, rep) == GECC_CLEAN) return;
+  } else {
+    if (rep->status != GECC_DETECTED) return;
+  }
+  decode_c_body(a, b, st, rep, 0);
+}
+
 // ---- operand audit -----------------------------------------------------------------------------
 // A single wrong symbol of a line (column l of A, row l of B) shows as (u1, u2) = (e, (pos+1) e)
 // in the difference of re-formed and stored parities.
@@ -586,7 +596,7 @@ __global__ __launch_bounds__(RP_THREADS) void repair_kernel(DecodeArgs a) {
   __syncthreads();
   const int na = cnt_a, nb = cnt_b;
   if (threadIdx.x == 0) {
-    ok = (na + nb > 0) && (na + nb <= GECC_MAX_ERR);
+    ok = na + nb <= GECC_MAX_ERR;       // no hit at all: the pattern lies in C-bar alone (second pass below)
     if (ok) {
       for (int x = 0; x < na; ++x) if (ha[x].pos < 0) ok = 0;
       for (int x = 0; x < nb; ++x) if (hb[x].pos < 0) ok = 0;
@@ -608,7 +618,14 @@ __global__ __launch_bounds__(RP_THREADS) void repair_kernel(DecodeArgs a) {
   double* al_q1 = al_r1 + 2 * n;
   double* al_q2 = al_r1 + 2 * n + m;
   const double cc = a.p.tau_rep * sqrt((double)k);
-  __shared__ double red[2][RP_THREADS];
+  // residual syndromes: every repair below also moves the syndromes by exactly what it changes
+  // (the stored symbols' differences and the parity symbols), so that Section V can run again
+  // without another pass over C
+  double* sy_r1 = synd_of(a, b);
+  double* sy_r2 = sy_r1 + n;
+  double* sy_q1 = sy_r1 + 2 * n;
+  double* sy_q2 = sy_r1 + 2 * n + m;
+  __shared__ double red[4][RP_THREADS];
   for (int o = threadIdx.x; o < 2 * n + 2 * m; o += blockDim.x) al_r1[o] = 0.0;
   __syncthreads();
   for (int x = 0; x < na; ++x) {
@@ -618,23 +635,34 @@ __global__ __launch_bounds__(RP_THREADS) void repair_kernel(DecodeArgs a) {
       cpar[i] -= e * bpar[l];              // cbar_{i,m+1}
       cpar[n + i] -= e * bpar[k + l];      // cbar_{i,m+2}
     }
-    double s2 = 0.0, w2 = 0.0;
+    double s2 = 0.0, w2 = 0.0, ds = 0.0, dw = 0.0;
     for (int j = threadIdx.x; j < m; j += blockDim.x) {
       const int64_t ic = (int64_t)i * a.p.ldc + j;
       const double f = e * load_elem(a.B, a.p.dtype, b_index(a.p, b, l, j));
-      C[ic] = (float)((double)C[ic] - f);
+      const float cold = C[ic], cnew = (float)((double)cold - f);
+      C[ic] = cnew;
+      const double d = (double)cold - (double)cnew;      // what the sums of row i and column j lose
+      sy_q1[j] -= d;
+      sy_q2[j] -= (double)(i + 1) * d;
+      ds += d;
+      dw += (double)(j + 1) * d;
       s2 += f * f;
       w2 += (double)(j + 1) * (j + 1) * f * f;
       al_q1[j] += cc * fabs(f);
       al_q2[j] += cc * (double)(i + 1) * fabs(f);
     }
-    red[0][threadIdx.x] = s2; red[1][threadIdx.x] = w2;
+    red[0][threadIdx.x] = s2; red[1][threadIdx.x] = w2; red[2][threadIdx.x] = ds; red[3][threadIdx.x] = dw;
     __syncthreads();
     for (int w = RP_THREADS / 2; w > 0; w >>= 1) {
-      if ((int)threadIdx.x < w) { red[0][threadIdx.x] += red[0][threadIdx.x + w]; red[1][threadIdx.x] += red[1][threadIdx.x + w]; }
+      if ((int)threadIdx.x < w)
+        for (int q = 0; q < 4; ++q) red[q][threadIdx.x] += red[q][threadIdx.x + w];
       __syncthreads();
     }
-    if (threadIdx.x == 0) { al_r1[i] += cc * sqrt(red[0][0]); al_r2[i] += cc * sqrt(red[1][0]); }
+    if (threadIdx.x == 0) {
+      al_r1[i] += cc * sqrt(red[0][0]); al_r2[i] += cc * sqrt(red[1][0]);
+      sy_r1[i] += e * bpar[l] - red[2][0];          // sum - parity: both moved
+      sy_r2[i] += e * bpar[k + l] - red[3][0];
+    }
     __syncthreads();
   }
   for (int x = 0; x < nb; ++x) {
@@ -644,26 +672,37 @@ __global__ __launch_bounds__(RP_THREADS) void repair_kernel(DecodeArgs a) {
       cpar[2 * n + j] -= apar[l] * e;          // cbar_{n+1,j}
       cpar[2 * n + m + j] -= apar[k + l] * e;  // cbar_{n+2,j}
     }
-    double s2 = 0.0, w2 = 0.0;
+    double s2 = 0.0, w2 = 0.0, ds = 0.0, dw = 0.0;
     for (int i = threadIdx.x; i < n; i += blockDim.x) {
       double av = load_elem(a.A, a.p.dtype, a_index(a.p, b, i, l));
       for (int z = 0; z < na; ++z)
         if (ha[z].pos == i && ha[z].line == l) av -= ha[z].e;   // corrected A
       const int64_t ic = (int64_t)i * a.p.ldc + j;
       const double f = av * e;
-      C[ic] = (float)((double)C[ic] - f);
+      const float cold = C[ic], cnew = (float)((double)cold - f);
+      C[ic] = cnew;
+      const double d = (double)cold - (double)cnew;
+      sy_r1[i] -= d;
+      sy_r2[i] -= (double)(j + 1) * d;
+      ds += d;
+      dw += (double)(i + 1) * d;
       s2 += f * f;
       w2 += (double)(i + 1) * (i + 1) * f * f;
       al_r1[i] += cc * fabs(f);
       al_r2[i] += cc * (double)(j + 1) * fabs(f);
     }
-    red[0][threadIdx.x] = s2; red[1][threadIdx.x] = w2;
+    red[0][threadIdx.x] = s2; red[1][threadIdx.x] = w2; red[2][threadIdx.x] = ds; red[3][threadIdx.x] = dw;
     __syncthreads();
     for (int w = RP_THREADS / 2; w > 0; w >>= 1) {
-      if ((int)threadIdx.x < w) { red[0][threadIdx.x] += red[0][threadIdx.x + w]; red[1][threadIdx.x] += red[1][threadIdx.x + w]; }
+      if ((int)threadIdx.x < w)
+        for (int q = 0; q < 4; ++q) red[q][threadIdx.x] += red[q][threadIdx.x + w];
       __syncthreads();
     }
-    if (threadIdx.x == 0) { al_q1[j] += cc * sqrt(red[0][0]); al_q2[j] += cc * sqrt(red[1][0]); }
+    if (threadIdx.x == 0) {
+      al_q1[j] += cc * sqrt(red[0][0]); al_q2[j] += cc * sqrt(red[1][0]);
+      sy_q1[j] += apar[l] * e - red[2][0];
+      sy_q2[j] += apar[k + l] * e - red[3][0];
+    }
     __syncthreads();
   }
   if (threadIdx.x == 0) {
@@ -700,25 +739,31 @@ __global__ __launch_bounds__(RP_THREADS) void repair_kernel(DecodeArgs a) {
       st->errs[ne++] = g;
     }
     st->n_err = ne;
-    st->s_cnt = 0;
-    st->t_cnt = 0;
-    // strips of C whose partial sums the residual pass has to form again
-    int ntm = 0, ntn = 0;
-    for (int x = 0; x < na; ++x) {
-      const int t = ha[x].pos / a.tile_m;
-      bool seen = false;
-      for (int y = 0; y < ntm; ++y) seen = seen || st->tm_list[y] == t;
-      if (!seen) st->tm_list[ntm++] = t;
-    }
-    for (int x = 0; x < nb; ++x) {
-      const int t = hb[x].pos / a.tile_n;
-      bool seen = false;
-      for (int y = 0; y < ntn; ++y) seen = seen || st->tn_list[y] == t;
-      if (!seen) st->tn_list[ntn++] = t;
-    }
-    st->n_tm = ntm; st->n_tn = ntn;
-    st->phase = PH_REVERIFY;
   }
+  // Section V step 1 on the residual syndromes (thresholds widened by the allowances above) ...
+  __shared__ int res_s, res_t;
+  if (threadIdx.x == 0) { res_s = 0; res_t = 0; }
+  __syncthreads();
+  for (int o = threadIdx.x; o < n + m; o += blockDim.x) {
+    if (o < n) {
+      if (fabs(sy_r1[o]) > a.p.tau_r1 + al_r1[o] || fabs(sy_r2[o]) > a.p.tau_r2 + al_r2[o]) {
+        const int idx = atomicAdd(&res_s, 1);
+        if (idx < GECC_MAX_ERR) st->rows[idx] = o;
+      }
+    } else {
+      const int j = o - n;
+      if (fabs(sy_q1[j]) > a.p.tau_q1 + al_q1[j] || fabs(sy_q2[j]) > a.p.tau_q2 + al_q2[j]) {
+        const int idx = atomicAdd(&res_t, 1);
+        if (idx < GECC_MAX_ERR) st->cols[idx] = j;
+      }
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) { st->s_cnt = res_s; st->t_cnt = res_t; st->phase = PH_REVERIFY; }
+  __syncthreads();
+  // ... and step 2, by the first DC_THREADS threads (the other wavefronts end here)
+  if (threadIdx.x >= DC_THREADS) return;
+  decode_c_body(a, b, st, rep, 1);
 }
 
 }  // namespace
@@ -739,8 +784,8 @@ hipError_t launch_summarize(const DecodeArgs& a, hipStream_t st) {
   return hipGetLastError();
 }
 
-hipError_t launch_decode_c(const DecodeArgs& a, int final_pass, int with_summary, hipStream_t st) {
-  hipLaunchKernelGGL(decode_c_kernel, dim3(a.p.batch), dim3(256), 0, st, a, final_pass, with_summary);
+hipError_t launch_decode_c(const DecodeArgs& a, int with_summary, hipStream_t st) {
+  hipLaunchKernelGGL(decode_c_kernel, dim3(a.p.batch), dim3(DC_THREADS), 0, st, a, with_summary);
   return hipGetLastError();
 }
 

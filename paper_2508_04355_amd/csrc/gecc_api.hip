@@ -331,29 +331,19 @@ int verify_impl(gecc_ctx* ctx, const float* dev_C, const double* dev_C_par, gecc
 // S6 + S7.  with_summary = 1: the first decoder pass also writes the first report.
 int correct_impl(gecc_ctx* ctx, void* dev_A, const double* dev_A_par, void* dev_B, const double* dev_B_par,
                  float* dev_C, double* dev_C_par, gecc_report* dev_report, int with_summary, hipStream_t st) {
-  const gecc_params& p = ctx->p;
   DecodeArgs d = decode_args(ctx, dev_A, dev_A_par, dev_B, dev_B_par, dev_C, dev_C_par, dev_report);
   const int32_t* gate = &d.state->phase;
   hipError_t e;
   // Section V step 2 on the flagged lines; on failure the phase becomes PH_AUDIT
-  if ((e = launch_decode_c(d, 0, with_summary, st)) != hipSuccess) return hip_rc(e);
+  if ((e = launch_decode_c(d, with_summary, st)) != hipSuccess) return hip_rc(e);
   // operand audit: re-form the parities of A and B as the product read them
   if ((e = reduce_a_over_n(ctx, dev_A, nullptr, const_cast<double*>(d.audit_a), gate, st)) != hipSuccess)
     return hip_rc(e);
   if ((e = reduce_b_over_m(ctx, dev_B, nullptr, const_cast<double*>(d.audit_b), gate, st)) != hipSuccess)
     return hip_rc(e);
-  if ((e = launch_repair(d, st)) != hipSuccess) return hip_rc(e);
-  // residual syndromes of the repaired C-bar, then Section V once more
-  PartialArgs pa{};
-  pa.C = dev_C; pa.n = p.n; pa.m = p.m; pa.batch = p.batch; pa.ldc = p.ldc; pa.sc = p.stride_c;
-  pa.rowpart = const_cast<float*>(d.rowpart); pa.colpart = const_cast<float*>(d.colpart);
-  pa.tile_m = ctx->tile_m; pa.tile_n = ctx->tile_n; pa.ntm = ctx->ntm; pa.ntn = ctx->ntn;
-  pa.rp_ld = ctx->rp_ld; pa.cp_ld = ctx->cp_ld;
-  pa.gate = gate; pa.gate_stride = sizeof(DecodeState); pa.gate_value = PH_REVERIFY;
-  pa.strips = d.state;   // only the strips of C the repair wrote to
-  if ((e = launch_partials(pa, st)) != hipSuccess) return hip_rc(e);
-  if ((e = launch_threshold(d, 0, st)) != hipSuccess) return hip_rc(e);
-  return hip_rc(launch_decode_c(d, 1, 0, st));
+  // parity differences, operand patches, rank-one repair of C-bar with the residual syndromes
+  // kept up to date, then Section V once more -- all in one workgroup per batch item
+  return hip_rc(launch_repair(d, st));
 }
 
 }  // namespace

@@ -29,9 +29,6 @@ struct DecodeState {
   // decoder
   int32_t phase;
   int32_t n_err;              // operand errors already accepted by the audit
-  // 128-row / 128-column strips of C that the repair touched (the residual pass re-sums only these)
-  int32_t n_tm, n_tn;
-  int32_t tm_list[GECC_MAX_ERR], tn_list[GECC_MAX_ERR];
   gecc_err errs[GECC_MAX_ERR];
 };
 
@@ -121,7 +118,6 @@ static __device__ __forceinline__ void reset_state(DecodeState* s) {
   s->s_cnt = 0; s->t_cnt = 0;
   s->phase = PH_DONE;
   s->n_err = 0;
-  s->n_tm = 0; s->n_tn = 0;
 }
 
 // Global parity block P_g = A_P B_P (Section III, 2 x 2) of batch item b, in fp64 and in a fixed
@@ -170,9 +166,6 @@ struct PartialArgs {
   const int32_t* gate;
   int64_t gate_stride;
   int gate_value;
-  // null: every sub-tile.  Else the DecodeState of batch item 0 (stride gate_stride): only the
-  // sub-tiles in the strips its tm_list / tn_list name
-  const DecodeState* strips;
 };
 hipError_t launch_partials(const PartialArgs& a, hipStream_t st);
 
@@ -204,9 +197,9 @@ hipError_t launch_reset_state(const DecodeArgs& a, hipStream_t st);
 hipError_t launch_threshold(const DecodeArgs& a, int first, hipStream_t st);
 // first report (s, t, maxima, CLEAN / DETECTED) from the counters of the first threshold pass
 hipError_t launch_summarize(const DecodeArgs& a, hipStream_t st);
-// Section V step 2.  with_summary = 1 (first pass only): also writes the first report
-hipError_t launch_decode_c(const DecodeArgs& a, int final_pass, int with_summary, hipStream_t st);
-// audit differences, operand patches, rank-one repair of C-bar
+// Section V step 2 right after detection.  with_summary = 1: also writes the first report
+hipError_t launch_decode_c(const DecodeArgs& a, int with_summary, hipStream_t st);
+// audit differences, operand patches, rank-one repair of C-bar and of the syndromes, Section V on the rest
 hipError_t launch_repair(const DecodeArgs& a, hipStream_t st);
 
 }  // namespace gecc

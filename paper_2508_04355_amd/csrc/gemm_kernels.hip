@@ -291,21 +291,7 @@ __global__ __launch_bounds__(THREADS) void partials_kernel(PartialArgs a) {
                                                         a.gate_stride * b);
     if (g != a.gate_value) return;
   }
-  int tm = blockIdx.y, tn = blockIdx.x;
-  if (a.strips) {
-    // strip mode: blockIdx.y < GECC_MAX_ERR names a touched strip of 128 rows (all its
-    // sub-tiles along m), the others a touched strip of 128 columns
-    const DecodeState* st = reinterpret_cast<const DecodeState*>(reinterpret_cast<const char*>(a.strips) +
-                                                                 a.gate_stride * b);
-    const int s = blockIdx.y;
-    if (s < GECC_MAX_ERR) {
-      if (s >= st->n_tm || (int)blockIdx.x >= a.ntn) return;
-      tm = st->tm_list[s]; tn = blockIdx.x;
-    } else {
-      if (s - GECC_MAX_ERR >= st->n_tn || (int)blockIdx.x >= a.ntm) return;
-      tn = st->tn_list[s - GECC_MAX_ERR]; tm = blockIdx.x;
-    }
-  }
+  const int tm = blockIdx.y, tn = blockIdx.x;
   const int tile_r0 = tm * 128, tile_c0 = tn * 128;
   const float* C = a.C + (int64_t)b * a.sc;
   const int tid = threadIdx.x;
@@ -390,7 +376,6 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t st) {
 hipError_t launch_partials(const PartialArgs& a, hipStream_t st) {
   if (a.tile_m != 128 || a.tile_n != 128) return hipErrorInvalidValue;
   dim3 grid(a.ntn, a.ntm, a.batch);
-  if (a.strips) grid = dim3(a.ntn > a.ntm ? a.ntn : a.ntm, 2 * GECC_MAX_ERR, a.batch);
   hipLaunchKernelGGL(partials_kernel, grid, dim3(THREADS), 0, st, a);
   return hipGetLastError();
 }

@@ -449,3 +449,28 @@ def test_theorem2_operand_errors_still_go_through_the_audit():
     assert res.status == CORRECTED
     assert [(mt, i, j) for (mt, i, j, _) in res.errors] == [(MAT_A, 2, 1), (MAT_C, 0, 4)]
     assert res.t >= 3 and res.s == 1
+
+
+def test_theorem2_runs_after_the_operand_audit():
+    """With loose weighted thresholds a wrong symbol of A in row 5 is, seen from the columns,
+    the same as errors of C in the flagged row 6 next to it: Theorem 2's decoder alone accepts
+    that reading.  The operand parities (Section III: every column of A-bar is a codeword of
+    its own) say otherwise, so the decoder has to ask them first."""
+    n, k, m = 12, 4, 8
+    A, B = int_mats(35, n, k, m)
+    B[2, :] = [1, -1, 2, -2, 3, -3, 1, -1]            # row of B with plain and weighted sums near zero
+    AP, BP = oc.encode_a(A), oc.encode_b(B)
+    tau = Thresholds(0.5, 40.0, 0.5, 40.0, 0.0)
+    A2 = A.copy()
+    A2[5, 2] += 1.0
+    Cbar = oc.encoded_product(A2, AP, B, BP)
+    oc.inject_c(Cbar, [(6, 3, 7.0)])
+    r1, r2, q1, q2 = oc.syndromes(Cbar)
+    Er, Et = oc.detect(r1, r2, q1, q2, tau)
+    assert Er == [6] and len(Et) == m
+    alone = oc.known_lines_correct(r1, r2, q1, q2, Er, Et, oc.LineThresholds(tau, n, m))
+    assert alone is not None and len(alone) == m and all(i == 6 for (i, _, _) in alone)
+    res = oc.decode(Cbar, A2, AP, B, BP, tau)
+    assert res.status == CORRECTED
+    assert res.errors == [(MAT_A, 5, 2, 1.0), (MAT_C, 6, 3, 7.0)]
+    assert np.array_equal(res.A, A) and np.array_equal(res.Cbar, oc.encoded_product(A, AP, B, BP))
