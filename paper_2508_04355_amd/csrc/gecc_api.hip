@@ -68,7 +68,6 @@ DecodeArgs decode_args(gecc_ctx* c, void* A, const double* A_par, void* B, const
   return d;
 }
 
-// out[2][k] = parity of A over its n-index with weights w (null: Section III's index weights)
 ScanArgs scan_base(const gecc_ctx* c, const void* X, int64_t ld, int64_t xs) {
   ScanArgs s{};
   s.X = X; s.dtype = c->p.dtype; s.ld = ld; s.xs = xs; s.batch = c->p.batch;
@@ -76,57 +75,98 @@ ScanArgs scan_base(const gecc_ctx* c, const void* X, int64_t ld, int64_t xs) {
   return s;
 }
 
-// reduce A over its row index i (length n) -> [2][k]
-hipError_t reduce_a_over_n(gecc_ctx* c, const void* A, const double* w, double* out,
-                           const int32_t* gate, hipStream_t st) {
+// The four scans of the path.  Each operand is reduced once along its contiguous index (rowdot:
+// one launch) and once along the other (coldot: two stages), whichever way it is stored.
+struct ScanJob {
+  ScanArgs s;
+  bool rowdot;
+};
+
+// reduce A over its row index i (length n) -> [2][k]; w = null: Section III's index weights
+ScanJob scan_a_over_n(gecc_ctx* c, const void* A, const double* w, double* out, const int32_t* gate) {
   const gecc_params& p = c->p;
-  ScanArgs s = scan_base(c, A, p.lda, p.stride_a);
+  ScanJob j{scan_base(c, A, p.lda, p.stride_a), p.trans_a != 0};
+  ScanArgs& s = j.s;
   s.w = w; s.out = out; s.w_stride = 2 * (int64_t)p.n; s.out_stride = 2 * (int64_t)p.k;
-  s.gate = gate; s.gate_stride = sizeof(DecodeState); s.gate_value = PH_AUDIT;
-  if (p.trans_a) { s.R = p.k; s.Cc = p.n; return launch_rowdot(s, st); }   // stored k x n
-  s.R = p.n; s.Cc = p.k;
-  s.scratch = reinterpret_cast<double*>(c->ws + c->lay.scan_a);
-  return launch_coldot(s, st);
+  if (gate) { s.gate = gate; s.gate_stride = sizeof(DecodeState); s.gate_value = PH_AUDIT; }
+  if (p.trans_a) { s.R = p.k; s.Cc = p.n; }   // stored k x n
+  else { s.R = p.n; s.Cc = p.k; s.scratch = reinterpret_cast<double*>(c->ws + c->lay.scan_a); }
+  return j;
 }
 // reduce A over its column index l (length k) -> [2][n]
-hipError_t reduce_a_over_k(gecc_ctx* c, const void* A, const double* w, double* out,
-                           int64_t out_stride, hipStream_t st) {
+ScanJob scan_a_over_k(gecc_ctx* c, const void* A, const double* w, double* out, int64_t out_stride) {
   const gecc_params& p = c->p;
-  ScanArgs s = scan_base(c, A, p.lda, p.stride_a);
+  ScanJob j{scan_base(c, A, p.lda, p.stride_a), p.trans_a == 0};
+  ScanArgs& s = j.s;
   s.w = w; s.out = out; s.w_stride = 2 * (int64_t)p.k; s.out_stride = out_stride;
-  if (p.trans_a) {
-    s.R = p.k; s.Cc = p.n;
-    s.scratch = reinterpret_cast<double*>(c->ws + c->lay.scan_a);
-    return launch_coldot(s, st);
-  }
-  s.R = p.n; s.Cc = p.k;
-  return launch_rowdot(s, st);
+  if (p.trans_a) { s.R = p.k; s.Cc = p.n; s.scratch = reinterpret_cast<double*>(c->ws + c->lay.scan_a); }
+  else { s.R = p.n; s.Cc = p.k; }
+  return j;
 }
 // reduce B over its column index j (length m) -> [2][k]
-hipError_t reduce_b_over_m(gecc_ctx* c, const void* B, const double* w, double* out,
-                           const int32_t* gate, hipStream_t st) {
+ScanJob scan_b_over_m(gecc_ctx* c, const void* B, const double* w, double* out, const int32_t* gate) {
   const gecc_params& p = c->p;
-  ScanArgs s = scan_base(c, B, p.ldb, p.stride_b);
+  ScanJob j{scan_base(c, B, p.ldb, p.stride_b), p.trans_b == 0};
+  ScanArgs& s = j.s;
   s.w = w; s.out = out; s.w_stride = 2 * (int64_t)p.m; s.out_stride = 2 * (int64_t)p.k;
-  s.gate = gate; s.gate_stride = sizeof(DecodeState); s.gate_value = PH_AUDIT;
-  if (p.trans_b) {                                                         // stored m x k
-    s.R = p.m; s.Cc = p.k;
-    s.scratch = reinterpret_cast<double*>(c->ws + c->lay.scan_b);
-    return launch_coldot(s, st);
-  }
-  s.R = p.k; s.Cc = p.m;
-  return launch_rowdot(s, st);
+  if (gate) { s.gate = gate; s.gate_stride = sizeof(DecodeState); s.gate_value = PH_AUDIT; }
+  if (p.trans_b) { s.R = p.m; s.Cc = p.k; s.scratch = reinterpret_cast<double*>(c->ws + c->lay.scan_b); }   // stored m x k
+  else { s.R = p.k; s.Cc = p.m; }
+  return j;
 }
 // reduce B over its row index l (length k) -> [2][m]
-hipError_t reduce_b_over_k(gecc_ctx* c, const void* B, const double* w, double* out,
-                           int64_t out_stride, hipStream_t st) {
+ScanJob scan_b_over_k(gecc_ctx* c, const void* B, const double* w, double* out, int64_t out_stride) {
   const gecc_params& p = c->p;
-  ScanArgs s = scan_base(c, B, p.ldb, p.stride_b);
+  ScanJob j{scan_base(c, B, p.ldb, p.stride_b), p.trans_b != 0};
+  ScanArgs& s = j.s;
   s.w = w; s.out = out; s.w_stride = 2 * (int64_t)p.k; s.out_stride = out_stride;
-  if (p.trans_b) { s.R = p.m; s.Cc = p.k; return launch_rowdot(s, st); }
-  s.R = p.k; s.Cc = p.m;
-  s.scratch = reinterpret_cast<double*>(c->ws + c->lay.scan_b);
-  return launch_coldot(s, st);
+  if (p.trans_b) { s.R = p.m; s.Cc = p.k; }
+  else { s.R = p.k; s.Cc = p.m; s.scratch = reinterpret_cast<double*>(c->ws + c->lay.scan_b); }
+  return j;
+}
+
+// Scans in stream order.  The second stage of a coldot is held back: the next rowdot carries it in
+// the same launch unless it reads that stage's output (or is gated differently); anything else
+// flushes it first.  The caller flushes before the results are needed.
+struct ScanQueue {
+  hipStream_t st;
+  Stage2Job pending{};
+  hipError_t flush() {
+    if (!pending.valid) return hipSuccess;
+    pending.valid = false;
+    return launch_stage2(pending, st);
+  }
+  hipError_t run(const ScanJob& j) {
+    hipError_t e;
+    const ScanArgs& s = j.s;
+    const bool can_carry = j.rowdot && pending.valid && s.w != pending.out && s.batch == pending.batch &&
+                           s.gate == pending.gate && s.gate_stride == pending.gate_stride &&
+                           s.gate_value == pending.gate_value;
+    if (pending.valid && !can_carry && (e = flush()) != hipSuccess) return e;
+    if (j.rowdot) {
+      e = launch_rowdot(s, can_carry ? &pending : nullptr, st);
+      pending.valid = false;
+      return e;
+    }
+    return launch_coldot_stage1(s, &pending, st);
+  }
+};
+
+// P_r = A B_P (n x 2) and P_c = A_P B (2 x m) of C-bar; the coldot of the two goes first so that the
+// rowdot can carry its second stage
+hipError_t parity_products(gecc_ctx* c, ScanQueue& q, const void* A, const double* A_par, const void* B,
+                           const double* B_par, double* C_par) {
+  const gecc_params& p = c->p;
+  const int64_t rec = 2 * (int64_t)p.n + 2 * (int64_t)p.m + 4;
+  const ScanJob pr = scan_a_over_k(c, A, B_par, C_par, rec);
+  const ScanJob pc = scan_b_over_k(c, B, A_par, C_par + 2 * (size_t)p.n, rec);
+  hipError_t e;
+  if (!pc.rowdot && pr.rowdot) {
+    if ((e = q.run(pc)) != hipSuccess) return e;
+    return q.run(pr);
+  }
+  if ((e = q.run(pr)) != hipSuccess) return e;
+  return q.run(pc);
 }
 
 GemmArgs gemm_args(const gecc_ctx* c, const void* A, const void* B, float* C) {
@@ -260,7 +300,9 @@ int gecc_encode_a(gecc_ctx* ctx, const void* dev_A, double* dev_A_par, void* str
   if (rc) return rc;
   if (!dev_A || !dev_A_par) return GECC_ERR_ARG;
   if (!aligned_to(dev_A, elem_size(ctx->p.dtype)) || !aligned_to(dev_A_par, 8)) return GECC_ERR_ALIGN;
-  return hip_rc(reduce_a_over_n(ctx, dev_A, nullptr, dev_A_par, nullptr, (hipStream_t)stream));
+  ScanQueue q{(hipStream_t)stream};
+  hipError_t e = q.run(scan_a_over_n(ctx, dev_A, nullptr, dev_A_par, nullptr));
+  return hip_rc(e != hipSuccess ? e : q.flush());
 }
 
 int gecc_encode_b(gecc_ctx* ctx, const void* dev_B, double* dev_B_par, void* stream) {
@@ -268,12 +310,16 @@ int gecc_encode_b(gecc_ctx* ctx, const void* dev_B, double* dev_B_par, void* str
   if (rc) return rc;
   if (!dev_B || !dev_B_par) return GECC_ERR_ARG;
   if (!aligned_to(dev_B, elem_size(ctx->p.dtype)) || !aligned_to(dev_B_par, 8)) return GECC_ERR_ALIGN;
-  return hip_rc(reduce_b_over_m(ctx, dev_B, nullptr, dev_B_par, nullptr, (hipStream_t)stream));
+  ScanQueue q{(hipStream_t)stream};
+  hipError_t e = q.run(scan_b_over_m(ctx, dev_B, nullptr, dev_B_par, nullptr));
+  return hip_rc(e != hipSuccess ? e : q.flush());
 }
 
-int gecc_multiply(gecc_ctx* ctx, const void* dev_A, const double* dev_A_par, const void* dev_B,
-                  const double* dev_B_par, float* dev_C, double* dev_C_par,
-                  const gecc_fault* dev_faults, int32_t n_faults, void* stream) {
+namespace {
+
+int check_multiply_args(gecc_ctx* ctx, const void* dev_A, const double* dev_A_par, const void* dev_B,
+                        const double* dev_B_par, float* dev_C, double* dev_C_par, const gecc_fault* dev_faults,
+                        int32_t n_faults) {
   int rc = check_ws(ctx);
   if (rc) return rc;
   if (!dev_A || !dev_A_par || !dev_B || !dev_B_par || !dev_C || !dev_C_par) return GECC_ERR_ARG;
@@ -282,14 +328,14 @@ int gecc_multiply(gecc_ctx* ctx, const void* dev_A, const double* dev_A_par, con
       !aligned_to(dev_C, 4) || !aligned_to(dev_C_par, 8) || !aligned_to(dev_A_par, 8) ||
       !aligned_to(dev_B_par, 8))
     return GECC_ERR_ALIGN;
-  hipStream_t st = (hipStream_t)stream;
+  return GECC_OK;
+}
+
+// S3 after the parity products: the data block, the fused syndrome partial sums, P_g
+hipError_t product(gecc_ctx* ctx, const void* dev_A, const double* dev_A_par, const void* dev_B,
+                   const double* dev_B_par, float* dev_C, double* dev_C_par, const gecc_fault* dev_faults,
+                   int32_t n_faults, hipStream_t st) {
   const gecc_params& p = ctx->p;
-  hipError_t e;
-  // parity blocks of C-bar: P_r = A B_P (n x 2), P_c = A_P B (2 x m), P_g = A_P B_P
-  const int64_t rec = 2 * (int64_t)p.n + 2 * (int64_t)p.m + 4;
-  if ((e = reduce_a_over_k(ctx, dev_A, dev_B_par, dev_C_par, rec, st)) != hipSuccess) return hip_rc(e);
-  if ((e = reduce_b_over_k(ctx, dev_B, dev_A_par, dev_C_par + 2 * (size_t)p.n, rec, st)) != hipSuccess)
-    return hip_rc(e);
   GemmArgs g = gemm_args(ctx, dev_A, dev_B, dev_C);
   g.rowpart = reinterpret_cast<float*>(ctx->ws + ctx->lay.rowpart);
   g.colpart = reinterpret_cast<float*>(ctx->ws + ctx->lay.colpart);
@@ -299,9 +345,24 @@ int gecc_multiply(gecc_ctx* ctx, const void* dev_A, const double* dev_A_par, con
   // fused verification that follows
   g.A_par = dev_A_par; g.B_par = dev_B_par;
   g.pg_out = dev_C_par + 2 * (size_t)p.n + 2 * (size_t)p.m;
-  g.pg_stride = rec;
+  g.pg_stride = 2 * (int64_t)p.n + 2 * (int64_t)p.m + 4;
   g.state = reinterpret_cast<DecodeState*>(ctx->ws + ctx->lay.state);
-  return hip_rc(timed_gemm(ctx, g, st));
+  return timed_gemm(ctx, g, st);
+}
+
+}  // namespace
+
+int gecc_multiply(gecc_ctx* ctx, const void* dev_A, const double* dev_A_par, const void* dev_B,
+                  const double* dev_B_par, float* dev_C, double* dev_C_par,
+                  const gecc_fault* dev_faults, int32_t n_faults, void* stream) {
+  int rc = check_multiply_args(ctx, dev_A, dev_A_par, dev_B, dev_B_par, dev_C, dev_C_par, dev_faults, n_faults);
+  if (rc) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  ScanQueue q{st};
+  hipError_t e;
+  if ((e = parity_products(ctx, q, dev_A, dev_A_par, dev_B, dev_B_par, dev_C_par)) != hipSuccess) return hip_rc(e);
+  if ((e = q.flush()) != hipSuccess) return hip_rc(e);
+  return hip_rc(product(ctx, dev_A, dev_A_par, dev_B, dev_B_par, dev_C, dev_C_par, dev_faults, n_faults, st));
 }
 
 namespace {
@@ -337,13 +398,48 @@ int correct_impl(gecc_ctx* ctx, void* dev_A, const double* dev_A_par, void* dev_
   // Section V step 2 on the flagged lines; on failure the phase becomes PH_AUDIT
   if ((e = launch_decode_c(d, with_summary, st)) != hipSuccess) return hip_rc(e);
   // operand audit: re-form the parities of A and B as the product read them
-  if ((e = reduce_a_over_n(ctx, dev_A, nullptr, const_cast<double*>(d.audit_a), gate, st)) != hipSuccess)
-    return hip_rc(e);
-  if ((e = reduce_b_over_m(ctx, dev_B, nullptr, const_cast<double*>(d.audit_b), gate, st)) != hipSuccess)
-    return hip_rc(e);
+  // (the coldot of the two first, so that the rowdot carries its second stage)
+  ScanQueue q{st};
+  const ScanJob ja = scan_a_over_n(ctx, dev_A, nullptr, const_cast<double*>(d.audit_a), gate);
+  const ScanJob jb = scan_b_over_m(ctx, dev_B, nullptr, const_cast<double*>(d.audit_b), gate);
+  const bool b_first = ja.rowdot && !jb.rowdot;
+  if ((e = q.run(b_first ? jb : ja)) != hipSuccess) return hip_rc(e);
+  if ((e = q.run(b_first ? ja : jb)) != hipSuccess) return hip_rc(e);
+  if ((e = q.flush()) != hipSuccess) return hip_rc(e);
   // parity differences, operand patches, rank-one repair of C-bar with the residual syndromes
   // kept up to date, then Section V once more -- all in one workgroup per batch item
   return hip_rc(launch_repair(d, st));
+}
+
+}  // namespace
+
+namespace {
+
+// S1-S3 as one chain of scans.  The order of the four scans depends on how the operands are stored
+// (which of them are rowdots) and on what reads what: P_r needs B_P, P_c needs A_P.
+int encode_and_multiply(gecc_ctx* ctx, void* dev_A, void* dev_B, float* dev_C, double* dev_A_par,
+                        double* dev_B_par, double* dev_C_par, const gecc_fault* dev_faults, int32_t n_faults,
+                        hipStream_t st) {
+  int rc = check_multiply_args(ctx, dev_A, dev_A_par, dev_B, dev_B_par, dev_C, dev_C_par, dev_faults, n_faults);
+  if (rc) return rc;
+  const gecc_params& p = ctx->p;
+  const int64_t rec = 2 * (int64_t)p.n + 2 * (int64_t)p.m + 4;
+  const ScanJob ea = scan_a_over_n(ctx, dev_A, nullptr, dev_A_par, nullptr);
+  const ScanJob eb = scan_b_over_m(ctx, dev_B, nullptr, dev_B_par, nullptr);
+  const ScanJob pr = scan_a_over_k(ctx, dev_A, dev_B_par, dev_C_par, rec);
+  const ScanJob pc = scan_b_over_k(ctx, dev_B, dev_A_par, dev_C_par + 2 * (size_t)p.n, rec);
+  // stored:        A n x k, B k x m   A n x k, B m x k   A k x n, B k x m   A k x n, B m x k
+  // rowdots:       B_P, P_r           P_r, P_c           A_P, B_P           A_P, P_c
+  const ScanJob* order[4];
+  if (!p.trans_a) { order[0] = &ea; order[1] = &eb; order[2] = &pc; order[3] = &pr; }
+  else if (!p.trans_b) { order[0] = &eb; order[1] = &pr; order[2] = &ea; order[3] = &pc; }
+  else { order[0] = &eb; order[1] = &ea; order[2] = &pr; order[3] = &pc; }
+  ScanQueue q{st};
+  hipError_t e;
+  for (int x = 0; x < 4; ++x)
+    if ((e = q.run(*order[x])) != hipSuccess) return hip_rc(e);
+  if ((e = q.flush()) != hipSuccess) return hip_rc(e);
+  return hip_rc(product(ctx, dev_A, dev_A_par, dev_B, dev_B_par, dev_C, dev_C_par, dev_faults, n_faults, st));
 }
 
 }  // namespace
@@ -371,9 +467,8 @@ int gecc_protected_gemm(gecc_ctx* ctx, void* dev_A, void* dev_B, float* dev_C, d
                         double* dev_B_par, double* dev_C_par, gecc_report* dev_report, void* stream) {
   int rc;
   if (!dev_report) return GECC_ERR_ARG;
-  if ((rc = gecc_encode_a(ctx, dev_A, dev_A_par, stream))) return rc;
-  if ((rc = gecc_encode_b(ctx, dev_B, dev_B_par, stream))) return rc;
-  if ((rc = gecc_multiply(ctx, dev_A, dev_A_par, dev_B, dev_B_par, dev_C, dev_C_par, nullptr, 0, stream)))
+  if ((rc = encode_and_multiply(ctx, dev_A, dev_B, dev_C, dev_A_par, dev_B_par, dev_C_par, nullptr, 0,
+                                (hipStream_t)stream)))
     return rc;
   if ((rc = verify_impl(ctx, dev_C, dev_C_par, dev_report, 1, 0, (hipStream_t)stream))) return rc;
   return correct_impl(ctx, dev_A, dev_A_par, dev_B, dev_B_par, dev_C, dev_C_par, dev_report, 1,
@@ -387,13 +482,14 @@ int gecc_protected_gemm_retry(gecc_ctx* ctx, void* dev_A, void* dev_B, float* de
   int rc;
   if (!dev_report || !host_report || max_retries < 0) return GECC_ERR_ARG;
   if (attempts) *attempts = 0;
-  if ((rc = gecc_encode_a(ctx, dev_A, dev_A_par, stream))) return rc;
-  if ((rc = gecc_encode_b(ctx, dev_B, dev_B_par, stream))) return rc;
   for (int32_t a = 0; a <= max_retries; ++a) {
     // the planted faults are transient: they strike the first product only
-    if ((rc = gecc_multiply(ctx, dev_A, dev_A_par, dev_B, dev_B_par, dev_C, dev_C_par,
-                            a == 0 ? dev_faults : nullptr, a == 0 ? n_faults : 0, stream)))
-      return rc;
+    if (a == 0)
+      rc = encode_and_multiply(ctx, dev_A, dev_B, dev_C, dev_A_par, dev_B_par, dev_C_par, dev_faults, n_faults,
+                               (hipStream_t)stream);
+    else
+      rc = gecc_multiply(ctx, dev_A, dev_A_par, dev_B, dev_B_par, dev_C, dev_C_par, nullptr, 0, stream);
+    if (rc) return rc;
     if ((rc = verify_impl(ctx, dev_C, dev_C_par, dev_report, 1, 0, (hipStream_t)stream))) return rc;
     if ((rc = correct_impl(ctx, dev_A, dev_A_par, dev_B, dev_B_par, dev_C, dev_C_par, dev_report, 1,
                            (hipStream_t)stream)))

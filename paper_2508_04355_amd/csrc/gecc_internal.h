@@ -83,9 +83,31 @@ struct ScanArgs {
   const int32_t* gate;
   int64_t gate_stride;  // in bytes
   int gate_value;
+  // rowdot only: the second stage of an earlier coldot launch, done by carry_blocks extra
+  // workgroups at the end of the grid (same batch and gate as the carrier)
+  const double* carry_scratch;
+  double* carry_out;
+  int64_t carry_out_stride;
+  int carry_Cc, carry_nchunk, carry_blocks;
 };
-hipError_t launch_rowdot(const ScanArgs& a, hipStream_t st);
-hipError_t launch_coldot(const ScanArgs& a, hipStream_t st);
+// Second stage of a coldot that has not been launched yet: either launch_stage2() runs it as a
+// kernel of its own, or the next rowdot launch carries it (a dependent launch costs about 5 us of
+// stream time whatever it does, and this stage is tiny).
+struct Stage2Job {
+  bool valid;
+  const double* scratch;
+  double* out;
+  int64_t out_stride;
+  int Cc, nchunk, batch;
+  const int32_t* gate;
+  int64_t gate_stride;
+  int gate_value;
+};
+// carry: null, or a pending second stage whose output this scan does not read
+hipError_t launch_rowdot(const ScanArgs& a, const Stage2Job* carry, hipStream_t st);
+// launches the first stage only and describes the second in *pending
+hipError_t launch_coldot_stage1(const ScanArgs& a, Stage2Job* pending, hipStream_t st);
+hipError_t launch_stage2(const Stage2Job& j, hipStream_t st);
 size_t coldot_scratch_doubles(int R, int Cc, int batch);
 
 // ---- product (gemm_kernels.hip) ------------------------------------------------------------

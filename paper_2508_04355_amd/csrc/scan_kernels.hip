@@ -46,6 +46,29 @@ __device__ __forceinline__ bool gated_off(const int32_t* gate, int64_t stride, i
   return g != value;
 }
 
+// Stage 2 of coldot (see below): 64 outputs per workgroup of 256 threads; the 4 wavefronts take
+// the chunks 4 apart and are combined in order.  scratch, out: of batch item b.
+__device__ __forceinline__ void coldot_stage2_body(const double* scratch, double* out, int Cc, int nchunk, int blk) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int o = blk * 64 + lane;                   // index into [2][Cc]
+  __shared__ double red[4][64];
+  double s = 0.0;
+  if (o < 2 * Cc) {
+    const double* part = scratch + o;
+    double t[4] = {0.0, 0.0, 0.0, 0.0};
+    int ch = wave;
+    for (; ch + 12 < nchunk; ch += 16) {           // 4 loads in flight
+#pragma unroll
+      for (int u = 0; u < 4; ++u) t[u] += part[(int64_t)(ch + 4 * u) * 2 * Cc];
+    }
+    for (; ch < nchunk; ch += 4) t[0] += part[(int64_t)ch * 2 * Cc];
+    s = (t[0] + t[1]) + (t[2] + t[3]);
+  }
+  red[wave][lane] = s;
+  __syncthreads();
+  if (wave == 0 && o < 2 * Cc) out[o] = (red[0][lane] + red[1][lane]) + (red[2][lane] + red[3][lane]);
+}
+
 // -------------------------------------------------------------------------------------------
 // rowdot: out[t][r] = sum_c w_t[c] X[r,c].   One workgroup owns RB rows and walks all columns;
 // a thread keeps the weights of its VEC columns in registers and reuses them for the RB rows.
@@ -65,6 +88,13 @@ __global__ __launch_bounds__(RD_THREADS) void rowdot_kernel(ScanArgs a) {
   constexpr int STEP = RD_THREADS * VEC;   // columns one pass of the workgroup covers
   const int b = blockIdx.y;
   if (gated_off(a.gate, a.gate_stride, b, a.gate_value)) return;
+  const int own = (int)gridDim.x - a.carry_blocks;
+  if ((int)blockIdx.x >= own) {   // carried second stage of an earlier coldot
+    coldot_stage2_body(a.carry_scratch + (int64_t)b * a.carry_nchunk * 2 * a.carry_Cc,
+                       a.carry_out + (int64_t)b * a.carry_out_stride, a.carry_Cc, a.carry_nchunk,
+                       (int)blockIdx.x - own);
+    return;
+  }
   const T* X = reinterpret_cast<const T*>(a.X) + (int64_t)b * a.xs;
   const double* w0 = IDXW ? nullptr : a.w + (int64_t)b * a.w_stride;
   const double* w1 = IDXW ? nullptr : w0 + a.Cc;
@@ -277,29 +307,11 @@ __global__ __launch_bounds__(CD_THREADS) void coldot_stage1(ScanArgs a, int nchu
   }
 }
 
-// 64 outputs per workgroup; the 4 wavefronts take the chunks 4 apart and are combined in order
-__global__ __launch_bounds__(256) void coldot_stage2(ScanArgs a, int nchunk) {
+__global__ __launch_bounds__(256) void coldot_stage2(Stage2Job j) {
   const int b = blockIdx.y;
-  if (gated_off(a.gate, a.gate_stride, b, a.gate_value)) return;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int o = blockIdx.x * 64 + lane;            // index into [2][Cc]
-  __shared__ double red[4][64];
-  double s = 0.0;
-  if (o < 2 * a.Cc) {
-    const double* part = a.scratch + (int64_t)b * nchunk * 2 * a.Cc + o;
-    double t[4] = {0.0, 0.0, 0.0, 0.0};
-    int ch = wave;
-    for (; ch + 12 < nchunk; ch += 16) {           // 4 loads in flight
-#pragma unroll
-      for (int u = 0; u < 4; ++u) t[u] += part[(int64_t)(ch + 4 * u) * 2 * a.Cc];
-    }
-    for (; ch < nchunk; ch += 4) t[0] += part[(int64_t)ch * 2 * a.Cc];
-    s = (t[0] + t[1]) + (t[2] + t[3]);
-  }
-  red[wave][lane] = s;
-  __syncthreads();
-  if (wave == 0 && o < 2 * a.Cc)
-    a.out[(int64_t)b * a.out_stride + o] = (red[0][lane] + red[1][lane]) + (red[2][lane] + red[3][lane]);
+  if (gated_off(j.gate, j.gate_stride, b, j.gate_value)) return;
+  coldot_stage2_body(j.scratch + (int64_t)b * j.nchunk * 2 * j.Cc, j.out + (int64_t)b * j.out_stride, j.Cc,
+                     j.nchunk, blockIdx.x);
 }
 
 // vector loads need 16-byte aligned rows
@@ -316,19 +328,29 @@ size_t coldot_scratch_doubles(int R, int Cc, int batch) {
   return (size_t)batch * nchunk * 2 * (size_t)Cc;
 }
 
-hipError_t launch_rowdot(const ScanArgs& a0, hipStream_t st) {
+hipError_t launch_rowdot(const ScanArgs& a0, const Stage2Job* carry, hipStream_t st) {
   ScanArgs a = a0;
   a.vec_ok = vec_ok(a0) ? 1 : 0;
+  a.carry_blocks = 0;
+  if (carry && carry->valid) {
+    if (carry->batch != a.batch || carry->gate != a.gate || carry->gate_stride != a.gate_stride ||
+        carry->gate_value != a.gate_value)
+      return hipErrorInvalidValue;
+    a.carry_scratch = carry->scratch; a.carry_out = carry->out; a.carry_out_stride = carry->out_stride;
+    a.carry_Cc = carry->Cc; a.carry_nchunk = carry->nchunk;
+    a.carry_blocks = (2 * carry->Cc + 63) / 64;
+  }
+  const int extra = a.carry_blocks;
   const bool idx = a.w == nullptr;
   const bool small = (int64_t)((a.R + RD_BIG_RB - 1) / RD_BIG_RB) * a.batch < 1024;   // fewer than 4 workgroups per CU
 #define GECC_LAUNCH_ROWDOT(DT, IDX)                                                                  \
   do {                                                                                              \
     constexpr int BIG = IDX ? RD_BIG_RB : RD_BIG_RB_W;                                                \
     if (small) hipLaunchKernelGGL((rowdot_kernel<DT, IDX, RD_SMALL_RB, RD_SMALL_U>),                  \
-                                  dim3((a.R + RD_SMALL_RB - 1) / RD_SMALL_RB, a.batch),               \
+                                  dim3((a.R + RD_SMALL_RB - 1) / RD_SMALL_RB + extra, a.batch),       \
                                   dim3(RD_THREADS), 0, st, a);                                        \
     else       hipLaunchKernelGGL((rowdot_kernel<DT, IDX, BIG, RD_BIG_U>),                            \
-                                  dim3((a.R + BIG - 1) / BIG, a.batch),                               \
+                                  dim3((a.R + BIG - 1) / BIG + extra, a.batch),                       \
                                   dim3(RD_THREADS), 0, st, a);                                        \
   } while (0)
   if (a.dtype == GECC_BF16) {
@@ -340,9 +362,10 @@ hipError_t launch_rowdot(const ScanArgs& a0, hipStream_t st) {
   return hipGetLastError();
 }
 
-hipError_t launch_coldot(const ScanArgs& a0, hipStream_t st) {
+hipError_t launch_coldot_stage1(const ScanArgs& a0, Stage2Job* pending, hipStream_t st) {
   ScanArgs a = a0;
   a.vec_ok = vec_ok(a0) ? 1 : 0;
+  a.carry_blocks = 0;
   const int vec = a.dtype == GECC_BF16 ? 8 : 4;
   const int nchunk = (a.R + SCAN_CHUNK_ROWS - 1) / SCAN_CHUNK_ROWS;
   dim3 grid((a.Cc + 64 * vec - 1) / (64 * vec), nchunk, a.batch);
@@ -354,10 +377,16 @@ hipError_t launch_coldot(const ScanArgs& a0, hipStream_t st) {
     if (idx) hipLaunchKernelGGL((coldot_stage1<GECC_F32, true>), grid, dim3(CD_THREADS), 0, st, a, nchunk);
     else     hipLaunchKernelGGL((coldot_stage1<GECC_F32, false>), grid, dim3(CD_THREADS), 0, st, a, nchunk);
   }
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  dim3 g2((2 * a.Cc + 63) / 64, a.batch);
-  hipLaunchKernelGGL(coldot_stage2, g2, dim3(256), 0, st, a, nchunk);
+  pending->valid = true;
+  pending->scratch = a.scratch; pending->out = a.out; pending->out_stride = a.out_stride;
+  pending->Cc = a.Cc; pending->nchunk = nchunk; pending->batch = a.batch;
+  pending->gate = a.gate; pending->gate_stride = a.gate_stride; pending->gate_value = a.gate_value;
+  return hipGetLastError();
+}
+
+hipError_t launch_stage2(const Stage2Job& j, hipStream_t st) {
+  dim3 g2((2 * j.Cc + 63) / 64, j.batch);
+  hipLaunchKernelGGL(coldot_stage2, g2, dim3(256), 0, st, j);
   return hipGetLastError();
 }
 
