@@ -168,6 +168,13 @@ int gecc_verify(gecc_ctx* ctx, const float* dev_C, const double* dev_C_par,
                 gecc_report* dev_report, int32_t fused, void* stream);
 
 /* S6 + S7, Section V step 2 and the operand audit: locates and removes the errors.
+   Order: at most two flagged rows and two flagged columns: Section V's rule, every estimate
+   verified against the syndromes.  Anything else, or a failed verification: both operands are
+   re-encoded and compared with their stored parities (Section III: every column of A-bar, every
+   row of B-bar is a codeword of its own); located operand symbols are patched and their
+   rank-one footprint is taken out of C-bar; what is left goes through Section V's rule again or,
+   with errors in many columns of at most two flagged rows (or the mirror image), through the
+   decoder of Theorem 2 (Appendix B).
    Patches dev_A / dev_B / dev_C / dev_C_par in place; dev_report must be the one
    gecc_verify just filled.  All work is gated on device-side state, so the call is cheap
    when the report says CLEAN.  On GECC_UNCORRECTABLE the buffers hold whatever the attempt
@@ -203,7 +210,8 @@ int gecc_report_to_host(gecc_ctx* ctx, const gecc_report* dev_report, gecc_repor
                         int32_t count, void* stream);
 
 /* Copies the syndromes of the last gecc_verify (r1[n], r2[n], q1[m], q2[m] per batch item,
-   doubles) device -> host and waits; for threshold calibration. */
+   doubles) device -> host and waits; for threshold calibration.  A gecc_correct that repaired
+   an operand error has moved them to the syndromes of the repaired C-bar. */
 int gecc_syndromes_to_host(gecc_ctx* ctx, double* host_syndromes, void* stream);
 
 /* Timing of the product kernel (the kernel of gecc_multiply / gecc_plain_gemm that holds all
