@@ -64,6 +64,18 @@ def run_gpu(A_enc, B_enc, A_mul, B_mul, c_faults, tau, dtype, trans_a=0, trans_b
     rep = ctx.alloc_report()
     Cd = ctx.alloc_c()
     Cd.fill_(float("nan"))
+    if not staged:
+        # the one-call chain: everything in one stream-ordered sequence, C faults planted into its
+        # product; there is no point between its encode and its product for an operand fault
+        assert fused and np.array_equal(A_enc, A_mul) and np.array_equal(B_enc, B_mul)
+        fl, nf = gecc.make_faults(c_faults, DEV)
+        reports, attempts = ctx.protected_gemm_retry(dA, dB, Cd, A_par, B_par, C_par, rep, 0, fl, nf)
+        assert attempts == 1
+        return GpuResult(reports=reports,
+                         C=Cd.cpu().numpy().astype(np.float64)[:, :, :m],
+                         A=from_dev(dA, trans_a, n if trans_a else k), B=from_dev(dB, trans_b, k if trans_b else m),
+                         A_par=A_par.cpu().numpy().reshape(batch, 2, k), B_par=B_par.cpu().numpy().reshape(batch, 2, k),
+                         C_par=C_par.cpu().numpy().reshape(batch, -1), synd=ctx.syndromes_to_host())
     ctx.encode_a(dA, A_par)
     ctx.encode_b(dB, B_par)
     # operand faults strike after the parities were formed (E1/E2)

@@ -149,6 +149,26 @@ def test_recomputation_after_an_uncorrectable_pattern():
     assert np.max(np.abs(Cd[0].cpu().numpy() - ref)) / np.max(np.abs(ref)) <= 1e-5
 
 
+@pytest.mark.parametrize("trans", [(0, 0), (0, 1), (1, 0), (1, 1)])
+@pytest.mark.parametrize("dtype,shape,batch", [("f32", (300, 200, 260), 2), ("bf16", (520, 256, 264), 1)])
+def test_one_call_chain_equals_the_staged_calls_bit_for_bit(dtype, shape, batch, trans):
+    """gecc_protected_gemm orders its four parity scans by storage layout and lets row scans carry
+    the second stage of column scans; none of that may change a bit of any result."""
+    n, k, m = shape
+    rng = inputs.rng_for(95, trans[0] * 2 + trans[1])
+    A = np.stack([inputs.operands(rng, n, k, m, ("normal", 1.0), ("normal", 1.0), dtype)[0] for _ in range(batch)])
+    B = np.stack([inputs.operands(rng, n, k, m, ("normal", 1.0), ("normal", 1.0), dtype)[1] for _ in range(batch)])
+    tau = gecc.noise_thresholds(n, k, m, 1.0, 1.0)
+    cf = [(b, 7 + b, 250, 40.0) for b in range(batch)] + [(0, n - 1, 3, -25.0)]
+    g1 = H.run_gpu(A, B, A, B, cf, tau, dtype, trans[0], trans[1], staged=True)
+    g2 = H.run_gpu(A, B, A, B, cf, tau, dtype, trans[0], trans[1], staged=False)
+    for name in ("A_par", "B_par", "C_par", "C", "synd"):
+        assert np.array_equal(getattr(g1, name), getattr(g2, name)), name
+    for r1, r2 in zip(g1.reports, g2.reports):
+        assert (r1.status, r1.n_total, r1.errors()) == (r2.status, r2.n_total, r2.errors())
+    H.compare(g2, H.run_oracle(A, B, A, B, cf, tau), 1e-5, what="one call")
+
+
 def test_unaligned_leading_dimensions_take_the_scalar_paths():
     n, k, m = 67, 45, 83
     rng = inputs.rng_for(91)
