@@ -8,6 +8,10 @@ fault list itself.  Prints one JSON object.
 
     python -m paper_2508_04355_amd.campaign --workload cfg3 --trials 10000
 
+Pairs of faults in one column of A (one row of B) are beyond the code (that line carries two
+parity symbols, Section III); they are counted in classes of their own, where "corrected_exactly"
+means the expected outcome, UNCORRECTABLE.
+
 Fault classes follow the paper's scenarios (Section VI: a = A, b = B, c = C, d = A+C,
 e = B+C, f = C+C) plus the pairs it does not test (A+A, B+B, A+B) and the fault-free case.
 """
@@ -101,7 +105,7 @@ def run(workload: str, trials: int, seed_cfg: int = 30, progress=None):
             failures.append({"trial": t, "class": cls, "status": int(r.status), "n_total": int(r.n_total),
                              "faults": [[int(f.matrix), int(f.row), int(f.col), float(f.offset)] for f in faults],
                              "located": [[int(e[0]), int(e[1]), int(e[2]), float(e[3])] for e in r.errors()]})
-        if touched and not exact:                       # the decoder may have patched elsewhere
+        if touched and (not exact or r.status != gecc.CORRECTED):   # the attempt may have patched elsewhere
             dA.copy_(Aclean)
             dB.copy_(Bclean)
         for (T, i, j, old) in touched:                  # restore the planted symbols
