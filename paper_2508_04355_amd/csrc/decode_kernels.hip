@@ -55,16 +55,14 @@ __global__ void reset_state_kernel(DecodeArgs a) {
 constexpr int TH_SLICES = 4;    // wavefronts of a workgroup; each adds every 4th sub-tile of a line
 constexpr int TH_MAXLOADS = 32; // loads a thread keeps in flight
 
-__global__ __launch_bounds__(64 * TH_SLICES) void threshold_kernel(DecodeArgs a, int first) {
+__global__ __launch_bounds__(64 * TH_SLICES) void threshold_kernel(DecodeArgs a) {
   const int b = blockIdx.y;
   DecodeState* st = state_of(a, b);
-  if (!first && st->phase != PH_REVERIFY) return;
   const int n = a.p.n, m = a.p.m;
   const int lane = threadIdx.x & 63, slice = threadIdx.x >> 6;
   const int o = blockIdx.x * 64 + lane;          // line: rows first, then columns
   const double* cpar = cpar_of(a, b);
   double* synd = synd_of(a, b);
-  const double* allow = allow_of(a, b);   // valid in the residual pass only
   const bool is_row = o < n, valid = o < n + m;
 
   // partial sums of this line over the sub-tiles slice, slice + 4, ... (fixed order); all loads
@@ -106,8 +104,7 @@ __global__ __launch_bounds__(64 * TH_SLICES) void threshold_kernel(DecodeArgs a,
       v2 = W - cpar[n + i];
       synd[i] = v1;
       synd[n + i] = v2;
-      const double x1 = first ? 0.0 : allow[i], x2 = first ? 0.0 : allow[n + i];
-      if (fabs(v1) > a.p.tau_r1 + x1 || fabs(v2) > a.p.tau_r2 + x2) {
+      if (fabs(v1) > a.p.tau_r1 || fabs(v2) > a.p.tau_r2) {
         const int idx = atomicAdd(&st->s_cnt, 1);
         if (idx < GECC_MAX_ERR) st->rows[idx] = i;
       }
@@ -117,14 +114,13 @@ __global__ __launch_bounds__(64 * TH_SLICES) void threshold_kernel(DecodeArgs a,
       v2 = W - cpar[2 * n + m + j];
       synd[2 * n + j] = v1;
       synd[2 * n + m + j] = v2;
-      const double x1 = first ? 0.0 : allow[2 * n + j], x2 = first ? 0.0 : allow[2 * n + m + j];
-      if (fabs(v1) > a.p.tau_q1 + x1 || fabs(v2) > a.p.tau_q2 + x2) {
+      if (fabs(v1) > a.p.tau_q1 || fabs(v2) > a.p.tau_q2) {
         const int idx = atomicAdd(&st->t_cnt, 1);
         if (idx < GECC_MAX_ERR) st->cols[idx] = j;
       }
     }
   }
-  if (first) {
+  {
     // family maxima of this workgroup (rows: [0], [1]; columns: [2], [3]); the summary reduces
     // them (atomics on one line from every workgroup would serialise in L2)
     double mr1 = (valid && is_row) ? fabs(v1) : 0.0, mr2 = (valid && is_row) ? fabs(v2) : 0.0;
@@ -298,9 +294,19 @@ __device__ int d0_correct(Est* out, const int* Er, int s, const int* Et, int t, 
 // fp64 dot product of row i of A with column j of B over k, by the whole workgroup
 __device__ double block_dot(const DecodeArgs& a, int b, int i, int j, double* red) {
   double s = 0.0;
-  for (int l = threadIdx.x; l < a.p.k; l += DC_THREADS)
-    s = fma(load_elem(a.A, a.p.dtype, a_index(a.p, b, i, l)),
-            load_elem(a.B, a.p.dtype, b_index(a.p, b, l, j)), s);
+  constexpr int U = 8;   // products per thread whose loads are issued together (one workgroup: latency-bound)
+  for (int l0 = threadIdx.x; l0 < a.p.k; l0 += U * DC_THREADS) {
+    double x[U], y[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int l = min(l0 + u * DC_THREADS, a.p.k - 1);
+      x[u] = load_elem(a.A, a.p.dtype, a_index(a.p, b, i, l));
+      y[u] = load_elem(a.B, a.p.dtype, b_index(a.p, b, l, j));
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (l0 + u * DC_THREADS < a.p.k) s = fma(x[u], y[u], s);
+  }
   red[threadIdx.x] = s;
   __syncthreads();
   for (int w = DC_THREADS / 2; w > 0; w >>= 1) {
@@ -569,6 +575,7 @@ __device__ void sort_hits(AuditHit* h, int cnt) {
 // corrected A.  The operands themselves are written last, so nothing here depends on a
 // store becoming visible to another wavefront.
 constexpr int RP_THREADS = 1024;   // one workgroup per batch item: latency-bound loops, so a full one
+constexpr int RP_U = 4;            // symbols (lines) a thread has in flight
 
 __global__ __launch_bounds__(RP_THREADS) void repair_kernel(DecodeArgs a) {
   const int b = blockIdx.x;
@@ -585,6 +592,7 @@ __global__ __launch_bounds__(RP_THREADS) void repair_kernel(DecodeArgs a) {
     const double* cur_b = a.audit_b + (int64_t)b * 2 * k;
     const double* ref_a = a.A_par + (int64_t)b * 2 * k;
     const double* ref_b = a.B_par + (int64_t)b * 2 * k;
+#pragma unroll 4
     for (int l = threadIdx.x; l < k; l += blockDim.x) {
       bool hit;
       AuditHit h = audit_line(cur_a, ref_a, k, l, n, a.p.tau_op, &hit);
@@ -636,20 +644,35 @@ __global__ __launch_bounds__(RP_THREADS) void repair_kernel(DecodeArgs a) {
       cpar[n + i] -= e * bpar[k + l];      // cbar_{i,m+2}
     }
     double s2 = 0.0, w2 = 0.0, ds = 0.0, dw = 0.0;
-    for (int j = threadIdx.x; j < m; j += blockDim.x) {
-      const int64_t ic = (int64_t)i * a.p.ldc + j;
-      const double f = e * load_elem(a.B, a.p.dtype, b_index(a.p, b, l, j));
-      const float cold = C[ic], cnew = (float)((double)cold - f);
-      C[ic] = cnew;
-      const double d = (double)cold - (double)cnew;      // what the sums of row i and column j lose
-      sy_q1[j] -= d;
-      sy_q2[j] -= (double)(i + 1) * d;
-      ds += d;
-      dw += (double)(j + 1) * d;
-      s2 += f * f;
-      w2 += (double)(j + 1) * (j + 1) * f * f;
-      al_q1[j] += cc * fabs(f);
-      al_q2[j] += cc * (double)(i + 1) * fabs(f);
+    // (RP_U symbols per thread at a time: all their loads are issued before the first store, one
+    // workgroup has nothing else to hide the memory latency with)
+    for (int j0 = threadIdx.x; j0 < m; j0 += RP_U * RP_THREADS) {
+      float cold[RP_U];
+      double bv[RP_U], q1[RP_U], q2[RP_U], g1[RP_U], g2[RP_U];
+#pragma unroll
+      for (int u = 0; u < RP_U; ++u) {
+        const int j = min(j0 + u * RP_THREADS, m - 1);
+        cold[u] = C[(int64_t)i * a.p.ldc + j];
+        bv[u] = load_elem(a.B, a.p.dtype, b_index(a.p, b, l, j));
+        q1[u] = sy_q1[j]; q2[u] = sy_q2[j]; g1[u] = al_q1[j]; g2[u] = al_q2[j];
+      }
+#pragma unroll
+      for (int u = 0; u < RP_U; ++u) {
+        const int j = j0 + u * RP_THREADS;
+        if (j >= m) break;
+        const double f = e * bv[u];
+        const float cnew = (float)((double)cold[u] - f);
+        C[(int64_t)i * a.p.ldc + j] = cnew;
+        const double d = (double)cold[u] - (double)cnew;   // what the sums of row i and column j lose
+        sy_q1[j] = q1[u] - d;
+        sy_q2[j] = q2[u] - (double)(i + 1) * d;
+        ds += d;
+        dw += (double)(j + 1) * d;
+        s2 += f * f;
+        w2 += (double)(j + 1) * (j + 1) * f * f;
+        al_q1[j] = g1[u] + cc * fabs(f);
+        al_q2[j] = g2[u] + cc * (double)(i + 1) * fabs(f);
+      }
     }
     red[0][threadIdx.x] = s2; red[1][threadIdx.x] = w2; red[2][threadIdx.x] = ds; red[3][threadIdx.x] = dw;
     __syncthreads();
@@ -673,23 +696,36 @@ __global__ __launch_bounds__(RP_THREADS) void repair_kernel(DecodeArgs a) {
       cpar[2 * n + m + j] -= apar[k + l] * e;  // cbar_{n+2,j}
     }
     double s2 = 0.0, w2 = 0.0, ds = 0.0, dw = 0.0;
-    for (int i = threadIdx.x; i < n; i += blockDim.x) {
-      double av = load_elem(a.A, a.p.dtype, a_index(a.p, b, i, l));
-      for (int z = 0; z < na; ++z)
-        if (ha[z].pos == i && ha[z].line == l) av -= ha[z].e;   // corrected A
-      const int64_t ic = (int64_t)i * a.p.ldc + j;
-      const double f = av * e;
-      const float cold = C[ic], cnew = (float)((double)cold - f);
-      C[ic] = cnew;
-      const double d = (double)cold - (double)cnew;
-      sy_r1[i] -= d;
-      sy_r2[i] -= (double)(j + 1) * d;
-      ds += d;
-      dw += (double)(i + 1) * d;
-      s2 += f * f;
-      w2 += (double)(i + 1) * (i + 1) * f * f;
-      al_r1[i] += cc * fabs(f);
-      al_r2[i] += cc * (double)(j + 1) * fabs(f);
+    for (int i0 = threadIdx.x; i0 < n; i0 += RP_U * RP_THREADS) {
+      float cold[RP_U];
+      double av[RP_U], r1[RP_U], r2[RP_U], g1[RP_U], g2[RP_U];
+#pragma unroll
+      for (int u = 0; u < RP_U; ++u) {
+        const int i = min(i0 + u * RP_THREADS, n - 1);
+        cold[u] = C[(int64_t)i * a.p.ldc + j];
+        av[u] = load_elem(a.A, a.p.dtype, a_index(a.p, b, i, l));
+        r1[u] = sy_r1[i]; r2[u] = sy_r2[i]; g1[u] = al_r1[i]; g2[u] = al_r2[i];
+      }
+#pragma unroll
+      for (int u = 0; u < RP_U; ++u) {
+        const int i = i0 + u * RP_THREADS;
+        if (i >= n) break;
+        double ai = av[u];
+        for (int z = 0; z < na; ++z)
+          if (ha[z].pos == i && ha[z].line == l) ai -= ha[z].e;   // corrected A
+        const double f = ai * e;
+        const float cnew = (float)((double)cold[u] - f);
+        C[(int64_t)i * a.p.ldc + j] = cnew;
+        const double d = (double)cold[u] - (double)cnew;
+        sy_r1[i] = r1[u] - d;
+        sy_r2[i] = r2[u] - (double)(j + 1) * d;
+        ds += d;
+        dw += (double)(i + 1) * d;
+        s2 += f * f;
+        w2 += (double)(i + 1) * (i + 1) * f * f;
+        al_r1[i] = g1[u] + cc * fabs(f);
+        al_r2[i] = g2[u] + cc * (double)(j + 1) * fabs(f);
+      }
     }
     red[0][threadIdx.x] = s2; red[1][threadIdx.x] = w2; red[2][threadIdx.x] = ds; red[3][threadIdx.x] = dw;
     __syncthreads();
@@ -744,17 +780,27 @@ __global__ __launch_bounds__(RP_THREADS) void repair_kernel(DecodeArgs a) {
   __shared__ int res_s, res_t;
   if (threadIdx.x == 0) { res_s = 0; res_t = 0; }
   __syncthreads();
-  for (int o = threadIdx.x; o < n + m; o += blockDim.x) {
-    if (o < n) {
-      if (fabs(sy_r1[o]) > a.p.tau_r1 + al_r1[o] || fabs(sy_r2[o]) > a.p.tau_r2 + al_r2[o]) {
-        const int idx = atomicAdd(&res_s, 1);
-        if (idx < GECC_MAX_ERR) st->rows[idx] = o;
-      }
-    } else {
-      const int j = o - n;
-      if (fabs(sy_q1[j]) > a.p.tau_q1 + al_q1[j] || fabs(sy_q2[j]) > a.p.tau_q2 + al_q2[j]) {
+  for (int o0 = threadIdx.x; o0 < n + m; o0 += 2 * RP_U * RP_THREADS) {
+    double y1[2 * RP_U], y2[2 * RP_U], g1[2 * RP_U], g2[2 * RP_U];
+#pragma unroll
+    for (int u = 0; u < 2 * RP_U; ++u) {
+      const int o = min(o0 + u * RP_THREADS, n + m - 1);
+      // row line o: r1 at [o], r2 at [n + o]; column line j = o - n: q1 at [2n + j], q2 at [2n + m + j]
+      const int p1 = o < n ? o : n + o, p2 = o < n ? n + o : n + m + o;
+      y1[u] = sy_r1[p1]; y2[u] = sy_r1[p2]; g1[u] = al_r1[p1]; g2[u] = al_r1[p2];
+    }
+#pragma unroll
+    for (int u = 0; u < 2 * RP_U; ++u) {
+      const int o = o0 + u * RP_THREADS;
+      if (o >= n + m) break;
+      if (o < n) {
+        if (fabs(y1[u]) > a.p.tau_r1 + g1[u] || fabs(y2[u]) > a.p.tau_r2 + g2[u]) {
+          const int idx = atomicAdd(&res_s, 1);
+          if (idx < GECC_MAX_ERR) st->rows[idx] = o;
+        }
+      } else if (fabs(y1[u]) > a.p.tau_q1 + g1[u] || fabs(y2[u]) > a.p.tau_q2 + g2[u]) {
         const int idx = atomicAdd(&res_t, 1);
-        if (idx < GECC_MAX_ERR) st->cols[idx] = j;
+        if (idx < GECC_MAX_ERR) st->cols[idx] = o - n;
       }
     }
   }
@@ -773,9 +819,9 @@ hipError_t launch_reset_state(const DecodeArgs& a, hipStream_t st) {
   return hipGetLastError();
 }
 
-hipError_t launch_threshold(const DecodeArgs& a, int first, hipStream_t st) {
+hipError_t launch_threshold(const DecodeArgs& a, hipStream_t st) {
   dim3 grid((a.p.n + a.p.m + 63) / 64, a.p.batch);   // 64 lines per workgroup: spreads over all CUs
-  hipLaunchKernelGGL(threshold_kernel, grid, dim3(64 * TH_SLICES), 0, st, a, first);
+  hipLaunchKernelGGL(threshold_kernel, grid, dim3(64 * TH_SLICES), 0, st, a);
   return hipGetLastError();
 }
 

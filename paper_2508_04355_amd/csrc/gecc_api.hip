@@ -385,7 +385,7 @@ int verify_impl(gecc_ctx* ctx, const float* dev_C, const double* dev_C_par, gecc
     pa.gate = nullptr;
     if ((e = launch_partials(pa, st)) != hipSuccess) return hip_rc(e);
   }
-  if ((e = launch_threshold(d, 1, st)) != hipSuccess) return hip_rc(e);
+  if ((e = launch_threshold(d, st)) != hipSuccess) return hip_rc(e);
   return summary ? hip_rc(launch_summarize(d, st)) : GECC_OK;
 }
 

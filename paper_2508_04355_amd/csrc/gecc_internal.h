@@ -214,9 +214,8 @@ struct DecodeArgs {
   gecc_report* report;
 };
 hipError_t launch_reset_state(const DecodeArgs& a, hipStream_t st);
-// partial sums -> syndromes -> threshold flags.  first = 1: also collects max |syndrome| per
-// family; first = 0: residual pass of the decoder, gated on phase == PH_REVERIFY.
-hipError_t launch_threshold(const DecodeArgs& a, int first, hipStream_t st);
+// partial sums -> syndromes -> threshold flags (Section V step 1) and max |syndrome| per family
+hipError_t launch_threshold(const DecodeArgs& a, hipStream_t st);
 // first report (s, t, maxima, CLEAN / DETECTED) from the counters of the first threshold pass
 hipError_t launch_summarize(const DecodeArgs& a, hipStream_t st);
 // Section V step 2 right after detection.  with_summary = 1: also writes the first report
