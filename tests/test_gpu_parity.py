@@ -169,6 +169,41 @@ def test_one_call_chain_equals_the_staged_calls_bit_for_bit(dtype, shape, batch,
     H.compare(g2, H.run_oracle(A, B, A, B, cf, tau), 1e-5, what="one call")
 
 
+def test_two_contexts_on_two_streams_do_not_disturb_each_other():
+    """Every call takes the caller's stream and the library keeps all its state in the context's
+    own workspace: two products enqueued alternately on two side streams give the results of the
+    same products run alone on the default stream, bit for bit."""
+    import torch
+    shapes = [("bf16", (520, 256, 264), [(0, 17, 200, 30.0)]), ("f32", (300, 200, 260), [(0, 5, 6, -12.0), (0, 299, 1, 8.0)])]
+    alone, jobs = [], []
+    for idx, (dtype, (n, k, m), cf) in enumerate(shapes):
+        rng = inputs.rng_for(96, idx)
+        A, B = inputs.operands(rng, n, k, m, ("normal", 1.0), ("normal", 1.0), dtype)
+        tau = gecc.noise_thresholds(n, k, m, 1.0, 1.0)
+        alone.append(H.run_gpu(A, B, A, B, cf, tau, dtype, staged=False))
+        ctx = gecc.Context(n, k, m, gecc.BF16 if dtype == "bf16" else gecc.F32,
+                           gecc.Thresholds(tau.r1, tau.r2, tau.q1, tau.q2, tau.op, tau.rep, tau.rel))
+        dA, dB = H.to_dev(A[None], dtype, False), H.to_dev(B[None], dtype, False)
+        par = ctx.alloc_parities()
+        jobs.append((ctx, dA, dB, ctx.alloc_c(), par, ctx.alloc_report(), gecc.make_faults(cf, H.DEV), torch.cuda.Stream()))
+    torch.cuda.synchronize()
+    for rnd in range(3):                                  # interleaved, nothing waits in between
+        for (ctx, dA, dB, Cd, par, rep, (fl, nf), st) in jobs:
+            with torch.cuda.stream(st):
+                ctx.encode_a(dA, par[0])
+                ctx.encode_b(dB, par[1])
+                ctx.multiply(dA, par[0], dB, par[1], Cd, par[2], fl, nf)
+                ctx.verify(Cd, par[2], rep, fused=True)
+                ctx.correct(dA, par[0], dB, par[1], Cd, par[2], rep)
+    torch.cuda.synchronize()
+    for (ctx, dA, dB, Cd, par, rep, _, st), ref in zip(jobs, alone):
+        with torch.cuda.stream(st):
+            r = ctx.report_to_host(rep)[0]
+        assert (r.status, r.errors()) == (ref.reports[0].status, ref.reports[0].errors())
+        assert np.array_equal(Cd.cpu().numpy().astype(np.float64)[:, :, :ref.C.shape[2]], ref.C)
+        assert np.array_equal(par[2].cpu().numpy().reshape(1, -1), ref.C_par)
+
+
 def test_unaligned_leading_dimensions_take_the_scalar_paths():
     n, k, m = 67, 45, 83
     rng = inputs.rng_for(91)
