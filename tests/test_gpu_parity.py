@@ -204,6 +204,59 @@ def test_two_contexts_on_two_streams_do_not_disturb_each_other():
         assert np.array_equal(par[2].cpu().numpy().reshape(1, -1), ref.C_par)
 
 
+def test_the_staged_chain_replays_from_a_captured_graph():
+    """Nothing on the path allocates, synchronises or clears memory with a memset node, so the
+    whole chain can be captured into a HIP graph.  Every replay (with eager work and a fresh fault
+    list between them) has to give what the eager calls give for the same faults."""
+    import torch
+    n, k, m = 520, 256, 264
+    rng = inputs.rng_for(97)
+    A, B = inputs.operands(rng, n, k, m, ("normal", 1.0), ("normal", 1.0), "bf16")
+    tau = gecc.noise_thresholds(n, k, m, 1.0, 1.0)
+    ctx = gecc.Context(n, k, m, gecc.BF16, gecc.Thresholds(tau.r1, tau.r2, tau.q1, tau.q2, tau.op, tau.rep, tau.rel))
+    dA, dB = H.to_dev(A[None], "bf16", False), H.to_dev(B[None], "bf16", False)
+    A_par, B_par, C_par = ctx.alloc_parities()
+    rep, Cd = ctx.alloc_report(), ctx.alloc_c()
+    fl, nf = gecc.make_faults([(0, 1, 2, 10.0), (0, 3, 4, 10.0)], H.DEV)      # two slots, rewritten below
+
+    def chain():
+        ctx.encode_a(dA, A_par)
+        ctx.encode_b(dB, B_par)
+        ctx.multiply(dA, A_par, dB, B_par, Cd, C_par, fl, nf)
+        ctx.verify(Cd, C_par, rep, fused=True)
+        ctx.correct(dA, A_par, dB, B_par, Cd, C_par, rep)
+
+    def plant(cases):
+        new, _ = gecc.make_faults(cases, H.DEV)
+        fl.copy_(new)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        chain()                                           # first launches configure the kernels
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        chain()
+    patterns = [[(0, 10, 20, 40.0), (0, 300, 100, -25.0)], [(0, 519, 263, 33.0), (0, 0, 0, 17.0)],
+                [(0, 77, 5, -60.0), (0, 77, 200, 21.0)]]
+    for cases in patterns:
+        plant(cases)
+        Cd.fill_(float("nan"))
+        chain()
+        eager_rep = ctx.report_to_host(rep)[0]
+        eager_C = Cd.clone()
+        eager_par = C_par.clone()
+        Cd.fill_(float("nan"))
+        rep.zero_()
+        graph.replay()
+        r = ctx.report_to_host(rep)[0]
+        assert r.status == gecc.CORRECTED and sorted((e[1], e[2]) for e in r.errors()) == sorted((c[1], c[2]) for c in cases)
+        assert (r.status, r.errors()) == (eager_rep.status, eager_rep.errors())
+        assert torch.equal(Cd, eager_C) and torch.equal(C_par, eager_par)
+
+
 def test_unaligned_leading_dimensions_take_the_scalar_paths():
     n, k, m = 67, 45, 83
     rng = inputs.rng_for(91)
