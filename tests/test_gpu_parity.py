@@ -494,3 +494,16 @@ def test_cfg4_full_size_sampled(wname):
     assert np.allclose(cp[2 * n + m:2 * n + 2 * m], R[len(rows) + 1, :m], rtol=1e-10, atol=1e-12 * scale * n * n)
     Ccols = oc.encoded_product(A, AP, B[:, cols], BP)[:n, :len(cols)]
     assert np.abs(g.C[0][:, cols] - Ccols).max() / scale <= 1e-5
+    del g
+    # the same product through the one call that bench.py times (its own order of the parity
+    # scans), with the C fault only: same sampled symbols, same parities
+    g1 = H.run_gpu(A, B, A, B, cfb, w.tau, w.dtype, w.trans_a, w.trans_b, staged=False)
+    rep = g1.reports[0]
+    assert rep.status == gecc.CORRECTED and [(e[0], e[1], e[2]) for e in rep.errors()] == [(MAT_C, 4321 % n, m - 1)]
+    assert np.abs(g1.C[0][rows] - R[:len(rows), :m]).max() / scale <= 1e-5
+    assert np.abs(g1.C[0][:, cols] - Ccols).max() / scale <= 1e-5
+    assert np.allclose(g1.A_par[0], AP, rtol=1e-12, atol=1e-12 * np.abs(AP).max())
+    assert np.allclose(g1.B_par[0], BP.T, rtol=1e-12, atol=1e-12 * np.abs(BP).max())
+    cp = g1.C_par[0]
+    assert np.allclose(cp[rows], R[:len(rows), m], rtol=1e-10, atol=1e-12 * scale * m)
+    assert np.allclose(cp[2 * n:2 * n + m], R[len(rows), :m], rtol=1e-10, atol=1e-12 * scale * n)
