@@ -50,9 +50,11 @@ constexpr int NSTAGE = 4;                          // k-tiles of one operand res
 constexpr int REGION_BYTES = NSTAGE * TILE_BYTES;  // 64 KiB per operand
 constexpr int SMEM_BYTES = 2 * REGION_BYTES;       // 128 KiB
 constexpr int EPI_SMEM_BYTES = 4 * 2 * 128 * 33 * 4;  // 132 KiB: row-sum transpose of the epilogue
-// DMA spread (see the schedule in the kernel): instructions of a pair in its first two halves,
-// instructions of a single k-tile in its first half
-constexpr int PA = 3, PB = 3, MX = 0;
+// DMA spread (see the schedule in the kernel): the 8 instructions of a pair go out as early as its
+// slot allows (all in the half after the slot is released when there is one k-contiguous operand,
+// 5 + 3 over two halves when there are two: a burst of 16 makes the address unit push back); the
+// 4 instructions of a single k-tile go into its first half
+constexpr int MX = 0;
 constexpr int SKEW_M = 1, SKEW_N = 1;              // k start offset (pairs of k-tiles) per tile row / column
 constexpr int GROUP_M = 8;                         // tile rows per L2-sharing group
 constexpr unsigned OOB = 0x80000000u;              // voffset beyond any num_records: reads zero
@@ -227,20 +229,21 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
   // them, 8 instructions per wavefront and unit), one k-tile otherwise (nM of them, 4
   // instructions).  An iteration (one k-tile) has two halves of 16 MFMAs with the workgroup
   // barrier between them; that barrier releases the slot of k-tile kt (and of its pair when kt
-  // is odd) and is where k-tile kt+1 must have landed.  The loads are spread over the halves so
-  // that L2 sees a steady stream instead of bursts (the achieved L2 latency, which bounds the
-  // per-CU bandwidth through the L1 miss capacity, depends on it):
+  // is odd) and is where k-tile kt+1 must have landed.  Where the loads go is a trade between
+  // lead time (a pair's slot is free from the barrier of k-tile 2q+1 on and its data is needed
+  // at the barrier of 2q+3; with two k-contiguous operands the wavefronts used to wait there for
+  // a sixth of the loop) and bursts (the address unit takes one instruction per 16 cycles):
   //   pair q+2:      PA instructions in the 2nd half of k-tile 2q+1, PB in the 1st half of
-  //                  2q+2, the rest in the 2nd half of 2q+2         (needed at barrier 2q+3)
+  //                  2q+2, PC = 8 - PA - PB in the 2nd half of 2q+2   (needed at barrier 2q+3)
   //   k-tile kt+4:   MX instructions in the 2nd half of kt, the rest in the 1st half of kt+1
   // Inside a half the k-contiguous operands go first.  The memory counter retires in order, so
-  // "k-tile kt+1 has landed" becomes "at most W instructions are pending", W = what the
-  // schedule issues after the last instruction of that k-tile's units:
+  // "k-tile kt+1 has landed" becomes "at most W instructions are pending", W = at most what the
+  // schedule issues after the last instruction of that k-tile's units (for any PA, PB, PC):
   //   kt even: (PA + PB) nK + 8 nM        kt odd: 4 nM  (8 nM without a k-contiguous operand)
   // Units past the end of k are clamped to the last one (a harmless reload into a free slot),
   // which keeps every iteration identical.
   constexpr int nK = (KCA ? 1 : 0) + (KCB ? 1 : 0), nM = 2 - nK;
-  constexpr int PC = 8 - PA - PB;
+  constexpr int PA = nK == 2 ? 5 : 8, PB = 8 - PA, PC = 8 - PA - PB;
   constexpr int W_EVEN = (PA + PB) * nK + 8 * nM, W_ODD = nK > 0 ? 4 * nM : 8 * nM;
   const int NP = KT / 2;
   // k order of this tile: cyclic, starting at pair p0 (see SKEW_M, SKEW_N)
