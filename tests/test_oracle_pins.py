@@ -474,3 +474,81 @@ def test_theorem2_runs_after_the_operand_audit():
     assert res.status == CORRECTED
     assert res.errors == [(MAT_A, 5, 2, 1.0), (MAT_C, 6, 3, 7.0)]
     assert np.array_equal(res.A, A) and np.array_equal(res.Cbar, oc.encoded_product(A, AP, B, BP))
+
+
+# ---- pins of the decoder's own readings (thresholded arithmetic; the paper is silent) ----------
+def test_equal_offsets_on_a_diagonal_are_ambiguous_below_the_weighted_threshold():
+    """Two equal errors x on the diagonal of a 2 x 2 block and the same two on the anti-diagonal
+    have identical plain sums; their weighted sums differ by exactly x per line (weights one
+    apart, Section V).  Below the weighted threshold the decoder therefore cannot tell them
+    apart and must not choose; above it both are corrected."""
+    n, k, m = 8, 3, 8
+    A, B = int_mats(36, n, k, m)
+    AP, BP = oc.encode_a(A), oc.encode_b(B)
+    clean = oc.encoded_product(A, AP, B, BP)
+    tau = Thresholds(0.5, 5.0, 0.5, 5.0, 0.0)
+    for cells in ([(2, 4), (3, 5)], [(2, 5), (3, 4)]):
+        Cbar = clean.copy()
+        oc.inject_c(Cbar, [(i, j, 2.0) for (i, j) in cells])
+        assert oc.decode(Cbar, A, AP, B, BP, tau).status == UNCORRECTABLE
+        Cbar = clean.copy()
+        oc.inject_c(Cbar, [(i, j, 20.0) for (i, j) in cells])
+        res = oc.decode(Cbar, A, AP, B, BP, tau)
+        assert res.status == CORRECTED and [(i, j) for (_, i, j, _) in res.errors] == sorted(cells)
+        assert np.array_equal(res.Cbar, clean)
+    # rows two apart: the weighted sums differ by 2 x, so x = 4 is already enough
+    Cbar = clean.copy()
+    oc.inject_c(Cbar, [(2, 4, 4.0), (4, 5, 4.0)])
+    assert oc.decode(Cbar, A, AP, B, BP, tau).status == CORRECTED
+
+
+def test_verification_trusts_a_syndrome_relative_to_its_size_detection_does_not():
+    """A syndrome that carries a relative error eps (as any finite-precision sum does) puts
+    (j+1) x eps into the weighted check of an error x in column j.  With rel = 0 that fails
+    the verification as soon as it exceeds the absolute threshold; with rel > eps it passes.
+    Detection itself compares with the absolute threshold only."""
+    n = m = 64
+    i, j, x, eps = 10, 40, 1.0e6, 1.0e-7
+    r1, r2, q1, q2 = np.zeros(n), np.zeros(n), np.zeros(m), np.zeros(m)
+    r1[i], r2[i] = x, (j + 1) * x * (1 + eps)
+    q1[j], q2[j] = x * (1 - eps), (i + 1) * x
+    for rel, ok in ((0.0, False), (2.0 ** -20, True)):
+        tau = Thresholds(1e-3, 1e-1, 1e-3, 1e-1, 0.0, 0.0, rel)
+        fix = oc.d0_correct(r1, r2, q1, q2, [i], [j], oc.LineThresholds(tau, n, m))
+        assert (fix is not None) == ok
+        if ok:
+            assert [(a, b) for (a, b, _) in fix] == [(i, j)] and abs(fix[0][2] - x) <= 2 * eps * x
+    # a syndrome of 0.05 in a family whose threshold is 0.1 is not flagged whatever rel is
+    r2b = np.zeros(n); r2b[3] = 0.05
+    tau = Thresholds(1e-3, 1e-1, 1e-3, 1e-1, 0.0, 0.0, 0.5)
+    assert oc.detect(np.zeros(n), r2b, q1 * 0, q2 * 0, tau) == ([], [])
+
+
+def test_lines_touched_by_an_operand_repair_get_their_allowance_and_only_they():
+    """After an operand repair, row i of C-bar still carries the rounding of the corrupted terms
+    e b_lj that sat in its sums: noise proportional to |e b_lj|, symbol by symbol.  With
+    rep sqrt(k) above that proportion the second pass of Section V ignores it and reports the
+    operand error alone; with rep = 0 the same noise is taken for errors of C.  An error of C in an
+    untouched line is judged by the plain thresholds either way."""
+    n, k, m = 24, 16, 20
+    rng = np.random.default_rng(37)
+    A, B = rng.standard_normal((n, k)), rng.standard_normal((k, m))
+    AP, BP = oc.encode_a(A), oc.encode_b(B)
+    i, l, e, rho = 7, 5, 1000.0, 1e-6
+    A2 = A.copy(); A2[i, l] += e
+    Cbar = oc.encoded_product(A2, AP, B, BP)
+    noise = rho * np.abs(e * B[l, :]) * rng.choice([-1.0, 1.0], m)
+    Cbar[i, :m] += noise                                   # what a finite-precision product leaves behind
+    base = dict(r1=1e-9, r2=1e-9, q1=1e-9, q2=1e-9, op=0.0)
+    with_rep = oc.decode(Cbar, A2, AP, B, BP, Thresholds(**base, rep=4 * rho / np.sqrt(k)))
+    assert with_rep.status == CORRECTED and [(mt, a, b) for (mt, a, b, _) in with_rep.errors] == [(MAT_A, i, l)]
+    assert np.allclose(with_rep.A, A, rtol=0, atol=1e-9)
+    without = oc.decode(Cbar, A2, AP, B, BP, Thresholds(**base, rep=0.0))
+    assert without.status == UNCORRECTABLE or len(without.errors) > 1
+    # the allowance belongs to the repaired row and to the columns in proportion to |e b_lj|:
+    # a small error of C elsewhere is still found with it
+    Cbar2 = Cbar.copy()
+    Cbar2[i + 3, 2] += 1e-4
+    res = oc.decode(Cbar2, A2, AP, B, BP, Thresholds(**base, rep=4 * rho / np.sqrt(k)))
+    assert res.status == CORRECTED
+    assert [(mt, a, b) for (mt, a, b, _) in res.errors] == [(MAT_A, i, l), (MAT_C, i + 3, 2)]
