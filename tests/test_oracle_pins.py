@@ -545,10 +545,16 @@ def test_lines_touched_by_an_operand_repair_get_their_allowance_and_only_they():
     assert np.allclose(with_rep.A, A, rtol=0, atol=1e-9)
     without = oc.decode(Cbar, A2, AP, B, BP, Thresholds(**base, rep=0.0))
     assert without.status == UNCORRECTABLE or len(without.errors) > 1
-    # the allowance belongs to the repaired row and to the columns in proportion to |e b_lj|:
-    # a small error of C elsewhere is still found with it
+    # the allowance belongs to the repaired row and, in proportion to |e b_lj|, to every column:
+    # an error of C in another row that exceeds its column's allowance is still found ...
     Cbar2 = Cbar.copy()
-    Cbar2[i + 3, 2] += 1e-4
+    Cbar2[i + 3, 2] += 1.0
     res = oc.decode(Cbar2, A2, AP, B, BP, Thresholds(**base, rep=4 * rho / np.sqrt(k)))
     assert res.status == CORRECTED
     assert [(mt, a, b) for (mt, a, b, _) in res.errors] == [(MAT_A, i, l), (MAT_C, i + 3, 2)]
+    # ... and one below it flags its own row (rows other than i are not widened) but no column:
+    # nothing to pair it with, so nothing is corrected
+    Cbar3 = Cbar.copy()
+    Cbar3[i + 3, 2] += 1e-4
+    assert 1e-4 < 4 * rho * abs(e * B[l, 2])
+    assert oc.decode(Cbar3, A2, AP, B, BP, Thresholds(**base, rep=4 * rho / np.sqrt(k))).status == UNCORRECTABLE
