@@ -159,7 +159,7 @@ def main():
         "overhead_pct": round((ms_step / ms_plain - 1.0) * 100.0, 2),
         "all_clean_reported_clean": clean,
         "correction_rate": {"scenarios": "a,b,c,d,e,f (Section VI)", "corrected": n_ok, "trials": n_tot},
-        "roofline": {"bound": "mfma", "kernel": "gemm_kernel (data block + fused syndrome partials)",
+        "roofline": {"bound": "mfma", "kernel": ("gemm_bf16_256" if w.dtype == "bf16" and min(n, m) >= 256 and k % 64 == 0 else "gemm_kernel") + " (data block + fused syndrome partials)",
                      "achieved": round(achieved, 3) if achieved else None, "peak": peak, "unit": "TFLOP/s",
                      "frac": round(achieved / peak, 4) if achieved else None,
                      "kernel_ms": round(g_ms, 4) if g_ms else None,
