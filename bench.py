@@ -110,36 +110,48 @@ def main():
 
     ms_plain = 0.5 * (ms_plain_before + time_plain())
 
-    # ---- correction rate on the paper's six scenarios (Section VI a-f), untimed --------------
+    # ---- the paper's six scenarios (Section VI a-f): correction rate, and the time of one
+    # protected product whose correction stage really runs (encode .. correct, median of 5) ----
     MA, MB, MC = inputs.MAT_A, inputs.MAT_B, inputs.MAT_C
     scen = {"a": [MA], "b": [MB], "c": [MC], "d": [MA, MC], "e": [MB, MC], "f": [MC, MC]}
-    n_ok = n_tot = 0
     frng = inputs.rng_for(41, 0)
     Aclean, Bclean = dA.clone(), dB.clone()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    plan = {}
     for name, mats in scen.items():
         faults = inputs.draw_faults(frng, n, k, m, len(mats), w.offset_law, mats)
-        ctx.encode_a(dA, A_par)
-        ctx.encode_b(dB, B_par)
-        want, cf = [], []
-        for f in faults:            # E1/E2 strike after encoding; E3 inside the product
-            if f.matrix == MC:
-                cf.append((0, f.row, f.col, f.offset))
-            else:
-                T, tr = (dA, w.trans_a) if f.matrix == MA else (dB, w.trans_b)
-                i, j = (f.col, f.row) if tr else (f.row, f.col)
-                T[0, i, j] += f.offset
-            want.append((f.matrix, f.row, f.col))
-        fl, nf = gecc.make_faults(cf, dev)
-        ctx.multiply(dA, A_par, dB, B_par, Cd, C_par, fl, nf)
-        ctx.verify(Cd, C_par, rep, fused=True)
-        ctx.correct(dA, A_par, dB, B_par, Cd, C_par, rep)
-        r = ctx.report_to_host(rep)[0]
-        got = [(e[0], e[1], e[2]) for e in r.errors()]
-        restored = bool(torch.equal(dA, Aclean) and torch.equal(dB, Bclean))
-        n_tot += 1
-        n_ok += int(r.status == gecc.CORRECTED and got == sorted(want) and restored)
-        dA.copy_(Aclean)
-        dB.copy_(Bclean)
+        cf = [(0, f.row, f.col, f.offset) for f in faults if f.matrix == MC]
+        plan[name] = (faults, [(f.matrix, f.row, f.col) for f in faults], gecc.make_faults(cf, dev))
+    times = {name: [] for name in scen}
+    good = {name: True for name in scen}
+    for rnd in range(6):            # round 0 untimed: it loads the kernels of the staged calls
+        if rnd == 1:                # ... and the chip needs a few products to be back at its steady clock
+            for _ in range(args.warmup):
+                ctx.plain_gemm(dA, dB, Cd)
+        for name in scen:
+            faults, want, (fl, nf) = plan[name]
+            ev0.record()
+            ctx.encode_a(dA, A_par)
+            ctx.encode_b(dB, B_par)
+            for f in faults:        # E1/E2 strike after encoding (tiny torch kernels inside the timed span); E3 inside the product
+                if f.matrix != MC:
+                    T, tr = (dA, w.trans_a) if f.matrix == MA else (dB, w.trans_b)
+                    i, j = (f.col, f.row) if tr else (f.row, f.col)
+                    T[0, i, j] += f.offset
+            ctx.multiply(dA, A_par, dB, B_par, Cd, C_par, fl, nf)
+            ctx.verify(Cd, C_par, rep, fused=True)
+            ctx.correct(dA, A_par, dB, B_par, Cd, C_par, rep)
+            ev1.record()
+            r = ctx.report_to_host(rep)[0]
+            if rnd > 0:
+                times[name].append(ev0.elapsed_time(ev1))
+            got = [(e[0], e[1], e[2]) for e in r.errors()]
+            restored = bool(torch.equal(dA, Aclean) and torch.equal(dB, Bclean))
+            good[name] = good[name] and r.status == gecc.CORRECTED and got == sorted(want) and restored
+            dA.copy_(Aclean)
+            dB.copy_(Bclean)
+    n_tot, n_ok = len(scen), sum(int(v) for v in good.values())
+    scen_ms = {name: round(float(np.median(t)), 4) for name, t in times.items()}
 
     flops = w.flops
     value = flops / (ms_step * 1e-3) / 1e12
@@ -159,6 +171,8 @@ def main():
         "overhead_pct": round((ms_step / ms_plain - 1.0) * 100.0, 2),
         "all_clean_reported_clean": clean,
         "correction_rate": {"scenarios": "a,b,c,d,e,f (Section VI)", "corrected": n_ok, "trials": n_tot},
+        "scenario_ms": scen_ms,
+        "scenario_overhead_pct": {kk: round((vv / ms_plain - 1.0) * 100.0, 1) for kk, vv in scen_ms.items()},
         "roofline": {"bound": "mfma", "kernel": ("gemm_bf16_256" if w.dtype == "bf16" and min(n, m) >= 256 and k % 64 == 0 else "gemm_kernel") + " (data block + fused syndrome partials)",
                      "achieved": round(achieved, 3) if achieved else None, "peak": peak, "unit": "TFLOP/s",
                      "frac": round(achieved / peak, 4) if achieved else None,
