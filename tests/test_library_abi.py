@@ -94,3 +94,40 @@ def test_stated_thresholds_follow_the_noise_model(built):
         t = built.noise_thresholds(w.n, w.k, w.m, w.sigma_a, w.sigma_b, 16.0)
         for got, want in zip((w.tau.r1, w.tau.r2, w.tau.q1, w.tau.q2), (t.r1, t.r2, t.q1, t.q2)):
             assert got == pytest.approx(want, rel=0.01), w.name
+
+
+def test_every_compute_entry_point_checks_its_pointers_before_any_gpu_call(built):
+    """Null and misaligned pointers come back as error codes (no exceptions, no abort), and they
+    do so before the library touches the GPU: this test runs where there is none."""
+    L = built.lib()
+    h = C.c_void_p()
+    assert L.gecc_create(C.byref(h), C.byref(_params(built))) == 0
+    ws = L.gecc_workspace_bytes(h)
+    assert L.gecc_set_workspace(h, C.c_void_p(1 << 20), ws) == 0      # any aligned address: never dereferenced here
+    ok, nul, odd = C.c_void_p(1 << 16), C.c_void_p(0), C.c_void_p((1 << 16) + 2)
+    i0 = C.c_int32(0)
+    assert L.gecc_encode_a(h, nul, ok, None) == -1 and L.gecc_encode_a(h, ok, nul, None) == -1
+    assert L.gecc_encode_a(h, odd, ok, None) == -4 and L.gecc_encode_a(h, ok, odd, None) == -4   # fp32 operand, fp64 parity
+    assert L.gecc_encode_b(h, nul, ok, None) == -1 and L.gecc_encode_b(h, ok, odd, None) == -4
+    args = [ok] * 6
+    for pos in range(6):
+        bad = list(args); bad[pos] = nul
+        assert L.gecc_multiply(h, *bad, nul, 0, None) == -1, pos
+        bad = list(args); bad[pos] = odd
+        assert L.gecc_multiply(h, *bad, nul, 0, None) == -4, pos
+    assert L.gecc_multiply(h, *args, nul, 1, None) == -1        # faults announced, list missing
+    assert L.gecc_multiply(h, *args, ok, -1, None) == -1
+    assert L.gecc_verify(h, ok, nul, ok, 1, None) == -1 and L.gecc_verify(h, ok, ok, nul, 1, None) == -1
+    assert L.gecc_verify(h, nul, ok, ok, 0, None) == -1         # the stand-alone scan needs C
+    for pos in range(7):
+        bad = [ok] * 7; bad[pos] = nul
+        assert L.gecc_correct(h, *bad, None) == -1, pos
+    assert L.gecc_protected_gemm(h, ok, ok, ok, ok, ok, ok, nul, None) == -1
+    assert L.gecc_protected_gemm(h, nul, ok, ok, ok, ok, ok, ok, None) == -1
+    assert L.gecc_protected_gemm_retry(h, ok, ok, ok, ok, ok, ok, ok, None, 1, nul, 0, None, None) == -1   # no host report
+    rep = (built.Report * 1)()
+    assert L.gecc_protected_gemm_retry(h, ok, ok, ok, ok, ok, ok, ok, rep, -1, nul, 0, None, None) == -1    # negative retries
+    assert L.gecc_plain_gemm(h, nul, ok, ok, None) == -1
+    for f in (L.gecc_encode_a, L.gecc_encode_b):
+        assert f(None, ok, ok, None) == -1                       # no context
+    L.gecc_destroy(h)
