@@ -121,7 +121,11 @@ typedef struct {
 
 /* ---- context ------------------------------------------------------------------------ */
 
-/* Validates *p and builds a context (host memory only). *out receives it. */
+/* Validates *p and builds a context (host memory only). *out receives it.
+   Reads the environment variable GECC_CU_COUNT once, here: if set to a positive number the
+   bf16 product plans its rounds of tiles as for that many compute units instead of the
+   device's own count (for tests of the k-split of a half-empty last round on small shapes;
+   any value gives correct results). */
 int gecc_create(gecc_ctx** out, const gecc_params* p);
 void gecc_destroy(gecc_ctx* ctx);
 

@@ -1,5 +1,6 @@
 // C ABI of libgecc: argument checking, workspace layout and the stream-ordered launch
 // sequences.  Host code only; all arithmetic of the path runs in the kernels.
+#include <cstdlib>
 #include <new>
 #include "gecc_internal.h"
 
@@ -178,6 +179,7 @@ GemmArgs gemm_args(const gecc_ctx* c, const void* A, const void* B, float* C) {
   g.lda = p.lda; g.ldb = p.ldb; g.ldc = p.ldc;
   g.sa = p.stride_a; g.sb = p.stride_b; g.sc = p.stride_c;
   g.tile_m = c->tile_m; g.tile_n = c->tile_n; g.ntm = c->ntm; g.ntn = c->ntn;
+  g.cu_hint = c->cu_hint; g.split_first = -1;
   g.rp_ld = c->rp_ld; g.cp_ld = c->cp_ld;
   return g;
 }
@@ -221,6 +223,11 @@ int gecc_create(gecc_ctx** out, const gecc_params* p) {
   gecc_ctx* c = new (std::nothrow) gecc_ctx;
   if (!c) return GECC_ERR_ARG;
   c->p = *p;
+  {
+    const char* e = getenv("GECC_CU_COUNT");       // test hook: see GemmArgs::cu_hint
+    c->cu_hint = e ? atoi(e) : 0;
+    if (c->cu_hint < 0) c->cu_hint = 0;
+  }
   c->tile_m = 128;
   c->tile_n = 128;
   c->ntm = (p->n + c->tile_m - 1) / c->tile_m;

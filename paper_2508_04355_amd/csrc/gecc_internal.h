@@ -55,6 +55,7 @@ struct gecc_ctx {
   int tile_m, tile_n;      // blocking of the product kernel = granularity of the partials
   int ntm, ntn;            // partial tiles along n and m
   int rp_ld, cp_ld;        // lines per slab of the row / column partials (n, m plus padding)
+  int cu_hint;             // GECC_CU_COUNT (tests: plan the tile rounds as for that many CUs), else 0
   char* ws;                // device workspace (caller's)
   size_t ws_bytes;
   hipEvent_t* ev;          // optional timing records around the product kernel (start, stop pairs)
@@ -124,6 +125,9 @@ struct GemmArgs {
   int rp_ld, cp_ld;     // lines per sub-tile slab of rowpart / colpart (n, m plus padding)
   const gecc_fault* faults;
   int n_faults;
+  int cu_hint;          // compute units to plan the rounds of tiles for (0: ask the device)
+  int split_first;      // set by the launcher of the bf16 256 x 256 kernel: first workgroup of the
+                        // k-split tail (-1: none)
   // protected product only: P_g = A_P B_P goes to pg_out[b * pg_stride + 0..3], formed by the
   // workgroup of the first tile, which also resets the decoder state of its batch item
   const double* A_par;

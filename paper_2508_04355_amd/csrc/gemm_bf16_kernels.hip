@@ -172,20 +172,11 @@ __device__ __forceinline__ void wait_vm() {
   asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
 }
 
-template <bool KCA, bool KCB, bool EPI, bool FAULTS>
-__global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
-  extern __shared__ __attribute__((aligned(1024))) char smem[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wr = wave >> 1, wc = wave & 1;
-  const int l32 = lane & 31, lhi = lane >> 5;
-  const int b = blockIdx.y;
-
-  // ---- tile order: consecutive workgroups land on different XCDs (round robin), so give
-  // every XCD a contiguous range of the tile sequence; inside it walk GROUP_M tile rows at a
-  // time, column by column, so that co-resident tiles share A row panels and B column panels
-  const int ntm = (a.n + BM - 1) / BM, ntn = (a.m + BN - 1) / BN;
+// ---- tile order: consecutive workgroups land on different XCDs (round robin), so give every
+// XCD a contiguous range of the tile sequence; inside it walk GROUP_M tile rows at a time, column
+// by column, so that co-resident tiles share A row panels and B column panels
+__device__ __forceinline__ void tile_of(int pid, int ntm, int ntn, int& tm, int& tn) {
   const int ntiles = ntm * ntn;
-  int pid = blockIdx.x;
   {
     const int per = ntiles / 8, rem = ntiles - per * 8;     // XCD x gets per (+1 if x < rem)
     const int x = pid & 7, idx = pid >> 3;
@@ -195,18 +186,67 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
   const int grp = pid / gsz;
   const int first_m = grp * GROUP_M;
   const int gm = min(GROUP_M, ntm - first_m);
-  const int tm = first_m + (pid - grp * gsz) % gm;
-  const int tn = (pid - grp * gsz) / gm;
-  const int tile_r0 = tm * BM, tile_c0 = tn * BN;
+  tm = first_m + (pid - grp * gsz) % gm;
+  tn = (pid - grp * gsz) / gm;
+}
 
-  const uint16_t* A = reinterpret_cast<const uint16_t*>(a.A) + (int64_t)b * a.sa;
-  const uint16_t* B = reinterpret_cast<const uint16_t*>(a.B) + (int64_t)b * a.sb;
+// The k-split tail (see launch_one): a tile of the last, at most half filled round is computed
+// by two workgroups, one per half of k, which add their halves into C and into the partial sums
+// (both zeroed by this kernel first: one workgroup per tail tile).
+__global__ __launch_bounds__(256) void zero_tail_kernel(GemmArgs a, int first) {
+  const int ntm = (a.n + BM - 1) / BM, ntn = (a.m + BN - 1) / BN;
+  int tm, tn;
+  tile_of(first + blockIdx.x, ntm, ntn, tm, tn);
+  const int r0 = tm * BM, c0 = tn * BN;
+  const int rows = min(BM, a.n - r0), cols = min(BN, a.m - c0);
+  for (int o = threadIdx.x; o < rows * BN; o += 256) {
+    const int r = o / BN, c = o % BN;
+    if (c < cols) a.C[(int64_t)(r0 + r) * a.ldc + c0 + c] = 0.f;
+  }
+  if (a.rowpart) {
+    for (int o = threadIdx.x; o < 2 * BM; o += 256) {          // two 128-column slabs x 256 rows
+      const int tn128 = 2 * tn + o / BM, row = r0 + o % BM;
+      if (row < a.n && tn128 * 128 < a.m) {
+        float2* rp = reinterpret_cast<float2*>(a.rowpart + ((int64_t)tn128 * a.rp_ld + row) * 2);
+        *rp = make_float2(0.f, 0.f);
+      }
+    }
+    for (int o = threadIdx.x; o < 2 * BN; o += 256) {
+      const int tm128 = 2 * tm + o / BN, col = c0 + o % BN;
+      if (col < a.m && tm128 * 128 < a.n) {
+        float2* cp = reinterpret_cast<float2*>(a.colpart + ((int64_t)tm128 * a.cp_ld + col) * 2);
+        *cp = make_float2(0.f, 0.f);
+      }
+    }
+  }
+}
+
+template <bool KCA, bool KCB, bool EPI, bool FAULTS, bool SP>
+__global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wr = wave >> 1, wc = wave & 1;
+  const int l32 = lane & 31, lhi = lane >> 5;
+  const int b = blockIdx.y;
+
+  const int ntm = (a.n + BM - 1) / BM, ntn = (a.m + BN - 1) / BN;
+  // SP (the k-split launch, see launch_one): the workgroups share the tiles from split_first on
+  // in pairs, khalf = 0 / 1 takes the first / second half of k.  Otherwise: one tile, all of k.
+  const int khalf = SP ? (int)(blockIdx.x & 1) : -1;
+  int tm, tn;
+  tile_of(SP ? a.split_first + (int)(blockIdx.x >> 1) : (int)blockIdx.x, ntm, ntn, tm, tn);
+  const int tile_r0 = tm * BM, tile_c0 = tn * BN;
+  const int KT = SP ? a.k / (2 * BK) : a.k / BK;                 // even (checked by the launcher)
+  const int k0 = khalf == 1 ? KT * BK : 0;
+
+  const uint16_t* A = reinterpret_cast<const uint16_t*>(a.A) + (int64_t)b * a.sa + (KCA ? (int64_t)k0 : (int64_t)k0 * a.lda);
+  const uint16_t* B = reinterpret_cast<const uint16_t*>(a.B) + (int64_t)b * a.sb + (KCB ? (int64_t)k0 : (int64_t)k0 * a.ldb);
   float* C = a.C + (int64_t)b * a.sc;
 
   Operand<KCA> oa;
   Operand<KCB> ob;
-  oa.init(A, a.lda, tile_r0, a.n, a.k, wr * 128);
-  ob.init(B, a.ldb, tile_c0, a.m, a.k, wc * 128);
+  oa.init(A, a.lda, tile_r0, a.n, KT * BK, wr * 128);
+  ob.init(B, a.ldb, tile_c0, a.m, KT * BK, wc * 128);
 
   f32x16_t acc[4][4];
 #pragma unroll
@@ -221,7 +261,6 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
   const unsigned ldsB = ldsA + REGION_BYTES;
   const char* regA = smem;
   const char* regB = smem + REGION_BYTES;
-  const int KT = a.k / BK;                           // even: k % 64 == 0 (checked by the launcher)
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);
 
   // ---- DMA schedule ---------------------------------------------------------------------------
@@ -348,7 +387,7 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
 
   // ---- epilogue -------------------------------------------------------------------------------
   const int R0 = tile_r0 + wr * 128, C0 = tile_c0 + wc * 128;   // origin of this wavefront's sub-tile
-  if (FAULTS) {
+  if (FAULTS && khalf <= 0) {     // (of a split tile: planted into the first half)
     for (int f = 0; f < a.n_faults; ++f) {
       const gecc_fault ft = a.faults[f];
       if (ft.batch != b || ft.row < R0 || ft.row >= R0 + 128 || ft.col < C0 || ft.col >= C0 + 128) continue;
@@ -379,87 +418,127 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
   // columns (one per 32-wide block) and u = x1 + 2 x2 + 3 x3, the block part of the column
   // weight -- both go through LDS, where the 32 lanes of a half wavefront are added and the
   // lane part of the weight is applied.
-  const int tm128 = R0 >> 7, tn128 = C0 >> 7;
-  const int R0u = tile_r0 + (wave_u >> 1) * 128, C0u = tile_c0 + (wave_u & 1) * 128;   // scalar copies
-  const int rows_left = min(a.n - R0u, 128), cols_left = a.m - C0u;
-  const __amdgpu_buffer_rsrc_t crsrc = __builtin_amdgcn_make_buffer_rsrc(
-      C + (int64_t)R0u * a.ldc + C0u, 0, rows_left > 0 && cols_left > 0 ? rows_left * a.ldc * 4 : 0, 0x00020000);
-  int vo[4];   // byte offset of this lane in row 4 lhi of the sub-tile, per 32-wide block
+  // (SP: this workgroup has one half of k of a split tile; its partner has the other.  Both add
+  // into zeroed memory instead of storing: two terms, so the result does not depend on who is
+  // first.)
+  {
+    const int tm128 = R0 >> 7, tn128 = C0 >> 7;
+    const int R0u = tile_r0 + (wave_u >> 1) * 128, C0u = tile_c0 + (wave_u & 1) * 128;   // scalar copies
+    const int rows_left = min(a.n - R0u, 128), cols_left = a.m - C0u;
+    const __amdgpu_buffer_rsrc_t crsrc = __builtin_amdgcn_make_buffer_rsrc(
+        C + (int64_t)R0u * a.ldc + C0u, 0, rows_left > 0 && cols_left > 0 ? rows_left * a.ldc * 4 : 0, 0x00020000);
+    auto put = [&](float x, int off) {
+      if (SP) __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(x, crsrc, off, 0, 0);
+      else __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, x), crsrc, off, 0, 2);
+    };
+    int vo[4];   // byte offset of this lane in row 4 lhi of the sub-tile, per 32-wide block
 #pragma unroll
-  for (int j = 0; j < 4; ++j)
-    vo[j] = j * 32 + l32 < cols_left ? ((lhi * 4) * a.ldc + j * 32 + l32) * 4 : (int)OOB;
-  float cs[4] = {0.f, 0.f, 0.f, 0.f}, cw[4] = {0.f, 0.f, 0.f, 0.f};
-  float2* red2 = reinterpret_cast<float2*>(smem) + wave_u * (128 * 33) + (lhi * 4) * 33 + l32;
+    for (int j = 0; j < 4; ++j)
+      vo[j] = j * 32 + l32 < cols_left ? ((lhi * 4) * a.ldc + j * 32 + l32) * 4 : (int)OOB;
+    float cs[4] = {0.f, 0.f, 0.f, 0.f}, cw[4] = {0.f, 0.f, 0.f, 0.f};
+    float2* red2 = reinterpret_cast<float2*>(smem) + wave_u * (128 * 33) + (lhi * 4) * 33 + l32;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < 4; ++i) {
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int ru = i * 32 + (v >> 2) * 8 + (v & 3);   // row inside the sub-tile, without 4 lhi
-      const int rowoff = ru * a.ldc * 4;                // scalar; < 2^31 (ldc < 2^22, checked by the launcher)
-      const float x0 = acc[i][0][v], x1 = acc[i][1][v], x2 = acc[i][2][v], x3 = acc[i][3][v];
-      __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, x0), crsrc, vo[0] + rowoff, 0, 2);
-      __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, x1), crsrc, vo[1] + rowoff, 0, 2);
-      __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, x2), crsrc, vo[2] + rowoff, 0, 2);
-      __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, x3), crsrc, vo[3] + rowoff, 0, 2);
-      if (EPI) {
-        const float t2 = x2 + x3, t1 = x1 + t2;
-        red2[ru * 33] = make_float2(x0 + t1, (t1 + t2) + x3);
-        const float wr_ = (float)(ru + 1);
-        cs[0] += x0; cw[0] = fmaf(x0, wr_, cw[0]);
-        cs[1] += x1; cw[1] = fmaf(x1, wr_, cw[1]);
-        cs[2] += x2; cw[2] = fmaf(x2, wr_, cw[2]);
-        cs[3] += x3; cw[3] = fmaf(x3, wr_, cw[3]);
+      for (int v = 0; v < 16; ++v) {
+        const int ru = i * 32 + (v >> 2) * 8 + (v & 3);   // row inside the sub-tile, without 4 lhi
+        const int rowoff = ru * a.ldc * 4;                // scalar; < 2^31 (ldc < 2^22, checked by the launcher)
+        const float x0 = acc[i][0][v], x1 = acc[i][1][v], x2 = acc[i][2][v], x3 = acc[i][3][v];
+        put(x0, vo[0] + rowoff);
+        put(x1, vo[1] + rowoff);
+        put(x2, vo[2] + rowoff);
+        put(x3, vo[3] + rowoff);
+        if (EPI) {
+          const float t2 = x2 + x3, t1 = x1 + t2;
+          red2[ru * 33] = make_float2(x0 + t1, (t1 + t2) + x3);
+          const float wr_ = (float)(ru + 1);
+          cs[0] += x0; cw[0] = fmaf(x0, wr_, cw[0]);
+          cs[1] += x1; cw[1] = fmaf(x1, wr_, cw[1]);
+          cs[2] += x2; cw[2] = fmaf(x2, wr_, cw[2]);
+          cs[3] += x3; cw[3] = fmaf(x3, wr_, cw[3]);
+        }
       }
     }
-  }
-  if (EPI) {
+    if (EPI) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const float w1 = fmaf((float)(lhi * 4), cs[j], cw[j]);
-      const float s = cs[j] + __shfl_xor(cs[j], 32, 64), w = w1 + __shfl_xor(w1, 32, 64);
-      const int col = C0 + j * 32 + l32;
-      if (lhi == 0 && col < a.m && R0 < a.n) {
-        float2* cp = reinterpret_cast<float2*>(a.colpart + (((int64_t)b * a.ntm + tm128) * a.cp_ld + col) * 2);
-        *cp = make_float2(s, w);
+      for (int j = 0; j < 4; ++j) {
+        const float w1 = fmaf((float)(lhi * 4), cs[j], cw[j]);
+        const float s = cs[j] + __shfl_xor(cs[j], 32, 64), w = w1 + __shfl_xor(w1, 32, 64);
+        const int col = C0 + j * 32 + l32;
+        if (lhi == 0 && col < a.m && R0 < a.n) {
+          float* cp = a.colpart + (((int64_t)b * a.ntm + tm128) * a.cp_ld + col) * 2;
+          if (SP) { atomicAdd(cp, s); atomicAdd(cp + 1, w); }
+          else *reinterpret_cast<float2*>(cp) = make_float2(s, w);
+        }
       }
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the region is this wavefront's own
+      const float2* mine = reinterpret_cast<const float2*>(smem) + wave_u * (128 * 33);
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const int r = lane + 64 * h;
+        float s = 0.f, w = 0.f, u = 0.f;
+#pragma unroll
+        for (int c = 0; c < 32; ++c) {
+          const float2 t = mine[r * 33 + c];
+          s += t.x;
+          w = fmaf((float)(c + 1), t.x, w);
+          u += t.y;
+        }
+        const int row = R0 + r;
+        if (row < a.n && C0 < a.m) {
+          float* rp = a.rowpart + (((int64_t)b * a.ntn + tn128) * a.rp_ld + row) * 2;
+          if (SP) { atomicAdd(rp, s); atomicAdd(rp + 1, fmaf(32.f, u, w)); }
+          else *reinterpret_cast<float2*>(rp) = make_float2(s, fmaf(32.f, u, w));
+        }
+      }
+    if (!SP && blockIdx.x == 0) form_pg(a, b, reinterpret_cast<double*>(smem));   // P_g, once per batch item
     }
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the region is this wavefront's own
-    const float2* mine = reinterpret_cast<const float2*>(smem) + wave_u * (128 * 33);
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const int r = lane + 64 * h;
-      float s = 0.f, w = 0.f, u = 0.f;
-#pragma unroll
-      for (int c = 0; c < 32; ++c) {
-        const float2 t = mine[r * 33 + c];
-        s += t.x;
-        w = fmaf((float)(c + 1), t.x, w);
-        u += t.y;
-      }
-      const int row = R0 + r;
-      if (row < a.n && C0 < a.m) {
-        float2* rp = reinterpret_cast<float2*>(a.rowpart + (((int64_t)b * a.ntn + tn128) * a.rp_ld + row) * 2);
-        *rp = make_float2(s, fmaf(32.f, u, w));
-      }
-    }
-    if (blockIdx.x == 0) form_pg(a, b, reinterpret_cast<double*>(smem));   // P_g, once per batch item
   }
 }
 
 template <bool KCA, bool KCB, bool EPI, bool FAULTS>
-hipError_t launch_one(const GemmArgs& a, hipStream_t st) {
+hipError_t launch_one(const GemmArgs& a0, hipStream_t st) {
   static bool configured = false;   // per instantiation
   constexpr int lds_bytes = EPI && EPI_SMEM_BYTES > SMEM_BYTES ? EPI_SMEM_BYTES : SMEM_BYTES;
-  auto kern = gemm_bf16_256<KCA, KCB, EPI, FAULTS>;
+  auto kern = gemm_bf16_256<KCA, KCB, EPI, FAULTS, false>;
+  auto kern_split = gemm_bf16_256<KCA, KCB, EPI, FAULTS, true>;
   if (!configured) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
     if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern_split),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+    if (e != hipSuccess) return e;
     configured = true;
   }
-  const int ntm = (a.n + BM - 1) / BM, ntn = (a.m + BN - 1) / BN;
-  dim3 grid(ntm * ntn, a.batch);
-  hipLaunchKernelGGL(kern, grid, dim3(THREADS), lds_bytes, st, a);
+  GemmArgs a = a0;
+  const int ntm = (a.n + BM - 1) / BM, ntn = (a.m + BN - 1) / BN, ntiles = ntm * ntn;
+  // Tiles run in rounds of one per compute unit.  When the last round is at most half full, its
+  // tiles go to a launch of their own in which two workgroups share a tile, one per half of k,
+  // so that the round takes half as long (cfg4-wgrad: 896 tiles on 256 CUs -> the time of 3.5
+  // rounds instead of 4).  The halves add into C and the partial sums, zeroed beforehand.
+  static int n_cu = 0;
+  if (n_cu == 0) {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+      cus = 256;
+    n_cu = cus;
+  }
+  const int cus = a.cu_hint > 0 ? a.cu_hint : n_cu;
+  const int tail = ntiles % cus;
+  a.split_first = -1;
+  if (a.batch == 1 && ntiles > cus && tail > 0 && 2 * tail <= cus && a.k % (4 * BK) == 0) {
+    a.split_first = ntiles - tail;
+    hipLaunchKernelGGL(zero_tail_kernel, dim3(tail), dim3(256), 0, st, a, a.split_first);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, dim3(ntiles - tail, 1), dim3(THREADS), lds_bytes, st, a);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipLaunchKernelGGL(kern_split, dim3(2 * tail, 1), dim3(THREADS), lds_bytes, st, a);
+    return hipGetLastError();
+  }
+  hipLaunchKernelGGL(kern, dim3(ntiles, a.batch), dim3(THREADS), lds_bytes, st, a);
   return hipGetLastError();
 }
 

@@ -79,6 +79,50 @@ def test_ragged_tiles_of_the_fast_bf16_kernel_with_errors(pattern, trans):
     assert [(e[0], e[1], e[2]) for e in g.reports[0].errors()] == [(e[0], e[1], e[2]) for e in eff]
 
 
+@pytest.mark.parametrize("trans", [(0, 0), (0, 1), (1, 0), (1, 1)])
+@pytest.mark.parametrize("shape,cus", [((520, 256, 264), 4), ((520, 128, 264), 4), ((1000, 512, 776), 12)])
+@pytest.mark.parametrize("pattern", ["clean", "C+C in split tiles", "A+C", "B+C", "C outside the split tiles"])
+def test_k_split_tail_of_the_fast_bf16_kernel(pattern, shape, cus, trans, monkeypatch):
+    """A last round of tiles that is at most half full is shared out over two workgroups per tile,
+    one per half of k, which add into zeroed C and partial sums.  GECC_CU_COUNT (read when the
+    context is created) makes the launcher plan as for that many compute units, so that small
+    shapes reach this path: 6 tiles on 4 -> tiles 4, 5 are split; 16 on 12 -> tiles 12..15."""
+    monkeypatch.setenv("GECC_CU_COUNT", str(cus))
+    n, k, m = shape
+    rng = inputs.rng_for(93, n + k)
+    law = ("normal", 1.0)
+    faults = {"clean": [],
+              "C+C in split tiles": [inputs.Fault(MAT_C, n - 1, m - 1, 37.5), inputs.Fault(MAT_C, n - 200, m - 3, -12.25)],
+              "A+C": [inputs.Fault(MAT_A, n - 1, k - 1, 3.0), inputs.Fault(MAT_C, n - 7, m - 2, 55.0)],
+              "B+C": [inputs.Fault(MAT_B, k // 2, m - 1, -2.5), inputs.Fault(MAT_C, n - 1, m - 8, 9.0)],
+              "C outside the split tiles": [inputs.Fault(MAT_C, 3, 5, 21.0), inputs.Fault(MAT_C, 100, 200, -8.0)]}[pattern]
+    A, B, A2, B2, cf, eff = _trial(rng, n, k, m, "bf16", law, law, faults)
+    tau = gecc.noise_thresholds(n, k, m, 1.0, 1.0)
+    cfb = [(0,) + c for c in cf]
+    g = H.run_gpu(A, B, A2, B2, cfb, tau, "bf16", trans[0], trans[1])
+    o = H.run_oracle(A, B, A2, B2, cfb, tau)
+    H.compare(g, o, 1e-5, what="k-split tail, %s, trans %s" % (pattern, trans))
+    assert g.reports[0].status == (gecc.CORRECTED if faults else gecc.CLEAN)
+    assert [(e[0], e[1], e[2]) for e in g.reports[0].errors()] == [(e[0], e[1], e[2]) for e in eff]
+    AP, BP = oc.encode_a(A), oc.encode_b(B)
+    Cbar = oc.encoded_product(A, AP, B, BP)
+    ref = np.concatenate([Cbar[:n, m], Cbar[:n, m + 1], Cbar[n, :m], Cbar[n + 1, :m], Cbar[n:, m:].ravel()])
+    assert np.allclose(g.C_par[0], ref, rtol=1e-11, atol=1e-12 * np.abs(ref).max())
+    # two terms added onto zero: the order of arrival cannot show
+    g2 = H.run_gpu(A, B, A2, B2, cfb, tau, "bf16", trans[0], trans[1])
+    assert np.array_equal(g.C, g2.C) and np.array_equal(g.synd, g2.synd)
+    if pattern == "clean":      # the one-call chain takes the same launches
+        g3 = H.run_gpu(A, B, A, B, [], tau, "bf16", trans[0], trans[1], staged=False)
+        assert np.array_equal(g.C, g3.C) and g3.reports[0].status == gecc.CLEAN
+        # and the split changes C only by the rounding of one more fp32 addition per element
+        monkeypatch.delenv("GECC_CU_COUNT")
+        g4 = H.run_gpu(A, B, A, B, [], tau, "bf16", trans[0], trans[1])
+        assert not np.array_equal(g.C, g4.C)
+        assert np.abs(g.C - g4.C).max() <= 4e-6 * np.abs(g4.C).max()
+        split_rows = np.any(g.C[0] != g4.C[0], axis=1)
+        assert not split_rows[:256].any()          # tile row 0 is in the full rounds either way
+
+
 # ---- Theorem 2: many errors in at most two rows (or columns) of C ---------------------------------
 def _t2_faults(rng, lines, others, n_other, frac, rows_known):
     faults = []
