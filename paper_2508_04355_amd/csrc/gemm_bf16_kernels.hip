@@ -2,7 +2,9 @@
 // that holds nearly all flops of the path.
 //
 // Workgroup: 256 x 256 tile of C, 4 wavefronts (2 x 2), each owning a 128 x 128 sub-tile as
-// 4 x 4 MFMA 32x32x16 accumulators (256 fp32 registers per lane).  k advances in tiles of 32.
+// 8 x 8 MFMA 16x16x32 accumulators (256 fp32 registers per lane).  k advances in tiles of 32.
+// (Both bf16 MFMA shapes deliver 1024 flop per cycle and SIMD, but the chip is power-limited
+// under this load and sustains a 15 % higher clock on 16x16x32 than on 32x32x16.)
 // Operand tiles travel HBM -> LDS directly (buffer loads with the LDS bit set: no registers in
 // between, out-of-range rows read as zero) and several k-tiles ahead of the one the MFMA units
 // are consuming, which is what hides the memory latency with one workgroup per compute unit.
@@ -15,17 +17,18 @@
 // an 8-byte read):
 //   operand contiguous along k in memory:  two slots, each a PAIR of k-tiles: tile[row][64 k],
 //     128 bytes per row (one full line per row and request), the eight 16-byte chunks of a row
-//     XOR-swizzled with (row >> 1) & 7; fragments by ds_read_b128.
+//     XOR-swizzled with (row >> 1) & 7; fragments (16 rows x 32 k) by ds_read_b128.
 //   operand contiguous along m (or n):     four slots of one k-tile: tile[32 k][256 m], 512
-//     bytes per k-row, the eight 64-byte chunks of a row XOR-swizzled with k & 3; fragments
-//     by the transposing LDS read (two ds_read_b64_tr_b16 per fragment: 16 lanes fetch 4
-//     k-rows x 16 columns and each lane receives the 4 k-values of its own column).
+//     bytes per k-row, the eight 64-byte chunks of a row XOR-swizzled with k & 3 and the two
+//     32-byte halves of a chunk swapped when k & 8; fragments by the transposing LDS read (two
+//     ds_read_b64_tr_b16 per fragment: 16 lanes fetch 4 k-rows x 16 columns and each lane
+//     receives the 4 k-values of its own column).
 //
 // Epilogue, from the accumulators (C itself never passes through LDS): one branch-free pass that
 // stores C through a range-checked raw buffer (rows and columns outside C are dropped by the
 // hardware) and forms, per 128 x 128 sub-tile, the column sums (in-lane) and row sums (through
-// a small LDS transpose) for Section V's syndromes.  A second instantiation additionally plants
-// test faults into the accumulators first.
+// a small LDS transpose) for Section V's syndromes.  Test faults, when a list is given, are
+// planted into the accumulators first.
 //
 // Every tile walks k cyclically from its own start (a few k-tiles apart for neighbouring
 // tiles), so that the compute units sharing an operand panel do not ask L2 for the same line
@@ -39,7 +42,7 @@ namespace {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(4))) short s16x4_t;
 typedef __attribute__((ext_vector_type(8))) short s16x8_t;
-typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 typedef __attribute__((ext_vector_type(4))) int i32x4_t;
 typedef __attribute__((address_space(3))) s16x4_t lds_s16x4_t;
 
@@ -49,7 +52,7 @@ constexpr int TILE_BYTES = BM * BK * 2;            // 16 KiB: one k-tile of one 
 constexpr int NSTAGE = 4;                          // k-tiles of one operand resident in LDS
 constexpr int REGION_BYTES = NSTAGE * TILE_BYTES;  // 64 KiB per operand
 constexpr int SMEM_BYTES = 2 * REGION_BYTES;       // 128 KiB
-constexpr int EPI_SMEM_BYTES = 4 * 2 * 128 * 33 * 4;  // 132 KiB: row-sum transpose of the epilogue
+constexpr int EPI_SMEM_BYTES = 4 * 2 * 128 * 17 * 4;  // 68 KiB: row-sum transpose of the epilogue
 // DMA spread (see the schedule in the kernel): the 8 instructions of a pair go out as early as its
 // slot allows (all in the half after the slot is released when there is one k-contiguous operand,
 // 5 + 3 over two halves when there are two: a burst of 16 makes the address unit push back); the
@@ -65,6 +68,14 @@ constexpr unsigned OOB = 0x80000000u;              // voffset beyond any num_rec
 __device__ __forceinline__ void dma16(unsigned lds_addr, unsigned voff, i32x4_t rsrc, unsigned soff) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                :: "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff) : "memory");
+}
+// The same in two parts, for the main loop, where an MFMA goes between them (M0 must be written
+// at least one instruction before the load that reads it; nothing else in the loop writes M0)
+__device__ __forceinline__ void dma16_dest(unsigned lds_base, unsigned lds_off) {
+  asm volatile("s_add_u32 m0, %0, %1" :: "s"(lds_base), "s"(lds_off) : "memory", "scc");
+}
+__device__ __forceinline__ void dma16_load(unsigned voff, i32x4_t rsrc, unsigned soff) {
+  asm volatile("buffer_load_dwordx4 %0, %1, %2 offen lds" :: "v"(voff), "s"(rsrc), "s"(soff) : "memory");
 }
 
 __device__ __forceinline__ i32x4_t make_rsrc(const void* base, unsigned bytes) {
@@ -86,7 +97,7 @@ struct Operand {
   i32x4_t rsrc;
   unsigned voff[NV];    // byte offsets of this lane's 16-byte slots, loop invariant
   unsigned sstep;       // soffset advance per pair (KC) / per k-tile
-  int frag[4];          // LDS byte offset of this lane's fragment address for i = 0..3
+  int frag[8];          // LDS byte offset of this lane's fragment address for i = 0..7 (16 rows each)
 
   // P: operand base for this batch item; r0: first row (m- or n-index) of the tile;
   // rlim: number of valid rows; sub: first row of this wavefront's sub-tile inside the tile
@@ -103,12 +114,13 @@ struct Operand {
         const int row = s >> 3, c = (s & 7) ^ ((row >> 1) & 7);   // 8 lanes = one 128-byte line
         voff[i] = (unsigned)(row * ld * 2 + c * 16);
       }
-      const int l32 = lane & 31, lhi = lane >> 5;
+      const int l16 = lane & 15, g = lane >> 4;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int row = sub + i * 32 + l32;
-        // chunk = 4 (k-tile parity) + 2 ks + lhi; parity and ks toggle bits 6 and 5 of the offset
-        frag[i] = row * 128 + ((lhi ^ ((row >> 1) & 7)) << 4);
+      for (int i = 0; i < 8; ++i) {
+        const int row = sub + i * 16 + l16;
+        // chunk = 4 (k-tile parity) + g: lane group g holds k = 8 g .. 8 g + 7 of the k-tile; the
+        // parity toggles bit 6 of the offset
+        frag[i] = row * 128 + ((g ^ ((row >> 1) & 7)) << 4);
       }
     } else {
       const int64_t bytes = ((int64_t)klim * ld - r0) * 2;
@@ -118,17 +130,19 @@ struct Operand {
       for (int i = 0; i < NV; ++i) {
         const int s = (wave * NV + i) * 64 + lane;
         const int krow = s >> 5, p = s & 31;
-        const int u = ((((p >> 2) ^ (krow & 3)) << 2) | (p & 3));   // logical 16-byte unit along r
+        const int u = ((((p >> 2) ^ (krow & 3)) << 2) | ((p & 3) ^ (((krow >> 3) & 1) << 1)));   // logical 16-byte unit along r
         voff[i] = (r0 + u * 8 < rlim) ? (unsigned)(krow * ld * 2 + u * 16) : OOB;
       }
-      // transposing read: in each group of 16 lanes, lane 4 j + q supplies k-row j, columns 4 q..4 q + 3
+      // transposing read: in each group of 16 lanes, lane 4 j + q supplies k-row j, columns
+      // 4 q..4 q + 3, and lane t receives the 4 k-values of column t; group g reads k-rows 8 g + j
+      // (+ 4 for the second read), which makes lane (t, g) hold k = 8 g .. 8 g + 7 of row t
       const int g = lane >> 4, j = (lane >> 2) & 3, q = lane & 3;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int col = sub + i * 32 + 16 * (g & 1) + 4 * q;        // first of the 4 columns
-        const int krow = 8 * (g >> 1) + j;                          // + 16 ks, + 4 for the second read
+      for (int i = 0; i < 8; ++i) {
+        const int col = sub + i * 16 + 4 * q;                       // first of the 4 columns
+        const int krow = 8 * g + j;
         const int u = col >> 3;
-        frag[i] = krow * 512 + (((((u >> 2) ^ j) << 2) | (u & 3)) << 4) + (col & 7) * 2;
+        frag[i] = krow * 512 + (((((u >> 2) ^ j) << 2) | ((u & 3) ^ ((g & 1) << 1))) << 4) + (col & 7) * 2;
       }
     }
   }
@@ -144,19 +158,26 @@ struct Operand {
     const unsigned slot = KC ? (unit & 1) * (2 * TILE_BYTES) : (unit & (NSTAGE - 1)) * TILE_BYTES;
     dma16(lds_region + slot + (wave_u * NV + i) * 1024, voff[i], rsrc, src * sstep);
   }
+  // ... in two parts (PART 0: destination into M0, PART 1: the load)
+  template <int PART>
+  __device__ __forceinline__ void issue_part(unsigned lds_region, int wave_u, int unit, int src, int i) const {
+    const unsigned slot = KC ? (unit & 1) * (2 * TILE_BYTES) : (unit & (NSTAGE - 1)) * TILE_BYTES;
+    if (PART == 0) dma16_dest(lds_region + (wave_u * NV + i) * 1024, slot);
+    else dma16_load(voff[i], rsrc, src * sstep);
+  }
   __device__ __forceinline__ void issue_range(unsigned lds_region, int wave_u, int unit, int src, int first, int count) const {
 #pragma unroll
     for (int i = 0; i < NV; ++i)
       if (i >= first && i < first + count) issue_one(lds_region, wave_u, unit, src, i);
   }
 
-  // fragment i of the ks-th 16 k of k-tile kt; region = this operand's LDS region
-  __device__ __forceinline__ bf16x8_t fragment(const char* region, int kt, int i, int ks) const {
+  // fragment i (16 rows x the 32 k) of k-tile kt; region = this operand's LDS region
+  __device__ __forceinline__ bf16x8_t fragment(const char* region, int kt, int i) const {
     const char* tile = region + slot_of(kt);
     if (KC) {
-      return *reinterpret_cast<const bf16x8_t*>(tile + (frag[i] ^ (((kt & 1) << 6) | (ks << 5))));
+      return *reinterpret_cast<const bf16x8_t*>(tile + (frag[i] ^ ((kt & 1) << 6)));
     } else {
-      const char* p = tile + frag[i] + ks * (16 * 512);
+      const char* p = tile + frag[i];
       const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(p));
       const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(p + 4 * 512));
       const s16x8_t v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
@@ -221,12 +242,12 @@ __global__ __launch_bounds__(256) void zero_tail_kernel(GemmArgs a, int first) {
   }
 }
 
-template <bool KCA, bool KCB, bool EPI, bool FAULTS, bool SP>
+template <bool KCA, bool KCB, bool EPI, bool SP>
 __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wr = wave >> 1, wc = wave & 1;
-  const int l32 = lane & 31, lhi = lane >> 5;
+  const int l16 = lane & 15, lg = lane >> 4;
   const int b = blockIdx.y;
 
   const int ntm = (a.n + BM - 1) / BM, ntn = (a.m + BN - 1) / BN;
@@ -248,13 +269,14 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
   oa.init(A, a.lda, tile_r0, a.n, KT * BK, wr * 128);
   ob.init(B, a.ldb, tile_c0, a.m, KT * BK, wc * 128);
 
-  f32x16_t acc[4][4];
+  // acc[i][j][v] = C[16 i + 4 g + v][16 j + l16] of the sub-tile (g = lane >> 4, l16 = lane & 15)
+  f32x4_t acc[8][8];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < 8; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < 8; ++j)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+      for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.f;
 
   // LDS byte addresses of the two operand regions (address-space-3 values, not flat addresses)
   const unsigned ldsA = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
@@ -266,7 +288,7 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
   // ---- DMA schedule ---------------------------------------------------------------------------
   // A "unit" is what one LDS slot holds: a pair of k-tiles for a k-contiguous operand (nK of
   // them, 8 instructions per wavefront and unit), one k-tile otherwise (nM of them, 4
-  // instructions).  An iteration (one k-tile) has two halves of 16 MFMAs with the workgroup
+  // instructions).  An iteration (one k-tile) has two halves of 16 steps (two MFMAs each) with the workgroup
   // barrier between them; that barrier releases the slot of k-tile kt (and of its pair when kt
   // is odd) and is where k-tile kt+1 must have landed.  Where the loads go is a trade between
   // lead time (a pair's slot is free from the barrier of k-tile 2q+1 on and its data is needed
@@ -290,27 +312,33 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
   auto src_pair = [&](int pair) { int x = pair + p0; x -= x >= NP ? NP : 0; x -= x >= NP ? NP : 0; return x; };
   auto src_kt = [&](int t) { int x = t + 2 * p0; x -= x >= KT ? KT : 0; x -= x >= KT ? KT : 0; return x; };
 
+  // Sources (cyclic k order) of what the loop requests next, kept as running scalars: cp = pair
+  // kt/2 + 1 and cn = pair kt/2 + 2 of the current even kt, cm0 = k-tile kt + 3, cm1 = kt + 4
+  int cp = src_pair(1), cn = src_pair(2), cm0 = src_kt(3), cm1 = src_kt(4);
   // DMA instructions of half PH (0: 1st of even kt, 1: 2nd of even, 2: 1st of odd, 3: 2nd of odd)
-  // that belong behind MFMA number `step` of the half
-  auto dma_ops = [&](auto ph_c, const int step, const int kt) {
-    constexpr int PH = decltype(ph_c)::value;
+  // that belong behind step number `step` of the half
+  auto dma_ops = [&](auto ph_c, auto part_c, const int step, const int kt) {
+    constexpr int PH = decltype(ph_c)::value, PART = decltype(part_c)::value;
     constexpr int k_cnt = PH == 3 ? PA : PH == 0 ? PB : PH == 1 ? PC : 0;       // per operand
     constexpr int k_first = PH == 3 ? 0 : PH == 0 ? PA : PA + PB;
     constexpr int m_cnt = (PH & 1) ? MX : 4 - MX;
     constexpr int m_first = (PH & 1) ? 0 : MX;
     constexpr int issued = k_cnt * nK + m_cnt * nM, total = issued > 0 ? issued : 1;
-    const int pair = PH == 3 ? (kt + 3) >> 1 : (kt + 2) >> 1;   // slot (and source, clamped)
+    static_assert(total <= 16, "at most one DMA instruction per step: its two parts share M0");
+    const int pair = PH == 3 ? (kt + 3) >> 1 : (kt + 2) >> 1;   // slot
     const int mt = (PH & 1) ? kt + 4 : kt + 3;
+    static_assert(MX == 0, "the running sources cover the k-tiles requested in first halves only");
+    const int spair = PH == 3 ? cn : cp, smt = PH == 2 ? cm1 : cm0;
     int r = 0;
 #pragma unroll
     for (int x = 0; x < k_cnt; ++x) {
-      if (KCA) { if (step == (r * 16) / total) oa.issue_one(ldsA, wave_u, pair, src_pair(pair), k_first + x); ++r; }
-      if (KCB) { if (step == (r * 16) / total) ob.issue_one(ldsB, wave_u, pair, src_pair(pair), k_first + x); ++r; }
+      if (KCA) { if (step == (r * 16) / total) oa.template issue_part<PART>(ldsA, wave_u, pair, spair, k_first + x); ++r; }
+      if (KCB) { if (step == (r * 16) / total) ob.template issue_part<PART>(ldsB, wave_u, pair, spair, k_first + x); ++r; }
     }
 #pragma unroll
     for (int x = 0; x < m_cnt; ++x) {
-      if (!KCA) { if (step == (r * 16) / total) oa.issue_one(ldsA, wave_u, mt, src_kt(mt), m_first + x); ++r; }
-      if (!KCB) { if (step == (r * 16) / total) ob.issue_one(ldsB, wave_u, mt, src_kt(mt), m_first + x); ++r; }
+      if (!KCA) { if (step == (r * 16) / total) oa.template issue_part<PART>(ldsA, wave_u, mt, smt, m_first + x); ++r; }
+      if (!KCB) { if (step == (r * 16) / total) ob.template issue_part<PART>(ldsB, wave_u, mt, smt, m_first + x); ++r; }
     }
   };
 
@@ -332,39 +360,51 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
 
-  // Software pipeline with two fragment sets: fr0 = first 16 k of a k-tile, fr1 = second.
-  // 1st half of kt: 16 MFMAs on fr0, the reads of fr1 behind the first eight of them; barrier;
-  // 2nd half: 16 MFMAs on fr1, the reads of fr0 of k-tile kt+1 likewise.  Behind every MFMA at
-  // most one fragment read and the DMA instructions the schedule puts there, in exactly this
-  // order (every step is fenced), so each of them has MFMAs in flight as cover.
-  bf16x8_t fa0[4], fb0[4], fa1[4], fb1[4];
+  // Software pipeline.  A k-tile is 8 x 8 MFMA 16x16x32 per wavefront (the 16-row shape runs at
+  // a higher sustained clock than 32x32x16 at the same flops per cycle), in two halves of 32:
+  // rows 0..63 of the sub-tile (A fragments 0..3), then rows 64..127 (fragments 4..7), each
+  // against the 8 B fragments of the k-tile.  A "step" is two MFMAs.  1st half of kt: the reads
+  // of A fragments 4..7 of kt behind its first four steps; barrier; 2nd half: the reads of the 8
+  // B fragments (into the other of two sets) and of A fragments 0..3 of k-tile kt+1 behind its
+  // first twelve.  Behind every step at most one fragment read and the DMA instructions the
+  // schedule puts there, in exactly this order (every step is fenced), so each of them has MFMAs
+  // in flight as cover.
+  bf16x8_t fal[4], fah[4], fbe[8], fbo[8];     // A low / high rows; B of the even / odd k-tile
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    fa0[i] = oa.fragment(regA, 0, i, 0);
-    fb0[i] = ob.fragment(regB, 0, i, 0);
-  }
+  for (int i = 0; i < 4; ++i) fal[i] = oa.fragment(regA, 0, i);
+#pragma unroll
+  for (int j = 0; j < 8; ++j) fbe[j] = ob.fragment(regB, 0, j);
 
   auto half = [&](auto ph_c, const int kt) {
     constexpr int PH = decltype(ph_c)::value;
-    constexpr bool SECOND = PH & 1;
+    constexpr bool SECOND = PH & 1, ODD = (PH >> 1) & 1;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int step = i * 4 + j;
-        if (SECOND) {
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa1[i], fb1[j], acc[i][j], 0, 0, 0);
-          // (past the last k-tile this reads a slot nobody filled: in range, never used)
-          if (step < 4)      fb0[step] = ob.fragment(regB, kt + 1, step, 0);
-          else if (step < 8) fa0[step - 4] = oa.fragment(regA, kt + 1, step - 4, 0);
-        } else {
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0[i], fb0[j], acc[i][j], 0, 0, 0);
-          if (step < 4)      fb1[step] = ob.fragment(regB, kt, step, 1);
-          else if (step < 8) fa1[step - 4] = oa.fragment(regA, kt, step - 4, 1);
-        }
-        dma_ops(ph_c, step, kt);
-        __builtin_amdgcn_sched_barrier(0);
+    for (int step = 0; step < 16; ++step) {
+      const int i = step >> 2, j0 = (step & 3) * 2;
+      auto mfma = [&](const int j) {
+        const bf16x8_t fb = ODD ? fbo[j] : fbe[j];
+        if (SECOND) acc[4 + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fah[i], fb, acc[4 + i][j], 0, 0, 0);
+        else        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fal[i], fb, acc[i][j], 0, 0, 0);
+      };
+      // an MFMA occupies its pipe for 16 cycles, in which the wavefront can issue three other
+      // instructions: behind the first of the pair go the fragment read and the destination of
+      // the step's DMA instruction, behind the second its load
+      mfma(j0);
+      __builtin_amdgcn_sched_barrier(0);
+      if (SECOND) {
+        // (past the last k-tile this reads a slot nobody filled: in range, never used)
+        if (step < 8) { if (ODD) fbe[step] = ob.fragment(regB, kt + 1, step); else fbo[step] = ob.fragment(regB, kt + 1, step); }
+        else if (step < 12) fal[step - 8] = oa.fragment(regA, kt + 1, step - 8);
+      } else {
+        if (step >= 1 && step < 5) fah[step - 1] = oa.fragment(regA, kt, 3 + step);   // (not behind step 0: the
+                                                   // wait for the previous half's reads would take it along)
       }
+      dma_ops(ph_c, std::integral_constant<int, 0>{}, step, kt);
+      __builtin_amdgcn_sched_barrier(0);
+      mfma(j0 + 1);
+      __builtin_amdgcn_sched_barrier(0);
+      dma_ops(ph_c, std::integral_constant<int, 1>{}, step, kt);
+      __builtin_amdgcn_sched_barrier(0);
     }
   };
   auto barrier = [&](auto w_c) {
@@ -381,26 +421,32 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
     half(std::integral_constant<int, 2>{}, kt + 1);
     barrier(std::integral_constant<int, W_ODD>{});
     half(std::integral_constant<int, 3>{}, kt + 1);
+    cp = cn;
+    cn = cn + 1 >= NP ? cn + 1 - NP : cn + 1;
+    cm0 = cm1 + 1 >= KT ? cm1 + 1 - KT : cm1 + 1;
+    cm1 = cm0 + 1 >= KT ? cm0 + 1 - KT : cm0 + 1;
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __builtin_amdgcn_s_barrier();            // nobody's clamped reloads still land in LDS
 
   // ---- epilogue -------------------------------------------------------------------------------
   const int R0 = tile_r0 + wr * 128, C0 = tile_c0 + wc * 128;   // origin of this wavefront's sub-tile
-  if (FAULTS && khalf <= 0) {     // (of a split tile: planted into the first half)
+  // Test faults (none in production calls: then this is one scalar compare).  The loop is in
+  // every instantiation: with it the compiler keeps all accumulators in place in the accumulation
+  // registers through the main loop, without it it shuffles hundreds of them per iteration.
+  if (khalf <= 0) {     // (of a split tile: planted into the first half)
     for (int f = 0; f < a.n_faults; ++f) {
       const gecc_fault ft = a.faults[f];
       if (ft.batch != b || ft.row < R0 || ft.row >= R0 + 128 || ft.col < C0 || ft.col >= C0 + 128) continue;
       const int dr = ft.row - R0, dc = ft.col - C0;
-      const int fi = dr >> 5, rr = dr & 31, fj = dc >> 5;
-      const int fv = ((rr >> 3) << 2) | (rr & 3);
-      const bool mine = (((rr >> 2) & 1) == lhi) && ((dc & 31) == l32);
+      const int fi = dr >> 4, fv = dr & 3, fj = dc >> 4;
+      const bool mine = (((dr >> 2) & 3) == lg) && ((dc & 15) == l16);
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
+      for (int i = 0; i < 8; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < 8; ++j)
 #pragma unroll
-          for (int v = 0; v < 16; ++v)
+          for (int v = 0; v < 4; ++v)
             if (mine && i == fi && j == fj && v == fv) acc[i][j][v] += ft.offset;
     }
   }
@@ -408,16 +454,16 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
   // One pass over the accumulators, no branches.  C goes straight to memory through a raw
   // buffer whose base is the sub-tile origin and whose size ends with the last valid row: rows
   // beyond n fail the hardware range check and are dropped, and a lane whose column is beyond m
-  // carries an offset that is out of range by itself.  (One store = 2 rows x 32 consecutive
-  // columns = two full lines, marked non-temporal: C is written once and is larger than the
-  // memory-side cache, which is better spent on the operands the parity kernels read again.)
+  // carries an offset that is out of range by itself.  (One store = 4 rows x 16 consecutive
+  // columns, marked non-temporal: C is written once and is larger than the memory-side cache,
+  // which is better spent on the operands the parity kernels read again.)
   // The accumulators of such rows and columns are exact zeros (their
   // operand rows were read as zeros), so the sums below need no predicates.
-  // Column sums build up in 8 registers with the lane-independent part of the row weight (the
-  // lane part, 4 lhi, is added at the end); of every row the lane keeps the sum of its 4
-  // columns (one per 32-wide block) and u = x1 + 2 x2 + 3 x3, the block part of the column
-  // weight -- both go through LDS, where the 32 lanes of a half wavefront are added and the
-  // lane part of the weight is applied.
+  // Column sums build up in 16 registers with the lane-independent part of the row weight (the
+  // lane part, 4 g, is added at the end); of every row the lane keeps the sum of its 8
+  // columns (one per 16-wide block) and u = x1 + 2 x2 + .. + 7 x7, the block part of the column
+  // weight -- both go through LDS, where the 16 lanes of a group are added and the lane part of
+  // the weight is applied.
   // (SP: this workgroup has one half of k of a split tile; its partner has the other.  Both add
   // into zeroed memory instead of storing: two terms, so the result does not depend on who is
   // first.)
@@ -431,55 +477,60 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
       if (SP) __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(x, crsrc, off, 0, 0);
       else __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, x), crsrc, off, 0, 2);
     };
-    int vo[4];   // byte offset of this lane in row 4 lhi of the sub-tile, per 32-wide block
+    int vo[8];   // byte offset of this lane in row 4 g of the sub-tile, per 16-wide block
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
-      vo[j] = j * 32 + l32 < cols_left ? ((lhi * 4) * a.ldc + j * 32 + l32) * 4 : (int)OOB;
-    float cs[4] = {0.f, 0.f, 0.f, 0.f}, cw[4] = {0.f, 0.f, 0.f, 0.f};
-    float2* red2 = reinterpret_cast<float2*>(smem) + wave_u * (128 * 33) + (lhi * 4) * 33 + l32;
+    for (int j = 0; j < 8; ++j)
+      vo[j] = j * 16 + l16 < cols_left ? ((lg * 4) * a.ldc + j * 16 + l16) * 4 : (int)OOB;
+    float cs[8], cw[8];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int j = 0; j < 8; ++j) cs[j] = cw[j] = 0.f;
+    float2* red2 = reinterpret_cast<float2*>(smem) + wave_u * (128 * 17) + (lg * 4) * 17 + l16;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int ru = i * 32 + (v >> 2) * 8 + (v & 3);   // row inside the sub-tile, without 4 lhi
+    for (int i = 0; i < 8; ++i) {
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int ru = i * 16 + v;                        // row inside the sub-tile, without 4 g
         const int rowoff = ru * a.ldc * 4;                // scalar; < 2^31 (ldc < 2^22, checked by the launcher)
-        const float x0 = acc[i][0][v], x1 = acc[i][1][v], x2 = acc[i][2][v], x3 = acc[i][3][v];
-        put(x0, vo[0] + rowoff);
-        put(x1, vo[1] + rowoff);
-        put(x2, vo[2] + rowoff);
-        put(x3, vo[3] + rowoff);
+        float x[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          x[j] = acc[i][j][v];
+          put(x[j], vo[j] + rowoff);
+        }
         if (EPI) {
-          const float t2 = x2 + x3, t1 = x1 + t2;
-          red2[ru * 33] = make_float2(x0 + t1, (t1 + t2) + x3);
+          // s = x0 + .. + x7 and u = x1 + 2 x2 + .. + 7 x7 from suffix sums: u = t1 + t2 + .. + t7
+          const float t7 = x[7], t6 = x[6] + t7, t5 = x[5] + t6, t4 = x[4] + t5;
+          const float t3 = x[3] + t4, t2 = x[2] + t3, t1 = x[1] + t2;
+          red2[ru * 17] = make_float2(x[0] + t1, ((t1 + t2) + (t3 + t4)) + ((t5 + t6) + t7));
           const float wr_ = (float)(ru + 1);
-          cs[0] += x0; cw[0] = fmaf(x0, wr_, cw[0]);
-          cs[1] += x1; cw[1] = fmaf(x1, wr_, cw[1]);
-          cs[2] += x2; cw[2] = fmaf(x2, wr_, cw[2]);
-          cs[3] += x3; cw[3] = fmaf(x3, wr_, cw[3]);
+#pragma unroll
+          for (int j = 0; j < 8; ++j) { cs[j] += x[j]; cw[j] = fmaf(x[j], wr_, cw[j]); }
         }
       }
     }
     if (EPI) {
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const float w1 = fmaf((float)(lhi * 4), cs[j], cw[j]);
-        const float s = cs[j] + __shfl_xor(cs[j], 32, 64), w = w1 + __shfl_xor(w1, 32, 64);
-        const int col = C0 + j * 32 + l32;
-        if (lhi == 0 && col < a.m && R0 < a.n) {
+      for (int j = 0; j < 8; ++j) {
+        const float w1 = fmaf((float)(lg * 4), cs[j], cw[j]);
+        float s = cs[j] + __shfl_xor(cs[j], 16, 64), w = w1 + __shfl_xor(w1, 16, 64);
+        s += __shfl_xor(s, 32, 64);
+        w += __shfl_xor(w, 32, 64);
+        const int col = C0 + j * 16 + l16;
+        if (lg == 0 && col < a.m && R0 < a.n) {
           float* cp = a.colpart + (((int64_t)b * a.ntm + tm128) * a.cp_ld + col) * 2;
           if (SP) { atomicAdd(cp, s); atomicAdd(cp + 1, w); }
           else *reinterpret_cast<float2*>(cp) = make_float2(s, w);
         }
       }
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the region is this wavefront's own
-      const float2* mine = reinterpret_cast<const float2*>(smem) + wave_u * (128 * 33);
+      const float2* mine = reinterpret_cast<const float2*>(smem) + wave_u * (128 * 17);
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
         const int r = lane + 64 * h;
         float s = 0.f, w = 0.f, u = 0.f;
 #pragma unroll
-        for (int c = 0; c < 32; ++c) {
-          const float2 t = mine[r * 33 + c];
+        for (int c = 0; c < 16; ++c) {
+          const float2 t = mine[r * 17 + c];
           s += t.x;
           w = fmaf((float)(c + 1), t.x, w);
           u += t.y;
@@ -487,8 +538,8 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
         const int row = R0 + r;
         if (row < a.n && C0 < a.m) {
           float* rp = a.rowpart + (((int64_t)b * a.ntn + tn128) * a.rp_ld + row) * 2;
-          if (SP) { atomicAdd(rp, s); atomicAdd(rp + 1, fmaf(32.f, u, w)); }
-          else *reinterpret_cast<float2*>(rp) = make_float2(s, fmaf(32.f, u, w));
+          if (SP) { atomicAdd(rp, s); atomicAdd(rp + 1, fmaf(16.f, u, w)); }
+          else *reinterpret_cast<float2*>(rp) = make_float2(s, fmaf(16.f, u, w));
         }
       }
     if (!SP && blockIdx.x == 0) form_pg(a, b, reinterpret_cast<double*>(smem));   // P_g, once per batch item
@@ -496,12 +547,12 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
   }
 }
 
-template <bool KCA, bool KCB, bool EPI, bool FAULTS>
+template <bool KCA, bool KCB, bool EPI>
 hipError_t launch_one(const GemmArgs& a0, hipStream_t st) {
   static bool configured = false;   // per instantiation
   constexpr int lds_bytes = EPI && EPI_SMEM_BYTES > SMEM_BYTES ? EPI_SMEM_BYTES : SMEM_BYTES;
-  auto kern = gemm_bf16_256<KCA, KCB, EPI, FAULTS, false>;
-  auto kern_split = gemm_bf16_256<KCA, KCB, EPI, FAULTS, true>;
+  auto kern = gemm_bf16_256<KCA, KCB, EPI, false>;
+  auto kern_split = gemm_bf16_256<KCA, KCB, EPI, true>;
   if (!configured) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
@@ -542,13 +593,13 @@ hipError_t launch_one(const GemmArgs& a0, hipStream_t st) {
   return hipGetLastError();
 }
 
-template <bool EPI, bool FAULTS>
+template <bool EPI>
 hipError_t launch_layout(const GemmArgs& a, hipStream_t st) {
   const bool kca = a.trans_a == 0, kcb = a.trans_b != 0;
-  if (kca && kcb) return launch_one<true, true, EPI, FAULTS>(a, st);
-  if (kca && !kcb) return launch_one<true, false, EPI, FAULTS>(a, st);
-  if (!kca && kcb) return launch_one<false, true, EPI, FAULTS>(a, st);
-  return launch_one<false, false, EPI, FAULTS>(a, st);
+  if (kca && kcb) return launch_one<true, true, EPI>(a, st);
+  if (kca && !kcb) return launch_one<true, false, EPI>(a, st);
+  if (!kca && kcb) return launch_one<false, true, EPI>(a, st);
+  return launch_one<false, false, EPI>(a, st);
 }
 
 }  // namespace
@@ -572,8 +623,7 @@ bool gemm_bf16_fast_ok(const GemmArgs& a) {
 }
 
 hipError_t launch_gemm_bf16_fast(const GemmArgs& a, hipStream_t st) {
-  if (!a.rowpart) return launch_layout<false, false>(a, st);
-  return a.n_faults > 0 ? launch_layout<true, true>(a, st) : launch_layout<true, false>(a, st);
+  return a.rowpart ? launch_layout<true>(a, st) : launch_layout<false>(a, st);
 }
 
 }  // namespace gecc
