@@ -171,18 +171,35 @@ struct Operand {
       if (i >= first && i < first + count) issue_one(lds_region, wave_u, unit, src, i);
   }
 
-  // fragment i (16 rows x the 32 k) of k-tile kt; region = this operand's LDS region
-  __device__ __forceinline__ bf16x8_t fragment(const char* region, int kt, int i) const {
+  // fragment i (16 rows x the 32 k) of k-tile kt, as two halves of 4 k-values per lane (a
+  // transposing read fetches one half; the main loop puts them behind different MFMAs);
+  // region = this operand's LDS region
+  struct Frag {
+    s16x4_t lo, hi;
+    __device__ __forceinline__ bf16x8_t get() const {
+      return __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    }
+  };
+  // PART 0: all of a k-contiguous operand's fragment (one ds_read_b128), else the first half;
+  // PART 1: the second half of the other kind
+  template <int PART>
+  __device__ __forceinline__ void fragment_part(Frag& f, const char* region, int kt, int i) const {
     const char* tile = region + slot_of(kt);
     if (KC) {
-      return *reinterpret_cast<const bf16x8_t*>(tile + (frag[i] ^ ((kt & 1) << 6)));
+      if (PART == 0) {
+        const s16x8_t v = *reinterpret_cast<const s16x8_t*>(tile + (frag[i] ^ ((kt & 1) << 6)));
+        f.lo = __builtin_shufflevector(v, v, 0, 1, 2, 3);
+        f.hi = __builtin_shufflevector(v, v, 4, 5, 6, 7);
+      }
     } else {
       const char* p = tile + frag[i];
-      const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(p));
-      const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(p + 4 * 512));
-      const s16x8_t v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-      return __builtin_bit_cast(bf16x8_t, v);
+      if (PART == 0) f.lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(p));
+      else           f.hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(p + 4 * 512));
     }
+  }
+  __device__ __forceinline__ void fragment(Frag& f, const char* region, int kt, int i) const {
+    fragment_part<0>(f, region, kt, i);
+    fragment_part<1>(f, region, kt, i);
   }
 };
 
@@ -369,11 +386,12 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
   // first twelve.  Behind every step at most one fragment read and the DMA instructions the
   // schedule puts there, in exactly this order (every step is fenced), so each of them has MFMAs
   // in flight as cover.
-  bf16x8_t fal[4], fah[4], fbe[8], fbo[8];     // A low / high rows; B of the even / odd k-tile
+  typename Operand<KCA>::Frag fal[4], fah[4];     // A low / high rows
+  typename Operand<KCB>::Frag fbe[8], fbo[8];     // B of the even / odd k-tile
 #pragma unroll
-  for (int i = 0; i < 4; ++i) fal[i] = oa.fragment(regA, 0, i);
+  for (int i = 0; i < 4; ++i) oa.fragment(fal[i], regA, 0, i);
 #pragma unroll
-  for (int j = 0; j < 8; ++j) fbe[j] = ob.fragment(regB, 0, j);
+  for (int j = 0; j < 8; ++j) ob.fragment(fbe[j], regB, 0, j);
 
   auto half = [&](auto ph_c, const int kt) {
     constexpr int PH = decltype(ph_c)::value;
@@ -382,27 +400,34 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
     for (int step = 0; step < 16; ++step) {
       const int i = step >> 2, j0 = (step & 3) * 2;
       auto mfma = [&](const int j) {
-        const bf16x8_t fb = ODD ? fbo[j] : fbe[j];
-        if (SECOND) acc[4 + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fah[i], fb, acc[4 + i][j], 0, 0, 0);
-        else        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fal[i], fb, acc[i][j], 0, 0, 0);
+        const bf16x8_t fb = ODD ? fbo[j].get() : fbe[j].get();
+        if (SECOND) acc[4 + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fah[i].get(), fb, acc[4 + i][j], 0, 0, 0);
+        else        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fal[i].get(), fb, acc[i][j], 0, 0, 0);
       };
       // an MFMA occupies its pipe for 16 cycles, in which the wavefront can issue three other
-      // instructions: behind the first of the pair go the fragment read and the destination of
-      // the step's DMA instruction, behind the second its load
+      // instructions: behind the first of the pair go the fragment read (the first of the two
+      // transposing ones) and the destination of the step's DMA instruction, behind the second
+      // the other transposing read and the load
+      auto read = [&](auto part_c) {
+        constexpr int PART = decltype(part_c)::value;
+        if (SECOND) {
+          // (past the last k-tile this reads a slot nobody filled: in range, never used)
+          if (step < 8) { if (ODD) ob.template fragment_part<PART>(fbe[step], regB, kt + 1, step);
+                          else     ob.template fragment_part<PART>(fbo[step], regB, kt + 1, step); }
+          else if (step < 12) oa.template fragment_part<PART>(fal[step - 8], regA, kt + 1, step - 8);
+        } else {
+          // (not behind step 0: the wait for the previous half's reads would take it along)
+          if (step >= 1 && step < 5) oa.template fragment_part<PART>(fah[step - 1], regA, kt, 3 + step);
+        }
+      };
       mfma(j0);
       __builtin_amdgcn_sched_barrier(0);
-      if (SECOND) {
-        // (past the last k-tile this reads a slot nobody filled: in range, never used)
-        if (step < 8) { if (ODD) fbe[step] = ob.fragment(regB, kt + 1, step); else fbo[step] = ob.fragment(regB, kt + 1, step); }
-        else if (step < 12) fal[step - 8] = oa.fragment(regA, kt + 1, step - 8);
-      } else {
-        if (step >= 1 && step < 5) fah[step - 1] = oa.fragment(regA, kt, 3 + step);   // (not behind step 0: the
-                                                   // wait for the previous half's reads would take it along)
-      }
+      read(std::integral_constant<int, 0>{});
       dma_ops(ph_c, std::integral_constant<int, 0>{}, step, kt);
       __builtin_amdgcn_sched_barrier(0);
       mfma(j0 + 1);
       __builtin_amdgcn_sched_barrier(0);
+      read(std::integral_constant<int, 1>{});
       dma_ops(ph_c, std::integral_constant<int, 1>{}, step, kt);
       __builtin_amdgcn_sched_barrier(0);
     }
