@@ -479,9 +479,13 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
   // One pass over the accumulators, no branches.  C goes straight to memory through a raw
   // buffer whose base is the sub-tile origin and whose size ends with the last valid row: rows
   // beyond n fail the hardware range check and are dropped, and a lane whose column is beyond m
-  // carries an offset that is out of range by itself.  (One store = 4 rows x 16 consecutive
-  // columns, marked non-temporal: C is written once and is larger than the memory-side cache,
-  // which is better spent on the operands the parity kernels read again.)
+  // carries an offset that is out of range by itself.  An accumulator register holds 4 rows x
+  // 16 columns (64-byte pieces, which the memory system takes a third slower than whole
+  // lines), so the registers of two neighbouring column blocks first trade their odd / even
+  // groups of 16 lanes (v_permlane16_swap): each then holds 2 rows x 32 consecutive columns, two
+  // full lines per store.  (Stores are marked non-temporal: C is written once and is larger
+  // than the memory-side cache, which is better spent on the operands the parity kernels read
+  // again.)
   // The accumulators of such rows and columns are exact zeros (their
   // operand rows were read as zeros), so the sums below need no predicates.
   // Column sums build up in 16 registers with the lane-independent part of the row weight (the
@@ -502,10 +506,14 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
       if (SP) __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(x, crsrc, off, 0, 0);
       else __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, x), crsrc, off, 0, 2);
     };
-    int vo[8];   // byte offset of this lane in row 4 g of the sub-tile, per 16-wide block
+    // after the swap lane (l16, g) of the first register of a pair has row 8 (g >> 1), column
+    // 16 (g & 1) + l16 of the 32-wide block (the second register: 4 rows further down)
+    int vo[4];   // byte offset of this lane in the sub-tile, per 32-wide block
 #pragma unroll
-    for (int j = 0; j < 8; ++j)
-      vo[j] = j * 16 + l16 < cols_left ? ((lg * 4) * a.ldc + j * 16 + l16) * 4 : (int)OOB;
+    for (int jp = 0; jp < 4; ++jp) {
+      const int col = jp * 32 + (lg & 1) * 16 + l16;
+      vo[jp] = col < cols_left ? ((lg >> 1) * 8 * a.ldc + col) * 4 : (int)OOB;
+    }
     float cs[8], cw[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) cs[j] = cw[j] = 0.f;
@@ -518,9 +526,15 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
         const int rowoff = ru * a.ldc * 4;                // scalar; < 2^31 (ldc < 2^22, checked by the launcher)
         float x[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          x[j] = acc[i][j][v];
-          put(x[j], vo[j] + rowoff);
+        for (int j = 0; j < 8; ++j) x[j] = acc[i][j][v];
+#pragma unroll
+        for (int jp = 0; jp < 4; ++jp) {
+          // (inline: this compiler's builtin for the swap loses its second result; the wait
+          // states are the ones a swap needs after a vector instruction wrote its operands)
+          float t0 = x[2 * jp], t1 = x[2 * jp + 1];
+          asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1" : "+v"(t0), "+v"(t1));
+          put(t0, vo[jp] + rowoff);
+          put(t1, vo[jp] + rowoff + 4 * a.ldc * 4);
         }
         if (EPI) {
           // s = x0 + .. + x7 and u = x1 + 2 x2 + .. + 7 x7 from suffix sums: u = t1 + t2 + .. + t7
