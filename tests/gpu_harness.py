@@ -40,6 +40,7 @@ class GpuResult:
     B_par: np.ndarray
     C_par: np.ndarray      # (batch, 2n+2m+4)
     synd: np.ndarray
+    pad_untouched: bool = True   # the columns of C between m and ldc still hold what they held before
 
 
 def run_gpu(A_enc, B_enc, A_mul, B_mul, c_faults, tau, dtype, trans_a=0, trans_b=0, refine=1,
@@ -72,7 +73,7 @@ def run_gpu(A_enc, B_enc, A_mul, B_mul, c_faults, tau, dtype, trans_a=0, trans_b
         reports, attempts = ctx.protected_gemm_retry(dA, dB, Cd, A_par, B_par, C_par, rep, 0, fl, nf)
         assert attempts == 1
         return GpuResult(reports=reports,
-                         C=Cd.cpu().numpy().astype(np.float64)[:, :, :m],
+                         C=Cd.cpu().numpy().astype(np.float64)[:, :, :m], pad_untouched=bool(torch.isnan(Cd[:, :, m:]).all()),
                          A=from_dev(dA, trans_a, n if trans_a else k), B=from_dev(dB, trans_b, k if trans_b else m),
                          A_par=A_par.cpu().numpy().reshape(batch, 2, k), B_par=B_par.cpu().numpy().reshape(batch, 2, k),
                          C_par=C_par.cpu().numpy().reshape(batch, -1), synd=ctx.syndromes_to_host())
@@ -95,7 +96,7 @@ def run_gpu(A_enc, B_enc, A_mul, B_mul, c_faults, tau, dtype, trans_a=0, trans_b
     reports = ctx.report_to_host(rep)
     torch.cuda.synchronize()
     return GpuResult(reports=reports,
-                     C=Cd.cpu().numpy().astype(np.float64)[:, :, :m],
+                     C=Cd.cpu().numpy().astype(np.float64)[:, :, :m], pad_untouched=bool(torch.isnan(Cd[:, :, m:]).all()),
                      A=from_dev(dA, trans_a, n if trans_a else k), B=from_dev(dB, trans_b, k if trans_b else m),
                      A_par=A_par.cpu().numpy().reshape(batch, 2, k), B_par=B_par.cpu().numpy().reshape(batch, 2, k),
                      C_par=C_par.cpu().numpy().reshape(batch, -1), synd=synd)

@@ -314,6 +314,23 @@ def test_unaligned_leading_dimensions_take_the_scalar_paths():
         assert g.reports[0].status == gecc.CORRECTED
 
 
+@pytest.mark.parametrize("trans", [(0, 0), (0, 1), (1, 0), (1, 1)])
+def test_padded_leading_dimensions_in_the_fast_bf16_kernel(trans):
+    """Leading dimensions larger than the rows (by a multiple of 8 elements, which keeps the 256 x 256
+    kernel): operand panels and the stores of C, two rows x 32 columns each, walk the padded rows."""
+    n, k, m = 520, 256, 264
+    rng = inputs.rng_for(94, 1)
+    law = ("normal", 1.0)
+    faults = [inputs.Fault(MAT_A, 300, 7, 3.0), inputs.Fault(MAT_C, n - 1, m - 1, 21.5)]
+    A, B, A2, B2, cf, eff = _trial(rng, n, k, m, "bf16", law, law, faults)
+    tau = gecc.noise_thresholds(n, k, m, 1.0, 1.0)
+    cfb = [(0,) + c for c in cf]
+    g = H.run_gpu(A, B, A2, B2, cfb, tau, "bf16", trans[0], trans[1], ld_pad=24)
+    H.compare(g, H.run_oracle(A, B, A2, B2, cfb, tau), 1e-5, what="padded ld, trans %s" % (trans,))
+    assert g.reports[0].status == gecc.CORRECTED and g.pad_untouched
+    assert [(e[0], e[1], e[2]) for e in g.reports[0].errors()] == [(e[0], e[1], e[2]) for e in eff]
+
+
 def test_all_zero_operands_are_clean():
     n, k, m = 200, 64, 136
     Z = np.zeros((n, k), np.float32), np.zeros((k, m), np.float32)
