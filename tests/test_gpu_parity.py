@@ -30,7 +30,8 @@ def _trial(rng, n, k, m, dtype, law_a, law_b, faults):
 # the last two reach the 256 x 256-tile bf16 kernel (k % 64 == 0, rows of 8 elements) with ragged
 # tiles on both edges; everything else goes to the generic kernel
 SHAPES = [(128, 128, 128), (1, 1, 1), (3, 5, 2), (130, 70, 257), (300, 200, 260), (257, 1031, 129),
-          (520, 256, 264), (1000, 320, 776)]
+          (520, 256, 264), (1000, 320, 776),
+          (520, 64, 264), (264, 192, 520)]    # the 256 x 256 bf16 kernel at its shortest k (one pair of k-tiles), and three pairs
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
