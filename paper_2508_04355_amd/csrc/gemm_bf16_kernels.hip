@@ -305,8 +305,8 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
   // ---- DMA schedule ---------------------------------------------------------------------------
   // A "unit" is what one LDS slot holds: a pair of k-tiles for a k-contiguous operand (nK of
   // them, 8 instructions per wavefront and unit), one k-tile otherwise (nM of them, 4
-  // instructions).  An iteration (one k-tile) has two halves of 16 steps (two MFMAs each) with the workgroup
-  // barrier between them; that barrier releases the slot of k-tile kt (and of its pair when kt
+  // instructions).  An iteration (one k-tile) has two halves of 16 steps (two MFMAs each) with
+  // the workgroup barrier between them; that barrier releases the slot of k-tile kt (and of its pair when kt
   // is odd) and is where k-tile kt+1 must have landed.  Where the loads go is a trade between
   // lead time (a pair's slot is free from the barrier of k-tile 2q+1 on and its data is needed
   // at the barrier of 2q+3; with two k-contiguous operands the wavefronts used to wait there for
@@ -318,8 +318,8 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
   // "k-tile kt+1 has landed" becomes "at most W instructions are pending", W = at most what the
   // schedule issues after the last instruction of that k-tile's units (for any PA, PB, PC):
   //   kt even: (PA + PB) nK + 8 nM        kt odd: 4 nM  (8 nM without a k-contiguous operand)
-  // Units past the end of k are clamped to the last one (a harmless reload into a free slot),
-  // which keeps every iteration identical.
+  // Units past the end of k wrap around to the start of the tile's cyclic order (a harmless
+  // reload into a free slot that nobody reads), which keeps every iteration identical.
   constexpr int nK = (KCA ? 1 : 0) + (KCB ? 1 : 0), nM = 2 - nK;
   constexpr int PA = nK == 2 ? 5 : 8, PB = 8 - PA, PC = 8 - PA - PB;
   constexpr int W_EVEN = (PA + PB) * nK + 8 * nM, W_ODD = nK > 0 ? 4 * nM : 8 * nM;
@@ -383,9 +383,9 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
   // against the 8 B fragments of the k-tile.  A "step" is two MFMAs.  1st half of kt: the reads
   // of A fragments 4..7 of kt behind its first four steps; barrier; 2nd half: the reads of the 8
   // B fragments (into the other of two sets) and of A fragments 0..3 of k-tile kt+1 behind its
-  // first twelve.  Behind every step at most one fragment read and the DMA instructions the
-  // schedule puts there, in exactly this order (every step is fenced), so each of them has MFMAs
-  // in flight as cover.
+  // first twelve.  A step carries at most one fragment read and one DMA instruction, dealt out
+  // over its two MFMAs in exactly the order written below (every position is fenced), so each
+  // of them has an MFMA in flight as cover.
   typename Operand<KCA>::Frag fal[4], fah[4];     // A low / high rows
   typename Operand<KCB>::Frag fbe[8], fbo[8];     // B of the even / odd k-tile
 #pragma unroll
