@@ -71,8 +71,9 @@ __device__ __forceinline__ void dma16(unsigned lds_addr, unsigned voff, i32x4_t 
 }
 // The same in two parts, for the main loop, where an MFMA goes between them (M0 must be written
 // at least one instruction before the load that reads it; nothing else in the loop writes M0)
-__device__ __forceinline__ void dma16_dest(unsigned lds_base, unsigned lds_off) {
-  asm volatile("s_add_u32 m0, %0, %1" :: "s"(lds_base), "s"(lds_off) : "memory", "scc");
+template <unsigned LDS_OFF>
+__device__ __forceinline__ void dma16_dest(unsigned lds_base) {
+  asm volatile("s_add_u32 m0, %0, %1" :: "s"(lds_base), "n"(LDS_OFF) : "memory", "scc");
 }
 __device__ __forceinline__ void dma16_load(unsigned voff, i32x4_t rsrc, unsigned soff) {
   asm volatile("buffer_load_dwordx4 %0, %1, %2 offen lds" :: "v"(voff), "s"(rsrc), "s"(soff) : "memory");
@@ -159,11 +160,13 @@ struct Operand {
     dma16(lds_region + slot + (wave_u * NV + i) * 1024, voff[i], rsrc, src * sstep);
   }
   // ... in two parts (PART 0: destination into M0, PART 1: the load)
-  template <int PART>
-  __device__ __forceinline__ void issue_part(unsigned lds_region, int wave_u, int unit, int src, int i) const {
-    const unsigned slot = KC ? (unit & 1) * (2 * TILE_BYTES) : (unit & (NSTAGE - 1)) * TILE_BYTES;
-    if (PART == 0) dma16_dest(lds_region + (wave_u * NV + i) * 1024, slot);
-    else dma16_load(voff[i], rsrc, src * sstep);
+  // UNIT: the unit's number modulo the slots (a compile-time constant in the main loop)
+  template <int PART, int UNIT>
+  __device__ __forceinline__ void issue_part(unsigned lds_region, int wave_u, int src, int i) const {
+    constexpr unsigned slot = KC ? (UNIT & 1) * (2 * TILE_BYTES) : (UNIT & (NSTAGE - 1)) * TILE_BYTES;
+    if (PART == 0) dma16_dest<slot>(lds_region + (wave_u * NV + i) * 1024);
+    else if (PART == 1) dma16_load(voff[i], rsrc, src * sstep);
+    else dma16(lds_region + slot + (wave_u * NV + i) * 1024, voff[i], rsrc, src * sstep);
   }
   __device__ __forceinline__ void issue_range(unsigned lds_region, int wave_u, int unit, int src, int first, int count) const {
 #pragma unroll
@@ -182,26 +185,75 @@ struct Operand {
   };
   // PART 0: all of a k-contiguous operand's fragment (one ds_read_b128), else the first half;
   // PART 1: the second half of the other kind
-  template <int PART>
-  __device__ __forceinline__ void fragment_part(Frag& f, const char* region, int kt, int i) const {
-    const char* tile = region + slot_of(kt);
+  // KT4: the k-tile's number modulo 4 (a compile-time constant in the main loop, so that slot
+  // and fragment become the immediate offset of the read: the address registers are loop invariant)
+  template <int PART, int KT4>
+  __device__ __forceinline__ void fragment_part(Frag& f, const char* region, int i) const {
     if (KC) {
       if (PART == 0) {
-        const s16x8_t v = *reinterpret_cast<const s16x8_t*>(tile + (frag[i] ^ ((kt & 1) << 6)));
+        // frag[i] = frag[0] + 2048 i, and the parity only toggles bit 6 of frag[0]
+        const char* p = region + (frag[0] ^ ((KT4 & 1) << 6)) + (((KT4 >> 1) & 1) * (2 * TILE_BYTES) + i * 2048);
+        const s16x8_t v = *reinterpret_cast<const s16x8_t*>(p);
         f.lo = __builtin_shufflevector(v, v, 0, 1, 2, 3);
         f.hi = __builtin_shufflevector(v, v, 4, 5, 6, 7);
       }
     } else {
-      const char* p = tile + frag[i];
+      const char* p = region + frag[i] + (KT4 & (NSTAGE - 1)) * TILE_BYTES;
       if (PART == 0) f.lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(p));
       else           f.hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(p + 4 * 512));
     }
   }
-  __device__ __forceinline__ void fragment(Frag& f, const char* region, int kt, int i) const {
-    fragment_part<0>(f, region, kt, i);
-    fragment_part<1>(f, region, kt, i);
+  // k-tile 0 (prologue)
+  __device__ __forceinline__ void fragment(Frag& f, const char* region, int i) const {
+    fragment_part<0, 0>(f, region, i);
+    fragment_part<1, 0>(f, region, i);
   }
 };
+
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>), in order
+template <int N, int I = 0, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    static_for<N, I + 1>(f);
+  }
+}
+
+// What goes behind each of the 32 MFMAs of a half.  Measured on the chip with one wavefront per
+// SIMD: behind a 16-cycle MFMA one other instruction issues for free, a second costs 4 cycles,
+// a third 8 more.  So the D DMA instructions of the half (two instructions each: destination
+// into M0, then -- behind the next MFMA, which also is the wait state M0 needs -- the load) and
+// its R LDS reads are dealt out one per MFMA, DMA instructions evenly over the half, reads from
+// MFMA number G0 on and over the first four fifths of it (their data is needed when the half ends).
+// With more than 32 of them some MFMAs get two.
+enum { OP_NONE = 0, OP_READ = 1, OP_DEST = 2, OP_LOAD = 3, OP_DMA = 4 /* both parts, with the wait state */ };
+struct HalfPlan {
+  signed char kind[32][2], idx[32][2];
+};
+template <int D, int R, int G0>
+constexpr HalfPlan make_half_plan() {
+  HalfPlan p{};
+  int sk[80] = {}, si[80] = {}, T = 0;
+  int d = 0, r = 0;
+  while (d < D || r < R) {   // merge by position: DMA d at (d + 1/2) / D, read r at 4/5 (r + 1/2) / R
+    const bool dma = d < D && (r >= R || 5 * (2 * d + 1) * R <= 4 * (2 * r + 1) * D);
+    if (dma) { sk[T] = OP_DEST; si[T] = d; ++T; sk[T] = OP_LOAD; si[T] = d; ++T; ++d; }
+    else { sk[T] = OP_READ; si[T] = r; ++T; ++r; }
+  }
+  const int cap = 32 - G0, den = T > cap ? T : cap;
+  int fill[32] = {};
+  for (int k = 0; k < T; ++k) {
+    int g = G0 + k * cap / den;
+    while (fill[g] >= 2) ++g;                       // (never past 31: T <= 64 - 2 G0 is asserted by the caller)
+    if (fill[g] == 1 && p.kind[g][0] == OP_DEST && sk[k] == OP_LOAD) { p.kind[g][0] = OP_DMA; continue; }
+    p.kind[g][fill[g]] = (signed char)sk[k];
+    p.idx[g][fill[g]] = (signed char)si[k];
+    ++fill[g];
+  }
+  return p;
+}
+template <int D, int R, int G0>
+inline constexpr HalfPlan kHalfPlan = make_half_plan<D, R, G0>();
 
 // s_waitcnt vmcnt(N), N a compile-time constant below 64
 template <int N>
@@ -334,28 +386,29 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
   int cp = src_pair(1), cn = src_pair(2), cm0 = src_kt(3), cm1 = src_kt(4);
   // DMA instructions of half PH (0: 1st of even kt, 1: 2nd of even, 2: 1st of odd, 3: 2nd of odd)
   // that belong behind step number `step` of the half
-  auto dma_ops = [&](auto ph_c, auto part_c, const int step, const int kt) {
-    constexpr int PH = decltype(ph_c)::value, PART = decltype(part_c)::value;
+  // DMA instruction number ORD of half PH of the main loop (PH = 0..3: the halves of k-tiles kt,
+  // kt + 1 with kt = 0 mod 4; 4..7: those of kt + 2, kt + 3), PART 0: destination, 1: load, 2: both
+  auto dma_op = [&](auto ph_c, auto part_c, auto ord_c) {
+    constexpr int PH8 = decltype(ph_c)::value, PH = PH8 & 3, KT0 = (PH8 >> 2) * 2 + (PH >> 1);   // k-tile mod 4
+    constexpr int PART = decltype(part_c)::value, ORD = decltype(ord_c)::value;
     constexpr int k_cnt = PH == 3 ? PA : PH == 0 ? PB : PH == 1 ? PC : 0;       // per operand
     constexpr int k_first = PH == 3 ? 0 : PH == 0 ? PA : PA + PB;
     constexpr int m_cnt = (PH & 1) ? MX : 4 - MX;
     constexpr int m_first = (PH & 1) ? 0 : MX;
-    constexpr int issued = k_cnt * nK + m_cnt * nM, total = issued > 0 ? issued : 1;
-    static_assert(total <= 16, "at most one DMA instruction per step: its two parts share M0");
-    const int pair = PH == 3 ? (kt + 3) >> 1 : (kt + 2) >> 1;   // slot
-    const int mt = (PH & 1) ? kt + 4 : kt + 3;
+    constexpr int pair = PH == 3 ? (KT0 + 3) >> 1 : (KT0 + 2) >> 1;   // slot
+    constexpr int mt = (PH & 1) ? KT0 + 4 : KT0 + 3;
     static_assert(MX == 0, "the running sources cover the k-tiles requested in first halves only");
     const int spair = PH == 3 ? cn : cp, smt = PH == 2 ? cm1 : cm0;
     int r = 0;
 #pragma unroll
     for (int x = 0; x < k_cnt; ++x) {
-      if (KCA) { if (step == (r * 16) / total) oa.template issue_part<PART>(ldsA, wave_u, pair, spair, k_first + x); ++r; }
-      if (KCB) { if (step == (r * 16) / total) ob.template issue_part<PART>(ldsB, wave_u, pair, spair, k_first + x); ++r; }
+      if (KCA) { if (r == ORD) oa.template issue_part<PART, pair>(ldsA, wave_u, spair, k_first + x); ++r; }
+      if (KCB) { if (r == ORD) ob.template issue_part<PART, pair>(ldsB, wave_u, spair, k_first + x); ++r; }
     }
 #pragma unroll
     for (int x = 0; x < m_cnt; ++x) {
-      if (!KCA) { if (step == (r * 16) / total) oa.template issue_part<PART>(ldsA, wave_u, mt, smt, m_first + x); ++r; }
-      if (!KCB) { if (step == (r * 16) / total) ob.template issue_part<PART>(ldsB, wave_u, mt, smt, m_first + x); ++r; }
+      if (!KCA) { if (r == ORD) oa.template issue_part<PART, mt>(ldsA, wave_u, smt, m_first + x); ++r; }
+      if (!KCB) { if (r == ORD) ob.template issue_part<PART, mt>(ldsB, wave_u, smt, m_first + x); ++r; }
     }
   };
 
@@ -389,48 +442,55 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
   typename Operand<KCA>::Frag fal[4], fah[4];     // A low / high rows
   typename Operand<KCB>::Frag fbe[8], fbo[8];     // B of the even / odd k-tile
 #pragma unroll
-  for (int i = 0; i < 4; ++i) oa.fragment(fal[i], regA, 0, i);
+  for (int i = 0; i < 4; ++i) oa.fragment(fal[i], regA, i);
 #pragma unroll
-  for (int j = 0; j < 8; ++j) ob.fragment(fbe[j], regB, 0, j);
+  for (int j = 0; j < 8; ++j) ob.fragment(fbe[j], regB, j);
 
-  auto half = [&](auto ph_c, const int kt) {
-    constexpr int PH = decltype(ph_c)::value;
+  auto half = [&](auto ph_c) {
+    constexpr int PH8 = decltype(ph_c)::value, PH = PH8 & 3, KT0 = (PH8 >> 2) * 2 + (PH >> 1);   // k-tile mod 4
     constexpr bool SECOND = PH & 1, ODD = (PH >> 1) & 1;
-#pragma unroll
-    for (int step = 0; step < 16; ++step) {
-      const int i = step >> 2, j0 = (step & 3) * 2;
-      auto mfma = [&](const int j) {
-        const bf16x8_t fb = ODD ? fbo[j].get() : fbe[j].get();
-        if (SECOND) acc[4 + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fah[i].get(), fb, acc[4 + i][j], 0, 0, 0);
-        else        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fal[i].get(), fb, acc[i][j], 0, 0, 0);
-      };
-      // an MFMA occupies its pipe for 16 cycles, in which the wavefront can issue three other
-      // instructions: behind the first of the pair go the fragment read (the first of the two
-      // transposing ones) and the destination of the step's DMA instruction, behind the second
-      // the other transposing read and the load
-      auto read = [&](auto part_c) {
-        constexpr int PART = decltype(part_c)::value;
-        if (SECOND) {
-          // (past the last k-tile this reads a slot nobody filled: in range, never used)
-          if (step < 8) { if (ODD) ob.template fragment_part<PART>(fbe[step], regB, kt + 1, step);
-                          else     ob.template fragment_part<PART>(fbo[step], regB, kt + 1, step); }
-          else if (step < 12) oa.template fragment_part<PART>(fal[step - 8], regA, kt + 1, step - 8);
+    constexpr int OA = KCA ? 1 : 2, OB = KCB ? 1 : 2;     // LDS instructions per fragment
+    constexpr int D = (PH == 3 ? PA : PH == 0 ? PB : PH == 1 ? PC : 0) * nK + ((PH & 1) ? MX : 4 - MX) * nM;
+    constexpr int R = SECOND ? 8 * OB + 4 * OA : 4 * OA;
+    constexpr int G0 = SECOND ? 0 : 2;   // (1st half: not behind the first MFMAs, or the wait for the previous half's reads takes them along)
+    static_assert(2 * D + R <= 64 - 2 * G0, "two instructions per MFMA at most");
+    // LDS instruction number OP of the half: 2nd half: the 8 B fragments, then A fragments 0..3, of
+    // the next k-tile (past the last k-tile this reads a slot nobody filled: in range, never
+    // used); 1st half: A fragments 4..7 of this k-tile
+    auto read_op = [&](auto op_c) {
+      constexpr int op = decltype(op_c)::value;
+      if constexpr (SECOND) {
+        if constexpr (op < 8 * OB) {
+          constexpr int f = op / OB, part = op % OB;
+          if (ODD) ob.template fragment_part<part, (KT0 + 1) & 3>(fbe[f], regB, f);
+          else     ob.template fragment_part<part, (KT0 + 1) & 3>(fbo[f], regB, f);
         } else {
-          // (not behind step 0: the wait for the previous half's reads would take it along)
-          if (step >= 1 && step < 5) oa.template fragment_part<PART>(fah[step - 1], regA, kt, 3 + step);
+          constexpr int f = (op - 8 * OB) / OA, part = (op - 8 * OB) % OA;
+          oa.template fragment_part<part, (KT0 + 1) & 3>(fal[f], regA, f);
         }
-      };
-      mfma(j0);
+      } else {
+        constexpr int f = op / OA, part = op % OA;
+        oa.template fragment_part<part, KT0>(fah[f], regA, 4 + f);
+      }
+    };
+    static_for<32>([&](auto g_c) {
+      constexpr int g = decltype(g_c)::value, i = g >> 3, j = g & 7;
+      const bf16x8_t fb = ODD ? fbo[j].get() : fbe[j].get();
+      // (inline, with the accumulator tied to the accumulation registers: left to itself the
+      // compiler moves hundreds of accumulators between register files in every round of the loop)
+      if (SECOND) asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[4 + i][j]) : "v"(fah[i].get()), "v"(fb));
+      else        asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[i][j]) : "v"(fal[i].get()), "v"(fb));
       __builtin_amdgcn_sched_barrier(0);
-      read(std::integral_constant<int, 0>{});
-      dma_ops(ph_c, std::integral_constant<int, 0>{}, step, kt);
+      static_for<2>([&](auto s_c) {
+        constexpr int sl = decltype(s_c)::value;
+        constexpr int kind = kHalfPlan<D, R, G0>.kind[g][sl], idx = kHalfPlan<D, R, G0>.idx[g][sl];
+        if constexpr (kind == OP_READ) read_op(std::integral_constant<int, idx>{});
+        else if constexpr (kind == OP_DEST) dma_op(ph_c, std::integral_constant<int, 0>{}, std::integral_constant<int, idx>{});
+        else if constexpr (kind == OP_LOAD) dma_op(ph_c, std::integral_constant<int, 1>{}, std::integral_constant<int, idx>{});
+        else if constexpr (kind == OP_DMA)  dma_op(ph_c, std::integral_constant<int, 2>{}, std::integral_constant<int, idx>{});
+      });
       __builtin_amdgcn_sched_barrier(0);
-      mfma(j0 + 1);
-      __builtin_amdgcn_sched_barrier(0);
-      read(std::integral_constant<int, 1>{});
-      dma_ops(ph_c, std::integral_constant<int, 1>{}, step, kt);
-      __builtin_amdgcn_sched_barrier(0);
-    }
+    });
   };
   auto barrier = [&](auto w_c) {
     wait_vm<decltype(w_c)::value>();                     // k-tile kt+1 of this wavefront's loads
@@ -439,26 +499,34 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
     asm volatile("" ::: "memory");
     __builtin_amdgcn_sched_barrier(0);
   };
-  for (int kt = 0; kt < KT; kt += 2) {     // KT is even
-    half(std::integral_constant<int, 0>{}, kt);
+  // two k-tiles, the first of them number 2 Q modulo 4
+  auto two_ktiles = [&](auto q_c) {
+    constexpr int Q = decltype(q_c)::value;
+    half(std::integral_constant<int, 4 * Q + 0>{});
     barrier(std::integral_constant<int, W_EVEN>{});
-    half(std::integral_constant<int, 1>{}, kt);
-    half(std::integral_constant<int, 2>{}, kt + 1);
+    half(std::integral_constant<int, 4 * Q + 1>{});
+    half(std::integral_constant<int, 4 * Q + 2>{});
     barrier(std::integral_constant<int, W_ODD>{});
-    half(std::integral_constant<int, 3>{}, kt + 1);
+    half(std::integral_constant<int, 4 * Q + 3>{});
     cp = cn;
     cn = cn + 1 >= NP ? cn + 1 - NP : cn + 1;
     cm0 = cm1 + 1 >= KT ? cm1 + 1 - KT : cm1 + 1;
     cm1 = cm0 + 1 >= KT ? cm0 + 1 - KT : cm0 + 1;
+  };
+  // four k-tiles per round of the loop, so that every LDS slot is a compile-time constant (KT is even)
+  for (int kt = 0; kt + 4 <= KT; kt += 4) {
+    two_ktiles(std::integral_constant<int, 0>{});
+    two_ktiles(std::integral_constant<int, 1>{});
   }
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  if (KT & 2) two_ktiles(std::integral_constant<int, 0>{});
+  // (the wait states between the last MFMA and the first read of its result: the compiler does
+  // not see the instruction inside the assembly statement)
+  asm volatile("s_nop 15\n\ts_nop 15\n\ts_waitcnt vmcnt(0)" ::: "memory");
   __builtin_amdgcn_s_barrier();            // nobody's clamped reloads still land in LDS
 
   // ---- epilogue -------------------------------------------------------------------------------
   const int R0 = tile_r0 + wr * 128, C0 = tile_c0 + wc * 128;   // origin of this wavefront's sub-tile
-  // Test faults (none in production calls: then this is one scalar compare).  The loop is in
-  // every instantiation: with it the compiler keeps all accumulators in place in the accumulation
-  // registers through the main loop, without it it shuffles hundreds of them per iteration.
+  // Test faults (none in production calls: then this is one scalar compare).
   if (khalf <= 0) {     // (of a split tile: planted into the first half)
     for (int f = 0; f < a.n_faults; ++f) {
       const gecc_fault ft = a.faults[f];
