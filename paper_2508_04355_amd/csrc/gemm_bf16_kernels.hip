@@ -225,14 +225,17 @@ __device__ __forceinline__ void static_for(F&& f) {
 // into M0, then -- behind the next MFMA, which also is the wait state M0 needs -- the load) and
 // its R LDS reads are dealt out one per MFMA, DMA instructions evenly over the half, reads from
 // MFMA number G0 on and over the first four fifths of it (their data is needed when the half ends).
-// With more than 32 of them some MFMAs get two.
+// With more than 32 of them some MFMAs get two.  S further scalar instructions (the bookkeeping
+// of the cyclic k order) go behind MFMAs that have nothing yet, from the end of the half
+// backwards, then next to LDS reads (a read and a scalar instruction together still cost nothing).
 enum { OP_NONE = 0, OP_READ = 1, OP_DEST = 2, OP_LOAD = 3, OP_DMA = 4 /* both parts, with the wait state */ };
 struct HalfPlan {
-  signed char kind[32][2], idx[32][2];
+  signed char kind[32][2], idx[32][2], scalar[32];
 };
-template <int D, int R, int G0>
+template <int D, int R, int G0, int S>
 constexpr HalfPlan make_half_plan() {
   HalfPlan p{};
+  for (int g = 0; g < 32; ++g) p.scalar[g] = -1;
   int sk[80] = {}, si[80] = {}, T = 0;
   int d = 0, r = 0;
   while (d < D || r < R) {   // merge by position: DMA d at (d + 1/2) / D, read r at 4/5 (r + 1/2) / R
@@ -250,10 +253,17 @@ constexpr HalfPlan make_half_plan() {
     p.idx[g][fill[g]] = (signed char)si[k];
     ++fill[g];
   }
+  int left = S;     // scalar instruction number S - left goes ...
+  for (int g = 31; g >= 0 && left > 0; --g)
+    if (fill[g] == 0) { p.scalar[g] = (signed char)(left - 1); --left; }
+  for (int g = 31; g >= 0 && left > 0; --g)
+    if (p.scalar[g] < 0 && fill[g] == 1 && p.kind[g][0] == OP_READ) { p.scalar[g] = (signed char)(left - 1); --left; }
+  for (int g = 31; g >= 0 && left > 0; --g)
+    if (p.scalar[g] < 0) { p.scalar[g] = (signed char)(left - 1); --left; }
   return p;
 }
-template <int D, int R, int G0>
-inline constexpr HalfPlan kHalfPlan = make_half_plan<D, R, G0>();
+template <int D, int R, int G0, int S>
+inline constexpr HalfPlan kHalfPlan = make_half_plan<D, R, G0, S>();
 
 // s_waitcnt vmcnt(N), N a compile-time constant below 64
 template <int N>
@@ -446,6 +456,23 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
 #pragma unroll
   for (int j = 0; j < 8; ++j) ob.fragment(fbe[j], regB, j);
 
+  // The sources of the next two k-tiles' requests, one scalar instruction at a time (x + 1
+  // modulo N as min(x + 1, x + 1 - N) in unsigned arithmetic); they replace cp, cn, cm0, cm1
+  // when the two k-tiles are done
+  unsigned nx0 = 0, nx1 = 0, ncn = 0, ncm0 = 0, ncm1 = 0;
+  constexpr int N_SCALAR = 9;
+  auto scalar_op = [&](auto op_c) {
+    constexpr int op = decltype(op_c)::value;
+    if constexpr (op == 0) nx0 = (unsigned)cn + 1u;
+    else if constexpr (op == 1) nx1 = nx0 - (unsigned)NP;
+    else if constexpr (op == 2) ncn = nx0 < nx1 ? nx0 : nx1;
+    else if constexpr (op == 3) nx0 = (unsigned)cm1 + 1u;
+    else if constexpr (op == 4) nx1 = nx0 - (unsigned)KT;
+    else if constexpr (op == 5) ncm0 = nx0 < nx1 ? nx0 : nx1;
+    else if constexpr (op == 6) nx0 = ncm0 + 1u;
+    else if constexpr (op == 7) nx1 = nx0 - (unsigned)KT;
+    else if constexpr (op == 8) ncm1 = nx0 < nx1 ? nx0 : nx1;
+  };
   auto half = [&](auto ph_c) {
     constexpr int PH8 = decltype(ph_c)::value, PH = PH8 & 3, KT0 = (PH8 >> 2) * 2 + (PH >> 1);   // k-tile mod 4
     constexpr bool SECOND = PH & 1, ODD = (PH >> 1) & 1;
@@ -454,6 +481,7 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
     constexpr int R = SECOND ? 8 * OB + 4 * OA : 4 * OA;
     constexpr int G0 = SECOND ? 0 : 2;   // (1st half: not behind the first MFMAs, or the wait for the previous half's reads takes them along)
     static_assert(2 * D + R <= 64 - 2 * G0, "two instructions per MFMA at most");
+    constexpr int S = PH == 1 ? N_SCALAR : 0;   // the 2nd half of the even k-tile requests nothing: room for the bookkeeping
     // LDS instruction number OP of the half: 2nd half: the 8 B fragments, then A fragments 0..3, of
     // the next k-tile (past the last k-tile this reads a slot nobody filled: in range, never
     // used); 1st half: A fragments 4..7 of this k-tile
@@ -483,12 +511,13 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
       __builtin_amdgcn_sched_barrier(0);
       static_for<2>([&](auto s_c) {
         constexpr int sl = decltype(s_c)::value;
-        constexpr int kind = kHalfPlan<D, R, G0>.kind[g][sl], idx = kHalfPlan<D, R, G0>.idx[g][sl];
+        constexpr int kind = kHalfPlan<D, R, G0, S>.kind[g][sl], idx = kHalfPlan<D, R, G0, S>.idx[g][sl];
         if constexpr (kind == OP_READ) read_op(std::integral_constant<int, idx>{});
         else if constexpr (kind == OP_DEST) dma_op(ph_c, std::integral_constant<int, 0>{}, std::integral_constant<int, idx>{});
         else if constexpr (kind == OP_LOAD) dma_op(ph_c, std::integral_constant<int, 1>{}, std::integral_constant<int, idx>{});
         else if constexpr (kind == OP_DMA)  dma_op(ph_c, std::integral_constant<int, 2>{}, std::integral_constant<int, idx>{});
       });
+      if constexpr (kHalfPlan<D, R, G0, S>.scalar[g] >= 0) scalar_op(std::integral_constant<int, kHalfPlan<D, R, G0, S>.scalar[g]>{});
       __builtin_amdgcn_sched_barrier(0);
     });
   };
@@ -509,9 +538,9 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
     barrier(std::integral_constant<int, W_ODD>{});
     half(std::integral_constant<int, 4 * Q + 3>{});
     cp = cn;
-    cn = cn + 1 >= NP ? cn + 1 - NP : cn + 1;
-    cm0 = cm1 + 1 >= KT ? cm1 + 1 - KT : cm1 + 1;
-    cm1 = cm0 + 1 >= KT ? cm0 + 1 - KT : cm0 + 1;
+    cn = (int)ncn;
+    cm0 = (int)ncm0;
+    cm1 = (int)ncm1;
   };
   // four k-tiles per round of the loop, so that every LDS slot is a compile-time constant (KT is even)
   for (int kt = 0; kt + 4 <= KT; kt += 4) {
