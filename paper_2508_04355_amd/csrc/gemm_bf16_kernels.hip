@@ -262,6 +262,28 @@ constexpr HalfPlan make_half_plan() {
     if (p.scalar[g] < 0) { p.scalar[g] = (signed char)(left - 1); --left; }
   return p;
 }
+// What the kernel relies on: every read and every scalar instruction once and in order of their
+// numbers (the scalar ones depend on each other); every DMA instruction once, its load behind a
+// later MFMA than its destination (or both together, with the wait state), and no other
+// destination in between (there is one M0)
+template <int D, int R, int G0, int S>
+constexpr bool half_plan_ok(const HalfPlan& p) {
+  int next_read = 0, next_scalar = 0, next_dest = 0, next_load = 0;
+  for (int g = 0; g < 32; ++g) {
+    for (int sl = 0; sl < 2; ++sl) {
+      const int k = p.kind[g][sl], i = p.idx[g][sl];
+      if (k == OP_NONE) continue;
+      if (g < G0) return false;
+      if (k == OP_READ) { if (i != next_read) return false; ++next_read; }
+      else if (k == OP_DEST) { if (i != next_dest || next_load != next_dest) return false; ++next_dest; }
+      else if (k == OP_LOAD) { if (i != next_load || next_dest != next_load + 1 || sl != 0 && p.kind[g][0] == OP_DEST) return false; ++next_load; }
+      else if (k == OP_DMA) { if (i != next_dest || next_load != next_dest) return false; ++next_dest; ++next_load; }
+      else return false;
+    }
+    if (p.scalar[g] >= 0) { if (p.scalar[g] != next_scalar) return false; ++next_scalar; }
+  }
+  return next_read == R && next_dest == D && next_load == D && next_scalar == S;
+}
 template <int D, int R, int G0, int S>
 inline constexpr HalfPlan kHalfPlan = make_half_plan<D, R, G0, S>();
 
@@ -482,6 +504,7 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
     constexpr int G0 = SECOND ? 0 : 2;   // (1st half: not behind the first MFMAs, or the wait for the previous half's reads takes them along)
     static_assert(2 * D + R <= 64 - 2 * G0, "two instructions per MFMA at most");
     constexpr int S = PH == 1 ? N_SCALAR : 0;   // the 2nd half of the even k-tile requests nothing: room for the bookkeeping
+    static_assert(half_plan_ok<D, R, G0, S>(kHalfPlan<D, R, G0, S>), "instruction plan of the half");
     // LDS instruction number OP of the half: 2nd half: the 8 B fragments, then A fragments 0..3, of
     // the next k-tile (past the last k-tile this reads a slot nobody filled: in range, never
     // used); 1st half: A fragments 4..7 of this k-tile
