@@ -40,7 +40,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (--gpus 1); the path shards without "
-              "communication (see DESIGN.md), no multi-GPU figure is produced.", file=sys.stderr)
+              "communication, no multi-GPU figure is produced.", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
@@ -124,7 +124,7 @@ def main():
         plan[name] = (faults, [(f.matrix, f.row, f.col) for f in faults], gecc.make_faults(cf, dev))
     times = {name: [] for name in scen}
     good = {name: True for name in scen}
-    for rnd in range(6):            # round 0 untimed: it loads the kernels of the staged calls
+    for rnd in range(6):            # pass 0 untimed: it loads the kernels of the staged calls
         if rnd == 1:                # ... and the chip needs a few products to be back at its steady clock
             for _ in range(args.warmup):
                 ctx.plain_gemm(dA, dB, Cd)
