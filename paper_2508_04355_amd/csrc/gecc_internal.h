@@ -128,6 +128,8 @@ struct GemmArgs {
   int cu_hint;          // compute units to plan the rounds of tiles for (0: ask the device)
   int split_first;      // set by the launcher of the bf16 256 x 256 kernel: first workgroup of the
                         // k-split tail (-1: none)
+  int map_sr, map_sc;   // set by the same launcher: a round of 256 workgroups takes a block of
+                        // map_sr x map_sc tiles (0: the default order)
   // protected product only: P_g = A_P B_P goes to pg_out[b * pg_stride + 0..3], formed by the
   // workgroup of the first tile, which also resets the decoder state of its batch item
   const double* A_par;
