@@ -24,7 +24,7 @@ HBM_PEAK_GBS = 8000.0
 # Memory traffic of the product kernel per launch (bytes), from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE runs, each scaled by what the same counter reads for a 1 GiB copy (factors 2.000 and
 # 1.000); profiles/bench_cfg4-fwd_hbm_traffic.txt.  Workloads not listed: not measured.
-TRAFFIC_BYTES = {"cfg4-fwd": 3.009e9 + 1.004e9}
+TRAFFIC_BYTES = {"cfg4-fwd": 3.078e9 + 1.004e9}
 
 
 def main():
