@@ -748,7 +748,7 @@ hipError_t launch_one(const GemmArgs& a0, hipStream_t st) {
     n_cu = cus;
   }
   const int cus = a.cu_hint > 0 ? a.cu_hint : n_cu;
-  // rounds as blocks of tiles (see tile_of): the squarest of 16 x 16, 32 x 8, 8 x 32 that fits
+  // rounds as blocks of tiles (see tile_of): 16 x 16 or 32 x 8, whichever fits
   // exactly -- where the panels a round of the default order touches (64 tile rows + 4 tile
   // columns) would not fit the 256 MiB memory-side cache; where they do, the default order is as
   // fast or a little faster
@@ -757,7 +757,6 @@ hipError_t launch_one(const GemmArgs& a0, hipStream_t st) {
   if (cus == 256 && a.batch == 1 && default_round_bytes > ((int64_t)192 << 20)) {
     if (ntm % 16 == 0 && ntn % 16 == 0) { a.map_sr = 16; a.map_sc = 16; }
     else if (ntm % 32 == 0 && ntn % 8 == 0) { a.map_sr = 32; a.map_sc = 8; }
-    else if (ntm % 8 == 0 && ntn % 32 == 0) { a.map_sr = 8; a.map_sc = 32; }
   }
   const int tail = ntiles % cus;
   a.split_first = -1;

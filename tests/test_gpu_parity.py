@@ -524,6 +524,34 @@ def test_cfg5_batched_two_errors_each():
             assert [(e[0], e[1], e[2]) for e in rep.errors()] == [(e[0], e[1], e[2]) for e in eff]
 
 
+def test_rounds_as_32_by_8_blocks_of_tiles():
+    """A product whose default round of tiles would touch more operand panels than the memory-side
+    cache holds, with a tile grid of 32 x 8: the launcher hands the tiles out in blocks of 32 x 8
+    (cfg4-dgrad, in the test below, takes 16 x 16 blocks).  Sampled rows and columns against the oracle."""
+    n, k, m = 8192, 11264, 2048
+    rng = inputs.rng_for(95, 0)
+    faults = [inputs.Fault(MAT_C, 8000, 2047, 41.0)]
+    A, B, A2, B2, cf, eff = _trial(rng, n, k, m, "bf16", ("normal", 1.0), ("normal", 0.02), faults)
+    tau = gecc.noise_thresholds(n, k, m, 1.0, 0.02)
+    cfb = [(0,) + c for c in cf]
+    g = H.run_gpu(A, B, A2, B2, cfb, tau, "bf16", 0, 0)
+    rep = g.reports[0]
+    assert rep.status == gecc.CORRECTED
+    assert [(e[0], e[1], e[2]) for e in rep.errors()] == [(e[0], e[1], e[2]) for e in eff]
+    AP, BP = oc.encode_a(A), oc.encode_b(B)
+    rows = sorted({0, 255, 256, 4095, 4096, 8000, n - 1})
+    cols = sorted({0, 255, 256, 1023, 1024, m - 1})
+    R = oc.encoded_product(A[rows], AP, B, BP)
+    scale = np.abs(R[:len(rows), :m]).max()
+    assert np.abs(g.C[0][rows] - R[:len(rows), :m]).max() / scale <= 1e-5
+    Ccols = oc.encoded_product(A, AP, B[:, cols], BP)[:n, :len(cols)]
+    assert np.abs(g.C[0][:, cols] - Ccols).max() / scale <= 1e-5
+    cp = g.C_par[0]
+    assert np.allclose(cp[2 * n:2 * n + m], R[len(rows), :m], rtol=1e-10, atol=1e-12 * scale * n)
+    # every tile was written exactly once: no element of C kept the NaN it was filled with
+    assert not np.isnan(g.C[0]).any()
+
+
 # ---- configuration 4 at full size: sampled outputs and invariants -----------------------------
 @pytest.mark.parametrize("wname", ["cfg4-fwd", "cfg4-dgrad", "cfg4-wgrad"])
 def test_cfg4_full_size_sampled(wname):
