@@ -301,16 +301,23 @@ __global__ __launch_bounds__(THREADS) void partials_kernel(PartialArgs a) {
   __shared__ float red_row[2][128][33];
   __shared__ float red_col[2][8][128];
   float cs[4] = {0.f, 0.f, 0.f, 0.f}, cw[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll 4
+  // the kernel is a stream over C: all 16 loads of a thread are issued before the first is used
+  // (rows past the end are clamped, not branched on, and count as zero below)
+  float4 pre[16];
+  if (vec) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+      pre[r] = *reinterpret_cast<const float4*>(C + (int64_t)min(tile_r0 + rg * 16 + r, a.n - 1) * a.ldc + gj);
+  }
+#pragma unroll
   for (int r = 0; r < 16; ++r) {
     const int rl = rg * 16 + r, gi = tile_r0 + rl;
     float x[4] = {0.f, 0.f, 0.f, 0.f};
     if (gi < a.n) {
-      const float* src = C + (int64_t)gi * a.ldc + gj;
       if (vec) {
-        const float4 v = *reinterpret_cast<const float4*>(src);
-        x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
+        x[0] = pre[r].x; x[1] = pre[r].y; x[2] = pre[r].z; x[3] = pre[r].w;
       } else {
+        const float* src = C + (int64_t)gi * a.ldc + gj;
         for (int e = 0; e < 4; ++e) if (gj + e < a.m) x[e] = src[e];
       }
     }
