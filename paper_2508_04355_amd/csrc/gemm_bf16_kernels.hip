@@ -276,7 +276,7 @@ constexpr bool half_plan_ok(const HalfPlan& p) {
       if (g < G0) return false;
       if (k == OP_READ) { if (i != next_read) return false; ++next_read; }
       else if (k == OP_DEST) { if (i != next_dest || next_load != next_dest) return false; ++next_dest; }
-      else if (k == OP_LOAD) { if (i != next_load || next_dest != next_load + 1 || sl != 0 && p.kind[g][0] == OP_DEST) return false; ++next_load; }
+      else if (k == OP_LOAD) { if (i != next_load || next_dest != next_load + 1 || (sl != 0 && p.kind[g][0] == OP_DEST)) return false; ++next_load; }
       else if (k == OP_DMA) { if (i != next_dest || next_load != next_dest) return false; ++next_dest; ++next_load; }
       else return false;
     }
