@@ -54,6 +54,8 @@ enum {
   GECC_ERR_ARG = -1,       /* null pointer, non-positive size, bad enum, bad leading dim */
   GECC_ERR_WORKSPACE = -2, /* workspace missing or too small                             */
   GECC_ERR_HIP = -3,       /* a HIP runtime call failed (launch, copy)                   */
+  GECC_ERR_SCRATCH = -5,   /* gecc_protected_gemm_static: the problem needs more scratch than
+                              GECC_STATIC_SCRATCH_BYTES                                   */
   GECC_ERR_ALIGN = -4      /* a device pointer is not aligned to its element type (A, B: 2 or
                               4 bytes; C: 4; parity buffers: 8; workspace: 256).  Operands
                               whose base and rows are 16-byte aligned (lda/ldb multiples of 8
@@ -191,6 +193,22 @@ int gecc_correct(gecc_ctx* ctx, void* dev_A, const double* dev_A_par, void* dev_
 int gecc_protected_gemm(gecc_ctx* ctx, void* dev_A, void* dev_B, float* dev_C, double* dev_A_par,
                         double* dev_B_par, double* dev_C_par, gecc_report* dev_report,
                         void* stream);
+
+/* For callers that cannot allocate device memory or hand a workspace over (code under HIP graph
+   capture, tight serving loops, harnesses that forbid hipMalloc): gecc_protected_gemm on a scratch
+   buffer that lives inside the library, a static device array of GECC_STATIC_SCRATCH_BYTES per GPU,
+   held until the process ends.  Needs no gecc_set_workspace and calls no allocating routine.
+   Returns GECC_ERR_SCRATCH, before anything is enqueued, when gecc_workspace_bytes(ctx) exceeds
+   GECC_STATIC_SCRATCH_BYTES (a 16384 x 4096 x 14336 product needs 45 MiB in any storage layout,
+   256 products of 512^3 need 37 MiB).  All calls on one GPU share that GPU's array, whatever their context:
+   two such calls that overlap in time on one GPU race; calls in stream order on one stream are
+   safe, and nothing has to be cleared between them.  The fused verification state lives in that
+   array too, so gecc_syndromes_to_host does not see this call's syndromes.  The device current at
+   the time of the call must be the one `stream` belongs to. */
+#define GECC_STATIC_SCRATCH_BYTES (48u << 20)
+int gecc_protected_gemm_static(gecc_ctx* ctx, void* dev_A, void* dev_B, float* dev_C,
+                               double* dev_A_par, double* dev_B_par, double* dev_C_par,
+                               gecc_report* dev_report, void* stream);
 
 /* The recomputation Section V asks for when a pattern is beyond the code ("needs to be
    recalculated"): encode_a, encode_b once, then multiply, verify(fused), correct and a read-back

@@ -1,6 +1,7 @@
 // C ABI of libgecc: argument checking, workspace layout and the stream-ordered launch
 // sequences.  Host code only; all arithmetic of the path runs in the kernels.
 #include <cstdlib>
+#include <mutex>
 #include <new>
 #include "gecc_internal.h"
 
@@ -510,6 +511,53 @@ int gecc_protected_gemm_retry(gecc_ctx* ctx, void* dev_A, void* dev_B, float* de
   return GECC_OK;
 }
 
+namespace {
+
+// Scratch of gecc_protected_gemm_static: one array per GPU, placed by the code-object loader, held
+// until the process ends.  In host code the name is only a handle for hipGetSymbolAddress; the
+// device address it yields (one per device) is what kernels and copies get.
+static __device__ __align__(256) unsigned char scratch[GECC_STATIC_SCRATCH_BYTES];
+
+constexpr int MAX_DEVICES = 64;
+std::mutex scratch_mutex;
+char* scratch_addr[MAX_DEVICES] = {};
+
+// device address of `scratch` on the current device, looked up once per device
+int static_scratch(char** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return GECC_ERR_HIP;
+  std::lock_guard<std::mutex> lock(scratch_mutex);
+  if (!scratch_addr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return GECC_ERR_HIP;
+    scratch_addr[dev] = static_cast<char*>(p);
+  }
+  *out = scratch_addr[dev];
+  return GECC_OK;
+}
+
+}  // namespace
+
+int gecc_protected_gemm_static(gecc_ctx* ctx, void* dev_A, void* dev_B, float* dev_C, double* dev_A_par,
+                               double* dev_B_par, double* dev_C_par, gecc_report* dev_report,
+                               void* stream) {
+  if (!ctx || !dev_A || !dev_B || !dev_C || !dev_A_par || !dev_B_par || !dev_C_par || !dev_report)
+    return GECC_ERR_ARG;
+  if (ctx->lay.total > (size_t)GECC_STATIC_SCRATCH_BYTES) return GECC_ERR_SCRATCH;
+  char* ws = nullptr;
+  int rc = static_scratch(&ws);
+  if (rc) return rc;
+  // the context's own workspace (if any) is left alone: this call runs on the static one
+  char* const keep_ws = ctx->ws;
+  const size_t keep_bytes = ctx->ws_bytes;
+  ctx->ws = ws;
+  ctx->ws_bytes = GECC_STATIC_SCRATCH_BYTES;
+  rc = gecc_protected_gemm(ctx, dev_A, dev_B, dev_C, dev_A_par, dev_B_par, dev_C_par, dev_report, stream);
+  ctx->ws = keep_ws;
+  ctx->ws_bytes = keep_bytes;
+  return rc;
+}
+
 int gecc_plain_gemm(gecc_ctx* ctx, const void* dev_A, const void* dev_B, float* dev_C, void* stream) {
   if (!ctx || !dev_A || !dev_B || !dev_C) return GECC_ERR_ARG;
   if (!aligned_to(dev_A, elem_size(ctx->p.dtype)) || !aligned_to(dev_B, elem_size(ctx->p.dtype)) ||
@@ -548,6 +596,8 @@ const char* gecc_strerror(int code) {
     case GECC_ERR_WORKSPACE: return "workspace missing or too small";
     case GECC_ERR_HIP: return "HIP runtime error";
     case GECC_ERR_ALIGN: return "pointer or leading dimension breaks the alignment rule";
+    case GECC_ERR_SCRATCH: return "problem needs more scratch than the library's static buffer holds "
+                                  "(GECC_STATIC_SCRATCH_BYTES); use gecc_set_workspace and gecc_protected_gemm";
     default: return "unknown error code";
   }
 }

@@ -53,6 +53,7 @@ _lib = None
 _SYMBOLS = ["gecc_create", "gecc_destroy", "gecc_workspace_bytes", "gecc_set_workspace",
             "gecc_a_par_len", "gecc_b_par_len", "gecc_c_par_len", "gecc_encode_a", "gecc_encode_b",
             "gecc_multiply", "gecc_verify", "gecc_correct", "gecc_protected_gemm", "gecc_protected_gemm_retry",
+            "gecc_protected_gemm_static",
             "gecc_plain_gemm",
             "gecc_report_to_host", "gecc_syndromes_to_host", "gecc_timing_enable", "gecc_timing_read",
             "gecc_strerror"]
@@ -83,6 +84,7 @@ def lib():
     L.gecc_verify.argtypes = [vp, vp, vp, vp, i32, vp]
     L.gecc_correct.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp]
     L.gecc_protected_gemm.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    L.gecc_protected_gemm_static.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp]
     L.gecc_protected_gemm_retry.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, C.POINTER(Report), i32, vp, i32,
                                             C.POINTER(i32), vp]
     L.gecc_plain_gemm.argtypes = [vp, vp, vp, vp, vp]
@@ -209,6 +211,11 @@ class Context:
     def protected_gemm(self, A, B, Cmat, A_par, B_par, C_par, report):
         _check(lib().gecc_protected_gemm(self._h, _ptr(A), _ptr(B), _ptr(Cmat), _ptr(A_par), _ptr(B_par),
                                          _ptr(C_par), _ptr(report), _stream()))
+
+    def protected_gemm_static(self, A, B, Cmat, A_par, B_par, C_par, report):
+        """protected_gemm on the library's static scratch array (no workspace, no allocation)."""
+        _check(lib().gecc_protected_gemm_static(self._h, _ptr(A), _ptr(B), _ptr(Cmat), _ptr(A_par),
+                                                _ptr(B_par), _ptr(C_par), _ptr(report), _stream()))
 
     def protected_gemm_retry(self, A, B, Cmat, A_par, B_par, C_par, report, max_retries=1, faults=None, n_faults=0):
         """protected_gemm with recomputation on UNCORRECTABLE (waits for the stream after every
