@@ -15,7 +15,7 @@ What follows the paper directly
                                 blocks C, P_r, P_c, P_g.
   * syndromes / detect       -- Section V step 1, the four threshold tests.
   * d0_correct               -- Section V step 2 (s = 1 rule, 2x2 system for
-                                s = 2, "without loss of generality s <= t").
+                                s = 2; stated for s <= t, s > t is its mirror image).
   * known_lines_correct      -- Theorem 2 and its proof (Appendix B): errors in
                                 any number of columns are corrected from the
                                 column parities once they are confined to at
@@ -37,9 +37,9 @@ the design notes of the repository):
   * operand errors (E1/E2 of Section II-A) hit the data part of A or B
     after the parity rows/columns were formed and before the product reads
     them, so every product term sees the same corrupted symbol;
-  * completion D1 (operand audit) -- the paper asserts that operand errors
-    "can be traced back to errors in C" and reports 100 % for its scenarios
-    a, b, d, e without printing a locating rule.  Because a corrupted a_il
+  * completion D1 (operand audit) -- Section II-A reduces operand errors to
+    the errors they cause in C, and Section VI reports 100 % for its scenarios
+    a, b, d, e, without a locating rule being given.  Because a corrupted a_il
     also enters row i's own two parity symbols, the row syndromes are blind
     to it; D1 re-forms the operand parities, diffs them with the stored
     ones (each column of A-bar is a two-parity codeword, Section III),
@@ -56,11 +56,12 @@ the design notes of the repository):
     plain second pass.
   * a syndrome is a difference of sums of computed symbols, so in any
     finite-precision product its own rounding error grows with its magnitude
-    (Section V: corrected symbols deviate "solely" by rounding); when an
+    (Section V closes on the remark that corrected symbols are off by rounding
+    only); when an
     estimate is verified, every syndrome y is therefore trusted to
     tau + rel * |y| instead of tau.  Detection itself uses tau alone, and
     rel = 0 gives the plain rule.
-  * Theorem 2 asks for the rows (columns) of the errors to be "known"; the
+  * Theorem 2 presupposes that the rows (columns) of the errors are known; the
     only knowledge the decoder has is Section V step 1, so the at most two
     flagged rows are taken as the known rows when three or more columns are
     flagged (and the other way round).  A row whose own two syndromes vanish
@@ -70,6 +71,10 @@ the design notes of the repository):
     (on what the repair leaves, or on the whole pattern when the operands
     are intact): a wrong symbol of A a few rows from a known row would
     otherwise be taken for a row full of small errors of C.
+  * a syndrome or a parity difference that is NaN or infinite counts as outside
+    its threshold (Section V step 1 clears a line only when its test holds);
+    a pattern with such a value is UNCORRECTABLE: subtracting an estimate
+    cannot restore the symbol, the product has to be computed again.
   * the located-error list of a result is complete here; the library's
     report carries the first MAX_REPORTED entries and the total.
   * for s = t = 2 the 2x2 systems are first evaluated under the two sparse
@@ -219,10 +224,21 @@ def global_syndromes(Cbar):
 
 def detect(r1, r2, q1, q2, tau):
     """E_r, E_t of Section V step 1 (a line is flagged if either test fails).
-    tau: Thresholds (one number per family) or LineThresholds (per-line arrays)."""
-    Er = np.nonzero((np.abs(r1) > tau.r1) | (np.abs(r2) > tau.r2))[0]
-    Et = np.nonzero((np.abs(q1) > tau.q1) | (np.abs(q2) > tau.q2))[0]
+    tau: Thresholds (one number per family) or LineThresholds (per-line arrays).
+
+    Section V clears the product when |sum - parity| <= delta holds for every line and
+    puts a line into E_r / E_t otherwise.  A line is therefore flagged when its
+    syndrome is *not* inside the threshold, which also holds for a syndrome that is
+    not a number (a symbol of C that became NaN or infinite)."""
+    Er = np.nonzero(~(np.abs(r1) <= tau.r1) | ~(np.abs(r2) <= tau.r2))[0]
+    Et = np.nonzero(~(np.abs(q1) <= tau.q1) | ~(np.abs(q2) <= tau.q2))[0]
     return [int(i) for i in Er], [int(j) for j in Et]
+
+
+def all_finite(*vectors):
+    """False when a syndrome (or parity difference) is NaN or infinite: Section V's subtraction
+    cannot restore such a symbol, so the pattern is handed back for recomputation."""
+    return all(bool(np.all(np.isfinite(v))) for v in vectors)
 
 
 def _residual_ok(est, r1, r2, q1, q2, Er, Et, tau):
@@ -355,6 +371,8 @@ def audit_a(A, AP, tau_op):
     u1 = cur[0] - AP[0]
     u2 = cur[1] - AP[1]
     found = []
+    if not all_finite(u1, u2):
+        return False, []
     for l in np.nonzero((np.abs(u1) > tau_op) | (np.abs(u2) > tau_op))[0]:
         if not abs(u1[l]) > tau_op:
             return False, []
@@ -373,6 +391,8 @@ def audit_b(B, BP, tau_op):
     u1 = cur[:, 0] - BP[:, 0]
     u2 = cur[:, 1] - BP[:, 1]
     found = []
+    if not all_finite(u1, u2):
+        return False, []
     for l in np.nonzero((np.abs(u1) > tau_op) | (np.abs(u2) > tau_op))[0]:
         if not abs(u1[l]) > tau_op:
             return False, []
@@ -391,7 +411,7 @@ def decode(Cbar, A, AP, B, BP, tau):
     A, B : operands as the product read them (possibly corrupted)
     AP,BP: parities formed before the corruption
     On UNCORRECTABLE the returned buffers hold whatever the attempt left
-    behind; a caller has to recompute (Section V: "needs to be recalculated").
+    behind; a caller has to compute the product again (Section V step 1, last case).
     """
     Cbar = np.array(Cbar, dtype=np.float64)
     A = np.array(A, dtype=np.float64)
@@ -408,6 +428,8 @@ def decode(Cbar, A, AP, B, BP, tau):
 
     if s0 == 0 and t0 == 0:
         return done(CLEAN, [])
+    if not all_finite(r1, r2, q1, q2):
+        return done(UNCORRECTABLE, [])
 
     fix = None
     if 1 <= s0 <= 2 and 1 <= t0 <= 2:
@@ -455,6 +477,8 @@ def decode(Cbar, A, AP, B, BP, tau):
     s, t = len(Er), len(Et)
     if s == 0 and t == 0:
         return done(CORRECTED, errs)
+    if not all_finite(r1, r2, q1, q2):
+        return done(UNCORRECTABLE, [])
     fix = None
     if 1 <= s <= 2 and 1 <= t <= 2:
         fix = d0_correct(r1, r2, q1, q2, Er, Et, tau2)

@@ -558,3 +558,241 @@ def test_lines_touched_by_an_operand_repair_get_their_allowance_and_only_they():
     Cbar3[i + 3, 2] += 1e-4
     assert 1e-4 < 4 * rho * abs(e * B[l, 2])
     assert oc.decode(Cbar3, A2, AP, B, BP, Thresholds(**base, rep=4 * rho / np.sqrt(k))).status == UNCORRECTABLE
+
+
+# ---- pin: the incremental evaluation (oracle/incremental.py) is the full oracle -----------------
+def _as_trial(A, B, placed):
+    """placements with offsets -> the incremental oracle's arguments (stored values for A, B)"""
+    af = [(r, c, A[r, c] + e) for (mt, r, c, e) in placed if mt == MAT_A]
+    bf = [(r, c, B[r, c] + e) for (mt, r, c, e) in placed if mt == MAT_B]
+    cf = [(r, c, e) for (mt, r, c, e) in placed if mt == MAT_C]
+    return af, bf, cf
+
+
+def _same_outcome(inc_res, full_res, clean_scale, tag):
+    assert inc_res.status == full_res.status, tag
+    assert (inc_res.s, inc_res.t) == (full_res.s, full_res.t), tag
+    assert [e[:3] for e in inc_res.errors] == [e[:3] for e in full_res.errors], tag
+    for x, y in zip(inc_res.errors, full_res.errors):
+        assert abs(x[3] - y[3]) <= 1e-9 * max(1.0, abs(y[3])), tag
+    assert np.allclose(inc_res.max_abs_synd, full_res.max_abs_synd, rtol=1e-9, atol=1e-9 * clean_scale), tag
+    if full_res.status != UNCORRECTABLE:
+        assert np.max(np.abs(inc_res.Cbar - full_res.Cbar)) <= 1e-9 * clean_scale, tag
+
+
+@pytest.mark.parametrize("n,k,m,mags", [(3, 3, 3, (1.0, 1.0)), (4, 2, 3, (3.0, -5.0)), (3, 4, 5, (-1.0, 4.0))])
+def test_incremental_oracle_equals_the_full_one_on_every_single_and_pair_placement(n, k, m, mags):
+    """Linearity of the syndromes (Section V step 1) and of the product in each operand: a trial
+    evaluated as changes of rows, columns and symbols of the clean C-bar has to end exactly where
+    the from-scratch evaluation ends, for every placement of one and of two faults over A, B, C,
+    the pairs beyond the code included."""
+    from oracle.incremental import IncrementalOracle
+    A, B = int_mats(41 + n + k + m, n, k, m)
+    AP, BP = oc.encode_a(A), oc.encode_b(B)
+    inc = IncrementalOracle(A, B, TAU0)
+    scale = np.abs(inc.clean).max()
+    cases = [[p + (mags[0],)] for p in _placements(n, k, m)] + \
+            [[p1 + (mags[0],), p2 + (mags[1],)] for p1, p2 in itertools.combinations(_placements(n, k, m), 2)]
+    for placed in cases:
+        full = _run_faults(A, B, AP, BP, placed)
+        got = inc.trial(*_as_trial(A, B, placed), keep_cbar=True)
+        _same_outcome(got, full, scale, placed)
+        if full.status == CORRECTED and not (len(placed) == 2 and _beyond_code(placed[0], placed[1])):
+            assert got.left_in_cbar <= 1e-9 * scale and got.operands_restored
+        # a trial leaves nothing behind
+        assert np.array_equal(inc.W, inc.clean) and np.array_equal(inc.A, A) and np.array_equal(inc.B, B)
+    assert inc.trial([], [], []).status == CLEAN
+
+
+def test_incremental_oracle_equals_the_full_one_on_real_operands_with_rounding_noise():
+    """Real-valued operands, thresholds above the rounding level, second-pass allowances in use,
+    0 to 3 faults of any kind, a same-index A+B pair (cross term) and a pattern of Theorem 2."""
+    from oracle.incremental import IncrementalOracle
+    n, k, m = 40, 24, 36
+    rng = np.random.default_rng(2024)
+    A, B = rng.standard_normal((n, k)), rng.standard_normal((k, m)) * 0.02
+    tau = Thresholds(1e-7, 1e-5, 1e-7, 1e-5, 0.0, rep=1e-9, rel=1e-9)
+    inc = IncrementalOracle(A, B, tau)
+    scale = np.abs(inc.clean[:n, :m]).max()
+    P = _placements(n, k, m)
+    cases = []
+    for t in range(300):
+        cnt = int(rng.integers(0, 4))
+        idx = rng.choice(len(P), cnt, replace=False)
+        cases.append([P[x] + (float(np.exp(rng.uniform(np.log(1e-3), np.log(1e3))) * rng.choice([-1, 1])),) for x in idx])
+    cases.append([(MAT_A, 3, 7, 2.5), (MAT_B, 7, 30, -40.0)])                      # same l: cross term
+    cases.append([(MAT_C, 5, j, 1.0 + j) for j in range(0, m, 3)])                 # Theorem 2, one row
+    cases.append([(MAT_A, 9, 2, 3.0)] + [(MAT_C, 9, j, 0.5) for j in (1, 4, 8)])   # audit, then the rest in its row
+    seen = set()
+    for placed in cases:
+        A2, B2, cf = A.copy(), B.copy(), []
+        for (mt, r, c, e) in placed:
+            if mt == MAT_A: A2[r, c] += e
+            elif mt == MAT_B: B2[r, c] += e
+            else: cf.append((r, c, e))
+        full = oc.protected_gemm(A, B, A2, B2, cf, tau)
+        af = [(r, c, A2[r, c]) for (mt, r, c, e) in placed if mt == MAT_A]
+        bf = [(r, c, B2[r, c]) for (mt, r, c, e) in placed if mt == MAT_B]
+        got = inc.trial(af, bf, cf, keep_cbar=True)
+        _same_outcome(got, full, scale, placed)
+        seen.add(full.status)
+    assert seen == {CLEAN, CORRECTED, UNCORRECTABLE}
+
+
+# ---- pin: the scheme is symmetric under transposition (C^T = B^T A^T swaps the roles of A and B, of
+#      rows and columns, of r and q): every B-side branch of the decoder has to mirror its A-side twin
+def _mirror(res):
+    out = []
+    for (mt, r, c, x) in res.errors:
+        out.append((MAT_B, c, r, x) if mt == MAT_A else (MAT_A, c, r, x) if mt == MAT_B else (MAT_C, c, r, x))
+    return sorted(out)
+
+
+def test_decoder_is_symmetric_under_transposition():
+    n, k, m = 14, 9, 11
+    rng = np.random.default_rng(5)
+    A, B = rng.standard_normal((n, k)), rng.standard_normal((k, m))
+    AP, BP = oc.encode_a(A), oc.encode_b(B)
+    tau = Thresholds(r1=1e-8, r2=2e-8, q1=3e-8, q2=4e-8, op=0.0, rep=1e-7, rel=1e-9)
+    tau_t = Thresholds(r1=tau.q1, r2=tau.q2, q1=tau.r1, q2=tau.r2, op=0.0, rep=tau.rep, rel=tau.rel)
+    P = _placements(n, k, m)
+    statuses = set()
+    for t in range(400):
+        cnt = int(rng.integers(1, 4))
+        placed = [P[x] + (float(rng.uniform(1, 50) * rng.choice([-1, 1])),) for x in rng.choice(len(P), cnt, replace=False)]
+        A2, B2, cf = A.copy(), B.copy(), []
+        for (mt, r, c, e) in placed:
+            if mt == MAT_A: A2[r, c] += e
+            elif mt == MAT_B: B2[r, c] += e
+            else: cf.append((r, c, e))
+        Cbar = oc.encoded_product(A2, AP, B2, BP)
+        oc.inject_c(Cbar, cf)
+        # rounding left behind by a finite-precision product: proportional to the corrupted terms
+        for (mt, r, c, e) in placed:
+            if mt == MAT_A: Cbar[r, :m] += 1e-8 * np.abs(e * B[c, :]) * rng.choice([-1.0, 1.0], m)
+            if mt == MAT_B: Cbar[:n, c] += 1e-8 * np.abs(A[:, r] * e) * rng.choice([-1.0, 1.0], n)
+        res = oc.decode(Cbar, A2, AP, B2, BP, tau)
+        res_t = oc.decode(Cbar.T, B2.T, BP.T, A2.T, AP.T, tau_t)
+        assert res.status == res_t.status, placed
+        assert (res.s, res.t) == (res_t.t, res_t.s)
+        statuses.add(res.status)
+        if res.status == UNCORRECTABLE:
+            continue
+        mirrored = _mirror(res_t)
+        assert [e[:3] for e in mirrored] == [e[:3] for e in res.errors], placed
+        # (values agree to the planted noise, not better: with s = t the rule reads the columns, and
+        # the columns of the transposed problem are the rows of this one, whose sums hold other noise)
+        assert np.allclose([e[3] for e in mirrored], [e[3] for e in res.errors], rtol=1e-6, atol=2e-5)
+        assert np.allclose(res.Cbar, res_t.Cbar.T, rtol=0, atol=2e-5)
+        assert np.allclose(res.A, res_t.B.T, atol=1e-9) and np.allclose(res.B, res_t.A.T, atol=1e-9)
+    assert statuses == {CORRECTED, UNCORRECTABLE}
+
+
+def test_lines_touched_by_a_repair_of_B_get_their_allowance_and_only_they():
+    """Mirror image of the pin for A: after a wrong symbol b_lj is repaired, column j of C-bar keeps
+    the rounding of the corrupted terms a_il e; the allowance belongs to that column and, symbol by
+    symbol in proportion to |a_il e|, to every row -- and to nothing else."""
+    n, k, m = 20, 16, 24
+    rng = np.random.default_rng(38)
+    A, B = rng.standard_normal((n, k)), rng.standard_normal((k, m))
+    AP, BP = oc.encode_a(A), oc.encode_b(B)
+    l, j, e, rho = 5, 7, 1000.0, 1e-6
+    B2 = B.copy(); B2[l, j] += e
+    Cbar = oc.encoded_product(A, AP, B2, BP)
+    Cbar[:n, j] += rho * np.abs(A[:, l] * e) * rng.choice([-1.0, 1.0], n)
+    base = dict(r1=1e-9, r2=1e-9, q1=1e-9, q2=1e-9, op=0.0)
+    with_rep = oc.decode(Cbar, A, AP, B2, BP, Thresholds(**base, rep=4 * rho / np.sqrt(k)))
+    assert with_rep.status == CORRECTED and [x[:3] for x in with_rep.errors] == [(MAT_B, l, j)]
+    assert np.allclose(with_rep.B, B, rtol=0, atol=1e-9)
+    without = oc.decode(Cbar, A, AP, B2, BP, Thresholds(**base, rep=0.0))
+    assert without.status == UNCORRECTABLE or len(without.errors) > 1
+    # an error of C in another column, above its row's allowance: found beside the operand error
+    Cbar2 = Cbar.copy(); Cbar2[2, j + 3] += 1.0
+    res = oc.decode(Cbar2, A, AP, B2, BP, Thresholds(**base, rep=4 * rho / np.sqrt(k)))
+    assert res.status == CORRECTED and [x[:3] for x in res.errors] == [(MAT_B, l, j), (MAT_C, 2, j + 3)]
+    # below it: its own column (not widened) is flagged, no row is: nothing to pair it with
+    Cbar3 = Cbar.copy(); Cbar3[2, j + 3] += 1e-4
+    assert 1e-4 < 4 * rho * abs(A[2, l] * e)
+    assert oc.decode(Cbar3, A, AP, B2, BP, Thresholds(**base, rep=4 * rho / np.sqrt(k))).status == UNCORRECTABLE
+    # the allowance of column j itself is the root-sum-square over the column, plain and weighted: a
+    # residual in that column just inside it passes, the same residual with half the allowance does not
+    foot = A[:, l] * e
+    inside = 0.9 * 4 * rho * np.sqrt(np.sum(foot ** 2))
+    Cbar4 = oc.encoded_product(A, AP, B2, BP)
+    Cbar4[n, j] -= inside                                   # moves q1_j only (a parity symbol of that column)
+    ok = oc.decode(Cbar4, A, AP, B2, BP, Thresholds(**base, rep=4 * rho / np.sqrt(k)))
+    assert ok.status == CORRECTED and [x[:3] for x in ok.errors] == [(MAT_B, l, j)]
+    assert oc.decode(Cbar4, A, AP, B2, BP, Thresholds(**base, rep=2 * rho / np.sqrt(k))).status == UNCORRECTABLE
+
+
+def test_an_audit_accepts_eight_operand_errors_and_gives_up_at_nine():
+    """MAX_REPORTED: eight wrong operand symbols in eight different lines are all repaired; a ninth makes
+    the pattern UNCORRECTABLE (the library's report has eight slots)."""
+    n, k, m = 12, 12, 12
+    A, B = int_mats(99, n, k, m)
+    AP, BP = oc.encode_a(A), oc.encode_b(B)
+    spots = [(MAT_A, i, i, 3.0 + i) for i in range(5)] + [(MAT_B, l, (l + 2) % m, -2.0 - l) for l in range(5, 9)]
+    res = _run_faults(A, B, AP, BP, spots[:8])
+    assert res.status == CORRECTED and res.errors == sorted(spots[:8])
+    assert np.array_equal(res.A, A) and np.array_equal(res.B, B)
+    assert _run_faults(A, B, AP, BP, spots[:9]).status == UNCORRECTABLE
+    assert oc.MAX_REPORTED == 8
+
+
+def test_audit_ratio_tolerance_is_a_quarter_from_both_sides():
+    """A line whose weighted/plain ratio misses every integer by 1/4 or more holds more than one wrong
+    symbol; within 1/4 it is read as one.  Two errors in one column of A at rows 3 and 4 (1-based)
+    with offsets (1-f, f) give the ratio 3 + f exactly."""
+    n, k, m = 6, 3, 4
+    A, B = int_mats(5, n, k, m)
+    AP = oc.encode_a(A)
+    for f, want in ((0.2421875, (True, 2)), (0.2578125, (False, None)), (0.7421875, (False, None)), (0.7578125, (True, 3))):
+        A2 = A.copy(); A2[2, 1] += 1.0 - f; A2[3, 1] += f       # dyadic fractions: every sum is exact
+        ok, found = oc.audit_a(A2, AP, 0.0)
+        assert ok == want[0], f
+        if ok:
+            assert found == [(want[1], 1, 1.0)]
+    BP = oc.encode_b(B)
+    for f, want in ((0.2421875, (True, 1)), (0.2578125, (False, None)), (0.7578125, (True, 2))):
+        B2 = B.copy(); B2[0, 1] += 1.0 - f; B2[0, 2] += f
+        ok, found = oc.audit_b(B2, BP, 0.0)
+        assert ok == want[0], f
+        if ok:
+            assert found == [(0, want[1], 1.0)]
+    # a ratio that rounds to a row outside 1..n is refused as well
+    A2 = A.copy(); A2[0, 0] += 2.0; A2[1, 0] -= 1.0             # ratio (2*1 - 1*2) / 1 = 0
+    assert oc.audit_a(A2, AP, 0.0)[0] is False
+
+
+def test_a_syndrome_equal_to_its_threshold_is_not_flagged():
+    """Section V step 1 clears a line whose |sum - parity| is <= delta: equality is inside."""
+    z = np.zeros(3)
+    tau = Thresholds(0.5, 2.0, 0.25, 4.0)
+    r1 = np.array([0.5, -0.5, np.nextafter(0.5, 1.0)])
+    assert oc.detect(r1, z, z, z, tau) == ([2], [])
+    assert oc.detect(z, np.array([2.0, -np.nextafter(2.0, 3.0), 0.0]), z, z, tau) == ([1], [])
+    assert oc.detect(z, z, np.array([0.25, 0.25, -0.25]), np.array([4.0, -4.0, np.nextafter(4.0, 5.0)]), tau) == ([], [2])
+
+
+def test_a_symbol_that_is_not_a_number_is_detected_and_handed_back():
+    """A NaN (or infinite) symbol of C makes its row and column syndromes NaN; `not <= delta` flags
+    them, and since no subtraction restores such a symbol the product has to be computed again.  The
+    same for an operand symbol (a whole row of C turns NaN)."""
+    n, k, m = 6, 4, 5
+    A, B = int_mats(3, n, k, m)
+    AP, BP = oc.encode_a(A), oc.encode_b(B)
+    for bad in (np.nan, np.inf, -np.inf):
+        Cbar = oc.encoded_product(A, AP, B, BP)
+        Cbar[2, 3] = bad
+        r1, r2, q1, q2 = oc.syndromes(Cbar)
+        assert oc.detect(r1, r2, q1, q2, TAU0) == ([2], [3])
+        res = oc.decode(Cbar, A, AP, B, BP, TAU0)
+        assert res.status == UNCORRECTABLE and (res.s, res.t) == (1, 1)
+        A2 = A.copy(); A2[1, 2] = bad
+        res = oc.protected_gemm(A, B, A2, B, [], TAU0)
+        assert res.status == UNCORRECTABLE and res.t == m
+    # a NaN that appears only in the second pass (left by a repair) is not waved through either
+    A2 = A.copy(); A2[1, 2] += 3.0
+    Cbar = oc.encoded_product(A2, AP, B, BP)
+    B2 = B.copy(); B2[2, 0] = np.nan        # the repair of row 1 multiplies e by this symbol
+    assert oc.decode(Cbar, A2, AP, B2, BP, TAU0).status == UNCORRECTABLE
