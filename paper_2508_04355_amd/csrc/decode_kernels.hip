@@ -44,6 +44,13 @@ __device__ __forceinline__ int64_t b_index(const gecc_params& p, int b, int l, i
   return (int64_t)b * p.stride_b + (p.trans_b ? (int64_t)j * p.ldb + l : (int64_t)l * p.ldb + j);
 }
 
+// Section V step 1 clears a line when |sum - parity| <= threshold holds; anything else, a NaN
+// included, flags it.
+__device__ __forceinline__ bool outside(double v, double tau) { return !(fabs(v) <= tau); }
+__device__ __forceinline__ bool finite2(double a, double b) { return isfinite(a) && isfinite(b); }
+// maximum that keeps a NaN (fmax would drop it)
+__device__ __forceinline__ double max_nan(double a, double b) { return (a != a || a > b) ? a : b; }
+
 // -------------------------------------------------------------------------------------------
 __global__ void reset_state_kernel(DecodeArgs a) {
   const int b = blockIdx.x * blockDim.x + threadIdx.x;
@@ -104,7 +111,7 @@ __global__ __launch_bounds__(64 * TH_SLICES) void threshold_kernel(DecodeArgs a)
       v2 = W - cpar[n + i];
       synd[i] = v1;
       synd[n + i] = v2;
-      if (fabs(v1) > a.p.tau_r1 || fabs(v2) > a.p.tau_r2) {
+      if (outside(v1, a.p.tau_r1) || outside(v2, a.p.tau_r2)) {
         const int idx = atomicAdd(&st->s_cnt, 1);
         if (idx < GECC_MAX_ERR) st->rows[idx] = i;
       }
@@ -114,11 +121,12 @@ __global__ __launch_bounds__(64 * TH_SLICES) void threshold_kernel(DecodeArgs a)
       v2 = W - cpar[2 * n + m + j];
       synd[2 * n + j] = v1;
       synd[2 * n + m + j] = v2;
-      if (fabs(v1) > a.p.tau_q1 || fabs(v2) > a.p.tau_q2) {
+      if (outside(v1, a.p.tau_q1) || outside(v2, a.p.tau_q2)) {
         const int idx = atomicAdd(&st->t_cnt, 1);
         if (idx < GECC_MAX_ERR) st->cols[idx] = j;
       }
     }
+    if (!finite2(v1, v2)) atomicOr(&st->nonfinite, 1);
   }
   {
     // family maxima of this workgroup (rows: [0], [1]; columns: [2], [3]); the summary reduces
@@ -127,10 +135,10 @@ __global__ __launch_bounds__(64 * TH_SLICES) void threshold_kernel(DecodeArgs a)
     double mq1 = (valid && !is_row) ? fabs(v1) : 0.0, mq2 = (valid && !is_row) ? fabs(v2) : 0.0;
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) {
-      mr1 = fmax(mr1, __shfl_down(mr1, off, 64));
-      mr2 = fmax(mr2, __shfl_down(mr2, off, 64));
-      mq1 = fmax(mq1, __shfl_down(mq1, off, 64));
-      mq2 = fmax(mq2, __shfl_down(mq2, off, 64));
+      mr1 = max_nan(mr1, __shfl_down(mr1, off, 64));
+      mr2 = max_nan(mr2, __shfl_down(mr2, off, 64));
+      mq1 = max_nan(mq1, __shfl_down(mq1, off, 64));
+      mq2 = max_nan(mq2, __shfl_down(mq2, off, 64));
     }
     if (lane == 0) {
       double* bm = a.blockmax + ((int64_t)b * gridDim.x + blockIdx.x) * 4;
@@ -148,11 +156,11 @@ __device__ int summarize(const DecodeArgs& a, int b, const DecodeState* st, gecc
   const double* bm = a.blockmax + (int64_t)b * a.nblk * 4;
   for (int i = threadIdx.x; i < a.nblk; i += blockDim.x)
 #pragma unroll
-    for (int f = 0; f < 4; ++f) mx[f] = fmax(mx[f], bm[(int64_t)i * 4 + f]);
+    for (int f = 0; f < 4; ++f) mx[f] = max_nan(mx[f], bm[(int64_t)i * 4 + f]);
 #pragma unroll
   for (int f = 0; f < 4; ++f)
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) mx[f] = fmax(mx[f], __shfl_down(mx[f], off, 64));
+    for (int off = 32; off > 0; off >>= 1) mx[f] = max_nan(mx[f], __shfl_down(mx[f], off, 64));
   const int wave = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
   if ((threadIdx.x & 63) == 0)
 #pragma unroll
@@ -167,7 +175,7 @@ __device__ int summarize(const DecodeArgs& a, int b, const DecodeState* st, gecc
     rep->reserved = 0;
     for (int f = 0; f < 4; ++f) {
       double v = smx[0][f];
-      for (int w = 1; w < nw; ++w) v = fmax(v, smx[w][f]);
+      for (int w = 1; w < nw; ++w) v = max_nan(v, smx[w][f]);
       rep->max_abs_synd[f] = v;
     }
     rep->status = status;
@@ -442,6 +450,11 @@ __device__ void decode_c_body(const DecodeArgs& a, int b, DecodeState* st, gecc_
   __shared__ int nfix;          // -1: the rule does not apply / failed
   __shared__ double red[256];
   const int n = a.p.n, m = a.p.m;
+  if (st->nonfinite) {
+    // a syndrome that is not a number: no estimate can be subtracted, the product is computed again
+    if (threadIdx.x == 0) { rep->status = GECC_UNCORRECTABLE; rep->n_err = 0; rep->n_total = 0; st->phase = PH_DONE; }
+    return;
+  }
   {
     const int s = st->s_cnt, t = st->t_cnt, lo = min(s, t), hi = max(s, t);
     // Theorem 2: many lines of one kind, at most two of the other.  Its errors all lie in C-bar,
@@ -552,8 +565,8 @@ __device__ AuditHit audit_line(const double* cur, const double* ref, int k, int 
   const double u1 = cur[l] - ref[l], u2 = cur[k + l] - ref[k + l];
   AuditHit h;
   h.line = l; h.pos = -1; h.e = u1;
-  *hit = fabs(u1) > tau || fabs(u2) > tau;
-  if (*hit && fabs(u1) > tau) {
+  *hit = outside(u1, tau) || outside(u2, tau);
+  if (*hit && fabs(u1) > tau && finite2(u1, u2)) {
     const double rho = u2 / u1, w = rint(rho);
     if (fabs(rho - w) < 0.25 && w >= 1.0 && w <= (double)len) h.pos = (int)w - 1;
   }
@@ -777,8 +790,8 @@ __global__ __launch_bounds__(RP_THREADS) void repair_kernel(DecodeArgs a) {
     st->n_err = ne;
   }
   // Section V step 1 on the residual syndromes (thresholds widened by the allowances above) ...
-  __shared__ int res_s, res_t;
-  if (threadIdx.x == 0) { res_s = 0; res_t = 0; }
+  __shared__ int res_s, res_t, res_bad;
+  if (threadIdx.x == 0) { res_s = 0; res_t = 0; res_bad = 0; }
   __syncthreads();
   for (int o0 = threadIdx.x; o0 < n + m; o0 += 2 * RP_U * RP_THREADS) {
     double y1[2 * RP_U], y2[2 * RP_U], g1[2 * RP_U], g2[2 * RP_U];
@@ -794,18 +807,19 @@ __global__ __launch_bounds__(RP_THREADS) void repair_kernel(DecodeArgs a) {
       const int o = o0 + u * RP_THREADS;
       if (o >= n + m) break;
       if (o < n) {
-        if (fabs(y1[u]) > a.p.tau_r1 + g1[u] || fabs(y2[u]) > a.p.tau_r2 + g2[u]) {
+        if (outside(y1[u], a.p.tau_r1 + g1[u]) || outside(y2[u], a.p.tau_r2 + g2[u])) {
           const int idx = atomicAdd(&res_s, 1);
           if (idx < GECC_MAX_ERR) st->rows[idx] = o;
         }
-      } else if (fabs(y1[u]) > a.p.tau_q1 + g1[u] || fabs(y2[u]) > a.p.tau_q2 + g2[u]) {
+      } else if (outside(y1[u], a.p.tau_q1 + g1[u]) || outside(y2[u], a.p.tau_q2 + g2[u])) {
         const int idx = atomicAdd(&res_t, 1);
         if (idx < GECC_MAX_ERR) st->cols[idx] = o - n;
       }
+      if (!finite2(y1[u], y2[u])) res_bad = 1;
     }
   }
   __syncthreads();
-  if (threadIdx.x == 0) { st->s_cnt = res_s; st->t_cnt = res_t; st->phase = PH_REVERIFY; }
+  if (threadIdx.x == 0) { st->s_cnt = res_s; st->t_cnt = res_t; st->nonfinite = res_bad; st->phase = PH_REVERIFY; }
   __syncthreads();
   // ... and step 2, by the first DC_THREADS threads (the other wavefronts end here)
   if (threadIdx.x >= DC_THREADS) return;

@@ -25,6 +25,7 @@ struct AuditHit {
 struct DecodeState {
   // filled by the threshold kernel (atomics; cleared by reset_state before each verify)
   int32_t s_cnt, t_cnt;
+  int32_t nonfinite;          // some syndrome is NaN or infinite: nothing can be subtracted, recompute
   int32_t rows[GECC_MAX_ERR], cols[GECC_MAX_ERR];
   // decoder
   int32_t phase;
@@ -144,6 +145,7 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t st);
 // counters, phase and error list of one batch item, as before any verification
 static __device__ __forceinline__ void reset_state(DecodeState* s) {
   s->s_cnt = 0; s->t_cnt = 0;
+  s->nonfinite = 0;
   s->phase = PH_DONE;
   s->n_err = 0;
 }

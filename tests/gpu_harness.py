@@ -41,10 +41,11 @@ class GpuResult:
     C_par: np.ndarray      # (batch, 2n+2m+4)
     synd: np.ndarray
     pad_untouched: bool = True   # the columns of C between m and ldc still hold what they held before
+    reverify_status: Optional[int] = None   # gecc_verify(fused=0) on the stored C after correction
 
 
 def run_gpu(A_enc, B_enc, A_mul, B_mul, c_faults, tau, dtype, trans_a=0, trans_b=0, refine=1,
-            fused=True, ld_pad=0, staged=True) -> GpuResult:
+            fused=True, ld_pad=0, staged=True, reverify=False) -> GpuResult:
     """All array arguments are (batch, rows, cols) or (rows, cols) float32 logical matrices.
     c_faults: [(batch, i, j, e)].  fused=False plants the C faults after the product (plain
     device writes) and verifies with the stand-alone syndrome scan instead."""
@@ -72,7 +73,7 @@ def run_gpu(A_enc, B_enc, A_mul, B_mul, c_faults, tau, dtype, trans_a=0, trans_b
         fl, nf = gecc.make_faults(c_faults, DEV)
         reports, attempts = ctx.protected_gemm_retry(dA, dB, Cd, A_par, B_par, C_par, rep, 0, fl, nf)
         assert attempts == 1
-        return GpuResult(reports=reports,
+        return GpuResult(reports=reports, reverify_status=_reverify(ctx, Cd, C_par) if reverify else None,
                          C=Cd.cpu().numpy().astype(np.float64)[:, :, :m], pad_untouched=bool(torch.isnan(Cd[:, :, m:]).all()),
                          A=from_dev(dA, trans_a, n if trans_a else k), B=from_dev(dB, trans_b, k if trans_b else m),
                          A_par=A_par.cpu().numpy().reshape(batch, 2, k), B_par=B_par.cpu().numpy().reshape(batch, 2, k),
@@ -95,11 +96,19 @@ def run_gpu(A_enc, B_enc, A_mul, B_mul, c_faults, tau, dtype, trans_a=0, trans_b
     ctx.correct(dA, A_par, dB, B_par, Cd, C_par, rep)
     reports = ctx.report_to_host(rep)
     torch.cuda.synchronize()
-    return GpuResult(reports=reports,
+    return GpuResult(reports=reports, reverify_status=_reverify(ctx, Cd, C_par) if reverify else None,
                      C=Cd.cpu().numpy().astype(np.float64)[:, :, :m], pad_untouched=bool(torch.isnan(Cd[:, :, m:]).all()),
                      A=from_dev(dA, trans_a, n if trans_a else k), B=from_dev(dB, trans_b, k if trans_b else m),
                      A_par=A_par.cpu().numpy().reshape(batch, 2, k), B_par=B_par.cpu().numpy().reshape(batch, 2, k),
                      C_par=C_par.cpu().numpy().reshape(batch, -1), synd=synd)
+
+
+def _reverify(ctx, Cd, C_par):
+    """Section V step 1 once more, from the C that is stored in memory (the fused path never reads
+    it back): status of batch item 0."""
+    rep2 = ctx.alloc_report()
+    ctx.verify(Cd, C_par, rep2, fused=False)
+    return ctx.report_to_host(rep2)[0].status
 
 
 def run_oracle(A_enc, B_enc, A_mul, B_mul, c_faults, tau) -> List[oc.Result]:
@@ -132,8 +141,14 @@ def compare(g: GpuResult, o: List[oc.Result], tol_c: float, tol_mag: float = Non
         mt = tol_mag if tol_mag is not None else 10 * tol_c * scale
         for x, y in zip(ge, oe):
             assert abs(x[3] - y[3]) <= mt + 1e-6 * abs(y[3]), (tag, x, y)
+        assert not np.isnan(g.C[b]).any(), (tag, "some symbol of C was never written")
         err = float(np.max(np.abs(g.C[b] - res.C))) / scale
         assert err <= tol_c, (tag, "C mismatch", err)
+        # the parity blocks of C-bar as the decoder left them (repaired lines included)
+        n, m = res.C.shape
+        ref = np.concatenate([res.Cbar[:n, m], res.Cbar[:n, m + 1], res.Cbar[n, :m], res.Cbar[n + 1, :m],
+                              res.Cbar[n:, m:].ravel()])
+        assert np.allclose(g.C_par[b], ref, rtol=1e-10, atol=1e-11 * np.abs(ref).max()), (tag, "parity blocks")
         if res.status == oc.CORRECTED:
             assert np.max(np.abs(g.A[b] - res.A)) <= 1e-6 * max(1.0, np.max(np.abs(res.A))), tag
             assert np.max(np.abs(g.B[b] - res.B)) <= 1e-6 * max(1.0, np.max(np.abs(res.B))), tag
