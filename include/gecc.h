@@ -88,6 +88,15 @@ typedef struct {
      (a difference of fp32 sums) is trusted to tau + tau_rel * |y|.  Detection uses tau alone.
      2^-20 suits fp32 partial sums. */
   double tau_rel;
+  /* 1: the grid code of Section III, two parities per line (the default of every binding).
+     0: single-checksum mode, the conventional checksum scheme Section VI compares with (Table 1):
+        the same kernels run, but detection and correction read the plain parities only -- errors
+        confined to one row or one column of C are corrected (Appendix A, cases s = t = 1 and
+        s = 1), everything else, a wrong operand symbol included (one parity names its line, not
+        its place in it), is GECC_UNCORRECTABLE.  tau_r2 / tau_q2 are ignored, max_abs_synd[1] and
+        [3] read 0. */
+  int32_t weighted;
+  int32_t reserved;
 } gecc_params;
 
 /* one located error: `magnitude` is the additive offset that was removed */

@@ -16,6 +16,9 @@ What follows the paper directly
   * syndromes / detect       -- Section V step 1, the four threshold tests.
   * d0_correct               -- Section V step 2 (s = 1 rule, 2x2 system for
                                 s = 2; stated for s <= t, s > t is its mirror image).
+  * single_checksum_correct / decode_single_checksum
+                             -- the conventional checksum scheme Section VI compares with
+                                (Table 1), as Appendix A uses it: plain parities only.
   * known_lines_correct      -- Theorem 2 and its proof (Appendix B): errors in
                                 any number of columns are corrected from the
                                 column parities once they are confined to at
@@ -109,6 +112,7 @@ class Thresholds:
     op: float = 0.0       # operand audit: |parity difference| > op flags a line
     rep: float = 0.0      # relative rounding allowance for lines touched by an operand repair
     rel: float = 0.0      # relative rounding allowance of a syndrome value (verification only)
+    weighted: bool = True # False: single-checksum mode, the second parity of every line is ignored
 
 
 class LineThresholds:
@@ -491,6 +495,78 @@ def decode(Cbar, A, AP, B, BP, tau):
     return done(UNCORRECTABLE, [])
 
 
+# ------------------------------------------ single-checksum mode (the comparison scheme of Section VI)
+def single_checksum_correct(r1, q1, Er, Et, tau):
+    """Conventional checksum correction: the plain parities alone.
+
+    Appendix A uses exactly this inside the proof of Theorem 1: one erroneous symbol (s = t = 1)
+    is corrected by a conventional checksum, and errors that all lie in one row s1 are
+    found column by column from the plain column parities, e_{s1,j} = q1_j (mirror image for
+    one column).  With one parity per line nothing else is decodable: two faulty rows and two
+    faulty columns leave four candidate positions and three independent equations.
+    Requires min(s, t) = 1.  tau: LineThresholds.  Verified like d0_correct: the single known
+    line's own plain syndrome has to be the sum of what was found in it.
+    Returns [(i, j, x)] or None.
+    """
+    s, t = len(Er), len(Et)
+    assert min(s, t) == 1
+    if s == 1:
+        known, lines, y, u_, z, uz = Er[0], Et, q1, tau.q1 + tau.rel * np.abs(q1), r1, tau.r1 + tau.rel * np.abs(r1)
+        at = lambda c: (known, c)
+    else:
+        known, lines, y, u_, z, uz = Et[0], Er, r1, tau.r1 + tau.rel * np.abs(r1), q1, tau.q1 + tau.rel * np.abs(q1)
+        at = lambda c: (c, known)
+    est = [(at(c) + (y[c], u_[c])) for c in lines if abs(y[c]) > u_[c]]
+    if abs(z[known] - sum(e[2] for e in est)) > uz[known] + sum(e[3] for e in est):
+        return None
+    return sorted((i, j, x) for (i, j, x, u) in est)
+
+
+def decode_single_checksum(Cbar, A, AP, B, BP, tau):
+    """Detection and correction with the plain parities only (Section VI compares the grid code
+    with such a checksum scheme; Table 1: it corrects one faulty line of C and nothing beyond).
+
+    Same order as `decode`: one flagged row and one flagged column are corrected at once;
+    otherwise the operands are audited first -- a wrong operand symbol shows in the plain parity
+    of its line, but one parity cannot say where in the line it sits, so any hit ends
+    UNCORRECTABLE -- and what is left is corrected when it is confined to one row or one column.
+    """
+    Cbar = np.array(Cbar, dtype=np.float64)
+    A = np.array(A, dtype=np.float64)
+    B = np.array(B, dtype=np.float64)
+    n, m = Cbar.shape[0] - 2, Cbar.shape[1] - 2
+    r1, r2, q1, q2 = syndromes(Cbar)
+    mx = (float(np.max(np.abs(r1))), 0.0, float(np.max(np.abs(q1))), 0.0)
+    inf = np.inf
+    lt = LineThresholds(tau, n, m)
+    only_plain = Thresholds(tau.r1, inf, tau.q1, inf)
+    Er, Et = detect(r1, 0.0 * r1, q1, 0.0 * q1, only_plain)
+    s0, t0 = len(Er), len(Et)
+
+    def done(status, errs):
+        return Result(status, s0, t0, sorted(errs), Cbar, A, B, mx)
+
+    if s0 == 0 and t0 == 0:
+        return done(CLEAN, [])
+    if not all_finite(r1, q1):
+        return done(UNCORRECTABLE, [])
+    fix = None
+    if s0 == 1 and t0 == 1:
+        fix = single_checksum_correct(r1, q1, Er, Et, lt)
+    if fix is None:
+        u_a = encode_a(A)[0] - AP[0]
+        u_b = encode_b(B)[:, 0] - BP[:, 0]
+        if np.any(~(np.abs(u_a) <= tau.op)) or np.any(~(np.abs(u_b) <= tau.op)):
+            return done(UNCORRECTABLE, [])
+        if min(s0, t0) == 1:
+            fix = single_checksum_correct(r1, q1, Er, Et, lt)
+    if fix is None:
+        return done(UNCORRECTABLE, [])
+    for (i, j, x) in fix:
+        Cbar[i, j] -= x
+    return done(CORRECTED, [(MAT_C, i, j, x) for (i, j, x) in fix])
+
+
 def protected_gemm(A_enc, B_enc, A_mul, B_mul, c_faults, tau):
     """The whole path: encode -> (operand faults) -> product -> (C faults) -> decode.
 
@@ -503,4 +579,6 @@ def protected_gemm(A_enc, B_enc, A_mul, B_mul, c_faults, tau):
     BP = encode_b(B_enc)
     Cbar = encoded_product(A_mul, AP, B_mul, BP)
     inject_c(Cbar, c_faults)
+    if not tau.weighted:
+        return decode_single_checksum(Cbar, A_mul, AP, B_mul, BP, tau)
     return decode(Cbar, A_mul, AP, B_mul, BP, tau)

@@ -71,6 +71,7 @@ __global__ __launch_bounds__(64 * TH_SLICES) void threshold_kernel(DecodeArgs a)
   const double* cpar = cpar_of(a, b);
   double* synd = synd_of(a, b);
   const bool is_row = o < n, valid = o < n + m;
+  const bool wt = a.p.weighted != 0;     // single-checksum mode: the weighted sums are not read
 
   // partial sums of this line over the sub-tiles slice, slice + 4, ... (fixed order); all loads
   // of a thread are issued before the first is used
@@ -111,7 +112,7 @@ __global__ __launch_bounds__(64 * TH_SLICES) void threshold_kernel(DecodeArgs a)
       v2 = W - cpar[n + i];
       synd[i] = v1;
       synd[n + i] = v2;
-      if (outside(v1, a.p.tau_r1) || outside(v2, a.p.tau_r2)) {
+      if (outside(v1, a.p.tau_r1) || (wt && outside(v2, a.p.tau_r2))) {
         const int idx = atomicAdd(&st->s_cnt, 1);
         if (idx < GECC_MAX_ERR) st->rows[idx] = i;
       }
@@ -121,11 +122,12 @@ __global__ __launch_bounds__(64 * TH_SLICES) void threshold_kernel(DecodeArgs a)
       v2 = W - cpar[2 * n + m + j];
       synd[2 * n + j] = v1;
       synd[2 * n + m + j] = v2;
-      if (outside(v1, a.p.tau_q1) || outside(v2, a.p.tau_q2)) {
+      if (outside(v1, a.p.tau_q1) || (wt && outside(v2, a.p.tau_q2))) {
         const int idx = atomicAdd(&st->t_cnt, 1);
         if (idx < GECC_MAX_ERR) st->cols[idx] = j;
       }
     }
+    if (!wt) v2 = 0.0;
     if (!finite2(v1, v2)) atomicOr(&st->nonfinite, 1);
   }
   {
@@ -206,6 +208,7 @@ struct Synd {
   double b_r1, b_r2, b_q1, b_q2;            // thresholds of the four families
   const double *a_r1, *a_r2, *a_q1, *a_q2;  // per-line allowances (null: none)
   double rel;                               // relative rounding allowance of a syndrome value
+  bool wt;                                  // false: single-checksum mode, r2 / q2 are not read
   // how far each syndrome value is trusted when an estimate is verified
   __device__ double tr1(int i) const { return b_r1 + (a_r1 ? a_r1[i] : 0.0) + rel * fabs(r1[i]); }
   __device__ double tr2(int i) const { return b_r2 + (a_r2 ? a_r2[i] : 0.0) + rel * fabs(r2[i]); }
@@ -226,7 +229,7 @@ __device__ bool residual_ok(const Est* est, int ne, const int* Er, int s, const 
         wx += (est[e].j + 1) * est[e].x; wu += (est[e].j + 1) * est[e].u;
       }
     if (fabs(y.r1[i] - sx) > y.tr1(i) + su) return false;
-    if (fabs(y.r2[i] - wx) > y.tr2(i) + wu) return false;
+    if (y.wt && fabs(y.r2[i] - wx) > y.tr2(i) + wu) return false;
   }
   for (int c = 0; c < t; ++c) {
     const int j = Et[c];
@@ -237,7 +240,7 @@ __device__ bool residual_ok(const Est* est, int ne, const int* Er, int s, const 
         wx += (est[e].i + 1) * est[e].x; wu += (est[e].i + 1) * est[e].u;
       }
     if (fabs(y.q1[j] - sx) > y.tq1(j) + su) return false;
-    if (fabs(y.q2[j] - wx) > y.tq2(j) + wu) return false;
+    if (y.wt && fabs(y.q2[j] - wx) > y.tq2(j) + wu) return false;
   }
   return true;
 }
@@ -338,7 +341,7 @@ __device__ int known_lines_correct(const DecodeArgs& a, int b, DecodeState* st, 
                                    const Synd& y, int final_pass) {
   const int n = a.p.n, m = a.p.m;
   const int s = st->s_cnt, t = st->t_cnt;
-  const bool rows_known = s <= 2;
+  const bool rows_known = a.p.weighted ? s <= 2 : s == 1;
   const int nk = rows_known ? s : t;
   const int L = rows_known ? m : n;
   int K[2] = {0, 0};
@@ -351,7 +354,7 @@ __device__ int known_lines_correct(const DecodeArgs& a, int b, DecodeState* st, 
 
   auto estimate = [&](int c) {
     LineEst e;
-    e.flagged = fabs(y1[c]) > b1 + (a1 ? a1[c] : 0.0) || fabs(y2[c]) > b2 + (a2 ? a2[c] : 0.0);
+    e.flagged = fabs(y1[c]) > b1 + (a1 ? a1[c] : 0.0) || (y.wt && fabs(y2[c]) > b2 + (a2 ? a2[c] : 0.0));
     e.sig[0] = e.sig[1] = false; e.x[0] = e.x[1] = e.u[0] = e.u[1] = 0.0;
     if (!e.flagged) return e;
     const double u1 = rows_known ? y.tq1(c) : y.tr1(c), u2 = rows_known ? y.tq2(c) : y.tr2(c);
@@ -391,7 +394,7 @@ __device__ int known_lines_correct(const DecodeArgs& a, int b, DecodeState* st, 
         ++cnt[q];
       }
     const double u1 = rows_known ? y.tq1(c) : y.tr1(c), u2 = rows_known ? y.tq2(c) : y.tr2(c);
-    bad = bad || fabs(y1[c] - sx) > u1 + su || fabs(y2[c] - wx) > u2 + wu;
+    bad = bad || fabs(y1[c] - sx) > u1 + su || (y.wt && fabs(y2[c] - wx) > u2 + wu);
   }
   for (int q = 0; q < 8; ++q) t2_red[q][tid] = acc[q];
   t2_cnt[0][tid] = cnt[0]; t2_cnt[1][tid] = cnt[1];
@@ -406,7 +409,7 @@ __device__ int known_lines_correct(const DecodeArgs& a, int b, DecodeState* st, 
       const int line = K[q];
       const double z1 = rows_known ? y.r1[line] : y.q1[line], z2 = rows_known ? y.r2[line] : y.q2[line];
       const double tz1 = rows_known ? y.tr1(line) : y.tq1(line), tz2 = rows_known ? y.tr2(line) : y.tq2(line);
-      if (fabs(z1 - v[0]) > tz1 + v[1] || fabs(z2 - v[2]) > tz2 + v[3]) t2_bad = 1;
+      if (fabs(z1 - v[0]) > tz1 + v[1] || (y.wt && fabs(z2 - v[2]) > tz2 + v[3])) t2_bad = 1;
     }
   }
   __syncthreads();
@@ -461,12 +464,13 @@ __device__ void decode_c_body(const DecodeArgs& a, int b, DecodeState* st, gecc_
     // so it runs only after the operand audit (on what the repair leaves, or on the whole pattern
     // when both operands are intact): a wrong symbol of A a few rows from a flagged row would
     // otherwise pass for a row full of small errors of C.
-    if (final_pass && lo >= 1 && lo <= 2 && hi > 2) {
+    // (single-checksum mode: one known line only, any number of the other kind -- Appendix A, case s = 1)
+    if (final_pass && (a.p.weighted ? (lo >= 1 && lo <= 2 && hi > 2) : (lo == 1 && hi >= 2))) {
       const double* sy = synd_of(a, b);
       const double* al = final_pass ? allow_of(a, b) : nullptr;
       const Synd y{sy, sy + n, sy + 2 * n, sy + 2 * n + m, a.p.tau_r1, a.p.tau_r2, a.p.tau_q1, a.p.tau_q2,
                    al, al ? al + n : nullptr, al ? al + 2 * n : nullptr, al ? al + 2 * n + m : nullptr,
-                   a.p.tau_rel};
+                   a.p.tau_rel, a.p.weighted != 0};
       const int k = known_lines_correct(a, b, st, rep, y, final_pass);
       if (threadIdx.x == 0) {
         if (k < 0) {
@@ -487,7 +491,7 @@ __device__ void decode_c_body(const DecodeArgs& a, int b, DecodeState* st, gecc_
     nfix = -1;
     if (s == 0 && t == 0) {
       nfix = 0;
-    } else if (s >= 1 && s <= 2 && t >= 1 && t <= 2) {
+    } else if (s >= 1 && s <= 2 && t >= 1 && t <= 2 && (a.p.weighted || (s == 1 && t == 1))) {
       int Er[2], Et[2];
       for (int x = 0; x < s; ++x) Er[x] = st->rows[x];
       for (int x = 0; x < t; ++x) Et[x] = st->cols[x];
@@ -497,7 +501,7 @@ __device__ void decode_c_body(const DecodeArgs& a, int b, DecodeState* st, gecc_
       const double* al = final_pass ? allow_of(a, b) : nullptr;
       Synd y{sy, sy + n, sy + 2 * n, sy + 2 * n + m, a.p.tau_r1, a.p.tau_r2, a.p.tau_q1, a.p.tau_q2,
              al, al ? al + n : nullptr, al ? al + 2 * n : nullptr, al ? al + 2 * n + m : nullptr,
-             a.p.tau_rel};
+             a.p.tau_rel, a.p.weighted != 0};
       Est tmp[4];
       const int k = d0_correct(tmp, Er, s, Et, t, y);
       if (k >= 0) {
@@ -561,11 +565,11 @@ __global__ __launch_bounds__(DC_THREADS) void decode_c_kernel(DecodeArgs a, int 
 // A single wrong symbol of a line (column l of A, row l of B) shows as (u1, u2) = (e, (pos+1) e)
 // in the difference of re-formed and stored parities.
 __device__ AuditHit audit_line(const double* cur, const double* ref, int k, int l, int len, double tau,
-                               bool* hit) {
+                               bool wt, bool* hit) {
   const double u1 = cur[l] - ref[l], u2 = cur[k + l] - ref[k + l];
   AuditHit h;
   h.line = l; h.pos = -1; h.e = u1;
-  *hit = outside(u1, tau) || outside(u2, tau);
+  *hit = outside(u1, tau) || (wt && outside(u2, tau));
   if (*hit && fabs(u1) > tau && finite2(u1, u2)) {
     const double rho = u2 / u1, w = rint(rho);
     if (fabs(rho - w) < 0.25 && w >= 1.0 && w <= (double)len) h.pos = (int)w - 1;
@@ -608,9 +612,9 @@ __global__ __launch_bounds__(RP_THREADS) void repair_kernel(DecodeArgs a) {
 #pragma unroll 4
     for (int l = threadIdx.x; l < k; l += blockDim.x) {
       bool hit;
-      AuditHit h = audit_line(cur_a, ref_a, k, l, n, a.p.tau_op, &hit);
+      AuditHit h = audit_line(cur_a, ref_a, k, l, n, a.p.tau_op, a.p.weighted != 0, &hit);
       if (hit) { const int idx = atomicAdd(&cnt_a, 1); if (idx < GECC_MAX_ERR) ha[idx] = h; }
-      h = audit_line(cur_b, ref_b, k, l, m, a.p.tau_op, &hit);
+      h = audit_line(cur_b, ref_b, k, l, m, a.p.tau_op, a.p.weighted != 0, &hit);
       if (hit) { const int idx = atomicAdd(&cnt_b, 1); if (idx < GECC_MAX_ERR) hb[idx] = h; }
     }
   }
@@ -618,6 +622,8 @@ __global__ __launch_bounds__(RP_THREADS) void repair_kernel(DecodeArgs a) {
   const int na = cnt_a, nb = cnt_b;
   if (threadIdx.x == 0) {
     ok = na + nb <= GECC_MAX_ERR;       // no hit at all: the pattern lies in C-bar alone (second pass below)
+    // single-checksum mode: one parity names the line of a wrong operand symbol, not its place in it
+    if (!a.p.weighted && na + nb > 0) ok = 0;
     if (ok) {
       for (int x = 0; x < na; ++x) if (ha[x].pos < 0) ok = 0;
       for (int x = 0; x < nb; ++x) if (hb[x].pos < 0) ok = 0;
@@ -791,6 +797,7 @@ __global__ __launch_bounds__(RP_THREADS) void repair_kernel(DecodeArgs a) {
   }
   // Section V step 1 on the residual syndromes (thresholds widened by the allowances above) ...
   __shared__ int res_s, res_t, res_bad;
+  const bool wt = a.p.weighted != 0;
   if (threadIdx.x == 0) { res_s = 0; res_t = 0; res_bad = 0; }
   __syncthreads();
   for (int o0 = threadIdx.x; o0 < n + m; o0 += 2 * RP_U * RP_THREADS) {
@@ -807,15 +814,15 @@ __global__ __launch_bounds__(RP_THREADS) void repair_kernel(DecodeArgs a) {
       const int o = o0 + u * RP_THREADS;
       if (o >= n + m) break;
       if (o < n) {
-        if (outside(y1[u], a.p.tau_r1 + g1[u]) || outside(y2[u], a.p.tau_r2 + g2[u])) {
+        if (outside(y1[u], a.p.tau_r1 + g1[u]) || (wt && outside(y2[u], a.p.tau_r2 + g2[u]))) {
           const int idx = atomicAdd(&res_s, 1);
           if (idx < GECC_MAX_ERR) st->rows[idx] = o;
         }
-      } else if (outside(y1[u], a.p.tau_q1 + g1[u]) || outside(y2[u], a.p.tau_q2 + g2[u])) {
+      } else if (outside(y1[u], a.p.tau_q1 + g1[u]) || (wt && outside(y2[u], a.p.tau_q2 + g2[u]))) {
         const int idx = atomicAdd(&res_t, 1);
         if (idx < GECC_MAX_ERR) st->cols[idx] = o - n;
       }
-      if (!finite2(y1[u], y2[u])) res_bad = 1;
+      if (!finite2(y1[u], wt ? y2[u] : 0.0)) res_bad = 1;
     }
   }
   __syncthreads();

@@ -220,6 +220,7 @@ int gecc_create(gecc_ctx** out, const gecc_params* p) {
   if (!(p->tau_r1 >= 0) || !(p->tau_r2 >= 0) || !(p->tau_q1 >= 0) || !(p->tau_q2 >= 0) ||
       !(p->tau_op >= 0) || !(p->tau_rep >= 0) || !(p->tau_rel >= 0))
     return GECC_ERR_ARG;
+  if (p->weighted != 0 && p->weighted != 1) return GECC_ERR_ARG;
   if ((int64_t)p->n + p->m > (int64_t)1 << 30) return GECC_ERR_ARG;
   gecc_ctx* c = new (std::nothrow) gecc_ctx;
   if (!c) return GECC_ERR_ARG;

@@ -28,7 +28,7 @@ class Params(C.Structure):
                 ("stride_a", C.c_int64), ("stride_b", C.c_int64), ("stride_c", C.c_int64),
                 ("tau_r1", C.c_double), ("tau_r2", C.c_double), ("tau_q1", C.c_double),
                 ("tau_q2", C.c_double), ("tau_op", C.c_double), ("tau_rep", C.c_double),
-                ("tau_rel", C.c_double)]
+                ("tau_rel", C.c_double), ("weighted", C.c_int32), ("reserved", C.c_int32)]
 
 
 class Err(C.Structure):
@@ -128,6 +128,7 @@ class Thresholds:
     op: float = 0.0
     rep: float = 16.0 * 2.0 ** -24     # rounding allowance for repaired lines (fp32 accumulation)
     rel: float = 2.0 ** -20            # relative rounding allowance of a syndrome value (fp32 sums)
+    weighted: bool = True              # False: single-checksum mode (plain parities only)
 
 
 def noise_thresholds(n, k, m, sigma_a, sigma_b, safety=16.0) -> Thresholds:
@@ -161,7 +162,7 @@ class Context:
                              stride_b=stride_b if stride_b is not None else rows_b * ldb,
                              stride_c=stride_c if stride_c is not None else n * ldc,
                              tau_r1=tau.r1, tau_r2=tau.r2, tau_q1=tau.q1, tau_q2=tau.q2, tau_op=tau.op,
-                             tau_rep=tau.rep, tau_rel=tau.rel)
+                             tau_rep=tau.rep, tau_rel=tau.rel, weighted=1 if tau.weighted else 0, reserved=0)
         self._h = C.c_void_p()
         _check(lib().gecc_create(C.byref(self._h), C.byref(self.params)))
         self.device = torch.device(device)

@@ -58,7 +58,7 @@ def run_gpu(A_enc, B_enc, A_mul, B_mul, c_faults, tau, dtype, trans_a=0, trans_b
     ldb = (k if trans_b else m) + ld_pad
     ldc = m + ld_pad
     ctx = gecc.Context(n, k, m, gecc.BF16 if dtype == "bf16" else gecc.F32,
-                       gecc.Thresholds(tau.r1, tau.r2, tau.q1, tau.q2, tau.op, tau.rep, tau.rel), batch=batch,
+                       gecc.Thresholds(tau.r1, tau.r2, tau.q1, tau.q2, tau.op, tau.rep, tau.rel, getattr(tau, 'weighted', True)), batch=batch,
                        trans_a=trans_a, trans_b=trans_b, refine=refine, lda=lda, ldb=ldb, ldc=ldc)
     dA = to_dev(A_enc, dtype, trans_a, lda)
     dB = to_dev(B_enc, dtype, trans_b, ldb)
@@ -119,7 +119,7 @@ def run_oracle(A_enc, B_enc, A_mul, B_mul, c_faults, tau) -> List[oc.Result]:
     for b in range(A_enc.shape[0]):
         cf = [(i, j, e) for (bb, i, j, e) in c_faults if bb == b]
         out.append(oc.protected_gemm(A_enc[b], B_enc[b], A_mul[b], B_mul[b], cf,
-                                     oc.Thresholds(tau.r1, tau.r2, tau.q1, tau.q2, tau.op, tau.rep, tau.rel)))
+                                     oc.Thresholds(tau.r1, tau.r2, tau.q1, tau.q2, tau.op, tau.rep, tau.rel, getattr(tau, 'weighted', True))))
     return out
 
 

@@ -353,6 +353,55 @@ def test_results_are_reproducible_bit_for_bit():
     assert g1.reports[0].errors() == g2.reports[0].errors()
 
 
+# ---- single-checksum mode (Section VI's comparison scheme: plain parities only) -----------------------
+@pytest.mark.parametrize("pattern", ["none", "C", "C+C same row", "C+C same column", "C+C elsewhere", "A", "B", "A+C", "B+C",
+                                     "one row, 40 columns", "one column, 25 rows", "two rows", "C nan"])
+@pytest.mark.parametrize("dtype,shape,trans", [("f32", (300, 200, 260), (0, 0)), ("bf16", (520, 256, 264), (0, 1)),
+                                               ("bf16", (520, 256, 264), (1, 0))])
+def test_single_checksum_mode(pattern, dtype, shape, trans):
+    """gecc_params.weighted = 0: the same kernels, decoder restricted to the plain parities.  One
+    faulty row or column of C is corrected whatever the number of symbols (scenario c of Section VI
+    and Appendix A's case s = 1), everything else is UNCORRECTABLE -- scenarios d, e, f, and a, b
+    too under the fault model used here (the spoiled row of C takes its own parity symbols along,
+    and one parity per operand line cannot place the symbol).  Status, positions and C as the
+    oracle's single-checksum decoder gives them; the grid code corrects all of these but 'two rows'."""
+    n, k, m = shape
+    rng = inputs.rng_for(98, len(pattern))
+    F = inputs.Fault
+    faults = {"none": [], "C": [F(MAT_C, n - 1, 3, 21.0)],
+              "C+C same row": [F(MAT_C, 257, 0, 9.0), F(MAT_C, 257, m - 1, -30.0)],
+              "C+C same column": [F(MAT_C, 0, 258, 5.5), F(MAT_C, n - 1, 258, 14.0)],
+              "C+C elsewhere": [F(MAT_C, 10, 20, 7.0), F(MAT_C, 200, 100, -8.0)],
+              "A": [F(MAT_A, 100, k - 1, 3.0)], "B": [F(MAT_B, 0, 259, -4.0)],
+              "A+C": [F(MAT_A, 100, 5, 3.0), F(MAT_C, 100, 7, 12.0)], "B+C": [F(MAT_B, 9, 70, 2.0), F(MAT_C, 1, 2, 6.0)],
+              "one row, 40 columns": _t2_faults(rng, [n - 2], None, m, 40 / m, True),
+              "one column, 25 rows": _t2_faults(rng, [1], None, n, 25 / n, False),
+              "two rows": _t2_faults(rng, [3, 200], None, m, 5 / m, True),
+              "C nan": [F(MAT_C, 5, 6, float("nan"))]}[pattern]
+    A, B, A2, B2, cf, eff = _trial(rng, n, k, m, dtype, ("normal", 1.0), ("normal", 1.0), faults)
+    t = gecc.noise_thresholds(n, k, m, 1.0, 1.0)
+    tau = gecc.Thresholds(t.r1, t.r2, t.q1, t.q2, weighted=False)
+    cfb = [(0,) + c for c in cf]
+    g = H.run_gpu(A, B, A2, B2, cfb, tau, dtype, trans[0], trans[1])
+    with np.errstate(invalid="ignore"):
+        o = H.run_oracle(A, B, A2, B2, cfb, tau)
+    scale = float(np.max(np.abs(np.nan_to_num(o[0].C))))
+    # more than one symbol in the line: Section V's subtraction without re-evaluation (as for Theorem 2)
+    many = len(faults) > 1
+    tol = 4 * max(tau.r1, tau.q1) / scale if many else 1e-5
+    H.compare(g, o, tol, tol_mag=4 * max(tau.r1, tau.q1), what="single checksum, " + pattern)
+    want = {"none": gecc.CLEAN, "C": gecc.CORRECTED, "C+C same row": gecc.CORRECTED, "C+C same column": gecc.CORRECTED,
+            "one row, 40 columns": gecc.CORRECTED, "one column, 25 rows": gecc.CORRECTED}.get(pattern, gecc.UNCORRECTABLE)
+    assert g.reports[0].status == want
+    assert g.reports[0].max_abs_synd[1] == 0.0 and g.reports[0].max_abs_synd[3] == 0.0
+    if want == gecc.CORRECTED:
+        assert g.reports[0].n_total == len(faults)
+    # the grid code on the same faults
+    if pattern not in ("two rows", "C nan", "none"):
+        g2 = H.run_gpu(A, B, A2, B2, cfb, t, dtype, trans[0], trans[1])
+        assert g2.reports[0].status == gecc.CORRECTED and g2.reports[0].n_total == len(eff)
+
+
 # ---- symbols that are not numbers ------------------------------------------------------------------
 @pytest.mark.parametrize("where", ["C nan", "C inf", "C nan, stand-alone verify", "A nan", "B -inf"])
 @pytest.mark.parametrize("dtype,shape", [("f32", (300, 200, 260)), ("bf16", (520, 256, 264))])

@@ -796,3 +796,108 @@ def test_a_symbol_that_is_not_a_number_is_detected_and_handed_back():
     Cbar = oc.encoded_product(A2, AP, B, BP)
     B2 = B.copy(); B2[2, 0] = np.nan        # the repair of row 1 multiplies e by this symbol
     assert oc.decode(Cbar, A2, AP, B2, BP, TAU0).status == UNCORRECTABLE
+
+
+# ---- single-checksum mode: the conventional checksum scheme Section VI compares with ------------
+TAU0_SINGLE = Thresholds(1e-9, 1e-9, 1e-9, 1e-9, 0.0, weighted=False)
+
+
+def test_single_checksum_corrects_exactly_the_patterns_confined_to_one_line_of_C():
+    """With one parity per line, errors of C are decodable iff they all lie in one row or in one
+    column (Appendix A: s = t = 1 is the conventional checksum, one faulty row is read column by
+    column from the plain column parities).  Every pattern of one to three symbols on a 4 x 4 grid,
+    magnitudes 1, 10, 100 (no partial sum cancels)."""
+    n, k, m = 4, 3, 4
+    A, B = int_mats(7, n, k, m)
+    clean = oc.encoded_product(A, oc.encode_a(A), B, oc.encode_b(B))
+    cells = [(i, j) for i in range(n) for j in range(m)]
+    n_ok = n_not = 0
+    for cnt in (1, 2, 3):
+        for pos in itertools.combinations(cells, cnt):
+            cf = [(i, j, 10.0 ** x) for x, (i, j) in enumerate(pos)]
+            one_line = len({i for i, j in pos}) == 1 or len({j for i, j in pos}) == 1
+            res = oc.protected_gemm(A, B, A, B, cf, TAU0_SINGLE)
+            if one_line:
+                n_ok += 1
+                assert res.status == CORRECTED and res.errors == sorted((MAT_C, i, j, e) for (i, j, e) in cf), pos
+                assert np.array_equal(res.Cbar, clean)
+            else:
+                n_not += 1
+                assert res.status == UNCORRECTABLE, pos
+            # the grid code corrects all of these as long as they fit two rows and two columns ...
+            if len({i for i, j in pos}) <= 2 and len({j for i, j in pos}) <= 2:
+                assert oc.protected_gemm(A, B, A, B, cf, TAU0).status == CORRECTED
+    assert n_ok == 16 + 2 * 4 * 6 + 2 * 4 * 4 and n_not > 0
+
+
+def test_single_checksum_cannot_tell_the_two_diagonals_apart():
+    """Textbook fact behind the bound: equal errors on the diagonal and on the anti-diagonal of a
+    2 x 2 sub-grid have the same row sums and the same column sums."""
+    n, k, m = 5, 3, 6
+    A, B = int_mats(8, n, k, m)
+    AP, BP = oc.encode_a(A), oc.encode_b(B)
+    Cd, Ca = oc.encoded_product(A, AP, B, BP), oc.encoded_product(A, AP, B, BP)
+    oc.inject_c(Cd, [(1, 2, 3.0), (3, 4, 3.0)])
+    oc.inject_c(Ca, [(1, 4, 3.0), (3, 2, 3.0)])
+    sd, sa = oc.syndromes(Cd), oc.syndromes(Ca)
+    assert np.array_equal(sd[0], sa[0]) and np.array_equal(sd[2], sa[2])       # plain sums coincide
+    assert not np.array_equal(sd[1], sa[1])                                     # the weighted ones do not
+    for Cx in (Cd, Ca):
+        assert oc.decode_single_checksum(Cx, A, AP, B, BP, TAU0_SINGLE).status == UNCORRECTABLE
+        assert oc.decode(Cx, A, AP, B, BP, TAU0).status == CORRECTED
+
+
+@pytest.mark.parametrize("n,k,m", [(3, 3, 3), (4, 2, 3)])
+def test_single_checksum_on_every_single_and_pair_placement(n, k, m):
+    """Scenarios of Section VI in single-checksum mode, exhaustively on tiny sizes: one error of C is
+    corrected; a wrong operand symbol is detected but cannot be placed (its line carries one parity,
+    and the row of C it spoils takes its own parity symbols along); pairs are corrected only when
+    both lie in one row or one column of C.  Nothing is ever mis-corrected, nothing goes unseen."""
+    A, B = int_mats(41 + n + k + m, n, k, m)
+    AP, BP = oc.encode_a(A), oc.encode_b(B)
+    clean = oc.encoded_product(A, AP, B, BP)
+
+    def run(placed):
+        A2, B2, cf = A.copy(), B.copy(), []
+        for (mt, r, c, e) in placed:
+            if mt == MAT_A: A2[r, c] += e
+            elif mt == MAT_B: B2[r, c] += e
+            else: cf.append((r, c, e))
+        return oc.protected_gemm(A, B, A2, B2, cf, TAU0_SINGLE)
+
+    P = _placements(n, k, m)
+    for p in P:
+        res = run([p + (2.0,)])
+        if p[0] == MAT_C:
+            assert res.status == CORRECTED and res.errors == [p + (2.0,)] and np.array_equal(res.Cbar, clean)
+        else:
+            assert res.status == UNCORRECTABLE
+    seen = set()
+    for p1, p2 in itertools.combinations(P, 2):
+        res = run([p1 + (3.0,), p2 + (-5.0,)])
+        both_c = p1[0] == p2[0] == MAT_C
+        if both_c and (p1[1] == p2[1] or p1[2] == p2[2]):
+            assert res.status == CORRECTED and res.errors == sorted([p1 + (3.0,), p2 + (-5.0,)])
+            assert np.array_equal(res.Cbar, clean)
+        else:
+            assert res.status == UNCORRECTABLE, (p1, p2)
+        seen.add(res.status)
+    assert seen == {CORRECTED, UNCORRECTABLE}
+
+
+def test_single_checksum_verifies_its_estimates_and_ignores_the_weighted_sums():
+    n, k, m = 6, 4, 7
+    A, B = int_mats(9, n, k, m)
+    AP, BP = oc.encode_a(A), oc.encode_b(B)
+    Cbar = oc.encoded_product(A, AP, B, BP)
+    # a wrong weighted parity symbol alone is invisible in this mode and flags a row of the grid code
+    C1 = Cbar.copy(); C1[2, m + 1] += 5.0
+    assert oc.decode_single_checksum(C1, A, AP, B, BP, TAU0_SINGLE).status == CLEAN
+    assert oc.decode(C1, A, AP, B, BP, TAU0).s == 1
+    # one flagged row whose own sum does not add up to what the columns say: refused
+    C2 = Cbar.copy(); C2[1, 2] += 4.0; C2[1, 5] -= 1.0; C2[1, m] += 0.5       # row parity symbol off as well
+    assert oc.decode_single_checksum(C2, A, AP, B, BP, TAU0_SINGLE).status == UNCORRECTABLE
+    # NaN: flagged and handed back
+    C3 = Cbar.copy(); C3[0, 0] = np.nan
+    res = oc.decode_single_checksum(C3, A, AP, B, BP, TAU0_SINGLE)
+    assert res.status == UNCORRECTABLE and (res.s, res.t) == (1, 1)
