@@ -96,13 +96,13 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    ctx.timing_enable(args.steps)
+    ctx.timing_enable(args.steps, (gecc.K_PRODUCT,))
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    gemm_ms = ctx.timing_read(args.steps)
+    gemm_ms = [ms for (_, ms) in ctx.timing_read(args.steps)]
     ctx.timing_enable(0)
     ms_step = (t1 - t0) * 1e3 / args.steps
     reports = ctx.report_to_host(rep)
@@ -110,8 +110,62 @@ def main():
 
     ms_plain = 0.5 * (ms_plain_before + time_plain())
 
+    # ---- HBM rooflines of the memory-bound kernels: the same steps once more with an event pair
+    # around every launch (not part of `value`: the records cost stream time), then the stand-alone
+    # syndrome scan of C, then the same steps on three rotating copies of the operands, so that no
+    # scan finds its operand in the 256 MiB memory-side cache -----------------------------------
+    s_in = 2 if w.dtype == "bf16" else 4
+    ntm, ntn = -(-n // 128), -(-m // 128)
+    scan_bytes = {"encode_a": s_in * n * k * batch, "encode_b": s_in * k * m * batch,
+                  "parity_r": s_in * n * k * batch, "parity_c": s_in * k * m * batch,
+                  "threshold": 8 * (ntn * n + ntm * m) * batch, "partials": 4 * n * m * batch}
+    scan_kinds = (gecc.K_ENCODE_A, gecc.K_ENCODE_B, gecc.K_PARITY_R, gecc.K_PARITY_C, gecc.K_THRESHOLD,
+                  gecc.K_PARTIALS, gecc.K_STAGE2, gecc.K_DECODE, gecc.K_AUDIT_A, gecc.K_AUDIT_B, gecc.K_REPAIR)
+
+    def per_kernel(run, reps):
+        ctx.timing_enable(16 * reps, scan_kinds)
+        for _ in range(reps):
+            run()
+        torch.cuda.synchronize()
+        rec = ctx.timing_read(16 * reps)
+        ctx.timing_enable(0)
+        by = {}
+        for kind, ms in rec:
+            by.setdefault(gecc.K_NAMES[kind], []).append(ms * 1e3)
+        return by
+
+    def hbm_table(by):
+        out = {}
+        for name, us in by.items():
+            e = {"launches": len(us), "us": round(float(np.mean(us)), 2)}
+            if name in scan_bytes:
+                e["bytes"] = scan_bytes[name]
+                e["GBs"] = round(scan_bytes[name] / np.mean(us) / 1e3, 1)
+                e["frac"] = round(scan_bytes[name] / (np.mean(us) * 1e-6) / (HBM_PEAK_GBS * 1e9), 4)
+            out[name] = e
+        return out
+
+    reps = max(5, min(args.steps, 20))
+    hbm_steady = hbm_table(per_kernel(step, reps))
+    rep2 = ctx.alloc_report()
+    hbm_steady.update(hbm_table({kk: v for kk, v in per_kernel(lambda: ctx.verify(Cd, C_par, rep2, fused=False), reps).items()
+                                 if kk == "partials"}))
+    sets = [(dA, dB)] + [(dA.clone(), dB.clone()) for _ in range(2)]
+    turn = [0]
+
+    def rotating_step():
+        a_, b_ = sets[turn[0] % 3]
+        turn[0] += 1
+        ctx.protected_gemm(a_, b_, Cd, A_par, B_par, C_par, rep)
+
+    for _ in range(3):
+        rotating_step()
+    hbm_rotated = {kk: v for kk, v in hbm_table(per_kernel(rotating_step, reps)).items() if kk in scan_bytes}
+    del sets
+
     # ---- the paper's six scenarios (Section VI a-f): correction rate, and the time of one
-    # protected product whose correction stage really runs (encode .. correct, median of 5) ----
+    # protected product whose correction stage really runs (encode .. correct, median of 5), with
+    # the grid code and in single-checksum mode (Table 1 sets the two side by side) -------------
     MA, MB, MC = inputs.MAT_A, inputs.MAT_B, inputs.MAT_C
     scen = {"a": [MA], "b": [MB], "c": [MC], "d": [MA, MC], "e": [MB, MC], "f": [MC, MC]}
     frng = inputs.rng_for(41, 0)
@@ -122,36 +176,47 @@ def main():
         faults = inputs.draw_faults(frng, n, k, m, len(mats), w.offset_law, mats)
         cf = [(0, f.row, f.col, f.offset) for f in faults if f.matrix == MC]
         plan[name] = (faults, [(f.matrix, f.row, f.col) for f in faults], gecc.make_faults(cf, dev))
-    times = {name: [] for name in scen}
-    good = {name: True for name in scen}
-    for rnd in range(6):            # pass 0 untimed: it loads the kernels of the staged calls
-        if rnd == 1:                # ... and the chip needs a few products to be back at its steady clock
-            for _ in range(args.warmup):
-                ctx.plain_gemm(dA, dB, Cd)
-        for name in scen:
-            faults, want, (fl, nf) = plan[name]
-            ev0.record()
-            ctx.encode_a(dA, A_par)
-            ctx.encode_b(dB, B_par)
-            for f in faults:        # E1/E2 strike after encoding (tiny torch kernels inside the timed span); E3 inside the product
-                if f.matrix != MC:
-                    T, tr = (dA, w.trans_a) if f.matrix == MA else (dB, w.trans_b)
-                    i, j = (f.col, f.row) if tr else (f.row, f.col)
-                    T[0, i, j] += f.offset
-            ctx.multiply(dA, A_par, dB, B_par, Cd, C_par, fl, nf)
-            ctx.verify(Cd, C_par, rep, fused=True)
-            ctx.correct(dA, A_par, dB, B_par, Cd, C_par, rep)
-            ev1.record()
-            r = ctx.report_to_host(rep)[0]
-            if rnd > 0:
-                times[name].append(ev0.elapsed_time(ev1))
-            got = [(e[0], e[1], e[2]) for e in r.errors()]
-            restored = bool(torch.equal(dA, Aclean) and torch.equal(dB, Bclean))
-            good[name] = good[name] and r.status == gecc.CORRECTED and got == sorted(want) and restored
-            dA.copy_(Aclean)
-            dB.copy_(Bclean)
+    single_tau = gecc.Thresholds(w.tau.r1, w.tau.r2, w.tau.q1, w.tau.q2, w.tau.op, w.tau.rep, w.tau.rel, weighted=False)
+    ctx1 = gecc.Context(n, k, m, gecc.BF16 if w.dtype == "bf16" else gecc.F32, single_tau, batch=batch,
+                        trans_a=w.trans_a, trans_b=w.trans_b)
+    STATUS = {gecc.CLEAN: "clean", gecc.CORRECTED: "corrected", gecc.UNCORRECTABLE: "uncorrectable", gecc.DETECTED: "detected"}
+
+    def run_scenarios(cx):
+        times = {name: [] for name in scen}
+        good = {name: True for name in scen}
+        status = {}
+        for rnd in range(6):            # pass 0 untimed: it loads the kernels of the staged calls
+            if rnd == 1:                # ... and the chip needs a few products to be back at its steady clock
+                for _ in range(args.warmup):
+                    cx.plain_gemm(dA, dB, Cd)
+            for name in scen:
+                faults, want, (fl, nf) = plan[name]
+                ev0.record()
+                cx.encode_a(dA, A_par)
+                cx.encode_b(dB, B_par)
+                for f in faults:        # E1/E2 strike after encoding (tiny torch kernels inside the timed span); E3 inside the product
+                    if f.matrix != MC:
+                        T, tr = (dA, w.trans_a) if f.matrix == MA else (dB, w.trans_b)
+                        i, j = (f.col, f.row) if tr else (f.row, f.col)
+                        T[0, i, j] += f.offset
+                cx.multiply(dA, A_par, dB, B_par, Cd, C_par, fl, nf)
+                cx.verify(Cd, C_par, rep, fused=True)
+                cx.correct(dA, A_par, dB, B_par, Cd, C_par, rep)
+                ev1.record()
+                r = cx.report_to_host(rep)[0]
+                if rnd > 0:
+                    times[name].append(ev0.elapsed_time(ev1))
+                got = [(e[0], e[1], e[2]) for e in r.errors()]
+                restored = bool(torch.equal(dA, Aclean) and torch.equal(dB, Bclean))
+                good[name] = good[name] and r.status == gecc.CORRECTED and got == sorted(want) and restored
+                status[name] = STATUS[r.status]
+                dA.copy_(Aclean)
+                dB.copy_(Bclean)
+        return good, {name: round(float(np.median(t)), 4) for name, t in times.items()}, status
+
+    good, scen_ms, _ = run_scenarios(ctx)
+    good1, scen_ms1, status1 = run_scenarios(ctx1)
     n_tot, n_ok = len(scen), sum(int(v) for v in good.values())
-    scen_ms = {name: round(float(np.median(t)), 4) for name, t in times.items()}
 
     flops = w.flops
     value = flops / (ms_step * 1e-3) / 1e12
@@ -173,6 +238,12 @@ def main():
         "correction_rate": {"scenarios": "a,b,c,d,e,f (Section VI)", "corrected": n_ok, "trials": n_tot},
         "scenario_ms": scen_ms,
         "scenario_overhead_pct": {kk: round((vv / ms_plain - 1.0) * 100.0, 1) for kk, vv in scen_ms.items()},
+        "single_checksum_mode": {"corrected": sum(int(v) for v in good1.values()), "trials": n_tot, "status": status1,
+                                 "scenario_ms": scen_ms1,
+                                 "scenario_overhead_pct": {kk: round((vv / ms_plain - 1.0) * 100.0, 1) for kk, vv in scen_ms1.items()}},
+        "hbm_rooflines": {"peak_GBs": HBM_PEAK_GBS,
+                          "steady_loop": hbm_steady,       # as in the timed steps: operands may sit in the memory-side cache
+                          "operands_rotated": hbm_rotated},  # three operand sets in turn: every first read comes from HBM
         "roofline": {"bound": "mfma", "kernel": ("gemm_bf16_256" if w.dtype == "bf16" and min(n, m) >= 256 and k % 64 == 0 else "gemm_kernel") + " (data block + fused syndrome partials)",
                      "achieved": round(achieved, 3) if achieved else None, "peak": peak, "unit": "TFLOP/s",
                      "frac": round(achieved / peak, 4) if achieved else None,
@@ -196,8 +267,16 @@ def main():
             cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
         except Exception:
             cores = os.cpu_count()
+        cpu_model = "unknown"
+        try:
+            for line in open("/proc/cpuinfo"):
+                if line.startswith("model name"):
+                    cpu_model = line.split(":", 1)[1].strip()
+                    break
+        except OSError:
+            pass
         out["cpu_baseline"] = {"value": round(2.0 * rows * k * m / dt / 1e12, 4), "unit": "TFLOP/s",
-                               "cores": cores, "kind": "oracle",
+                               "cores": cores, "cpu": cpu_model, "kind": "oracle",
                                "sample": "oracle.protected_gemm (fp64 numpy: encode, product, syndromes, "
                                          "decode) on the first %d of %d rows of A times the full B, "
                                          "batch item 0, no faults, %.1f s" % (rows, n, dt),

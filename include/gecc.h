@@ -15,7 +15,8 @@
  *     the library allocates no device memory and frees none.
  *   - All work is enqueued on the HIP stream handed in (a hipStream_t passed
  *     as void*; NULL = the default stream).  No call synchronises except
- *     gecc_report_to_host.
+ *     gecc_report_to_host, gecc_syndromes_to_host, gecc_timing_read and
+ *     gecc_protected_gemm_retry (which reads its reports back after every attempt).
  *   - Return value: 0 = ok, negative = usage or HIP error (see
  *     gecc_strerror); nothing throws or aborts.  The outcome of decoding
  *     travels in gecc_report.status, not in the return value.
@@ -245,13 +246,32 @@ int gecc_report_to_host(gecc_ctx* ctx, const gecc_report* dev_report, gecc_repor
    an operand error has moved them to the syndromes of the repaired C-bar. */
 int gecc_syndromes_to_host(gecc_ctx* ctx, double* host_syndromes, void* stream);
 
-/* Timing of the product kernel (the kernel of gecc_multiply / gecc_plain_gemm that holds all
-   the flops), for roofline reports.  gecc_timing_enable(ctx, r) with r > 0 makes the next r
-   product launches record a HIP event pair on their stream (host objects only, no device
-   memory); r = 0 disables and frees them.  gecc_timing_read waits for the recorded pairs,
-   writes their durations in milliseconds to host_ms[0..*count) (at most cap) and rearms. */
-int gecc_timing_enable(gecc_ctx* ctx, int32_t max_records);
-int gecc_timing_read(gecc_ctx* ctx, float* host_ms, int32_t cap, int32_t* count);
+/* Per-launch timing, for roofline reports.  Every kernel launch of the library belongs to one of
+   the classes below.  gecc_timing_enable(ctx, r, mask) with r > 0 makes the next r launches whose
+   class has its bit set in mask (bit GECC_K_x) record a HIP event pair on their stream (host
+   objects only, no device memory); r = 0 disables and frees them.  gecc_timing_read waits for the
+   recorded pairs, writes their durations in milliseconds to host_ms[0..*count) and their classes
+   to host_kind[0..*count) (at most cap each; host_kind may be null) and rearms.  The product
+   class brackets everything gecc_multiply's product step enqueues (the k-split tail's zeroing
+   and second launch included); a row scan that carries the second stage of a column scan is
+   timed with it. */
+enum {
+  GECC_K_ENCODE_A = 0,  /* A_P = [P_n1; P_n2] A                          */
+  GECC_K_ENCODE_B = 1,  /* B_P = B [P_m1^T P_m2^T]                       */
+  GECC_K_PARITY_R = 2,  /* P_r = A B_P                                   */
+  GECC_K_PARITY_C = 3,  /* P_c = A_P B                                   */
+  GECC_K_PRODUCT = 4,   /* data block C (+ fused partial sums, P_g)      */
+  GECC_K_THRESHOLD = 5, /* partial sums -> syndromes -> flags            */
+  GECC_K_DECODE = 6,    /* report / Section V step 2                     */
+  GECC_K_AUDIT_A = 7,   /* gated re-encoding of A                        */
+  GECC_K_AUDIT_B = 8,   /* gated re-encoding of B                        */
+  GECC_K_REPAIR = 9,    /* gated operand repair + second pass            */
+  GECC_K_PARTIALS = 10, /* stand-alone partial sums of a C in memory     */
+  GECC_K_STAGE2 = 11,   /* second stage of a column scan, launched alone */
+  GECC_K_COUNT = 12
+};
+int gecc_timing_enable(gecc_ctx* ctx, int32_t max_records, uint32_t kinds_mask);
+int gecc_timing_read(gecc_ctx* ctx, float* host_ms, int32_t* host_kind, int32_t cap, int32_t* count);
 
 const char* gecc_strerror(int code);
 

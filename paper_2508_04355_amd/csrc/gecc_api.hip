@@ -82,12 +82,37 @@ ScanArgs scan_base(const gecc_ctx* c, const void* X, int64_t ld, int64_t xs) {
 struct ScanJob {
   ScanArgs s;
   bool rowdot;
+  int kind;   // GECC_K_x, for the timing records
+};
+
+// Brackets the launches between its construction and done() with a timing record, when the
+// context records launches of that class.
+struct Timed {
+  gecc_ctx* c;
+  hipStream_t st;
+  int kind;
+  bool on;
+  hipError_t err;
+  Timed(gecc_ctx* ctx, int k, hipStream_t s) : c(ctx), st(s), kind(k), err(hipSuccess) {
+    on = c->ev && ((c->ev_mask >> k) & 1u) && c->ev_n < c->ev_cap;
+    if (on) err = hipEventRecord(c->ev[2 * c->ev_n], st);
+  }
+  hipError_t done(hipError_t launch_result) {
+    if (launch_result != hipSuccess) return launch_result;
+    if (err != hipSuccess) return err;
+    if (on) {
+      if ((err = hipEventRecord(c->ev[2 * c->ev_n + 1], st)) != hipSuccess) return err;
+      c->ev_kind[c->ev_n] = kind;
+      ++c->ev_n;
+    }
+    return hipSuccess;
+  }
 };
 
 // reduce A over its row index i (length n) -> [2][k]; w = null: Section III's index weights
 ScanJob scan_a_over_n(gecc_ctx* c, const void* A, const double* w, double* out, const int32_t* gate) {
   const gecc_params& p = c->p;
-  ScanJob j{scan_base(c, A, p.lda, p.stride_a), p.trans_a != 0};
+  ScanJob j{scan_base(c, A, p.lda, p.stride_a), p.trans_a != 0, gate ? GECC_K_AUDIT_A : GECC_K_ENCODE_A};
   ScanArgs& s = j.s;
   s.w = w; s.out = out; s.w_stride = 2 * (int64_t)p.n; s.out_stride = 2 * (int64_t)p.k;
   if (gate) { s.gate = gate; s.gate_stride = sizeof(DecodeState); s.gate_value = PH_AUDIT; }
@@ -98,7 +123,7 @@ ScanJob scan_a_over_n(gecc_ctx* c, const void* A, const double* w, double* out, 
 // reduce A over its column index l (length k) -> [2][n]
 ScanJob scan_a_over_k(gecc_ctx* c, const void* A, const double* w, double* out, int64_t out_stride) {
   const gecc_params& p = c->p;
-  ScanJob j{scan_base(c, A, p.lda, p.stride_a), p.trans_a == 0};
+  ScanJob j{scan_base(c, A, p.lda, p.stride_a), p.trans_a == 0, GECC_K_PARITY_R};
   ScanArgs& s = j.s;
   s.w = w; s.out = out; s.w_stride = 2 * (int64_t)p.k; s.out_stride = out_stride;
   if (p.trans_a) { s.R = p.k; s.Cc = p.n; s.scratch = reinterpret_cast<double*>(c->ws + c->lay.scan_a); }
@@ -108,7 +133,7 @@ ScanJob scan_a_over_k(gecc_ctx* c, const void* A, const double* w, double* out, 
 // reduce B over its column index j (length m) -> [2][k]
 ScanJob scan_b_over_m(gecc_ctx* c, const void* B, const double* w, double* out, const int32_t* gate) {
   const gecc_params& p = c->p;
-  ScanJob j{scan_base(c, B, p.ldb, p.stride_b), p.trans_b == 0};
+  ScanJob j{scan_base(c, B, p.ldb, p.stride_b), p.trans_b == 0, gate ? GECC_K_AUDIT_B : GECC_K_ENCODE_B};
   ScanArgs& s = j.s;
   s.w = w; s.out = out; s.w_stride = 2 * (int64_t)p.m; s.out_stride = 2 * (int64_t)p.k;
   if (gate) { s.gate = gate; s.gate_stride = sizeof(DecodeState); s.gate_value = PH_AUDIT; }
@@ -119,7 +144,7 @@ ScanJob scan_b_over_m(gecc_ctx* c, const void* B, const double* w, double* out, 
 // reduce B over its row index l (length k) -> [2][m]
 ScanJob scan_b_over_k(gecc_ctx* c, const void* B, const double* w, double* out, int64_t out_stride) {
   const gecc_params& p = c->p;
-  ScanJob j{scan_base(c, B, p.ldb, p.stride_b), p.trans_b != 0};
+  ScanJob j{scan_base(c, B, p.ldb, p.stride_b), p.trans_b != 0, GECC_K_PARITY_C};
   ScanArgs& s = j.s;
   s.w = w; s.out = out; s.w_stride = 2 * (int64_t)p.k; s.out_stride = out_stride;
   if (p.trans_b) { s.R = p.m; s.Cc = p.k; }
@@ -131,12 +156,14 @@ ScanJob scan_b_over_k(gecc_ctx* c, const void* B, const double* w, double* out, 
 // the same launch unless it reads that stage's output (or is gated differently); anything else
 // flushes it first.  The caller flushes before the results are needed.
 struct ScanQueue {
+  gecc_ctx* c;
   hipStream_t st;
   Stage2Job pending{};
   hipError_t flush() {
     if (!pending.valid) return hipSuccess;
     pending.valid = false;
-    return launch_stage2(pending, st);
+    Timed t(c, GECC_K_STAGE2, st);
+    return t.done(launch_stage2(pending, st));
   }
   hipError_t run(const ScanJob& j) {
     hipError_t e;
@@ -145,12 +172,13 @@ struct ScanQueue {
                            s.gate == pending.gate && s.gate_stride == pending.gate_stride &&
                            s.gate_value == pending.gate_value;
     if (pending.valid && !can_carry && (e = flush()) != hipSuccess) return e;
+    Timed t(c, j.kind, st);
     if (j.rowdot) {
       e = launch_rowdot(s, can_carry ? &pending : nullptr, st);
       pending.valid = false;
-      return e;
+      return t.done(e);
     }
-    return launch_coldot_stage1(s, &pending, st);
+    return t.done(launch_coldot_stage1(s, &pending, st));
   }
 };
 
@@ -185,17 +213,10 @@ GemmArgs gemm_args(const gecc_ctx* c, const void* A, const void* B, float* C) {
   return g;
 }
 
-// the product kernel, bracketed by a timing record when timing is enabled
+// the product kernel(s), bracketed by a timing record when timing is enabled
 hipError_t timed_gemm(gecc_ctx* c, const GemmArgs& g, hipStream_t st) {
-  const bool rec = c->ev && c->ev_n < c->ev_cap;
-  hipError_t e;
-  if (rec && (e = hipEventRecord(c->ev[2 * c->ev_n], st)) != hipSuccess) return e;
-  if ((e = launch_gemm(g, st)) != hipSuccess) return e;
-  if (rec) {
-    if ((e = hipEventRecord(c->ev[2 * c->ev_n + 1], st)) != hipSuccess) return e;
-    ++c->ev_n;
-  }
-  return hipSuccess;
+  Timed t(c, GECC_K_PRODUCT, st);
+  return t.done(launch_gemm(g, st));
 }
 
 }  // namespace
@@ -241,6 +262,8 @@ int gecc_create(gecc_ctx** out, const gecc_params* p) {
   c->ws = nullptr;
   c->ws_bytes = 0;
   c->ev = nullptr;
+  c->ev_kind = nullptr;
+  c->ev_mask = 0;
   c->ev_cap = 0;
   c->ev_n = 0;
   make_layout(c);
@@ -250,37 +273,47 @@ int gecc_create(gecc_ctx** out, const gecc_params* p) {
 
 void gecc_destroy(gecc_ctx* ctx) {
   if (!ctx) return;
-  gecc_timing_enable(ctx, 0);
+  gecc_timing_enable(ctx, 0, 0);
   delete ctx;
 }
 
-int gecc_timing_enable(gecc_ctx* ctx, int32_t max_records) {
+int gecc_timing_enable(gecc_ctx* ctx, int32_t max_records, uint32_t kinds_mask) {
   if (!ctx || max_records < 0) return GECC_ERR_ARG;
   for (int i = 0; i < 2 * ctx->ev_cap; ++i) (void)hipEventDestroy(ctx->ev[i]);
   delete[] ctx->ev;
+  delete[] ctx->ev_kind;
   ctx->ev = nullptr;
+  ctx->ev_kind = nullptr;
   ctx->ev_cap = 0;
   ctx->ev_n = 0;
+  ctx->ev_mask = 0;
   if (max_records == 0) return GECC_OK;
   ctx->ev = new (std::nothrow) hipEvent_t[2 * (size_t)max_records];
-  if (!ctx->ev) return GECC_ERR_ARG;
+  ctx->ev_kind = new (std::nothrow) int32_t[(size_t)max_records];
+  if (!ctx->ev || !ctx->ev_kind) {
+    delete[] ctx->ev; delete[] ctx->ev_kind;
+    ctx->ev = nullptr; ctx->ev_kind = nullptr;
+    return GECC_ERR_ARG;
+  }
   for (int i = 0; i < 2 * max_records; ++i)
     if (hipEventCreate(&ctx->ev[i]) != hipSuccess) {
       for (int j = 0; j < i; ++j) (void)hipEventDestroy(ctx->ev[j]);
-      delete[] ctx->ev;
-      ctx->ev = nullptr;
+      delete[] ctx->ev; delete[] ctx->ev_kind;
+      ctx->ev = nullptr; ctx->ev_kind = nullptr;
       return GECC_ERR_HIP;
     }
   ctx->ev_cap = max_records;
+  ctx->ev_mask = kinds_mask;
   return GECC_OK;
 }
 
-int gecc_timing_read(gecc_ctx* ctx, float* host_ms, int32_t cap, int32_t* count) {
+int gecc_timing_read(gecc_ctx* ctx, float* host_ms, int32_t* host_kind, int32_t cap, int32_t* count) {
   if (!ctx || !host_ms || !count || cap < 0) return GECC_ERR_ARG;
   const int n = ctx->ev_n < cap ? ctx->ev_n : cap;
   for (int i = 0; i < n; ++i) {
     if (hipEventSynchronize(ctx->ev[2 * i + 1]) != hipSuccess) return GECC_ERR_HIP;
     if (hipEventElapsedTime(&host_ms[i], ctx->ev[2 * i], ctx->ev[2 * i + 1]) != hipSuccess) return GECC_ERR_HIP;
+    if (host_kind) host_kind[i] = ctx->ev_kind[i];
   }
   *count = n;
   ctx->ev_n = 0;
@@ -309,7 +342,7 @@ int gecc_encode_a(gecc_ctx* ctx, const void* dev_A, double* dev_A_par, void* str
   if (rc) return rc;
   if (!dev_A || !dev_A_par) return GECC_ERR_ARG;
   if (!aligned_to(dev_A, elem_size(ctx->p.dtype)) || !aligned_to(dev_A_par, 8)) return GECC_ERR_ALIGN;
-  ScanQueue q{(hipStream_t)stream};
+  ScanQueue q{ctx, (hipStream_t)stream};
   hipError_t e = q.run(scan_a_over_n(ctx, dev_A, nullptr, dev_A_par, nullptr));
   return hip_rc(e != hipSuccess ? e : q.flush());
 }
@@ -319,7 +352,7 @@ int gecc_encode_b(gecc_ctx* ctx, const void* dev_B, double* dev_B_par, void* str
   if (rc) return rc;
   if (!dev_B || !dev_B_par) return GECC_ERR_ARG;
   if (!aligned_to(dev_B, elem_size(ctx->p.dtype)) || !aligned_to(dev_B_par, 8)) return GECC_ERR_ALIGN;
-  ScanQueue q{(hipStream_t)stream};
+  ScanQueue q{ctx, (hipStream_t)stream};
   hipError_t e = q.run(scan_b_over_m(ctx, dev_B, nullptr, dev_B_par, nullptr));
   return hip_rc(e != hipSuccess ? e : q.flush());
 }
@@ -367,7 +400,7 @@ int gecc_multiply(gecc_ctx* ctx, const void* dev_A, const double* dev_A_par, con
   int rc = check_multiply_args(ctx, dev_A, dev_A_par, dev_B, dev_B_par, dev_C, dev_C_par, dev_faults, n_faults);
   if (rc) return rc;
   hipStream_t st = (hipStream_t)stream;
-  ScanQueue q{st};
+  ScanQueue q{ctx, st};
   hipError_t e;
   if ((e = parity_products(ctx, q, dev_A, dev_A_par, dev_B, dev_B_par, dev_C_par)) != hipSuccess) return hip_rc(e);
   if ((e = q.flush()) != hipSuccess) return hip_rc(e);
@@ -384,7 +417,10 @@ int verify_impl(gecc_ctx* ctx, const float* dev_C, const double* dev_C_par, gecc
   hipError_t e;
   if (!fused) {
     // (the fused path had its state reset by gecc_multiply)
-    if ((e = launch_reset_state(d, st)) != hipSuccess) return hip_rc(e);
+    {
+      Timed t(ctx, GECC_K_DECODE, st);
+      if ((e = t.done(launch_reset_state(d, st))) != hipSuccess) return hip_rc(e);
+    }
     const gecc_params& p = ctx->p;
     PartialArgs pa{};
     pa.C = dev_C; pa.n = p.n; pa.m = p.m; pa.batch = p.batch; pa.ldc = p.ldc; pa.sc = p.stride_c;
@@ -392,10 +428,16 @@ int verify_impl(gecc_ctx* ctx, const float* dev_C, const double* dev_C_par, gecc
     pa.tile_m = ctx->tile_m; pa.tile_n = ctx->tile_n; pa.ntm = ctx->ntm; pa.ntn = ctx->ntn;
     pa.rp_ld = ctx->rp_ld; pa.cp_ld = ctx->cp_ld;
     pa.gate = nullptr;
-    if ((e = launch_partials(pa, st)) != hipSuccess) return hip_rc(e);
+    Timed t(ctx, GECC_K_PARTIALS, st);
+    if ((e = t.done(launch_partials(pa, st))) != hipSuccess) return hip_rc(e);
   }
-  if ((e = launch_threshold(d, st)) != hipSuccess) return hip_rc(e);
-  return summary ? hip_rc(launch_summarize(d, st)) : GECC_OK;
+  {
+    Timed t(ctx, GECC_K_THRESHOLD, st);
+    if ((e = t.done(launch_threshold(d, st))) != hipSuccess) return hip_rc(e);
+  }
+  if (!summary) return GECC_OK;
+  Timed t(ctx, GECC_K_DECODE, st);
+  return hip_rc(t.done(launch_summarize(d, st)));
 }
 
 // S6 + S7.  with_summary = 1: the first decoder pass also writes the first report.
@@ -405,10 +447,13 @@ int correct_impl(gecc_ctx* ctx, void* dev_A, const double* dev_A_par, void* dev_
   const int32_t* gate = &d.state->phase;
   hipError_t e;
   // Section V step 2 on the flagged lines; on failure the phase becomes PH_AUDIT
-  if ((e = launch_decode_c(d, with_summary, st)) != hipSuccess) return hip_rc(e);
+  {
+    Timed t(ctx, GECC_K_DECODE, st);
+    if ((e = t.done(launch_decode_c(d, with_summary, st))) != hipSuccess) return hip_rc(e);
+  }
   // operand audit: re-form the parities of A and B as the product read them
   // (the coldot of the two first, so that the rowdot carries its second stage)
-  ScanQueue q{st};
+  ScanQueue q{ctx, st};
   const ScanJob ja = scan_a_over_n(ctx, dev_A, nullptr, const_cast<double*>(d.audit_a), gate);
   const ScanJob jb = scan_b_over_m(ctx, dev_B, nullptr, const_cast<double*>(d.audit_b), gate);
   const bool b_first = ja.rowdot && !jb.rowdot;
@@ -417,7 +462,8 @@ int correct_impl(gecc_ctx* ctx, void* dev_A, const double* dev_A_par, void* dev_
   if ((e = q.flush()) != hipSuccess) return hip_rc(e);
   // parity differences, operand patches, rank-one repair of C-bar with the residual syndromes
   // kept up to date, then Section V once more -- all in one workgroup per batch item
-  return hip_rc(launch_repair(d, st));
+  Timed t(ctx, GECC_K_REPAIR, st);
+  return hip_rc(t.done(launch_repair(d, st)));
 }
 
 }  // namespace
@@ -443,7 +489,7 @@ int encode_and_multiply(gecc_ctx* ctx, void* dev_A, void* dev_B, float* dev_C, d
   if (!p.trans_a) { order[0] = &ea; order[1] = &eb; order[2] = &pc; order[3] = &pr; }
   else if (!p.trans_b) { order[0] = &eb; order[1] = &pr; order[2] = &ea; order[3] = &pc; }
   else { order[0] = &eb; order[1] = &ea; order[2] = &pr; order[3] = &pc; }
-  ScanQueue q{st};
+  ScanQueue q{ctx, st};
   hipError_t e;
   for (int x = 0; x < 4; ++x)
     if ((e = q.run(*order[x])) != hipSuccess) return hip_rc(e);

@@ -59,7 +59,9 @@ struct gecc_ctx {
   int cu_hint;             // GECC_CU_COUNT (tests: plan the tile rounds as for that many CUs), else 0
   char* ws;                // device workspace (caller's)
   size_t ws_bytes;
-  hipEvent_t* ev;          // optional timing records around the product kernel (start, stop pairs)
+  hipEvent_t* ev;          // optional timing records around kernel launches (start, stop pairs)
+  int32_t* ev_kind;        // class (GECC_K_x) of each record
+  uint32_t ev_mask;        // classes that are recorded
   int ev_cap, ev_n;
 };
 

@@ -80,14 +80,16 @@ constexpr int RD_BIG_RB_W = 8;   // with explicit weights (they take registers t
 // steps are taken together, so that a thread has RD_RB * RD_U independent 16-byte loads in
 // flight before the first of them is used (the kernel is a stream over the operand: what it
 // needs is memory-level parallelism, the arithmetic hides behind it).
-template <int DT, bool IDXW, int RD_RB, int RD_U>
+// GATED: the launch belongs to the operand audit and returns at once unless the decoder asked for
+// it (a separate instantiation, so that profiles list encoding and audit launches apart).
+template <int DT, bool IDXW, int RD_RB, int RD_U, bool GATED>
 __global__ __launch_bounds__(RD_THREADS) void rowdot_kernel(ScanArgs a) {
   using E = Elem<DT>;
   using T = typename E::type;
   constexpr int VEC = E::VEC;
   constexpr int STEP = RD_THREADS * VEC;   // columns one pass of the workgroup covers
   const int b = blockIdx.y;
-  if (gated_off(a.gate, a.gate_stride, b, a.gate_value)) return;
+  if (GATED && gated_off(a.gate, a.gate_stride, b, a.gate_value)) return;
   const int own = (int)gridDim.x - a.carry_blocks;
   if ((int)blockIdx.x >= own) {   // carried second stage of an earlier coldot
     coldot_stage2_body(a.carry_scratch + (int64_t)b * a.carry_nchunk * 2 * a.carry_Cc,
@@ -204,13 +206,13 @@ __global__ __launch_bounds__(RD_THREADS) void rowdot_kernel(ScanArgs a) {
 // LDS.  Stage 2 adds the chunks in order.
 constexpr int CD_THREADS = 256;
 
-template <int DT, bool IDXW>
+template <int DT, bool IDXW, bool GATED>
 __global__ __launch_bounds__(CD_THREADS) void coldot_stage1(ScanArgs a, int nchunk) {
   using E = Elem<DT>;
   using T = typename E::type;
   constexpr int VEC = E::VEC;
   const int b = blockIdx.z;
-  if (gated_off(a.gate, a.gate_stride, b, a.gate_value)) return;
+  if (GATED && gated_off(a.gate, a.gate_stride, b, a.gate_value)) return;
   const T* X = reinterpret_cast<const T*>(a.X) + (int64_t)b * a.xs;
   const double* w0 = IDXW ? nullptr : a.w + (int64_t)b * a.w_stride;
   const double* w1 = IDXW ? nullptr : w0 + a.R;
@@ -343,20 +345,26 @@ hipError_t launch_rowdot(const ScanArgs& a0, const Stage2Job* carry, hipStream_t
   const int extra = a.carry_blocks;
   const bool idx = a.w == nullptr;
   const bool small = (int64_t)((a.R + RD_BIG_RB - 1) / RD_BIG_RB) * a.batch < 1024;   // fewer than 4 workgroups per CU
-#define GECC_LAUNCH_ROWDOT(DT, IDX)                                                                  \
+  const bool gated = a.gate != nullptr;   // audits only, and audits use the index weights
+#define GECC_LAUNCH_ROWDOT(DT, IDX, G)                                                               \
   do {                                                                                              \
     constexpr int BIG = IDX ? RD_BIG_RB : RD_BIG_RB_W;                                                \
-    if (small) hipLaunchKernelGGL((rowdot_kernel<DT, IDX, RD_SMALL_RB, RD_SMALL_U>),                  \
+    if (small) hipLaunchKernelGGL((rowdot_kernel<DT, IDX, RD_SMALL_RB, RD_SMALL_U, G>),               \
                                   dim3((a.R + RD_SMALL_RB - 1) / RD_SMALL_RB + extra, a.batch),       \
                                   dim3(RD_THREADS), 0, st, a);                                        \
-    else       hipLaunchKernelGGL((rowdot_kernel<DT, IDX, BIG, RD_BIG_U>),                            \
+    else       hipLaunchKernelGGL((rowdot_kernel<DT, IDX, BIG, RD_BIG_U, G>),                         \
                                   dim3((a.R + BIG - 1) / BIG + extra, a.batch),                       \
                                   dim3(RD_THREADS), 0, st, a);                                        \
   } while (0)
+  if (gated && !idx) return hipErrorInvalidValue;
   if (a.dtype == GECC_BF16) {
-    if (idx) GECC_LAUNCH_ROWDOT(GECC_BF16, true); else GECC_LAUNCH_ROWDOT(GECC_BF16, false);
+    if (gated) GECC_LAUNCH_ROWDOT(GECC_BF16, true, true);
+    else if (idx) GECC_LAUNCH_ROWDOT(GECC_BF16, true, false);
+    else GECC_LAUNCH_ROWDOT(GECC_BF16, false, false);
   } else {
-    if (idx) GECC_LAUNCH_ROWDOT(GECC_F32, true); else GECC_LAUNCH_ROWDOT(GECC_F32, false);
+    if (gated) GECC_LAUNCH_ROWDOT(GECC_F32, true, true);
+    else if (idx) GECC_LAUNCH_ROWDOT(GECC_F32, true, false);
+    else GECC_LAUNCH_ROWDOT(GECC_F32, false, false);
   }
 #undef GECC_LAUNCH_ROWDOT
   return hipGetLastError();
@@ -369,13 +377,16 @@ hipError_t launch_coldot_stage1(const ScanArgs& a0, Stage2Job* pending, hipStrea
   const int vec = a.dtype == GECC_BF16 ? 8 : 4;
   const int nchunk = (a.R + SCAN_CHUNK_ROWS - 1) / SCAN_CHUNK_ROWS;
   dim3 grid((a.Cc + 64 * vec - 1) / (64 * vec), nchunk, a.batch);
-  const bool idx = a.w == nullptr;
+  const bool idx = a.w == nullptr, gated = a.gate != nullptr;
+  if (gated && !idx) return hipErrorInvalidValue;
   if (a.dtype == GECC_BF16) {
-    if (idx) hipLaunchKernelGGL((coldot_stage1<GECC_BF16, true>), grid, dim3(CD_THREADS), 0, st, a, nchunk);
-    else     hipLaunchKernelGGL((coldot_stage1<GECC_BF16, false>), grid, dim3(CD_THREADS), 0, st, a, nchunk);
+    if (gated)    hipLaunchKernelGGL((coldot_stage1<GECC_BF16, true, true>), grid, dim3(CD_THREADS), 0, st, a, nchunk);
+    else if (idx) hipLaunchKernelGGL((coldot_stage1<GECC_BF16, true, false>), grid, dim3(CD_THREADS), 0, st, a, nchunk);
+    else          hipLaunchKernelGGL((coldot_stage1<GECC_BF16, false, false>), grid, dim3(CD_THREADS), 0, st, a, nchunk);
   } else {
-    if (idx) hipLaunchKernelGGL((coldot_stage1<GECC_F32, true>), grid, dim3(CD_THREADS), 0, st, a, nchunk);
-    else     hipLaunchKernelGGL((coldot_stage1<GECC_F32, false>), grid, dim3(CD_THREADS), 0, st, a, nchunk);
+    if (gated)    hipLaunchKernelGGL((coldot_stage1<GECC_F32, true, true>), grid, dim3(CD_THREADS), 0, st, a, nchunk);
+    else if (idx) hipLaunchKernelGGL((coldot_stage1<GECC_F32, true, false>), grid, dim3(CD_THREADS), 0, st, a, nchunk);
+    else          hipLaunchKernelGGL((coldot_stage1<GECC_F32, false, false>), grid, dim3(CD_THREADS), 0, st, a, nchunk);
   }
   pending->valid = true;
   pending->scratch = a.scratch; pending->out = a.out; pending->out_stride = a.out_stride;

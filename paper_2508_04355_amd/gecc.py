@@ -16,6 +16,11 @@ F32, BF16 = 0, 1
 CLEAN, CORRECTED, UNCORRECTABLE, DETECTED = 0, 1, 2, 3
 MAT_A, MAT_B, MAT_C = 0, 1, 2
 MAX_ERR, MAX_FAULTS = 8, 1024
+# kernel classes of the timing records (include/gecc.h)
+(K_ENCODE_A, K_ENCODE_B, K_PARITY_R, K_PARITY_C, K_PRODUCT, K_THRESHOLD, K_DECODE, K_AUDIT_A, K_AUDIT_B,
+ K_REPAIR, K_PARTIALS, K_STAGE2) = range(12)
+K_NAMES = ["encode_a", "encode_b", "parity_r", "parity_c", "product", "threshold", "decode", "audit_a", "audit_b",
+           "repair", "partials", "stage2"]
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libgecc.so")
 
@@ -90,8 +95,8 @@ def lib():
     L.gecc_plain_gemm.argtypes = [vp, vp, vp, vp, vp]
     L.gecc_report_to_host.argtypes = [vp, vp, C.POINTER(Report), i32, vp]
     L.gecc_syndromes_to_host.argtypes = [vp, vp, vp]
-    L.gecc_timing_enable.argtypes = [vp, i32]
-    L.gecc_timing_read.argtypes = [vp, C.POINTER(C.c_float), i32, C.POINTER(i32)]
+    L.gecc_timing_enable.argtypes = [vp, i32, C.c_uint32]
+    L.gecc_timing_read.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(i32), i32, C.POINTER(i32)]
     L.gecc_strerror.argtypes = [C.c_int]
     L.gecc_strerror.restype = C.c_char_p
     for f in _SYMBOLS:
@@ -237,14 +242,20 @@ class Context:
         _check(lib().gecc_report_to_host(self._h, _ptr(report), host, self.batch, _stream()))
         return list(host)
 
-    def timing_enable(self, max_records: int):
-        _check(lib().gecc_timing_enable(self._h, max_records))
+    def timing_enable(self, max_records: int, kinds=(K_PRODUCT,)):
+        """Record an event pair around the next max_records launches of the given kernel classes."""
+        mask = 0
+        for kk in kinds:
+            mask |= 1 << kk
+        _check(lib().gecc_timing_enable(self._h, max_records, mask))
 
-    def timing_read(self, cap: int) -> List[float]:
-        buf = (C.c_float * max(cap, 1))()
+    def timing_read(self, cap: int) -> List[Tuple[int, float]]:
+        """[(kernel class, milliseconds)] of the recorded launches, in launch order."""
+        ms = (C.c_float * max(cap, 1))()
+        kinds = (C.c_int32 * max(cap, 1))()
         cnt = C.c_int32(0)
-        _check(lib().gecc_timing_read(self._h, buf, cap, C.byref(cnt)))
-        return [float(buf[i]) for i in range(cnt.value)]
+        _check(lib().gecc_timing_read(self._h, ms, kinds, cap, C.byref(cnt)))
+        return [(int(kinds[i]), float(ms[i])) for i in range(cnt.value)]
 
     def syndromes_to_host(self):
         """(batch, 2n+2m) float64 numpy array: r1, r2, q1, q2 of the last verify."""
