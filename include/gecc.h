@@ -267,8 +267,10 @@ enum {
   GECC_K_AUDIT_B = 8,   /* gated re-encoding of B                        */
   GECC_K_REPAIR = 9,    /* gated operand repair + second pass            */
   GECC_K_PARTIALS = 10, /* stand-alone partial sums of a C in memory     */
-  GECC_K_STAGE2 = 11,   /* second stage of a column scan, launched alone */
-  GECC_K_COUNT = 12
+  GECC_K_STAGE2 = 11,   /* second stage of a scan, launched alone        */
+  GECC_K_TILE_A = 12,   /* A_P and P_r in one pass over A                */
+  GECC_K_TILE_B = 13,   /* B_P and P_c in one pass over B                */
+  GECC_K_COUNT = 14
 };
 int gecc_timing_enable(gecc_ctx* ctx, int32_t max_records, uint32_t kinds_mask);
 int gecc_timing_read(gecc_ctx* ctx, float* host_ms, int32_t* host_kind, int32_t cap, int32_t* count);

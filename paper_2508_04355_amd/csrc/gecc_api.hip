@@ -35,6 +35,10 @@ void make_layout(gecc_ctx* c) {
                               : coldot_scratch_doubles(p.k, p.m, p.batch);
   L.scan_a = take(sa * sizeof(double));
   L.scan_b = take(sb * sizeof(double));
+  // the operand that gets the one-pass tile scan, as stored: rows x contiguous columns
+  const size_t ra = tile_scan_row_scratch_doubles(p.trans_a ? p.k : p.n, p.trans_a ? p.n : p.k, p.dtype, p.batch);
+  const size_t rb = tile_scan_row_scratch_doubles(p.trans_b ? p.m : p.k, p.trans_b ? p.k : p.m, p.dtype, p.batch);
+  L.scan_row = take((ra > rb ? ra : rb) * sizeof(double));
   L.total = off;
 }
 
@@ -152,6 +156,41 @@ ScanJob scan_b_over_k(gecc_ctx* c, const void* B, const double* w, double* out, 
   return j;
 }
 
+// The tile scan of operand `op` (as stored: rows x contiguous columns).  enc_out: where the
+// index-weighted reduction of Section III goes (A_P or B_P, or an audit buffer), or null;
+// par_w / par_out: weights and destination of the parity block of C-bar along the other axis
+// (P_r = A B_P or P_c = A_P B), or null.
+TileScanJob tile_job(gecc_ctx* c, int op, const void* X, double* enc_out, const double* par_w, double* par_out,
+                     int64_t par_out_stride, const int32_t* gate) {
+  const gecc_params& p = c->p;
+  const bool is_a = op == GECC_MAT_A;
+  const bool tr = is_a ? p.trans_a != 0 : p.trans_b != 0;
+  TileScanJob t{};
+  t.X = X; t.dtype = p.dtype; t.batch = p.batch;
+  t.ld = is_a ? p.lda : p.ldb;
+  t.xs = is_a ? p.stride_a : p.stride_b;
+  const int len = is_a ? p.n : p.m;                 // the axis the encoding sums over
+  t.R = is_a ? (tr ? p.k : p.n) : (tr ? p.m : p.k);
+  t.Cc = is_a ? (tr ? p.n : p.k) : (tr ? p.k : p.m);
+  (void)len;
+  // A stored n x k and B stored m x k keep the encoded axis in the rows: column part.  The other
+  // two layouts keep it in the columns: row part.
+  const bool enc_is_col = is_a ? !tr : tr;
+  t.col_scratch = reinterpret_cast<double*>(c->ws + (is_a ? c->lay.scan_a : c->lay.scan_b));
+  t.row_scratch = reinterpret_cast<double*>(c->ws + c->lay.scan_row);
+  const int64_t k2 = 2 * (int64_t)p.k;
+  if (enc_out) {
+    if (enc_is_col) { t.col_on = true; t.wr = nullptr; t.col_out = enc_out; t.col_out_stride = k2; }
+    else            { t.row_on = true; t.wc = nullptr; t.row_out = enc_out; t.row_out_stride = k2; }
+  }
+  if (par_w) {
+    if (enc_is_col) { t.row_on = true; t.wc = par_w; t.wc_stride = k2; t.row_out = par_out; t.row_out_stride = par_out_stride; }
+    else            { t.col_on = true; t.wr = par_w; t.wr_stride = k2; t.col_out = par_out; t.col_out_stride = par_out_stride; }
+  }
+  if (gate) { t.gate = gate; t.gate_stride = sizeof(DecodeState); t.gate_value = PH_AUDIT; }
+  return t;
+}
+
 // Scans in stream order.  The second stage of a coldot is held back: the next rowdot carries it in
 // the same launch unless it reads that stage's output (or is gated differently); anything else
 // flushes it first.  The caller flushes before the results are needed.
@@ -168,7 +207,8 @@ struct ScanQueue {
   hipError_t run(const ScanJob& j) {
     hipError_t e;
     const ScanArgs& s = j.s;
-    const bool can_carry = j.rowdot && pending.valid && s.w != pending.out && s.batch == pending.batch &&
+    const bool can_carry = j.rowdot && pending.valid && s.w != pending.out && s.w != pending.row_out &&
+                           s.batch == pending.batch &&
                            s.gate == pending.gate && s.gate_stride == pending.gate_stride &&
                            s.gate_value == pending.gate_value;
     if (pending.valid && !can_carry && (e = flush()) != hipSuccess) return e;
@@ -179,6 +219,13 @@ struct ScanQueue {
       return t.done(e);
     }
     return t.done(launch_coldot_stage1(s, &pending, st));
+  }
+  // a tile scan: its second stage becomes the pending one
+  hipError_t run_tile(const TileScanJob& tj, int kind) {
+    hipError_t e;
+    if (pending.valid && (e = flush()) != hipSuccess) return e;
+    Timed t(c, kind, st);
+    return t.done(launch_tile_scan(tj, &pending, st));
   }
 };
 
@@ -251,6 +298,8 @@ int gecc_create(gecc_ctx** out, const gecc_params* p) {
     c->cu_hint = e ? atoi(e) : 0;
     if (c->cu_hint < 0) c->cu_hint = 0;
   }
+  // the larger operand is read once for both of its reductions (tile scan), the other one twice
+  c->tile_op = p->n >= p->m ? GECC_MAT_A : GECC_MAT_B;
   c->tile_m = 128;
   c->tile_n = 128;
   c->ntm = (p->n + c->tile_m - 1) / c->tile_m;
@@ -343,7 +392,9 @@ int gecc_encode_a(gecc_ctx* ctx, const void* dev_A, double* dev_A_par, void* str
   if (!dev_A || !dev_A_par) return GECC_ERR_ARG;
   if (!aligned_to(dev_A, elem_size(ctx->p.dtype)) || !aligned_to(dev_A_par, 8)) return GECC_ERR_ALIGN;
   ScanQueue q{ctx, (hipStream_t)stream};
-  hipError_t e = q.run(scan_a_over_n(ctx, dev_A, nullptr, dev_A_par, nullptr));
+  const TileScanJob tj = tile_job(ctx, GECC_MAT_A, dev_A, dev_A_par, nullptr, nullptr, 0, nullptr);
+  hipError_t e = ctx->tile_op == GECC_MAT_A && tile_scan_ok(tj) ? q.run_tile(tj, GECC_K_ENCODE_A)
+                                                                : q.run(scan_a_over_n(ctx, dev_A, nullptr, dev_A_par, nullptr));
   return hip_rc(e != hipSuccess ? e : q.flush());
 }
 
@@ -353,7 +404,9 @@ int gecc_encode_b(gecc_ctx* ctx, const void* dev_B, double* dev_B_par, void* str
   if (!dev_B || !dev_B_par) return GECC_ERR_ARG;
   if (!aligned_to(dev_B, elem_size(ctx->p.dtype)) || !aligned_to(dev_B_par, 8)) return GECC_ERR_ALIGN;
   ScanQueue q{ctx, (hipStream_t)stream};
-  hipError_t e = q.run(scan_b_over_m(ctx, dev_B, nullptr, dev_B_par, nullptr));
+  const TileScanJob tj = tile_job(ctx, GECC_MAT_B, dev_B, dev_B_par, nullptr, nullptr, 0, nullptr);
+  hipError_t e = ctx->tile_op == GECC_MAT_B && tile_scan_ok(tj) ? q.run_tile(tj, GECC_K_ENCODE_B)
+                                                                : q.run(scan_b_over_m(ctx, dev_B, nullptr, dev_B_par, nullptr));
   return hip_rc(e != hipSuccess ? e : q.flush());
 }
 
@@ -453,12 +506,21 @@ int correct_impl(gecc_ctx* ctx, void* dev_A, const double* dev_A_par, void* dev_
   }
   // operand audit: re-form the parities of A and B as the product read them
   // (the coldot of the two first, so that the rowdot carries its second stage)
+  // (an encoding made by the tile scan is re-formed by the tile scan: same sums, same order)
   ScanQueue q{ctx, st};
   const ScanJob ja = scan_a_over_n(ctx, dev_A, nullptr, const_cast<double*>(d.audit_a), gate);
   const ScanJob jb = scan_b_over_m(ctx, dev_B, nullptr, const_cast<double*>(d.audit_b), gate);
-  const bool b_first = ja.rowdot && !jb.rowdot;
-  if ((e = q.run(b_first ? jb : ja)) != hipSuccess) return hip_rc(e);
-  if ((e = q.run(b_first ? ja : jb)) != hipSuccess) return hip_rc(e);
+  const bool t_is_a = ctx->tile_op == GECC_MAT_A;
+  const TileScanJob tj = tile_job(ctx, ctx->tile_op, t_is_a ? dev_A : dev_B,
+                                  const_cast<double*>(t_is_a ? d.audit_a : d.audit_b), nullptr, nullptr, 0, gate);
+  if (tile_scan_ok(tj)) {
+    if ((e = q.run_tile(tj, t_is_a ? GECC_K_AUDIT_A : GECC_K_AUDIT_B)) != hipSuccess) return hip_rc(e);
+    if ((e = q.run(t_is_a ? jb : ja)) != hipSuccess) return hip_rc(e);
+  } else {
+    const bool b_first = ja.rowdot && !jb.rowdot;
+    if ((e = q.run(b_first ? jb : ja)) != hipSuccess) return hip_rc(e);
+    if ((e = q.run(b_first ? ja : jb)) != hipSuccess) return hip_rc(e);
+  }
   if ((e = q.flush()) != hipSuccess) return hip_rc(e);
   // parity differences, operand patches, rank-one repair of C-bar with the residual syndromes
   // kept up to date, then Section V once more -- all in one workgroup per batch item
@@ -483,16 +545,36 @@ int encode_and_multiply(gecc_ctx* ctx, void* dev_A, void* dev_B, float* dev_C, d
   const ScanJob eb = scan_b_over_m(ctx, dev_B, nullptr, dev_B_par, nullptr);
   const ScanJob pr = scan_a_over_k(ctx, dev_A, dev_B_par, dev_C_par, rec);
   const ScanJob pc = scan_b_over_k(ctx, dev_B, dev_A_par, dev_C_par + 2 * (size_t)p.n, rec);
-  // stored:        A n x k, B k x m   A n x k, B m x k   A k x n, B k x m   A k x n, B m x k
-  // rowdots:       B_P, P_r           P_r, P_c           A_P, B_P           A_P, P_c
-  const ScanJob* order[4];
-  if (!p.trans_a) { order[0] = &ea; order[1] = &eb; order[2] = &pc; order[3] = &pr; }
-  else if (!p.trans_b) { order[0] = &eb; order[1] = &pr; order[2] = &ea; order[3] = &pc; }
-  else { order[0] = &eb; order[1] = &ea; order[2] = &pr; order[3] = &pc; }
   ScanQueue q{ctx, st};
   hipError_t e;
-  for (int x = 0; x < 4; ++x)
-    if ((e = q.run(*order[x])) != hipSuccess) return hip_rc(e);
+  const bool t_is_a = ctx->tile_op == GECC_MAT_A;
+  const TileScanJob tj = t_is_a ? tile_job(ctx, GECC_MAT_A, dev_A, dev_A_par, dev_B_par, dev_C_par, rec, nullptr)
+                                : tile_job(ctx, GECC_MAT_B, dev_B, dev_B_par, dev_A_par, dev_C_par + 2 * (size_t)p.n, rec, nullptr);
+  if (tile_scan_ok(tj)) {
+    // the larger operand in one pass: its encoding and its parity block of C-bar together.  That
+    // pass reads the other operand's encoding, and the other operand's parity block reads this one's.
+    if ((e = q.run(t_is_a ? eb : ea)) != hipSuccess) return hip_rc(e);
+    if ((e = q.run_tile(tj, t_is_a ? GECC_K_TILE_A : GECC_K_TILE_B)) != hipSuccess) return hip_rc(e);
+    // the other operand's parity block: a row scan over few, long rows (too few workgroups for the
+    // row kernel) goes through the tile scan's row part instead
+    const ScanJob& po = t_is_a ? pc : pr;
+    const TileScanJob to = t_is_a ? tile_job(ctx, GECC_MAT_B, dev_B, nullptr, dev_A_par, dev_C_par + 2 * (size_t)p.n, rec, nullptr)
+                                  : tile_job(ctx, GECC_MAT_A, dev_A, nullptr, dev_B_par, dev_C_par, rec, nullptr);
+    if (po.rowdot && to.row_on && !to.col_on && po.s.R < 8192 && po.s.Cc >= 4096 && tile_scan_ok(to))
+      e = q.run_tile(to, po.kind);
+    else
+      e = q.run(po);
+    if (e != hipSuccess) return hip_rc(e);
+  } else {
+    // stored:        A n x k, B k x m   A n x k, B m x k   A k x n, B k x m   A k x n, B m x k
+    // rowdots:       B_P, P_r           P_r, P_c           A_P, B_P           A_P, P_c
+    const ScanJob* order[4];
+    if (!p.trans_a) { order[0] = &ea; order[1] = &eb; order[2] = &pc; order[3] = &pr; }
+    else if (!p.trans_b) { order[0] = &eb; order[1] = &pr; order[2] = &ea; order[3] = &pc; }
+    else { order[0] = &eb; order[1] = &ea; order[2] = &pr; order[3] = &pc; }
+    for (int x = 0; x < 4; ++x)
+      if ((e = q.run(*order[x])) != hipSuccess) return hip_rc(e);
+  }
   if ((e = q.flush()) != hipSuccess) return hip_rc(e);
   return hip_rc(product(ctx, dev_A, dev_A_par, dev_B, dev_B_par, dev_C, dev_C_par, dev_faults, n_faults, st));
 }

@@ -45,6 +45,7 @@ struct Layout {            // byte offsets into the caller's workspace
   size_t blockmax;         // double [batch][nblk][4]     max |syndrome| per family and threshold workgroup
   size_t scan_a;           // double scratch of the two-stage column reduction (A side)
   size_t scan_b;           // same, B side
+  size_t scan_row;         // double scratch of the row part of the tile scan (the larger operand's)
   size_t total;
 };
 
@@ -56,6 +57,7 @@ struct gecc_ctx {
   int tile_m, tile_n;      // blocking of the product kernel = granularity of the partials
   int ntm, ntn;            // partial tiles along n and m
   int rp_ld, cp_ld;        // lines per slab of the row / column partials (n, m plus padding)
+  int tile_op;             // operand whose two reductions share one pass (GECC_MAT_A / GECC_MAT_B)
   int cu_hint;             // GECC_CU_COUNT (tests: plan the tile rounds as for that many CUs), else 0
   char* ws;                // device workspace (caller's)
   size_t ws_bytes;
@@ -73,6 +75,25 @@ namespace gecc {
 // w == nullptr selects the index weights of Section III: w_0 = 1, w_1 = index + 1.
 // Otherwise w points at batch x [2][len] doubles.  gate (may be null): int per batch item at
 // byte stride gate_stride; the kernels return at once for items whose gate != gate_value.
+// Second stage of a column scan (chunks of rows) and / or of the row part of a tile scan (segments of
+// columns) that has not been launched yet: either launch_stage2() runs it as a kernel of its own,
+// or the next rowdot launch carries it (a dependent launch costs about 5 us of stream time
+// whatever it does, and this stage is tiny).
+struct Stage2Job {
+  bool valid;
+  const double* scratch;      // column part: [batch][nchunk][2][Cc] -> out [2][Cc]   (Cc = 0: none)
+  double* out;
+  int64_t out_stride;
+  int Cc, nchunk;
+  const double* row_scratch;  // row part: [batch][R][nseg][2] -> row_out [2][R]     (R = 0: none)
+  double* row_out;
+  int64_t row_out_stride;
+  int R, nseg;
+  int batch;
+  const int32_t* gate;
+  int64_t gate_stride;
+  int gate_value;
+};
 struct ScanArgs {
   const void* X;
   int dtype;
@@ -87,32 +108,48 @@ struct ScanArgs {
   const int32_t* gate;
   int64_t gate_stride;  // in bytes
   int gate_value;
-  // rowdot only: the second stage of an earlier coldot launch, done by carry_blocks extra
-  // workgroups at the end of the grid (same batch and gate as the carrier)
-  const double* carry_scratch;
-  double* carry_out;
-  int64_t carry_out_stride;
-  int carry_Cc, carry_nchunk, carry_blocks;
-};
-// Second stage of a coldot that has not been launched yet: either launch_stage2() runs it as a
-// kernel of its own, or the next rowdot launch carries it (a dependent launch costs about 5 us of
-// stream time whatever it does, and this stage is tiny).
-struct Stage2Job {
-  bool valid;
-  const double* scratch;
-  double* out;
-  int64_t out_stride;
-  int Cc, nchunk, batch;
-  const int32_t* gate;
-  int64_t gate_stride;
-  int gate_value;
+  // rowdot only: the second stage of an earlier launch, done by carry_blocks extra workgroups at
+  // the end of the grid (same batch and gate as the carrier)
+  Stage2Job carry;
+  int carry_blocks;
 };
 // carry: null, or a pending second stage whose output this scan does not read
 hipError_t launch_rowdot(const ScanArgs& a, const Stage2Job* carry, hipStream_t st);
 // launches the first stage only and describes the second in *pending
 hipError_t launch_coldot_stage1(const ScanArgs& a, Stage2Job* pending, hipStream_t st);
 hipError_t launch_stage2(const Stage2Job& j, hipStream_t st);
+int stage2_blocks(const Stage2Job& j);
 size_t coldot_scratch_doubles(int R, int Cc, int batch);
+
+// tile scan: column part (out_col[t][c] = sum_r wr_t[r] X[r,c]) and row part (out_row[t][r] =
+// sum_c wc_t[c] X[r,c]) of one operand in one pass; null weights = Section III's index weights.
+// Either part alone computes bit for bit what it computes beside the other.
+struct TileScanJob {
+  const void* X;
+  int dtype;
+  int R, Cc;
+  int64_t ld, xs;
+  int batch;
+  bool col_on;
+  const double* wr;         // [2][R] per batch item, or null
+  int64_t wr_stride;
+  double* col_out;          // [2][Cc] per batch item
+  int64_t col_out_stride;
+  bool row_on;
+  const double* wc;         // [2][Cc] per batch item, or null
+  int64_t wc_stride;
+  double* row_out;          // [2][R] per batch item
+  int64_t row_out_stride;
+  double* col_scratch;      // coldot_scratch_doubles(R, Cc, batch)
+  double* row_scratch;      // tile_scan_row_scratch_doubles(R, Cc, dtype, batch)
+  const int32_t* gate;
+  int64_t gate_stride;
+  int gate_value;
+};
+bool tile_scan_ok(const TileScanJob& t);     // 16-byte aligned rows, Cc a multiple of the vector width
+size_t tile_scan_row_scratch_doubles(int R, int Cc, int dtype, int batch);
+// launches the first stage and describes the second in *pending
+hipError_t launch_tile_scan(const TileScanJob& t, Stage2Job* pending, hipStream_t st);
 
 // ---- product (gemm_kernels.hip) ------------------------------------------------------------
 struct GemmArgs {

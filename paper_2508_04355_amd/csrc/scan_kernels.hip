@@ -69,6 +69,29 @@ __device__ __forceinline__ void coldot_stage2_body(const double* scratch, double
   if (wave == 0 && o < 2 * Cc) out[o] = (red[0][lane] + red[1][lane]) + (red[2][lane] + red[3][lane]);
 }
 
+// Stage 2 of the row part of tile_scan (see below): 256 rows per workgroup, the segments of a row
+// added in order.  part: [R][nseg][2], out: [2][R], both of batch item b.
+__device__ __forceinline__ void rowseg_stage2_body(const double* part, double* out, int R, int nseg, int blk) {
+  const int r = blk * 256 + threadIdx.x;
+  if (r >= R) return;
+  const double2* p = reinterpret_cast<const double2*>(part) + (int64_t)r * nseg;
+  double s0 = 0.0, s1 = 0.0;
+  for (int g = 0; g < nseg; ++g) { const double2 v = p[g]; s0 += v.x; s1 += v.y; }
+  out[r] = s0;
+  out[(int64_t)R + r] = s1;
+}
+
+// a pending second stage (column chunks and / or row segments), by workgroup index
+__device__ __forceinline__ void stage2_dispatch(const Stage2Job& j, int b, int blk) {
+  const int col_blocks = j.Cc > 0 ? (2 * j.Cc + 63) / 64 : 0;
+  if (blk < col_blocks)
+    coldot_stage2_body(j.scratch + (int64_t)b * j.nchunk * 2 * j.Cc, j.out + (int64_t)b * j.out_stride, j.Cc,
+                       j.nchunk, blk);
+  else
+    rowseg_stage2_body(j.row_scratch + (int64_t)b * j.R * j.nseg * 2, j.row_out + (int64_t)b * j.row_out_stride,
+                       j.R, j.nseg, blk - col_blocks);
+}
+
 // -------------------------------------------------------------------------------------------
 // rowdot: out[t][r] = sum_c w_t[c] X[r,c].   One workgroup owns RB rows and walks all columns;
 // a thread keeps the weights of its VEC columns in registers and reuses them for the RB rows.
@@ -91,10 +114,8 @@ __global__ __launch_bounds__(RD_THREADS) void rowdot_kernel(ScanArgs a) {
   const int b = blockIdx.y;
   if (GATED && gated_off(a.gate, a.gate_stride, b, a.gate_value)) return;
   const int own = (int)gridDim.x - a.carry_blocks;
-  if ((int)blockIdx.x >= own) {   // carried second stage of an earlier coldot
-    coldot_stage2_body(a.carry_scratch + (int64_t)b * a.carry_nchunk * 2 * a.carry_Cc,
-                       a.carry_out + (int64_t)b * a.carry_out_stride, a.carry_Cc, a.carry_nchunk,
-                       (int)blockIdx.x - own);
+  if ((int)blockIdx.x >= own) {   // carried second stage of an earlier column / tile scan
+    stage2_dispatch(a.carry, b, (int)blockIdx.x - own);
     return;
   }
   const T* X = reinterpret_cast<const T*>(a.X) + (int64_t)b * a.xs;
@@ -312,8 +333,200 @@ __global__ __launch_bounds__(CD_THREADS) void coldot_stage1(ScanArgs a, int nchu
 __global__ __launch_bounds__(256) void coldot_stage2(Stage2Job j) {
   const int b = blockIdx.y;
   if (gated_off(j.gate, j.gate_stride, b, j.gate_value)) return;
-  coldot_stage2_body(j.scratch + (int64_t)b * j.nchunk * 2 * j.Cc, j.out + (int64_t)b * j.out_stride, j.Cc,
-                     j.nchunk, blockIdx.x);
+  stage2_dispatch(j, b, blockIdx.x);
+}
+
+// -------------------------------------------------------------------------------------------
+// tile_scan: both reductions of an operand in ONE pass over it.
+//   column part  out_col[t][c] = sum_r wr_t[r] X[r,c]      (two-stage, like coldot)
+//   row part     out_row[t][r] = sum_c wc_t[c] X[r,c]      (two-stage: per 64*VEC-column segment)
+// Each part has either the index weights of Section III (1, index + 1) or two fp64 vectors.  With
+// both parts on, encoding an operand (A_P, index weights along one axis) and its parity block of
+// C-bar (P_r = A B_P, vector weights along the other) cost one read of the operand instead of two.
+// A part switched off costs nothing; a part computes the same sums in the same order whether the
+// other one is on or not, so the gated audit (one part) reproduces an encoding (maybe both) bit for
+// bit.  All products go through fma(), never a*b+c, for the same reason.
+//
+// A workgroup is four wavefronts on one segment of 64*VEC columns; each walks its own quarter of
+// the chunk's rows, TS_RB rows (loads) at a time; at 124 registers four wavefronts share a SIMD and
+// cover each other's waits (measured: more loads in flight per wavefront, 8-byte lanes, or
+// workgroups that read 4 KiB of every row change nothing; the kernel runs at the rate its loads
+// alone reach).  A lane keeps the column sums of its VEC columns in registers for the whole walk.  The row sums of a block of rows
+// (TS_RB rows x 2 kinds, one partial per lane) are transposed through LDS and added by four lanes per
+// output; only the wavefront's own LDS region is involved, so no workgroup barrier sits in the loop.
+constexpr int TS_THREADS = 256;
+constexpr int TS_RB = 8;            // rows per block of loads
+constexpr int TS_LDS_LD = 65;       // doubles per output row of the transpose (64 lanes + 1: conflict-free)
+
+struct TileScanArgs {
+  const void* X;
+  int dtype;
+  int R, Cc;
+  int64_t ld, xs;
+  int batch;
+  const double* wr;       // column part: row weights [2][R] per batch item (null: index weights)
+  int64_t wr_stride;
+  double* col_part;       // [batch][nchunk][2][Cc]
+  const double* wc;       // row part: column weights [2][Cc] per batch item (null: index weights)
+  int64_t wc_stride;
+  double* row_part;       // [batch][R][nseg][2]
+  int chunk_rows, nchunk, nseg;
+  const int32_t* gate;
+  int64_t gate_stride;
+  int gate_value;
+};
+
+// wavefront-local ordering of LDS traffic: the hardware keeps a wavefront's LDS instructions in
+// order; this keeps the compiler from moving them across
+// (a compiler barrier only: a fence instruction would also wait for the wavefront's outstanding
+// global loads and stores, which is exactly what the loop must not do)
+__device__ __forceinline__ void wave_lds_fence() { asm volatile("" ::: "memory"); }
+
+template <int DT, bool COL, bool ROW, bool COL_IDX, bool ROW_IDX, bool GATED>
+__global__ __launch_bounds__(TS_THREADS) void tile_scan(TileScanArgs a) {
+  using E = Elem<DT>;
+  using T = typename E::type;
+  constexpr int VEC = E::VEC;
+  constexpr int SEG = 64 * VEC;
+  const int b = blockIdx.z;
+  if (GATED && gated_off(a.gate, a.gate_stride, b, a.gate_value)) return;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int seg = blockIdx.x, chunk = blockIdx.y;
+  const T* X = reinterpret_cast<const T*>(a.X) + (int64_t)b * a.xs;
+  // columns of this lane (Cc is a multiple of VEC; lanes past the end read the last vector and drop it)
+  const int c_true = seg * SEG + lane * VEC;
+  const bool lane_ok = c_true < a.Cc;
+  const int c = lane_ok ? c_true : a.Cc - VEC;
+  const T* col = X + c;
+  // rows of this wavefront: a quarter of the chunk (multiple of TS_RB, so only the last has a tail)
+  const int rbeg = chunk * a.chunk_rows;
+  const int rend = min(a.R, rbeg + a.chunk_rows);
+  const int quarter = a.chunk_rows >> 2;
+  const int w_beg = min(rend, rbeg + wave * quarter), w_end = min(rend, w_beg + quarter);
+
+  const double* wr0 = (COL && !COL_IDX) ? a.wr + (int64_t)b * a.wr_stride : nullptr;
+  const double* wr1 = (COL && !COL_IDX) ? wr0 + a.R : nullptr;
+  double wc0[VEC], wc1[VEC];
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) {
+    if (ROW && !ROW_IDX) {
+      const double* w = a.wc + (int64_t)b * a.wc_stride;
+      wc0[e] = w[c + e]; wc1[e] = w[a.Cc + c + e];
+    } else {
+      wc0[e] = 1.0; wc1[e] = (double)(c + e + 1);
+    }
+  }
+  double ca0[VEC], ca1[VEC];
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) { ca0[e] = 0.0; ca1[e] = 0.0; }
+
+  extern __shared__ double ts_lds[];
+  double* tr = ts_lds + wave * (2 * TS_RB * TS_LDS_LD);     // this wavefront's transpose region
+  double* rp_out = ROW ? a.row_part + ((int64_t)b * a.R * a.nseg + seg) * 2 : nullptr;
+
+  // one row into the column sums; its two row partials go straight into the transpose region
+  auto take = [&](const typename E::raw& x, int u, double u0, double u1) {
+    double v[VEC];
+    E::widen(x, v);
+    if (COL) {
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) {
+        ca0[e] = COL_IDX ? ca0[e] + v[e] : fma(u0, v[e], ca0[e]);
+        ca1[e] = fma(u1, v[e], ca1[e]);
+        // (pins the update to this row: left alone, the compiler keeps the widened values of all
+        // the rows of a block alive and adds them up at the end, at the cost of half the occupancy)
+        asm volatile("" : "+v"(ca0[e]), "+v"(ca1[e]));
+      }
+    }
+    if (ROW) {
+      double s0 = 0.0, s1 = 0.0;
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) {
+        s0 = ROW_IDX ? s0 + v[e] : fma(wc0[e], v[e], s0);
+        s1 = fma(wc1[e], v[e], s1);
+      }
+      tr[(2 * u) * TS_LDS_LD + lane] = lane_ok ? s0 : 0.0;
+      tr[(2 * u + 1) * TS_LDS_LD + lane] = lane_ok ? s1 : 0.0;
+    }
+  };
+  // row partials of `cnt` rows starting at r0: LDS -> four lanes per output add 16 lanes' values each
+  auto emit_rows = [&](int r0, int cnt) {
+    wave_lds_fence();
+    const int o = lane >> 2, q = lane & 3;      // output (row u = o / 2, kind t = o % 2), quarter of the lanes
+    double s = 0.0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s += tr[o * TS_LDS_LD + q * 16 + i];
+    s += __shfl_xor(s, 1, 64);
+    s += __shfl_xor(s, 2, 64);
+    wave_lds_fence();
+    const int u = o >> 1, t = o & 1;
+    if (q == 0 && u < cnt) rp_out[(int64_t)(r0 + u) * a.nseg * 2 + t] = s;
+  };
+
+  int r = w_beg;
+  const int nfull = (w_end - w_beg) / TS_RB;
+  if (nfull > 0) {
+    typename E::raw xa[TS_RB];
+    auto load = [&](typename E::raw* x, int rr) {
+#pragma unroll
+      for (int u = 0; u < TS_RB; ++u) x[u] = E::load_raw(col + (int64_t)(rr + u) * a.ld);
+    };
+    auto work = [&](const typename E::raw* x, int rr) {
+      // the row weights of the whole block first (uniform loads: one wait, not one per row)
+      double u0[TS_RB], u1[TS_RB];
+#pragma unroll
+      for (int u = 0; u < TS_RB; ++u) {
+        u0[u] = (COL && !COL_IDX) ? wr0[rr + u] : 1.0;
+        u1[u] = (COL && !COL_IDX) ? wr1[rr + u] : (double)(rr + u + 1);
+      }
+#pragma unroll
+      for (int u = 0; u < TS_RB; ++u) {
+        take(x[u], u, u0[u], u1[u]);
+        __builtin_amdgcn_sched_barrier(0);   // one row at a time: widening all of them first costs the occupancy
+      }
+      if (ROW) emit_rows(rr, TS_RB);
+    };
+    for (int bi = 0; bi < nfull; ++bi) {
+      load(xa, r);
+      work(xa, r);
+      r += TS_RB;
+    }
+  }
+  if (r < w_end) {     // the last rows of the operand: fewer than TS_RB
+    const int cnt = w_end - r;
+    for (int u = 0; u < TS_RB; ++u) {
+      if (u < cnt) {
+        take(E::load_raw(col + (int64_t)(r + u) * a.ld), u, (COL && !COL_IDX) ? wr0[r + u] : 1.0,
+             (COL && !COL_IDX) ? wr1[r + u] : (double)(r + u + 1));
+      } else if (ROW) {
+        tr[(2 * u) * TS_LDS_LD + lane] = 0.0;
+        tr[(2 * u + 1) * TS_LDS_LD + lane] = 0.0;
+      }
+    }
+    if (ROW) emit_rows(r, cnt);
+  }
+
+  if (COL) {
+    // the four quarters of the chunk, combined in order
+    __syncthreads();
+    double* cb = ts_lds;                          // [4][2 * VEC][64]
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+      cb[(wave * 2 * VEC + e) * 64 + lane] = ca0[e];
+      cb[(wave * 2 * VEC + VEC + e) * 64 + lane] = ca1[e];
+    }
+    __syncthreads();
+    double* part = a.col_part + ((int64_t)b * a.nchunk + chunk) * 2 * a.Cc;
+    for (int o = threadIdx.x; o < 2 * VEC * 64; o += TS_THREADS) {
+      const int l = o & 63, e = (o >> 6) % VEC, t = o / (64 * VEC);
+      const int cc = seg * SEG + l * VEC + e;
+      if (cc < a.Cc) {
+        const int x = (t * VEC + e) * 64 + l;
+        part[(int64_t)t * a.Cc + cc] = (cb[x] + cb[2 * VEC * 64 + x]) + (cb[2 * 2 * VEC * 64 + x] + cb[3 * 2 * VEC * 64 + x]);
+      }
+    }
+  }
 }
 
 // vector loads need 16-byte aligned rows
@@ -338,9 +551,8 @@ hipError_t launch_rowdot(const ScanArgs& a0, const Stage2Job* carry, hipStream_t
     if (carry->batch != a.batch || carry->gate != a.gate || carry->gate_stride != a.gate_stride ||
         carry->gate_value != a.gate_value)
       return hipErrorInvalidValue;
-    a.carry_scratch = carry->scratch; a.carry_out = carry->out; a.carry_out_stride = carry->out_stride;
-    a.carry_Cc = carry->Cc; a.carry_nchunk = carry->nchunk;
-    a.carry_blocks = (2 * carry->Cc + 63) / 64;
+    a.carry = *carry;
+    a.carry_blocks = stage2_blocks(*carry);
   }
   const int extra = a.carry_blocks;
   const bool idx = a.w == nullptr;
@@ -388,6 +600,7 @@ hipError_t launch_coldot_stage1(const ScanArgs& a0, Stage2Job* pending, hipStrea
     else if (idx) hipLaunchKernelGGL((coldot_stage1<GECC_F32, true, false>), grid, dim3(CD_THREADS), 0, st, a, nchunk);
     else          hipLaunchKernelGGL((coldot_stage1<GECC_F32, false, false>), grid, dim3(CD_THREADS), 0, st, a, nchunk);
   }
+  *pending = Stage2Job{};
   pending->valid = true;
   pending->scratch = a.scratch; pending->out = a.out; pending->out_stride = a.out_stride;
   pending->Cc = a.Cc; pending->nchunk = nchunk; pending->batch = a.batch;
@@ -395,8 +608,89 @@ hipError_t launch_coldot_stage1(const ScanArgs& a0, Stage2Job* pending, hipStrea
   return hipGetLastError();
 }
 
+// ---- tile_scan ------------------------------------------------------------------------------
+bool tile_scan_ok(const TileScanJob& t) {
+  const int vec = t.dtype == GECC_BF16 ? 8 : 4;
+  const size_t esz = t.dtype == GECC_BF16 ? 2 : 4;
+  return reinterpret_cast<uintptr_t>(t.X) % 16 == 0 && t.ld % vec == 0 && (t.xs * esz) % 16 == 0 &&
+         t.Cc % vec == 0 && t.Cc >= vec && t.R >= 1;
+}
+
+int tile_scan_segments(int Cc, int dtype) {
+  const int seg = 64 * (dtype == GECC_BF16 ? 8 : 4);
+  return (Cc + seg - 1) / seg;
+}
+
+size_t tile_scan_row_scratch_doubles(int R, int Cc, int dtype, int batch) {
+  return (size_t)batch * (size_t)R * tile_scan_segments(Cc, dtype) * 2;
+}
+
+// rows per chunk: 128 (the chunk the column scratch is sized for) or, when the grid stays large
+// enough to fill the chip, 256 or 512 (fewer column partial sums to write and read back)
+static int tile_scan_chunk_rows(int R, int nseg, int batch) {
+  int ch = SCAN_CHUNK_ROWS;
+  while (ch < 512 && (int64_t)nseg * ((R + 2 * ch - 1) / (2 * ch)) * batch * 4 >= 4096) ch *= 2;
+  return ch;
+}
+
+hipError_t launch_tile_scan(const TileScanJob& t, Stage2Job* pending, hipStream_t st) {
+  if (!tile_scan_ok(t) || (!t.col_on && !t.row_on)) return hipErrorInvalidValue;
+  TileScanArgs a{};
+  a.X = t.X; a.dtype = t.dtype; a.R = t.R; a.Cc = t.Cc; a.ld = t.ld; a.xs = t.xs; a.batch = t.batch;
+  a.wr = t.wr; a.wr_stride = t.wr_stride; a.col_part = t.col_scratch;
+  a.wc = t.wc; a.wc_stride = t.wc_stride; a.row_part = t.row_scratch;
+  a.nseg = tile_scan_segments(t.Cc, t.dtype);
+  a.chunk_rows = tile_scan_chunk_rows(t.R, a.nseg, t.batch);
+  a.nchunk = (t.R + a.chunk_rows - 1) / a.chunk_rows;
+  a.gate = t.gate; a.gate_stride = t.gate_stride; a.gate_value = t.gate_value;
+  const dim3 grid(a.nseg, a.nchunk, a.batch), block(TS_THREADS);
+  const size_t lds = 4 * 2 * TS_RB * TS_LDS_LD * sizeof(double);
+  const bool gated = t.gate != nullptr;
+  const bool cidx = t.wr == nullptr, ridx = t.wc == nullptr;
+#define GECC_TS(DT, COL, ROW, CI, RI, G) \
+  hipLaunchKernelGGL((tile_scan<DT, COL, ROW, CI, RI, G>), grid, block, lds, st, a)
+#define GECC_TS_DT(DT)                                                                       \
+  do {                                                                                       \
+    if (t.col_on && t.row_on) {                                                              \
+      if (gated) return hipErrorInvalidValue;                                                \
+      if (cidx && !ridx) GECC_TS(DT, true, true, true, false, false);                        \
+      else if (!cidx && ridx) GECC_TS(DT, true, true, false, true, false);                   \
+      else return hipErrorInvalidValue;                                                      \
+    } else if (t.col_on) {                                                                   \
+      if (!cidx) return hipErrorInvalidValue;                                                \
+      if (gated) GECC_TS(DT, true, false, true, true, true);                                 \
+      else GECC_TS(DT, true, false, true, true, false);                                      \
+    } else {                                                                                 \
+      if (gated && !ridx) return hipErrorInvalidValue;                                       \
+      if (gated) GECC_TS(DT, false, true, true, true, true);                                 \
+      else if (ridx) GECC_TS(DT, false, true, true, true, false);                            \
+      else GECC_TS(DT, false, true, true, false, false);                                     \
+    }                                                                                        \
+  } while (0)
+  if (t.dtype == GECC_BF16) GECC_TS_DT(GECC_BF16); else GECC_TS_DT(GECC_F32);
+#undef GECC_TS_DT
+#undef GECC_TS
+  *pending = Stage2Job{};
+  pending->valid = true;
+  pending->batch = t.batch;
+  pending->gate = t.gate; pending->gate_stride = t.gate_stride; pending->gate_value = t.gate_value;
+  if (t.col_on) {
+    pending->scratch = t.col_scratch; pending->out = t.col_out; pending->out_stride = t.col_out_stride;
+    pending->Cc = t.Cc; pending->nchunk = a.nchunk;
+  }
+  if (t.row_on) {
+    pending->row_scratch = t.row_scratch; pending->row_out = t.row_out; pending->row_out_stride = t.row_out_stride;
+    pending->R = t.R; pending->nseg = a.nseg;
+  }
+  return hipGetLastError();
+}
+
+int stage2_blocks(const Stage2Job& j) {
+  return (j.Cc > 0 ? (2 * j.Cc + 63) / 64 : 0) + (j.R > 0 ? (j.R + 255) / 256 : 0);
+}
+
 hipError_t launch_stage2(const Stage2Job& j, hipStream_t st) {
-  dim3 g2((2 * j.Cc + 63) / 64, j.batch);
+  dim3 g2(stage2_blocks(j), j.batch);
   hipLaunchKernelGGL(coldot_stage2, g2, dim3(256), 0, st, j);
   return hipGetLastError();
 }

@@ -197,8 +197,11 @@ def test_recomputation_after_an_uncorrectable_pattern():
 @pytest.mark.parametrize("trans", [(0, 0), (0, 1), (1, 0), (1, 1)])
 @pytest.mark.parametrize("dtype,shape,batch", [("f32", (300, 200, 260), 2), ("bf16", (520, 256, 264), 3)])
 def test_one_call_chain_equals_the_staged_calls_bit_for_bit(dtype, shape, batch, trans):
-    """gecc_protected_gemm orders its four parity scans by storage layout and lets row scans carry
-    the second stage of column scans; none of that may change a bit of any result."""
+    """gecc_protected_gemm orders its parity scans by storage layout, lets row scans carry the second
+    stage of column scans and reads the larger operand once for both of its reductions.  None of that
+    may change a bit of C, of the operand parities (the audit re-forms them and tests for equality) or
+    of a decision; the parity blocks of C-bar, fp64 sums taken in another order by the one-pass scan,
+    agree to rounding."""
     n, k, m = shape
     rng = inputs.rng_for(95, trans[0] * 2 + trans[1])
     A = np.stack([inputs.operands(rng, n, k, m, ("normal", 1.0), ("normal", 1.0), dtype)[0] for _ in range(batch)])
@@ -207,8 +210,10 @@ def test_one_call_chain_equals_the_staged_calls_bit_for_bit(dtype, shape, batch,
     cf = [(b, 7 + b, 250, 40.0) for b in range(batch)] + [(0, n - 1, 3, -25.0)]
     g1 = H.run_gpu(A, B, A, B, cf, tau, dtype, trans[0], trans[1], staged=True)
     g2 = H.run_gpu(A, B, A, B, cf, tau, dtype, trans[0], trans[1], staged=False)
-    for name in ("A_par", "B_par", "C_par", "C", "synd"):
+    for name in ("A_par", "B_par", "C"):
         assert np.array_equal(getattr(g1, name), getattr(g2, name)), name
+    assert np.allclose(g1.C_par, g2.C_par, rtol=1e-12, atol=1e-13 * np.abs(g1.C_par).max())
+    assert np.allclose(g1.synd, g2.synd, rtol=0, atol=1e-11 * np.abs(g1.C_par).max())
     for r1, r2 in zip(g1.reports, g2.reports):
         assert (r1.status, r1.n_total, r1.errors()) == (r2.status, r2.n_total, r2.errors())
     H.compare(g2, H.run_oracle(A, B, A, B, cf, tau), 1e-5, what="one call")
@@ -225,7 +230,7 @@ def test_two_contexts_on_two_streams_do_not_disturb_each_other():
         rng = inputs.rng_for(96, idx)
         A, B = inputs.operands(rng, n, k, m, ("normal", 1.0), ("normal", 1.0), dtype)
         tau = gecc.noise_thresholds(n, k, m, 1.0, 1.0)
-        alone.append(H.run_gpu(A, B, A, B, cf, tau, dtype, staged=False))
+        alone.append(H.run_gpu(A, B, A, B, cf, tau, dtype, staged=True))
         ctx = gecc.Context(n, k, m, gecc.BF16 if dtype == "bf16" else gecc.F32,
                            gecc.Thresholds(tau.r1, tau.r2, tau.q1, tau.q2, tau.op, tau.rep, tau.rel))
         dA, dB = H.to_dev(A[None], dtype, False), H.to_dev(B[None], dtype, False)
