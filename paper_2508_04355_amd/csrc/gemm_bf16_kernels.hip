@@ -325,12 +325,13 @@ __device__ __forceinline__ void tile_of(int pid, int ntm, int ntn, int sr, int s
 }
 
 // The k-split tail (see launch_one): a tile of the last, at most half filled round is computed
-// by two workgroups, one per half of k, which add their halves into C and into the partial sums
-// (both zeroed by this kernel first: one workgroup per tail tile).
-__global__ __launch_bounds__(256) void zero_tail_kernel(GemmArgs a, int first) {
+// by two workgroups, one per half of k, which add their halves into C and into the partial sums.
+// Both are zeroed first, by the first workgroups of the launch that computes the full rounds
+// (one tail tile each, before their own tile: that launch ends before the split one starts).
+__device__ __forceinline__ void zero_tail_tile(const GemmArgs& a, int tile) {
   const int ntm = (a.n + BM - 1) / BM, ntn = (a.m + BN - 1) / BN;
   int tm, tn;
-  tile_of(first + blockIdx.x, ntm, ntn, a.map_sr, a.map_sc, tm, tn);
+  tile_of(tile, ntm, ntn, a.map_sr, a.map_sc, tm, tn);
   const int r0 = tm * BM, c0 = tn * BN;
   const int rows = min(BM, a.n - r0), cols = min(BN, a.m - c0);
   for (int o = threadIdx.x; o < rows * BN; o += 256) {
@@ -362,6 +363,10 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
   const int wr = wave >> 1, wc = wave & 1;
   const int l16 = lane & 15, lg = lane >> 4;
   const int b = blockIdx.y;
+  if (!SP && a.split_first >= 0) {
+    const int ntiles_all = ((a.n + BM - 1) / BM) * ((a.m + BN - 1) / BN);
+    if (a.split_first + (int)blockIdx.x < ntiles_all) zero_tail_tile(a, a.split_first + (int)blockIdx.x);
+  }
 
   const int ntm = (a.n + BM - 1) / BM, ntn = (a.m + BN - 1) / BN;
   // SP (the k-split launch, see launch_one): the workgroups share the tiles from split_first on
@@ -761,12 +766,10 @@ hipError_t launch_one(const GemmArgs& a0, hipStream_t st) {
   const int tail = ntiles % cus;
   a.split_first = -1;
   if (a.batch == 1 && ntiles > cus && tail > 0 && 2 * tail <= cus && a.k % (4 * BK) == 0) {
-    a.split_first = ntiles - tail;
-    hipLaunchKernelGGL(zero_tail_kernel, dim3(tail), dim3(256), 0, st, a, a.split_first);
+    a.split_first = ntiles - tail;      // (tail <= ntiles - tail: every tail tile has a workgroup to zero it)
+    hipLaunchKernelGGL(kern, dim3(ntiles - tail, 1), dim3(THREADS), lds_bytes, st, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3(ntiles - tail, 1), dim3(THREADS), lds_bytes, st, a);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
     hipLaunchKernelGGL(kern_split, dim3(2 * tail, 1), dim3(THREADS), lds_bytes, st, a);
     return hipGetLastError();
   }
