@@ -34,6 +34,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="cfg4-fwd")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--panels", type=int, default=0,
+                    help="also time the per-k-panel path (gecc_protected_gemm_panels) with this many panels")
     ap.add_argument("--traffic-ref", action="store_true",
                     help="also run one 1 GiB device copy (untimed): the known-size kernel that "
                          "FETCH_SIZE / WRITE_SIZE counter runs are scaled by")
@@ -109,6 +111,32 @@ def main():
     clean = all(r.status == gecc.CLEAN for r in reports)
 
     ms_plain = 0.5 * (ms_plain_before + time_plain())
+
+    # ---- per-k-panel verification (optional): the same product one panel of k after the other ----
+    panel_out = None
+    if args.panels > 1 and batch == 1:
+        import ctypes as C
+        P = ctx.panel_count(args.panels)
+        Cp = ctx.alloc_c()
+        C_par_p = torch.empty(P * (2 * n + 2 * m + 4), dtype=torch.float64, device=dev)
+        reps_p = torch.zeros(P * C.sizeof(gecc.Report), dtype=torch.uint8, device=dev)
+
+        def pstep():
+            ctx.protected_gemm_panels(dA, dB, Cd, Cp, A_par, B_par, C_par_p, reps_p, args.panels)
+
+        for _ in range(args.warmup):
+            pstep()
+        torch.cuda.synchronize()
+        t0p = time.perf_counter()
+        for _ in range(args.steps):
+            pstep()
+        torch.cuda.synchronize()
+        ms_p = (time.perf_counter() - t0p) * 1e3 / args.steps
+        rp = ctx.reports_to_host(reps_p, P)
+        panel_out = {"panels": P, "ms_per_step": round(ms_p, 4), "tflops": round(w.flops / (ms_p * 1e-3) / 1e12, 3),
+                     "overhead_pct_vs_plain": round((ms_p / ms_plain - 1.0) * 100.0, 2),
+                     "all_clean": all(r.status == gecc.CLEAN for r in rp)}
+        del Cp
 
     # ---- HBM rooflines of the memory-bound kernels: the same steps once more with an event pair
     # around every launch (not part of `value`: the records cost stream time), then the stand-alone
@@ -243,6 +271,7 @@ def main():
         "single_checksum_mode": {"corrected": sum(int(v) for v in good1.values()), "trials": n_tot, "status": status1,
                                  "scenario_ms": scen_ms1,
                                  "scenario_overhead_pct": {kk: round((vv / ms_plain - 1.0) * 100.0, 1) for kk, vv in scen_ms1.items()}},
+        "per_k_panel_verification": panel_out,
         "hbm_rooflines": {"peak_GBs": HBM_PEAK_GBS,
                           "steady_loop": hbm_steady,       # as in the timed steps: operands may sit in the memory-side cache
                           "operands_rotated": hbm_rotated},  # three operand sets in turn: every first read comes from HBM

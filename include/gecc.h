@@ -204,6 +204,30 @@ int gecc_protected_gemm(gecc_ctx* ctx, void* dev_A, void* dev_B, float* dev_C, d
                         double* dev_B_par, double* dev_C_par, gecc_report* dev_report,
                         void* stream);
 
+/* Per-k-panel verification.  The code of Section III is linear in the operands: with the k index
+   cut into `panels` consecutive panels, C-bar is the sum of the partial products
+   A-bar[:, g] B-bar[g, :], and each of them has the grid structure of Definition 1 on its own, with
+   the panel's slices of A_P and B_P as its operand parities.  This call runs the whole path --
+   encode, multiply, verify (fused), correct -- on one panel after the other and adds the corrected
+   partial products up in dev_C, so that a fault is caught, located and removed in the panel it
+   strikes (two faults in two panels are two single faults), at the price of one more pass over C
+   per panel after the first.  batch must be 1.
+   Panel g covers k indices [g * step, min(k, (g + 1) * step)), step = k / panels rounded up to a
+   multiple of 64; gecc_panel_count(ctx, panels) says how many of them are not empty (P below).
+     dev_C_partial   n x ldc floats of scratch (may be null when P = 1)
+     dev_A_par, dev_B_par   2 k doubles each: panel after panel, [2][k_g] of the panel's slice
+     dev_C_par       P x (2 n + 2 m + 4) doubles: the parity blocks of every partial product
+     dev_report      P reports; operand errors carry the column (of A) / row (of B) inside the panel
+     dev_faults      NULL or n_faults test faults; the `batch` field of a fault names its panel
+   The detection thresholds of a panel are the context's scaled by k_g / k (rounding noise of an
+   fp32-accumulated sum grows with its number of terms).  The workspace of the context serves
+   every panel in turn. */
+int32_t gecc_panel_count(const gecc_ctx* ctx, int32_t panels);
+int gecc_protected_gemm_panels(gecc_ctx* ctx, void* dev_A, void* dev_B, float* dev_C, float* dev_C_partial,
+                               double* dev_A_par, double* dev_B_par, double* dev_C_par,
+                               gecc_report* dev_report, int32_t panels, const gecc_fault* dev_faults,
+                               int32_t n_faults, void* stream);
+
 /* For callers that cannot allocate device memory or hand a workspace over (code under HIP graph
    capture, tight serving loops, harnesses that forbid hipMalloc): gecc_protected_gemm on a scratch
    buffer that lives inside the library, a static device array of GECC_STATIC_SCRATCH_BYTES per GPU,

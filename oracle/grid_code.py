@@ -582,3 +582,40 @@ def protected_gemm(A_enc, B_enc, A_mul, B_mul, c_faults, tau):
     if not tau.weighted:
         return decode_single_checksum(Cbar, A_mul, AP, B_mul, BP, tau)
     return decode(Cbar, A_mul, AP, B_mul, BP, tau)
+
+
+# ------------------------------------------- per-k-panel verification (linearity of Section III)
+def panel_bounds(k, panels, align=64):
+    """k cut into `panels` consecutive panels of equal length rounded up to `align` (the last one
+    takes what is left; panels past the end of k are empty and dropped): [(k0, k1)]."""
+    step = -(-(-(-k // panels)) // align) * align
+    return [(g * step, min(k, (g + 1) * step)) for g in range(panels) if g * step < k]
+
+
+def panel_thresholds(tau, kg, k):
+    """Thresholds of a partial product over kg of the k terms: rounding noise of an fp32-accumulated
+    sum grows in proportion to the number of terms, and so do the four detection thresholds."""
+    f = kg / float(k)
+    return Thresholds(tau.r1 * f, tau.r2 * f, tau.q1 * f, tau.q2 * f, tau.op, tau.rep, tau.rel, tau.weighted)
+
+
+def protected_gemm_panels(A_enc, B_enc, A_mul, B_mul, c_faults_by_panel, tau, bounds):
+    """The protected product one k-panel at a time.
+
+    The encoding of Section III is linear in the operands: with the k index cut into panels,
+    A-bar B-bar = sum_g A-bar[:, g] B-bar[g, :], and each term is itself an (n+2) x (m+2) matrix
+    with the grid structure of Definition 1 -- its parity blocks are the products with the
+    panel's slices of A_P and B_P.  So every partial product is encoded, multiplied, verified and
+    corrected on its own (a fault is caught in the panel it strikes, before it is summed into
+    C), and C is the sum of the corrected partial products.
+    c_faults_by_panel: {g: [(i, j, e)]}.  Returns ([Result per panel], C).  Positions of operand
+    errors are relative to the panel's slice.
+    """
+    k = A_enc.shape[1]
+    results, C = [], None
+    for g, (k0, k1) in enumerate(bounds):
+        res = protected_gemm(A_enc[:, k0:k1], B_enc[k0:k1, :], A_mul[:, k0:k1], B_mul[k0:k1, :],
+                             c_faults_by_panel.get(g, []), panel_thresholds(tau, k1 - k0, k))
+        results.append(res)
+        C = res.C.copy() if C is None else C + res.C
+    return results, C

@@ -310,6 +310,9 @@ int gecc_create(gecc_ctx** out, const gecc_params* p) {
   c->cp_ld = p->m % 256 == 0 ? p->m + 16 : p->m;
   c->ws = nullptr;
   c->ws_bytes = 0;
+  c->panel = nullptr;
+  c->n_panel = 0;
+  c->fault_bias = 0;
   c->ev = nullptr;
   c->ev_kind = nullptr;
   c->ev_mask = 0;
@@ -320,8 +323,18 @@ int gecc_create(gecc_ctx** out, const gecc_params* p) {
   return GECC_OK;
 }
 
+namespace {
+void drop_panels(gecc_ctx* ctx) {
+  for (int g = 0; g < ctx->n_panel; ++g) delete ctx->panel[g];
+  delete[] ctx->panel;
+  ctx->panel = nullptr;
+  ctx->n_panel = 0;
+}
+}  // namespace
+
 void gecc_destroy(gecc_ctx* ctx) {
   if (!ctx) return;
+  drop_panels(ctx);
   gecc_timing_enable(ctx, 0, 0);
   delete ctx;
 }
@@ -436,6 +449,7 @@ hipError_t product(gecc_ctx* ctx, const void* dev_A, const double* dev_A_par, co
   g.colpart = reinterpret_cast<float*>(ctx->ws + ctx->lay.colpart);
   g.faults = dev_faults;
   g.n_faults = n_faults;
+  g.fault_bias = ctx->fault_bias;
   // P_g is formed inside the product kernel, which also resets the decoder state for the
   // fused verification that follows
   g.A_par = dev_A_par; g.B_par = dev_B_par;
@@ -685,6 +699,80 @@ int gecc_protected_gemm_static(gecc_ctx* ctx, void* dev_A, void* dev_B, float* d
   ctx->ws = keep_ws;
   ctx->ws_bytes = keep_bytes;
   return rc;
+}
+
+namespace {
+int panel_step(const gecc_ctx* ctx, int panels) {
+  const int per = (ctx->p.k + panels - 1) / panels;
+  return (per + 63) / 64 * 64;
+}
+}  // namespace
+
+int32_t gecc_panel_count(const gecc_ctx* ctx, int32_t panels) {
+  if (!ctx || panels < 1) return 0;
+  const int step = panel_step(ctx, panels);
+  return (ctx->p.k + step - 1) / step;
+}
+
+int gecc_protected_gemm_panels(gecc_ctx* ctx, void* dev_A, void* dev_B, float* dev_C, float* dev_C_partial,
+                               double* dev_A_par, double* dev_B_par, double* dev_C_par,
+                               gecc_report* dev_report, int32_t panels, const gecc_fault* dev_faults,
+                               int32_t n_faults, void* stream) {
+  int rc = check_ws(ctx);
+  if (rc) return rc;
+  if (panels < 1 || ctx->p.batch != 1 || !dev_report) return GECC_ERR_ARG;
+  const int P = gecc_panel_count(ctx, panels), step = panel_step(ctx, panels);
+  if (P > 1 && !dev_C_partial) return GECC_ERR_ARG;
+  if (dev_C_partial && !aligned_to(dev_C_partial, 4)) return GECC_ERR_ALIGN;
+  // one context per panel: the same product with k_g terms (host objects, rebuilt when the panel count changes)
+  if (ctx->n_panel != P || !ctx->panel || ctx->panel[0]->p.k != (P == 1 ? ctx->p.k : step)) {
+    drop_panels(ctx);
+    ctx->panel = new (std::nothrow) gecc_ctx*[P];
+    if (!ctx->panel) return GECC_ERR_ARG;
+    for (int g = 0; g < P; ++g) {
+      gecc_params q = ctx->p;
+      const int k0 = g * step;
+      q.k = ctx->p.k - k0 < step ? ctx->p.k - k0 : step;
+      const double f = (double)q.k / (double)ctx->p.k;
+      q.tau_r1 *= f; q.tau_r2 *= f; q.tau_q1 *= f; q.tau_q2 *= f;
+      gecc_ctx* child = nullptr;
+      rc = gecc_create(&child, &q);
+      if (rc || child->lay.total > ctx->lay.total) {
+        if (child) gecc_destroy(child);
+        ctx->n_panel = g;
+        drop_panels(ctx);
+        return rc ? rc : GECC_ERR_WORKSPACE;
+      }
+      child->cu_hint = ctx->cu_hint;
+      ctx->panel[g] = child;
+      ctx->n_panel = g + 1;
+    }
+  }
+  hipStream_t st = (hipStream_t)stream;
+  const gecc_params& p = ctx->p;
+  const size_t esz = elem_size(p.dtype);
+  const int64_t rec = 2 * (int64_t)p.n + 2 * (int64_t)p.m + 4;
+  for (int g = 0; g < P; ++g) {
+    gecc_ctx* c = ctx->panel[g];
+    c->ws = ctx->ws; c->ws_bytes = ctx->ws_bytes;
+    c->ev = ctx->ev; c->ev_kind = ctx->ev_kind; c->ev_mask = ctx->ev_mask; c->ev_cap = ctx->ev_cap; c->ev_n = ctx->ev_n;
+    const int64_t k0 = (int64_t)g * step;
+    char* Ag = static_cast<char*>(dev_A) + (p.trans_a ? k0 * p.lda : k0) * (int64_t)esz;
+    char* Bg = static_cast<char*>(dev_B) + (p.trans_b ? k0 : k0 * p.ldb) * (int64_t)esz;
+    float* Cg = g == 0 ? dev_C : dev_C_partial;
+    double* Apg = dev_A_par + 2 * k0;
+    double* Bpg = dev_B_par + 2 * k0;
+    double* Cpg = dev_C_par + g * rec;
+    c->fault_bias = g;
+    rc = encode_and_multiply(c, Ag, Bg, Cg, Apg, Bpg, Cpg, dev_faults, n_faults, st);
+    if (!rc) rc = verify_impl(c, Cg, Cpg, dev_report + g, 1, 0, st);
+    if (!rc) rc = correct_impl(c, Ag, Apg, Bg, Bpg, Cg, Cpg, dev_report + g, 1, st);
+    if (!rc && g > 0) rc = hip_rc(launch_accumulate(dev_C, dev_C_partial, p.n, p.m, p.ldc, st));
+    ctx->ev_n = c->ev_n;
+    c->ev = nullptr; c->ev_kind = nullptr; c->ev_cap = 0; c->ev_n = 0;     // the records stay the parent's
+    if (rc) return rc;
+  }
+  return GECC_OK;
 }
 
 int gecc_plain_gemm(gecc_ctx* ctx, const void* dev_A, const void* dev_B, float* dev_C, void* stream) {

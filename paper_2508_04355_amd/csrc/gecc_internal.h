@@ -61,6 +61,9 @@ struct gecc_ctx {
   int cu_hint;             // GECC_CU_COUNT (tests: plan the tile rounds as for that many CUs), else 0
   char* ws;                // device workspace (caller's)
   size_t ws_bytes;
+  int fault_bias;          // see GemmArgs::fault_bias (nonzero only in a panel's context)
+  gecc_ctx** panel;        // contexts of the k-panels of the last gecc_protected_gemm_panels call
+  int n_panel;
   hipEvent_t* ev;          // optional timing records around kernel launches (start, stop pairs)
   int32_t* ev_kind;        // class (GECC_K_x) of each record
   uint32_t ev_mask;        // classes that are recorded
@@ -165,6 +168,8 @@ struct GemmArgs {
   int rp_ld, cp_ld;     // lines per sub-tile slab of rowpart / colpart (n, m plus padding)
   const gecc_fault* faults;
   int n_faults;
+  int fault_bias;       // a fault strikes batch item b when its `batch` field equals b + fault_bias
+                        // (the per-panel call uses that field for the panel number)
   int cu_hint;          // compute units to plan the rounds of tiles for (0: ask the device)
   int split_first;      // set by the launcher of the bf16 256 x 256 kernel: first workgroup of the
                         // k-split tail (-1: none)
@@ -237,6 +242,8 @@ struct PartialArgs {
   int gate_value;
 };
 hipError_t launch_partials(const PartialArgs& a, hipStream_t st);
+// C += P (both n x m fp32, leading dimension ldc): the sum of per-panel partial products
+hipError_t launch_accumulate(float* C, const float* P, int n, int m, int64_t ldc, hipStream_t st);
 
 // ---- decoder (decode_kernels.hip) ----------------------------------------------------------
 struct DecodeArgs {

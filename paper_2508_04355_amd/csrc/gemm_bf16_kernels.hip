@@ -599,7 +599,7 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
   if (khalf <= 0) {     // (of a split tile: planted into the first half)
     for (int f = 0; f < a.n_faults; ++f) {
       const gecc_fault ft = a.faults[f];
-      if (ft.batch != b || ft.row < R0 || ft.row >= R0 + 128 || ft.col < C0 || ft.col >= C0 + 128) continue;
+      if (ft.batch != b + a.fault_bias || ft.row < R0 || ft.row >= R0 + 128 || ft.col < C0 || ft.col >= C0 + 128) continue;
       const int dr = ft.row - R0, dc = ft.col - C0;
       const int fi = dr >> 4, fv = dr & 3, fj = dc >> 4;
       const bool mine = (((dr >> 2) & 3) == lg) && ((dc & 15) == l16);

@@ -265,7 +265,7 @@ __global__ __launch_bounds__(THREADS) void gemm_kernel(GemmArgs a) {
     }
     __syncthreads();
     const int r_lo = tile_r0 + slab * SLAB;
-    apply_faults(a.faults, a.n_faults, b, r_lo, min(r_lo + SLAB, a.n), tile_c0,
+    apply_faults(a.faults, a.n_faults, b + a.fault_bias, r_lo, min(r_lo + SLAB, a.n), tile_c0,
                  min(tile_c0 + BN, a.m), &Cs[0][0], BN + CPAD);
     if (a.n_faults > 0) __syncthreads();
     slab_reduce<BN, SLAB>(Cs, slab * SLAB, tile_r0, tile_c0, a.n, a.m, rowpart_tile, cs, cw);
@@ -378,6 +378,35 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t st) {
   if (a.tile_m != 128 || a.tile_n != 128) return hipErrorInvalidValue;
   if (gemm_bf16_fast_ok(a)) return launch_gemm_bf16_fast(a, st);
   return a.dtype == GECC_BF16 ? launch_dt<GECC_BF16>(a, st) : launch_dt<GECC_F32>(a, st);
+}
+
+namespace {
+// C += P, 16 bytes per thread where the rows allow it
+__global__ __launch_bounds__(256) void accumulate_kernel(float* C, const float* P, int n, int m, int64_t ldc, int vec_ok) {
+  const int64_t total4 = (int64_t)n * ((m + 3) / 4);
+  for (int64_t o = (int64_t)blockIdx.x * 256 + threadIdx.x; o < total4; o += (int64_t)gridDim.x * 256) {
+    const int64_t i = o / ((m + 3) / 4);
+    const int j = (int)(o - i * ((m + 3) / 4)) * 4;
+    float* c = C + i * ldc + j;
+    const float* p = P + i * ldc + j;
+    if (vec_ok && j + 4 <= m) {
+      float4 x = *reinterpret_cast<const float4*>(c);
+      const float4 y = *reinterpret_cast<const float4*>(p);
+      x.x += y.x; x.y += y.y; x.z += y.z; x.w += y.w;
+      *reinterpret_cast<float4*>(c) = x;
+    } else {
+      for (int e = 0; e < 4 && j + e < m; ++e) c[e] += p[e];
+    }
+  }
+}
+}  // namespace
+
+hipError_t launch_accumulate(float* C, const float* P, int n, int m, int64_t ldc, hipStream_t st) {
+  const int vec_ok = ldc % 4 == 0 && reinterpret_cast<uintptr_t>(C) % 16 == 0 && reinterpret_cast<uintptr_t>(P) % 16 == 0;
+  const int64_t total4 = (int64_t)n * ((m + 3) / 4);
+  const int blocks = (int)((total4 + 255) / 256 < 16384 ? (total4 + 255) / 256 : 16384);
+  hipLaunchKernelGGL(accumulate_kernel, dim3(blocks > 0 ? blocks : 1), dim3(256), 0, st, C, P, n, m, ldc, vec_ok);
+  return hipGetLastError();
 }
 
 hipError_t launch_partials(const PartialArgs& a, hipStream_t st) {

@@ -58,7 +58,7 @@ _lib = None
 _SYMBOLS = ["gecc_create", "gecc_destroy", "gecc_workspace_bytes", "gecc_set_workspace",
             "gecc_a_par_len", "gecc_b_par_len", "gecc_c_par_len", "gecc_encode_a", "gecc_encode_b",
             "gecc_multiply", "gecc_verify", "gecc_correct", "gecc_protected_gemm", "gecc_protected_gemm_retry",
-            "gecc_protected_gemm_static",
+            "gecc_protected_gemm_static", "gecc_panel_count", "gecc_protected_gemm_panels",
             "gecc_plain_gemm",
             "gecc_report_to_host", "gecc_syndromes_to_host", "gecc_timing_enable", "gecc_timing_read",
             "gecc_strerror"]
@@ -90,6 +90,9 @@ def lib():
     L.gecc_correct.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp]
     L.gecc_protected_gemm.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp]
     L.gecc_protected_gemm_static.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    L.gecc_panel_count.argtypes = [vp, i32]
+    L.gecc_panel_count.restype = i32
+    L.gecc_protected_gemm_panels.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, i32, vp]
     L.gecc_protected_gemm_retry.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, C.POINTER(Report), i32, vp, i32,
                                             C.POINTER(i32), vp]
     L.gecc_plain_gemm.argtypes = [vp, vp, vp, vp, vp]
@@ -101,7 +104,7 @@ def lib():
     L.gecc_strerror.restype = C.c_char_p
     for f in _SYMBOLS:
         if f not in ("gecc_destroy", "gecc_workspace_bytes", "gecc_a_par_len", "gecc_b_par_len",
-                     "gecc_c_par_len", "gecc_strerror"):
+                     "gecc_c_par_len", "gecc_strerror", "gecc_panel_count"):
             getattr(L, f).restype = C.c_int
     _lib = L
     return L
@@ -222,6 +225,22 @@ class Context:
         """protected_gemm on the library's static scratch array (no workspace, no allocation)."""
         _check(lib().gecc_protected_gemm_static(self._h, _ptr(A), _ptr(B), _ptr(Cmat), _ptr(A_par),
                                                 _ptr(B_par), _ptr(C_par), _ptr(report), _stream()))
+
+    def panel_count(self, panels: int) -> int:
+        return lib().gecc_panel_count(self._h, panels)
+
+    def protected_gemm_panels(self, A, B, Cmat, C_partial, A_par, B_par, C_par_panels, reports, panels,
+                              faults=None, n_faults=0):
+        """The protected product one k-panel at a time (batch 1).  C_par_panels: P x c_par_len doubles,
+        reports: P reports (device), with P = panel_count(panels)."""
+        _check(lib().gecc_protected_gemm_panels(self._h, _ptr(A), _ptr(B), _ptr(Cmat), _ptr(C_partial), _ptr(A_par),
+                                                _ptr(B_par), _ptr(C_par_panels), _ptr(reports), panels,
+                                                _ptr(faults), n_faults, _stream()))
+
+    def reports_to_host(self, report, count) -> List[Report]:
+        host = (Report * count)()
+        _check(lib().gecc_report_to_host(self._h, _ptr(report), host, count, _stream()))
+        return list(host)
 
     def protected_gemm_retry(self, A, B, Cmat, A_par, B_par, C_par, report, max_retries=1, faults=None, n_faults=0):
         """protected_gemm with recomputation on UNCORRECTABLE (waits for the stream after every

@@ -358,6 +358,60 @@ def test_results_are_reproducible_bit_for_bit():
     assert g1.reports[0].errors() == g2.reports[0].errors()
 
 
+# ---- per-k-panel verification: every partial product over a panel of k is a codeword ------------------
+@pytest.mark.parametrize("dtype,shape,trans,panels", [("bf16", (520, 512, 264), (0, 0), 4), ("bf16", (520, 512, 264), (0, 1), 2),
+                                                      ("bf16", (264, 448, 520), (1, 0), 3), ("f32", (300, 200, 260), (0, 0), 3),
+                                                      ("bf16", (1000, 512, 776), (1, 1), 1)])
+def test_protected_product_panel_by_panel(dtype, shape, trans, panels):
+    """gecc_protected_gemm_panels against the oracle's panel-wise path: same panels, same scaled
+    thresholds, one fault of C in every panel (each a single fault there, although together they
+    lie on a diagonal, beyond the code for the whole product).  Reports bit for bit, summed C to
+    1e-5, parity blocks of every partial product and the panel-wise operand parities to rounding."""
+    import torch
+    import ctypes as C
+    n, k, m = shape
+    rng = inputs.rng_for(97, n + k + panels)
+    A, B = inputs.operands(rng, n, k, m, ("normal", 1.0), ("normal", 1.0), dtype)
+    t = gecc.noise_thresholds(n, k, m, 1.0, 1.0)
+    tau_o = oc.Thresholds(t.r1, t.r2, t.q1, t.q2, t.op, t.rep, t.rel)
+    ctx = gecc.Context(n, k, m, gecc.BF16 if dtype == "bf16" else gecc.F32, t, trans_a=trans[0], trans_b=trans[1])
+    P = ctx.panel_count(panels)
+    bounds = oc.panel_bounds(k, panels)
+    assert P == len(bounds)
+    # faults: one of C per panel, together on a diagonal (the call encodes and multiplies in one
+    # go, so there is no moment for an operand fault between the two; the staged calls cover those)
+    cf = {g: [(10 + 60 * g, 20 + 60 * g, 25.0 + g)] for g in range(P)}
+    A2 = A
+    res, Csum = oc.protected_gemm_panels(A, B, A, B, cf, tau_o, bounds)
+    dA, dB = H.to_dev(A[None], dtype, trans[0]), H.to_dev(B[None], dtype, trans[1])
+    A_par, B_par, _ = ctx.alloc_parities()
+    C_par = torch.empty(P * (2 * n + 2 * m + 4), dtype=torch.float64, device=H.DEV)
+    reps = torch.zeros(P * C.sizeof(gecc.Report), dtype=torch.uint8, device=H.DEV)
+    Cd, Cp = ctx.alloc_c(), ctx.alloc_c()
+    Cd.fill_(float("nan")); Cp.fill_(float("nan"))
+    fl, nf = gecc.make_faults([(g, i, j, e) for g, lst in cf.items() for (i, j, e) in lst], H.DEV)
+    ctx.protected_gemm_panels(dA, dB, Cd, Cp if P > 1 else None, A_par, B_par, C_par, reps, panels, fl, nf)
+    host = ctx.reports_to_host(reps, P)
+    for g, (r, o) in enumerate(zip(host, res)):
+        assert r.status == o.status == gecc.CORRECTED, (g, r.status, o.status)
+        assert [e[:3] for e in r.errors()] == [e[:3] for e in o.errors] == [(MAT_C, 10 + 60 * g, 20 + 60 * g)]
+    scale = np.abs(Csum).max()
+    assert np.abs(Cd[0].cpu().numpy().astype(np.float64) - Csum).max() / scale <= 1e-5
+    # parity blocks of every partial product, and the operand parities panel after panel
+    cp = C_par.cpu().numpy().reshape(P, -1)
+    ap, bp = A_par.cpu().numpy(), B_par.cpu().numpy()
+    for g, (k0, k1) in enumerate(bounds):
+        ob = res[g].Cbar
+        ref = np.concatenate([ob[:n, m], ob[:n, m + 1], ob[n, :m], ob[n + 1, :m], ob[n:, m:].ravel()])
+        assert np.allclose(cp[g], ref, rtol=1e-10, atol=1e-11 * np.abs(ref).max()), g
+        assert np.allclose(ap[2 * k0:2 * k1].reshape(2, -1), oc.encode_a(A2[:, k0:k1]), rtol=1e-12, atol=1e-12)
+        assert np.allclose(bp[2 * k0:2 * k1].reshape(2, -1), oc.encode_b(B[k0:k1, :]).T, rtol=1e-12, atol=1e-12)
+    # the same three faults in one product of the whole k: beyond the code
+    if P >= 3:
+        g1 = H.run_gpu(A2, B, A2, B, [(0, 10 + 60 * g, 20 + 60 * g, 25.0 + g) for g in range(P)], t, dtype, trans[0], trans[1])
+        assert g1.reports[0].status == gecc.UNCORRECTABLE
+
+
 # ---- single-checksum mode (Section VI's comparison scheme: plain parities only) -----------------------
 @pytest.mark.parametrize("pattern", ["none", "C", "C+C same row", "C+C same column", "C+C elsewhere", "A", "B", "A+C", "B+C",
                                      "one row, 40 columns", "one column, 25 rows", "two rows", "C nan"])

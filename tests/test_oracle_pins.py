@@ -901,3 +901,44 @@ def test_single_checksum_verifies_its_estimates_and_ignores_the_weighted_sums():
     C3 = Cbar.copy(); C3[0, 0] = np.nan
     res = oc.decode_single_checksum(C3, A, AP, B, BP, TAU0_SINGLE)
     assert res.status == UNCORRECTABLE and (res.s, res.t) == (1, 1)
+
+
+# ---- per-k-panel verification: the code is linear, every partial product is a codeword -------------
+def test_partial_products_over_k_panels_are_codewords_and_add_up():
+    """Section III: C-bar = A-bar B-bar is linear in both operands, so with k cut into panels the
+    encoded partial products add up to C-bar block by block (exactly, on integers), and each of
+    them satisfies all of Definition 1's constraints on its own."""
+    n, k, m = 5, 12, 6
+    A, B = int_mats(123, n, k, m, -4, 4)
+    AP, BP = oc.encode_a(A), oc.encode_b(B)
+    full = oc.encoded_product(A, AP, B, BP)
+    bounds = oc.panel_bounds(k, 3, align=2)
+    assert bounds == [(0, 4), (4, 8), (8, 12)] and oc.panel_bounds(10, 4, align=4) == [(0, 4), (4, 8), (8, 10)]
+    total = np.zeros_like(full)
+    for (k0, k1) in bounds:
+        part = oc.encoded_product(A[:, k0:k1], oc.encode_a(A[:, k0:k1]), B[k0:k1, :], oc.encode_b(B[k0:k1, :]))
+        assert np.array_equal(oc.encode_a(A[:, k0:k1]), AP[:, k0:k1]) and np.array_equal(oc.encode_b(B[k0:k1, :]), BP[k0:k1, :])
+        assert all(np.all(v == 0) for v in oc.syndromes(part)) and np.all(oc.global_syndromes(part) == 0)
+        total += part
+    assert np.array_equal(total, full)
+
+
+def test_a_fault_is_caught_in_the_panel_it_strikes():
+    n, k, m = 6, 12, 5
+    A, B = int_mats(321, n, k, m)
+    bounds = oc.panel_bounds(k, 3, align=2)
+    clean = A @ B
+    # one fault of C in panel 1's partial product, one wrong symbol of A in panel 2 (column 9 = 1 of its slice)
+    A2 = A.copy(); A2[4, 9] += 3.0
+    res, C = oc.protected_gemm_panels(A, B, A2, B, {1: [(2, 3, -7.0)]}, TAU0, bounds)
+    assert [r.status for r in res] == [CLEAN, CORRECTED, CORRECTED]
+    assert res[1].errors == [(MAT_C, 2, 3, -7.0)] and res[2].errors == [(MAT_A, 4, 1, 3.0)]
+    assert np.array_equal(C, clean)
+    # two faults in two different panels are two single faults: each panel corrects its own, also
+    # where the whole product would see a pattern beyond the code (three faults on a diagonal)
+    res, C = oc.protected_gemm_panels(A, B, A, B, {0: [(0, 0, 1.0)], 1: [(1, 1, 2.0)], 2: [(2, 2, 4.0)]}, TAU0, bounds)
+    assert [r.status for r in res] == [CORRECTED] * 3 and np.array_equal(C, clean)
+    assert oc.protected_gemm(A, B, A, B, [(0, 0, 1.0), (1, 1, 2.0), (2, 2, 4.0)], TAU0).status == UNCORRECTABLE
+    # thresholds shrink with the panel: a third of the terms, a third of the rounding noise
+    t = oc.panel_thresholds(Thresholds(3.0, 6.0, 9.0, 12.0, 0.5, 0.25, 0.125), 4, 12)
+    assert (t.r1, t.r2, t.q1, t.q2, t.op, t.rep, t.rel) == (1.0, 2.0, 3.0, 4.0, 0.5, 0.25, 0.125)
