@@ -619,3 +619,42 @@ def protected_gemm_panels(A_enc, B_enc, A_mul, B_mul, c_faults_by_panel, tau, bo
         results.append(res)
         C = res.C.copy() if C is None else C + res.C
     return results, C
+
+
+# --------------------------------------------------------- blocked grid code (Section III per block)
+def protected_gemm_blocked(A_enc, B_enc, A_mul, B_mul, c_faults, tau, nb, mb):
+    """The code of Section III applied to every nb x mb block of C on its own.
+
+    Block (I, J) of C is the product of the row block A_I (nb x k) and the column block B_J
+    (k x mb), so it is encoded, multiplied and decoded exactly as Section III and V prescribe for
+    a product of that size: two parity rows per row block of A (weights 1..nb), two parity
+    columns per column block of B (weights 1..mb), parity blocks P_r, P_c, P_g per block of C.
+    Up to two errors are corrected *per block* (Theorem 1 holds block by block), the weights of
+    the weighted sums stay below the block size, and no syndrome involves more than one block.
+    tau: thresholds of one block.  n, m must be multiples of nb, mb.
+    Returns ({(I, J): Result} with positions relative to the block, C, A, B): C assembled from the
+    corrected blocks; A, B patched where the audit of a row block / column block located wrong
+    symbols (a block that needed no audit leaves its operands alone).
+    """
+    n, k = A_enc.shape
+    m = B_enc.shape[1]
+    assert n % nb == 0 and m % mb == 0
+    A_out = np.array(A_mul, dtype=np.float64)
+    B_out = np.array(B_mul, dtype=np.float64)
+    C = np.zeros((n, m))
+    results = {}
+    for I in range(n // nb):
+        ri = slice(I * nb, (I + 1) * nb)
+        for J in range(m // mb):
+            cj = slice(J * mb, (J + 1) * mb)
+            cf = [(i - I * nb, j - J * mb, e) for (i, j, e) in c_faults
+                  if I * nb <= i < (I + 1) * nb and J * mb <= j < (J + 1) * mb]
+            res = protected_gemm(A_enc[ri, :], B_enc[:, cj], A_mul[ri, :], B_mul[:, cj], cf, tau)
+            results[(I, J)] = res
+            C[ri, cj] = res.C
+            for (mt, r, c, e) in res.errors:          # located operand symbols: the same in every block of the line
+                if mt == MAT_A:
+                    A_out[I * nb + r, c] = res.A[r, c]
+                elif mt == MAT_B:
+                    B_out[r, J * mb + c] = res.B[r, c]
+    return results, C, A_out, B_out

@@ -942,3 +942,64 @@ def test_a_fault_is_caught_in_the_panel_it_strikes():
     # thresholds shrink with the panel: a third of the terms, a third of the rounding noise
     t = oc.panel_thresholds(Thresholds(3.0, 6.0, 9.0, 12.0, 0.5, 0.25, 0.125), 4, 12)
     assert (t.r1, t.r2, t.q1, t.q2, t.op, t.rep, t.rel) == (1.0, 2.0, 3.0, 4.0, 0.5, 0.25, 0.125)
+
+
+# ---- blocked grid code: Section III per nb x mb block of C ------------------------------------------
+def test_block_parities_add_up_to_the_parities_of_the_whole_product():
+    """Plain block parities of a line add up to the line's plain parity of the whole product, weighted
+    ones after shifting the block-local weights (1..mb) to the global ones: sum_J (w_J + J mb s_J)."""
+    n, k, m, nb, mb = 6, 5, 8, 3, 4
+    A, B = int_mats(55, n, k, m, -5, 5)
+    whole = oc.encoded_product(A, oc.encode_a(A), B, oc.encode_b(B))
+    pr1, pr2, pc1, pc2 = np.zeros(n), np.zeros(n), np.zeros(m), np.zeros(m)
+    for I in range(n // nb):
+        for J in range(m // mb):
+            AI, BJ = A[I * nb:(I + 1) * nb], B[:, J * mb:(J + 1) * mb]
+            blk = oc.encoded_product(AI, oc.encode_a(AI), BJ, oc.encode_b(BJ))
+            assert np.array_equal(blk[:nb, :mb], whole[I * nb:(I + 1) * nb, J * mb:(J + 1) * mb])
+            assert all(np.all(v == 0) for v in oc.syndromes(blk)) and np.all(oc.global_syndromes(blk) == 0)
+            pr1[I * nb:(I + 1) * nb] += blk[:nb, mb]
+            pr2[I * nb:(I + 1) * nb] += blk[:nb, mb + 1] + J * mb * blk[:nb, mb]
+            pc1[J * mb:(J + 1) * mb] += blk[nb, :mb]
+            pc2[J * mb:(J + 1) * mb] += blk[nb + 1, :mb] + I * nb * blk[nb, :mb]
+    assert np.array_equal(pr1, whole[:n, m]) and np.array_equal(pr2, whole[:n, m + 1])
+    assert np.array_equal(pc1, whole[n, :m]) and np.array_equal(pc2, whole[n + 1, :m])
+
+
+def test_blocked_code_corrects_two_errors_in_every_block():
+    """Theorem 1 block by block: two errors in each of the six blocks (twelve in all, far beyond the
+    whole-matrix code) are all located and removed; three errors in general position inside one block
+    exceed that block alone."""
+    n, k, m, nb, mb = 8, 4, 9, 4, 3
+    A, B = int_mats(56, n, k, m)
+    clean = A @ B
+    cf = []
+    for I in range(2):
+        for J in range(3):
+            cf += [(I * nb + 0, J * mb + 1, 3.0 + I + J), (I * nb + 2, J * mb + 2, -5.0 - J)]
+    res, C, A2, B2 = oc.protected_gemm_blocked(A, B, A, B, cf, TAU0, nb, mb)
+    assert all(r.status == CORRECTED and len(r.errors) == 2 for r in res.values())
+    assert res[(1, 2)].errors == [(MAT_C, 0, 1, 6.0), (MAT_C, 2, 2, -7.0)]        # block-local positions
+    assert np.array_equal(C, clean)
+    assert oc.protected_gemm(A, B, A, B, cf, TAU0).status == UNCORRECTABLE
+    cf3 = [(0, 0, 1.0), (1, 1, 2.0), (2, 2, 4.0), (5, 7, 9.0)]
+    res, C, _, _ = oc.protected_gemm_blocked(A, B, A, B, cf3, TAU0, nb, mb)
+    assert res[(0, 0)].status == UNCORRECTABLE and res[(1, 2)].status == CORRECTED
+    assert sum(r.status == CLEAN for r in res.values()) == 4
+    assert np.array_equal(C[nb:], clean[nb:])
+
+
+def test_blocked_code_traces_an_operand_error_through_every_block_of_its_line():
+    """A wrong symbol of A spoils row i of C in every column block; each of those blocks finds it in
+    the parity rows of its own row block of A (weights 1..nb: the position comes out block-local),
+    repairs its part of the row, and the operand is restored.  The other row blocks stay clean."""
+    n, k, m, nb, mb = 8, 4, 9, 4, 3
+    A, B = int_mats(57, n, k, m)
+    A2 = A.copy(); A2[6, 1] += 5.0
+    B2 = B.copy(); B2[3, 4] -= 2.0
+    res, C, Ap, Bp = oc.protected_gemm_blocked(A, B, A2, B2, [(1, 8, 7.0)], TAU0, nb, mb)
+    assert np.array_equal(C, A @ B) and np.array_equal(Ap, A) and np.array_equal(Bp, B)
+    assert [res[(1, J)].errors for J in (0, 2)] == [[(MAT_A, 2, 1, 5.0)]] * 2
+    assert res[(1, 1)].errors == [(MAT_A, 2, 1, 5.0), (MAT_B, 3, 1, -2.0)]
+    assert res[(0, 1)].errors == [(MAT_B, 3, 1, -2.0)]
+    assert res[(0, 2)].errors == [(MAT_C, 1, 2, 7.0)] and res[(0, 0)].status == CLEAN
