@@ -97,6 +97,24 @@ typedef struct {
         its place in it), is GECC_UNCORRECTABLE.  tau_r2 / tau_q2 are ignored, max_abs_synd[1] and
         [3] read 0. */
   int32_t weighted;
+  /* Blocked grid code: block_n = block_m = 0 (the default) encodes the whole product as one
+     codeword, as Section III does.  block_n, block_m > 0 (multiples of 128 that divide n and m;
+     batch = 1, weighted = 1) apply Section III to every block_n x block_m block of C on its own:
+     block (I, J) = A[rows of I, :] B[:, columns of J] gets two parity rows over its row block of A
+     (weights 1 .. block_n), two parity columns over its column block of B (weights 1 .. block_m)
+     and its own parity blocks P_r, P_c, P_g; Section V runs per block.  Up to two errors are
+     corrected per block, the weights (and with them the rounding noise of the weighted sums,
+     hence tau_r2 / tau_q2) are bounded by the block size, and no syndrome crosses a block.  The
+     four thresholds are those of one block.  Buffer shapes in this mode, with NI = n / block_n,
+     NJ = m / block_m, item (I, J) = I * NJ + J:
+       A_par  NI x [2][k]      B_par  NJ x [2][k]
+       C_par  NI * NJ items x { P_r [2][block_n], P_c [2][block_m], P_g [4] }
+       reports, syndromes      one per item, positions relative to the block (operand errors: row
+                               inside the row block of A / column inside the column block of B)
+     gecc_item_count() gives NI * NJ; gecc_a_par_len() etc. give the sizes above.  The parity blocks
+     P_r, P_c are formed on the matrix units (A times the parity columns of all column blocks at
+     once, split into three bf16 pieces each for bf16 operands), in fp32 like C itself. */
+  int32_t block_n, block_m;
   int32_t reserved;
 } gecc_params;
 
@@ -147,10 +165,12 @@ void gecc_destroy(gecc_ctx* ctx);
 size_t gecc_workspace_bytes(const gecc_ctx* ctx);
 int gecc_set_workspace(gecc_ctx* ctx, void* dev_workspace, size_t bytes);
 
-/* Sizes (in doubles, per batch item) of the parity buffers below. */
+/* Sizes (in doubles, per batch item) of the parity buffers below (blocked mode: see gecc_params). */
 size_t gecc_a_par_len(const gecc_ctx* ctx); /* 2*k           */
 size_t gecc_b_par_len(const gecc_ctx* ctx); /* 2*k           */
 size_t gecc_c_par_len(const gecc_ctx* ctx); /* 2*n + 2*m + 4 */
+/* Number of reports (and of syndrome records) a call fills: batch, or the number of blocks. */
+int32_t gecc_item_count(const gecc_ctx* ctx);
 
 /* ---- the path ----------------------------------------------------------------------- */
 

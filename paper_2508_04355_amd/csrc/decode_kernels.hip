@@ -37,12 +37,22 @@ __device__ __forceinline__ void store_elem(void* P, int dtype, int64_t idx, doub
     reinterpret_cast<float*>(P)[idx] = f;
   }
 }
-__device__ __forceinline__ int64_t a_index(const gecc_params& p, int b, int i, int l) {
-  return (int64_t)b * p.stride_a + (p.trans_a ? (int64_t)l * p.lda + i : (int64_t)i * p.lda + l);
+// item b -> its row block I (A, A_P) and column block J (B, B_P); batch items: I = J = b
+__device__ __forceinline__ int item_i(const DecodeArgs& a, int b) { return a.nbj ? b / a.nbj : b; }
+__device__ __forceinline__ int item_j(const DecodeArgs& a, int b) { return a.nbj ? b % a.nbj : b; }
+__device__ __forceinline__ int64_t a_index(const DecodeArgs& a, int b, int i, int l) {
+  const gecc_params& p = a.p;
+  return (int64_t)item_i(a, b) * a.ia_stride + (p.trans_a ? (int64_t)l * p.lda + i : (int64_t)i * p.lda + l);
 }
-__device__ __forceinline__ int64_t b_index(const gecc_params& p, int b, int l, int j) {
-  return (int64_t)b * p.stride_b + (p.trans_b ? (int64_t)j * p.ldb + l : (int64_t)l * p.ldb + j);
+__device__ __forceinline__ int64_t b_index(const DecodeArgs& a, int b, int l, int j) {
+  const gecc_params& p = a.p;
+  return (int64_t)item_j(a, b) * a.jb_stride + (p.trans_b ? (int64_t)j * p.ldb + l : (int64_t)l * p.ldb + j);
 }
+__device__ __forceinline__ float* c_of(const DecodeArgs& a, int b) {
+  return a.C + (int64_t)item_i(a, b) * a.ic_stride + (int64_t)item_j(a, b) * a.jc_stride;
+}
+__device__ __forceinline__ const double* apar_of(const DecodeArgs& a, int b) { return a.A_par + (int64_t)item_i(a, b) * 2 * a.p.k; }
+__device__ __forceinline__ const double* bpar_of(const DecodeArgs& a, int b) { return a.B_par + (int64_t)item_j(a, b) * 2 * a.p.k; }
 
 // Section V step 1 clears a line when |sum - parity| <= threshold holds; anything else, a NaN
 // included, flags it.
@@ -311,8 +321,8 @@ __device__ double block_dot(const DecodeArgs& a, int b, int i, int j, double* re
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int l = min(l0 + u * DC_THREADS, a.p.k - 1);
-      x[u] = load_elem(a.A, a.p.dtype, a_index(a.p, b, i, l));
-      y[u] = load_elem(a.B, a.p.dtype, b_index(a.p, b, l, j));
+      x[u] = load_elem(a.A, a.p.dtype, a_index(a, b, i, l));
+      y[u] = load_elem(a.B, a.p.dtype, b_index(a, b, l, j));
     }
 #pragma unroll
     for (int u = 0; u < U; ++u)
@@ -425,7 +435,7 @@ __device__ int known_lines_correct(const DecodeArgs& a, int b, DecodeState* st, 
   int idx[2];
   if (rows_known) { idx[0] = before[0]; idx[1] = total[0] + before[1]; }     // row K0 first, then row K1
   else            { idx[0] = idx[1] = before[0] + before[1]; }               // row by row
-  float* C = a.C + (int64_t)b * a.p.stride_c;
+  float* C = c_of(a, b);
   for (int c = c0; c < c1; ++c) {
     const LineEst e = estimate(c);
     if (!e.flagged) continue;
@@ -515,12 +525,12 @@ __device__ void decode_c_body(const DecodeArgs& a, int b, DecodeState* st, gecc_
   if (k < 0) {
     if (threadIdx.x == 0) {
       if (final_pass) { rep->status = GECC_UNCORRECTABLE; rep->n_err = 0; rep->n_total = 0; st->phase = PH_DONE; }
-      else            { st->phase = PH_AUDIT; }
+      else            { st->phase = PH_AUDIT; if (a.gate_word) *a.gate_word = PH_AUDIT; }
     }
     return;
   }
   // patch C: Section V's subtraction, optionally followed by re-evaluating the symbol
-  float* C = a.C + (int64_t)b * a.p.stride_c;
+  float* C = c_of(a, b);
   for (int e = 0; e < k; ++e) {
     const int64_t idx = (int64_t)fix[e].i * a.p.ldc + fix[e].j;
     if (a.p.refine) {
@@ -594,6 +604,9 @@ __device__ void sort_hits(AuditHit* h, int cnt) {
 constexpr int RP_THREADS = 1024;   // one workgroup per batch item: latency-bound loops, so a full one
 constexpr int RP_U = 4;            // symbols (lines) a thread has in flight
 
+// SPLIT (blocked mode: several blocks share an operand line): this launch leaves the operands alone
+// and stops before Section V's second pass; patch_operands_kernel and final_decode_kernel follow.
+template <bool SPLIT>
 __global__ __launch_bounds__(RP_THREADS) void repair_kernel(DecodeArgs a) {
   const int b = blockIdx.x;
   DecodeState* st = state_of(a, b);
@@ -605,10 +618,10 @@ __global__ __launch_bounds__(RP_THREADS) void repair_kernel(DecodeArgs a) {
   if (threadIdx.x == 0) { cnt_a = 0; cnt_b = 0; }
   __syncthreads();
   {   // difference of the re-formed and the stored operand parities, line by line
-    const double* cur_a = a.audit_a + (int64_t)b * 2 * k;
-    const double* cur_b = a.audit_b + (int64_t)b * 2 * k;
-    const double* ref_a = a.A_par + (int64_t)b * 2 * k;
-    const double* ref_b = a.B_par + (int64_t)b * 2 * k;
+    const double* cur_a = a.audit_a + (int64_t)item_i(a, b) * 2 * k;
+    const double* cur_b = a.audit_b + (int64_t)item_j(a, b) * 2 * k;
+    const double* ref_a = apar_of(a, b);
+    const double* ref_b = bpar_of(a, b);
 #pragma unroll 4
     for (int l = threadIdx.x; l < k; l += blockDim.x) {
       bool hit;
@@ -635,10 +648,10 @@ __global__ __launch_bounds__(RP_THREADS) void repair_kernel(DecodeArgs a) {
     if (threadIdx.x == 0) { rep->status = GECC_UNCORRECTABLE; rep->n_err = 0; rep->n_total = 0; st->phase = PH_DONE; }
     return;
   }
-  float* C = a.C + (int64_t)b * a.p.stride_c;
+  float* C = c_of(a, b);
   double* cpar = cpar_of(a, b);
-  const double* apar = a.A_par + (int64_t)b * 2 * k;
-  const double* bpar = a.B_par + (int64_t)b * 2 * k;
+  const double* apar = apar_of(a, b);
+  const double* bpar = bpar_of(a, b);
   // threshold allowances of the lines a repair touches (rounding noise of the corrupted terms)
   double* al_r1 = allow_of(a, b);
   double* al_r2 = al_r1 + n;
@@ -672,7 +685,7 @@ __global__ __launch_bounds__(RP_THREADS) void repair_kernel(DecodeArgs a) {
       for (int u = 0; u < RP_U; ++u) {
         const int j = min(j0 + u * RP_THREADS, m - 1);
         cold[u] = C[(int64_t)i * a.p.ldc + j];
-        bv[u] = load_elem(a.B, a.p.dtype, b_index(a.p, b, l, j));
+        bv[u] = load_elem(a.B, a.p.dtype, b_index(a, b, l, j));
         q1[u] = sy_q1[j]; q2[u] = sy_q2[j]; g1[u] = al_q1[j]; g2[u] = al_q2[j];
       }
 #pragma unroll
@@ -722,7 +735,7 @@ __global__ __launch_bounds__(RP_THREADS) void repair_kernel(DecodeArgs a) {
       for (int u = 0; u < RP_U; ++u) {
         const int i = min(i0 + u * RP_THREADS, n - 1);
         cold[u] = C[(int64_t)i * a.p.ldc + j];
-        av[u] = load_elem(a.A, a.p.dtype, a_index(a.p, b, i, l));
+        av[u] = load_elem(a.A, a.p.dtype, a_index(a, b, i, l));
         r1[u] = sy_r1[i]; r2[u] = sy_r2[i]; g1[u] = al_r1[i]; g2[u] = al_r2[i];
       }
 #pragma unroll
@@ -761,12 +774,12 @@ __global__ __launch_bounds__(RP_THREADS) void repair_kernel(DecodeArgs a) {
     __syncthreads();
   }
   if (threadIdx.x == 0) {
-    for (int x = 0; x < na; ++x) {
-      const int64_t ia = a_index(a.p, b, ha[x].pos, ha[x].line);
+    for (int x = 0; x < na && !SPLIT; ++x) {
+      const int64_t ia = a_index(a, b, ha[x].pos, ha[x].line);
       store_elem(a.A, a.p.dtype, ia, load_elem(a.A, a.p.dtype, ia) - ha[x].e);
     }
-    for (int x = 0; x < nb; ++x) {
-      const int64_t ib = b_index(a.p, b, hb[x].line, hb[x].pos);
+    for (int x = 0; x < nb && !SPLIT; ++x) {
+      const int64_t ib = b_index(a, b, hb[x].line, hb[x].pos);
       store_elem(a.B, a.p.dtype, ib, load_elem(a.B, a.p.dtype, ib) - hb[x].e);
     }
     // located operand errors, sorted by (matrix, row, col)
@@ -829,8 +842,166 @@ __global__ __launch_bounds__(RP_THREADS) void repair_kernel(DecodeArgs a) {
   if (threadIdx.x == 0) { st->s_cnt = res_s; st->t_cnt = res_t; st->nonfinite = res_bad; st->phase = PH_REVERIFY; }
   __syncthreads();
   // ... and step 2, by the first DC_THREADS threads (the other wavefronts end here)
-  if (threadIdx.x >= DC_THREADS) return;
+  if (SPLIT || threadIdx.x >= DC_THREADS) return;
   decode_c_body(a, b, st, rep, 1);
+}
+
+// Blocked mode, after repair_kernel<true>: the located operand symbols are put right, once per
+// operand line (workgroup x < nbi: row block x of A; otherwise column block x - nbi of B), from
+// the same parity differences the blocks used -- after every block has finished reading the
+// operands as the product read them.
+__global__ __launch_bounds__(256) void patch_operands_kernel(DecodeArgs a, int nbi) {
+  if (*a.gate_word != PH_AUDIT) return;
+  const bool is_a = (int)blockIdx.x < nbi;
+  const int line_blk = is_a ? blockIdx.x : blockIdx.x - nbi;
+  const int b = is_a ? line_blk * a.nbj : line_blk;           // an item of that line (item_i / item_j = line_blk)
+  const int k = a.p.k, len = is_a ? a.p.n : a.p.m;
+  const double* cur = (is_a ? a.audit_a : a.audit_b) + (int64_t)line_blk * 2 * k;
+  const double* ref = (is_a ? a.A_par : a.B_par) + (int64_t)line_blk * 2 * k;
+  __shared__ int cnt;
+  __shared__ AuditHit h[GECC_MAX_ERR];
+  if (threadIdx.x == 0) cnt = 0;
+  __syncthreads();
+  for (int l = threadIdx.x; l < k; l += blockDim.x) {
+    bool hit;
+    const AuditHit x = audit_line(cur, ref, k, l, len, a.p.tau_op, true, &hit);
+    if (hit) { const int idx = atomicAdd(&cnt, 1); if (idx < GECC_MAX_ERR) h[idx] = x; }
+  }
+  __syncthreads();
+  if (threadIdx.x != 0 || cnt == 0 || cnt > GECC_MAX_ERR) return;
+  for (int x = 0; x < cnt; ++x) if (h[x].pos < 0) return;      // a line no single wrong symbol explains: hands off
+  for (int x = 0; x < cnt; ++x) {
+    const int64_t idx = is_a ? a_index(a, b, h[x].pos, h[x].line) : b_index(a, b, h[x].line, h[x].pos);
+    void* M = is_a ? a.A : a.B;
+    store_elem(M, a.p.dtype, idx, load_elem(M, a.p.dtype, idx) - h[x].e);
+  }
+}
+
+// Blocked mode: Section V once more on what the repairs left, block by block.
+__global__ __launch_bounds__(DC_THREADS) void final_decode_kernel(DecodeArgs a) {
+  const int b = blockIdx.x;
+  DecodeState* st = state_of(a, b);
+  if (st->phase != PH_REVERIFY) return;
+  decode_c_body(a, b, st, a.report + b, 1);
+}
+
+// Blocked mode: syndromes of every block from the partial sums of the 128 x 128 sub-tiles (a block
+// is a whole number of them), one thread per line and block along it.  a.p.n, a.p.m: block sizes.
+__global__ __launch_bounds__(256) void threshold_blocked_kernel(DecodeArgs a, int n_full, int m_full) {
+  const int nb = a.p.n, mb = a.p.m, nbj = a.nbj, nbi = n_full / nb;
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t total_r = (int64_t)n_full * nbj, total = total_r + (int64_t)m_full * nbi;
+  if (idx >= total) return;
+  const bool is_row = idx < total_r;
+  double S = 0.0, W = 0.0;
+  int b, loc;
+  if (is_row) {
+    const int i = (int)(idx % n_full), J = (int)(idx / n_full);
+    const float2* pp = reinterpret_cast<const float2*>(a.rowpart) + i;
+    for (int t = J * (mb / 128); t < (J + 1) * (mb / 128); ++t) {
+      const float2 v = pp[(int64_t)t * a.rp_ld];
+      S += (double)v.x;
+      W += (double)v.y + (double)(t * 128 - J * mb) * (double)v.x;
+    }
+    b = (i / nb) * nbj + J; loc = i % nb;
+  } else {
+    const int64_t o = idx - total_r;
+    const int j = (int)(o % m_full), I = (int)(o / m_full);
+    const float2* pp = reinterpret_cast<const float2*>(a.colpart) + j;
+    for (int t = I * (nb / 128); t < (I + 1) * (nb / 128); ++t) {
+      const float2 v = pp[(int64_t)t * a.cp_ld];
+      S += (double)v.x;
+      W += (double)v.y + (double)(t * 128 - I * nb) * (double)v.x;
+    }
+    b = I * nbj + j / mb; loc = j % mb;
+  }
+  DecodeState* st = state_of(a, b);
+  const double* cpar = cpar_of(a, b);
+  double* synd = synd_of(a, b);
+  const int o1 = is_row ? loc : 2 * nb + loc, o2 = is_row ? nb + loc : 2 * nb + mb + loc;
+  const double v1 = S - cpar[o1], v2 = W - cpar[o2];
+  synd[o1] = v1;
+  synd[o2] = v2;
+  const double t1 = is_row ? a.p.tau_r1 : a.p.tau_q1, t2 = is_row ? a.p.tau_r2 : a.p.tau_q2;
+  if (outside(v1, t1) || outside(v2, t2)) {
+    const int x = atomicAdd(is_row ? &st->s_cnt : &st->t_cnt, 1);
+    if (x < GECC_MAX_ERR) (is_row ? st->rows : st->cols)[x] = loc;
+  }
+  if (!finite2(v1, v2)) atomicOr(&st->nonfinite, 1);
+  // family maxima of the block: non-negative doubles order like their bit patterns (a NaN above all)
+  unsigned long long* mx = reinterpret_cast<unsigned long long*>(a.blockmax) + (int64_t)b * 4 + (is_row ? 0 : 2);
+  atomicMax(mx, (unsigned long long)__double_as_longlong(fabs(v1)));
+  atomicMax(mx + 1, (unsigned long long)__double_as_longlong(fabs(v2)));
+}
+
+// Blocked mode: the parity blocks of every block of C-bar from the two side products (A times the
+// parity columns of all column blocks, the parity rows of all row blocks times B), P_g in fp64,
+// and the per-block resets.  One workgroup per block.
+__global__ __launch_bounds__(256) void blocked_parities_kernel(BlockedParityArgs a) {
+  const int b = blockIdx.x, I = b / a.nbj, J = b % a.nbj;
+  const int nb = a.nb, mb = a.mb, S = a.pieces;
+  double* cpar = a.C_par + (int64_t)b * (2 * nb + 2 * mb + 4);
+  for (int o = threadIdx.x; o < 2 * nb; o += blockDim.x) {
+    const int t = o / nb, il = o % nb;
+    const float* p = a.side_r + (int64_t)(I * nb + il) * a.ld_r + (J * 2 + t) * S;
+    double v = 0.0;
+    for (int s = 0; s < S; ++s) v += (double)p[s];
+    cpar[o] = v;
+  }
+  for (int o = threadIdx.x; o < 2 * mb; o += blockDim.x) {
+    const int t = o / mb, jl = o % mb;
+    const float* p = a.side_c + (int64_t)((I * 2 + t) * S) * a.ld_c + J * mb + jl;
+    double v = 0.0;
+    for (int s = 0; s < S; ++s) v += (double)p[(int64_t)s * a.ld_c];
+    cpar[2 * nb + o] = v;
+  }
+  const double* ap = a.A_par + (int64_t)I * 2 * a.k;
+  const double* bp = a.B_par + (int64_t)J * 2 * a.k;
+  double acc[4] = {0.0, 0.0, 0.0, 0.0};
+  for (int l = threadIdx.x; l < a.k; l += blockDim.x) {
+    const double a0 = ap[l], a1 = ap[a.k + l], b0 = bp[l], b1 = bp[a.k + l];
+    acc[0] = fma(a0, b0, acc[0]); acc[1] = fma(a0, b1, acc[1]);
+    acc[2] = fma(a1, b0, acc[2]); acc[3] = fma(a1, b1, acc[3]);
+  }
+  __shared__ double red[4][4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) acc[q] += __shfl_down(acc[q], off, 64);
+  if ((threadIdx.x & 63) == 0)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) red[threadIdx.x >> 6][q] = acc[q];
+  __syncthreads();
+  if (threadIdx.x < 4) cpar[2 * nb + 2 * mb + threadIdx.x] = (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
+  if (threadIdx.x == 0) {
+    reset_state(a.state + b);
+    for (int f = 0; f < 4; ++f) a.itemmax[(int64_t)b * 4 + f] = 0.0;
+    if (b == 0) *a.gate_word = PH_DONE;
+  }
+}
+
+// fp64 parities -> rows of an operand of the product: `pieces` values of the operand's type per
+// parity whose sum (in fp32 arithmetic of the product) restores 24 bits of it
+__global__ __launch_bounds__(256) void split_parities_kernel(const double* par, void* W, int dtype, int lines, int k,
+                                                             int pieces, int rows_padded) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (int64_t)rows_padded * k) return;
+  const int row = (int)(idx / k), l = (int)(idx % k);
+  const int line_t = row / pieces, s = row % pieces;     // line_t = line * 2 + t
+  double x = line_t < 2 * lines ? par[(int64_t)line_t * k + l] : 0.0;
+  if (dtype == GECC_F32) {
+    reinterpret_cast<float*>(W)[idx] = (float)x;
+    return;
+  }
+  float piece = 0.f;
+  for (int q = 0; q <= s; ++q) {          // hi, then what is left of it, then what is left of that
+    uint32_t u = __float_as_uint((float)x);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    u &= 0xffff0000u;
+    piece = __uint_as_float(u);
+    x -= (double)piece;
+  }
+  reinterpret_cast<uint16_t*>(W)[idx] = (uint16_t)(__float_as_uint(piece) >> 16);
 }
 
 }  // namespace
@@ -857,7 +1028,36 @@ hipError_t launch_decode_c(const DecodeArgs& a, int with_summary, hipStream_t st
 }
 
 hipError_t launch_repair(const DecodeArgs& a, hipStream_t st) {
-  hipLaunchKernelGGL(repair_kernel, dim3(a.p.batch), dim3(RP_THREADS), 0, st, a);
+  hipLaunchKernelGGL(repair_kernel<false>, dim3(a.p.batch), dim3(RP_THREADS), 0, st, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_repair_blocked(const DecodeArgs& a, int nbi, hipStream_t st) {
+  hipLaunchKernelGGL(repair_kernel<true>, dim3(a.p.batch), dim3(RP_THREADS), 0, st, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(patch_operands_kernel, dim3(nbi + a.nbj), dim3(256), 0, st, a, nbi);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  hipLaunchKernelGGL(final_decode_kernel, dim3(a.p.batch), dim3(DC_THREADS), 0, st, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_threshold_blocked(const DecodeArgs& a, int n_full, int m_full, hipStream_t st) {
+  const int64_t total = (int64_t)n_full * a.nbj + (int64_t)m_full * (n_full / a.p.n);
+  hipLaunchKernelGGL(threshold_blocked_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, a, n_full, m_full);
+  return hipGetLastError();
+}
+
+hipError_t launch_blocked_parities(const BlockedParityArgs& a, hipStream_t st) {
+  hipLaunchKernelGGL(blocked_parities_kernel, dim3(a.nbi * a.nbj), dim3(256), 0, st, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_split_parities(const double* par, void* W, int dtype, int lines, int k, int pieces, int rows_padded,
+                                 hipStream_t st) {
+  const int64_t total = (int64_t)rows_padded * k;
+  hipLaunchKernelGGL(split_parities_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, par, W, dtype, lines, k,
+                     pieces, rows_padded);
   return hipGetLastError();
 }
 

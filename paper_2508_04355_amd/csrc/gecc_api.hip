@@ -13,20 +13,25 @@ size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 size_t elem_size(int dtype) { return dtype == GECC_BF16 ? 2 : 4; }
 
+bool blocked(const gecc_ctx* c) { return c->nbi > 0; }
+int items_of(const gecc_ctx* c) { return blocked(c) ? c->nbi * c->nbj : c->p.batch; }
+
 void make_layout(gecc_ctx* c) {
   const gecc_params& p = c->p;
   const size_t b = p.batch, n = p.n, k = p.k, m = p.m;
+  const size_t ni = blocked(c) ? c->nbi : 1, nj = blocked(c) ? c->nbj : 1;   // (blocked mode has batch 1)
   Layout& L = c->lay;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
   L.rowpart = take(b * c->ntn * (size_t)c->rp_ld * 2 * sizeof(float));
   L.colpart = take(b * c->ntm * (size_t)c->cp_ld * 2 * sizeof(float));
-  L.synd = take(b * (2 * n + 2 * m) * sizeof(double));
-  L.allow = take(b * (2 * n + 2 * m) * sizeof(double));
-  L.state = take(b * sizeof(DecodeState));
-  L.audit_a = take(b * 2 * k * sizeof(double));
-  L.audit_b = take(b * 2 * k * sizeof(double));
-  L.blockmax = take(b * ((n + m + 63) / 64) * 4 * sizeof(double));
+  // (blocked mode: one record per block, nj * 2n + ni * 2m doubles in all; audits per operand line)
+  L.synd = take(b * (nj * 2 * n + ni * 2 * m) * sizeof(double));
+  L.allow = take(b * (nj * 2 * n + ni * 2 * m) * sizeof(double));
+  L.state = take(b * ni * nj * sizeof(DecodeState));
+  L.audit_a = take(b * ni * 2 * k * sizeof(double));
+  L.audit_b = take(b * nj * 2 * k * sizeof(double));
+  L.blockmax = take(b * (((n + m + 63) / 64) + ni * nj) * 4 * sizeof(double));
   // column reductions: A side reduces over n (A stored n x k) or over k (P_r with A stored
   // k x n); B side over k (P_c with B stored k x m) or over m (B stored m x k)
   const size_t sa = p.trans_a ? coldot_scratch_doubles(p.k, p.n, p.batch)
@@ -39,6 +44,15 @@ void make_layout(gecc_ctx* c) {
   const size_t ra = tile_scan_row_scratch_doubles(p.trans_a ? p.k : p.n, p.trans_a ? p.n : p.k, p.dtype, p.batch);
   const size_t rb = tile_scan_row_scratch_doubles(p.trans_b ? p.m : p.k, p.trans_b ? p.k : p.m, p.dtype, p.batch);
   L.scan_row = take((ra > rb ? ra : rb) * sizeof(double));
+  L.w_a = L.w_b = L.side_r = L.side_c = L.gate = 0;
+  if (blocked(c)) {
+    const size_t esz = p.dtype == GECC_BF16 ? 2 : 4;
+    L.w_a = take((size_t)c->w_cols_a * k * esz);
+    L.w_b = take((size_t)c->w_cols_b * k * esz);
+    L.side_r = take(n * (size_t)c->w_cols_b * sizeof(float));
+    L.side_c = take((size_t)c->w_cols_a * m * sizeof(float));
+    L.gate = take(256);
+  }
   L.total = off;
 }
 
@@ -71,7 +85,41 @@ DecodeArgs decode_args(gecc_ctx* c, void* A, const double* A_par, void* B, const
   d.audit_a = reinterpret_cast<double*>(c->ws + c->lay.audit_a);
   d.audit_b = reinterpret_cast<double*>(c->ws + c->lay.audit_b);
   d.report = rep;
+  d.nbj = 0;
+  d.ia_stride = c->p.stride_a; d.jb_stride = c->p.stride_b; d.ic_stride = c->p.stride_c; d.jc_stride = 0;
+  d.gate_word = nullptr;
+  if (blocked(c)) {
+    // the decoder sees every block as an item of its own: n, m are the block sizes
+    const gecc_params& p = c->p;
+    d.p.n = p.block_n; d.p.m = p.block_m; d.p.batch = c->nbi * c->nbj;
+    d.nbj = c->nbj;
+    d.ia_stride = p.trans_a ? (int64_t)p.block_n : (int64_t)p.block_n * p.lda;
+    d.jb_stride = p.trans_b ? (int64_t)p.block_m * p.ldb : (int64_t)p.block_m;
+    d.ic_stride = (int64_t)p.block_n * p.ldc; d.jc_stride = p.block_m;
+    d.nblk = 1;
+    d.blockmax += (size_t)((p.n + p.m + 63) / 64) * 4;     // the per-block maxima live behind the per-workgroup ones
+    d.gate_word = reinterpret_cast<int32_t*>(c->ws + c->lay.gate);
+  }
   return d;
+}
+
+// Blocked mode: the row blocks of A (column blocks of B) as batch items of the scans -- a copy of
+// the context whose n (m) is the block size, whose batch is the number of blocks and whose batch
+// stride walks from block to block.  Both views use the tile scan for their operand (encoding and
+// audit alike) where it applies.
+gecc_ctx view_a(const gecc_ctx* c) {
+  gecc_ctx v = *c;
+  v.p.n = c->p.block_n; v.p.batch = c->nbi;
+  v.p.stride_a = c->p.trans_a ? (int64_t)c->p.block_n : (int64_t)c->p.block_n * c->p.lda;
+  v.nbi = v.nbj = 0; v.tile_op = GECC_MAT_A;
+  return v;
+}
+gecc_ctx view_b(const gecc_ctx* c) {
+  gecc_ctx v = *c;
+  v.p.m = c->p.block_m; v.p.batch = c->nbj;
+  v.p.stride_b = c->p.trans_b ? (int64_t)c->p.block_m * c->p.ldb : (int64_t)c->p.block_m;
+  v.nbi = v.nbj = 0; v.tile_op = GECC_MAT_B;
+  return v;
 }
 
 ScanArgs scan_base(const gecc_ctx* c, const void* X, int64_t ld, int64_t xs) {
@@ -289,6 +337,10 @@ int gecc_create(gecc_ctx** out, const gecc_params* p) {
       !(p->tau_op >= 0) || !(p->tau_rep >= 0) || !(p->tau_rel >= 0))
     return GECC_ERR_ARG;
   if (p->weighted != 0 && p->weighted != 1) return GECC_ERR_ARG;
+  if ((p->block_n == 0) != (p->block_m == 0) || p->block_n < 0 || p->block_m < 0) return GECC_ERR_ARG;
+  if (p->block_n > 0 && (p->block_n % 128 || p->block_m % 128 || p->n % p->block_n || p->m % p->block_m ||
+                         p->batch != 1 || p->weighted != 1))
+    return GECC_ERR_ARG;
   if ((int64_t)p->n + p->m > (int64_t)1 << 30) return GECC_ERR_ARG;
   gecc_ctx* c = new (std::nothrow) gecc_ctx;
   if (!c) return GECC_ERR_ARG;
@@ -300,6 +352,11 @@ int gecc_create(gecc_ctx** out, const gecc_params* p) {
   }
   // the larger operand is read once for both of its reductions (tile scan), the other one twice
   c->tile_op = p->n >= p->m ? GECC_MAT_A : GECC_MAT_B;
+  c->nbi = p->block_n > 0 ? p->n / p->block_n : 0;
+  c->nbj = p->block_n > 0 ? p->m / p->block_m : 0;
+  c->pieces = p->dtype == GECC_BF16 ? 3 : 1;
+  c->w_cols_a = (2 * c->pieces * c->nbi + 7) / 8 * 8;
+  c->w_cols_b = (2 * c->pieces * c->nbj + 7) / 8 * 8;
   c->tile_m = 128;
   c->tile_n = 128;
   c->ntm = (p->n + c->tile_m - 1) / c->tile_m;
@@ -393,17 +450,30 @@ int gecc_set_workspace(gecc_ctx* ctx, void* dev_workspace, size_t bytes) {
   return GECC_OK;
 }
 
-size_t gecc_a_par_len(const gecc_ctx* ctx) { return ctx ? 2 * (size_t)ctx->p.k : 0; }
-size_t gecc_b_par_len(const gecc_ctx* ctx) { return ctx ? 2 * (size_t)ctx->p.k : 0; }
-size_t gecc_c_par_len(const gecc_ctx* ctx) {
-  return ctx ? 2 * (size_t)ctx->p.n + 2 * (size_t)ctx->p.m + 4 : 0;
+size_t gecc_a_par_len(const gecc_ctx* ctx) {
+  return ctx ? 2 * (size_t)ctx->p.k * (blocked(ctx) ? ctx->nbi : 1) : 0;
 }
+size_t gecc_b_par_len(const gecc_ctx* ctx) {
+  return ctx ? 2 * (size_t)ctx->p.k * (blocked(ctx) ? ctx->nbj : 1) : 0;
+}
+size_t gecc_c_par_len(const gecc_ctx* ctx) {
+  if (!ctx) return 0;
+  if (blocked(ctx)) return (size_t)ctx->nbi * ctx->nbj * (2 * (size_t)ctx->p.block_n + 2 * (size_t)ctx->p.block_m + 4);
+  return 2 * (size_t)ctx->p.n + 2 * (size_t)ctx->p.m + 4;
+}
+int32_t gecc_item_count(const gecc_ctx* ctx) { return ctx ? items_of(ctx) : 0; }
 
 int gecc_encode_a(gecc_ctx* ctx, const void* dev_A, double* dev_A_par, void* stream) {
   int rc = check_ws(ctx);
   if (rc) return rc;
   if (!dev_A || !dev_A_par) return GECC_ERR_ARG;
   if (!aligned_to(dev_A, elem_size(ctx->p.dtype)) || !aligned_to(dev_A_par, 8)) return GECC_ERR_ALIGN;
+  if (blocked(ctx)) {
+    gecc_ctx v = view_a(ctx);
+    const int rc2 = gecc_encode_a(&v, dev_A, dev_A_par, stream);
+    ctx->ev_n = v.ev_n;
+    return rc2;
+  }
   ScanQueue q{ctx, (hipStream_t)stream};
   const TileScanJob tj = tile_job(ctx, GECC_MAT_A, dev_A, dev_A_par, nullptr, nullptr, 0, nullptr);
   hipError_t e = ctx->tile_op == GECC_MAT_A && tile_scan_ok(tj) ? q.run_tile(tj, GECC_K_ENCODE_A)
@@ -416,6 +486,12 @@ int gecc_encode_b(gecc_ctx* ctx, const void* dev_B, double* dev_B_par, void* str
   if (rc) return rc;
   if (!dev_B || !dev_B_par) return GECC_ERR_ARG;
   if (!aligned_to(dev_B, elem_size(ctx->p.dtype)) || !aligned_to(dev_B_par, 8)) return GECC_ERR_ALIGN;
+  if (blocked(ctx)) {
+    gecc_ctx v = view_b(ctx);
+    const int rc2 = gecc_encode_b(&v, dev_B, dev_B_par, stream);
+    ctx->ev_n = v.ev_n;
+    return rc2;
+  }
   ScanQueue q{ctx, (hipStream_t)stream};
   const TileScanJob tj = tile_job(ctx, GECC_MAT_B, dev_B, dev_B_par, nullptr, nullptr, 0, nullptr);
   hipError_t e = ctx->tile_op == GECC_MAT_B && tile_scan_ok(tj) ? q.run_tile(tj, GECC_K_ENCODE_B)
@@ -459,6 +535,58 @@ hipError_t product(gecc_ctx* ctx, const void* dev_A, const double* dev_A_par, co
   return timed_gemm(ctx, g, st);
 }
 
+// Blocked mode, S3: the parity blocks of every block of C-bar on the matrix units -- the parity
+// columns of all column blocks of B-bar, split into operand-type pieces, form one narrow operand
+// W_B (and the parity rows of all row blocks of A-bar one flat operand W_A); A W_B^T and W_A B are
+// two plain products of the same kernels -- then the data block with the fused partial sums.
+hipError_t blocked_multiply(gecc_ctx* ctx, const void* dev_A, const double* dev_A_par, const void* dev_B,
+                            const double* dev_B_par, float* dev_C, double* dev_C_par, const gecc_fault* dev_faults,
+                            int32_t n_faults, hipStream_t st) {
+  const gecc_params& p = ctx->p;
+  void* WA = ctx->ws + ctx->lay.w_a;
+  void* WB = ctx->ws + ctx->lay.w_b;
+  float* side_r = reinterpret_cast<float*>(ctx->ws + ctx->lay.side_r);
+  float* side_c = reinterpret_cast<float*>(ctx->ws + ctx->lay.side_c);
+  hipError_t e;
+  {
+    Timed t(ctx, GECC_K_PARITY_R, st);
+    if ((e = launch_split_parities(dev_B_par, WB, p.dtype, ctx->nbj, p.k, ctx->pieces, ctx->w_cols_b, st)) != hipSuccess) return e;
+    GemmArgs g = gemm_args(ctx, dev_A, WB, side_r);
+    g.trans_b = 1; g.m = ctx->w_cols_b; g.ldb = p.k; g.ldc = ctx->w_cols_b;
+    g.ntn = (g.m + ctx->tile_n - 1) / ctx->tile_n;
+    g.rowpart = nullptr; g.colpart = nullptr; g.faults = nullptr; g.n_faults = 0;
+    if ((e = t.done(launch_gemm(g, st))) != hipSuccess) return e;
+  }
+  {
+    Timed t(ctx, GECC_K_PARITY_C, st);
+    if ((e = launch_split_parities(dev_A_par, WA, p.dtype, ctx->nbi, p.k, ctx->pieces, ctx->w_cols_a, st)) != hipSuccess) return e;
+    GemmArgs g = gemm_args(ctx, WA, dev_B, side_c);
+    g.trans_a = 0; g.n = ctx->w_cols_a; g.lda = p.k; g.ldc = p.m;
+    g.ntm = (g.n + ctx->tile_m - 1) / ctx->tile_m;
+    g.rowpart = nullptr; g.colpart = nullptr; g.faults = nullptr; g.n_faults = 0;
+    if ((e = t.done(launch_gemm(g, st))) != hipSuccess) return e;
+  }
+  {
+    BlockedParityArgs b{};
+    b.nb = p.block_n; b.mb = p.block_m; b.k = p.k; b.nbi = ctx->nbi; b.nbj = ctx->nbj; b.pieces = ctx->pieces;
+    b.side_r = side_r; b.ld_r = ctx->w_cols_b; b.side_c = side_c; b.ld_c = p.m;
+    b.A_par = dev_A_par; b.B_par = dev_B_par; b.C_par = dev_C_par;
+    b.state = reinterpret_cast<DecodeState*>(ctx->ws + ctx->lay.state);
+    b.itemmax = reinterpret_cast<double*>(ctx->ws + ctx->lay.blockmax) + (size_t)((p.n + p.m + 63) / 64) * 4;
+    b.gate_word = reinterpret_cast<int32_t*>(ctx->ws + ctx->lay.gate);
+    Timed t(ctx, GECC_K_DECODE, st);
+    if ((e = t.done(launch_blocked_parities(b, st))) != hipSuccess) return e;
+  }
+  GemmArgs g = gemm_args(ctx, dev_A, dev_B, dev_C);
+  g.rowpart = reinterpret_cast<float*>(ctx->ws + ctx->lay.rowpart);
+  g.colpart = reinterpret_cast<float*>(ctx->ws + ctx->lay.colpart);
+  g.faults = dev_faults;
+  g.n_faults = n_faults;
+  g.pg_out = nullptr;      // P_g of every block and the resets are done above
+  g.state = nullptr;
+  return timed_gemm(ctx, g, st);
+}
+
 }  // namespace
 
 int gecc_multiply(gecc_ctx* ctx, const void* dev_A, const double* dev_A_par, const void* dev_B,
@@ -467,6 +595,7 @@ int gecc_multiply(gecc_ctx* ctx, const void* dev_A, const double* dev_A_par, con
   int rc = check_multiply_args(ctx, dev_A, dev_A_par, dev_B, dev_B_par, dev_C, dev_C_par, dev_faults, n_faults);
   if (rc) return rc;
   hipStream_t st = (hipStream_t)stream;
+  if (blocked(ctx)) return hip_rc(blocked_multiply(ctx, dev_A, dev_A_par, dev_B, dev_B_par, dev_C, dev_C_par, dev_faults, n_faults, st));
   ScanQueue q{ctx, st};
   hipError_t e;
   if ((e = parity_products(ctx, q, dev_A, dev_A_par, dev_B, dev_B_par, dev_C_par)) != hipSuccess) return hip_rc(e);
@@ -482,6 +611,7 @@ int verify_impl(gecc_ctx* ctx, const float* dev_C, const double* dev_C_par, gecc
   DecodeArgs d = decode_args(ctx, nullptr, nullptr, nullptr, nullptr, const_cast<float*>(dev_C),
                              const_cast<double*>(dev_C_par), dev_report);
   hipError_t e;
+  if (!fused && blocked(ctx)) return GECC_ERR_ARG;   // (blocked mode verifies from the product's own partial sums)
   if (!fused) {
     // (the fused path had its state reset by gecc_multiply)
     {
@@ -500,7 +630,8 @@ int verify_impl(gecc_ctx* ctx, const float* dev_C, const double* dev_C_par, gecc
   }
   {
     Timed t(ctx, GECC_K_THRESHOLD, st);
-    if ((e = t.done(launch_threshold(d, st))) != hipSuccess) return hip_rc(e);
+    e = blocked(ctx) ? launch_threshold_blocked(d, ctx->p.n, ctx->p.m, st) : launch_threshold(d, st);
+    if ((e = t.done(e)) != hipSuccess) return hip_rc(e);
   }
   if (!summary) return GECC_OK;
   Timed t(ctx, GECC_K_DECODE, st);
@@ -517,6 +648,33 @@ int correct_impl(gecc_ctx* ctx, void* dev_A, const double* dev_A_par, void* dev_
   {
     Timed t(ctx, GECC_K_DECODE, st);
     if ((e = t.done(launch_decode_c(d, with_summary, st))) != hipSuccess) return hip_rc(e);
+  }
+  if (blocked(ctx)) {
+    // the audits of all row blocks of A and all column blocks of B, gated on one word that the
+    // first block in need sets; then the repair in three launches (see launch_repair_blocked)
+    gecc_ctx va = view_a(ctx), vb = view_b(ctx);
+    const int32_t* gw = d.gate_word;
+    auto audit = [&](gecc_ctx& v, int op, const void* X, double* out, const ScanJob& old_job, int kind) -> hipError_t {
+      ScanQueue qv{&v, st};
+      TileScanJob tj = tile_job(&v, op, X, out, nullptr, nullptr, 0, gw);
+      tj.gate_stride = 0;
+      hipError_t ee;
+      if (tile_scan_ok(tj)) ee = qv.run_tile(tj, kind);
+      else { ScanJob j = old_job; j.s.gate_stride = 0; ee = qv.run(j); }
+      if (ee == hipSuccess) { qv.pending.gate_stride = 0; ee = qv.flush(); }
+      ctx->ev_n = v.ev_n;
+      return ee;
+    };
+    va.ev_n = ctx->ev_n;
+    if ((e = audit(va, GECC_MAT_A, dev_A, const_cast<double*>(d.audit_a),
+                   scan_a_over_n(&va, dev_A, nullptr, const_cast<double*>(d.audit_a), gw), GECC_K_AUDIT_A)) != hipSuccess)
+      return hip_rc(e);
+    vb.ev_n = ctx->ev_n;
+    if ((e = audit(vb, GECC_MAT_B, dev_B, const_cast<double*>(d.audit_b),
+                   scan_b_over_m(&vb, dev_B, nullptr, const_cast<double*>(d.audit_b), gw), GECC_K_AUDIT_B)) != hipSuccess)
+      return hip_rc(e);
+    Timed t(ctx, GECC_K_REPAIR, st);
+    return hip_rc(t.done(launch_repair_blocked(d, ctx->nbi, st)));
   }
   // operand audit: re-form the parities of A and B as the product read them
   // (the coldot of the two first, so that the rowdot carries its second stage)
@@ -553,6 +711,10 @@ int encode_and_multiply(gecc_ctx* ctx, void* dev_A, void* dev_B, float* dev_C, d
                         hipStream_t st) {
   int rc = check_multiply_args(ctx, dev_A, dev_A_par, dev_B, dev_B_par, dev_C, dev_C_par, dev_faults, n_faults);
   if (rc) return rc;
+  if (blocked(ctx)) {
+    if ((rc = gecc_encode_a(ctx, dev_A, dev_A_par, st)) || (rc = gecc_encode_b(ctx, dev_B, dev_B_par, st))) return rc;
+    return hip_rc(blocked_multiply(ctx, dev_A, dev_A_par, dev_B, dev_B_par, dev_C, dev_C_par, dev_faults, n_faults, st));
+  }
   const gecc_params& p = ctx->p;
   const int64_t rec = 2 * (int64_t)p.n + 2 * (int64_t)p.m + 4;
   const ScanJob ea = scan_a_over_n(ctx, dev_A, nullptr, dev_A_par, nullptr);
@@ -645,10 +807,10 @@ int gecc_protected_gemm_retry(gecc_ctx* ctx, void* dev_A, void* dev_B, float* de
     if ((rc = correct_impl(ctx, dev_A, dev_A_par, dev_B, dev_B_par, dev_C, dev_C_par, dev_report, 1,
                            (hipStream_t)stream)))
       return rc;
-    if ((rc = gecc_report_to_host(ctx, dev_report, host_report, ctx->p.batch, stream))) return rc;
+    if ((rc = gecc_report_to_host(ctx, dev_report, host_report, items_of(ctx), stream))) return rc;
     if (attempts) *attempts = a + 1;
     bool again = false;
-    for (int32_t b = 0; b < ctx->p.batch; ++b) again = again || host_report[b].status == GECC_UNCORRECTABLE;
+    for (int32_t b = 0; b < items_of(ctx); ++b) again = again || host_report[b].status == GECC_UNCORRECTABLE;
     if (!again) break;
   }
   return GECC_OK;
@@ -720,7 +882,7 @@ int gecc_protected_gemm_panels(gecc_ctx* ctx, void* dev_A, void* dev_B, float* d
                                int32_t n_faults, void* stream) {
   int rc = check_ws(ctx);
   if (rc) return rc;
-  if (panels < 1 || ctx->p.batch != 1 || !dev_report) return GECC_ERR_ARG;
+  if (panels < 1 || ctx->p.batch != 1 || !dev_report || blocked(ctx)) return GECC_ERR_ARG;
   const int P = gecc_panel_count(ctx, panels), step = panel_step(ctx, panels);
   if (P > 1 && !dev_C_partial) return GECC_ERR_ARG;
   if (dev_C_partial && !aligned_to(dev_C_partial, 4)) return GECC_ERR_ALIGN;
@@ -800,7 +962,8 @@ int gecc_syndromes_to_host(gecc_ctx* ctx, double* host_syndromes, void* stream) 
   if (rc) return rc;
   if (!host_syndromes) return GECC_ERR_ARG;
   hipStream_t st = (hipStream_t)stream;
-  const size_t bytes = (size_t)ctx->p.batch * (2 * (size_t)ctx->p.n + 2 * (size_t)ctx->p.m) * sizeof(double);
+  const size_t bytes = blocked(ctx) ? ((size_t)ctx->nbj * 2 * ctx->p.n + (size_t)ctx->nbi * 2 * ctx->p.m) * sizeof(double)
+                                    : (size_t)ctx->p.batch * (2 * (size_t)ctx->p.n + 2 * (size_t)ctx->p.m) * sizeof(double);
   hipError_t e = hipMemcpyAsync(host_syndromes, ctx->ws + ctx->lay.synd, bytes, hipMemcpyDeviceToHost, st);
   if (e != hipSuccess) return GECC_ERR_HIP;
   return hip_rc(hipStreamSynchronize(st));

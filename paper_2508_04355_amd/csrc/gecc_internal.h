@@ -46,6 +46,10 @@ struct Layout {            // byte offsets into the caller's workspace
   size_t scan_a;           // double scratch of the two-stage column reduction (A side)
   size_t scan_b;           // same, B side
   size_t scan_row;         // double scratch of the row part of the tile scan (the larger operand's)
+  // blocked mode only
+  size_t w_a, w_b;         // parity rows of all row blocks of A / parity columns of all column blocks of B, as operands of the product
+  size_t side_r, side_c;   // float: A x (parity columns), (parity rows) x B
+  size_t gate;             // int32: some block asked for the operand audit
   size_t total;
 };
 
@@ -57,6 +61,9 @@ struct gecc_ctx {
   int tile_m, tile_n;      // blocking of the product kernel = granularity of the partials
   int ntm, ntn;            // partial tiles along n and m
   int rp_ld, cp_ld;        // lines per slab of the row / column partials (n, m plus padding)
+  int nbi, nbj;            // blocked mode: blocks along n and m (0, 0: the whole product is one codeword)
+  int pieces;              // blocked mode: operand-type pieces one fp64 parity is split into (bf16: 3, fp32: 1)
+  int w_cols_a, w_cols_b;  // rows of W_A (2 * pieces * nbi) and of W_B, padded to a multiple of 8
   int tile_op;             // operand whose two reductions share one pass (GECC_MAT_A / GECC_MAT_B)
   int cu_hint;             // GECC_CU_COUNT (tests: plan the tile rounds as for that many CUs), else 0
   char* ws;                // device workspace (caller's)
@@ -264,9 +271,33 @@ struct DecodeArgs {
   const double* audit_a;
   const double* audit_b;
   double* blockmax;     // [batch][nblk][4] family maxima per workgroup of the first threshold pass
-  int nblk;
+  int nblk;             // (blocked mode: [items][4], nblk = 1, kept as bit patterns for atomicMax)
   gecc_report* report;
+  // Item addressing.  An item is a batch item (nbj = 0: I = J = b) or a block of the blocked code
+  // (I = b / nbj, J = b % nbj; p.n, p.m are then the block sizes and p.batch the number of blocks).
+  // A and A_par go by I, B and B_par by J, C by both; everything else by b.
+  int nbj;
+  int64_t ia_stride, jb_stride, ic_stride, jc_stride;   // elements
+  int32_t* gate_word;   // blocked mode: set to PH_AUDIT by the first block that needs the operand audit
 };
+// P_r, P_c, P_g of every block from the side products (blocked mode), plus the per-item resets
+struct BlockedParityArgs {
+  int nb, mb, k, nbi, nbj, pieces;
+  const float* side_r; int64_t ld_r;     // n x (2 pieces nbj)
+  const float* side_c; int64_t ld_c;     // (2 pieces nbi) x m
+  const double* A_par; const double* B_par;
+  double* C_par;
+  DecodeState* state;
+  double* itemmax;
+  int32_t* gate_word;
+};
+hipError_t launch_blocked_parities(const BlockedParityArgs& a, hipStream_t st);
+// fp64 parities [lines][2][k] -> operand-type rows [(line * 2 + t) * pieces + s][k] (k contiguous)
+hipError_t launch_split_parities(const double* par, void* W, int dtype, int lines, int k, int pieces, int rows_padded, hipStream_t st);
+// blocked mode: per-block syndromes and flags from the sub-tile partial sums
+hipError_t launch_threshold_blocked(const DecodeArgs& a, int n_full, int m_full, hipStream_t st);
+// blocked mode: the repair in three launches (own block of C-bar; operands; Section V on the rest)
+hipError_t launch_repair_blocked(const DecodeArgs& a, int nbi, hipStream_t st);
 hipError_t launch_reset_state(const DecodeArgs& a, hipStream_t st);
 // partial sums -> syndromes -> threshold flags (Section V step 1) and max |syndrome| per family
 hipError_t launch_threshold(const DecodeArgs& a, hipStream_t st);

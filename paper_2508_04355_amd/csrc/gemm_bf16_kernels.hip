@@ -718,7 +718,7 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
           else *reinterpret_cast<float2*>(rp) = make_float2(s, fmaf(16.f, u, w));
         }
       }
-    if (!SP && blockIdx.x == 0) form_pg(a, b, reinterpret_cast<double*>(smem));   // P_g, once per batch item
+    if (!SP && blockIdx.x == 0 && a.pg_out) form_pg(a, b, reinterpret_cast<double*>(smem));   // P_g, once per batch item
     }
   }
 }

@@ -276,7 +276,7 @@ __global__ __launch_bounds__(THREADS) void gemm_kernel(GemmArgs a) {
     cp[0] = cs;
     cp[1] = cw;
   }
-  if (epi && tm == 0 && tn == 0) form_pg(a, b, reinterpret_cast<double*>(smem));   // P_g, once per batch item
+  if (epi && tm == 0 && tn == 0 && a.pg_out) form_pg(a, b, reinterpret_cast<double*>(smem));   // P_g, once per batch item
 }
 
 // -------------------------------------------------------------------------------------------

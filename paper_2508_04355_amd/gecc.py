@@ -33,7 +33,7 @@ class Params(C.Structure):
                 ("stride_a", C.c_int64), ("stride_b", C.c_int64), ("stride_c", C.c_int64),
                 ("tau_r1", C.c_double), ("tau_r2", C.c_double), ("tau_q1", C.c_double),
                 ("tau_q2", C.c_double), ("tau_op", C.c_double), ("tau_rep", C.c_double),
-                ("tau_rel", C.c_double), ("weighted", C.c_int32), ("reserved", C.c_int32)]
+                ("tau_rel", C.c_double), ("weighted", C.c_int32), ("block_n", C.c_int32), ("block_m", C.c_int32), ("reserved", C.c_int32)]
 
 
 class Err(C.Structure):
@@ -56,7 +56,7 @@ class Fault(C.Structure):
 
 _lib = None
 _SYMBOLS = ["gecc_create", "gecc_destroy", "gecc_workspace_bytes", "gecc_set_workspace",
-            "gecc_a_par_len", "gecc_b_par_len", "gecc_c_par_len", "gecc_encode_a", "gecc_encode_b",
+            "gecc_a_par_len", "gecc_b_par_len", "gecc_c_par_len", "gecc_item_count", "gecc_encode_a", "gecc_encode_b",
             "gecc_multiply", "gecc_verify", "gecc_correct", "gecc_protected_gemm", "gecc_protected_gemm_retry",
             "gecc_protected_gemm_static", "gecc_panel_count", "gecc_protected_gemm_panels",
             "gecc_plain_gemm",
@@ -92,6 +92,8 @@ def lib():
     L.gecc_protected_gemm_static.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp]
     L.gecc_panel_count.argtypes = [vp, i32]
     L.gecc_panel_count.restype = i32
+    L.gecc_item_count.argtypes = [vp]
+    L.gecc_item_count.restype = i32
     L.gecc_protected_gemm_panels.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, i32, vp]
     L.gecc_protected_gemm_retry.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, C.POINTER(Report), i32, vp, i32,
                                             C.POINTER(i32), vp]
@@ -104,7 +106,7 @@ def lib():
     L.gecc_strerror.restype = C.c_char_p
     for f in _SYMBOLS:
         if f not in ("gecc_destroy", "gecc_workspace_bytes", "gecc_a_par_len", "gecc_b_par_len",
-                     "gecc_c_par_len", "gecc_strerror", "gecc_panel_count"):
+                     "gecc_c_par_len", "gecc_strerror", "gecc_panel_count", "gecc_item_count"):
             getattr(L, f).restype = C.c_int
     _lib = L
     return L
@@ -157,7 +159,7 @@ class Context:
 
     def __init__(self, n, k, m, dtype, tau: Thresholds, batch=1, trans_a=0, trans_b=0, refine=1,
                  lda=None, ldb=None, ldc=None, stride_a=None, stride_b=None, stride_c=None,
-                 device="cuda:0"):
+                 device="cuda:0", block=(0, 0)):
         self.n, self.k, self.m, self.batch, self.dtype = n, k, m, batch, dtype
         self.trans_a, self.trans_b = trans_a, trans_b
         lda = lda if lda is not None else (n if trans_a else k)
@@ -170,10 +172,12 @@ class Context:
                              stride_b=stride_b if stride_b is not None else rows_b * ldb,
                              stride_c=stride_c if stride_c is not None else n * ldc,
                              tau_r1=tau.r1, tau_r2=tau.r2, tau_q1=tau.q1, tau_q2=tau.q2, tau_op=tau.op,
-                             tau_rep=tau.rep, tau_rel=tau.rel, weighted=1 if tau.weighted else 0, reserved=0)
+                             tau_rep=tau.rep, tau_rel=tau.rel, weighted=1 if tau.weighted else 0,
+                             block_n=block[0], block_m=block[1], reserved=0)
         self._h = C.c_void_p()
         _check(lib().gecc_create(C.byref(self._h), C.byref(self.params)))
         self.device = torch.device(device)
+        self.items = lib().gecc_item_count(self._h)
         nbytes = lib().gecc_workspace_bytes(self._h)
         self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.device)
         off = (-self.workspace.data_ptr()) % 256
@@ -194,7 +198,7 @@ class Context:
                 torch.empty(self.batch * L.gecc_c_par_len(self._h), **f64))
 
     def alloc_report(self):
-        return torch.zeros(self.batch * C.sizeof(Report), dtype=torch.uint8, device=self.device)
+        return torch.zeros(self.items * C.sizeof(Report), dtype=torch.uint8, device=self.device)
 
     def alloc_c(self):
         return torch.empty((self.batch, self.n, self.params.ldc), dtype=torch.float32, device=self.device)
@@ -245,7 +249,7 @@ class Context:
     def protected_gemm_retry(self, A, B, Cmat, A_par, B_par, C_par, report, max_retries=1, faults=None, n_faults=0):
         """protected_gemm with recomputation on UNCORRECTABLE (waits for the stream after every
         attempt).  Returns (host reports of the last attempt, products computed)."""
-        host = (Report * self.batch)()
+        host = (Report * self.items)()
         attempts = C.c_int32(0)
         _check(lib().gecc_protected_gemm_retry(self._h, _ptr(A), _ptr(B), _ptr(Cmat), _ptr(A_par), _ptr(B_par),
                                                _ptr(C_par), _ptr(report), host, max_retries,
@@ -257,8 +261,8 @@ class Context:
         _check(lib().gecc_plain_gemm(self._h, _ptr(A), _ptr(B), _ptr(Cmat), _stream()))
 
     def report_to_host(self, report) -> List[Report]:
-        host = (Report * self.batch)()
-        _check(lib().gecc_report_to_host(self._h, _ptr(report), host, self.batch, _stream()))
+        host = (Report * self.items)()
+        _check(lib().gecc_report_to_host(self._h, _ptr(report), host, self.items, _stream()))
         return list(host)
 
     def timing_enable(self, max_records: int, kinds=(K_PRODUCT,)):
@@ -277,9 +281,11 @@ class Context:
         return [(int(kinds[i]), float(ms[i])) for i in range(cnt.value)]
 
     def syndromes_to_host(self):
-        """(batch, 2n+2m) float64 numpy array: r1, r2, q1, q2 of the last verify."""
+        """(items, 2n+2m) float64 numpy array: r1, r2, q1, q2 of the last verify (blocked mode: n, m
+        are the block sizes)."""
         import numpy as np
-        out = np.empty((self.batch, 2 * self.n + 2 * self.m), dtype=np.float64)
+        bn, bm = self.params.block_n or self.n, self.params.block_m or self.m
+        out = np.empty((self.items, 2 * bn + 2 * bm), dtype=np.float64)
         _check(lib().gecc_syndromes_to_host(self._h, C.c_void_p(out.ctypes.data), _stream()))
         return out
 

@@ -152,3 +152,40 @@ def compare(g: GpuResult, o: List[oc.Result], tol_c: float, tol_mag: float = Non
         if res.status == oc.CORRECTED:
             assert np.max(np.abs(g.A[b] - res.A)) <= 1e-6 * max(1.0, np.max(np.abs(res.A))), tag
             assert np.max(np.abs(g.B[b] - res.B)) <= 1e-6 * max(1.0, np.max(np.abs(res.B))), tag
+
+
+def run_gpu_blocked(A_enc, B_enc, A_mul, B_mul, c_faults, tau, dtype, block, trans_a=0, trans_b=0, staged=True):
+    """Blocked grid code (one product, batch 1): block = (block_n, block_m).  c_faults: [(i, j, e)] in
+    coordinates of the whole C.  Returns (reports per block in item order, C, A, B, C_par per item, synd)."""
+    A_enc, B_enc, A_mul, B_mul = [np.asarray(x, dtype=np.float32)[None] for x in (A_enc, B_enc, A_mul, B_mul)]
+    _, n, k = A_enc.shape
+    m = B_enc.shape[2]
+    ctx = gecc.Context(n, k, m, gecc.BF16 if dtype == "bf16" else gecc.F32,
+                       gecc.Thresholds(tau.r1, tau.r2, tau.q1, tau.q2, tau.op, tau.rep, tau.rel), trans_a=trans_a,
+                       trans_b=trans_b, block=block)
+    dA, dB = to_dev(A_enc, dtype, trans_a), to_dev(B_enc, dtype, trans_b)
+    A_par, B_par, C_par = ctx.alloc_parities()
+    rep = ctx.alloc_report()
+    Cd = ctx.alloc_c()
+    Cd.fill_(float("nan"))
+    fl, nf = gecc.make_faults([(0, i, j, e) for (i, j, e) in c_faults], DEV)
+    if staged:
+        ctx.encode_a(dA, A_par)
+        ctx.encode_b(dB, B_par)
+        dA.copy_(to_dev(A_mul, dtype, trans_a))
+        dB.copy_(to_dev(B_mul, dtype, trans_b))
+        ctx.multiply(dA, A_par, dB, B_par, Cd, C_par, fl, nf)
+        ctx.verify(Cd, C_par, rep, fused=True)
+        synd = ctx.syndromes_to_host()
+        ctx.correct(dA, A_par, dB, B_par, Cd, C_par, rep)
+        reports = ctx.report_to_host(rep)
+    else:
+        assert np.array_equal(A_enc, A_mul) and np.array_equal(B_enc, B_mul)
+        reports, attempts = ctx.protected_gemm_retry(dA, dB, Cd, A_par, B_par, C_par, rep, 0, fl, nf)
+        synd = ctx.syndromes_to_host()
+    torch.cuda.synchronize()
+    items = ctx.items
+    return dict(reports=reports, C=Cd.cpu().numpy().astype(np.float64)[0, :, :m],
+                A=from_dev(dA, trans_a, n if trans_a else k)[0], B=from_dev(dB, trans_b, k if trans_b else m)[0],
+                A_par=A_par.cpu().numpy(), B_par=B_par.cpu().numpy(),
+                C_par=C_par.cpu().numpy().reshape(items, -1), synd=synd)

@@ -412,6 +412,105 @@ def test_protected_product_panel_by_panel(dtype, shape, trans, panels):
         assert g1.reports[0].status == gecc.UNCORRECTABLE
 
 
+# ---- blocked grid code: Section III per block of C ----------------------------------------------------
+def _blocked_compare(g, res, Cref, n, m, nb, mb, tol_c=1e-5, tol_mag=None):
+    nbj = m // mb
+    scale = np.abs(Cref).max()
+    for (I, J), o in res.items():
+        r = g["reports"][I * nbj + J]
+        assert r.status == o.status, ((I, J), r.status, o.status, r.errors(), o.errors)
+        if o.status == oc.UNCORRECTABLE:
+            continue
+        assert r.n_total == len(o.errors) and [e[:3] for e in r.errors()] == [e[:3] for e in o.errors[:8]], ((I, J), r.errors(), o.errors)
+        for x, y in zip(r.errors(), o.errors):
+            assert abs(x[3] - y[3]) <= (tol_mag if tol_mag is not None else 10 * tol_c * scale) + 1e-6 * abs(y[3]), ((I, J), x, y)
+        blk = g["C"][I * nb:(I + 1) * nb, J * mb:(J + 1) * mb]
+        assert not np.isnan(blk).any()
+        assert np.abs(blk - o.C).max() / scale <= tol_c, (I, J)
+        # the parity blocks of the block: formed on the matrix units in fp32 (relative to the largest of their kind)
+        ref = np.concatenate([o.Cbar[:nb, mb], o.Cbar[:nb, mb + 1], o.Cbar[nb, :mb], o.Cbar[nb + 1, :mb]])
+        got = g["C_par"][I * nbj + J][:2 * nb + 2 * mb]
+        for a0, a1 in ((0, nb), (nb, 2 * nb), (2 * nb, 2 * nb + mb), (2 * nb + mb, 2 * nb + 2 * mb)):
+            assert np.abs(got[a0:a1] - ref[a0:a1]).max() <= 2e-5 * max(np.abs(ref[a0:a1]).max(), 1e-30), ((I, J), a0)
+        pg = g["C_par"][I * nbj + J][2 * nb + 2 * mb:]
+        assert np.allclose(pg, o.Cbar[nb:, mb:].ravel(), rtol=1e-11, atol=1e-12 * np.abs(pg).max())
+
+
+@pytest.mark.parametrize("pattern", ["clean", "two errors in every block", "A", "B", "A+B same l, C elsewhere", "three in one block"])
+@pytest.mark.parametrize("dtype,shape,block,trans", [("bf16", (512, 256, 768), (256, 256), (0, 0)), ("bf16", (512, 256, 768), (256, 384), (0, 1)),
+                                                     ("bf16", (512, 192, 512), (128, 256), (1, 0)), ("f32", (256, 200, 384), (128, 128), (0, 0)),
+                                                     ("bf16", (768, 256, 512), (256, 256), (1, 1))])
+def test_blocked_grid_code(pattern, dtype, shape, block, trans):
+    """gecc_params.block_n / block_m: every block of C is a codeword of Section III of its own.  Status
+    and positions per block bit for bit with the oracle's block-by-block evaluation, C to 1e-5, the
+    operands restored; 'two errors in every block' is far beyond the whole-matrix code."""
+    n, k, m = shape
+    nb, mb = block
+    rng = inputs.rng_for(96, n + k + len(pattern))
+    F = inputs.Fault
+    nbi, nbj = n // nb, m // mb
+    if pattern == "clean":
+        faults = []
+    elif pattern == "two errors in every block":
+        faults = []
+        for I in range(nbi):
+            for J in range(nbj):
+                faults += [F(MAT_C, I * nb + 3 + J, J * mb + 5 + I, 20.0 + I + J), F(MAT_C, I * nb + nb - 1, J * mb + 100, -35.0 - J)]
+    elif pattern == "A":
+        faults = [F(MAT_A, nb + 7, k - 2, 4.0)]
+    elif pattern == "B":
+        faults = [F(MAT_B, 3, mb + 9, -5.0)]
+    elif pattern == "A+B same l, C elsewhere":
+        faults = [F(MAT_A, 5, 17, 3.0), F(MAT_B, 17, m - 1, 6.0), F(MAT_C, n - 1, 0, 44.0)]
+    else:
+        faults = [F(MAT_C, 1, 1, 10.0), F(MAT_C, 20, 30, 20.0), F(MAT_C, 40, 60, 30.0), F(MAT_C, n - 1, m - 1, 9.0)]
+    A, B, A2, B2, cf, eff = _trial(rng, n, k, m, dtype, ("normal", 1.0), ("normal", 1.0), faults)
+    tau = gecc.noise_thresholds(nb, k, mb, 1.0, 1.0)
+    tau_o = oc.Thresholds(tau.r1, tau.r2, tau.q1, tau.q2, tau.op, tau.rep, tau.rel)
+    res, Cref, Ao, Bo = oc.protected_gemm_blocked(A, B, A2, B2, cf, tau_o, nb, mb)
+    g = H.run_gpu_blocked(A, B, A2, B2, cf, tau, dtype, block, trans[0], trans[1])
+    _blocked_compare(g, res, Cref, n, m, nb, mb, tol_mag=4 * max(tau.r1, tau.q1))
+    st = [r.status for r in g["reports"]]
+    if pattern == "clean":
+        assert st == [gecc.CLEAN] * (nbi * nbj)
+        mx = np.array([list(r.max_abs_synd) for r in g["reports"]])
+        assert (mx[:, 0] <= tau.r1 / 2).all() and (mx[:, 1] <= tau.r2 / 2).all() and (mx[:, 2] <= tau.q1 / 2).all() and (mx[:, 3] <= tau.q2 / 2).all()
+    elif pattern == "three in one block":
+        assert st[0] == gecc.UNCORRECTABLE and st[-1] == gecc.CORRECTED and st.count(gecc.CLEAN) == nbi * nbj - 2
+    else:
+        assert gecc.UNCORRECTABLE not in st
+        assert np.array_equal(g["A"], A.astype(np.float64)) and np.array_equal(g["B"], B.astype(np.float64))
+        assert np.abs(g["C"] - A.astype(np.float64) @ B.astype(np.float64)).max() / np.abs(Cref).max() <= 1e-5
+    if pattern == "two errors in every block":
+        assert st == [gecc.CORRECTED] * (nbi * nbj)
+        # the one-call chain gives the same decisions
+        g1 = H.run_gpu_blocked(A, B, A, B, cf, tau, dtype, block, trans[0], trans[1], staged=False)
+        _blocked_compare(g1, res, Cref, n, m, nb, mb, tol_mag=4 * max(tau.r1, tau.q1))
+
+
+def test_blocked_grid_code_at_the_forward_shape():
+    """cfg4-fwd in 1024 x 1024 blocks (16 x 14 codewords): the parity blocks of all of them come from two
+    narrow products on the 256 x 256-tile kernel.  Two errors in each of five blocks, a wrong symbol of A
+    (seen by the 14 blocks of its row block) and one of B; every block against the oracle."""
+    w = configs.CFG4_FWD
+    n, k, m, nb, mb = w.n, w.k, w.m, 1024, 1024
+    rng = inputs.rng_for(4, 7)
+    F = inputs.Fault
+    faults = [F(MAT_A, 5 * nb + 17, 4000, 9.0), F(MAT_B, 123, 3 * mb + 1000, -3.0)]
+    for (I, J) in [(0, 0), (3, 13), (15, 0), (15, 13), (8, 7)]:
+        faults += [F(MAT_C, I * nb + 1, J * mb + 2, 40.0 + I), F(MAT_C, I * nb + 1000, J * mb + 1023, -25.0 - J)]
+    A, B, A2, B2, cf, eff = _trial(rng, n, k, m, w.dtype, w.law_a, w.law_b, faults)
+    tau = gecc.noise_thresholds(nb, k, mb, w.sigma_a, w.sigma_b)
+    assert tau.r2 < w.tau.r2 / 40 and tau.q2 < w.tau.q2 / 60        # weights bounded by the block: (1024 / 14336)^1.5, (1024 / 16384)^1.5
+    tau_o = oc.Thresholds(tau.r1, tau.r2, tau.q1, tau.q2, tau.op, tau.rep, tau.rel)
+    res, Cref, Ao, Bo = oc.protected_gemm_blocked(A, B, A2, B2, cf, tau_o, nb, mb)
+    g = H.run_gpu_blocked(A, B, A2, B2, cf, tau, w.dtype, (nb, mb))
+    _blocked_compare(g, res, Cref, n, m, nb, mb, tol_mag=4 * max(tau.r1, tau.q1))
+    st = [r.status for r in g["reports"]]
+    assert gecc.UNCORRECTABLE not in st and st.count(gecc.CLEAN) == 16 * 14 - 5 - (14 + 16 - 1)
+    assert np.array_equal(g["A"], A.astype(np.float64)) and np.array_equal(g["B"], B.astype(np.float64))
+
+
 # ---- single-checksum mode (Section VI's comparison scheme: plain parities only) -----------------------
 @pytest.mark.parametrize("pattern", ["none", "C", "C+C same row", "C+C same column", "C+C elsewhere", "A", "B", "A+C", "B+C",
                                      "one row, 40 columns", "one column, 25 rows", "two rows", "C nan"])

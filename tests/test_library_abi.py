@@ -34,13 +34,13 @@ def test_struct_layouts_match_the_header(built):
     assert C.sizeof(built.Err) == 24
     assert C.sizeof(built.Report) == 16 + 8 * 24 + 32 + 8
     assert C.sizeof(built.Fault) == 16
-    assert C.sizeof(built.Params) == 8 * 4 + 6 * 8 + 7 * 8 + 2 * 4
+    assert C.sizeof(built.Params) == 8 * 4 + 6 * 8 + 7 * 8 + 4 * 4
 
 
 def _params(built, **kw):
     d = dict(n=64, k=32, m=48, batch=1, dtype=built.F32, trans_a=0, trans_b=0, refine=1, lda=32, ldb=48,
              ldc=48, stride_a=64 * 32, stride_b=32 * 48, stride_c=64 * 48, tau_r1=1e-3, tau_r2=1e-3,
-             tau_q1=1e-3, tau_q2=1e-3, tau_op=0.0, tau_rep=1e-6, tau_rel=1e-6, weighted=1, reserved=0)
+             tau_q1=1e-3, tau_q2=1e-3, tau_op=0.0, tau_rep=1e-6, tau_rel=1e-6, weighted=1, block_n=0, block_m=0, reserved=0)
     d.update(kw)
     return built.Params(**d)
 
@@ -60,7 +60,8 @@ def test_create_validates_arguments(built):
     L.gecc_destroy(h)
     for bad in (dict(n=0), dict(k=-1), dict(batch=0), dict(dtype=7), dict(trans_a=2), dict(lda=31),
                 dict(ldb=47), dict(ldc=40), dict(tau_q1=-1.0), dict(tau_r2=float("nan")), dict(tau_rep=-1.0), dict(tau_rel=-1.0),
-                dict(batch=2, stride_c=10), dict(weighted=2), dict(weighted=-1)):
+                dict(batch=2, stride_c=10), dict(weighted=2), dict(weighted=-1), dict(block_n=128), dict(block_n=64, block_m=64),
+                dict(n=256, m=256, lda=32, ldb=256, ldc=256, block_n=128, block_m=96), dict(n=256, m=256, ldb=256, ldc=256, block_n=128, block_m=128, weighted=0)):
         assert L.gecc_create(C.byref(h), C.byref(_params(built, **bad))) == -1, bad
     assert L.gecc_create(None, C.byref(_params(built))) == -1
     for code in (0, -1, -2, -3, -4, -99):

@@ -19,7 +19,7 @@ pytestmark = pytest.mark.gpu
 def _params(n, k, m, dtype, tau, batch=1):
     return gecc.Params(n=n, k=k, m=m, batch=batch, dtype=dtype, trans_a=0, trans_b=0, refine=1, lda=k, ldb=m,
                        ldc=m, stride_a=n * k, stride_b=k * m, stride_c=n * m, tau_r1=tau.r1, tau_r2=tau.r2,
-                       tau_q1=tau.q1, tau_q2=tau.q2, tau_op=tau.op, tau_rep=tau.rep, tau_rel=tau.rel, weighted=1, reserved=0)
+                       tau_q1=tau.q1, tau_q2=tau.q2, tau_op=tau.op, tau_rep=tau.rep, tau_rel=tau.rel, weighted=1, block_n=0, block_m=0, reserved=0)
 
 
 def _both_ways(n, k, m, dtype, seed):
