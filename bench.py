@@ -34,6 +34,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="cfg4-fwd")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--block", type=int, nargs=2, default=None, metavar=("BLOCK_N", "BLOCK_M"),
+                    help="also time the blocked grid code with these block sizes (multiples of 128 dividing n, m)")
     ap.add_argument("--panels", type=int, default=0,
                     help="also time the per-k-panel path (gecc_protected_gemm_panels) with this many panels")
     ap.add_argument("--traffic-ref", action="store_true",
@@ -137,6 +139,36 @@ def main():
                      "overhead_pct_vs_plain": round((ms_p / ms_plain - 1.0) * 100.0, 2),
                      "all_clean": all(r.status == gecc.CLEAN for r in rp)}
         del Cp
+
+    # ---- blocked grid code (optional): Section III per block of C, thresholds of one block ---------
+    block_out = None
+    if args.block and batch == 1:
+        nbk, mbk = args.block
+        tb = gecc.noise_thresholds(nbk, k, mbk, w.sigma_a, w.sigma_b)
+        ctxb = gecc.Context(n, k, m, gecc.BF16 if w.dtype == "bf16" else gecc.F32, tb, trans_a=w.trans_a,
+                            trans_b=w.trans_b, block=(nbk, mbk))
+        A_pb, B_pb, C_pb = ctxb.alloc_parities()
+        rep_b = ctxb.alloc_report()
+
+        def bstep():
+            ctxb.protected_gemm(dA, dB, Cd, A_pb, B_pb, C_pb, rep_b)
+
+        for _ in range(args.warmup):
+            bstep()
+        torch.cuda.synchronize()
+        t0b = time.perf_counter()
+        for _ in range(args.steps):
+            bstep()
+        torch.cuda.synchronize()
+        ms_b = (time.perf_counter() - t0b) * 1e3 / args.steps
+        rb = ctxb.report_to_host(rep_b)
+        mxb = np.array([list(r.max_abs_synd) for r in rb]).max(axis=0)
+        block_out = {"block": [nbk, mbk], "codewords": ctxb.items, "thresholds": [tb.r1, tb.r2, tb.q1, tb.q2],
+                     "max_clean_syndromes": [float(x) for x in mxb],
+                     "ms_per_step": round(ms_b, 4), "tflops": round(w.flops / (ms_b * 1e-3) / 1e12, 3),
+                     "overhead_pct_vs_plain": round((ms_b / ms_plain - 1.0) * 100.0, 2),
+                     "all_clean": all(r.status == gecc.CLEAN for r in rb)}
+        del ctxb, A_pb, B_pb, C_pb
 
     # ---- HBM rooflines of the memory-bound kernels: the same steps once more with an event pair
     # around every launch (not part of `value`: the records cost stream time), then the stand-alone
@@ -272,6 +304,7 @@ def main():
                                  "scenario_ms": scen_ms1,
                                  "scenario_overhead_pct": {kk: round((vv / ms_plain - 1.0) * 100.0, 1) for kk, vv in scen_ms1.items()}},
         "per_k_panel_verification": panel_out,
+        "blocked_grid_code": block_out,
         "hbm_rooflines": {"peak_GBs": HBM_PEAK_GBS,
                           "steady_loop": hbm_steady,       # as in the timed steps: operands may sit in the memory-side cache
                           "operands_rotated": hbm_rotated},  # three operand sets in turn: every first read comes from HBM

@@ -889,6 +889,8 @@ __global__ __launch_bounds__(DC_THREADS) void final_decode_kernel(DecodeArgs a) 
 // is a whole number of them), one thread per line and block along it.  a.p.n, a.p.m: block sizes.
 __global__ __launch_bounds__(256) void threshold_blocked_kernel(DecodeArgs a, int n_full, int m_full) {
   const int nb = a.p.n, mb = a.p.m, nbj = a.nbj, nbi = n_full / nb;
+  // (n_full, m_full are multiples of 128: the 64 lines of a wavefront lie in one block, and every
+  // wavefront of the grid is full)
   const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const int64_t total_r = (int64_t)n_full * nbj, total = total_r + (int64_t)m_full * nbi;
   if (idx >= total) return;
@@ -928,10 +930,19 @@ __global__ __launch_bounds__(256) void threshold_blocked_kernel(DecodeArgs a, in
     if (x < GECC_MAX_ERR) (is_row ? st->rows : st->cols)[x] = loc;
   }
   if (!finite2(v1, v2)) atomicOr(&st->nonfinite, 1);
-  // family maxima of the block: non-negative doubles order like their bit patterns (a NaN above all)
-  unsigned long long* mx = reinterpret_cast<unsigned long long*>(a.blockmax) + (int64_t)b * 4 + (is_row ? 0 : 2);
-  atomicMax(mx, (unsigned long long)__double_as_longlong(fabs(v1)));
-  atomicMax(mx + 1, (unsigned long long)__double_as_longlong(fabs(v2)));
+  // family maxima of the block: first over the wavefront (one block, see above), then one atomic per
+  // wavefront -- non-negative doubles order like their bit patterns, a NaN above all
+  double m1 = fabs(v1), m2 = fabs(v2);
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    m1 = max_nan(m1, __shfl_xor(m1, off, 64));
+    m2 = max_nan(m2, __shfl_xor(m2, off, 64));
+  }
+  if ((threadIdx.x & 63) == 0) {
+    unsigned long long* mx = reinterpret_cast<unsigned long long*>(a.blockmax) + (int64_t)b * 4 + (is_row ? 0 : 2);
+    atomicMax(mx, (unsigned long long)__double_as_longlong(m1));
+    atomicMax(mx + 1, (unsigned long long)__double_as_longlong(m2));
+  }
 }
 
 // Blocked mode: the parity blocks of every block of C-bar from the two side products (A times the
@@ -941,12 +952,12 @@ __global__ __launch_bounds__(256) void blocked_parities_kernel(BlockedParityArgs
   const int b = blockIdx.x, I = b / a.nbj, J = b % a.nbj;
   const int nb = a.nb, mb = a.mb, S = a.pieces;
   double* cpar = a.C_par + (int64_t)b * (2 * nb + 2 * mb + 4);
-  for (int o = threadIdx.x; o < 2 * nb; o += blockDim.x) {
-    const int t = o / nb, il = o % nb;
-    const float* p = a.side_r + (int64_t)(I * nb + il) * a.ld_r + (J * 2 + t) * S;
-    double v = 0.0;
-    for (int s = 0; s < S; ++s) v += (double)p[s];
-    cpar[o] = v;
+  for (int il = threadIdx.x; il < nb; il += blockDim.x) {      // 2 S consecutive floats of a row of the side product
+    const float* p = a.side_r + (int64_t)(I * nb + il) * a.ld_r + J * 2 * S;
+    double v0 = 0.0, v1 = 0.0;
+    for (int s = 0; s < S; ++s) { v0 += (double)p[s]; v1 += (double)p[S + s]; }
+    cpar[il] = v0;
+    cpar[nb + il] = v1;
   }
   for (int o = threadIdx.x; o < 2 * mb; o += blockDim.x) {
     const int t = o / mb, jl = o % mb;
