@@ -264,8 +264,8 @@ int gecc_protected_gemm_static(gecc_ctx* ctx, void* dev_A, void* dev_B, float* d
                                double* dev_A_par, double* dev_B_par, double* dev_C_par,
                                gecc_report* dev_report, void* stream);
 
-/* The recomputation Section V asks for when a pattern is beyond the code ("needs to be
-   recalculated"): encode_a, encode_b once, then multiply, verify(fused), correct and a read-back
+/* The recomputation Section V step 1 prescribes for a pattern beyond the code:
+   encode_a, encode_b once, then multiply, verify(fused), correct and a read-back
    of the reports -- this call waits for the stream after every attempt -- until no batch item
    reports GECC_UNCORRECTABLE or max_retries (>= 0) recomputations were made.  The whole batch is
    recomputed from the operands as the last attempt left them (an attempt patches located

@@ -1,5 +1,4 @@
-"""Builds libgecc.so (HIP, gfx950 only) in-tree with hipcc, and the two stand-alone hardware probes under
-csrc/probes/ (small executables, not part of the library: what the product kernel's design rests on).
+"""Builds libgecc.so (HIP, gfx950 only) in-tree with hipcc.
 Usage: python -m paper_2508_04355_amd.build"""
 import os
 import subprocess
@@ -10,7 +9,6 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libgecc.so")
-PROBES = ["mfma_clock", "mfma_issue_slots"]
 SOURCES = ["scan_kernels.hip", "gemm_kernels.hip", "gemm_bf16_kernels.hip", "decode_kernels.hip",
            "gecc_api.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I" + os.path.join(ROOT, "include"),
@@ -41,20 +39,8 @@ def build(verbose=True):
             print(err, file=sys.stderr)
         return obj
 
-    def compile_probe(name):
-        exe = os.path.join(CSRC, "probes", name)
-        cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
-               "-packed-fp32-ops", os.path.join(CSRC, "probes", name + ".hip"), "-o", exe]
-        r = subprocess.run(cmd, capture_output=True, text=True)
-        if r.returncode != 0:
-            raise RuntimeError("hipcc failed on probe %s:\n%s" % (name, r.stderr))
-        return exe
-
     with ThreadPoolExecutor(max_workers=4) as ex:
-        probes = [ex.submit(compile_probe, p) for p in PROBES]
         objs = list(ex.map(compile_one, SOURCES))
-        for f in probes:
-            f.result()
     r = subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", OUT] + objs,
                        capture_output=True, text=True)
     if r.returncode != 0:

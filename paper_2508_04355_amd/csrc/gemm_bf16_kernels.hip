@@ -33,6 +33,7 @@
 // Every tile walks k cyclically from its own start (a few k-tiles apart for neighbouring
 // tiles), so that the compute units sharing an operand panel do not ask L2 for the same line
 // in the same cycle: the first one misses, the others hit.
+#include <mutex>
 #include <type_traits>
 #include "gecc_internal.h"
 
@@ -723,20 +724,42 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_256(GemmArgs a) {
   }
 }
 
+constexpr int MAX_DEVICES = 64;
+// compute units of a device, asked once per device
+int device_cus(int dev) {
+  static std::mutex mu;
+  static int cus_of[MAX_DEVICES] = {};
+  std::lock_guard<std::mutex> lock(mu);
+  if (cus_of[dev] == 0) {
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
+    cus_of[dev] = cus;
+  }
+  return cus_of[dev];
+}
+
 template <bool KCA, bool KCB, bool EPI>
 hipError_t launch_one(const GemmArgs& a0, hipStream_t st) {
-  static bool configured = false;   // per instantiation
   constexpr int lds_bytes = EPI && EPI_SMEM_BYTES > SMEM_BYTES ? EPI_SMEM_BYTES : SMEM_BYTES;
   auto kern = gemm_bf16_256<KCA, KCB, EPI, false>;
   auto kern_split = gemm_bf16_256<KCA, KCB, EPI, true>;
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern_split),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-    if (e != hipSuccess) return e;
-    configured = true;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+  {
+    // the LDS limit of the two kernels of this instantiation and the CU count, once per device,
+    // whichever host thread comes first
+    static std::mutex mu;
+    static bool configured[MAX_DEVICES] = {};
+    std::lock_guard<std::mutex> lock(mu);
+    if (!configured[dev]) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+      if (e != hipSuccess) return e;
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern_split),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+      if (e != hipSuccess) return e;
+      configured[dev] = true;
+    }
   }
   GemmArgs a = a0;
   const int ntm = (a.n + BM - 1) / BM, ntn = (a.m + BN - 1) / BN, ntiles = ntm * ntn;
@@ -744,15 +767,7 @@ hipError_t launch_one(const GemmArgs& a0, hipStream_t st) {
   // tiles go to a launch of their own in which two workgroups share a tile, one per half of k,
   // so that the round takes half as long (cfg4-wgrad: 896 tiles on 256 CUs -> the time of 3.5
   // rounds instead of 4).  The halves add into C and the partial sums, zeroed beforehand.
-  static int n_cu = 0;
-  if (n_cu == 0) {
-    int dev = 0, cus = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
-      cus = 256;
-    n_cu = cus;
-  }
-  const int cus = a.cu_hint > 0 ? a.cu_hint : n_cu;
+  const int cus = a.cu_hint > 0 ? a.cu_hint : device_cus(dev);
   // rounds as blocks of tiles (see tile_of): 16 x 16 or 32 x 8, whichever fits
   // exactly -- where the panels a round of the default order touches (64 tile rows + 4 tile
   // columns) would not fit the 256 MiB memory-side cache; where they do, the default order is as
