@@ -22,9 +22,9 @@ PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}     # MI355X dense MFMA peaks
 HBM_PEAK_GBS = 8000.0
 
 # Memory traffic of the product kernel per launch (bytes), from rocprofv3 --pmc FETCH_SIZE and
-# WRITE_SIZE runs, each scaled by what the same counter reads for a 1 GiB copy (factors 2.000 and
-# 1.000); profiles/bench_cfg4-fwd_hbm_traffic.txt.  Workloads not listed: not measured.
-TRAFFIC_BYTES = {"cfg4-fwd": 3.078e9 + 1.004e9}
+# WRITE_SIZE runs, each scaled by what the same counter reads for a 1 GiB copy (the factors are in
+# the files); profiles/bench_<workload>_hbm_traffic.txt.  Workloads not listed: not measured.
+TRAFFIC_BYTES = {"cfg4-fwd": 3.027e9 + 1.003e9, "cfg4-dgrad": 6.482e9 + 6.417e8, "cfg4-wgrad": 8.760e9 + 5.606e8}
 
 
 def main():

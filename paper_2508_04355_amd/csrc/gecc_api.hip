@@ -239,6 +239,15 @@ TileScanJob tile_job(gecc_ctx* c, int op, const void* X, double* enc_out, const 
   return t;
 }
 
+// Whether the tile scan serves this operand: its rows have to allow it, and the operand has to be
+// large enough for one pass to beat two (small operands are bound by the number of dependent
+// launches, and the two separate scans need one launch less: a row scan carries the second stage
+// of a column scan).  A function of shape and alignment alone, so that an encoding and the audit
+// that re-forms it always take the same kernel.
+bool use_tile(const TileScanJob& t) {
+  return tile_scan_ok(t) && (int64_t)t.R * t.Cc * t.batch >= ((int64_t)1 << 25);
+}
+
 // Scans in stream order.  The second stage of a coldot is held back: the next rowdot carries it in
 // the same launch unless it reads that stage's output (or is gated differently); anything else
 // flushes it first.  The caller flushes before the results are needed.
@@ -255,8 +264,8 @@ struct ScanQueue {
   hipError_t run(const ScanJob& j) {
     hipError_t e;
     const ScanArgs& s = j.s;
-    const bool can_carry = j.rowdot && pending.valid && s.w != pending.out && s.w != pending.row_out &&
-                           s.batch == pending.batch &&
+    const bool reads_pending = s.w != nullptr && (s.w == pending.out || s.w == pending.row_out);
+    const bool can_carry = j.rowdot && pending.valid && !reads_pending && s.batch == pending.batch &&
                            s.gate == pending.gate && s.gate_stride == pending.gate_stride &&
                            s.gate_value == pending.gate_value;
     if (pending.valid && !can_carry && (e = flush()) != hipSuccess) return e;
@@ -476,7 +485,7 @@ int gecc_encode_a(gecc_ctx* ctx, const void* dev_A, double* dev_A_par, void* str
   }
   ScanQueue q{ctx, (hipStream_t)stream};
   const TileScanJob tj = tile_job(ctx, GECC_MAT_A, dev_A, dev_A_par, nullptr, nullptr, 0, nullptr);
-  hipError_t e = ctx->tile_op == GECC_MAT_A && tile_scan_ok(tj) ? q.run_tile(tj, GECC_K_ENCODE_A)
+  hipError_t e = ctx->tile_op == GECC_MAT_A && use_tile(tj) ? q.run_tile(tj, GECC_K_ENCODE_A)
                                                                 : q.run(scan_a_over_n(ctx, dev_A, nullptr, dev_A_par, nullptr));
   return hip_rc(e != hipSuccess ? e : q.flush());
 }
@@ -494,7 +503,7 @@ int gecc_encode_b(gecc_ctx* ctx, const void* dev_B, double* dev_B_par, void* str
   }
   ScanQueue q{ctx, (hipStream_t)stream};
   const TileScanJob tj = tile_job(ctx, GECC_MAT_B, dev_B, dev_B_par, nullptr, nullptr, 0, nullptr);
-  hipError_t e = ctx->tile_op == GECC_MAT_B && tile_scan_ok(tj) ? q.run_tile(tj, GECC_K_ENCODE_B)
+  hipError_t e = ctx->tile_op == GECC_MAT_B && use_tile(tj) ? q.run_tile(tj, GECC_K_ENCODE_B)
                                                                 : q.run(scan_b_over_m(ctx, dev_B, nullptr, dev_B_par, nullptr));
   return hip_rc(e != hipSuccess ? e : q.flush());
 }
@@ -659,7 +668,7 @@ int correct_impl(gecc_ctx* ctx, void* dev_A, const double* dev_A_par, void* dev_
       TileScanJob tj = tile_job(&v, op, X, out, nullptr, nullptr, 0, gw);
       tj.gate_stride = 0;
       hipError_t ee;
-      if (tile_scan_ok(tj)) ee = qv.run_tile(tj, kind);
+      if (use_tile(tj)) ee = qv.run_tile(tj, kind);
       else { ScanJob j = old_job; j.s.gate_stride = 0; ee = qv.run(j); }
       if (ee == hipSuccess) { qv.pending.gate_stride = 0; ee = qv.flush(); }
       ctx->ev_n = v.ev_n;
@@ -685,7 +694,7 @@ int correct_impl(gecc_ctx* ctx, void* dev_A, const double* dev_A_par, void* dev_
   const bool t_is_a = ctx->tile_op == GECC_MAT_A;
   const TileScanJob tj = tile_job(ctx, ctx->tile_op, t_is_a ? dev_A : dev_B,
                                   const_cast<double*>(t_is_a ? d.audit_a : d.audit_b), nullptr, nullptr, 0, gate);
-  if (tile_scan_ok(tj)) {
+  if (use_tile(tj)) {
     if ((e = q.run_tile(tj, t_is_a ? GECC_K_AUDIT_A : GECC_K_AUDIT_B)) != hipSuccess) return hip_rc(e);
     if ((e = q.run(t_is_a ? jb : ja)) != hipSuccess) return hip_rc(e);
   } else {
@@ -726,7 +735,7 @@ int encode_and_multiply(gecc_ctx* ctx, void* dev_A, void* dev_B, float* dev_C, d
   const bool t_is_a = ctx->tile_op == GECC_MAT_A;
   const TileScanJob tj = t_is_a ? tile_job(ctx, GECC_MAT_A, dev_A, dev_A_par, dev_B_par, dev_C_par, rec, nullptr)
                                 : tile_job(ctx, GECC_MAT_B, dev_B, dev_B_par, dev_A_par, dev_C_par + 2 * (size_t)p.n, rec, nullptr);
-  if (tile_scan_ok(tj)) {
+  if (use_tile(tj)) {
     // the larger operand in one pass: its encoding and its parity block of C-bar together.  That
     // pass reads the other operand's encoding, and the other operand's parity block reads this one's.
     if ((e = q.run(t_is_a ? eb : ea)) != hipSuccess) return hip_rc(e);
