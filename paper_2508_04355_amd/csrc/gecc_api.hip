@@ -23,6 +23,7 @@ void make_layout(gecc_ctx* c) {
   Layout& L = c->lay;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+  L.done = take(SCAN_DONE_WORDS * sizeof(uint32_t));
   L.rowpart = take(b * c->ntn * (size_t)c->rp_ld * 2 * sizeof(float));
   L.colpart = take(b * c->ntm * (size_t)c->cp_ld * 2 * sizeof(float));
   // (blocked mode: one record per block, nj * 2n + ni * 2m doubles in all; audits per operand line)
@@ -63,6 +64,16 @@ int check_ws(const gecc_ctx* c) {
 }
 
 int hip_rc(hipError_t e) { return e == hipSuccess ? GECC_OK : GECC_ERR_HIP; }
+
+// The counters at the front of the workspace have to start at zero: done once per attached
+// workspace, on the stream of the first call that launches scans.
+int prep(gecc_ctx* c, hipStream_t st) {
+  if (c->ws_zeroed == c->ws) return GECC_OK;
+  if (launch_zero_words(reinterpret_cast<uint32_t*>(c->ws + c->lay.done), SCAN_DONE_WORDS, st) != hipSuccess)
+    return GECC_ERR_HIP;
+  c->ws_zeroed = c->ws;
+  return GECC_OK;
+}
 
 // operands need only their natural alignment; 16-byte aligned rows get the vector paths
 bool aligned_to(const void* p, size_t a) { return reinterpret_cast<uintptr_t>(p) % a == 0; }
@@ -255,6 +266,7 @@ struct ScanQueue {
   gecc_ctx* c;
   hipStream_t st;
   Stage2Job pending{};
+  uint32_t* done() const { return reinterpret_cast<uint32_t*>(c->ws + c->lay.done); }
   hipError_t flush() {
     if (!pending.valid) return hipSuccess;
     pending.valid = false;
@@ -275,14 +287,35 @@ struct ScanQueue {
       pending.valid = false;
       return t.done(e);
     }
-    return t.done(launch_coldot_stage1(s, &pending, st));
+    // a column scan finishes by itself where one workgroup can add a segment's chunks up
+    ScanArgs f = s;
+    if (coldot_done_words(f) > 0) f.done = done();
+    return t.done(launch_coldot_stage1(f, &pending, st));
   }
-  // a tile scan: its second stage becomes the pending one
+  // a tile scan: what is left of its second stage becomes the pending one
   hipError_t run_tile(const TileScanJob& tj, int kind) {
     hipError_t e;
     if (pending.valid && (e = flush()) != hipSuccess) return e;
+    TileScanJob f = tj;
+    f.done = done();
     Timed t(c, kind, st);
-    return t.done(launch_tile_scan(tj, &pending, st));
+    return t.done(launch_tile_scan(f, &pending, st));
+  }
+  // two scans that do not depend on each other can share a launch when every column scan among
+  // them finishes by itself
+  bool can_pair(const ScanJob& a, const ScanJob& b) const {
+    const int wa = a.rowdot ? 0 : coldot_done_words(a.s), wb = b.rowdot ? 0 : coldot_done_words(b.s);
+    return (a.rowdot || wa > 0) && (b.rowdot || wb > 0) && wa + wb <= SCAN_DONE_WORDS &&
+           a.s.gate == b.s.gate && a.s.gate_stride == b.s.gate_stride && a.s.gate_value == b.s.gate_value;
+  }
+  hipError_t run_pair(const ScanJob& a, const ScanJob& b, int kind) {
+    hipError_t e;
+    if (pending.valid && (e = flush()) != hipSuccess) return e;
+    ScanArgs fa = a.s, fb = b.s;
+    if (!a.rowdot) fa.done = done();
+    if (!b.rowdot) fb.done = done() + (a.rowdot ? 0 : coldot_done_words(a.s));
+    Timed t(c, kind, st);
+    return t.done(launch_scan_pair(fa, a.rowdot, fb, b.rowdot, st));
   }
 };
 
@@ -295,6 +328,7 @@ hipError_t parity_products(gecc_ctx* c, ScanQueue& q, const void* A, const doubl
   const ScanJob pr = scan_a_over_k(c, A, B_par, C_par, rec);
   const ScanJob pc = scan_b_over_k(c, B, A_par, C_par + 2 * (size_t)p.n, rec);
   hipError_t e;
+  if (q.can_pair(pr, pc)) return q.run_pair(pr, pc, GECC_K_PARITY_RC);
   if (!pc.rowdot && pr.rowdot) {
     if ((e = q.run(pc)) != hipSuccess) return e;
     return q.run(pr);
@@ -376,6 +410,7 @@ int gecc_create(gecc_ctx** out, const gecc_params* p) {
   c->cp_ld = p->m % 256 == 0 ? p->m + 16 : p->m;
   c->ws = nullptr;
   c->ws_bytes = 0;
+  c->ws_zeroed = nullptr;
   c->panel = nullptr;
   c->n_panel = 0;
   c->fault_bias = 0;
@@ -456,6 +491,7 @@ int gecc_set_workspace(gecc_ctx* ctx, void* dev_workspace, size_t bytes) {
   if (bytes < ctx->lay.total) return GECC_ERR_WORKSPACE;
   ctx->ws = static_cast<char*>(dev_workspace);
   ctx->ws_bytes = bytes;
+  ctx->ws_zeroed = nullptr;     // its counters are zeroed by the first call that launches something
   return GECC_OK;
 }
 
@@ -477,6 +513,7 @@ int gecc_encode_a(gecc_ctx* ctx, const void* dev_A, double* dev_A_par, void* str
   if (rc) return rc;
   if (!dev_A || !dev_A_par) return GECC_ERR_ARG;
   if (!aligned_to(dev_A, elem_size(ctx->p.dtype)) || !aligned_to(dev_A_par, 8)) return GECC_ERR_ALIGN;
+  if ((rc = prep(ctx, (hipStream_t)stream))) return rc;
   if (blocked(ctx)) {
     gecc_ctx v = view_a(ctx);
     const int rc2 = gecc_encode_a(&v, dev_A, dev_A_par, stream);
@@ -495,6 +532,7 @@ int gecc_encode_b(gecc_ctx* ctx, const void* dev_B, double* dev_B_par, void* str
   if (rc) return rc;
   if (!dev_B || !dev_B_par) return GECC_ERR_ARG;
   if (!aligned_to(dev_B, elem_size(ctx->p.dtype)) || !aligned_to(dev_B_par, 8)) return GECC_ERR_ALIGN;
+  if ((rc = prep(ctx, (hipStream_t)stream))) return rc;
   if (blocked(ctx)) {
     gecc_ctx v = view_b(ctx);
     const int rc2 = gecc_encode_b(&v, dev_B, dev_B_par, stream);
@@ -604,6 +642,7 @@ int gecc_multiply(gecc_ctx* ctx, const void* dev_A, const double* dev_A_par, con
   int rc = check_multiply_args(ctx, dev_A, dev_A_par, dev_B, dev_B_par, dev_C, dev_C_par, dev_faults, n_faults);
   if (rc) return rc;
   hipStream_t st = (hipStream_t)stream;
+  if ((rc = prep(ctx, st))) return rc;
   if (blocked(ctx)) return hip_rc(blocked_multiply(ctx, dev_A, dev_A_par, dev_B, dev_B_par, dev_C, dev_C_par, dev_faults, n_faults, st));
   ScanQueue q{ctx, st};
   hipError_t e;
@@ -614,10 +653,20 @@ int gecc_multiply(gecc_ctx* ctx, const void* dev_A, const double* dev_A_par, con
 
 namespace {
 
-// S4 + S5.  summary = 0 leaves the first report to the decoder's first pass (saves a launch).
+// whether the threshold launch also carries the first report and the decoder's first pass
+// (the blocked code has a threshold kernel of its own)
+int first_pass_rides(const gecc_ctx* c) { return blocked(c) ? 0 : 1; }
+
+// S4 + S5.  summary = 1: a launch of its own writes the first report; 0: that is left to the decoder's
+// first pass; 2: first report and first decoder pass ride in the threshold launch (its last workgroup).
+// ops: the operands and their parities {A, A_par, B, B_par}, which the decoder's first pass reads
+// (summary = 2 only; null otherwise).
+struct Operands { void* A; const double* A_par; void* B; const double* B_par; };
 int verify_impl(gecc_ctx* ctx, const float* dev_C, const double* dev_C_par, gecc_report* dev_report,
-                int32_t fused, int summary, hipStream_t st) {
-  DecodeArgs d = decode_args(ctx, nullptr, nullptr, nullptr, nullptr, const_cast<float*>(dev_C),
+                int32_t fused, int summary, const Operands* ops, hipStream_t st) {
+  if (summary == 2 && (!ops || !ops->A || !ops->A_par || !ops->B || !ops->B_par)) return GECC_ERR_ARG;
+  DecodeArgs d = decode_args(ctx, ops ? ops->A : nullptr, ops ? ops->A_par : nullptr, ops ? ops->B : nullptr,
+                             ops ? ops->B_par : nullptr, const_cast<float*>(dev_C),
                              const_cast<double*>(dev_C_par), dev_report);
   hipError_t e;
   if (!fused && blocked(ctx)) return GECC_ERR_ARG;   // (blocked mode verifies from the product's own partial sums)
@@ -639,22 +688,23 @@ int verify_impl(gecc_ctx* ctx, const float* dev_C, const double* dev_C_par, gecc
   }
   {
     Timed t(ctx, GECC_K_THRESHOLD, st);
-    e = blocked(ctx) ? launch_threshold_blocked(d, ctx->p.n, ctx->p.m, st) : launch_threshold(d, st);
+    e = blocked(ctx) ? launch_threshold_blocked(d, ctx->p.n, ctx->p.m, st) : launch_threshold(d, summary == 2, st);
     if ((e = t.done(e)) != hipSuccess) return hip_rc(e);
   }
-  if (!summary) return GECC_OK;
+  if (summary != 1) return GECC_OK;
   Timed t(ctx, GECC_K_DECODE, st);
   return hip_rc(t.done(launch_summarize(d, st)));
 }
 
-// S6 + S7.  with_summary = 1: the first decoder pass also writes the first report.
+// S6 + S7.  with_summary = 1: the first decoder pass also writes the first report; 2: that pass has
+// already run (see verify_impl).
 int correct_impl(gecc_ctx* ctx, void* dev_A, const double* dev_A_par, void* dev_B, const double* dev_B_par,
                  float* dev_C, double* dev_C_par, gecc_report* dev_report, int with_summary, hipStream_t st) {
   DecodeArgs d = decode_args(ctx, dev_A, dev_A_par, dev_B, dev_B_par, dev_C, dev_C_par, dev_report);
   const int32_t* gate = &d.state->phase;
   hipError_t e;
   // Section V step 2 on the flagged lines; on failure the phase becomes PH_AUDIT
-  {
+  if (with_summary != 2) {
     Timed t(ctx, GECC_K_DECODE, st);
     if ((e = t.done(launch_decode_c(d, with_summary, st))) != hipSuccess) return hip_rc(e);
   }
@@ -697,6 +747,8 @@ int correct_impl(gecc_ctx* ctx, void* dev_A, const double* dev_A_par, void* dev_
   if (use_tile(tj)) {
     if ((e = q.run_tile(tj, t_is_a ? GECC_K_AUDIT_A : GECC_K_AUDIT_B)) != hipSuccess) return hip_rc(e);
     if ((e = q.run(t_is_a ? jb : ja)) != hipSuccess) return hip_rc(e);
+  } else if (q.can_pair(ja, jb)) {
+    if ((e = q.run_pair(ja, jb, GECC_K_AUDIT_AB)) != hipSuccess) return hip_rc(e);
   } else {
     const bool b_first = ja.rowdot && !jb.rowdot;
     if ((e = q.run(b_first ? jb : ja)) != hipSuccess) return hip_rc(e);
@@ -720,6 +772,7 @@ int encode_and_multiply(gecc_ctx* ctx, void* dev_A, void* dev_B, float* dev_C, d
                         hipStream_t st) {
   int rc = check_multiply_args(ctx, dev_A, dev_A_par, dev_B, dev_B_par, dev_C, dev_C_par, dev_faults, n_faults);
   if (rc) return rc;
+  if ((rc = prep(ctx, st))) return rc;
   if (blocked(ctx)) {
     if ((rc = gecc_encode_a(ctx, dev_A, dev_A_par, st)) || (rc = gecc_encode_b(ctx, dev_B, dev_B_par, st))) return rc;
     return hip_rc(blocked_multiply(ctx, dev_A, dev_A_par, dev_B, dev_B_par, dev_C, dev_C_par, dev_faults, n_faults, st));
@@ -750,6 +803,10 @@ int encode_and_multiply(gecc_ctx* ctx, void* dev_A, void* dev_B, float* dev_C, d
     else
       e = q.run(po);
     if (e != hipSuccess) return hip_rc(e);
+  } else if (q.can_pair(ea, eb) && q.can_pair(pr, pc)) {
+    // two launches: both encodings, then both parity blocks of C-bar
+    if ((e = q.run_pair(ea, eb, GECC_K_ENCODE_AB)) != hipSuccess) return hip_rc(e);
+    if ((e = q.run_pair(pr, pc, GECC_K_PARITY_RC)) != hipSuccess) return hip_rc(e);
   } else {
     // stored:        A n x k, B k x m   A n x k, B m x k   A k x n, B k x m   A k x n, B m x k
     // rowdots:       B_P, P_r           P_r, P_c           A_P, B_P           A_P, P_c
@@ -771,7 +828,7 @@ int gecc_verify(gecc_ctx* ctx, const float* dev_C, const double* dev_C_par, gecc
   int rc = check_ws(ctx);
   if (rc) return rc;
   if (!dev_C_par || !dev_report || (!fused && !dev_C)) return GECC_ERR_ARG;
-  return verify_impl(ctx, dev_C, dev_C_par, dev_report, fused, 1, (hipStream_t)stream);
+  return verify_impl(ctx, dev_C, dev_C_par, dev_report, fused, 1, nullptr, (hipStream_t)stream);
 }
 
 int gecc_correct(gecc_ctx* ctx, void* dev_A, const double* dev_A_par, void* dev_B,
@@ -781,6 +838,7 @@ int gecc_correct(gecc_ctx* ctx, void* dev_A, const double* dev_A_par, void* dev_
   if (rc) return rc;
   if (!dev_A || !dev_A_par || !dev_B || !dev_B_par || !dev_C || !dev_C_par || !dev_report)
     return GECC_ERR_ARG;
+  if ((rc = prep(ctx, (hipStream_t)stream))) return rc;
   return correct_impl(ctx, dev_A, dev_A_par, dev_B, dev_B_par, dev_C, dev_C_par, dev_report, 0,
                       (hipStream_t)stream);
 }
@@ -792,8 +850,10 @@ int gecc_protected_gemm(gecc_ctx* ctx, void* dev_A, void* dev_B, float* dev_C, d
   if ((rc = encode_and_multiply(ctx, dev_A, dev_B, dev_C, dev_A_par, dev_B_par, dev_C_par, nullptr, 0,
                                 (hipStream_t)stream)))
     return rc;
-  if ((rc = verify_impl(ctx, dev_C, dev_C_par, dev_report, 1, 0, (hipStream_t)stream))) return rc;
-  return correct_impl(ctx, dev_A, dev_A_par, dev_B, dev_B_par, dev_C, dev_C_par, dev_report, 1,
+  const int fuse = first_pass_rides(ctx);
+  const Operands ops{dev_A, dev_A_par, dev_B, dev_B_par};
+  if ((rc = verify_impl(ctx, dev_C, dev_C_par, dev_report, 1, fuse ? 2 : 0, &ops, (hipStream_t)stream))) return rc;
+  return correct_impl(ctx, dev_A, dev_A_par, dev_B, dev_B_par, dev_C, dev_C_par, dev_report, fuse ? 2 : 1,
                       (hipStream_t)stream);
 }
 
@@ -812,8 +872,10 @@ int gecc_protected_gemm_retry(gecc_ctx* ctx, void* dev_A, void* dev_B, float* de
     else
       rc = gecc_multiply(ctx, dev_A, dev_A_par, dev_B, dev_B_par, dev_C, dev_C_par, nullptr, 0, stream);
     if (rc) return rc;
-    if ((rc = verify_impl(ctx, dev_C, dev_C_par, dev_report, 1, 0, (hipStream_t)stream))) return rc;
-    if ((rc = correct_impl(ctx, dev_A, dev_A_par, dev_B, dev_B_par, dev_C, dev_C_par, dev_report, 1,
+    const int fuse = first_pass_rides(ctx);
+    const Operands ops{dev_A, dev_A_par, dev_B, dev_B_par};
+    if ((rc = verify_impl(ctx, dev_C, dev_C_par, dev_report, 1, fuse ? 2 : 0, &ops, (hipStream_t)stream))) return rc;
+    if ((rc = correct_impl(ctx, dev_A, dev_A_par, dev_B, dev_B_par, dev_C, dev_C_par, dev_report, fuse ? 2 : 1,
                            (hipStream_t)stream)))
       return rc;
     if ((rc = gecc_report_to_host(ctx, dev_report, host_report, items_of(ctx), stream))) return rc;
@@ -864,11 +926,16 @@ int gecc_protected_gemm_static(gecc_ctx* ctx, void* dev_A, void* dev_B, float* d
   // the context's own workspace (if any) is left alone: this call runs on the static one
   char* const keep_ws = ctx->ws;
   const size_t keep_bytes = ctx->ws_bytes;
+  char* const keep_zeroed = ctx->ws_zeroed;
   ctx->ws = ws;
   ctx->ws_bytes = GECC_STATIC_SCRATCH_BYTES;
+  // the array starts as zeros (static storage) and every scan leaves its counters at zero: no launch
+  // is needed to clear them, whichever context used the array before
+  ctx->ws_zeroed = ws;
   rc = gecc_protected_gemm(ctx, dev_A, dev_B, dev_C, dev_A_par, dev_B_par, dev_C_par, dev_report, stream);
   ctx->ws = keep_ws;
   ctx->ws_bytes = keep_bytes;
+  ctx->ws_zeroed = keep_zeroed;
   return rc;
 }
 
@@ -920,12 +987,13 @@ int gecc_protected_gemm_panels(gecc_ctx* ctx, void* dev_A, void* dev_B, float* d
     }
   }
   hipStream_t st = (hipStream_t)stream;
+  if ((rc = prep(ctx, st))) return rc;
   const gecc_params& p = ctx->p;
   const size_t esz = elem_size(p.dtype);
   const int64_t rec = 2 * (int64_t)p.n + 2 * (int64_t)p.m + 4;
   for (int g = 0; g < P; ++g) {
     gecc_ctx* c = ctx->panel[g];
-    c->ws = ctx->ws; c->ws_bytes = ctx->ws_bytes;
+    c->ws = ctx->ws; c->ws_bytes = ctx->ws_bytes; c->ws_zeroed = ctx->ws_zeroed;
     c->ev = ctx->ev; c->ev_kind = ctx->ev_kind; c->ev_mask = ctx->ev_mask; c->ev_cap = ctx->ev_cap; c->ev_n = ctx->ev_n;
     const int64_t k0 = (int64_t)g * step;
     char* Ag = static_cast<char*>(dev_A) + (p.trans_a ? k0 * p.lda : k0) * (int64_t)esz;
@@ -936,8 +1004,9 @@ int gecc_protected_gemm_panels(gecc_ctx* ctx, void* dev_A, void* dev_B, float* d
     double* Cpg = dev_C_par + g * rec;
     c->fault_bias = g;
     rc = encode_and_multiply(c, Ag, Bg, Cg, Apg, Bpg, Cpg, dev_faults, n_faults, st);
-    if (!rc) rc = verify_impl(c, Cg, Cpg, dev_report + g, 1, 0, st);
-    if (!rc) rc = correct_impl(c, Ag, Apg, Bg, Bpg, Cg, Cpg, dev_report + g, 1, st);
+    const Operands ops{Ag, Apg, Bg, Bpg};
+    if (!rc) rc = verify_impl(c, Cg, Cpg, dev_report + g, 1, 2, &ops, st);
+    if (!rc) rc = correct_impl(c, Ag, Apg, Bg, Bpg, Cg, Cpg, dev_report + g, 2, st);
     if (!rc && g > 0) rc = hip_rc(launch_accumulate(dev_C, dev_C_partial, p.n, p.m, p.ldc, st));
     ctx->ev_n = c->ev_n;
     c->ev = nullptr; c->ev_kind = nullptr; c->ev_cap = 0; c->ev_n = 0;     // the records stay the parent's

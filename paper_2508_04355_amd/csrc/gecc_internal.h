@@ -12,6 +12,12 @@ namespace gecc {
 
 // rows per chunk of the two-stage column reduction (scan kernels)
 constexpr int SCAN_CHUNK_ROWS = 128;
+// "Done" counters at the front of the workspace: one per column segment (or chunk of rows) of a scan
+// whose last workgroup adds the partial results up itself.  Zero between launches (the last arrival
+// wraps its counter), zeroed once when a workspace is attached.
+constexpr int SCAN_DONE_WORDS = 16384;
+// A column reduction finishes by itself when one workgroup can add a segment's chunks up quickly
+constexpr int SCAN_FUSE_MAX_CHUNKS = 64;
 
 // decoder phases kept in device memory (per batch item)
 enum : int { PH_DONE = 0, PH_AUDIT = 1, PH_REVERIFY = 2 };
@@ -26,6 +32,7 @@ struct DecodeState {
   // filled by the threshold kernel (atomics; cleared by reset_state before each verify)
   int32_t s_cnt, t_cnt;
   int32_t nonfinite;          // some syndrome is NaN or infinite: nothing can be subtracted, recompute
+  uint32_t th_done;           // threshold workgroups that have finished (wraps to zero with the last one)
   int32_t rows[GECC_MAX_ERR], cols[GECC_MAX_ERR];
   // decoder
   int32_t phase;
@@ -34,6 +41,8 @@ struct DecodeState {
 };
 
 struct Layout {            // byte offsets into the caller's workspace
+  size_t done;             // uint32 [SCAN_DONE_WORDS]      always first, whatever the shape: contexts that share a
+                           //                               workspace in stream order share the counters too
   size_t rowpart;          // float  [batch][ntn][rp_ld][2]   per-tile row sums (plain, local-weighted)
   size_t colpart;          // float  [batch][ntm][cp_ld][2]   per-tile column sums
                            // (rp_ld, cp_ld: n, m padded so that the slab stride is no power of two)
@@ -68,6 +77,7 @@ struct gecc_ctx {
   int cu_hint;             // GECC_CU_COUNT (tests: plan the tile rounds as for that many CUs), else 0
   char* ws;                // device workspace (caller's)
   size_t ws_bytes;
+  char* ws_zeroed;         // the workspace whose "done" counters this context knows to be zero between launches
   int fault_bias;          // see GemmArgs::fault_bias (nonzero only in a panel's context)
   gecc_ctx** panel;        // contexts of the k-panels of the last gecc_protected_gemm_panels call
   int n_panel;
@@ -115,6 +125,8 @@ struct ScanArgs {
   int64_t w_stride, out_stride;
   int vec_ok;           // set by the launcher: rows are 16-byte aligned, vector loads allowed
   double* scratch;      // coldot only: [batch][nchunk][2][Cc]
+  uint32_t* done;       // coldot only: counters (coldot_done_words of them, all zero); the scan then finishes
+                        // by itself.  null: the second stage is left to the caller (see launch_coldot_stage1)
   const int32_t* gate;
   int64_t gate_stride;  // in bytes
   int gate_value;
@@ -125,10 +137,18 @@ struct ScanArgs {
 };
 // carry: null, or a pending second stage whose output this scan does not read
 hipError_t launch_rowdot(const ScanArgs& a, const Stage2Job* carry, hipStream_t st);
-// launches the first stage only and describes the second in *pending
+// launches the first stage and describes the second in *pending (pending->valid = false when the
+// scan finishes by itself: a.done set)
 hipError_t launch_coldot_stage1(const ScanArgs& a, Stage2Job* pending, hipStream_t st);
+// counters a column scan needs to finish by itself; 0: it cannot (too many chunks per segment)
+int coldot_done_words(const ScanArgs& a);
+// two independent scans (row0 / row1: rowdot, else coldot with `done` set) in one launch; both gated
+// alike or not at all; the two `done` ranges must not overlap
+hipError_t launch_scan_pair(const ScanArgs& a0, bool row0, const ScanArgs& a1, bool row1, hipStream_t st);
 hipError_t launch_stage2(const Stage2Job& j, hipStream_t st);
 int stage2_blocks(const Stage2Job& j);
+// words[0 .. count) = 0 (a kernel, so that a captured call stays free of memset nodes)
+hipError_t launch_zero_words(uint32_t* words, int count, hipStream_t st);
 size_t coldot_scratch_doubles(int R, int Cc, int batch);
 
 // tile scan: column part (out_col[t][c] = sum_r wr_t[r] X[r,c]) and row part (out_row[t][r] =
@@ -152,13 +172,14 @@ struct TileScanJob {
   int64_t row_out_stride;
   double* col_scratch;      // coldot_scratch_doubles(R, Cc, batch)
   double* row_scratch;      // tile_scan_row_scratch_doubles(R, Cc, dtype, batch)
+  uint32_t* done;           // SCAN_DONE_WORDS zeroed counters, or null: parts that can then finish by themselves
   const int32_t* gate;
   int64_t gate_stride;
   int gate_value;
 };
 bool tile_scan_ok(const TileScanJob& t);     // 16-byte aligned rows, Cc a multiple of the vector width
 size_t tile_scan_row_scratch_doubles(int R, int Cc, int dtype, int batch);
-// launches the first stage and describes the second in *pending
+// launches the first stage and describes in *pending what is left of the second (valid = false: nothing)
 hipError_t launch_tile_scan(const TileScanJob& t, Stage2Job* pending, hipStream_t st);
 
 // ---- product (gemm_kernels.hip) ------------------------------------------------------------
@@ -197,6 +218,7 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t st);
 static __device__ __forceinline__ void reset_state(DecodeState* s) {
   s->s_cnt = 0; s->t_cnt = 0;
   s->nonfinite = 0;
+  s->th_done = 0;
   s->phase = PH_DONE;
   s->n_err = 0;
 }
@@ -299,8 +321,10 @@ hipError_t launch_threshold_blocked(const DecodeArgs& a, int n_full, int m_full,
 // blocked mode: the repair in three launches (own block of C-bar; operands; Section V on the rest)
 hipError_t launch_repair_blocked(const DecodeArgs& a, int nbi, hipStream_t st);
 hipError_t launch_reset_state(const DecodeArgs& a, hipStream_t st);
-// partial sums -> syndromes -> threshold flags (Section V step 1) and max |syndrome| per family
-hipError_t launch_threshold(const DecodeArgs& a, hipStream_t st);
+// partial sums -> syndromes -> threshold flags (Section V step 1) and max |syndrome| per family.
+// with_decode = 1: the workgroup that finishes last also writes the first report and runs the
+// decoder's first pass (what launch_decode_c(a, 1) would do in a launch of its own)
+hipError_t launch_threshold(const DecodeArgs& a, int with_decode, hipStream_t st);
 // first report (s, t, maxima, CLEAN / DETECTED) from the counters of the first threshold pass
 hipError_t launch_summarize(const DecodeArgs& a, hipStream_t st);
 // Section V step 2 right after detection.  with_summary = 1: also writes the first report

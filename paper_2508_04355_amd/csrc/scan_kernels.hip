@@ -46,47 +46,117 @@ __device__ __forceinline__ bool gated_off(const int32_t* gate, int64_t stride, i
   return g != value;
 }
 
-// Stage 2 of coldot (see below): 64 outputs per workgroup of 256 threads; the 4 wavefronts take
-// the chunks 4 apart and are combined in order.  scratch, out: of batch item b.
-__device__ __forceinline__ void coldot_stage2_body(const double* scratch, double* out, int Cc, int nchunk, int blk) {
+// The second stage of a column reduction adds the chunk partials of an output in one fixed order,
+// whoever does it (a kernel of its own, workgroups carried by a row scan, or the last workgroup of
+// the first stage): four slices, slice w over the chunks w, w + 4, ..., each with four running sums,
+// combined as ((s0 + s1) + (s2 + s3)).
+// One slice of G outputs at once (G independent chains of loads in flight); part[g]: chunk 0's
+// partial of output g, stride: doubles between chunks.
+template <int G>
+__device__ __forceinline__ void slice_sums(const double* const* part, int64_t stride, int nchunk, int w, double* s) {
+  double t[G][4];
+#pragma unroll
+  for (int g = 0; g < G; ++g) { t[g][0] = 0.0; t[g][1] = 0.0; t[g][2] = 0.0; t[g][3] = 0.0; }
+  int ch = w;
+  for (; ch + 12 < nchunk; ch += 16) {
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+      for (int u = 0; u < 4; ++u) t[g][u] += part[g][(int64_t)(ch + 4 * u) * stride];
+  }
+  for (; ch < nchunk; ch += 4) {
+#pragma unroll
+    for (int g = 0; g < G; ++g) t[g][0] += part[g][(int64_t)ch * stride];
+  }
+#pragma unroll
+  for (int g = 0; g < G; ++g) s[g] = (t[g][0] + t[g][1]) + (t[g][2] + t[g][3]);
+}
+
+// Stage 2 of coldot as workgroups of its own: 64 outputs per workgroup of 256 threads, wavefront w
+// takes slice w.  scratch, out: of batch item b; red: 256 doubles of LDS.
+__device__ __forceinline__ void coldot_stage2_body(const double* scratch, double* out, int Cc, int nchunk, int blk,
+                                                   double* red) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int o = blk * 64 + lane;                   // index into [2][Cc]
-  __shared__ double red[4][64];
   double s = 0.0;
   if (o < 2 * Cc) {
     const double* part = scratch + o;
-    double t[4] = {0.0, 0.0, 0.0, 0.0};
-    int ch = wave;
-    for (; ch + 12 < nchunk; ch += 16) {           // 4 loads in flight
-#pragma unroll
-      for (int u = 0; u < 4; ++u) t[u] += part[(int64_t)(ch + 4 * u) * 2 * Cc];
-    }
-    for (; ch < nchunk; ch += 4) t[0] += part[(int64_t)ch * 2 * Cc];
-    s = (t[0] + t[1]) + (t[2] + t[3]);
+    slice_sums<1>(&part, 2 * (int64_t)Cc, nchunk, wave, &s);
   }
-  red[wave][lane] = s;
+  red[wave * 64 + lane] = s;
   __syncthreads();
-  if (wave == 0 && o < 2 * Cc) out[o] = (red[0][lane] + red[1][lane]) + (red[2][lane] + red[3][lane]);
+  if (wave == 0 && o < 2 * Cc) out[o] = (red[lane] + red[64 + lane]) + (red[128 + lane] + red[192 + lane]);
 }
 
-// Stage 2 of the row part of tile_scan (see below): 256 rows per workgroup, the segments of a row
-// added in order.  part: [R][nseg][2], out: [2][R], both of batch item b.
-__device__ __forceinline__ void rowseg_stage2_body(const double* part, double* out, int R, int nseg, int blk) {
-  const int r = blk * 256 + threadIdx.x;
-  if (r >= R) return;
+// The same sums for the 2 * 64 * VEC outputs of one column segment, by the workgroup that finished
+// the segment's last chunk.  col0: first column of the segment; red: 4 * 256 doubles of LDS.
+template <int VEC>
+__device__ __forceinline__ void coldot_finish_segment(const double* scratch, double* out, int Cc, int nchunk, int col0,
+                                                      double* red) {
+  constexpr int G = 4;                              // groups of 64 outputs a thread works on at once
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  static_assert((2 * VEC) % G == 0, "groups");
+#pragma unroll 1
+  for (int g0 = 0; g0 < 2 * VEC; g0 += G) {
+    const double* part[G];
+    int o[G];
+    bool ok[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      const int t = (g0 + g) / VEC, col = col0 + ((g0 + g) % VEC) * 64 + lane;
+      ok[g] = col < Cc;
+      o[g] = t * Cc + min(col, Cc - 1);
+      part[g] = scratch + o[g];
+    }
+    double s[G];
+    slice_sums<G>(part, 2 * (int64_t)Cc, nchunk, wave, s);
+#pragma unroll
+    for (int g = 0; g < G; ++g) red[(g * 4 + wave) * 64 + lane] = s[g];
+    __syncthreads();
+    if (wave < G) {                                 // wavefront g writes group g
+      const int g = wave;
+      if (ok[g]) out[o[g]] = (red[(g * 4 + 0) * 64 + lane] + red[(g * 4 + 1) * 64 + lane]) +
+                             (red[(g * 4 + 2) * 64 + lane] + red[(g * 4 + 3) * 64 + lane]);
+    }
+    __syncthreads();
+  }
+}
+
+// Stage 2 of the row part of tile_scan (see below): the segments of a row added in order.
+// part: [R][nseg][2], out: [2][R], both of batch item b.
+__device__ __forceinline__ void rowseg_sum(const double* part, double* out, int R, int nseg, int r) {
   const double2* p = reinterpret_cast<const double2*>(part) + (int64_t)r * nseg;
   double s0 = 0.0, s1 = 0.0;
   for (int g = 0; g < nseg; ++g) { const double2 v = p[g]; s0 += v.x; s1 += v.y; }
   out[r] = s0;
   out[(int64_t)R + r] = s1;
 }
+// as workgroups of their own: 256 rows each
+__device__ __forceinline__ void rowseg_stage2_body(const double* part, double* out, int R, int nseg, int blk) {
+  const int r = blk * 256 + threadIdx.x;
+  if (r < R) rowseg_sum(part, out, R, nseg, r);
+}
+
+// "Last workgroup finishes": every thread has written its partial results; the workgroup that finds
+// itself the last of `count` to arrive at *counter may read all of them.  The counter wraps to zero
+// with the last arrival, so it is ready for the next launch.  flag: an int of LDS nobody else uses
+// between the two barriers.  Every thread of the workgroup calls this.
+__device__ __forceinline__ bool arrive_last(uint32_t* counter, uint32_t count, int* flag) {
+  __threadfence();                                  // this thread's partial results, device-wide
+  __syncthreads();
+  if (threadIdx.x == 0) *flag = atomicInc(counter, count - 1) == count - 1;
+  __syncthreads();
+  const bool last = *flag != 0;
+  if (last) __threadfence();                        // nothing read before this point is reused
+  return last;
+}
 
 // a pending second stage (column chunks and / or row segments), by workgroup index
-__device__ __forceinline__ void stage2_dispatch(const Stage2Job& j, int b, int blk) {
+__device__ __forceinline__ void stage2_dispatch(const Stage2Job& j, int b, int blk, double* lds) {
   const int col_blocks = j.Cc > 0 ? (2 * j.Cc + 63) / 64 : 0;
   if (blk < col_blocks)
     coldot_stage2_body(j.scratch + (int64_t)b * j.nchunk * 2 * j.Cc, j.out + (int64_t)b * j.out_stride, j.Cc,
-                       j.nchunk, blk);
+                       j.nchunk, blk, lds);
   else
     rowseg_stage2_body(j.row_scratch + (int64_t)b * j.R * j.nseg * 2, j.row_out + (int64_t)b * j.row_out_stride,
                        j.R, j.nseg, blk - col_blocks);
@@ -103,26 +173,19 @@ constexpr int RD_BIG_RB_W = 8;   // with explicit weights (they take registers t
 // steps are taken together, so that a thread has RD_RB * RD_U independent 16-byte loads in
 // flight before the first of them is used (the kernel is a stream over the operand: what it
 // needs is memory-level parallelism, the arithmetic hides behind it).
-// GATED: the launch belongs to the operand audit and returns at once unless the decoder asked for
-// it (a separate instantiation, so that profiles list encoding and audit launches apart).
-template <int DT, bool IDXW, int RD_RB, int RD_U, bool GATED>
-__global__ __launch_bounds__(RD_THREADS) void rowdot_kernel(ScanArgs a) {
+// The rows bx * RD_RB ... of batch item b.  red: RD_RB * RD_THREADS doubles of LDS.  The sums of a row
+// do not depend on RD_RB or RD_U (a thread adds its columns in ascending order either way).
+template <int DT, bool IDXW, int RD_RB, int RD_U>
+__device__ __forceinline__ void rowdot_body(const ScanArgs& a, int bx, int b, double* lds) {
   using E = Elem<DT>;
   using T = typename E::type;
   constexpr int VEC = E::VEC;
   constexpr int STEP = RD_THREADS * VEC;   // columns one pass of the workgroup covers
-  const int b = blockIdx.y;
-  if (GATED && gated_off(a.gate, a.gate_stride, b, a.gate_value)) return;
-  const int own = (int)gridDim.x - a.carry_blocks;
-  if ((int)blockIdx.x >= own) {   // carried second stage of an earlier column / tile scan
-    stage2_dispatch(a.carry, b, (int)blockIdx.x - own);
-    return;
-  }
   const T* X = reinterpret_cast<const T*>(a.X) + (int64_t)b * a.xs;
   const double* w0 = IDXW ? nullptr : a.w + (int64_t)b * a.w_stride;
   const double* w1 = IDXW ? nullptr : w0 + a.Cc;
   double* out = a.out + (int64_t)b * a.out_stride;
-  const int r0 = blockIdx.x * RD_RB;
+  const int r0 = bx * RD_RB;
   const int tid = threadIdx.x;
 
   double acc0[RD_RB], acc1[RD_RB];
@@ -203,7 +266,7 @@ __global__ __launch_bounds__(RD_THREADS) void rowdot_kernel(ScanArgs a) {
   }
 
   // fixed-order reduction over the 256 threads, one parity kind (t) at a time
-  __shared__ double red[RD_RB][RD_THREADS];
+  double (*red)[RD_THREADS] = reinterpret_cast<double (*)[RD_THREADS]>(lds);
   const int wave = tid >> 6, lane = tid & 63;
 #pragma unroll
   for (int t = 0; t < 2; ++t) {
@@ -221,26 +284,45 @@ __global__ __launch_bounds__(RD_THREADS) void rowdot_kernel(ScanArgs a) {
   }
 }
 
+// GATED: the launch belongs to the operand audit and returns at once unless the decoder asked for
+// it (a separate instantiation, so that profiles list encoding and audit launches apart).
+template <int DT, bool IDXW, int RD_RB, int RD_U, bool GATED>
+__global__ __launch_bounds__(RD_THREADS) void rowdot_kernel(ScanArgs a) {
+  __shared__ double lds[RD_RB * RD_THREADS];
+  const int b = blockIdx.y;
+  if (GATED && gated_off(a.gate, a.gate_stride, b, a.gate_value)) return;
+  const int own = (int)gridDim.x - a.carry_blocks;
+  if ((int)blockIdx.x >= own) {   // carried second stage of an earlier column / tile scan
+    stage2_dispatch(a.carry, b, (int)blockIdx.x - own, lds);
+    return;
+  }
+  rowdot_body<DT, IDXW, RD_RB, RD_U>(a, blockIdx.x, b, lds);
+}
+
 // -------------------------------------------------------------------------------------------
 // coldot: out[t][c] = sum_r w_t[r] X[r,c].   Stage 1: a workgroup owns 64*VEC columns and one
 // chunk of SCAN_CHUNK_ROWS rows; its 4 wavefronts interleave the rows and are combined through
 // LDS.  Stage 2 adds the chunks in order.
 constexpr int CD_THREADS = 256;
 
-template <int DT, bool IDXW, bool GATED>
-__global__ __launch_bounds__(CD_THREADS) void coldot_stage1(ScanArgs a, int nchunk) {
+// LDS of a coldot workgroup: the four wavefronts' sums, reused by the last workgroup of a segment
+constexpr int CD_LDS_DOUBLES = 4 * 2 * 8 * 64;
+constexpr int CD_FLAG_AT = 1024;     // (behind what coldot_finish_segment uses)
+
+// Column segment bx, chunk `chunk` of batch item b.  With a.done set, the workgroup that finishes a
+// segment's last chunk also adds the chunks up (no second stage to launch).
+template <int DT, bool IDXW>
+__device__ __forceinline__ void coldot_body(const ScanArgs& a, int nchunk, int nsegx, int bx, int chunk, int b,
+                                            double* lds) {
   using E = Elem<DT>;
   using T = typename E::type;
   constexpr int VEC = E::VEC;
-  const int b = blockIdx.z;
-  if (GATED && gated_off(a.gate, a.gate_stride, b, a.gate_value)) return;
   const T* X = reinterpret_cast<const T*>(a.X) + (int64_t)b * a.xs;
   const double* w0 = IDXW ? nullptr : a.w + (int64_t)b * a.w_stride;
   const double* w1 = IDXW ? nullptr : w0 + a.R;
-  const int chunk = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int c = (blockIdx.x * 64 + lane) * VEC;
+  const int c = (bx * 64 + lane) * VEC;
   const int rbeg = chunk * SCAN_CHUNK_ROWS;
   const int rend = min(a.R, rbeg + SCAN_CHUNK_ROWS);
   const int nv = min(VEC, a.Cc - c);   // <= 0: this lane owns no column
@@ -314,7 +396,7 @@ __global__ __launch_bounds__(CD_THREADS) void coldot_stage1(ScanArgs a, int nchu
     }
   }
 
-  __shared__ double red[4][2][VEC][64];
+  double (*red)[2][VEC][64] = reinterpret_cast<double (*)[2][VEC][64]>(lds);
 #pragma unroll
   for (int e = 0; e < VEC; ++e) { red[wave][0][e][lane] = acc0[e]; red[wave][1][e][lane] = acc1[e]; }
   __syncthreads();
@@ -322,18 +404,30 @@ __global__ __launch_bounds__(CD_THREADS) void coldot_stage1(ScanArgs a, int nchu
   double* part = a.scratch + ((int64_t)b * nchunk + chunk) * 2 * a.Cc;
   for (int o = tid; o < 2 * VEC * 64; o += CD_THREADS) {
     const int l = o & 63, e = (o >> 6) % VEC, t = o / (64 * VEC);
-    const int col = (blockIdx.x * 64 + l) * VEC + e;
+    const int col = (bx * 64 + l) * VEC + e;
     if (col < a.Cc) {
       const double s = (red[0][t][e][l] + red[1][t][e][l]) + (red[2][t][e][l] + red[3][t][e][l]);
       part[(int64_t)t * a.Cc + col] = s;
     }
   }
+  if (a.done && arrive_last(a.done + (int64_t)b * nsegx + bx, (uint32_t)nchunk, reinterpret_cast<int*>(lds + CD_FLAG_AT)))
+    coldot_finish_segment<VEC>(a.scratch + (int64_t)b * nchunk * 2 * a.Cc, a.out + (int64_t)b * a.out_stride, a.Cc,
+                               nchunk, bx * 64 * VEC, lds);
+}
+
+template <int DT, bool IDXW, bool GATED>
+__global__ __launch_bounds__(CD_THREADS) void coldot_stage1(ScanArgs a, int nchunk) {
+  __shared__ double lds[CD_LDS_DOUBLES];
+  const int b = blockIdx.z;
+  if (GATED && gated_off(a.gate, a.gate_stride, b, a.gate_value)) return;
+  coldot_body<DT, IDXW>(a, nchunk, gridDim.x, blockIdx.x, blockIdx.y, b, lds);
 }
 
 __global__ __launch_bounds__(256) void coldot_stage2(Stage2Job j) {
+  __shared__ double lds[256];
   const int b = blockIdx.y;
   if (gated_off(j.gate, j.gate_stride, b, j.gate_value)) return;
-  stage2_dispatch(j, b, blockIdx.x);
+  stage2_dispatch(j, b, blockIdx.x, lds);
 }
 
 // -------------------------------------------------------------------------------------------
@@ -374,7 +468,15 @@ struct TileScanArgs {
   const int32_t* gate;
   int64_t gate_stride;
   int gate_value;
+  // With done_col set, the last workgroup of a column segment adds the segment's chunks up; with
+  // done_row set, the last one of a chunk of rows adds the row partials of its rows: that part
+  // then has no second stage to launch.
+  uint32_t* done_col;     // [batch][nseg]
+  uint32_t* done_row;     // [batch][nchunk]
+  double* col_out; int64_t col_out_stride;
+  double* row_out; int64_t row_out_stride;
 };
+constexpr int TS_FLAG_AT = 1024;   // doubles into the LDS: behind what coldot_finish_segment uses
 
 // wavefront-local ordering of LDS traffic: the hardware keeps a wavefront's LDS instructions in
 // order; this keeps the compiler from moving them across
@@ -527,6 +629,60 @@ __global__ __launch_bounds__(TS_THREADS) void tile_scan(TileScanArgs a) {
       }
     }
   }
+
+  if ((COL && a.done_col) || (ROW && a.done_row)) {
+    __threadfence();                                // this thread's partial results, device-wide
+    __syncthreads();
+    int* flag = reinterpret_cast<int*>(ts_lds + TS_FLAG_AT);
+    if (threadIdx.x == 0) {
+      flag[0] = (COL && a.done_col) ? atomicInc(a.done_col + (int64_t)b * a.nseg + seg, (uint32_t)a.nchunk - 1) == (uint32_t)a.nchunk - 1 : 0;
+      flag[1] = (ROW && a.done_row) ? atomicInc(a.done_row + (int64_t)b * a.nchunk + chunk, (uint32_t)a.nseg - 1) == (uint32_t)a.nseg - 1 : 0;
+    }
+    __syncthreads();
+    const bool last_col = flag[0] != 0, last_row = flag[1] != 0;
+    if (last_col || last_row) __threadfence();
+    if (ROW && last_row) {
+      const double* part = a.row_part + (int64_t)b * a.R * a.nseg * 2;
+      double* out = a.row_out + (int64_t)b * a.row_out_stride;
+      for (int rr = rbeg + (int)threadIdx.x; rr < rend; rr += TS_THREADS) rowseg_sum(part, out, a.R, a.nseg, rr);
+    }
+    if (COL && last_col)
+      coldot_finish_segment<VEC>(a.col_part + (int64_t)b * a.nchunk * 2 * a.Cc, a.col_out + (int64_t)b * a.col_out_stride,
+                                 a.Cc, a.nchunk, seg * SEG, ts_lds);
+  }
+}
+
+// -------------------------------------------------------------------------------------------
+// Two independent scans in one launch (the encodings of A and B; P_r and P_c; the two audits): a
+// dependent launch costs about 5 us of stream time whatever it does.  Every column scan in it
+// finishes its own second stage (ScanArgs::done).  The row scan here takes 4 rows per workgroup.
+struct PairJob {
+  ScanArgs s;
+  int rowdot, idxw;
+  int nblk;          // workgroups of this job
+  int gx, nchunk;    // rowdot: gx workgroups per batch item; coldot: gx column segments x nchunk chunks
+};
+struct PairArgs { PairJob j[2]; };
+
+template <int DT, bool GATED>
+__global__ __launch_bounds__(256) void scan_pair(PairArgs p) {
+  __shared__ double lds[CD_LDS_DOUBLES];
+  int v = blockIdx.x;
+  const bool second = v >= p.j[0].nblk;
+  if (second) v -= p.j[0].nblk;
+  const PairJob& j = second ? p.j[1] : p.j[0];
+  const ScanArgs& a = j.s;
+  if (j.rowdot) {
+    const int bx = v % j.gx, b = v / j.gx;
+    if (GATED && gated_off(a.gate, a.gate_stride, b, a.gate_value)) return;
+    if (GATED || j.idxw) rowdot_body<DT, true, RD_SMALL_RB, RD_SMALL_U>(a, bx, b, lds);
+    else rowdot_body<DT, false, RD_SMALL_RB, RD_SMALL_U>(a, bx, b, lds);
+  } else {
+    const int bx = v % j.gx, chunk = (v / j.gx) % j.nchunk, b = v / (j.gx * j.nchunk);
+    if (GATED && gated_off(a.gate, a.gate_stride, b, a.gate_value)) return;
+    if (GATED || j.idxw) coldot_body<DT, true>(a, j.nchunk, j.gx, bx, chunk, b, lds);
+    else coldot_body<DT, false>(a, j.nchunk, j.gx, bx, chunk, b, lds);
+  }
 }
 
 // vector loads need 16-byte aligned rows
@@ -582,6 +738,14 @@ hipError_t launch_rowdot(const ScanArgs& a0, const Stage2Job* carry, hipStream_t
   return hipGetLastError();
 }
 
+int coldot_done_words(const ScanArgs& a) {
+  const int vec = a.dtype == GECC_BF16 ? 8 : 4;
+  const int nchunk = (a.R + SCAN_CHUNK_ROWS - 1) / SCAN_CHUNK_ROWS;
+  if (nchunk > SCAN_FUSE_MAX_CHUNKS) return 0;
+  const int64_t words = (int64_t)((a.Cc + 64 * vec - 1) / (64 * vec)) * a.batch;
+  return words <= SCAN_DONE_WORDS ? (int)words : 0;
+}
+
 hipError_t launch_coldot_stage1(const ScanArgs& a0, Stage2Job* pending, hipStream_t st) {
   ScanArgs a = a0;
   a.vec_ok = vec_ok(a0) ? 1 : 0;
@@ -591,6 +755,7 @@ hipError_t launch_coldot_stage1(const ScanArgs& a0, Stage2Job* pending, hipStrea
   dim3 grid((a.Cc + 64 * vec - 1) / (64 * vec), nchunk, a.batch);
   const bool idx = a.w == nullptr, gated = a.gate != nullptr;
   if (gated && !idx) return hipErrorInvalidValue;
+  if (a.done && coldot_done_words(a) == 0) return hipErrorInvalidValue;
   if (a.dtype == GECC_BF16) {
     if (gated)    hipLaunchKernelGGL((coldot_stage1<GECC_BF16, true, true>), grid, dim3(CD_THREADS), 0, st, a, nchunk);
     else if (idx) hipLaunchKernelGGL((coldot_stage1<GECC_BF16, true, false>), grid, dim3(CD_THREADS), 0, st, a, nchunk);
@@ -601,10 +766,50 @@ hipError_t launch_coldot_stage1(const ScanArgs& a0, Stage2Job* pending, hipStrea
     else          hipLaunchKernelGGL((coldot_stage1<GECC_F32, false, false>), grid, dim3(CD_THREADS), 0, st, a, nchunk);
   }
   *pending = Stage2Job{};
-  pending->valid = true;
-  pending->scratch = a.scratch; pending->out = a.out; pending->out_stride = a.out_stride;
-  pending->Cc = a.Cc; pending->nchunk = nchunk; pending->batch = a.batch;
-  pending->gate = a.gate; pending->gate_stride = a.gate_stride; pending->gate_value = a.gate_value;
+  if (!a.done) {
+    pending->valid = true;
+    pending->scratch = a.scratch; pending->out = a.out; pending->out_stride = a.out_stride;
+    pending->Cc = a.Cc; pending->nchunk = nchunk; pending->batch = a.batch;
+    pending->gate = a.gate; pending->gate_stride = a.gate_stride; pending->gate_value = a.gate_value;
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_scan_pair(const ScanArgs& a0, bool row0, const ScanArgs& a1, bool row1, hipStream_t st) {
+  if (a0.dtype != a1.dtype || a0.gate != a1.gate || a0.gate_stride != a1.gate_stride || a0.gate_value != a1.gate_value)
+    return hipErrorInvalidValue;
+  const bool gated = a0.gate != nullptr;
+  PairArgs p{};
+  const ScanArgs* src[2] = {&a0, &a1};
+  const bool row[2] = {row0, row1};
+  const int vec = a0.dtype == GECC_BF16 ? 8 : 4;
+  for (int x = 0; x < 2; ++x) {
+    PairJob& j = p.j[x];
+    j.s = *src[x];
+    j.s.vec_ok = vec_ok(*src[x]) ? 1 : 0;
+    j.s.carry_blocks = 0;
+    j.rowdot = row[x] ? 1 : 0;
+    j.idxw = j.s.w == nullptr ? 1 : 0;
+    if (gated && !j.idxw) return hipErrorInvalidValue;
+    if (row[x]) {
+      j.gx = (j.s.R + RD_SMALL_RB - 1) / RD_SMALL_RB;
+      j.nchunk = 1;
+      j.nblk = j.gx * j.s.batch;
+    } else {
+      if (!j.s.done || coldot_done_words(j.s) == 0) return hipErrorInvalidValue;   // must finish by itself
+      j.gx = (j.s.Cc + 64 * vec - 1) / (64 * vec);
+      j.nchunk = (j.s.R + SCAN_CHUNK_ROWS - 1) / SCAN_CHUNK_ROWS;
+      j.nblk = j.gx * j.nchunk * j.s.batch;
+    }
+  }
+  const dim3 grid(p.j[0].nblk + p.j[1].nblk);
+  if (a0.dtype == GECC_BF16) {
+    if (gated) hipLaunchKernelGGL((scan_pair<GECC_BF16, true>), grid, dim3(256), 0, st, p);
+    else       hipLaunchKernelGGL((scan_pair<GECC_BF16, false>), grid, dim3(256), 0, st, p);
+  } else {
+    if (gated) hipLaunchKernelGGL((scan_pair<GECC_F32, true>), grid, dim3(256), 0, st, p);
+    else       hipLaunchKernelGGL((scan_pair<GECC_F32, false>), grid, dim3(256), 0, st, p);
+  }
   return hipGetLastError();
 }
 
@@ -643,6 +848,18 @@ hipError_t launch_tile_scan(const TileScanJob& t, Stage2Job* pending, hipStream_
   a.chunk_rows = tile_scan_chunk_rows(t.R, a.nseg, t.batch);
   a.nchunk = (t.R + a.chunk_rows - 1) / a.chunk_rows;
   a.gate = t.gate; a.gate_stride = t.gate_stride; a.gate_value = t.gate_value;
+  // parts that finish by themselves: the column part when a segment has few enough chunks for one
+  // workgroup to add up, the row part always -- as far as the counters reach
+  bool fuse_col = false, fuse_row = false;
+  if (t.done) {
+    int64_t used = 0;
+    if (t.col_on && a.nchunk <= SCAN_FUSE_MAX_CHUNKS && (int64_t)t.batch * a.nseg <= SCAN_DONE_WORDS) {
+      fuse_col = true; a.done_col = t.done; used = (int64_t)t.batch * a.nseg;
+    }
+    if (t.row_on && used + (int64_t)t.batch * a.nchunk <= SCAN_DONE_WORDS) { fuse_row = true; a.done_row = t.done + used; }
+  }
+  a.col_out = t.col_out; a.col_out_stride = t.col_out_stride;
+  a.row_out = t.row_out; a.row_out_stride = t.row_out_stride;
   const dim3 grid(a.nseg, a.nchunk, a.batch), block(TS_THREADS);
   const size_t lds = 4 * 2 * TS_RB * TS_LDS_LD * sizeof(double);
   const bool gated = t.gate != nullptr;
@@ -671,17 +888,28 @@ hipError_t launch_tile_scan(const TileScanJob& t, Stage2Job* pending, hipStream_
 #undef GECC_TS_DT
 #undef GECC_TS
   *pending = Stage2Job{};
-  pending->valid = true;
+  pending->valid = (t.col_on && !fuse_col) || (t.row_on && !fuse_row);
   pending->batch = t.batch;
   pending->gate = t.gate; pending->gate_stride = t.gate_stride; pending->gate_value = t.gate_value;
-  if (t.col_on) {
+  if (t.col_on && !fuse_col) {
     pending->scratch = t.col_scratch; pending->out = t.col_out; pending->out_stride = t.col_out_stride;
     pending->Cc = t.Cc; pending->nchunk = a.nchunk;
   }
-  if (t.row_on) {
+  if (t.row_on && !fuse_row) {
     pending->row_scratch = t.row_scratch; pending->row_out = t.row_out; pending->row_out_stride = t.row_out_stride;
     pending->R = t.R; pending->nseg = a.nseg;
   }
+  return hipGetLastError();
+}
+
+namespace {
+__global__ void zero_words_kernel(uint32_t* w, int count) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < count) w[i] = 0u;
+}
+}  // namespace
+hipError_t launch_zero_words(uint32_t* words, int count, hipStream_t st) {
+  hipLaunchKernelGGL(zero_words_kernel, dim3((count + 255) / 256), dim3(256), 0, st, words, count);
   return hipGetLastError();
 }
 

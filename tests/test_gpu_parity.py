@@ -358,6 +358,34 @@ def test_results_are_reproducible_bit_for_bit():
     assert g1.reports[0].errors() == g2.reports[0].errors()
 
 
+@pytest.mark.parametrize("dtype,shape,trans", [("f32", (1024, 1024, 1024), (0, 0)), ("bf16", (1024, 512, 768), (0, 1)),
+                                               ("bf16", (768, 512, 1024), (1, 0)), ("f32", (520, 264, 392), (1, 1))])
+def test_a_clean_step_is_six_launches(dtype, shape, trans):
+    """Both encodings in one launch, both parity blocks of C-bar in one, the product, the threshold pass
+    with the first report and decoder pass, both gated audits in one, the gated repair."""
+    import torch
+    n, k, m = shape
+    rng = inputs.rng_for(2, 77)
+    A = inputs.store(rng.standard_normal((n, k)), dtype)
+    B = inputs.store(rng.standard_normal((k, m)), dtype)
+    tau = gecc.noise_thresholds(n, k, m, 1.0, 1.0)
+    ctx = gecc.Context(n, k, m, gecc.BF16 if dtype == "bf16" else gecc.F32, tau, trans_a=trans[0], trans_b=trans[1])
+    dA = H.to_dev(A, dtype, trans[0])
+    dB = H.to_dev(B, dtype, trans[1])
+    C = ctx.alloc_c()
+    A_par, B_par, C_par = ctx.alloc_parities()
+    rep = ctx.alloc_report()
+    ctx.protected_gemm(dA, dB, C, A_par, B_par, C_par, rep)      # (the first call also zeroes the counters)
+    torch.cuda.synchronize()
+    ctx.timing_enable(32, tuple(range(len(gecc.K_NAMES))))
+    ctx.protected_gemm(dA, dB, C, A_par, B_par, C_par, rep)
+    torch.cuda.synchronize()
+    rec = ctx.timing_read(32)
+    ctx.timing_enable(0)
+    assert ctx.report_to_host(rep)[0].status == gecc.CLEAN
+    assert len(rec) == 6, [gecc.K_NAMES[kd] for kd, _ in rec]
+
+
 # ---- per-k-panel verification: every partial product over a panel of k is a codeword ------------------
 @pytest.mark.parametrize("dtype,shape,trans,panels", [("bf16", (520, 512, 264), (0, 0), 4), ("bf16", (520, 512, 264), (0, 1), 2),
                                                       ("bf16", (264, 448, 520), (1, 0), 3), ("f32", (300, 200, 260), (0, 0), 3),
