@@ -179,11 +179,10 @@ def main():
     scan_bytes = {"encode_a": s_in * n * k * batch, "encode_b": s_in * k * m * batch,
                   "parity_r": s_in * n * k * batch, "parity_c": s_in * k * m * batch,
                   "encode_a+parity_r": s_in * n * k * batch, "encode_b+parity_c": s_in * k * m * batch,
-                  "encode_a+encode_b": s_in * (n + m) * k * batch, "parity_r+parity_c": s_in * (n + m) * k * batch,
                   "threshold": 8 * (ntn * n + ntm * m) * batch, "partials": 4 * n * m * batch}
     scan_kinds = (gecc.K_ENCODE_A, gecc.K_ENCODE_B, gecc.K_PARITY_R, gecc.K_PARITY_C, gecc.K_THRESHOLD,
                   gecc.K_PARTIALS, gecc.K_STAGE2, gecc.K_DECODE, gecc.K_AUDIT_A, gecc.K_AUDIT_B, gecc.K_REPAIR,
-                  gecc.K_TILE_A, gecc.K_TILE_B, gecc.K_ENCODE_AB, gecc.K_PARITY_RC, gecc.K_AUDIT_AB)
+                  gecc.K_TILE_A, gecc.K_TILE_B, gecc.K_AUDIT_AB)
 
     def per_kernel(run, reps):
         ctx.timing_enable(16 * reps, scan_kinds)

@@ -305,8 +305,7 @@ enum {
   GECC_K_PARITY_R = 2,  /* P_r = A B_P                                   */
   GECC_K_PARITY_C = 3,  /* P_c = A_P B                                   */
   GECC_K_PRODUCT = 4,   /* data block C (+ fused partial sums, P_g)      */
-  GECC_K_THRESHOLD = 5, /* partial sums -> syndromes -> flags (one-call
-                           entry points: + first report, first decoder pass) */
+  GECC_K_THRESHOLD = 5, /* partial sums -> syndromes -> flags            */
   GECC_K_DECODE = 6,    /* report / Section V step 2                     */
   GECC_K_AUDIT_A = 7,   /* gated re-encoding of A                        */
   GECC_K_AUDIT_B = 8,   /* gated re-encoding of B                        */
@@ -315,10 +314,8 @@ enum {
   GECC_K_STAGE2 = 11,   /* second stage of a scan, launched alone        */
   GECC_K_TILE_A = 12,   /* A_P and P_r in one pass over A                */
   GECC_K_TILE_B = 13,   /* B_P and P_c in one pass over B                */
-  GECC_K_ENCODE_AB = 14, /* A_P and B_P in one launch                    */
-  GECC_K_PARITY_RC = 15, /* P_r and P_c in one launch                    */
-  GECC_K_AUDIT_AB = 16,  /* both gated re-encodings in one launch        */
-  GECC_K_COUNT = 17
+  GECC_K_AUDIT_AB = 14, /* both gated re-encodings in one launch         */
+  GECC_K_COUNT = 15
 };
 int gecc_timing_enable(gecc_ctx* ctx, int32_t max_records, uint32_t kinds_mask);
 int gecc_timing_read(gecc_ctx* ctx, float* host_ms, int32_t* host_kind, int32_t cap, int32_t* count);

@@ -72,12 +72,6 @@ __global__ void reset_state_kernel(DecodeArgs a) {
 constexpr int TH_SLICES = 4;    // wavefronts of a workgroup; each adds every 4th sub-tile of a line
 constexpr int TH_MAXLOADS = 32; // loads a thread keeps in flight
 
-__device__ void decode_c_body(const DecodeArgs& a, int b, DecodeState* st, gecc_report* rep, int pass);
-__device__ int summarize(const DecodeArgs& a, int b, const DecodeState* st, gecc_report* rep);
-
-// WITH_DECODE: the workgroup that finishes last goes on with the first report and the decoder's
-// first pass (one dependent launch less on every step).
-template <bool WITH_DECODE>
 __global__ __launch_bounds__(64 * TH_SLICES) void threshold_kernel(DecodeArgs a) {
   const int b = blockIdx.y;
   DecodeState* st = state_of(a, b);
@@ -117,7 +111,7 @@ __global__ __launch_bounds__(64 * TH_SLICES) void threshold_kernel(DecodeArgs a)
   red[0][slice][lane] = S;
   red[1][slice][lane] = W;
   __syncthreads();
-  if (slice == 0) {
+  if (slice != 0) return;
   double v1 = 0.0, v2 = 0.0;
   if (valid) {
     S = (red[0][0][lane] + red[0][1][lane]) + (red[0][2][lane] + red[0][3][lane]);
@@ -162,21 +156,6 @@ __global__ __launch_bounds__(64 * TH_SLICES) void threshold_kernel(DecodeArgs a)
       double* bm = a.blockmax + ((int64_t)b * gridDim.x + blockIdx.x) * 4;
       bm[0] = mr1; bm[1] = mr2; bm[2] = mq1; bm[3] = mq2;
     }
-  }
-  }
-  if (WITH_DECODE) {
-    // every workgroup of the item has written its syndromes, flags and maxima when the last one
-    // arrives here
-    __shared__ int last;
-    __threadfence();
-    __syncthreads();
-    if (threadIdx.x == 0) last = atomicInc(&st->th_done, gridDim.x - 1) == gridDim.x - 1;
-    __syncthreads();
-    if (!last) return;
-    __threadfence();
-    gecc_report* rep = a.report + b;
-    if (summarize(a, b, st, rep) == GECC_CLEAN) return;
-    decode_c_body(a, b, st, rep, 0);
   }
 }
 
@@ -1043,10 +1022,9 @@ hipError_t launch_reset_state(const DecodeArgs& a, hipStream_t st) {
   return hipGetLastError();
 }
 
-hipError_t launch_threshold(const DecodeArgs& a, int with_decode, hipStream_t st) {
+hipError_t launch_threshold(const DecodeArgs& a, hipStream_t st) {
   dim3 grid((a.p.n + a.p.m + 63) / 64, a.p.batch);   // 64 lines per workgroup: spreads over all CUs
-  if (with_decode) hipLaunchKernelGGL(threshold_kernel<true>, grid, dim3(64 * TH_SLICES), 0, st, a);
-  else             hipLaunchKernelGGL(threshold_kernel<false>, grid, dim3(64 * TH_SLICES), 0, st, a);
+  hipLaunchKernelGGL(threshold_kernel, grid, dim3(64 * TH_SLICES), 0, st, a);
   return hipGetLastError();
 }
 

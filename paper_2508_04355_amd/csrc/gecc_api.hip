@@ -287,9 +287,9 @@ struct ScanQueue {
       pending.valid = false;
       return t.done(e);
     }
-    // a column scan finishes by itself where one workgroup can add a segment's chunks up
+    // (a gated column scan finishes by itself where it can: the audits then need no launch for it)
     ScanArgs f = s;
-    if (coldot_done_words(f) > 0) f.done = done();
+    if (s.gate && coldot_done_words(f) > 0) f.done = done();
     return t.done(launch_coldot_stage1(f, &pending, st));
   }
   // a tile scan: what is left of its second stage becomes the pending one
@@ -297,25 +297,16 @@ struct ScanQueue {
     hipError_t e;
     if (pending.valid && (e = flush()) != hipSuccess) return e;
     TileScanJob f = tj;
-    f.done = done();
+    if (tj.gate) f.done = done();
     Timed t(c, kind, st);
     return t.done(launch_tile_scan(f, &pending, st));
   }
-  // two scans that do not depend on each other can share a launch when every column scan among
-  // them finishes by itself
-  bool can_pair(const ScanJob& a, const ScanJob& b) const {
-    const int wa = a.rowdot ? 0 : coldot_done_words(a.s), wb = b.rowdot ? 0 : coldot_done_words(b.s);
-    return (a.rowdot || wa > 0) && (b.rowdot || wb > 0) && wa + wb <= SCAN_DONE_WORDS &&
-           a.s.gate == b.s.gate && a.s.gate_stride == b.s.gate_stride && a.s.gate_value == b.s.gate_value;
-  }
-  hipError_t run_pair(const ScanJob& a, const ScanJob& b, int kind) {
+  // both gated audits in one launch, where every column reduction among them can finish by itself
+  hipError_t run_audit_pair(const ScanPairItem& x0, const ScanPairItem& x1) {
     hipError_t e;
     if (pending.valid && (e = flush()) != hipSuccess) return e;
-    ScanArgs fa = a.s, fb = b.s;
-    if (!a.rowdot) fa.done = done();
-    if (!b.rowdot) fb.done = done() + (a.rowdot ? 0 : coldot_done_words(a.s));
-    Timed t(c, kind, st);
-    return t.done(launch_scan_pair(fa, a.rowdot, fb, b.rowdot, st));
+    Timed t(c, GECC_K_AUDIT_AB, st);
+    return t.done(launch_audit_pair(x0, x1, done(), st));
   }
 };
 
@@ -328,7 +319,6 @@ hipError_t parity_products(gecc_ctx* c, ScanQueue& q, const void* A, const doubl
   const ScanJob pr = scan_a_over_k(c, A, B_par, C_par, rec);
   const ScanJob pc = scan_b_over_k(c, B, A_par, C_par + 2 * (size_t)p.n, rec);
   hipError_t e;
-  if (q.can_pair(pr, pc)) return q.run_pair(pr, pc, GECC_K_PARITY_RC);
   if (!pc.rowdot && pr.rowdot) {
     if ((e = q.run(pc)) != hipSuccess) return e;
     return q.run(pr);
@@ -653,20 +643,10 @@ int gecc_multiply(gecc_ctx* ctx, const void* dev_A, const double* dev_A_par, con
 
 namespace {
 
-// whether the threshold launch also carries the first report and the decoder's first pass
-// (the blocked code has a threshold kernel of its own)
-int first_pass_rides(const gecc_ctx* c) { return blocked(c) ? 0 : 1; }
-
-// S4 + S5.  summary = 1: a launch of its own writes the first report; 0: that is left to the decoder's
-// first pass; 2: first report and first decoder pass ride in the threshold launch (its last workgroup).
-// ops: the operands and their parities {A, A_par, B, B_par}, which the decoder's first pass reads
-// (summary = 2 only; null otherwise).
-struct Operands { void* A; const double* A_par; void* B; const double* B_par; };
+// S4 + S5.  summary = 0 leaves the first report to the decoder's first pass (saves a launch).
 int verify_impl(gecc_ctx* ctx, const float* dev_C, const double* dev_C_par, gecc_report* dev_report,
-                int32_t fused, int summary, const Operands* ops, hipStream_t st) {
-  if (summary == 2 && (!ops || !ops->A || !ops->A_par || !ops->B || !ops->B_par)) return GECC_ERR_ARG;
-  DecodeArgs d = decode_args(ctx, ops ? ops->A : nullptr, ops ? ops->A_par : nullptr, ops ? ops->B : nullptr,
-                             ops ? ops->B_par : nullptr, const_cast<float*>(dev_C),
+                int32_t fused, int summary, hipStream_t st) {
+  DecodeArgs d = decode_args(ctx, nullptr, nullptr, nullptr, nullptr, const_cast<float*>(dev_C),
                              const_cast<double*>(dev_C_par), dev_report);
   hipError_t e;
   if (!fused && blocked(ctx)) return GECC_ERR_ARG;   // (blocked mode verifies from the product's own partial sums)
@@ -688,23 +668,22 @@ int verify_impl(gecc_ctx* ctx, const float* dev_C, const double* dev_C_par, gecc
   }
   {
     Timed t(ctx, GECC_K_THRESHOLD, st);
-    e = blocked(ctx) ? launch_threshold_blocked(d, ctx->p.n, ctx->p.m, st) : launch_threshold(d, summary == 2, st);
+    e = blocked(ctx) ? launch_threshold_blocked(d, ctx->p.n, ctx->p.m, st) : launch_threshold(d, st);
     if ((e = t.done(e)) != hipSuccess) return hip_rc(e);
   }
-  if (summary != 1) return GECC_OK;
+  if (!summary) return GECC_OK;
   Timed t(ctx, GECC_K_DECODE, st);
   return hip_rc(t.done(launch_summarize(d, st)));
 }
 
-// S6 + S7.  with_summary = 1: the first decoder pass also writes the first report; 2: that pass has
-// already run (see verify_impl).
+// S6 + S7.  with_summary = 1: the first decoder pass also writes the first report.
 int correct_impl(gecc_ctx* ctx, void* dev_A, const double* dev_A_par, void* dev_B, const double* dev_B_par,
                  float* dev_C, double* dev_C_par, gecc_report* dev_report, int with_summary, hipStream_t st) {
   DecodeArgs d = decode_args(ctx, dev_A, dev_A_par, dev_B, dev_B_par, dev_C, dev_C_par, dev_report);
   const int32_t* gate = &d.state->phase;
   hipError_t e;
   // Section V step 2 on the flagged lines; on failure the phase becomes PH_AUDIT
-  if (with_summary != 2) {
+  {
     Timed t(ctx, GECC_K_DECODE, st);
     if ((e = t.done(launch_decode_c(d, with_summary, st))) != hipSuccess) return hip_rc(e);
   }
@@ -744,11 +723,14 @@ int correct_impl(gecc_ctx* ctx, void* dev_A, const double* dev_A_par, void* dev_
   const bool t_is_a = ctx->tile_op == GECC_MAT_A;
   const TileScanJob tj = tile_job(ctx, ctx->tile_op, t_is_a ? dev_A : dev_B,
                                   const_cast<double*>(t_is_a ? d.audit_a : d.audit_b), nullptr, nullptr, 0, gate);
-  if (use_tile(tj)) {
+  const bool tile = use_tile(tj);
+  const ScanPairItem xa{tile && t_is_a ? 2 : (ja.rowdot ? 0 : 1), ja.s, tj};
+  const ScanPairItem xb{tile && !t_is_a ? 2 : (jb.rowdot ? 0 : 1), jb.s, tj};
+  if (audit_pair_ok(xa, xb)) {
+    if ((e = q.run_audit_pair(xa, xb)) != hipSuccess) return hip_rc(e);
+  } else if (tile) {
     if ((e = q.run_tile(tj, t_is_a ? GECC_K_AUDIT_A : GECC_K_AUDIT_B)) != hipSuccess) return hip_rc(e);
     if ((e = q.run(t_is_a ? jb : ja)) != hipSuccess) return hip_rc(e);
-  } else if (q.can_pair(ja, jb)) {
-    if ((e = q.run_pair(ja, jb, GECC_K_AUDIT_AB)) != hipSuccess) return hip_rc(e);
   } else {
     const bool b_first = ja.rowdot && !jb.rowdot;
     if ((e = q.run(b_first ? jb : ja)) != hipSuccess) return hip_rc(e);
@@ -803,10 +785,6 @@ int encode_and_multiply(gecc_ctx* ctx, void* dev_A, void* dev_B, float* dev_C, d
     else
       e = q.run(po);
     if (e != hipSuccess) return hip_rc(e);
-  } else if (q.can_pair(ea, eb) && q.can_pair(pr, pc)) {
-    // two launches: both encodings, then both parity blocks of C-bar
-    if ((e = q.run_pair(ea, eb, GECC_K_ENCODE_AB)) != hipSuccess) return hip_rc(e);
-    if ((e = q.run_pair(pr, pc, GECC_K_PARITY_RC)) != hipSuccess) return hip_rc(e);
   } else {
     // stored:        A n x k, B k x m   A n x k, B m x k   A k x n, B k x m   A k x n, B m x k
     // rowdots:       B_P, P_r           P_r, P_c           A_P, B_P           A_P, P_c
@@ -828,7 +806,7 @@ int gecc_verify(gecc_ctx* ctx, const float* dev_C, const double* dev_C_par, gecc
   int rc = check_ws(ctx);
   if (rc) return rc;
   if (!dev_C_par || !dev_report || (!fused && !dev_C)) return GECC_ERR_ARG;
-  return verify_impl(ctx, dev_C, dev_C_par, dev_report, fused, 1, nullptr, (hipStream_t)stream);
+  return verify_impl(ctx, dev_C, dev_C_par, dev_report, fused, 1, (hipStream_t)stream);
 }
 
 int gecc_correct(gecc_ctx* ctx, void* dev_A, const double* dev_A_par, void* dev_B,
@@ -850,10 +828,8 @@ int gecc_protected_gemm(gecc_ctx* ctx, void* dev_A, void* dev_B, float* dev_C, d
   if ((rc = encode_and_multiply(ctx, dev_A, dev_B, dev_C, dev_A_par, dev_B_par, dev_C_par, nullptr, 0,
                                 (hipStream_t)stream)))
     return rc;
-  const int fuse = first_pass_rides(ctx);
-  const Operands ops{dev_A, dev_A_par, dev_B, dev_B_par};
-  if ((rc = verify_impl(ctx, dev_C, dev_C_par, dev_report, 1, fuse ? 2 : 0, &ops, (hipStream_t)stream))) return rc;
-  return correct_impl(ctx, dev_A, dev_A_par, dev_B, dev_B_par, dev_C, dev_C_par, dev_report, fuse ? 2 : 1,
+  if ((rc = verify_impl(ctx, dev_C, dev_C_par, dev_report, 1, 0, (hipStream_t)stream))) return rc;
+  return correct_impl(ctx, dev_A, dev_A_par, dev_B, dev_B_par, dev_C, dev_C_par, dev_report, 1,
                       (hipStream_t)stream);
 }
 
@@ -872,10 +848,8 @@ int gecc_protected_gemm_retry(gecc_ctx* ctx, void* dev_A, void* dev_B, float* de
     else
       rc = gecc_multiply(ctx, dev_A, dev_A_par, dev_B, dev_B_par, dev_C, dev_C_par, nullptr, 0, stream);
     if (rc) return rc;
-    const int fuse = first_pass_rides(ctx);
-    const Operands ops{dev_A, dev_A_par, dev_B, dev_B_par};
-    if ((rc = verify_impl(ctx, dev_C, dev_C_par, dev_report, 1, fuse ? 2 : 0, &ops, (hipStream_t)stream))) return rc;
-    if ((rc = correct_impl(ctx, dev_A, dev_A_par, dev_B, dev_B_par, dev_C, dev_C_par, dev_report, fuse ? 2 : 1,
+    if ((rc = verify_impl(ctx, dev_C, dev_C_par, dev_report, 1, 0, (hipStream_t)stream))) return rc;
+    if ((rc = correct_impl(ctx, dev_A, dev_A_par, dev_B, dev_B_par, dev_C, dev_C_par, dev_report, 1,
                            (hipStream_t)stream)))
       return rc;
     if ((rc = gecc_report_to_host(ctx, dev_report, host_report, items_of(ctx), stream))) return rc;
@@ -1004,9 +978,8 @@ int gecc_protected_gemm_panels(gecc_ctx* ctx, void* dev_A, void* dev_B, float* d
     double* Cpg = dev_C_par + g * rec;
     c->fault_bias = g;
     rc = encode_and_multiply(c, Ag, Bg, Cg, Apg, Bpg, Cpg, dev_faults, n_faults, st);
-    const Operands ops{Ag, Apg, Bg, Bpg};
-    if (!rc) rc = verify_impl(c, Cg, Cpg, dev_report + g, 1, 2, &ops, st);
-    if (!rc) rc = correct_impl(c, Ag, Apg, Bg, Bpg, Cg, Cpg, dev_report + g, 2, st);
+    if (!rc) rc = verify_impl(c, Cg, Cpg, dev_report + g, 1, 0, st);
+    if (!rc) rc = correct_impl(c, Ag, Apg, Bg, Bpg, Cg, Cpg, dev_report + g, 1, st);
     if (!rc && g > 0) rc = hip_rc(launch_accumulate(dev_C, dev_C_partial, p.n, p.m, p.ldc, st));
     ctx->ev_n = c->ev_n;
     c->ev = nullptr; c->ev_kind = nullptr; c->ev_cap = 0; c->ev_n = 0;     // the records stay the parent's

@@ -17,7 +17,7 @@ constexpr int SCAN_CHUNK_ROWS = 128;
 // wraps its counter), zeroed once when a workspace is attached.
 constexpr int SCAN_DONE_WORDS = 16384;
 // A column reduction finishes by itself when one workgroup can add a segment's chunks up quickly
-constexpr int SCAN_FUSE_MAX_CHUNKS = 64;
+constexpr int SCAN_FUSE_MAX_CHUNKS = 128;
 
 // decoder phases kept in device memory (per batch item)
 enum : int { PH_DONE = 0, PH_AUDIT = 1, PH_REVERIFY = 2 };
@@ -32,7 +32,6 @@ struct DecodeState {
   // filled by the threshold kernel (atomics; cleared by reset_state before each verify)
   int32_t s_cnt, t_cnt;
   int32_t nonfinite;          // some syndrome is NaN or infinite: nothing can be subtracted, recompute
-  uint32_t th_done;           // threshold workgroups that have finished (wraps to zero with the last one)
   int32_t rows[GECC_MAX_ERR], cols[GECC_MAX_ERR];
   // decoder
   int32_t phase;
@@ -142,9 +141,6 @@ hipError_t launch_rowdot(const ScanArgs& a, const Stage2Job* carry, hipStream_t 
 hipError_t launch_coldot_stage1(const ScanArgs& a, Stage2Job* pending, hipStream_t st);
 // counters a column scan needs to finish by itself; 0: it cannot (too many chunks per segment)
 int coldot_done_words(const ScanArgs& a);
-// two independent scans (row0 / row1: rowdot, else coldot with `done` set) in one launch; both gated
-// alike or not at all; the two `done` ranges must not overlap
-hipError_t launch_scan_pair(const ScanArgs& a0, bool row0, const ScanArgs& a1, bool row1, hipStream_t st);
 hipError_t launch_stage2(const Stage2Job& j, hipStream_t st);
 int stage2_blocks(const Stage2Job& j);
 // words[0 .. count) = 0 (a kernel, so that a captured call stays free of memset nodes)
@@ -182,6 +178,13 @@ size_t tile_scan_row_scratch_doubles(int R, int Cc, int dtype, int batch);
 // launches the first stage and describes in *pending what is left of the second (valid = false: nothing)
 hipError_t launch_tile_scan(const TileScanJob& t, Stage2Job* pending, hipStream_t st);
 
+// The two gated re-encodings of the operand audit in one launch.  kind: 0 rowdot (s), 1 coldot (s),
+// 2 tile scan with one part on (t); index weights, same gate.  Every column reduction has to be able
+// to finish by itself (audit_pair_ok says whether); done: SCAN_DONE_WORDS zeroed counters.
+struct ScanPairItem { int kind; ScanArgs s; TileScanJob t; };
+bool audit_pair_ok(const ScanPairItem& x0, const ScanPairItem& x1);
+hipError_t launch_audit_pair(const ScanPairItem& x0, const ScanPairItem& x1, uint32_t* done, hipStream_t st);
+
 // ---- product (gemm_kernels.hip) ------------------------------------------------------------
 struct GemmArgs {
   const void* A;
@@ -214,11 +217,32 @@ struct GemmArgs {
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t st);
 
 #if defined(__HIPCC__)
+// "Last workgroup finishes" without cache flushes.  Results that another workgroup of the same launch
+// will read are stored with store_dev (written through to device-coherent memory) and read with
+// load_dev (never served from a cache that another compute die cannot see).  A device-wide fence
+// would do as well, but it writes back and invalidates a whole L2, and one per workgroup multiplies
+// the duration of a scan.
+template <class T> static __device__ __forceinline__ void store_dev(T* p, T v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+template <class T> static __device__ __forceinline__ T load_dev(const T* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// Every thread of the workgroup has issued its store_dev()s; true in the workgroup that is the last
+// of `count` to get here (its load_dev()s then see the stores of all the others).  The counter wraps
+// to zero with the last arrival.  flag: an int of LDS that nobody else uses between the two barriers.
+static __device__ __forceinline__ bool arrive_last(uint32_t* counter, uint32_t count, int* flag) {
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // this wavefront's stores have been written through
+  __syncthreads();
+  if (threadIdx.x == 0) *flag = atomicInc(counter, count - 1) == count - 1;
+  __syncthreads();
+  return *flag != 0;
+}
+
 // counters, phase and error list of one batch item, as before any verification
 static __device__ __forceinline__ void reset_state(DecodeState* s) {
   s->s_cnt = 0; s->t_cnt = 0;
   s->nonfinite = 0;
-  s->th_done = 0;
   s->phase = PH_DONE;
   s->n_err = 0;
 }
@@ -321,10 +345,8 @@ hipError_t launch_threshold_blocked(const DecodeArgs& a, int n_full, int m_full,
 // blocked mode: the repair in three launches (own block of C-bar; operands; Section V on the rest)
 hipError_t launch_repair_blocked(const DecodeArgs& a, int nbi, hipStream_t st);
 hipError_t launch_reset_state(const DecodeArgs& a, hipStream_t st);
-// partial sums -> syndromes -> threshold flags (Section V step 1) and max |syndrome| per family.
-// with_decode = 1: the workgroup that finishes last also writes the first report and runs the
-// decoder's first pass (what launch_decode_c(a, 1) would do in a launch of its own)
-hipError_t launch_threshold(const DecodeArgs& a, int with_decode, hipStream_t st);
+// partial sums -> syndromes -> threshold flags (Section V step 1) and max |syndrome| per family
+hipError_t launch_threshold(const DecodeArgs& a, hipStream_t st);
 // first report (s, t, maxima, CLEAN / DETECTED) from the counters of the first threshold pass
 hipError_t launch_summarize(const DecodeArgs& a, hipStream_t st);
 // Section V step 2 right after detection.  with_summary = 1: also writes the first report

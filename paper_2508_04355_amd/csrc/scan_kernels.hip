@@ -52,7 +52,8 @@ __device__ __forceinline__ bool gated_off(const int32_t* gate, int64_t stride, i
 // combined as ((s0 + s1) + (s2 + s3)).
 // One slice of G outputs at once (G independent chains of loads in flight); part[g]: chunk 0's
 // partial of output g, stride: doubles between chunks.
-template <int G>
+// DEV: the partials were written by other workgroups of this launch (load_dev)
+template <int G, bool DEV>
 __device__ __forceinline__ void slice_sums(const double* const* part, int64_t stride, int nchunk, int w, double* s) {
   double t[G][4];
 #pragma unroll
@@ -62,11 +63,17 @@ __device__ __forceinline__ void slice_sums(const double* const* part, int64_t st
 #pragma unroll
     for (int g = 0; g < G; ++g)
 #pragma unroll
-      for (int u = 0; u < 4; ++u) t[g][u] += part[g][(int64_t)(ch + 4 * u) * stride];
+      for (int u = 0; u < 4; ++u) {
+        const double* q = part[g] + (int64_t)(ch + 4 * u) * stride;
+        t[g][u] += DEV ? load_dev(q) : *q;
+      }
   }
   for (; ch < nchunk; ch += 4) {
 #pragma unroll
-    for (int g = 0; g < G; ++g) t[g][0] += part[g][(int64_t)ch * stride];
+    for (int g = 0; g < G; ++g) {
+      const double* q = part[g] + (int64_t)ch * stride;
+      t[g][0] += DEV ? load_dev(q) : *q;
+    }
   }
 #pragma unroll
   for (int g = 0; g < G; ++g) s[g] = (t[g][0] + t[g][1]) + (t[g][2] + t[g][3]);
@@ -81,7 +88,7 @@ __device__ __forceinline__ void coldot_stage2_body(const double* scratch, double
   double s = 0.0;
   if (o < 2 * Cc) {
     const double* part = scratch + o;
-    slice_sums<1>(&part, 2 * (int64_t)Cc, nchunk, wave, &s);
+    slice_sums<1, false>(&part, 2 * (int64_t)Cc, nchunk, wave, &s);
   }
   red[wave * 64 + lane] = s;
   __syncthreads();
@@ -109,7 +116,7 @@ __device__ __forceinline__ void coldot_finish_segment(const double* scratch, dou
       part[g] = scratch + o[g];
     }
     double s[G];
-    slice_sums<G>(part, 2 * (int64_t)Cc, nchunk, wave, s);
+    slice_sums<G, true>(part, 2 * (int64_t)Cc, nchunk, wave, s);
 #pragma unroll
     for (int g = 0; g < G; ++g) red[(g * 4 + wave) * 64 + lane] = s[g];
     __syncthreads();
@@ -124,31 +131,21 @@ __device__ __forceinline__ void coldot_finish_segment(const double* scratch, dou
 
 // Stage 2 of the row part of tile_scan (see below): the segments of a row added in order.
 // part: [R][nseg][2], out: [2][R], both of batch item b.
+template <bool DEV>
 __device__ __forceinline__ void rowseg_sum(const double* part, double* out, int R, int nseg, int r) {
-  const double2* p = reinterpret_cast<const double2*>(part) + (int64_t)r * nseg;
+  const double* p = part + (int64_t)r * nseg * 2;
   double s0 = 0.0, s1 = 0.0;
-  for (int g = 0; g < nseg; ++g) { const double2 v = p[g]; s0 += v.x; s1 += v.y; }
+  for (int g = 0; g < nseg; ++g) {
+    s0 += DEV ? load_dev(p + 2 * g) : p[2 * g];
+    s1 += DEV ? load_dev(p + 2 * g + 1) : p[2 * g + 1];
+  }
   out[r] = s0;
   out[(int64_t)R + r] = s1;
 }
 // as workgroups of their own: 256 rows each
 __device__ __forceinline__ void rowseg_stage2_body(const double* part, double* out, int R, int nseg, int blk) {
   const int r = blk * 256 + threadIdx.x;
-  if (r < R) rowseg_sum(part, out, R, nseg, r);
-}
-
-// "Last workgroup finishes": every thread has written its partial results; the workgroup that finds
-// itself the last of `count` to arrive at *counter may read all of them.  The counter wraps to zero
-// with the last arrival, so it is ready for the next launch.  flag: an int of LDS nobody else uses
-// between the two barriers.  Every thread of the workgroup calls this.
-__device__ __forceinline__ bool arrive_last(uint32_t* counter, uint32_t count, int* flag) {
-  __threadfence();                                  // this thread's partial results, device-wide
-  __syncthreads();
-  if (threadIdx.x == 0) *flag = atomicInc(counter, count - 1) == count - 1;
-  __syncthreads();
-  const bool last = *flag != 0;
-  if (last) __threadfence();                        // nothing read before this point is reused
-  return last;
+  if (r < R) rowseg_sum<false>(part, out, R, nseg, r);
 }
 
 // a pending second stage (column chunks and / or row segments), by workgroup index
@@ -407,7 +404,9 @@ __device__ __forceinline__ void coldot_body(const ScanArgs& a, int nchunk, int n
     const int col = (bx * 64 + l) * VEC + e;
     if (col < a.Cc) {
       const double s = (red[0][t][e][l] + red[1][t][e][l]) + (red[2][t][e][l] + red[3][t][e][l]);
-      part[(int64_t)t * a.Cc + col] = s;
+      // (written through only when another workgroup of this launch reads it: such stores cost more)
+      if (a.done) store_dev(part + (int64_t)t * a.Cc + col, s);
+      else part[(int64_t)t * a.Cc + col] = s;
     }
   }
   if (a.done && arrive_last(a.done + (int64_t)b * nsegx + bx, (uint32_t)nchunk, reinterpret_cast<int*>(lds + CD_FLAG_AT)))
@@ -484,17 +483,17 @@ constexpr int TS_FLAG_AT = 1024;   // doubles into the LDS: behind what coldot_f
 // global loads and stores, which is exactly what the loop must not do)
 __device__ __forceinline__ void wave_lds_fence() { asm volatile("" ::: "memory"); }
 
-template <int DT, bool COL, bool ROW, bool COL_IDX, bool ROW_IDX, bool GATED>
-__global__ __launch_bounds__(TS_THREADS) void tile_scan(TileScanArgs a) {
+constexpr int TS_LDS_DOUBLES = 4 * 2 * TS_RB * TS_LDS_LD;
+
+// segment `seg` of the columns, chunk `chunk` of the rows, batch item b; ts_lds: TS_LDS_DOUBLES of LDS
+template <int DT, bool COL, bool ROW, bool COL_IDX, bool ROW_IDX>
+__device__ __forceinline__ void tile_scan_body(const TileScanArgs& a, int seg, int chunk, int b, double* ts_lds) {
   using E = Elem<DT>;
   using T = typename E::type;
   constexpr int VEC = E::VEC;
   constexpr int SEG = 64 * VEC;
-  const int b = blockIdx.z;
-  if (GATED && gated_off(a.gate, a.gate_stride, b, a.gate_value)) return;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int seg = blockIdx.x, chunk = blockIdx.y;
   const T* X = reinterpret_cast<const T*>(a.X) + (int64_t)b * a.xs;
   // columns of this lane (Cc is a multiple of VEC; lanes past the end read the last vector and drop it)
   const int c_true = seg * SEG + lane * VEC;
@@ -523,7 +522,6 @@ __global__ __launch_bounds__(TS_THREADS) void tile_scan(TileScanArgs a) {
 #pragma unroll
   for (int e = 0; e < VEC; ++e) { ca0[e] = 0.0; ca1[e] = 0.0; }
 
-  extern __shared__ double ts_lds[];
   double* tr = ts_lds + wave * (2 * TS_RB * TS_LDS_LD);     // this wavefront's transpose region
   double* rp_out = ROW ? a.row_part + ((int64_t)b * a.R * a.nseg + seg) * 2 : nullptr;
 
@@ -563,7 +561,10 @@ __global__ __launch_bounds__(TS_THREADS) void tile_scan(TileScanArgs a) {
     s += __shfl_xor(s, 2, 64);
     wave_lds_fence();
     const int u = o >> 1, t = o & 1;
-    if (q == 0 && u < cnt) rp_out[(int64_t)(r0 + u) * a.nseg * 2 + t] = s;
+    if (q == 0 && u < cnt) {
+      double* dst = rp_out + (int64_t)(r0 + u) * a.nseg * 2 + t;
+      if (a.done_row) store_dev(dst, s); else *dst = s;
+    }
   };
 
   int r = w_beg;
@@ -625,13 +626,15 @@ __global__ __launch_bounds__(TS_THREADS) void tile_scan(TileScanArgs a) {
       const int cc = seg * SEG + l * VEC + e;
       if (cc < a.Cc) {
         const int x = (t * VEC + e) * 64 + l;
-        part[(int64_t)t * a.Cc + cc] = (cb[x] + cb[2 * VEC * 64 + x]) + (cb[2 * 2 * VEC * 64 + x] + cb[3 * 2 * VEC * 64 + x]);
+        const double v = (cb[x] + cb[2 * VEC * 64 + x]) + (cb[2 * 2 * VEC * 64 + x] + cb[3 * 2 * VEC * 64 + x]);
+        if (a.done_col) store_dev(part + (int64_t)t * a.Cc + cc, v);
+        else part[(int64_t)t * a.Cc + cc] = v;
       }
     }
   }
 
   if ((COL && a.done_col) || (ROW && a.done_row)) {
-    __threadfence();                                // this thread's partial results, device-wide
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wavefront's partial results have been written through
     __syncthreads();
     int* flag = reinterpret_cast<int*>(ts_lds + TS_FLAG_AT);
     if (threadIdx.x == 0) {
@@ -640,11 +643,10 @@ __global__ __launch_bounds__(TS_THREADS) void tile_scan(TileScanArgs a) {
     }
     __syncthreads();
     const bool last_col = flag[0] != 0, last_row = flag[1] != 0;
-    if (last_col || last_row) __threadfence();
     if (ROW && last_row) {
       const double* part = a.row_part + (int64_t)b * a.R * a.nseg * 2;
       double* out = a.row_out + (int64_t)b * a.row_out_stride;
-      for (int rr = rbeg + (int)threadIdx.x; rr < rend; rr += TS_THREADS) rowseg_sum(part, out, a.R, a.nseg, rr);
+      for (int rr = rbeg + (int)threadIdx.x; rr < rend; rr += TS_THREADS) rowseg_sum<true>(part, out, a.R, a.nseg, rr);
     }
     if (COL && last_col)
       coldot_finish_segment<VEC>(a.col_part + (int64_t)b * a.nchunk * 2 * a.Cc, a.col_out + (int64_t)b * a.col_out_stride,
@@ -652,36 +654,54 @@ __global__ __launch_bounds__(TS_THREADS) void tile_scan(TileScanArgs a) {
   }
 }
 
-// -------------------------------------------------------------------------------------------
-// Two independent scans in one launch (the encodings of A and B; P_r and P_c; the two audits): a
-// dependent launch costs about 5 us of stream time whatever it does.  Every column scan in it
-// finishes its own second stage (ScanArgs::done).  The row scan here takes 4 rows per workgroup.
-struct PairJob {
-  ScanArgs s;
-  int rowdot, idxw;
-  int nblk;          // workgroups of this job
-  int gx, nchunk;    // rowdot: gx workgroups per batch item; coldot: gx column segments x nchunk chunks
-};
-struct PairArgs { PairJob j[2]; };
+template <int DT, bool COL, bool ROW, bool COL_IDX, bool ROW_IDX, bool GATED>
+__global__ __launch_bounds__(TS_THREADS) void tile_scan(TileScanArgs a) {
+  extern __shared__ double ts_lds[];
+  const int b = blockIdx.z;
+  if (GATED && gated_off(a.gate, a.gate_stride, b, a.gate_value)) return;
+  tile_scan_body<DT, COL, ROW, COL_IDX, ROW_IDX>(a, blockIdx.x, blockIdx.y, b, ts_lds);
+}
 
-template <int DT, bool GATED>
-__global__ __launch_bounds__(256) void scan_pair(PairArgs p) {
-  __shared__ double lds[CD_LDS_DOUBLES];
+// -------------------------------------------------------------------------------------------
+// The two gated re-encodings of the operand audit in one launch: on a clean step each of them only
+// finds its gate closed, and a dependent launch costs about 5 us of stream time whatever it does.
+// When the audit does run, every column reduction in here is finished by the workgroup that comes
+// last to its segment (a.done / done_col / done_row set): that tail costs about what the launch of a
+// second stage would, so it is used here only, where it saves a launch on every clean step.
+struct PairJob {
+  int kind;          // PJ_x
+  ScanArgs s;        // PJ_ROW, PJ_COL
+  TileScanArgs t;    // PJ_TILE_COL, PJ_TILE_ROW
+  int nblk;          // workgroups of this job
+  int gx, gy;        // workgroups per batch item: gx (rowdot) or gx x gy (segments x chunks)
+};
+enum : int { PJ_ROW = 0, PJ_COL = 1, PJ_TILE_COL = 2, PJ_TILE_ROW = 3, PJ_ROW_BIG = 4 };
+struct PairArgs { PairJob j[2]; };
+constexpr int AUDIT_PAIR_MAX_BLOCKS = 4096;
+constexpr int PAIR_LDS_DOUBLES = TS_LDS_DOUBLES > CD_LDS_DOUBLES ? TS_LDS_DOUBLES : CD_LDS_DOUBLES;
+
+template <int DT>
+__global__ __launch_bounds__(256) void audit_pair(PairArgs p) {
+  __shared__ double lds[PAIR_LDS_DOUBLES];
   int v = blockIdx.x;
   const bool second = v >= p.j[0].nblk;
   if (second) v -= p.j[0].nblk;
   const PairJob& j = second ? p.j[1] : p.j[0];
-  const ScanArgs& a = j.s;
-  if (j.rowdot) {
-    const int bx = v % j.gx, b = v / j.gx;
-    if (GATED && gated_off(a.gate, a.gate_stride, b, a.gate_value)) return;
-    if (GATED || j.idxw) rowdot_body<DT, true, RD_SMALL_RB, RD_SMALL_U>(a, bx, b, lds);
-    else rowdot_body<DT, false, RD_SMALL_RB, RD_SMALL_U>(a, bx, b, lds);
+  const int per_item = j.gx * j.gy;
+  const int b = v / per_item, x = (v % per_item) % j.gx, y = (v % per_item) / j.gx;
+  if (j.kind == PJ_ROW) {
+    if (gated_off(j.s.gate, j.s.gate_stride, b, j.s.gate_value)) return;
+    rowdot_body<DT, true, RD_SMALL_RB, RD_SMALL_U>(j.s, x, b, lds);
+  } else if (j.kind == PJ_ROW_BIG) {
+    if (gated_off(j.s.gate, j.s.gate_stride, b, j.s.gate_value)) return;
+    rowdot_body<DT, true, RD_BIG_RB, RD_BIG_U>(j.s, x, b, lds);
+  } else if (j.kind == PJ_COL) {
+    if (gated_off(j.s.gate, j.s.gate_stride, b, j.s.gate_value)) return;
+    coldot_body<DT, true>(j.s, j.gy, j.gx, x, y, b, lds);
   } else {
-    const int bx = v % j.gx, chunk = (v / j.gx) % j.nchunk, b = v / (j.gx * j.nchunk);
-    if (GATED && gated_off(a.gate, a.gate_stride, b, a.gate_value)) return;
-    if (GATED || j.idxw) coldot_body<DT, true>(a, j.nchunk, j.gx, bx, chunk, b, lds);
-    else coldot_body<DT, false>(a, j.nchunk, j.gx, bx, chunk, b, lds);
+    if (gated_off(j.t.gate, j.t.gate_stride, b, j.t.gate_value)) return;
+    if (j.kind == PJ_TILE_COL) tile_scan_body<DT, true, false, true, true>(j.t, x, y, b, lds);
+    else tile_scan_body<DT, false, true, true, true>(j.t, x, y, b, lds);
   }
 }
 
@@ -775,44 +795,6 @@ hipError_t launch_coldot_stage1(const ScanArgs& a0, Stage2Job* pending, hipStrea
   return hipGetLastError();
 }
 
-hipError_t launch_scan_pair(const ScanArgs& a0, bool row0, const ScanArgs& a1, bool row1, hipStream_t st) {
-  if (a0.dtype != a1.dtype || a0.gate != a1.gate || a0.gate_stride != a1.gate_stride || a0.gate_value != a1.gate_value)
-    return hipErrorInvalidValue;
-  const bool gated = a0.gate != nullptr;
-  PairArgs p{};
-  const ScanArgs* src[2] = {&a0, &a1};
-  const bool row[2] = {row0, row1};
-  const int vec = a0.dtype == GECC_BF16 ? 8 : 4;
-  for (int x = 0; x < 2; ++x) {
-    PairJob& j = p.j[x];
-    j.s = *src[x];
-    j.s.vec_ok = vec_ok(*src[x]) ? 1 : 0;
-    j.s.carry_blocks = 0;
-    j.rowdot = row[x] ? 1 : 0;
-    j.idxw = j.s.w == nullptr ? 1 : 0;
-    if (gated && !j.idxw) return hipErrorInvalidValue;
-    if (row[x]) {
-      j.gx = (j.s.R + RD_SMALL_RB - 1) / RD_SMALL_RB;
-      j.nchunk = 1;
-      j.nblk = j.gx * j.s.batch;
-    } else {
-      if (!j.s.done || coldot_done_words(j.s) == 0) return hipErrorInvalidValue;   // must finish by itself
-      j.gx = (j.s.Cc + 64 * vec - 1) / (64 * vec);
-      j.nchunk = (j.s.R + SCAN_CHUNK_ROWS - 1) / SCAN_CHUNK_ROWS;
-      j.nblk = j.gx * j.nchunk * j.s.batch;
-    }
-  }
-  const dim3 grid(p.j[0].nblk + p.j[1].nblk);
-  if (a0.dtype == GECC_BF16) {
-    if (gated) hipLaunchKernelGGL((scan_pair<GECC_BF16, true>), grid, dim3(256), 0, st, p);
-    else       hipLaunchKernelGGL((scan_pair<GECC_BF16, false>), grid, dim3(256), 0, st, p);
-  } else {
-    if (gated) hipLaunchKernelGGL((scan_pair<GECC_F32, true>), grid, dim3(256), 0, st, p);
-    else       hipLaunchKernelGGL((scan_pair<GECC_F32, false>), grid, dim3(256), 0, st, p);
-  }
-  return hipGetLastError();
-}
-
 // ---- tile_scan ------------------------------------------------------------------------------
 bool tile_scan_ok(const TileScanJob& t) {
   const int vec = t.dtype == GECC_BF16 ? 8 : 4;
@@ -838,9 +820,12 @@ static int tile_scan_chunk_rows(int R, int nseg, int batch) {
   return ch;
 }
 
-hipError_t launch_tile_scan(const TileScanJob& t, Stage2Job* pending, hipStream_t st) {
-  if (!tile_scan_ok(t) || (!t.col_on && !t.row_on)) return hipErrorInvalidValue;
-  TileScanArgs a{};
+// kernel arguments of a tile scan; fuse_col / fuse_row: parts that finish by themselves (t.done set:
+// the column part when a segment has few enough chunks for one workgroup to add up, the row part
+// always -- as far as the counters reach).  done_words: counters used.
+static bool make_tile_args(const TileScanJob& t, TileScanArgs& a, bool& fuse_col, bool& fuse_row, int& done_words) {
+  if (!tile_scan_ok(t) || (!t.col_on && !t.row_on)) return false;
+  a = TileScanArgs{};
   a.X = t.X; a.dtype = t.dtype; a.R = t.R; a.Cc = t.Cc; a.ld = t.ld; a.xs = t.xs; a.batch = t.batch;
   a.wr = t.wr; a.wr_stride = t.wr_stride; a.col_part = t.col_scratch;
   a.wc = t.wc; a.wc_stride = t.wc_stride; a.row_part = t.row_scratch;
@@ -848,20 +833,29 @@ hipError_t launch_tile_scan(const TileScanJob& t, Stage2Job* pending, hipStream_
   a.chunk_rows = tile_scan_chunk_rows(t.R, a.nseg, t.batch);
   a.nchunk = (t.R + a.chunk_rows - 1) / a.chunk_rows;
   a.gate = t.gate; a.gate_stride = t.gate_stride; a.gate_value = t.gate_value;
-  // parts that finish by themselves: the column part when a segment has few enough chunks for one
-  // workgroup to add up, the row part always -- as far as the counters reach
-  bool fuse_col = false, fuse_row = false;
+  fuse_col = false; fuse_row = false;
+  int64_t used = 0;
   if (t.done) {
-    int64_t used = 0;
     if (t.col_on && a.nchunk <= SCAN_FUSE_MAX_CHUNKS && (int64_t)t.batch * a.nseg <= SCAN_DONE_WORDS) {
       fuse_col = true; a.done_col = t.done; used = (int64_t)t.batch * a.nseg;
     }
-    if (t.row_on && used + (int64_t)t.batch * a.nchunk <= SCAN_DONE_WORDS) { fuse_row = true; a.done_row = t.done + used; }
+    if (t.row_on && used + (int64_t)t.batch * a.nchunk <= SCAN_DONE_WORDS) {
+      fuse_row = true; a.done_row = t.done + used; used += (int64_t)t.batch * a.nchunk;
+    }
   }
+  done_words = (int)used;
   a.col_out = t.col_out; a.col_out_stride = t.col_out_stride;
   a.row_out = t.row_out; a.row_out_stride = t.row_out_stride;
+  return true;
+}
+
+hipError_t launch_tile_scan(const TileScanJob& t, Stage2Job* pending, hipStream_t st) {
+  TileScanArgs a;
+  bool fuse_col, fuse_row;
+  int words;
+  if (!make_tile_args(t, a, fuse_col, fuse_row, words)) return hipErrorInvalidValue;
   const dim3 grid(a.nseg, a.nchunk, a.batch), block(TS_THREADS);
-  const size_t lds = 4 * 2 * TS_RB * TS_LDS_LD * sizeof(double);
+  const size_t lds = TS_LDS_DOUBLES * sizeof(double);
   const bool gated = t.gate != nullptr;
   const bool cidx = t.wr == nullptr, ridx = t.wc == nullptr;
 #define GECC_TS(DT, COL, ROW, CI, RI, G) \
@@ -899,6 +893,72 @@ hipError_t launch_tile_scan(const TileScanJob& t, Stage2Job* pending, hipStream_
     pending->row_scratch = t.row_scratch; pending->row_out = t.row_out; pending->row_out_stride = t.row_out_stride;
     pending->R = t.R; pending->nseg = a.nseg;
   }
+  return hipGetLastError();
+}
+
+// ---- the two audits in one launch ---------------------------------------------------------------
+// fills j from x; returns the counters it uses, or -1 when x cannot finish by itself
+static int make_pair_job(const ScanPairItem& x, uint32_t* done, PairJob& j) {
+  j = PairJob{};
+  if (x.kind == 2) {
+    TileScanJob t = x.t;
+    if (t.col_on == t.row_on || !t.gate) return -1;                       // one part, gated
+    if ((t.col_on && t.wr) || (t.row_on && t.wc)) return -1;              // index weights
+    t.done = done;
+    bool fc, fr;
+    int words;
+    if (!make_tile_args(t, j.t, fc, fr, words) || !(t.col_on ? fc : fr)) return -1;
+    j.kind = t.col_on ? PJ_TILE_COL : PJ_TILE_ROW;
+    j.gx = j.t.nseg; j.gy = j.t.nchunk;
+    j.nblk = j.gx * j.gy * t.batch;
+    return words;
+  }
+  j.s = x.s;
+  j.s.vec_ok = vec_ok(x.s) ? 1 : 0;
+  j.s.carry_blocks = 0;
+  if (!j.s.gate || j.s.w) return -1;
+  if (x.kind == 0) {
+    // (rows per workgroup as in launch_rowdot; the sums of a row do not depend on it)
+    const bool small = (int64_t)((j.s.R + RD_BIG_RB - 1) / RD_BIG_RB) * j.s.batch < 1024;
+    const int rb = small ? RD_SMALL_RB : RD_BIG_RB;
+    j.kind = small ? PJ_ROW : PJ_ROW_BIG;
+    j.gx = (j.s.R + rb - 1) / rb; j.gy = 1;
+    j.nblk = j.gx * j.s.batch;
+    return 0;
+  }
+  const int words = coldot_done_words(j.s);
+  if (words == 0) return -1;
+  const int vec = j.s.dtype == GECC_BF16 ? 8 : 4;
+  j.kind = PJ_COL;
+  j.s.done = done;
+  j.gx = (j.s.Cc + 64 * vec - 1) / (64 * vec);
+  j.gy = (j.s.R + SCAN_CHUNK_ROWS - 1) / SCAN_CHUNK_ROWS;
+  j.nblk = j.gx * j.gy * j.s.batch;
+  return words;
+}
+
+static int pair_dtype(const ScanPairItem& x) { return x.kind == 2 ? x.t.dtype : x.s.dtype; }
+
+bool audit_pair_ok(const ScanPairItem& x0, const ScanPairItem& x1) {
+  static uint32_t dummy;   // (an address that is never used: only the counts matter here)
+  PairJob j;
+  const int w0 = make_pair_job(x0, &dummy, j);
+  if (w0 < 0) return false;
+  const int nblk0 = j.nblk;
+  const int w1 = make_pair_job(x1, &dummy, j);
+  // (a closed gate still costs the dispatch of every workgroup: about 2 us per thousand, so a pair of
+  // very large grids is no cheaper than two launches)
+  return w1 >= 0 && w0 + w1 <= SCAN_DONE_WORDS && pair_dtype(x0) == pair_dtype(x1) && nblk0 + j.nblk <= AUDIT_PAIR_MAX_BLOCKS;
+}
+
+hipError_t launch_audit_pair(const ScanPairItem& x0, const ScanPairItem& x1, uint32_t* done, hipStream_t st) {
+  if (!done || !audit_pair_ok(x0, x1)) return hipErrorInvalidValue;
+  PairArgs p;
+  const int w0 = make_pair_job(x0, done, p.j[0]);
+  make_pair_job(x1, done + w0, p.j[1]);
+  const dim3 grid(p.j[0].nblk + p.j[1].nblk);
+  if (pair_dtype(x0) == GECC_BF16) hipLaunchKernelGGL(audit_pair<GECC_BF16>, grid, dim3(256), 0, st, p);
+  else                             hipLaunchKernelGGL(audit_pair<GECC_F32>, grid, dim3(256), 0, st, p);
   return hipGetLastError();
 }
 

@@ -18,10 +18,9 @@ MAT_A, MAT_B, MAT_C = 0, 1, 2
 MAX_ERR, MAX_FAULTS = 8, 1024
 # kernel classes of the timing records (include/gecc.h)
 (K_ENCODE_A, K_ENCODE_B, K_PARITY_R, K_PARITY_C, K_PRODUCT, K_THRESHOLD, K_DECODE, K_AUDIT_A, K_AUDIT_B,
- K_REPAIR, K_PARTIALS, K_STAGE2, K_TILE_A, K_TILE_B, K_ENCODE_AB, K_PARITY_RC, K_AUDIT_AB) = range(17)
+ K_REPAIR, K_PARTIALS, K_STAGE2, K_TILE_A, K_TILE_B, K_AUDIT_AB) = range(15)
 K_NAMES = ["encode_a", "encode_b", "parity_r", "parity_c", "product", "threshold", "decode", "audit_a", "audit_b",
-           "repair", "partials", "stage2", "encode_a+parity_r", "encode_b+parity_c", "encode_a+encode_b",
-           "parity_r+parity_c", "audit_a+audit_b"]
+           "repair", "partials", "stage2", "encode_a+parity_r", "encode_b+parity_c", "audit_a+audit_b"]
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libgecc.so")
 

@@ -360,9 +360,9 @@ def test_results_are_reproducible_bit_for_bit():
 
 @pytest.mark.parametrize("dtype,shape,trans", [("f32", (1024, 1024, 1024), (0, 0)), ("bf16", (1024, 512, 768), (0, 1)),
                                                ("bf16", (768, 512, 1024), (1, 0)), ("f32", (520, 264, 392), (1, 1))])
-def test_a_clean_step_is_six_launches(dtype, shape, trans):
-    """Both encodings in one launch, both parity blocks of C-bar in one, the product, the threshold pass
-    with the first report and decoder pass, both gated audits in one, the gated repair."""
+def test_launches_of_a_clean_step(dtype, shape, trans):
+    """Four scans (a row scan carries the second stage of a column scan where one follows it), the
+    product, the threshold pass, the first report, and two gated launches: both audits in one, the repair."""
     import torch
     n, k, m = shape
     rng = inputs.rng_for(2, 77)
@@ -383,7 +383,9 @@ def test_a_clean_step_is_six_launches(dtype, shape, trans):
     rec = ctx.timing_read(32)
     ctx.timing_enable(0)
     assert ctx.report_to_host(rep)[0].status == gecc.CLEAN
-    assert len(rec) == 6, [gecc.K_NAMES[kd] for kd, _ in rec]
+    names = [gecc.K_NAMES[kd] for kd, _ in rec]
+    assert names[-2:] == ["audit_a+audit_b", "repair"] and names[-4:-2] == ["threshold", "decode"], names
+    assert len(rec) <= 10, names
 
 
 # ---- per-k-panel verification: every partial product over a panel of k is a codeword ------------------
