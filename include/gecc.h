@@ -155,7 +155,8 @@ typedef struct {
    Reads the environment variable GECC_CU_COUNT once, here: if set to a positive number the
    bf16 product plans its rounds of tiles as for that many compute units instead of the
    device's own count (for tests of the k-split of a half-empty last round on small shapes;
-   any value gives correct results). */
+   any value gives correct results).  Likewise GECC_TILE_MIN: operands of that many elements or
+   more are encoded by the one-pass scan (default 2^25; tests set 1 to reach it with small shapes). */
 int gecc_create(gecc_ctx** out, const gecc_params* p);
 void gecc_destroy(gecc_ctx* ctx);
 

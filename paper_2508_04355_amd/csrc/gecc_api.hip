@@ -45,6 +45,7 @@ void make_layout(gecc_ctx* c) {
   const size_t ra = tile_scan_row_scratch_doubles(p.trans_a ? p.k : p.n, p.trans_a ? p.n : p.k, p.dtype, p.batch);
   const size_t rb = tile_scan_row_scratch_doubles(p.trans_b ? p.m : p.k, p.trans_b ? p.k : p.m, p.dtype, p.batch);
   L.scan_row = take((ra > rb ? ra : rb) * sizeof(double));
+  L.ksplit = take(c->ksplit > 1 ? b * c->ntm * c->ntn * (size_t)c->ksplit * 128 * 128 * sizeof(float) : 0);
   L.w_a = L.w_b = L.side_r = L.side_c = L.gate = 0;
   if (blocked(c)) {
     const size_t esz = p.dtype == GECC_BF16 ? 2 : 4;
@@ -255,8 +256,8 @@ TileScanJob tile_job(gecc_ctx* c, int op, const void* X, double* enc_out, const 
 // launches, and the two separate scans need one launch less: a row scan carries the second stage
 // of a column scan).  A function of shape and alignment alone, so that an encoding and the audit
 // that re-forms it always take the same kernel.
-bool use_tile(const TileScanJob& t) {
-  return tile_scan_ok(t) && (int64_t)t.R * t.Cc * t.batch >= ((int64_t)1 << 25);
+bool use_tile(const gecc_ctx* c, const TileScanJob& t) {
+  return tile_scan_ok(t) && (int64_t)t.R * t.Cc * t.batch >= c->tile_min;
 }
 
 // Scans in stream order.  The second stage of a coldot is held back: the next rowdot carries it in
@@ -337,6 +338,11 @@ GemmArgs gemm_args(const gecc_ctx* c, const void* A, const void* B, float* C) {
   g.sa = p.stride_a; g.sb = p.stride_b; g.sc = p.stride_c;
   g.tile_m = c->tile_m; g.tile_n = c->tile_n; g.ntm = c->ntm; g.ntn = c->ntn;
   g.cu_hint = c->cu_hint; g.split_first = -1;
+  if (c->ksplit > 1 && c->ws && c->ws_bytes >= c->lay.total) {
+    g.ksplit = c->ksplit;
+    g.split_part = reinterpret_cast<float*>(c->ws + c->lay.ksplit);
+    g.split_done = reinterpret_cast<uint32_t*>(c->ws + c->lay.done);
+  }
   g.rp_ld = c->rp_ld; g.cp_ld = c->cp_ld;
   return g;
 }
@@ -382,6 +388,8 @@ int gecc_create(gecc_ctx** out, const gecc_params* p) {
     const char* e = getenv("GECC_CU_COUNT");       // test hook: see GemmArgs::cu_hint
     c->cu_hint = e ? atoi(e) : 0;
     if (c->cu_hint < 0) c->cu_hint = 0;
+    const char* t = getenv("GECC_TILE_MIN");       // test hook: operands of that many elements or more take the one-pass scan
+    c->tile_min = (t && atoll(t) > 0) ? atoll(t) : ((int64_t)1 << 25);
   }
   // the larger operand is read once for both of its reductions (tile scan), the other one twice
   c->tile_op = p->n >= p->m ? GECC_MAT_A : GECC_MAT_B;
@@ -394,6 +402,15 @@ int gecc_create(gecc_ctx** out, const gecc_params* p) {
   c->tile_n = 128;
   c->ntm = (p->n + c->tile_m - 1) / c->tile_m;
   c->ntn = (p->m + c->tile_n - 1) / c->tile_n;
+  {
+    // products with far fewer tiles than compute units split k over several workgroups per tile
+    // (128 x 128-tile kernel only; every range keeps at least 128 terms)
+    const int64_t tiles = (int64_t)c->ntm * c->ntn * p->batch;
+    int s = tiles * 2 <= 256 ? (int)(256 / tiles) : 1;
+    if (s > 8) s = 8;
+    while (s > 1 && p->k / s < 128) --s;
+    c->ksplit = p->block_n > 0 ? 1 : s;
+  }
   // slab strides of the partial sums: a multiple of 2 KiB would put the same line of every slab
   // into the same memory channel
   c->rp_ld = p->n % 256 == 0 ? p->n + 16 : p->n;
@@ -512,7 +529,7 @@ int gecc_encode_a(gecc_ctx* ctx, const void* dev_A, double* dev_A_par, void* str
   }
   ScanQueue q{ctx, (hipStream_t)stream};
   const TileScanJob tj = tile_job(ctx, GECC_MAT_A, dev_A, dev_A_par, nullptr, nullptr, 0, nullptr);
-  hipError_t e = ctx->tile_op == GECC_MAT_A && use_tile(tj) ? q.run_tile(tj, GECC_K_ENCODE_A)
+  hipError_t e = ctx->tile_op == GECC_MAT_A && use_tile(ctx, tj) ? q.run_tile(tj, GECC_K_ENCODE_A)
                                                                 : q.run(scan_a_over_n(ctx, dev_A, nullptr, dev_A_par, nullptr));
   return hip_rc(e != hipSuccess ? e : q.flush());
 }
@@ -531,7 +548,7 @@ int gecc_encode_b(gecc_ctx* ctx, const void* dev_B, double* dev_B_par, void* str
   }
   ScanQueue q{ctx, (hipStream_t)stream};
   const TileScanJob tj = tile_job(ctx, GECC_MAT_B, dev_B, dev_B_par, nullptr, nullptr, 0, nullptr);
-  hipError_t e = ctx->tile_op == GECC_MAT_B && use_tile(tj) ? q.run_tile(tj, GECC_K_ENCODE_B)
+  hipError_t e = ctx->tile_op == GECC_MAT_B && use_tile(ctx, tj) ? q.run_tile(tj, GECC_K_ENCODE_B)
                                                                 : q.run(scan_b_over_m(ctx, dev_B, nullptr, dev_B_par, nullptr));
   return hip_rc(e != hipSuccess ? e : q.flush());
 }
@@ -591,7 +608,7 @@ hipError_t blocked_multiply(gecc_ctx* ctx, const void* dev_A, const double* dev_
     GemmArgs g = gemm_args(ctx, dev_A, WB, side_r);
     g.trans_b = 1; g.m = ctx->w_cols_b; g.ldb = p.k; g.ldc = ctx->w_cols_b;
     g.ntn = (g.m + ctx->tile_n - 1) / ctx->tile_n;
-    g.rowpart = nullptr; g.colpart = nullptr; g.faults = nullptr; g.n_faults = 0;
+    g.rowpart = nullptr; g.colpart = nullptr; g.faults = nullptr; g.n_faults = 0; g.ksplit = 1;
     if ((e = t.done(launch_gemm(g, st))) != hipSuccess) return e;
   }
   {
@@ -600,7 +617,7 @@ hipError_t blocked_multiply(gecc_ctx* ctx, const void* dev_A, const double* dev_
     GemmArgs g = gemm_args(ctx, WA, dev_B, side_c);
     g.trans_a = 0; g.n = ctx->w_cols_a; g.lda = p.k; g.ldc = p.m;
     g.ntm = (g.n + ctx->tile_m - 1) / ctx->tile_m;
-    g.rowpart = nullptr; g.colpart = nullptr; g.faults = nullptr; g.n_faults = 0;
+    g.rowpart = nullptr; g.colpart = nullptr; g.faults = nullptr; g.n_faults = 0; g.ksplit = 1;
     if ((e = t.done(launch_gemm(g, st))) != hipSuccess) return e;
   }
   {
@@ -697,7 +714,7 @@ int correct_impl(gecc_ctx* ctx, void* dev_A, const double* dev_A_par, void* dev_
       TileScanJob tj = tile_job(&v, op, X, out, nullptr, nullptr, 0, gw);
       tj.gate_stride = 0;
       hipError_t ee;
-      if (use_tile(tj)) ee = qv.run_tile(tj, kind);
+      if (use_tile(&v, tj)) ee = qv.run_tile(tj, kind);
       else { ScanJob j = old_job; j.s.gate_stride = 0; ee = qv.run(j); }
       if (ee == hipSuccess) { qv.pending.gate_stride = 0; ee = qv.flush(); }
       ctx->ev_n = v.ev_n;
@@ -723,7 +740,7 @@ int correct_impl(gecc_ctx* ctx, void* dev_A, const double* dev_A_par, void* dev_
   const bool t_is_a = ctx->tile_op == GECC_MAT_A;
   const TileScanJob tj = tile_job(ctx, ctx->tile_op, t_is_a ? dev_A : dev_B,
                                   const_cast<double*>(t_is_a ? d.audit_a : d.audit_b), nullptr, nullptr, 0, gate);
-  const bool tile = use_tile(tj);
+  const bool tile = use_tile(ctx, tj);
   const ScanPairItem xa{tile && t_is_a ? 2 : (ja.rowdot ? 0 : 1), ja.s, tj};
   const ScanPairItem xb{tile && !t_is_a ? 2 : (jb.rowdot ? 0 : 1), jb.s, tj};
   if (audit_pair_ok(xa, xb)) {
@@ -770,7 +787,7 @@ int encode_and_multiply(gecc_ctx* ctx, void* dev_A, void* dev_B, float* dev_C, d
   const bool t_is_a = ctx->tile_op == GECC_MAT_A;
   const TileScanJob tj = t_is_a ? tile_job(ctx, GECC_MAT_A, dev_A, dev_A_par, dev_B_par, dev_C_par, rec, nullptr)
                                 : tile_job(ctx, GECC_MAT_B, dev_B, dev_B_par, dev_A_par, dev_C_par + 2 * (size_t)p.n, rec, nullptr);
-  if (use_tile(tj)) {
+  if (use_tile(ctx, tj)) {
     // the larger operand in one pass: its encoding and its parity block of C-bar together.  That
     // pass reads the other operand's encoding, and the other operand's parity block reads this one's.
     if ((e = q.run(t_is_a ? eb : ea)) != hipSuccess) return hip_rc(e);
@@ -995,6 +1012,10 @@ int gecc_plain_gemm(gecc_ctx* ctx, const void* dev_A, const void* dev_B, float* 
     return GECC_ERR_ALIGN;
   GemmArgs g = gemm_args(ctx, dev_A, dev_B, dev_C);
   g.rowpart = nullptr; g.colpart = nullptr; g.faults = nullptr; g.n_faults = 0;
+  if (g.ksplit > 1) {
+    const int rc = prep(ctx, (hipStream_t)stream);
+    if (rc) return rc;
+  }
   return hip_rc(timed_gemm(ctx, g, (hipStream_t)stream));
 }
 

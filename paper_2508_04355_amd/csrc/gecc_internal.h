@@ -54,6 +54,7 @@ struct Layout {            // byte offsets into the caller's workspace
   size_t scan_a;           // double scratch of the two-stage column reduction (A side)
   size_t scan_b;           // same, B side
   size_t scan_row;         // double scratch of the row part of the tile scan (the larger operand's)
+  size_t ksplit;           // float [batch x tiles][ksplit][128 x 128]: partial tiles of a k-split product (0 bytes: none)
   // blocked mode only
   size_t w_a, w_b;         // parity rows of all row blocks of A / parity columns of all column blocks of B, as operands of the product
   size_t side_r, side_c;   // float: A x (parity columns), (parity rows) x B
@@ -73,7 +74,9 @@ struct gecc_ctx {
   int pieces;              // blocked mode: operand-type pieces one fp64 parity is split into (bf16: 3, fp32: 1)
   int w_cols_a, w_cols_b;  // rows of W_A (2 * pieces * nbi) and of W_B, padded to a multiple of 8
   int tile_op;             // operand whose two reductions share one pass (GECC_MAT_A / GECC_MAT_B)
+  int ksplit;              // workgroups per tile of the 128 x 128-tile product kernel (1: no split)
   int cu_hint;             // GECC_CU_COUNT (tests: plan the tile rounds as for that many CUs), else 0
+  int64_t tile_min;        // operands of that many elements or more take the tile scan (2^25; GECC_TILE_MIN for tests)
   char* ws;                // device workspace (caller's)
   size_t ws_bytes;
   char* ws_zeroed;         // the workspace whose "done" counters this context knows to be zero between launches
@@ -206,6 +209,12 @@ struct GemmArgs {
                         // k-split tail (-1: none)
   int map_sr, map_sc;   // set by the same launcher: a round of 256 workgroups takes a block of
                         // map_sr x map_sc tiles (0: the default order)
+  // 128 x 128-tile kernel only: ksplit workgroups share a tile, one per range of k (products with far
+  // fewer tiles than compute units); the last to finish adds their partial tiles up in a fixed order
+  int ksplit;           // 0 or 1: off
+  int k_per;            // set by the launcher: k range of one workgroup
+  float* split_part;    // [tiles x batch][ksplit][128 x 128]
+  uint32_t* split_done; // [tiles x batch] counters, zero between launches (shared with the scans)
   // protected product only: P_g = A_P B_P goes to pg_out[b * pg_stride + 0..3], formed by the
   // workgroup of the first tile, which also resets the decoder state of its batch item
   const double* A_par;

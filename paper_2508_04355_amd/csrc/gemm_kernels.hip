@@ -166,7 +166,11 @@ __global__ __launch_bounds__(THREADS) void gemm_kernel(GemmArgs a) {
   using G = GT<DT>;
   using T = typename G::T;
   constexpr int BM = 128, BN = 128, BK = G::BK, LDK = BK + G::KPAD, SLAB = 64;
-  const int b = blockIdx.z;
+  // k-split (products of few tiles): ksplit workgroups share a tile, one per range of k
+  const int S = a.ksplit > 1 ? a.ksplit : 1;
+  const int b = (int)blockIdx.z / S, split = (int)blockIdx.z % S;
+  const int k_begin = S > 1 ? min(a.k, split * a.k_per) : 0;
+  const int k_end = S > 1 ? min(a.k, k_begin + a.k_per) : a.k;
   const int tm = blockIdx.y, tn = blockIdx.x;
   const int tile_r0 = tm * BM, tile_c0 = tn * BN;
   const T* A = reinterpret_cast<const T*>(a.A) + (int64_t)b * a.sa;
@@ -197,17 +201,17 @@ __global__ __launch_bounds__(THREADS) void gemm_kernel(GemmArgs a) {
 
   Stager<DT, BM, KCA> sa;
   Stager<DT, BN, KCB> sb;
-  sa.load(A, a.lda, tile_r0, 0, a.n, a.k, vecA);
-  sb.load(B, a.ldb, tile_c0, 0, a.m, a.k, vecB);
+  sa.load(A, a.lda, tile_r0, k_begin, a.n, k_end, vecA);
+  sb.load(B, a.ldb, tile_c0, k_begin, a.m, k_end, vecB);
 
-  for (int k0 = 0; k0 < a.k; k0 += BK) {
+  for (int k0 = k_begin; k0 < k_end; k0 += BK) {
     __syncthreads();               // previous tile fully consumed
     sa.store(As);
     sb.store(Bs);
     __syncthreads();
-    if (k0 + BK < a.k) {           // prefetch the next tile into registers
-      sa.load(A, a.lda, tile_r0, k0 + BK, a.n, a.k, vecA);
-      sb.load(B, a.ldb, tile_c0, k0 + BK, a.m, a.k, vecB);
+    if (k0 + BK < k_end) {         // prefetch the next tile into registers
+      sa.load(A, a.lda, tile_r0, k0 + BK, a.n, k_end, vecA);
+      sb.load(B, a.ldb, tile_c0, k0 + BK, a.m, k_end, vecB);
     }
     if (DT == GECC_BF16) {
 #pragma unroll
@@ -241,6 +245,43 @@ __global__ __launch_bounds__(THREADS) void gemm_kernel(GemmArgs a) {
           for (int j = 0; j < 2; ++j)
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i], fb[j], acc[i][j], 0, 0, 0);
       }
+    }
+  }
+
+  if (S > 1) {
+    // Every workgroup of the tile leaves its partial sums in memory; the one that arrives last adds
+    // them all up in the order of the k ranges (so the result does not depend on which one that
+    // is) and goes on with the tile.
+    const int64_t tile_id = ((int64_t)b * gridDim.y + tm) * gridDim.x + tn;
+    float* part = a.split_part + tile_id * S * (BM * BN);
+    float* mine = part + (int64_t)split * (BM * BN);
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int r = wr * 64 + i * 32 + (v >> 2) * 8 + lhi * 4 + (v & 3);
+          store_dev(mine + r * BN + wc * 64 + j * 32 + l32, acc[i][j][v]);
+        }
+    if (!arrive_last(a.split_done + tile_id, (uint32_t)S, reinterpret_cast<int*>(smem))) return;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    for (int q = 0; q < S; ++q) {
+      const float* src = part + (int64_t)q * (BM * BN);
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int r = wr * 64 + i * 32 + (v >> 2) * 8 + lhi * 4 + (v & 3);
+            acc[i][j][v] += load_dev(src + r * BN + wc * 64 + j * 32 + l32);
+          }
     }
   }
 
@@ -361,8 +402,16 @@ __global__ __launch_bounds__(THREADS) void partials_kernel(PartialArgs a) {
 }
 
 template <int DT>
-hipError_t launch_dt(const GemmArgs& a, hipStream_t st) {
-  dim3 grid((a.m + 127) / 128, (a.n + 127) / 128, a.batch);
+hipError_t launch_dt(const GemmArgs& a0, hipStream_t st) {
+  GemmArgs a = a0;
+  const int ntiles = ((a.m + 127) / 128) * ((a.n + 127) / 128);
+  if (a.ksplit > 1 && a.split_part && a.split_done && (int64_t)ntiles * a.batch <= SCAN_DONE_WORDS) {
+    const int bk = GT<DT>::BK;
+    a.k_per = ((a.k + a.ksplit - 1) / a.ksplit + bk - 1) / bk * bk;
+  } else {
+    a.ksplit = 1;
+  }
+  dim3 grid((a.m + 127) / 128, (a.n + 127) / 128, a.batch * a.ksplit);
   // k-contiguous storage: A when not transposed, B when transposed
   const bool kca = a.trans_a == 0, kcb = a.trans_b != 0;
   if (kca && kcb)        hipLaunchKernelGGL((gemm_kernel<DT, true, true>), grid, dim3(THREADS), 0, st, a);

@@ -81,6 +81,63 @@ def test_ragged_tiles_of_the_fast_bf16_kernel_with_errors(pattern, trans):
 
 
 @pytest.mark.parametrize("trans", [(0, 0), (0, 1), (1, 0), (1, 1)])
+@pytest.mark.parametrize("dtype,shape,batch", [("f32", (520, 1024, 264), 1), ("bf16", (200, 1024, 136), 1), ("f32", (300, 520, 260), 2)])
+@pytest.mark.parametrize("pattern", ["clean", "C+C", "A+C", "B+C"])
+def test_k_split_of_products_with_few_tiles(pattern, dtype, shape, batch, trans):
+    """Products with far fewer 128 x 128 tiles than compute units split k over up to 8 workgroups per
+    tile; the one that finishes last adds the partial tiles up in the order of the k ranges, so the
+    result is the same bits whichever that is, and everything downstream is as for one workgroup."""
+    n, k, m = shape
+    rng = inputs.rng_for(97, trans[0] * 2 + trans[1])
+    law = ("normal", 1.0)
+    faults = {"clean": [], "C+C": [inputs.Fault(MAT_C, n - 1, m - 1, 37.5), inputs.Fault(MAT_C, 3, 129, -12.25)],
+              "A+C": [inputs.Fault(MAT_A, n - 1, k - 1, 3.0), inputs.Fault(MAT_C, 0, m - 1, 55.0)],
+              "B+C": [inputs.Fault(MAT_B, k // 2, m - 1, -2.5), inputs.Fault(MAT_C, n - 1, 5, 9.0)]}[pattern]
+    trials = [_trial(rng, n, k, m, dtype, law, law, faults) for _ in range(batch)]
+    A, B, A2, B2 = [np.stack([t[x] for t in trials]) for x in range(4)]
+    cfb = [(b,) + c for b, t in enumerate(trials) for c in t[4]]
+    tau = gecc.noise_thresholds(n, k, m, 1.0, 1.0)
+    g = H.run_gpu(A, B, A2, B2, cfb, tau, dtype, trans[0], trans[1])
+    o = H.run_oracle(A, B, A2, B2, cfb, tau)
+    H.compare(g, o, 1e-5, what="k-split, %s, %s, trans %s" % (pattern, shape, trans))
+    g2 = H.run_gpu(A, B, A2, B2, cfb, tau, dtype, trans[0], trans[1])
+    assert np.array_equal(g.C, g2.C) and np.array_equal(g.synd, g2.synd)
+
+
+@pytest.mark.parametrize("trans", [(0, 0), (0, 1), (1, 0), (1, 1)])
+@pytest.mark.parametrize("dtype,shape", [("bf16", (520, 256, 264)), ("bf16", (1000, 520, 776)), ("f32", (300, 200, 260)),
+                                         ("bf16", (2200, 136, 72))])
+@pytest.mark.parametrize("pattern", ["clean", "A+C", "B+C", "A+B"])
+def test_one_pass_scan_on_small_and_ragged_shapes(pattern, dtype, shape, trans, monkeypatch):
+    """The scan that reads an operand once for both of its reductions (rows straight into LDS, a last
+    column segment narrower than the others, chunks of rows that end in the middle of a block) serves
+    operands of 2^25 elements or more; GECC_TILE_MIN = 1 lets it serve these small ones, staged calls
+    and the one-call chain alike, and the audit re-forms the same sums bit for bit."""
+    monkeypatch.setenv("GECC_TILE_MIN", "1")
+    try:
+        n, k, m = shape
+        rng = inputs.rng_for(93, trans[0] * 2 + trans[1])
+        law = ("normal", 1.0)
+        faults = {"clean": [],
+                  "A+C": [inputs.Fault(MAT_A, n - 1, k - 1, 3.0), inputs.Fault(MAT_C, 0, m - 1, 55.0)],
+                  "B+C": [inputs.Fault(MAT_B, k - 1, m - 1, -2.5), inputs.Fault(MAT_C, n - 1, m // 2, 9.0)],
+                  "A+B": [inputs.Fault(MAT_A, n // 2, 0, 4.0), inputs.Fault(MAT_B, 0, m // 3, 6.0)]}[pattern]
+        A, B, A2, B2, cf, eff = _trial(rng, n, k, m, dtype, law, law, faults)
+        tau = gecc.noise_thresholds(n, k, m, 1.0, 1.0)
+        cfb = [(0,) + c for c in cf]
+        g = H.run_gpu(A, B, A2, B2, cfb, tau, dtype, trans[0], trans[1])
+        o = H.run_oracle(A, B, A2, B2, cfb, tau)
+        H.compare(g, o, 1e-5, what="one-pass scan, %s, %s, trans %s" % (pattern, shape, trans))
+        assert [(e[0], e[1], e[2]) for e in g.reports[0].errors()] == [(e[0], e[1], e[2]) for e in eff]
+        if pattern == "clean":
+            g2 = H.run_gpu(A, B, A, B, [], tau, dtype, trans[0], trans[1], staged=False)
+            assert np.array_equal(g.A_par, g2.A_par) and np.array_equal(g.B_par, g2.B_par) and np.array_equal(g.C, g2.C)
+            assert np.allclose(g.C_par, g2.C_par, rtol=1e-12, atol=1e-13 * np.abs(g.C_par).max())
+    finally:
+        monkeypatch.delenv("GECC_TILE_MIN")
+
+
+@pytest.mark.parametrize("trans", [(0, 0), (0, 1), (1, 0), (1, 1)])
 @pytest.mark.parametrize("shape,cus", [((520, 256, 264), 4), ((520, 128, 264), 4), ((1000, 512, 776), 12)])
 @pytest.mark.parametrize("pattern", ["clean", "C+C in split tiles", "A+C", "B+C", "C outside the split tiles"])
 def test_k_split_tail_of_the_fast_bf16_kernel(pattern, shape, cus, trans, monkeypatch):

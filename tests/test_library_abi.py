@@ -69,16 +69,22 @@ def test_create_validates_arguments(built):
 
 
 def test_workspace_grows_with_the_problem(built):
+    """(Shapes of 512 tiles and more: products of fewer tiles than compute units also hold the partial
+    tiles of their k-split, at most 16 MiB, whatever the shape.)"""
     L = built.lib()
     sizes = []
-    for n in (128, 1024, 4096):
+    for n in (4096, 8192, 16384):
         h = C.c_void_p()
         assert L.gecc_create(C.byref(h), C.byref(_params(built, n=n, k=n, m=n, lda=n, ldb=n, ldc=n))) == 0
         sizes.append(L.gecc_workspace_bytes(h))
         L.gecc_destroy(h)
     assert sizes[0] < sizes[1] < sizes[2]
     # partial sums stay a small fraction of C (4 n m bytes)
-    assert sizes[2] < 0.2 * 4 * 4096 * 4096
+    assert sizes[2] < 0.2 * 4 * 16384 * 16384
+    h = C.c_void_p()
+    assert L.gecc_create(C.byref(h), C.byref(_params(built, n=1024, k=1024, m=1024, lda=1024, ldb=1024, ldc=1024))) == 0
+    assert L.gecc_workspace_bytes(h) < (16 << 20) + 0.3 * 4 * 1024 * 1024
+    L.gecc_destroy(h)
 
 
 def test_noise_thresholds_scale_with_shape(built):
