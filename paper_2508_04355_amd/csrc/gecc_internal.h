@@ -17,7 +17,7 @@ constexpr int SCAN_CHUNK_ROWS = 128;
 // wraps its counter), zeroed once when a workspace is attached.
 constexpr int SCAN_DONE_WORDS = 16384;
 // A column reduction finishes by itself when one workgroup can add a segment's chunks up quickly
-constexpr int SCAN_FUSE_MAX_CHUNKS = 128;
+constexpr int SCAN_FUSE_MAX_CHUNKS = 64;
 
 // decoder phases kept in device memory (per batch item)
 enum : int { PH_DONE = 0, PH_AUDIT = 1, PH_REVERIFY = 2 };

@@ -682,7 +682,7 @@ struct PairJob {
 };
 enum : int { PJ_ROW = 0, PJ_COL = 1, PJ_TILE_COL = 2, PJ_TILE_ROW = 3, PJ_ROW_BIG = 4 };
 struct PairArgs { PairJob j[2]; };
-constexpr int AUDIT_PAIR_MAX_BLOCKS = 4096;
+constexpr int AUDIT_PAIR_MAX_BLOCKS = 5120;
 constexpr int PAIR_LDS_DOUBLES = TS_LDS_DOUBLES > CD_LDS_DOUBLES ? TS_LDS_DOUBLES : CD_LDS_DOUBLES;
 
 template <int DT>
