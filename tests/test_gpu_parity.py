@@ -364,6 +364,60 @@ def test_the_staged_chain_replays_from_a_captured_graph():
         assert torch.equal(Cd, eager_C) and torch.equal(C_par, eager_par)
 
 
+def test_last_arrival_counters_survive_graph_replays():
+    """The k-split of a small product and the paired audits count workgroups at counters in the workspace
+    that the last arrival wraps back to zero.  A captured chain with an operand fault (so that the audits
+    really run) is replayed several times, with eager runs in between; every replay has to give what the
+    eager calls give."""
+    import torch
+    n, k, m = 520, 1024, 264
+    rng = inputs.rng_for(98)
+    A, B = inputs.operands(rng, n, k, m, ("normal", 1.0), ("normal", 1.0), "f32")
+    A_bad = A.copy()
+    A_bad[333, 700] += 6.0
+    tau = gecc.noise_thresholds(n, k, m, 1.0, 1.0)
+    ctx = gecc.Context(n, k, m, gecc.F32, gecc.Thresholds(tau.r1, tau.r2, tau.q1, tau.q2, tau.op, tau.rep, tau.rel))
+    good, bad = H.to_dev(A[None], "f32", False), H.to_dev(A_bad[None], "f32", False)
+    dA, dB = good.clone(), H.to_dev(B[None], "f32", False)
+    A_par, B_par, C_par = ctx.alloc_parities()
+    rep, Cd = ctx.alloc_report(), ctx.alloc_c()
+    fl, nf = gecc.make_faults([(0, 1, 2, 10.0)], H.DEV)
+
+    def chain():
+        dA.copy_(good)
+        ctx.encode_a(dA, A_par)
+        ctx.encode_b(dB, B_par)
+        dA.copy_(bad)                                     # E1: after the parities were formed
+        ctx.multiply(dA, A_par, dB, B_par, Cd, C_par, fl, nf)
+        ctx.verify(Cd, C_par, rep, fused=True)
+        ctx.correct(dA, A_par, dB, B_par, Cd, C_par, rep)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        chain()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        chain()
+    for case in [(0, 10, 20, 40.0), (0, 519, 263, -33.0), (0, 77, 5, 21.0)]:
+        new, _ = gecc.make_faults([case], H.DEV)
+        fl.copy_(new)
+        Cd.fill_(float("nan"))
+        chain()
+        eager_rep = ctx.report_to_host(rep)[0]
+        eager_C, eager_A = Cd.clone(), dA.clone()
+        Cd.fill_(float("nan"))
+        rep.zero_()
+        graph.replay()
+        r = ctx.report_to_host(rep)[0]
+        assert r.status == gecc.CORRECTED
+        assert sorted((e[0], e[1], e[2]) for e in r.errors()) == sorted([(MAT_A, 333, 700), (MAT_C, case[1], case[2])])
+        assert (r.status, r.errors()) == (eager_rep.status, eager_rep.errors())
+        assert torch.equal(Cd, eager_C) and torch.equal(dA, eager_A) and torch.equal(dA, good)
+
+
 def test_unaligned_leading_dimensions_take_the_scalar_paths():
     n, k, m = 67, 45, 83
     rng = inputs.rng_for(91)
