@@ -161,8 +161,13 @@ int gecc_create(gecc_ctx** out, const gecc_params* p);
 void gecc_destroy(gecc_ctx* ctx);
 
 /* Bytes of device workspace the context needs (partial syndromes, syndromes, decoder
-   state, audit parities).  The caller allocates it (256-byte aligned) and hands it over;
-   it stays the caller's.  Its contents need not be initialised. */
+   state, audit parities, scan scratch, the partial tiles of a k-split product).  The caller
+   allocates it (256-byte aligned) and hands it over; it stays the caller's.  Its contents need
+   not be initialised: its first 64 KiB are counters that the library keeps at zero between
+   launches, and the first compute call after gecc_set_workspace clears them with a small kernel
+   on that call's stream (so a workspace is attached before, not while, a graph is captured, or
+   the clear is captured with it, which is harmless).  Contexts may share one workspace when
+   their calls are ordered on a stream; calls that overlap in time on one workspace race. */
 size_t gecc_workspace_bytes(const gecc_ctx* ctx);
 int gecc_set_workspace(gecc_ctx* ctx, void* dev_workspace, size_t bytes);
 
@@ -220,7 +225,10 @@ int gecc_correct(gecc_ctx* ctx, void* dev_A, const double* dev_A_par, void* dev_
                  const double* dev_B_par, float* dev_C, double* dev_C_par,
                  gecc_report* dev_report, void* stream);
 
-/* encode_a, encode_b, multiply, verify(fused), correct in stream order. */
+/* encode_a, encode_b, multiply, verify(fused), correct in stream order (the larger operand is read
+   once for its encoding and its parity block of C-bar).  No faults can be planted through this
+   entry point: tests that want a fault inside the product use gecc_protected_gemm_retry with
+   max_retries = 0, or the staged calls. */
 int gecc_protected_gemm(gecc_ctx* ctx, void* dev_A, void* dev_B, float* dev_C, double* dev_A_par,
                         double* dev_B_par, double* dev_C_par, gecc_report* dev_report,
                         void* stream);
