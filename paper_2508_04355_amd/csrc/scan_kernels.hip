@@ -441,12 +441,15 @@ __global__ __launch_bounds__(256) void coldot_stage2(Stage2Job j) {
 // bit.  All products go through fma(), never a*b+c, for the same reason.
 //
 // A workgroup is four wavefronts on one segment of 64*VEC columns; each walks its own quarter of
-// the chunk's rows, TS_RB rows (loads) at a time; at 124 registers four wavefronts share a SIMD and
-// cover each other's waits (measured: more loads in flight per wavefront, 8-byte lanes, or
-// workgroups that read 4 KiB of every row change nothing; the kernel runs at the rate its loads
-// alone reach).  A lane keeps the column sums of its VEC columns in registers for the whole walk.  The row sums of a block of rows
-// (TS_RB rows x 2 kinds, one partial per lane) are transposed through LDS and added by four lanes per
-// output; only the wavefront's own LDS region is involved, so no workgroup barrier sits in the loop.
+// the chunk's rows, TS_RB rows (loads) at a time; three wavefronts share a SIMD and cover each
+// other's waits.  The kernel is bound by its arithmetic as much as by memory: per 16 bytes a lane
+// spends 8 conversions and 32 fp64 operations, which issue at half rate, about 380 cycles per row
+// and wavefront (measured: its loads alone stream at 5.8 TB/s, the whole kernel at 4.4; more loads in
+// flight, 8-byte lanes, rows DMA'd into an LDS ring or workgroups that read 4 KiB of every row
+// change nothing).  A lane keeps the column sums of its VEC columns in registers for the whole walk.
+// The row sums of a block of rows (TS_RB rows x 2 kinds, one partial per lane) are transposed through
+// LDS and added by four lanes per output; only the wavefront's own LDS region is involved, so no
+// workgroup barrier sits in the loop.
 constexpr int TS_THREADS = 256;
 constexpr int TS_RB = 8;            // rows per block of loads
 constexpr int TS_LDS_LD = 65;       // doubles per output row of the transpose (64 lanes + 1: conflict-free)
