@@ -629,6 +629,33 @@ def test_blocked_grid_code(pattern, dtype, shape, block, trans):
         _blocked_compare(g1, res, Cref, n, m, nb, mb, tol_mag=4 * max(tau.r1, tau.q1))
 
 
+@pytest.mark.parametrize("dtype,shape,block,trans", [("bf16", (512, 256, 768), (256, 256), (0, 0)), ("bf16", (768, 256, 512), (256, 256), (1, 1)),
+                                                     ("f32", (256, 200, 384), (128, 128), (0, 1))])
+def test_blocked_grid_code_random_trials(dtype, shape, block, trans):
+    """40 seeded trials per layout with 0 to 5 faults anywhere in A, B and C: some blocks stay clean, some
+    hold up to two symbols, some more than the code corrects, an operand symbol is seen by every block
+    of its line.  Every block's status and positions as the oracle's block-by-block evaluation gives
+    them, every block that is not UNCORRECTABLE to 1e-5."""
+    n, k, m = shape
+    nb, mb = block
+    tau = gecc.noise_thresholds(nb, k, mb, 1.0, 1.0)
+    tau_o = oc.Thresholds(tau.r1, tau.r2, tau.q1, tau.q2, tau.op, tau.rep, tau.rel)
+    seen = {gecc.CLEAN: 0, gecc.CORRECTED: 0, gecc.UNCORRECTABLE: 0}
+    for trial in range(40):
+        rng = inputs.rng_for(99, 1000 * trans[0] + trial)
+        faults = inputs.draw_faults(rng, n, k, m, int(rng.integers(0, 6)), ("uniform", 1.0, 100.0))
+        if trial % 5 == 4:        # every fifth trial: three or four symbols of C inside the first block
+            faults = [inputs.Fault(MAT_C, f.row, f.col, f.offset)
+                      for f in inputs.draw_faults(rng, nb, k, mb, 3 + trial % 2, ("uniform", 1.0, 100.0), [MAT_C] * (3 + trial % 2))]
+        A, B, A2, B2, cf, eff = _trial(rng, n, k, m, dtype, ("normal", 1.0), ("normal", 1.0), faults)
+        res, Cref, Ao, Bo = oc.protected_gemm_blocked(A, B, A2, B2, cf, tau_o, nb, mb)
+        g = H.run_gpu_blocked(A, B, A2, B2, cf, tau, dtype, block, trans[0], trans[1])
+        _blocked_compare(g, res, Cref, n, m, nb, mb, tol_mag=4 * max(tau.r1, tau.q1))
+        for r in g["reports"]:
+            seen[r.status] += 1
+    assert min(seen.values()) > 0, seen
+
+
 def test_blocked_grid_code_at_the_forward_shape():
     """cfg4-fwd in 1024 x 1024 blocks (16 x 14 codewords): the parity blocks of all of them come from two
     narrow products on the 256 x 256-tile kernel.  Two errors in each of five blocks, a wrong symbol of A
@@ -699,6 +726,34 @@ def test_single_checksum_mode(pattern, dtype, shape, trans):
     if pattern not in ("two rows", "C nan", "none"):
         g2 = H.run_gpu(A, B, A2, B2, cfb, t, dtype, trans[0], trans[1])
         assert g2.reports[0].status == gecc.CORRECTED and g2.reports[0].n_total == len(eff)
+
+
+@pytest.mark.parametrize("dtype,shape,trans", [("f32", (300, 200, 260), (0, 0)), ("bf16", (520, 256, 264), (1, 0))])
+def test_single_checksum_mode_random_trials(dtype, shape, trans):
+    """60 seeded trials with 0 to 3 faults anywhere in A, B and C, decided by the HIP path and by the
+    oracle's single-checksum decoder: same status, same positions, C to the tolerance of the rule used."""
+    n, k, m = shape
+    t = gecc.noise_thresholds(n, k, m, 1.0, 1.0)
+    tau = gecc.Thresholds(t.r1, t.r2, t.q1, t.q2, weighted=False)
+    seen = {gecc.CLEAN: 0, gecc.CORRECTED: 0, gecc.UNCORRECTABLE: 0}
+    for trial in range(60):
+        rng = inputs.rng_for(99, 5000 + 100 * trans[0] + trial)
+        count = int(rng.integers(0, 4))
+        mats = [MAT_C] * count if trial % 2 else None              # every other trial: faults of C only
+        faults = inputs.draw_faults(rng, n, k, m, count, ("uniform", 1.0, 100.0), mats)
+        if trial % 4 == 1 and count >= 2:                          # ... and some of those in one row
+            faults = [inputs.Fault(MAT_C, faults[0].row, f.col, f.offset) for f in faults]
+            if len({f.col for f in faults}) < len(faults):
+                continue
+        A, B, A2, B2, cf, eff = _trial(rng, n, k, m, dtype, ("normal", 1.0), ("normal", 1.0), faults)
+        cfb = [(0,) + c for c in cf]
+        g = H.run_gpu(A, B, A2, B2, cfb, tau, dtype, trans[0], trans[1])
+        o = H.run_oracle(A, B, A2, B2, cfb, tau)
+        scale = float(np.max(np.abs(o[0].C)))
+        tol = 4 * max(tau.r1, tau.q1) / scale if len(faults) > 1 else 1e-5
+        H.compare(g, o, tol, tol_mag=4 * max(tau.r1, tau.q1), what="single checksum, trial %d" % trial)
+        seen[g.reports[0].status] += 1
+    assert min(seen.values()) > 0, seen
 
 
 # ---- symbols that are not numbers ------------------------------------------------------------------
