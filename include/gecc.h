@@ -265,7 +265,8 @@ int gecc_protected_gemm_panels(gecc_ctx* ctx, void* dev_A, void* dev_B, float* d
    GECC_STATIC_SCRATCH_BYTES (a 16384 x 4096 x 14336 product needs 45 MiB in any storage layout,
    256 products of 512^3 need 37 MiB).  All calls on one GPU share that GPU's array, whatever their context:
    two such calls that overlap in time on one GPU race; calls in stream order on one stream are
-   safe, and nothing has to be cleared between them.  The fused verification state lives in that
+   safe, and nothing has to be cleared between them (the first call on a GPU clears the array's
+   counters with a small kernel on its stream).  The fused verification state lives in that
    array too, so gecc_syndromes_to_host does not see this call's syndromes.  The device current at
    the time of the call must be the one `stream` belongs to. */
 #define GECC_STATIC_SCRATCH_BYTES (48u << 20)

@@ -888,9 +888,11 @@ static __device__ __align__(256) unsigned char scratch[GECC_STATIC_SCRATCH_BYTES
 constexpr int MAX_DEVICES = 64;
 std::mutex scratch_mutex;
 char* scratch_addr[MAX_DEVICES] = {};
+bool scratch_cleared[MAX_DEVICES] = {};
 
-// device address of `scratch` on the current device, looked up once per device
-int static_scratch(char** out) {
+// device address of `scratch` on the current device, looked up once per device; *first: nobody has
+// used the array on this device yet
+int static_scratch(char** out, bool* first, int* device) {
   int dev = -1;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return GECC_ERR_HIP;
   std::lock_guard<std::mutex> lock(scratch_mutex);
@@ -900,6 +902,8 @@ int static_scratch(char** out) {
     scratch_addr[dev] = static_cast<char*>(p);
   }
   *out = scratch_addr[dev];
+  *first = !scratch_cleared[dev];
+  *device = dev;
   return GECC_OK;
 }
 
@@ -912,7 +916,9 @@ int gecc_protected_gemm_static(gecc_ctx* ctx, void* dev_A, void* dev_B, float* d
     return GECC_ERR_ARG;
   if (ctx->lay.total > (size_t)GECC_STATIC_SCRATCH_BYTES) return GECC_ERR_SCRATCH;
   char* ws = nullptr;
-  int rc = static_scratch(&ws);
+  bool first = false;
+  int dev = 0;
+  int rc = static_scratch(&ws, &first, &dev);
   if (rc) return rc;
   // the context's own workspace (if any) is left alone: this call runs on the static one
   char* const keep_ws = ctx->ws;
@@ -920,13 +926,17 @@ int gecc_protected_gemm_static(gecc_ctx* ctx, void* dev_A, void* dev_B, float* d
   char* const keep_zeroed = ctx->ws_zeroed;
   ctx->ws = ws;
   ctx->ws_bytes = GECC_STATIC_SCRATCH_BYTES;
-  // the array starts as zeros (static storage) and every scan leaves its counters at zero: no launch
-  // is needed to clear them, whichever context used the array before
-  ctx->ws_zeroed = ws;
+  // every launch leaves the counters at the front of the array at zero, whichever context used it
+  // before; the first call on a device clears them (a kernel launch, not an allocation)
+  ctx->ws_zeroed = first ? nullptr : ws;
   rc = gecc_protected_gemm(ctx, dev_A, dev_B, dev_C, dev_A_par, dev_B_par, dev_C_par, dev_report, stream);
   ctx->ws = keep_ws;
   ctx->ws_bytes = keep_bytes;
   ctx->ws_zeroed = keep_zeroed;
+  if (rc == GECC_OK && first) {
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    scratch_cleared[dev] = true;
+  }
   return rc;
 }
 
