@@ -418,6 +418,39 @@ def test_last_arrival_counters_survive_graph_replays():
         assert torch.equal(Cd, eager_C) and torch.equal(dA, eager_A) and torch.equal(dA, good)
 
 
+def test_two_contexts_share_one_workspace_in_stream_order():
+    """Contexts of different shapes may take turns on one workspace (the counters sit at its front in
+    every layout and every launch leaves them at zero): alternating calls give what each context gives
+    on a workspace of its own."""
+    import torch
+    jobs = []
+    for idx, (dtype, (n, k, m)) in enumerate([("f32", (520, 1024, 264)), ("bf16", (520, 256, 264)), ("f32", (300, 200, 260))]):
+        rng = inputs.rng_for(94, idx)
+        A, B = inputs.operands(rng, n, k, m, ("normal", 1.0), ("normal", 1.0), dtype)
+        tau = gecc.noise_thresholds(n, k, m, 1.0, 1.0)
+        cf = [(0, 5 + idx, 6, -12.0), (0, n - 1, 1 + idx, 8.0)]
+        alone = H.run_gpu(A, B, A, B, cf, tau, dtype, staged=False)
+        ctx = gecc.Context(n, k, m, gecc.BF16 if dtype == "bf16" else gecc.F32,
+                           gecc.Thresholds(tau.r1, tau.r2, tau.q1, tau.q2, tau.op, tau.rep, tau.rel))
+        jobs.append((ctx, H.to_dev(A[None], dtype, False), H.to_dev(B[None], dtype, False), ctx.alloc_c(), ctx.alloc_parities(),
+                     ctx.alloc_report(), gecc.make_faults(cf, H.DEV), alone))
+    need = max(gecc.lib().gecc_workspace_bytes(j[0]._h) for j in jobs)
+    shared = torch.empty(need + 256, dtype=torch.uint8, device=H.DEV)
+    shared.fill_(0xA5)                                    # garbage: the first call has to clear the counters
+    base = shared.data_ptr() + (-shared.data_ptr()) % 256
+    import ctypes as C
+    for j in jobs:
+        assert gecc.lib().gecc_set_workspace(j[0]._h, C.c_void_p(base), need) == 0
+    for rnd in range(3):
+        for (ctx, dA, dB, Cd, par, rep, (fl, nf), alone) in jobs:
+            Cd.fill_(float("nan"))
+            reports, attempts = ctx.protected_gemm_retry(dA, dB, Cd, par[0], par[1], par[2], rep, 0, fl, nf)
+            assert attempts == 1 and reports[0].status == gecc.CORRECTED == alone.reports[0].status
+            assert reports[0].errors() == alone.reports[0].errors()
+            assert np.array_equal(Cd.cpu().numpy().astype(np.float64)[:, :, :ctx.m], alone.C)
+            assert np.array_equal(par[0].cpu().numpy().reshape(1, 2, -1), alone.A_par)
+
+
 def test_unaligned_leading_dimensions_take_the_scalar_paths():
     n, k, m = 67, 45, 83
     rng = inputs.rng_for(91)
