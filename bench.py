@@ -305,6 +305,8 @@ def main():
                                  "scenario_overhead_pct": {kk: round((vv / ms_plain - 1.0) * 100.0, 1) for kk, vv in scen_ms1.items()}},
         "per_k_panel_verification": panel_out,
         "blocked_grid_code": block_out,
+        # event pairs recorded per clean step outside the product (the product is one more, two with a k-split tail)
+        "launches_per_step_without_product": round(sum(v["launches"] for kk, v in hbm_steady.items() if kk != "partials") / reps, 2),
         "hbm_rooflines": {"peak_GBs": HBM_PEAK_GBS,
                           "steady_loop": hbm_steady,       # as in the timed steps: operands may sit in the memory-side cache
                           "operands_rotated": hbm_rotated},  # three operand sets in turn: every first read comes from HBM
