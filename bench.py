@@ -24,7 +24,7 @@ HBM_PEAK_GBS = 8000.0
 # Memory traffic of the product kernel per launch (bytes), from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE runs, each scaled by what the same counter reads for a 1 GiB copy (the factors are in
 # the files); profiles/bench_<workload>_hbm_traffic.txt.  Workloads not listed: not measured.
-TRAFFIC_BYTES = {"cfg4-fwd": 3.040e9 + 1.003e9, "cfg4-dgrad": 6.478e9 + 6.418e8, "cfg4-wgrad": 9.478e9 + 5.606e8}
+TRAFFIC_BYTES = {"cfg4-fwd": 3.051e9 + 1.003e9, "cfg4-dgrad": 6.478e9 + 6.418e8, "cfg4-wgrad": 9.478e9 + 5.606e8}
 
 
 def main():
